@@ -1,0 +1,203 @@
+/*
+ * elixir_chunk.h -- C ABI of libelixir_chunk.so
+ *
+ * The chunked mixed-precision AdamW step of Elixir (arXiv 2212.05339) on one
+ * AMD MI355X (gfx950).  Parameters are flattened into fixed-length 1-D chunks
+ * (paper Sec. 3 "Chunk"); each low-precision parameter chunk is paired with an
+ * optimizer chunk holding the fp32 master weight and the two Adam moments on
+ * the same device (paper Sec. 4.1); one optimizer update consumes a gradient
+ * chunk and its optimizer chunk and leaves the low-precision parameters for
+ * the next forward pass (paper Sec. 2 "Mixed Precision Training").  Chunks the
+ * plan keeps in host memory are moved to the GPU and back on side streams so
+ * that transfers overlap with work on resident chunks (paper Sec. 4.3).
+ *
+ * General rules
+ *   - Every function returns an int status: ELIXIR_OK (0) or a negative code;
+ *     elixir_last_error() gives a per-thread message for the last failure.
+ *     Nothing throws across this boundary.
+ *   - "d_" / device pointers must be accessible from the GPU that owns the
+ *     stream; "h_" / host pointers are ordinary or pinned host memory as stated.
+ *   - Lengths and offsets are counted in ELEMENTS (int64_t) unless named *_bytes.
+ *   - bf16 values are passed as their 16-bit patterns (uint16_t).
+ *   - Every GPU operation is enqueued on the caller's stream and returns
+ *     without waiting for it; no entry point synchronises the device except
+ *     elixir_ctx_destroy.  elixir_stream_t is a hipStream_t (NULL = the
+ *     default stream).  The caller's current device must be the one that owns
+ *     the stream and buffers.
+ *   - The caller owns every buffer it passes in.  The library owns only what
+ *     elixir_ctx_create and elixir_host_alloc allocate.  No entry point other
+ *     than those two allocates memory.
+ *   - Pointers must be naturally aligned for their element type.  16-byte
+ *     alignment (which whole chunks from any allocator have) selects the
+ *     128-bit vector kernels; other alignments take a slower scalar kernel with
+ *     identical results.
+ */
+#ifndef ELIXIR_CHUNK_H
+#define ELIXIR_CHUNK_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define ELIXIR_OK        0
+#define ELIXIR_EINVAL   (-1) /* NULL where a pointer is required, negative length, bad enum, overlapping slices ... */
+#define ELIXIR_EALIGN   (-2) /* pointer not naturally aligned for its element type */
+#define ELIXIR_ENOSLOT  (-3) /* every staging slot is held by a chunk that has not been evicted yet */
+#define ELIXIR_EHIP     (-4) /* a HIP runtime call failed; the message names it */
+#define ELIXIR_ESTATE   (-5) /* call out of order (slot not prefetched, slots not registered ...) */
+#define ELIXIR_ECAP     (-6) /* more chunks / elements than the context or an output array was sized for */
+
+typedef void* elixir_stream_t;          /* a hipStream_t */
+typedef struct elixir_ctx elixir_ctx;   /* opaque */
+
+/* Hyper-parameters of one AdamW step.  step is 1-based (the first update has step = 1). */
+typedef struct {
+    float lr, beta1, beta2, eps, weight_decay;
+    int64_t step;
+} elixir_adam_hparams;
+
+/* Chunk grouping policies for elixir_layout_plan. */
+enum {
+    ELIXIR_LAYOUT_NEXT_FIT = 0,  /* the paper's grouping (App. A.2): one current chunk */
+    ELIXIR_LAYOUT_FIRST_FIT = 1, /* earliest chunk with room */
+    ELIXIR_LAYOUT_DENSE = 2      /* parameters may straddle chunk boundaries */
+};
+
+/* Per-thread message describing the last non-OK status returned on this thread ("" if none). */
+const char* elixir_last_error(void);
+
+/*
+ * Context: device workspace for the norm reduction (one double per reduction
+ * block) and the bookkeeping of the offload pipeline.  max_chunk_elems and
+ * max_chunks bound what elixir_chunk_grad_norm accepts.  The context is bound
+ * to HIP device `device`.  Not thread-safe: use one context per host thread.
+ * elixir_ctx_destroy waits for the device, frees the workspace and events
+ * (not the caller's slots or host blocks).
+ */
+int elixir_ctx_create(elixir_ctx** out, int device, int64_t max_chunk_elems, int max_chunks);
+int elixir_ctx_destroy(elixir_ctx* ctx);
+
+/*
+ * Chunk layout (host only, integers).  Paper App. A.2: walk the parameters in
+ * their order of use, keep one current chunk, append a parameter if it fits,
+ * otherwise close the chunk and open a new one (NEXT_FIT).  A parameter longer
+ * than chunk_elems starts at offset 0 of a fresh chunk and runs through
+ * ceil(numel/chunk_elems) consecutive chunks; the rest of its last chunk stays
+ * open.  FIRST_FIT searches every chunk, oldest first; DENSE keeps one running
+ * position so that only the last chunk is padded.  Every start is rounded up to
+ * a multiple of align_elems (>= 1, must divide chunk_elems).
+ *   in : numel[T] (>= 0), chunk_elems (> 0), policy, align_elems
+ *   out: chunk_id[T], offset[T]  -- parameter i occupies the linear element
+ *        range [chunk_id[i]*chunk_elems + offset[i], +numel[i]);
+ *        *n_chunks; valid_len[0..*n_chunks) = elements in use per chunk
+ *        (valid_len may be NULL; otherwise valid_cap is its capacity and
+ *        ELIXIR_ECAP is returned, with *n_chunks set, if it is too small).
+ */
+int elixir_layout_plan(const int64_t* numel, int T, int64_t chunk_elems, int policy, int64_t align_elems,
+                       int64_t* chunk_id, int64_t* offset, int64_t* n_chunks, int64_t* valid_len,
+                       int64_t valid_cap);
+
+/*
+ * Pack / unpack (paper Fig. 3, left: "the data of each parameter is compacted
+ * into a parameter chunk").  Bit copies, elem_size 2 or 4 bytes.
+ *   pack  : d_chunk[offset[i] + k] = tensors[i][k] for k < numel[i]; every
+ *           element of the chunk not covered by a slice is set to zero bits.
+ *   unpack: tensors[i][k] = d_chunk[offset[i] + k].
+ * tensors is a HOST array of T device pointers; numel/offset are host arrays.
+ * Slices must lie inside [0, chunk_elems) and must not overlap (ELIXIR_EINVAL).
+ * A parameter that spans several chunks is passed piecewise by the caller.
+ */
+int elixir_chunk_pack(void* d_chunk, int64_t chunk_elems, int elem_size, const void* const* tensors,
+                      const int64_t* numel, const int64_t* offset, int T, elixir_stream_t stream);
+int elixir_chunk_unpack(const void* d_chunk, int64_t chunk_elems, int elem_size, void* const* tensors,
+                        const int64_t* numel, const int64_t* offset, int T, elixir_stream_t stream);
+
+/*
+ * Gradient reduction into the fp32 gradient chunk.  In the paper gradients are
+ * reduced across ranks and the reduced chunk feeds the optimizer update (Sec. 2
+ * "ZeRO", Fig. 3 right); with one GPU the reduction that remains is the sum
+ * over micro-batches:
+ *   d_grad_chunk[offset+k] = fl32( (accumulate ? d_grad_chunk[offset+k] : 0) + fl32(scale * bf16->fp32(d_grad_bf16[k])) )
+ * for k < n, with separately rounded multiply and add (no fused multiply-add).
+ * The caller guarantees offset + n does not exceed the chunk.
+ */
+int elixir_grad_reduce_into_chunk(float* d_grad_chunk, int64_t offset, const uint16_t* d_grad_bf16, int64_t n,
+                                  float scale, int accumulate, elixir_stream_t stream);
+
+/*
+ * Global gradient L2 norm over the valid part of n_chunks fp32 gradient chunks
+ * and the clipping coefficient derived from it (not in the paper; the usual
+ * definition):  norm = sqrt(sum g^2),  coef = max_norm > 0 ? min(1, max_norm/(norm + 1e-6)) : 1.
+ * The sum is taken in double precision over a fixed reduction tree, so the
+ * result is bitwise reproducible from run to run.  grad_chunks and valid_len
+ * are HOST arrays (device pointers / lengths).  *d_norm_out and
+ * *d_clip_coef_out (either may be NULL) are DEVICE floats written on `stream`;
+ * pass d_clip_coef_out as d_grad_scale to elixir_chunk_adam_step to clip
+ * without a host round trip.  Uses the context's workspace: calls on one
+ * context must be stream-ordered with each other.
+ */
+int elixir_chunk_grad_norm(elixir_ctx* ctx, const float* const* grad_chunks, const int64_t* valid_len,
+                           int n_chunks, float max_norm, float* d_norm_out, float* d_clip_coef_out,
+                           elixir_stream_t stream);
+
+/*
+ * Fused AdamW over one chunk pair (paper Sec. 4.1: one optimizer update per
+ * gradient chunk + optimizer chunk; Sec. 2: fp32 master rounded to the
+ * low-precision parameters).  Adam (Kingma & Ba, Alg. 1) with decoupled weight
+ * decay (Loshchilov & Hutter, Alg. 2), eps added after the bias correction of
+ * sqrt(v).  For k < n, with s = d_grad_scale ? *d_grad_scale : 1 and t = hp->step:
+ *   g = s * grad[k]
+ *   p = master[k] * (1 - lr*wd)
+ *   m = beta1*m[k] + (1-beta1)*g          v = beta2*v[k] + (1-beta2)*g*g
+ *   p = p - lr * (m / (1-beta1^t)) / ( sqrt(v / (1-beta2^t)) + eps )
+ *   master[k] = p;  exp_avg[k] = m;  exp_avg_sq[k] = v;  param_bf16[k] = round-to-nearest-even bf16(p)
+ * Exactly one of d_grad_fp32 / d_grad_bf16 is non-NULL.  d_param_bf16 may be
+ * NULL (no low-precision copy).  d_grad_scale is a DEVICE float or NULL.
+ * Arithmetic is fp32; algorithmic traffic is 28 bytes per element with bf16
+ * gradients (2 + 12 read, 12 + 2 written), 30 with fp32 gradients.
+ */
+int elixir_chunk_adam_step(float* d_master, float* d_exp_avg, float* d_exp_avg_sq, const float* d_grad_fp32,
+                           const uint16_t* d_grad_bf16, uint16_t* d_param_bf16, int64_t n,
+                           const elixir_adam_hparams* hp, const float* d_grad_scale, elixir_stream_t stream);
+
+/*
+ * Offload pipeline for chunks whose optimizer chunk lives in host memory (the
+ * paper keeps a searched number of chunks in CPU memory, Sec. 3 "Search
+ * Engine", and overlaps chunk movement with computation by running it on
+ * separate streams, Sec. 4.3).  Here the fp32 state of such a chunk is copied
+ * into a device staging slot, updated by elixir_chunk_adam_step, and copied
+ * back.
+ *
+ *   elixir_host_alloc / elixir_host_free : page-locked host memory.
+ *   elixir_offload_register_slots : d_slots is a HOST array of n_slots device
+ *       buffers of slot_bytes each, owned by the caller; replaces any earlier
+ *       registration (ELIXIR_ESTATE while a slot is held).
+ *   elixir_chunk_prefetch : picks a slot that is not held, makes h2d_stream
+ *       wait until that slot's previous eviction has finished, enqueues the
+ *       host-to-device copy of `bytes` (<= slot_bytes) from h_block and marks
+ *       the slot held.  *slot_out receives the slot index.  ELIXIR_ENOSLOT if
+ *       all slots are held.
+ *   elixir_chunk_wait_ready : makes compute_stream wait for the slot's copy.
+ *   elixir_chunk_evict : makes d2h_stream wait for the work enqueued so far on
+ *       compute_stream, enqueues the device-to-host copy of `bytes` into
+ *       h_block (h_block NULL: no copy, the slot is only released), and marks
+ *       the slot free for the next prefetch.
+ * No call blocks the host.  h_block should be pinned (elixir_host_alloc) for
+ * the copies to be asynchronous and at link speed.
+ */
+int elixir_host_alloc(void** h_out, size_t bytes);
+int elixir_host_free(void* h_ptr);
+int elixir_offload_register_slots(elixir_ctx* ctx, void* const* d_slots, int n_slots, size_t slot_bytes);
+int elixir_chunk_prefetch(elixir_ctx* ctx, const void* h_block, size_t bytes, int* slot_out,
+                          elixir_stream_t h2d_stream);
+int elixir_chunk_wait_ready(elixir_ctx* ctx, int slot, elixir_stream_t compute_stream);
+int elixir_chunk_evict(elixir_ctx* ctx, int slot, void* h_block, size_t bytes, elixir_stream_t compute_stream,
+                       elixir_stream_t d2h_stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ELIXIR_CHUNK_H */

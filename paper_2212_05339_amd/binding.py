@@ -1,0 +1,217 @@
+"""ctypes binding of libelixir_chunk.so: one Python function per C entry point, same names.
+
+Argument marshalling only -- every step of the path runs in the library's HIP kernels.
+Device buffers are torch tensors (torch is used for device memory and streams only) or raw
+integer addresses.  There is no CPU fallback: if the library is missing or a call fails an
+exception is raised.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional, Sequence
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG, "libelixir_chunk.so")
+
+ELIXIR_OK, ELIXIR_EINVAL, ELIXIR_EALIGN, ELIXIR_ENOSLOT, ELIXIR_EHIP, ELIXIR_ESTATE, ELIXIR_ECAP = 0, -1, -2, -3, -4, -5, -6
+ELIXIR_LAYOUT_NEXT_FIT, ELIXIR_LAYOUT_FIRST_FIT, ELIXIR_LAYOUT_DENSE = 0, 1, 2
+
+EXPORTS = (
+    "elixir_last_error", "elixir_ctx_create", "elixir_ctx_destroy", "elixir_layout_plan", "elixir_chunk_pack",
+    "elixir_chunk_unpack", "elixir_grad_reduce_into_chunk", "elixir_chunk_grad_norm", "elixir_chunk_adam_step",
+    "elixir_host_alloc", "elixir_host_free", "elixir_offload_register_slots", "elixir_chunk_prefetch",
+    "elixir_chunk_wait_ready", "elixir_chunk_evict",
+)
+
+
+class ElixirError(RuntimeError):
+    def __init__(self, code: int, message: str):
+        super().__init__(f"libelixir_chunk status {code}: {message}")
+        self.code = code
+
+
+class elixir_adam_hparams(ctypes.Structure):
+    _fields_ = [("lr", ctypes.c_float), ("beta1", ctypes.c_float), ("beta2", ctypes.c_float), ("eps", ctypes.c_float),
+                ("weight_decay", ctypes.c_float), ("step", ctypes.c_int64)]
+
+
+_lib = None
+
+
+def lib() -> ctypes.CDLL:
+    """Loads the library built by `__graft_entry__.build()`; raises if it is not there."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(f"{LIB_PATH} is missing: build it with `python -m paper_2212_05339_amd.build` "
+                               "(there is no fallback path)")
+        L = ctypes.CDLL(LIB_PATH)
+        vp, i64, ci, f32, sz = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int, ctypes.c_float, ctypes.c_size_t
+        pi64 = ctypes.POINTER(ctypes.c_int64)
+        L.elixir_last_error.restype = ctypes.c_char_p
+        L.elixir_last_error.argtypes = []
+        sigs = {
+            "elixir_ctx_create": [ctypes.POINTER(vp), ci, i64, ci],
+            "elixir_ctx_destroy": [vp],
+            "elixir_layout_plan": [pi64, ci, i64, ci, i64, pi64, pi64, pi64, pi64, i64],
+            "elixir_chunk_pack": [vp, i64, ci, ctypes.POINTER(vp), pi64, pi64, ci, vp],
+            "elixir_chunk_unpack": [vp, i64, ci, ctypes.POINTER(vp), pi64, pi64, ci, vp],
+            "elixir_grad_reduce_into_chunk": [vp, i64, vp, i64, f32, ci, vp],
+            "elixir_chunk_grad_norm": [vp, ctypes.POINTER(vp), pi64, ci, f32, vp, vp, vp],
+            "elixir_chunk_adam_step": [vp, vp, vp, vp, vp, vp, i64, ctypes.POINTER(elixir_adam_hparams), vp, vp],
+            "elixir_host_alloc": [ctypes.POINTER(vp), sz],
+            "elixir_host_free": [vp],
+            "elixir_offload_register_slots": [vp, ctypes.POINTER(vp), ci, sz],
+            "elixir_chunk_prefetch": [vp, vp, sz, ctypes.POINTER(ci), vp],
+            "elixir_chunk_wait_ready": [vp, ci, vp],
+            "elixir_chunk_evict": [vp, ci, vp, sz, vp, vp],
+        }
+        for name, argtypes in sigs.items():
+            f = getattr(L, name)
+            f.restype = ci
+            f.argtypes = argtypes
+        _lib = L
+    return _lib
+
+
+def _check(rc: int) -> None:
+    if rc != ELIXIR_OK:
+        raise ElixirError(rc, lib().elixir_last_error().decode())
+
+
+def elixir_last_error() -> str:
+    return lib().elixir_last_error().decode()
+
+
+def _addr(x) -> Optional[int]:
+    """Device/host address of a torch tensor, or the integer itself, or None."""
+    if x is None:
+        return None
+    if isinstance(x, int):
+        return x
+    return x.data_ptr()
+
+
+def _stream(stream) -> Optional[int]:
+    """hipStream_t of a torch.cuda.Stream, a raw handle, or torch's current stream when None."""
+    if stream is None:
+        import torch
+        return torch.cuda.current_stream().cuda_stream or None
+    if isinstance(stream, int):
+        return stream or None
+    return stream.cuda_stream or None
+
+
+def _i64_array(xs: Sequence[int]):
+    return (ctypes.c_int64 * len(xs))(*[int(x) for x in xs])
+
+
+def _ptr_array(xs):
+    return (ctypes.c_void_p * len(xs))(*[_addr(x) for x in xs])
+
+
+# --------------------------------------------------------------------------- context
+
+class Ctx:
+    """Owner of an elixir_ctx handle."""
+
+    def __init__(self, handle: int):
+        self.handle = handle
+
+
+def elixir_ctx_create(device: int, max_chunk_elems: int, max_chunks: int) -> Ctx:
+    h = ctypes.c_void_p()
+    _check(lib().elixir_ctx_create(ctypes.byref(h), device, max_chunk_elems, max_chunks))
+    return Ctx(h.value)
+
+
+def elixir_ctx_destroy(ctx: Ctx) -> None:
+    if ctx.handle:
+        h, ctx.handle = ctx.handle, None
+        _check(lib().elixir_ctx_destroy(h))
+
+
+# --------------------------------------------------------------------------- layout
+
+def elixir_layout_plan(numel: Sequence[int], chunk_elems: int, policy: int = ELIXIR_LAYOUT_NEXT_FIT, align_elems: int = 1):
+    """Returns (chunk_id, offset, valid_len) as Python lists."""
+    T = len(numel)
+    nm = _i64_array(numel)
+    cid, off = (ctypes.c_int64 * max(T, 1))(), (ctypes.c_int64 * max(T, 1))()
+    n_chunks = ctypes.c_int64(0)
+    _check(lib().elixir_layout_plan(nm, T, chunk_elems, policy, align_elems, cid, off, ctypes.byref(n_chunks), None, 0))
+    valid = (ctypes.c_int64 * max(n_chunks.value, 1))()
+    _check(lib().elixir_layout_plan(nm, T, chunk_elems, policy, align_elems, cid, off, ctypes.byref(n_chunks), valid,
+                                    n_chunks.value))
+    return list(cid[:T]), list(off[:T]), list(valid[:n_chunks.value])
+
+
+# --------------------------------------------------------------------------- pack / unpack
+
+def elixir_chunk_pack(chunk, chunk_elems: int, elem_size: int, tensors, numel, offset, stream=None) -> None:
+    T = len(tensors)
+    _check(lib().elixir_chunk_pack(_addr(chunk), chunk_elems, elem_size, _ptr_array(tensors), _i64_array(numel),
+                                   _i64_array(offset), T, _stream(stream)))
+
+
+def elixir_chunk_unpack(chunk, chunk_elems: int, elem_size: int, tensors, numel, offset, stream=None) -> None:
+    T = len(tensors)
+    _check(lib().elixir_chunk_unpack(_addr(chunk), chunk_elems, elem_size, _ptr_array(tensors), _i64_array(numel),
+                                     _i64_array(offset), T, _stream(stream)))
+
+
+# --------------------------------------------------------------------------- reduce / norm / step
+
+def elixir_grad_reduce_into_chunk(grad_chunk, offset: int, grad_bf16, n: int, scale: float, accumulate: bool,
+                                  stream=None) -> None:
+    _check(lib().elixir_grad_reduce_into_chunk(_addr(grad_chunk), offset, _addr(grad_bf16), n, scale,
+                                               1 if accumulate else 0, _stream(stream)))
+
+
+def elixir_chunk_grad_norm(ctx: Ctx, grad_chunks, valid_len, max_norm: float, d_norm_out, d_clip_coef_out,
+                           stream=None) -> None:
+    n = len(grad_chunks)
+    _check(lib().elixir_chunk_grad_norm(ctx.handle, _ptr_array(grad_chunks), _i64_array(valid_len), n, max_norm,
+                                        _addr(d_norm_out), _addr(d_clip_coef_out), _stream(stream)))
+
+
+def make_hparams(lr: float, beta1: float, beta2: float, eps: float, weight_decay: float, step: int) -> elixir_adam_hparams:
+    return elixir_adam_hparams(lr, beta1, beta2, eps, weight_decay, step)
+
+
+def elixir_chunk_adam_step(master, exp_avg, exp_avg_sq, grad_fp32, grad_bf16, param_bf16, n: int,
+                           hp: elixir_adam_hparams, d_grad_scale=None, stream=None) -> None:
+    _check(lib().elixir_chunk_adam_step(_addr(master), _addr(exp_avg), _addr(exp_avg_sq), _addr(grad_fp32),
+                                        _addr(grad_bf16), _addr(param_bf16), n, ctypes.byref(hp), _addr(d_grad_scale),
+                                        _stream(stream)))
+
+
+# --------------------------------------------------------------------------- offload
+
+def elixir_host_alloc(nbytes: int) -> int:
+    p = ctypes.c_void_p()
+    _check(lib().elixir_host_alloc(ctypes.byref(p), nbytes))
+    return p.value
+
+
+def elixir_host_free(ptr: int) -> None:
+    _check(lib().elixir_host_free(ptr))
+
+
+def elixir_offload_register_slots(ctx: Ctx, d_slots, slot_bytes: int) -> None:
+    _check(lib().elixir_offload_register_slots(ctx.handle, _ptr_array(d_slots), len(d_slots), slot_bytes))
+
+
+def elixir_chunk_prefetch(ctx: Ctx, h_block: int, nbytes: int, h2d_stream) -> int:
+    slot = ctypes.c_int(-1)
+    _check(lib().elixir_chunk_prefetch(ctx.handle, h_block, nbytes, ctypes.byref(slot), _stream(h2d_stream)))
+    return slot.value
+
+
+def elixir_chunk_wait_ready(ctx: Ctx, slot: int, compute_stream=None) -> None:
+    _check(lib().elixir_chunk_wait_ready(ctx.handle, slot, _stream(compute_stream)))
+
+
+def elixir_chunk_evict(ctx: Ctx, slot: int, h_block: Optional[int], nbytes: int, compute_stream, d2h_stream) -> None:
+    _check(lib().elixir_chunk_evict(ctx.handle, slot, h_block, nbytes, _stream(compute_stream), _stream(d2h_stream)))

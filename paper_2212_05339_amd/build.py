@@ -1,0 +1,48 @@
+"""Builds libelixir_chunk.so (HIP kernels + C ABI) for gfx950 with hipcc, in-tree."""
+from __future__ import annotations
+
+import os
+import subprocess
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+CSRC = os.path.join(_PKG, "csrc")
+LIB = os.path.join(_PKG, "libelixir_chunk.so")
+SOURCES = ["ctx.cpp", "layout.cpp", "offload.cpp", "pack.hip", "reduce.hip", "norm.hip", "adam.hip"]
+
+# -ffp-contract=off: fused multiply-adds appear only where the source asks for them, so the
+#   separately rounded multiply/add of the gradient reduction stay separate.
+# -packed-fp32-ops off: keeps the compiler from forming packed fp32 instructions.
+HIPCC_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-ffp-contract=off",
+               "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wall", "-Wno-unused-command-line-argument"]
+
+
+def build_library(verbose: bool = False) -> str:
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    tmp = LIB + f".tmp{os.getpid()}"
+    cmd = [hipcc, *HIPCC_FLAGS, "-x", "hip", *[os.path.join(CSRC, s) for s in SOURCES], "-o", tmp]
+    if verbose:
+        print(" ".join(cmd), flush=True)
+    subprocess.check_call(cmd)
+    os.replace(tmp, LIB)
+    return LIB
+
+
+def build_synth(verbose: bool = False) -> str:
+    """The device-side twin of the seeded input generator (harness code, separate library)."""
+    root = os.path.dirname(_PKG)
+    src = os.path.join(root, "synth", "gen.hip")
+    out = os.path.join(root, "synth", "libsynth_gen.so")
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    tmp = out + f".tmp{os.getpid()}"
+    cmd = [hipcc, "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-ffp-contract=off",
+           "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wno-unused-command-line-argument", src, "-o", tmp]
+    if verbose:
+        print(" ".join(cmd), flush=True)
+    subprocess.check_call(cmd)
+    os.replace(tmp, out)
+    return out
+
+
+if __name__ == "__main__":
+    print(build_library(verbose=True))
+    print(build_synth(verbose=True))

@@ -1,0 +1,53 @@
+// Internal helpers shared by the translation units of libelixir_chunk.so.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stdio.h>
+#include <string>
+
+#include "../../include/elixir_chunk.h"
+
+namespace elixir {
+
+// Stores the per-thread message returned by elixir_last_error() and hands back `code`.
+int fail(int code, const char* fmt, ...) __attribute__((format(printf, 2, 3)));
+
+inline bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
+
+#define ELIXIR_HIP_TRY(expr)                                                                         \
+    do {                                                                                             \
+        hipError_t e_ = (expr);                                                                      \
+        if (e_ != hipSuccess) return ::elixir::fail(ELIXIR_EHIP, "%s: %s", #expr, hipGetErrorString(e_)); \
+    } while (0)
+
+// Launch check: hipGetLastError after a kernel launch.
+#define ELIXIR_LAUNCH_CHECK(what)                                                                    \
+    do {                                                                                             \
+        hipError_t e_ = hipGetLastError();                                                           \
+        if (e_ != hipSuccess) return ::elixir::fail(ELIXIR_EHIP, "launch of %s: %s", what, hipGetErrorString(e_)); \
+    } while (0)
+
+constexpr int kBlock = 256;          // threads per workgroup: 4 wavefronts of 64
+constexpr int kNormBlocksPerChunk = 1024;  // fixed, so the reduction tree never depends on the launch
+
+struct Slot {
+    void* d_ptr = nullptr;
+    bool held = false;          // prefetched and not yet evicted
+    bool evict_pending = false; // an eviction was enqueued; evicted event is valid
+    hipEvent_t ready = nullptr;   // H2D copy finished
+    hipEvent_t updated = nullptr; // compute stream reached the eviction request
+    hipEvent_t evicted = nullptr; // D2H copy finished (slot reusable)
+};
+
+}  // namespace elixir
+
+struct elixir_ctx {
+    int device = 0;
+    int64_t max_chunk_elems = 0;
+    int max_chunks = 0;
+    double* d_partials = nullptr;  // max_chunks * kNormBlocksPerChunk
+    elixir::Slot* slots = nullptr;
+    int n_slots = 0;
+    size_t slot_bytes = 0;
+    int next_slot = 0;
+};

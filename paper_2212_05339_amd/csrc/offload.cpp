@@ -1,0 +1,98 @@
+// Offload pipeline: staging slots, prefetch (host -> device) and evict (device -> host)
+// of host-resident optimizer chunks on side streams.
+//
+// The paper overlaps chunk movement with computation by issuing it on separate
+// streams in the known order of use (Sec. 4.3).  Here ordering is expressed
+// only with events, so the host thread never blocks:
+//   prefetch : h2d stream waits for the slot's previous eviction, copies, records `ready`
+//   wait     : compute stream waits for `ready`
+//   evict    : d2h stream waits for an event recorded on the compute stream,
+//              copies back, records `evicted`
+// The two copy directions run on different streams and therefore on different
+// DMA engines, so uploads, downloads and kernels proceed concurrently.
+#include "common.hpp"
+
+namespace elixir {
+void destroy_slots(elixir_ctx* c);
+}
+using namespace elixir;
+
+extern "C" int elixir_offload_register_slots(elixir_ctx* ctx, void* const* d_slots, int n_slots, size_t slot_bytes) {
+    if (!ctx) return fail(ELIXIR_EINVAL, "elixir_offload_register_slots: ctx is NULL");
+    if (n_slots < 0 || (n_slots > 0 && (!d_slots || slot_bytes == 0)))
+        return fail(ELIXIR_EINVAL, "elixir_offload_register_slots: bad slot table");
+    for (int i = 0; i < ctx->n_slots; ++i)
+        if (ctx->slots[i].held) return fail(ELIXIR_ESTATE, "elixir_offload_register_slots: slot %d is still held", i);
+    for (int i = 0; i < n_slots; ++i)
+        if (!d_slots[i]) return fail(ELIXIR_EINVAL, "elixir_offload_register_slots: d_slots[%d] is NULL", i);
+    // pending evictions of the old registration must have finished before their events go away
+    for (int i = 0; i < ctx->n_slots; ++i)
+        if (ctx->slots[i].evict_pending) ELIXIR_HIP_TRY(hipEventSynchronize(ctx->slots[i].evicted));
+    destroy_slots(ctx);
+    if (n_slots == 0) return ELIXIR_OK;
+    ctx->slots = new (std::nothrow) Slot[n_slots];
+    if (!ctx->slots) return fail(ELIXIR_EINVAL, "elixir_offload_register_slots: out of host memory");
+    ctx->n_slots = n_slots;
+    ctx->slot_bytes = slot_bytes;
+    for (int i = 0; i < n_slots; ++i) {
+        ctx->slots[i].d_ptr = d_slots[i];
+        hipError_t e = hipEventCreateWithFlags(&ctx->slots[i].ready, hipEventDisableTiming);
+        if (e == hipSuccess) e = hipEventCreateWithFlags(&ctx->slots[i].updated, hipEventDisableTiming);
+        if (e == hipSuccess) e = hipEventCreateWithFlags(&ctx->slots[i].evicted, hipEventDisableTiming);
+        if (e != hipSuccess) {
+            destroy_slots(ctx);
+            return fail(ELIXIR_EHIP, "elixir_offload_register_slots: hipEventCreate: %s", hipGetErrorString(e));
+        }
+    }
+    return ELIXIR_OK;
+}
+
+extern "C" int elixir_chunk_prefetch(elixir_ctx* ctx, const void* h_block, size_t bytes, int* slot_out,
+                                     elixir_stream_t h2d_stream) {
+    if (!ctx || !h_block || !slot_out) return fail(ELIXIR_EINVAL, "elixir_chunk_prefetch: NULL argument");
+    if (ctx->n_slots == 0) return fail(ELIXIR_ESTATE, "elixir_chunk_prefetch: no staging slots registered");
+    if (bytes == 0 || bytes > ctx->slot_bytes)
+        return fail(ELIXIR_EINVAL, "elixir_chunk_prefetch: %zu bytes, slots hold %zu", bytes, ctx->slot_bytes);
+    int slot = -1;
+    for (int k = 0; k < ctx->n_slots; ++k) {  // round robin: the slot evicted longest ago comes first
+        const int i = (ctx->next_slot + k) % ctx->n_slots;
+        if (!ctx->slots[i].held) { slot = i; break; }
+    }
+    if (slot < 0) return fail(ELIXIR_ENOSLOT, "elixir_chunk_prefetch: all %d slots are held", ctx->n_slots);
+    Slot& sl = ctx->slots[slot];
+    hipStream_t s = (hipStream_t)h2d_stream;
+    if (sl.evict_pending) ELIXIR_HIP_TRY(hipStreamWaitEvent(s, sl.evicted, 0));
+    ELIXIR_HIP_TRY(hipMemcpyAsync(sl.d_ptr, h_block, bytes, hipMemcpyHostToDevice, s));
+    ELIXIR_HIP_TRY(hipEventRecord(sl.ready, s));
+    sl.held = true;
+    ctx->next_slot = (slot + 1) % ctx->n_slots;
+    *slot_out = slot;
+    return ELIXIR_OK;
+}
+
+extern "C" int elixir_chunk_wait_ready(elixir_ctx* ctx, int slot, elixir_stream_t compute_stream) {
+    if (!ctx) return fail(ELIXIR_EINVAL, "elixir_chunk_wait_ready: ctx is NULL");
+    if (slot < 0 || slot >= ctx->n_slots) return fail(ELIXIR_EINVAL, "elixir_chunk_wait_ready: slot %d of %d", slot, ctx->n_slots);
+    if (!ctx->slots[slot].held) return fail(ELIXIR_ESTATE, "elixir_chunk_wait_ready: slot %d holds no prefetched chunk", slot);
+    ELIXIR_HIP_TRY(hipStreamWaitEvent((hipStream_t)compute_stream, ctx->slots[slot].ready, 0));
+    return ELIXIR_OK;
+}
+
+extern "C" int elixir_chunk_evict(elixir_ctx* ctx, int slot, void* h_block, size_t bytes, elixir_stream_t compute_stream,
+                                  elixir_stream_t d2h_stream) {
+    if (!ctx) return fail(ELIXIR_EINVAL, "elixir_chunk_evict: ctx is NULL");
+    if (slot < 0 || slot >= ctx->n_slots) return fail(ELIXIR_EINVAL, "elixir_chunk_evict: slot %d of %d", slot, ctx->n_slots);
+    Slot& sl = ctx->slots[slot];
+    if (!sl.held) return fail(ELIXIR_ESTATE, "elixir_chunk_evict: slot %d holds no prefetched chunk", slot);
+    if (h_block && (bytes == 0 || bytes > ctx->slot_bytes))
+        return fail(ELIXIR_EINVAL, "elixir_chunk_evict: %zu bytes, slots hold %zu", bytes, ctx->slot_bytes);
+    hipStream_t cs = (hipStream_t)compute_stream, ds = (hipStream_t)d2h_stream;
+    // everything enqueued so far on the compute stream (the update of this slot) must finish first
+    ELIXIR_HIP_TRY(hipEventRecord(sl.updated, cs));
+    ELIXIR_HIP_TRY(hipStreamWaitEvent(ds, sl.updated, 0));
+    if (h_block) ELIXIR_HIP_TRY(hipMemcpyAsync(h_block, sl.d_ptr, bytes, hipMemcpyDeviceToHost, ds));
+    ELIXIR_HIP_TRY(hipEventRecord(sl.evicted, ds));
+    sl.evict_pending = true;
+    sl.held = false;
+    return ELIXIR_OK;
+}

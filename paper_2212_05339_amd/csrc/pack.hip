@@ -1,0 +1,166 @@
+// elixir_chunk_pack / elixir_chunk_unpack: bit copies between parameter tensors and one chunk.
+//
+// A chunk is the concatenation of a group of flattened parameters (paper Sec. 3
+// "Chunk", Fig. 3 left).  The host turns the request into a list of byte
+// segments (source, destination, length; for pack also the gaps, which are
+// zero-filled), cuts the segments into tiles of kTileBytes and launches one
+// workgroup per tile.  The segment table travels as a kernel argument, so no
+// device memory is allocated or copied for it.  Each tile is moved with the
+// widest access both addresses allow (16, 4 or 2 bytes per lane).
+// Traffic: read + write of every byte (write only for gaps).
+#include <algorithm>
+#include <vector>
+
+#include "common.hpp"
+
+using namespace elixir;
+
+namespace {
+
+constexpr int kMaxSeg = 96;
+constexpr int64_t kTileBytes = 32 * 1024;
+
+struct SegTable {
+    const char* src[kMaxSeg];  // nullptr: fill with zero bits
+    char* dst[kMaxSeg];
+    int64_t bytes[kMaxSeg];
+    uint32_t tile_begin[kMaxSeg + 1];
+    int n_seg;
+};
+
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+template <typename W>
+__device__ __forceinline__ void move_units(char* dst, const char* src, int64_t n_units) {
+    W* D = reinterpret_cast<W*>(dst);
+    const W* S = reinterpret_cast<const W*>(src);
+    if (src) {
+        for (int64_t i = threadIdx.x; i < n_units; i += 256) __builtin_nontemporal_store(__builtin_nontemporal_load(S + i), D + i);
+    } else {
+        const W z = W(0);
+        for (int64_t i = threadIdx.x; i < n_units; i += 256) __builtin_nontemporal_store(z, D + i);
+    }
+}
+
+__global__ __launch_bounds__(256) void segment_copy_kernel(SegTable tab) {
+    // which segment owns this tile: last s with tile_begin[s] <= blockIdx.x
+    int lo = 0, hi = tab.n_seg;
+    while (hi - lo > 1) {
+        const int mid = (lo + hi) >> 1;
+        if (tab.tile_begin[mid] <= blockIdx.x) lo = mid;
+        else hi = mid;
+    }
+    const int64_t off = (int64_t)(blockIdx.x - tab.tile_begin[lo]) * kTileBytes;
+    int64_t len = tab.bytes[lo] - off;
+    if (len > kTileBytes) len = kTileBytes;
+    const char* src = tab.src[lo] ? tab.src[lo] + off : nullptr;
+    char* dst = tab.dst[lo] + off;
+    const uintptr_t a = reinterpret_cast<uintptr_t>(dst) | reinterpret_cast<uintptr_t>(src);
+    int64_t done;
+    if ((a & 15) == 0) {
+        move_units<u32x4>(dst, src, len >> 4);
+        done = len & ~(int64_t)15;
+    } else if ((a & 3) == 0) {
+        move_units<uint32_t>(dst, src, len >> 2);
+        done = len & ~(int64_t)3;
+    } else {
+        done = 0;
+    }
+    if (done < len) move_units<uint16_t>(dst + done, src ? src + done : nullptr, (len - done) >> 1);
+}
+
+struct Seg {
+    const char* src;
+    char* dst;
+    int64_t bytes;
+};
+
+int launch_segments(const std::vector<Seg>& segs, hipStream_t s, const char* what) {
+    size_t i = 0;
+    while (i < segs.size()) {
+        SegTable tab;
+        tab.n_seg = 0;
+        uint64_t tiles = 0;
+        while (i < segs.size() && tab.n_seg < kMaxSeg) {
+            const Seg& g = segs[i];
+            const uint64_t t = (uint64_t)((g.bytes + kTileBytes - 1) / kTileBytes);
+            if (tiles + t > 0x7FFFFFFFull) break;  // keep the grid within 31 bits; the rest goes to the next launch
+            tab.src[tab.n_seg] = g.src;
+            tab.dst[tab.n_seg] = g.dst;
+            tab.bytes[tab.n_seg] = g.bytes;
+            tab.tile_begin[tab.n_seg] = (uint32_t)tiles;
+            tiles += t;
+            ++tab.n_seg;
+            ++i;
+        }
+        if (tab.n_seg == 0) return fail(ELIXIR_EINVAL, "%s: a single slice is too large for one launch", what);
+        for (int j = tab.n_seg; j <= kMaxSeg; ++j) tab.tile_begin[j] = (uint32_t)tiles;
+        for (int j = tab.n_seg; j < kMaxSeg; ++j) { tab.src[j] = nullptr; tab.dst[j] = nullptr; tab.bytes[j] = 0; }
+        hipLaunchKernelGGL(segment_copy_kernel, dim3((unsigned)tiles), dim3(256), 0, s, tab);
+        ELIXIR_LAUNCH_CHECK(what);
+    }
+    return ELIXIR_OK;
+}
+
+// Validates the slices and returns their indices ordered by offset (empty slices dropped).
+int check_slices(const char* what, const void* chunk, int64_t chunk_elems, int elem_size, const void* const* tensors,
+                 const int64_t* numel, const int64_t* offset, int T, std::vector<int>* order) {
+    if (chunk_elems < 0 || T < 0) return fail(ELIXIR_EINVAL, "%s: negative chunk_elems or T", what);
+    if (elem_size != 2 && elem_size != 4) return fail(ELIXIR_EINVAL, "%s: elem_size=%d, must be 2 or 4", what, elem_size);
+    if (chunk_elems > 0 && !chunk) return fail(ELIXIR_EINVAL, "%s: chunk is NULL", what);
+    if (T > 0 && (!tensors || !numel || !offset)) return fail(ELIXIR_EINVAL, "%s: NULL table", what);
+    if (!aligned(chunk, (size_t)elem_size)) return fail(ELIXIR_EALIGN, "%s: chunk not aligned to elem_size", what);
+    order->clear();
+    for (int i = 0; i < T; ++i) {
+        if (numel[i] < 0 || offset[i] < 0 || offset[i] > chunk_elems || numel[i] > chunk_elems - offset[i])
+            return fail(ELIXIR_EINVAL, "%s: slice %d (offset %lld, numel %lld) leaves the chunk of %lld elements", what, i,
+                        (long long)offset[i], (long long)numel[i], (long long)chunk_elems);
+        if (numel[i] == 0) continue;
+        if (!tensors[i]) return fail(ELIXIR_EINVAL, "%s: tensors[%d] is NULL", what, i);
+        if (!aligned(tensors[i], (size_t)elem_size)) return fail(ELIXIR_EALIGN, "%s: tensors[%d] not aligned to elem_size", what, i);
+        order->push_back(i);
+    }
+    std::sort(order->begin(), order->end(), [&](int a, int b) { return offset[a] < offset[b]; });
+    for (size_t k = 1; k < order->size(); ++k) {
+        const int a = (*order)[k - 1], b = (*order)[k];
+        if (offset[a] + numel[a] > offset[b])
+            return fail(ELIXIR_EINVAL, "%s: slices %d and %d overlap", what, a, b);
+    }
+    return ELIXIR_OK;
+}
+
+}  // namespace
+
+extern "C" int elixir_chunk_pack(void* d_chunk, int64_t chunk_elems, int elem_size, const void* const* tensors,
+                                 const int64_t* numel, const int64_t* offset, int T, elixir_stream_t stream) {
+    static const char* what = "elixir_chunk_pack";
+    std::vector<int> order;
+    const int rc = check_slices(what, d_chunk, chunk_elems, elem_size, tensors, numel, offset, T, &order);
+    if (rc != ELIXIR_OK) return rc;
+    char* base = static_cast<char*>(d_chunk);
+    const int64_t es = elem_size;
+    std::vector<Seg> segs;
+    segs.reserve(2 * order.size() + 1);
+    int64_t pos = 0;  // first element not yet covered
+    for (int i : order) {
+        if (offset[i] > pos) segs.push_back({nullptr, base + pos * es, (offset[i] - pos) * es});
+        segs.push_back({static_cast<const char*>(tensors[i]), base + offset[i] * es, numel[i] * es});
+        pos = offset[i] + numel[i];
+    }
+    if (pos < chunk_elems) segs.push_back({nullptr, base + pos * es, (chunk_elems - pos) * es});
+    return launch_segments(segs, (hipStream_t)stream, what);
+}
+
+extern "C" int elixir_chunk_unpack(const void* d_chunk, int64_t chunk_elems, int elem_size, void* const* tensors,
+                                   const int64_t* numel, const int64_t* offset, int T, elixir_stream_t stream) {
+    static const char* what = "elixir_chunk_unpack";
+    std::vector<int> order;
+    const int rc = check_slices(what, d_chunk, chunk_elems, elem_size, tensors, numel, offset, T, &order);
+    if (rc != ELIXIR_OK) return rc;
+    const char* base = static_cast<const char*>(d_chunk);
+    const int64_t es = elem_size;
+    std::vector<Seg> segs;
+    segs.reserve(order.size());
+    for (int i : order) segs.push_back({base + offset[i] * es, static_cast<char*>(tensors[i]), numel[i] * es});
+    return launch_segments(segs, (hipStream_t)stream, what);
+}

@@ -1,0 +1,69 @@
+"""Helpers shared by the GPU parity tests (no method arithmetic here)."""
+from concurrent.futures import ThreadPoolExecutor
+import os
+
+import numpy as np
+
+from oracle import elixir_oracle as orc
+
+HP = dict(lr=1e-4, beta1=0.9, beta2=0.999, eps=1e-8, weight_decay=0.01)
+
+
+def n_threads():
+    return max(1, min(16, len(os.sched_getaffinity(0))))
+
+
+def oracle_adam_parallel(p, m, v, g, out, *, step, grad_scale=1.0, hp=HP, threads=None):
+    """The oracle's AdamW over slices of one chunk on several host threads (the update is elementwise)."""
+    threads = threads or n_threads()
+    n = p.size
+    if n < (1 << 16) or threads == 1:
+        orc.chunk_adam_step(p, m, v, g, out, step=step, grad_scale=grad_scale, **hp)
+        return
+    edges = np.linspace(0, n, threads + 1).astype(np.int64)
+
+    def work(i):
+        a, b = int(edges[i]), int(edges[i + 1])
+        orc.chunk_adam_step(p[a:b], m[a:b], v[a:b], g[a:b], None if out is None else out[a:b], step=step,
+                            grad_scale=grad_scale, **hp)
+
+    with ThreadPoolExecutor(threads) as ex:
+        list(ex.map(work, range(threads)))
+
+
+def sign_magnitude(bits_u16):
+    """bf16 patterns on a line where neighbouring values differ by 1 (for the 1-ulp check)."""
+    b = bits_u16.astype(np.int32)
+    return np.where(b & 0x8000, -(b & 0x7FFF), b)
+
+
+def check_adam_close(got_p, got_m, got_v, ref_p, ref_m, ref_v, *, lr, gmax, steps=1, what=""):
+    """|x_gpu - x_ref| <= 1e-6 * (|x_ref| + floor), where the floor is the size of what was added into x:
+    steps*lr for the master weight (each update is of size ~lr and `steps` of them were summed), max|g| for
+    the momentum and max g^2 for the variance.  Without the floor a relative bound is meaningless for values
+    that cancel to ~0.  Returns the largest relative errors seen on values well above the floor."""
+    out = {}
+    for name, got, ref, floor in (("p", got_p, ref_p, steps * lr), ("m", got_m, ref_m, gmax),
+                                  ("v", got_v, ref_v, gmax * gmax)):
+        got64, ref64 = got.astype(np.float64), ref.astype(np.float64)
+        err = np.abs(got64 - ref64)
+        tol = 1e-6 * (np.abs(ref64) + floor)
+        bad = err > tol
+        assert not bad.any(), (f"{what} {name}: {int(bad.sum())} of {bad.size} elements outside tolerance; worst "
+                               f"err {err[bad].max():.3e} at ref {ref64[bad][np.argmax(err[bad])]:.6e}")
+        nz = np.abs(ref64) > floor
+        out[name] = float((err[nz] / np.abs(ref64[nz])).max()) if nz.any() else 0.0
+    return out
+
+
+def check_bf16_copy(got_bits, got_p, ref_bits, ref_p, *, lr, steps=1, what=""):
+    """The low-precision copy: (a) it is exactly the round-to-nearest-even bf16 of the fp32 master the GPU
+    stored (checked bit for bit with the oracle's rounding); (b) it is within one bf16 ulp of the oracle's
+    copy wherever |p| is large enough for an ulp to exceed the fp32 tolerance (|p| > 1e-3 * steps * lr; below
+    that the master weight is a cancellation residue and only (a) and the fp32 bound apply)."""
+    own = orc.f32_to_bf16(np.ascontiguousarray(got_p))
+    assert np.array_equal(got_bits, own), f"{what}: bf16 copy is not the RNE rounding of the stored master weight"
+    big = np.abs(ref_p) > 1e-3 * steps * lr
+    d = np.abs(sign_magnitude(got_bits[big]) - sign_magnitude(ref_bits[big]))
+    assert d.max(initial=0) <= 1, f"{what}: bf16 copy differs by {int(d.max())} ulp"
+    return float((got_bits == ref_bits).mean()) if got_bits.size else 1.0

@@ -1,0 +1,573 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle on the same seeded inputs.
+
+Bars: bit-exact for pack/unpack, chunk indexing and the gradient reduction; relative 1e-6 (plus the
+absolute floors stated in _util.check_adam_close) for fp32 master weights and moments; at most one
+bf16 ulp for the written-back parameters; relative 1e-5 for the global norm and the clip coefficient.
+"""
+import ctypes
+import zlib
+
+import numpy as np
+import pytest
+
+import paper_2212_05339_amd as ex
+from oracle import elixir_oracle as orc
+from synth import gen
+from tests._util import HP, check_adam_close, check_bf16_copy, oracle_adam_parallel
+
+torch = pytest.importorskip("torch")
+pytestmark = pytest.mark.gpu
+
+DEV = "cuda:0"
+
+
+def dev(a: np.ndarray):
+    """numpy -> device tensor; uint16 travels as int16 bits."""
+    if a.dtype == np.uint16:
+        return torch.from_numpy(a.view(np.int16).copy()).to(DEV)
+    return torch.from_numpy(a.copy()).to(DEV)
+
+
+def host(t, dtype=None) -> np.ndarray:
+    a = t.detach().cpu().numpy()
+    return a.view(dtype) if dtype is not None else a
+
+
+def sync():
+    torch.cuda.synchronize()
+
+
+def hp_struct(step, **over):
+    h = dict(HP, **over)
+    return ex.make_hparams(h["lr"], h["beta1"], h["beta2"], h["eps"], h["weight_decay"], step)
+
+
+@pytest.fixture(scope="module")
+def ctx():
+    c = ex.elixir_ctx_create(0, 64 * gen.Mi, 256)
+    yield c
+    ex.elixir_ctx_destroy(c)
+
+
+# --------------------------------------------------------------------------- generator twin
+
+@pytest.mark.parametrize("zero_pct", [0, 1, 37])
+def test_device_generator_matches_host_generator(zero_pct):
+    n, idx0 = 300_007, 123_456_789_012
+    key = gen.stream_key(gen.BASE_SEED, gen.TAG_GRAD, 3, 1, 2)
+    b = torch.empty(n, dtype=torch.int16, device=DEV)
+    f = torch.empty(n, dtype=torch.float32, device=DEV)
+    gen.fill_bf16_device(b.data_ptr(), n, key, idx0, 1e-3, zero_pct)
+    gen.fill_f32_device(f.data_ptr(), n, key, idx0, 0.02, zero_pct)
+    sync()
+    assert np.array_equal(host(b, np.uint16), gen.fill_bf16(key, idx0, n, 1e-3, zero_pct))
+    assert np.array_equal(host(f).view(np.uint32), gen.fill_f32(key, idx0, n, 0.02, zero_pct).view(np.uint32))
+    if zero_pct:
+        assert abs((host(f) == 0).mean() - zero_pct / 100) < 0.01
+
+
+# --------------------------------------------------------------------------- pack / unpack
+
+def _random_tensors(rng, numels, dtype):
+    if dtype == np.float32:
+        return [rng.integers(0, 1 << 32, size=n, dtype=np.uint64).astype(np.uint32).view(np.float32) for n in numels]
+    return [rng.integers(0, 1 << 16, size=n, dtype=np.uint32).astype(np.uint16) for n in numels]
+
+
+@pytest.mark.parametrize("dtype", [np.float32, np.uint16])
+@pytest.mark.parametrize("case", ["ragged", "aligned64", "many_segments", "big_tiles"])
+def test_pack_unpack_bit_exact(dtype, case):
+    rng = np.random.default_rng(zlib.crc32(f"{case}/{np.dtype(dtype)}".encode()))
+    if case == "ragged":
+        numels, C, align = [5, 1, 17, 0, 64, 9, 33_333, 3, 70_001, 2], 120_000, 1
+    elif case == "aligned64":
+        numels, C, align = [768, 768 * 3, 2304 * 768, 768, 64], 2 * gen.Mi, 64
+    elif case == "many_segments":
+        numels, C, align = [int(x) for x in rng.integers(1, 400, size=300)], 100_000, 1   # > 96 segments: several launches
+    else:
+        numels, C, align = [3_000_001, 17, 999_999], 4 * gen.Mi + 3, 1                    # slices spanning many 32 KiB tiles
+    cid, off, valid = orc.layout_plan(numels, C, orc.NEXT_FIT, align)
+    assert len(valid) == 1
+    tensors = _random_tensors(rng, numels, dtype)
+    want = np.empty(C, dtype)
+    want.view(np.uint8)[:] = 0xAB
+    orc.chunk_pack(want, tensors, off)
+
+    es = np.dtype(dtype).itemsize
+    d_tensors = [dev(t) for t in tensors]
+    d_chunk = dev(np.full(C, 0x5A5A, np.uint16) if es == 2 else np.full(C, 1.5, np.float32))
+    ex.elixir_chunk_pack(d_chunk, C, es, d_tensors, numels, off)
+    sync()
+    got = host(d_chunk, dtype)
+    assert np.array_equal(got.view(np.uint8), want.view(np.uint8)), "packed chunk differs from the oracle's"
+
+    d_outs = [torch.zeros_like(t) for t in d_tensors]
+    ex.elixir_chunk_unpack(d_chunk, C, es, d_outs, numels, off)
+    sync()
+    for t, o in zip(tensors, d_outs):
+        assert np.array_equal(host(o, dtype).view(np.uint8), t.view(np.uint8))
+
+
+def test_pack_misaligned_tensor_pointers_and_subset_unpack():
+    rng = np.random.default_rng(9)
+    C = 50_000
+    backing = dev(_random_tensors(rng, [40_000], np.uint16)[0])
+    h_back = host(backing, np.uint16)
+    # slices of one allocation starting at odd element indices: 2-byte aligned only
+    spans = [(1, 4097), (5001, 12_345), (20_003, 3)]
+    tensors = [backing[a:a + n] for a, n in spans]
+    numels = [n for _, n in spans]
+    off = [3, 4101, 30_001]
+    d_chunk = torch.full((C,), 7, dtype=torch.int16, device=DEV)
+    ex.elixir_chunk_pack(d_chunk, C, 2, tensors, numels, off)
+    sync()
+    want = np.zeros(C, np.uint16)
+    orc.chunk_pack(want, [np.ascontiguousarray(h_back[a:a + n]) for a, n in spans], off)
+    assert np.array_equal(host(d_chunk, np.uint16), want)
+    # unpack only the middle slice
+    out = torch.zeros(12_345, dtype=torch.int16, device=DEV)
+    ex.elixir_chunk_unpack(d_chunk, C, 2, [out], [12_345], [4101])
+    sync()
+    assert np.array_equal(host(out, np.uint16), h_back[5001:5001 + 12_345])
+
+
+def test_pack_empty_and_padding_only():
+    C = 1000
+    d_chunk = torch.full((C,), 3.0, dtype=torch.float32, device=DEV)
+    ex.elixir_chunk_pack(d_chunk, C, 4, [], [], [])
+    sync()
+    assert not host(d_chunk).view(np.uint32).any()
+
+
+# --------------------------------------------------------------------------- gradient reduction
+
+@pytest.mark.parametrize("scale", [0.25, 1.0, 0.3])
+@pytest.mark.parametrize("n,offset", [(0, 0), (1, 0), (3, 5), (5, 4), (4096 * 5 + 3, 64), (300_001, 7), (1 << 20, 0)])
+def test_grad_reduce_bit_exact(scale, n, offset):
+    K = 4
+    C = offset + n + 9
+    mbs = [gen.fill_bf16(gen.stream_key(gen.BASE_SEED, gen.TAG_GRAD, 1, mb, 4), 0, n, 1e-3, zero_pct=1) for mb in range(K)]
+    want = np.full(C, -2.5, np.float32)
+    d_g = dev(want)
+    for mb in range(K):
+        orc.grad_reduce_into_chunk(want, offset, mbs[mb], scale, accumulate=mb > 0)
+        ex.elixir_grad_reduce_into_chunk(d_g, offset, dev(mbs[mb]), n, scale, mb > 0)
+    sync()
+    assert np.array_equal(host(d_g).view(np.uint32), want.view(np.uint32))
+
+
+def test_grad_reduce_special_values():
+    bits = np.arange(65536, dtype=np.uint16)
+    want = np.zeros(65536, np.float32)
+    d_g = dev(np.ones(65536, np.float32))
+    for acc in (False, True):
+        orc.grad_reduce_into_chunk(want, 0, bits, 0.5, acc)
+        ex.elixir_grad_reduce_into_chunk(d_g, 0, dev(bits), 65536, 0.5, acc)
+    sync()
+    got = host(d_g)
+    nan = np.isnan(want)
+    assert np.array_equal(np.isnan(got), nan)
+    assert np.array_equal(got[~nan].view(np.uint32), want[~nan].view(np.uint32))   # incl. denormals, -0, +-Inf
+
+
+# --------------------------------------------------------------------------- norm + clip
+
+def _norm_case(ctx, chunks, valid, max_norm):
+    d_chunks = [dev(c) for c in chunks]
+    d_out = torch.zeros(2, dtype=torch.float32, device=DEV)
+    ex.elixir_chunk_grad_norm(ctx, d_chunks, valid, max_norm, d_out[0:1], d_out[1:2])
+    sync()
+    first = host(d_out).copy()
+    ex.elixir_chunk_grad_norm(ctx, d_chunks, valid, max_norm, d_out[0:1], d_out[1:2])
+    sync()
+    assert np.array_equal(first.view(np.uint32), host(d_out).view(np.uint32)), "norm is not reproducible run to run"
+    want = orc.grad_norm(chunks, valid)
+    want_coef = orc.clip_coef(want, max_norm)
+    assert first[0] == pytest.approx(want, rel=1e-5, abs=1e-30)
+    assert first[1] == pytest.approx(want_coef, rel=1e-5)
+    return float(first[0]), want
+
+
+def test_norm_many_ragged_chunks(ctx):
+    lens = [1 << 20, 777_777, 0, 1, 3, 4, 5, 1023, 4 * 256 * 1024 + 3, 65_536]
+    chunks = [gen.fill_f32(gen.stream_key(7, gen.TAG_GRAD, 0, i), 0, max(n, 1) + 11, 5e-4) for i, n in enumerate(lens)]
+    # padding beyond valid_len holds garbage that must not count
+    for c, n in zip(chunks, lens):
+        c[n:] = 1e20
+    got, want = _norm_case(ctx, chunks, lens, 1.0)
+    assert abs(got - want) <= 2e-7 * want      # fp32 output of a double sum
+
+
+def test_norm_more_chunks_than_one_launch_takes(ctx):
+    n_chunks = 200   # the pointer table of one launch holds 128
+    chunks = [gen.fill_f32(gen.stream_key(8, gen.TAG_GRAD, 0, i), 0, 5000 + 13 * i, 1e-3) for i in range(n_chunks)]
+    _norm_case(ctx, chunks, [c.size for c in chunks], 0.0)
+
+
+def test_norm_misaligned_chunk_pointers(ctx):
+    base = gen.fill_f32(gen.stream_key(9, gen.TAG_GRAD), 0, 100_000, 1e-3)
+    d_base = dev(base)
+    d_out = torch.zeros(2, dtype=torch.float32, device=DEV)
+    for start in (1, 2, 3):
+        views = [d_base[start:start + 50_001], d_base[60_000 + start:60_000 + start + 2]]
+        valid = [50_001, 2]
+        ex.elixir_chunk_grad_norm(ctx, views, valid, 0.5, d_out[0:1], d_out[1:2])
+        sync()
+        want = orc.grad_norm([np.ascontiguousarray(base[start:start + 50_001]),
+                              np.ascontiguousarray(base[60_000 + start:60_000 + start + 2])], valid)
+        assert host(d_out)[0] == pytest.approx(want, rel=1e-5)
+        assert host(d_out)[1] == pytest.approx(orc.clip_coef(want, 0.5), rel=1e-5)
+
+
+def test_norm_closed_forms_and_no_clip(ctx):
+    n = 3_000_001
+    c = np.full(n, np.float32(-0.0123))
+    got, _ = _norm_case(ctx, [c], [n], 0.0)
+    assert got == pytest.approx(0.0123 * np.sqrt(n), rel=1e-6)
+    z = np.zeros(1000, np.float32)
+    d_out = torch.full((2,), 9.0, dtype=torch.float32, device=DEV)
+    ex.elixir_chunk_grad_norm(ctx, [dev(z)], [1000], 1.0, d_out[0:1], d_out[1:2])
+    ex.elixir_chunk_grad_norm(ctx, [], [], 1.0, d_out[0:1], None)
+    sync()
+    assert host(d_out)[0] == 0.0 and host(d_out)[1] == 1.0
+    with pytest.raises(ex.ElixirError) as e:
+        ex.elixir_chunk_grad_norm(ctx, [dev(z)] * 300, [10] * 300, 1.0, d_out[0:1], None)
+    assert e.value.code == ex.ELIXIR_ECAP
+
+
+# --------------------------------------------------------------------------- AdamW
+
+def _adam_state(n, seed, zero_moments):
+    p = gen.fill_f32(gen.stream_key(seed, gen.TAG_PARAM), 0, n, 0.02)
+    if zero_moments:
+        return p, np.zeros(n, np.float32), np.zeros(n, np.float32)
+    # a state Adam can reach: |m| <= sqrt(v), so that an update stays of size ~lr
+    m = gen.fill_f32(gen.stream_key(seed, gen.TAG_MOMENT, 0), 0, n, 3e-4)
+    v = np.square(np.abs(m) + np.abs(gen.fill_f32(gen.stream_key(seed, gen.TAG_MOMENT, 1), 0, n, 1e-3)))
+    return p, m, v
+
+
+@pytest.mark.parametrize("grad_kind", ["bf16", "fp32"])
+@pytest.mark.parametrize("n", [0, 1, 3, 4, 5, 1023, 4096 * 3 + 2, 1_000_003])
+def test_adam_single_step_sizes(grad_kind, n):
+    p, m, v = _adam_state(n, 30, zero_moments=False)
+    gb = gen.fill_bf16(gen.stream_key(30, gen.TAG_GRAD, 5), 0, n, 1e-3, zero_pct=1)
+    g = gb if grad_kind == "bf16" else (orc.bf16_to_f32(gb) * np.float32(1.7)).astype(np.float32)
+    out = np.zeros(n, np.uint16)
+    d = [dev(x) for x in (p, m, v, g)]
+    d_out = torch.zeros(max(n, 1), dtype=torch.int16, device=DEV)
+    ex.elixir_chunk_adam_step(d[0], d[1], d[2], d[3] if grad_kind == "fp32" else None,
+                              d[3] if grad_kind == "bf16" else None, d_out, n, hp_struct(5))
+    sync()
+    orc.chunk_adam_step(p, m, v, g, out, step=5, **HP)
+    check_adam_close(host(d[0]), host(d[1]), host(d[2]), p, m, v, lr=HP["lr"], gmax=5e-3, what=f"n={n}")
+    check_bf16_copy(host(d_out, np.uint16)[:n], host(d[0]), out, p, lr=HP["lr"])
+
+
+@pytest.mark.parametrize("shift", [1, 2, 3])
+def test_adam_misaligned_buffers_take_the_scalar_kernel(shift):
+    n = 70_001
+    p, m, v = _adam_state(n + 8, 31, zero_moments=False)
+    gb = gen.fill_bf16(gen.stream_key(31, gen.TAG_GRAD, 2), 0, n + 8, 1e-3)
+    d_p, d_m, d_v, d_g = dev(p), dev(m), dev(v), dev(gb)
+    d_out = torch.zeros(n + 8, dtype=torch.int16, device=DEV)
+    s = slice(shift, shift + n)
+    ex.elixir_chunk_adam_step(d_p[s], d_m[s], d_v[s], None, d_g[s], d_out[s], n, hp_struct(2))
+    sync()
+    rp, rm, rv, out = p.copy(), m.copy(), v.copy(), np.zeros(n + 8, np.uint16)
+    orc.chunk_adam_step(rp[s], rm[s], rv[s], np.ascontiguousarray(gb[s]), out[s], step=2, **HP)
+    check_adam_close(host(d_p), host(d_m), host(d_v), rp, rm, rv, lr=HP["lr"], gmax=5e-3)
+    check_bf16_copy(host(d_out, np.uint16)[s], host(d_p)[s], out[s], rp[s], lr=HP["lr"])
+    # elements outside the slice are untouched, bit for bit
+    for got, ref in ((host(d_p), p), (host(d_m), m), (host(d_v), v)):
+        assert np.array_equal(got[:shift].view(np.uint32), ref[:shift].view(np.uint32))
+        assert np.array_equal(got[shift + n:].view(np.uint32), ref[shift + n:].view(np.uint32))
+
+
+def test_adam_grad_scale_from_device_and_no_bf16_copy():
+    n = 50_000
+    p, m, v = _adam_state(n, 32, zero_moments=False)
+    g = gen.fill_f32(gen.stream_key(32, gen.TAG_GRAD, 1), 0, n, 5e-4)
+    d = [dev(x) for x in (p, m, v, g)]
+    coef = np.float32(0.0257)
+    d_scale = dev(np.array([coef], np.float32))
+    ex.elixir_chunk_adam_step(d[0], d[1], d[2], d[3], None, None, n, hp_struct(3), d_scale)
+    sync()
+    orc.chunk_adam_step(p, m, v, g, None, step=3, grad_scale=float(coef), **HP)
+    check_adam_close(host(d[0]), host(d[1]), host(d[2]), p, m, v, lr=HP["lr"], gmax=5e-3 * float(coef))
+
+
+def test_adam_first_step_closed_form_on_gpu():
+    # m = v = 0, t = 1, no decay: every parameter moves by lr*g/(|g| + eps)
+    n = 200_000
+    p, m, v = _adam_state(n, 33, zero_moments=True)
+    gb = gen.fill_bf16(gen.stream_key(33, gen.TAG_GRAD, 1), 0, n, 1e-3, zero_pct=1)
+    d = [dev(x) for x in (p, m, v, gb)]
+    ex.elixir_chunk_adam_step(d[0], d[1], d[2], None, d[3], None, n, hp_struct(1, weight_decay=0.0))
+    sync()
+    gf = orc.bf16_to_f32(gb).astype(np.float64)
+    lr, eps = float(np.float32(HP["lr"])), float(np.float32(HP["eps"]))
+    want = p.astype(np.float64) - lr * gf / (np.abs(gf) + eps)
+    assert np.max(np.abs(host(d[0]).astype(np.float64) - want)) <= 1e-6 * lr + 2.0 ** -24 * 0.1
+    assert np.array_equal(host(d[0])[gf == 0], p[gf == 0])
+
+
+def test_adam_padding_stays_zero_bits():
+    n = 10_000
+    z = torch.zeros(4, n, dtype=torch.float32, device=DEV)
+    zg = torch.zeros(n, dtype=torch.int16, device=DEV)
+    out = torch.ones(n, dtype=torch.int16, device=DEV)
+    for t in (1, 2, 3):
+        ex.elixir_chunk_adam_step(z[0], z[1], z[2], None, zg, out, n, hp_struct(t))
+    sync()
+    assert not host(z).view(np.uint32).any() and not host(out).any()
+
+
+def test_adam_non_finite_inputs_propagate_like_the_oracle():
+    p = np.array([1.0, np.inf, np.nan, 0.5, -0.5, 3e38, 1.0, 2.0], np.float32)
+    m = np.zeros(8, np.float32)
+    v = np.zeros(8, np.float32)
+    g = np.array([np.nan, 1.0, 1.0, np.inf, -np.inf, 0.0, 0.0, 1e-3], np.float32)
+    d = [dev(x) for x in (p, m, v, g)]
+    out = torch.zeros(8, dtype=torch.int16, device=DEV)
+    ex.elixir_chunk_adam_step(d[0], d[1], d[2], d[3], None, out, 8, hp_struct(1))
+    sync()
+    ro = np.zeros(8, np.uint16)
+    orc.chunk_adam_step(p, m, v, g, ro, step=1, **HP)
+    for got, ref in ((host(d[0]), p), (host(d[1]), m), (host(d[2]), v)):
+        assert np.array_equal(np.isnan(got), np.isnan(ref))
+        ok = np.isfinite(ref)
+        assert np.allclose(got[ok], ref[ok], rtol=1e-6, atol=1e-10)
+        assert np.array_equal(np.isinf(got), np.isinf(ref))
+    gb, rb = host(out, np.uint16), ro
+    assert np.array_equal(np.isnan(orc.bf16_to_f32(gb)), np.isnan(orc.bf16_to_f32(rb)))
+
+
+# --------------------------------------------------------------------------- whole configurations
+
+def test_config_tiny_gpt2_ten_steps_end_to_end():
+    """Tiny GPT-2-shaped set (21M parameters, 4Mi-element chunks, next-fit grouping): plan, pack, ten AdamW
+    steps with fresh bf16 gradients per step, bf16 copy-out, unpack -- every chunk against the oracle."""
+    cfg = gen.CONFIGS["tiny"]
+    numels, C = cfg.numels(), cfg.chunk_elems
+    cid, off, valid = ex.elixir_layout_plan(numels, C, ex.ELIXIR_LAYOUT_NEXT_FIT, 1)
+    assert (cid, off, valid) == tuple(orc.layout_plan(numels, C, orc.NEXT_FIT, 1))
+    nch = len(valid)
+    assert nch == 7
+    # parameters: tensor i = values with global indices [start_i, start_i + n_i) of the parameter stream
+    pkey = gen.stream_key(gen.BASE_SEED, gen.TAG_PARAM, cfg=1)
+    starts = np.concatenate([[0], np.cumsum(numels)])
+    tensors = [gen.fill_f32(pkey, int(starts[i]), n, cfg.param_std) for i, n in enumerate(numels)]
+    d_tensors = [dev(t) for t in tensors]
+    # pack chunk by chunk (a tensor longer than a chunk is passed piecewise)
+    pieces = [[] for _ in range(nch)]   # per chunk: (tensor index, first element, count, offset in chunk)
+    for i, n in enumerate(numels):
+        c, o, k = cid[i], off[i], 0
+        while k < n or (n == 0 and k == 0):
+            take = min(n - k, C - o)
+            pieces[c].append((i, k, take, o))
+            k += take
+            c, o = c + 1, 0
+            if n == 0:
+                break
+    master = torch.empty(nch, C, dtype=torch.float32, device=DEV)
+    ref_master = np.zeros((nch, C), np.float32)
+    for c in range(nch):
+        ex.elixir_chunk_pack(master[c], C, 4, [d_tensors[i][k:k + t] for i, k, t, o in pieces[c]],
+                             [t for i, k, t, o in pieces[c]], [o for i, k, t, o in pieces[c]])
+        orc.chunk_pack(ref_master[c], [np.ascontiguousarray(tensors[i][k:k + t]) for i, k, t, o in pieces[c]],
+                       [o for i, k, t, o in pieces[c]])
+    sync()
+    assert np.array_equal(host(master).view(np.uint32), ref_master.view(np.uint32))
+    assert sum(valid) == cfg.total_params()
+
+    m = torch.zeros_like(master)
+    v = torch.zeros_like(master)
+    out = torch.zeros(nch, C, dtype=torch.int16, device=DEV)
+    grads = torch.zeros(nch, C, dtype=torch.int16, device=DEV)   # padding stays zero
+    ref_m, ref_v = np.zeros_like(ref_master), np.zeros_like(ref_master)
+    ref_out = np.zeros((nch, C), np.uint16)
+    worst = {"p": 0.0, "m": 0.0, "v": 0.0}
+    for step in range(1, cfg.steps + 1):
+        gkey = gen.stream_key(gen.BASE_SEED, gen.TAG_GRAD, step, 0, 1)
+        hp = hp_struct(step)
+        for c in range(nch):
+            gen.fill_bf16_device(grads[c].data_ptr(), valid[c], gkey, c * C, cfg.grad_std)
+            ex.elixir_chunk_adam_step(master[c], m[c], v[c], None, grads[c], out[c], C, hp)
+        for c in range(nch):
+            g = np.zeros(C, np.uint16)
+            g[:valid[c]] = gen.fill_bf16(gkey, c * C, valid[c], cfg.grad_std)
+            oracle_adam_parallel(ref_master[c], ref_m[c], ref_v[c], g, ref_out[c], step=step)
+    sync()
+    for c in range(nch):
+        e = check_adam_close(host(master[c]), host(m[c]), host(v[c]), ref_master[c], ref_m[c], ref_v[c], lr=HP["lr"],
+                             gmax=3.5e-3, steps=cfg.steps, what=f"chunk {c}")
+        worst = {k: max(worst[k], e[k]) for k in worst}
+        check_bf16_copy(host(out[c], np.uint16), host(master[c]), ref_out[c], ref_master[c], lr=HP["lr"],
+                        steps=cfg.steps, what=f"chunk {c}")
+        # padding never moves
+        assert not host(master[c])[valid[c]:].view(np.uint32).any()
+    print("tiny config, 10 steps: max relative error", worst)
+    # unpack the low-precision parameters back into tensor shapes and compare with the oracle's unpack
+    d_params = [torch.zeros(n, dtype=torch.int16, device=DEV) for n in numels]
+    ref_params = [np.zeros(n, np.uint16) for n in numels]
+    for c in range(nch):
+        ex.elixir_chunk_unpack(out[c], C, 2, [d_params[i][k:k + t] for i, k, t, o in pieces[c]],
+                               [t for i, k, t, o in pieces[c]], [o for i, k, t, o in pieces[c]])
+        views = [ref_params[i][k:k + t] for i, k, t, o in pieces[c]]
+        orc.chunk_unpack(host(out[c], np.uint16).copy(), views, [o for i, k, t, o in pieces[c]])
+    sync()
+    for dp, rp in zip(d_params, ref_params):
+        assert np.array_equal(host(dp, np.uint16), rp)
+
+
+def test_config_accumulate_clip_step_scaled_down(ctx):
+    """The gradient-accumulation + clipping pipeline (4 micro-batches, mean, max-norm 1) on a GPT-2-shaped set
+    scaled to 2 layers / hidden 512 so that the oracle runs in seconds; the launch sequence is the full-size one."""
+    numels = gen.gpt2_tensor_list(2, 512, 50257 // 8, 1024)
+    numels = [n for _, n in numels]
+    C = 2 * gen.Mi
+    cid, off, valid = ex.elixir_layout_plan(numels, C, ex.ELIXIR_LAYOUT_NEXT_FIT, 1)
+    nch = len(valid)
+    K, scale = 4, 0.25
+    gchunks = torch.full((nch, C), 5.0, dtype=torch.float32, device=DEV)
+    ref_g = np.zeros((nch, C), np.float32)
+    stage = torch.empty(C, dtype=torch.int16, device=DEV)
+    grad_std = 0.05                                           # large enough that clipping is active
+    for mb in range(K):
+        key = gen.stream_key(gen.BASE_SEED, gen.TAG_GRAD, 1, mb, 4)
+        for c in range(nch):
+            stage.zero_()
+            gen.fill_bf16_device(stage.data_ptr(), valid[c], key, c * C, grad_std)
+            ex.elixir_grad_reduce_into_chunk(gchunks[c], 0, stage, C, scale, mb > 0)
+            g = np.zeros(C, np.uint16)
+            g[:valid[c]] = gen.fill_bf16(key, c * C, valid[c], grad_std)
+            orc.grad_reduce_into_chunk(ref_g[c], 0, g, scale, mb > 0)
+    sync()
+    assert np.array_equal(host(gchunks).view(np.uint32), ref_g.view(np.uint32))
+    d_nc = torch.zeros(2, dtype=torch.float32, device=DEV)
+    ex.elixir_chunk_grad_norm(ctx, [gchunks[c] for c in range(nch)], valid, 1.0, d_nc[0:1], d_nc[1:2])
+    ref_norm = orc.grad_norm([ref_g[c] for c in range(nch)], valid)
+    ref_coef = orc.clip_coef(ref_norm, 1.0)
+    assert ref_coef < 0.5
+    p = gen.fill_f32(gen.stream_key(gen.BASE_SEED, gen.TAG_PARAM, cfg=4), 0, nch * C, 0.02).reshape(nch, C)
+    for c in range(nch):
+        p[c, valid[c]:] = 0
+    d_p, d_m, d_v = dev(p), torch.zeros(nch, C, device=DEV), torch.zeros(nch, C, device=DEV)
+    d_out = torch.zeros(nch, C, dtype=torch.int16, device=DEV)
+    for c in range(nch):
+        ex.elixir_chunk_adam_step(d_p[c], d_m[c], d_v[c], gchunks[c], None, d_out[c], C, hp_struct(1), d_nc[1:2])
+    sync()
+    assert host(d_nc)[0] == pytest.approx(ref_norm, rel=1e-5)
+    assert host(d_nc)[1] == pytest.approx(ref_coef, rel=1e-5)
+    rm, rv, ro = np.zeros_like(p), np.zeros_like(p), np.zeros((nch, C), np.uint16)
+    gpu_coef = float(host(d_nc)[1])
+    for c in range(nch):
+        # the clip coefficient is compared above to 1e-5; the update is checked with the coefficient the step used
+        oracle_adam_parallel(p[c], rm[c], rv[c], ref_g[c], ro[c], step=1, grad_scale=gpu_coef)
+        check_adam_close(host(d_p[c]), host(d_m[c]), host(d_v[c]), p[c], rm[c], rv[c], lr=HP["lr"],
+                         gmax=0.2 * gpu_coef, what=f"chunk {c}")
+        check_bf16_copy(host(d_out[c], np.uint16), host(d_p[c]), ro[c], p[c], lr=HP["lr"])
+    # gradients in memory stay unscaled
+    assert np.array_equal(host(gchunks).view(np.uint32), ref_g.view(np.uint32))
+
+
+# --------------------------------------------------------------------------- offload pipeline
+
+@pytest.mark.parametrize("n_slots", [1, 2, 3])
+def test_offload_is_bitwise_identical_to_resident(ctx, n_slots):
+    C, n_chunks = 300_000 + 3, 7
+    host_ids = [0, 2, 3, 5, 6]                                   # the rest are resident
+    key = gen.stream_key(gen.BASE_SEED, gen.TAG_PARAM, cfg=5)
+    state = np.stack([np.stack([gen.fill_f32(key, (3 * c + j) * C, C, 0.02) for j in range(3)]) for c in range(n_chunks)])
+    state[:, 2] = np.square(state[:, 2])                         # a valid second moment
+    grads = [dev(gen.fill_bf16(gen.stream_key(gen.BASE_SEED, gen.TAG_GRAD, 1, 0, 5), c * C, C, 1e-3)) for c in range(n_chunks)]
+    hp = hp_struct(4)
+    # all-resident run
+    res = dev(state)
+    res_out = torch.zeros(n_chunks, C, dtype=torch.int16, device=DEV)
+    for c in range(n_chunks):
+        ex.elixir_chunk_adam_step(res[c, 0], res[c, 1], res[c, 2], None, grads[c], res_out[c], C, hp)
+    sync()
+    # offloaded run
+    nbytes = 3 * C * 4
+    blocks = {c: ex.elixir_host_alloc(nbytes) for c in host_ids}
+    try:
+        for c in host_ids:
+            ctypes.memmove(blocks[c], state[c].ctypes.data, nbytes)
+        resident = {c: dev(state[c]) for c in range(n_chunks) if c not in host_ids}
+        slots = [torch.full((3, C), float("nan"), dtype=torch.float32, device=DEV) for _ in range(n_slots)]  # poisoned
+        ex.elixir_offload_register_slots(ctx, slots, nbytes)
+        out = torch.zeros(n_chunks, C, dtype=torch.int16, device=DEV)
+        compute, h2d, d2h = torch.cuda.Stream(), torch.cuda.Stream(), torch.cuda.Stream()
+        sync()
+        pending = list(host_ids)
+        inflight = []                                            # (chunk, slot) prefetched, not yet updated
+        with torch.cuda.stream(compute):
+            for c in range(n_chunks):
+                # keep the staging slots full: prefetch ahead in order of use
+                while pending and len(inflight) < n_slots:
+                    try:
+                        s = ex.elixir_chunk_prefetch(ctx, blocks[pending[0]], nbytes, h2d)
+                    except ex.ElixirError as e:
+                        assert e.code == ex.ELIXIR_ENOSLOT
+                        break
+                    inflight.append((pending.pop(0), s))
+                if c in host_ids:
+                    cc, s = inflight.pop(0)
+                    assert cc == c
+                    ex.elixir_chunk_wait_ready(ctx, s, compute)
+                    buf = slots[s]
+                    ex.elixir_chunk_adam_step(buf[0], buf[1], buf[2], None, grads[c], out[c], C, hp, None, compute)
+                    ex.elixir_chunk_evict(ctx, s, blocks[c], nbytes, compute, d2h)
+                else:
+                    r = resident[c]
+                    ex.elixir_chunk_adam_step(r[0], r[1], r[2], None, grads[c], out[c], C, hp, None, compute)
+        sync()
+        want = host(res)
+        for c in range(n_chunks):
+            if c in host_ids:
+                got = np.empty((3, C), np.float32)
+                ctypes.memmove(got.ctypes.data, blocks[c], nbytes)
+            else:
+                got = host(resident[c])
+            assert np.array_equal(got.view(np.uint32), want[c].view(np.uint32)), f"chunk {c}"
+        assert np.array_equal(host(out), host(res_out))
+        # every slot was released
+        with pytest.raises(ex.ElixirError) as e:
+            ex.elixir_chunk_wait_ready(ctx, 0, compute)
+        assert e.value.code == ex.ELIXIR_ESTATE
+    finally:
+        sync()
+        ex.elixir_offload_register_slots(ctx, [], 0)
+        for b in blocks.values():
+            ex.elixir_host_free(b)
+
+
+def test_offload_slot_exhaustion_and_release(ctx):
+    nbytes = 4096
+    slots = [torch.zeros(1024, dtype=torch.float32, device=DEV) for _ in range(2)]
+    ex.elixir_offload_register_slots(ctx, slots, nbytes)
+    blk = ex.elixir_host_alloc(nbytes)
+    s1 = torch.cuda.Stream()
+    try:
+        a = ex.elixir_chunk_prefetch(ctx, blk, nbytes, s1)
+        b = ex.elixir_chunk_prefetch(ctx, blk, nbytes, s1)
+        assert {a, b} == {0, 1}
+        with pytest.raises(ex.ElixirError) as e:
+            ex.elixir_chunk_prefetch(ctx, blk, nbytes, s1)
+        assert e.value.code == ex.ELIXIR_ENOSLOT
+        with pytest.raises(ex.ElixirError) as e:
+            ex.elixir_offload_register_slots(ctx, slots, nbytes)      # slots still held
+        assert e.value.code == ex.ELIXIR_ESTATE
+        with pytest.raises(ex.ElixirError) as e:
+            ex.elixir_chunk_prefetch(ctx, blk, nbytes + 1, s1)        # larger than a slot
+        assert e.value.code == ex.ELIXIR_EINVAL
+        ex.elixir_chunk_evict(ctx, a, None, 0, s1, s1)                # release without copying back
+        assert ex.elixir_chunk_prefetch(ctx, blk, nbytes, s1) == a
+        ex.elixir_chunk_evict(ctx, a, blk, nbytes, s1, s1)
+        ex.elixir_chunk_evict(ctx, b, None, 0, s1, s1)
+    finally:
+        sync()
+        ex.elixir_offload_register_slots(ctx, [], 0)
+        ex.elixir_host_free(blk)
