@@ -8,19 +8,37 @@ using namespace elixir;
 
 namespace {
 
-// Launch shape of the vector kernel (chosen by measurement on MI355X).
-constexpr int kUnroll = 4;
-constexpr bool kNtLoad = true;
-constexpr bool kNtStore = true;
-constexpr int64_t kMaxGrid = 256 * 16;  // workgroups: 16 per compute unit, grid-stride beyond that
+constexpr int64_t kMaxBlocksPerLaunch = 1ll << 30;  // grid.x stays far below its 2^31 limit; longer chunks take several launches
 
+// Elements [first, first + count) with the vector kernel; count is even and the pointers at `first` are aligned.
 template <bool GRAD_BF16, bool HAS_OUT>
-void launch_vec(float* p, float* m, float* v, const void* g, uint16_t* out, int64_t n4, const AdamConsts& c,
-                const float* d_scale, hipStream_t s) {
-    const int64_t tiles = (n4 + 256 * kUnroll - 1) / (256 * kUnroll);
-    const unsigned grid = (unsigned)(tiles < kMaxGrid ? tiles : kMaxGrid);
-    hipLaunchKernelGGL((adam_vec_kernel<GRAD_BF16, HAS_OUT, kUnroll, kNtLoad, kNtStore>), dim3(grid), dim3(256), 0, s,
-                       p, m, v, g, out, n4, c, d_scale);
+void launch_vec(float* p, float* m, float* v, const void* g, uint16_t* out, int64_t first, int64_t count,
+                const AdamConsts& c, const float* d_scale, hipStream_t s) {
+    const int64_t gsz = GRAD_BF16 ? 2 : 4;
+    while (count > 0) {
+        const int64_t pairs_all = count / kAdamVec;
+        int64_t blocks = (pairs_all + kAdamBlock - 1) / kAdamBlock;
+        if (blocks > kMaxBlocksPerLaunch) blocks = kMaxBlocksPerLaunch;
+        const int64_t pairs = pairs_all < blocks * kAdamBlock ? pairs_all : blocks * kAdamBlock;
+        hipLaunchKernelGGL((adam_vec_kernel<GRAD_BF16, HAS_OUT>), dim3((unsigned)blocks), dim3(kAdamBlock), kAdamLdsBytes, s,
+                           p + first, m + first, v + first, (const void*)((const char*)g + first * gsz),
+                           HAS_OUT ? out + first : nullptr, pairs, c, d_scale);
+        first += pairs * kAdamVec;
+        count -= pairs * kAdamVec;
+    }
+}
+
+template <bool GRAD_BF16>
+void launch_scalar(float* p, float* m, float* v, const void* g, uint16_t* out, int64_t first, int64_t end,
+                   const AdamConsts& c, const float* d_scale, hipStream_t s) {
+    while (first < end) {
+        int64_t blocks = (end - first + 255) / 256;
+        if (blocks > kMaxBlocksPerLaunch) blocks = kMaxBlocksPerLaunch;
+        const int64_t stop = first + blocks * 256 < end ? first + blocks * 256 : end;
+        hipLaunchKernelGGL(adam_scalar_kernel<GRAD_BF16>, dim3((unsigned)blocks), dim3(256), 0, s, p, m, v, g, out, first,
+                           stop, c, d_scale);
+        first = stop;
+    }
 }
 
 }  // namespace
@@ -61,29 +79,32 @@ extern "C" int elixir_chunk_adam_step(float* d_master, float* d_exp_avg, float* 
     hipStream_t s = (hipStream_t)stream;
     const bool bf16 = d_grad_bf16 != nullptr;
     const void* g = bf16 ? (const void*)d_grad_bf16 : (const void*)d_grad_fp32;
-    const bool vec = aligned(d_master, 16) && aligned(d_exp_avg, 16) && aligned(d_exp_avg_sq, 16) &&
-                     aligned(g, bf16 ? 8 : 16) && aligned(d_param_bf16, 8);
-    int64_t done = 0;
-    if (vec && n >= 4) {
-        const int64_t n4 = n / 4;
+    // Vector path: after peeling `head` (0 or 1) elements every fp32 pointer must sit on an 8-byte and every
+    // bf16 pointer on a 4-byte boundary.  Whole chunks always do (head = 0).  Anything else, and the odd
+    // elements at either end, go to the one-element-per-thread kernel, which computes the same values.
+    auto phase = [](const void* q, size_t elem) { return (int)((reinterpret_cast<uintptr_t>(q) / elem) & 1); };
+    const int head = phase(d_master, 4);
+    const bool vec = phase(d_exp_avg, 4) == head && phase(d_exp_avg_sq, 4) == head && phase(g, bf16 ? 2 : 4) == head &&
+                     (!d_param_bf16 || phase(d_param_bf16, 2) == head);
+    int64_t vec_first = 0, vec_count = 0;
+    if (vec && n - head >= kAdamVec) {
+        vec_first = head;
+        vec_count = (n - head) / kAdamVec * kAdamVec;
         if (bf16) {
-            if (d_param_bf16) launch_vec<true, true>(d_master, d_exp_avg, d_exp_avg_sq, g, d_param_bf16, n4, c, d_grad_scale, s);
-            else launch_vec<true, false>(d_master, d_exp_avg, d_exp_avg_sq, g, nullptr, n4, c, d_grad_scale, s);
+            if (d_param_bf16) launch_vec<true, true>(d_master, d_exp_avg, d_exp_avg_sq, g, d_param_bf16, vec_first, vec_count, c, d_grad_scale, s);
+            else launch_vec<true, false>(d_master, d_exp_avg, d_exp_avg_sq, g, nullptr, vec_first, vec_count, c, d_grad_scale, s);
         } else {
-            if (d_param_bf16) launch_vec<false, true>(d_master, d_exp_avg, d_exp_avg_sq, g, d_param_bf16, n4, c, d_grad_scale, s);
-            else launch_vec<false, false>(d_master, d_exp_avg, d_exp_avg_sq, g, nullptr, n4, c, d_grad_scale, s);
+            if (d_param_bf16) launch_vec<false, true>(d_master, d_exp_avg, d_exp_avg_sq, g, d_param_bf16, vec_first, vec_count, c, d_grad_scale, s);
+            else launch_vec<false, false>(d_master, d_exp_avg, d_exp_avg_sq, g, nullptr, vec_first, vec_count, c, d_grad_scale, s);
         }
         ELIXIR_LAUNCH_CHECK("adam_vec_kernel");
-        done = n4 * 4;
     }
-    if (done < n) {  // misaligned buffers, or the last n % 4 elements
-        const int64_t rest = n - done;
-        int64_t blocks = (rest + 255) / 256;
-        if (blocks > 256 * 8) blocks = 256 * 8;
-        if (bf16) hipLaunchKernelGGL(adam_scalar_kernel<true>, dim3((unsigned)blocks), dim3(256), 0, s, d_master, d_exp_avg,
-                                     d_exp_avg_sq, g, d_param_bf16, done, n, c, d_grad_scale);
-        else hipLaunchKernelGGL(adam_scalar_kernel<false>, dim3((unsigned)blocks), dim3(256), 0, s, d_master, d_exp_avg,
-                                d_exp_avg_sq, g, d_param_bf16, done, n, c, d_grad_scale);
+    // [0, vec_first) and [vec_first + vec_count, n)
+    const int64_t ranges[2][2] = {{0, vec_first}, {vec_first + vec_count, n}};
+    for (const auto& r : ranges) {
+        if (r[0] >= r[1]) continue;
+        if (bf16) launch_scalar<true>(d_master, d_exp_avg, d_exp_avg_sq, g, d_param_bf16, r[0], r[1], c, d_grad_scale, s);
+        else launch_scalar<false>(d_master, d_exp_avg, d_exp_avg_sq, g, d_param_bf16, r[0], r[1], c, d_grad_scale, s);
         ELIXIR_LAUNCH_CHECK("adam_scalar_kernel");
     }
     return ELIXIR_OK;
