@@ -71,6 +71,127 @@ def cpu_baseline(cfg, valid0, budget_elems):
                       f"{dt:.2f} s wall on {threads} threads"}
 
 
+def side_rows(ex, gen, torch, cfg, C, nch, valid, state, grads, out, stream, step_ms):
+    """Throughput of the other rows of the path, measured after (outside) the timed region on the same
+    buffers: pack (a plain copy), gradient reduction, global norm, and the offload pipeline."""
+    sh = stream.cuda_stream
+    dev = state.device
+
+    def timed(fn, reps):
+        fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(stream)
+        for _ in range(reps):
+            fn()
+        e1.record(stream)
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) * 1e-3 / reps
+
+    rows = {}
+    scratch = torch.empty(2, C, dtype=torch.float32, device=dev)
+    src, dst = scratch[0], scratch[1]
+    t = timed(lambda: ex.elixir_chunk_pack(dst, C, 4, [src], [C], [0], sh), 10)
+    rows["pack"] = {"what": f"one fp32 tensor of {C} elements into a chunk (plain copy)", "bytes": 8 * C, "GB/s": 8 * C / t / 1e9}
+    g16 = grads[0, 0]
+    t = timed(lambda: ex.elixir_grad_reduce_into_chunk(dst, 0, g16, C, 0.25, False, sh), 10)
+    rows["grad_reduce_first"] = {"what": "bf16 -> fp32 chunk, overwrite", "bytes": 6 * C, "GB/s": 6 * C / t / 1e9}
+    t = timed(lambda: ex.elixir_grad_reduce_into_chunk(dst, 0, g16, C, 0.25, True, sh), 10)
+    rows["grad_reduce_accumulate"] = {"what": "bf16 + fp32 chunk -> fp32 chunk", "bytes": 10 * C, "GB/s": 10 * C / t / 1e9}
+    ctx = ex.elixir_ctx_create(0, C, nch)
+    try:
+        d_nc = torch.zeros(2, dtype=torch.float32, device=dev)
+        chunks = [state[c, 1] for c in range(nch)]          # the momentum buffers stand in for fp32 gradient chunks
+        t = timed(lambda: ex.elixir_chunk_grad_norm(ctx, chunks, valid, 1.0, d_nc[0:1], d_nc[1:2], sh), 5)
+        rows["grad_norm"] = {"what": f"{nch} fp32 chunks, {sum(valid)} valid elements, two-stage fp64 tree",
+                             "bytes": 4 * sum(valid), "GB/s": 4 * sum(valid) / t / 1e9, "ms": t * 1e3}
+        # ---- offload pipeline: n_host chunks live in pinned host memory, the nch resident chunks are updated meanwhile
+        n_host, n_slots = 12, 3
+        nbytes = 3 * C * 4
+        blocks = [ex.elixir_host_alloc(nbytes) for _ in range(n_host)]
+        slots = [torch.zeros(3, C, dtype=torch.float32, device=dev) for _ in range(n_slots)]
+        ex.elixir_offload_register_slots(ctx, slots, nbytes)
+        h2d, d2h = torch.cuda.Stream(), torch.cuda.Stream()
+        hp = ex.make_hparams(cfg.lr, cfg.beta1, cfg.beta2, cfg.eps, cfg.weight_decay, 1)
+        try:
+            for b in blocks:                                   # touch the host blocks once (first-touch, zero state)
+                s = ex.elixir_chunk_prefetch(ctx, b, nbytes, h2d)
+                ex.elixir_chunk_evict(ctx, s, b, nbytes, h2d, d2h)
+            torch.cuda.synchronize()
+
+            def wall(fn):
+                torch.cuda.synchronize()
+                t0 = time.perf_counter()
+                fn()
+                torch.cuda.synchronize()
+                return time.perf_counter() - t0
+
+            def only_h2d():
+                for b in blocks:
+                    s = ex.elixir_chunk_prefetch(ctx, b, nbytes, h2d)
+                    ex.elixir_chunk_evict(ctx, s, None, 0, h2d, h2d)
+
+            def only_d2h():
+                # a slot must be held before it can be evicted: hold it with a 4 KiB upload, then copy the block back
+                for b in blocks:
+                    s = ex.elixir_chunk_prefetch(ctx, b, 4096, h2d)
+                    ex.elixir_chunk_evict(ctx, s, b, nbytes, h2d, d2h)
+
+            def both_ways():
+                # bare bidirectional traffic, no kernels: uploads on one stream, downloads of another block on the other
+                half = n_host // 2
+                for k in range(half):
+                    s = ex.elixir_chunk_prefetch(ctx, blocks[k], nbytes, h2d)          # upload block k
+                    ex.elixir_chunk_evict(ctx, s, None, 0, h2d, h2d)
+                    s2 = ex.elixir_chunk_prefetch(ctx, blocks[half + k], 4096, d2h)    # download into block half+k
+                    ex.elixir_chunk_evict(ctx, s2, blocks[half + k], nbytes, d2h, d2h)
+
+            def resident_step():
+                for c in range(nch):
+                    ex.elixir_chunk_adam_step(state[c, 0], state[c, 1], state[c, 2], None, grads[0, c], out[c], C, hp, None, sh)
+
+            def offload_step(with_resident):
+                pending, inflight = list(range(n_host)), []
+                for k in range(n_host):
+                    while pending and len(inflight) < n_slots:
+                        inflight.append((pending[0], ex.elixir_chunk_prefetch(ctx, blocks[pending.pop(0)], nbytes, h2d)))
+                    j, s = inflight.pop(0)
+                    ex.elixir_chunk_wait_ready(ctx, s, sh)
+                    ex.elixir_chunk_adam_step(slots[s][0], slots[s][1], slots[s][2], None, grads[0, j % nch], out[j % nch], C, hp, None, sh)
+                    ex.elixir_chunk_evict(ctx, s, blocks[j], nbytes, sh, d2h)
+                    if with_resident:                           # resident chunks are updated between offloaded ones
+                        for c in range(k * nch // n_host, (k + 1) * nch // n_host):
+                            ex.elixir_chunk_adam_step(state[c, 0], state[c, 1], state[c, 2], None, grads[0, c], out[c], C, hp, None, sh)
+
+            t_h2d = min(wall(only_h2d) for _ in range(2))
+            t_d2h = min(wall(only_d2h) for _ in range(2))
+            t_both = min(wall(both_ways) for _ in range(2))
+            t_res = min(wall(resident_step) for _ in range(2))
+            t_off = min(wall(lambda: offload_step(False)) for _ in range(2))
+            t_mix = min(wall(lambda: offload_step(True)) for _ in range(2))
+            moved = n_host * nbytes
+            t_dma = max(t_h2d, t_d2h)
+            rows["offload"] = {
+                "what": f"{n_host} host-resident chunks of {C} elements ([master|m|v], {nbytes} bytes each) through {n_slots} "
+                        f"staging slots, prefetch / AdamW / evict on three streams, with the {nch} resident chunks updated meanwhile",
+                "h2d_alone_GB/s": moved / t_h2d / 1e9, "d2h_alone_GB/s": moved / t_d2h / 1e9,
+                "pipeline_ms": t_off * 1e3, "pipeline_GB/s_each_way": moved / t_off / 1e9,
+                "bidirectional_GB/s_each_way": (n_host // 2) * nbytes / t_both / 1e9,
+                "pipeline_frac_of_one_way_link": t_dma / t_off,
+                "pipeline_frac_of_bidirectional_link": (moved / t_off) / ((n_host // 2) * nbytes / t_both),
+                "with_resident_ms": t_mix * 1e3, "resident_alone_ms": t_res * 1e3,
+                "overlap": 1.0 - (t_mix - max(t_off, t_res)) / min(t_off, t_res),
+            }
+        finally:
+            torch.cuda.synchronize()
+            ex.elixir_offload_register_slots(ctx, [], 0)
+            for b in blocks:
+                ex.elixir_host_free(b)
+    finally:
+        ex.elixir_ctx_destroy(ctx)
+    return rows
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -157,6 +278,8 @@ def main():
                      "launch_ms": launch_s * 1e3, "launches_timed": launches,
                      "timing": "HIP events on the launch stream around the timed region / launches"},
     }
+    if not args.no_rows:
+        line["rows"] = side_rows(ex, gen, torch, cfg, C, nch, valid, state, grads, out, stream, wall * 1e3 / K)
     if not args.no_cpu_baseline:
         line["cpu_baseline"] = cpu_baseline(cfg, valid[0], budget_elems=32 * 64 * gen.Mi)
     print(json.dumps(line), flush=True)

@@ -1,9 +1,9 @@
 // elixir_chunk_grad_norm: deterministic global L2 norm of the fp32 gradient chunks
 // and the clipping coefficient, both left in device memory.
 //
-// Stage 1: every chunk is cut into kNormBlocksPerChunk contiguous ranges; one
-//   workgroup sums the squares of one range in double precision: each thread
-//   walks its stripe in a fixed order, the 64 lanes of a wavefront are combined
+// Stage 1: kNormBlocksPerChunk workgroups per chunk; workgroup b sums, in double
+//   precision, the squares of the elements it meets striding through the chunk
+//   (a fixed set, whatever the launch): each thread walks its elements in a fixed order, the 64 lanes of a wavefront are combined
 //   with a shuffle tree, the 4 wavefronts through LDS in wavefront order.  One
 //   double per workgroup goes to a fixed slot of the workspace.
 // Stage 2: a single workgroup adds the slots (each thread a fixed strided
@@ -53,18 +53,16 @@ __global__ __launch_bounds__(256) void sumsq_kernel(ChunkTable tab, double* __re
     const int64_t tail0 = head + (n4 << 2);
     const f32x4* __restrict__ G = reinterpret_cast<const f32x4*>(g + head);
 
-    const int64_t per_block = (n4 + kNormBlocksPerChunk - 1) / kNormBlocksPerChunk;
-    const int64_t lo = (int64_t)blockIdx.x * per_block;
-    int64_t hi = lo + per_block;
-    if (hi > n4) hi = n4;
-
+    // Workgroup b takes the 4-element groups b*256 + t, then the same shifted by 1024*256, and so on:
+    // at any moment the 1024 workgroups of a chunk read one contiguous window that slides through it.
+    constexpr int64_t kStride = (int64_t)kNormBlocksPerChunk * 256;
     double acc = 0.0;
-    int64_t i = lo + threadIdx.x;
-    for (; i + 3 * 256 < hi; i += 4 * 256) {
+    int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    for (; i + 3 * kStride < n4; i += 4 * kStride) {
         const f32x4 a = __builtin_nontemporal_load(G + i);
-        const f32x4 b = __builtin_nontemporal_load(G + i + 256);
-        const f32x4 d = __builtin_nontemporal_load(G + i + 512);
-        const f32x4 e = __builtin_nontemporal_load(G + i + 768);
+        const f32x4 b = __builtin_nontemporal_load(G + i + kStride);
+        const f32x4 d = __builtin_nontemporal_load(G + i + 2 * kStride);
+        const f32x4 e = __builtin_nontemporal_load(G + i + 3 * kStride);
         acc = fma((double)a.x, (double)a.x, acc); acc = fma((double)a.y, (double)a.y, acc);
         acc = fma((double)a.z, (double)a.z, acc); acc = fma((double)a.w, (double)a.w, acc);
         acc = fma((double)b.x, (double)b.x, acc); acc = fma((double)b.y, (double)b.y, acc);
@@ -74,7 +72,7 @@ __global__ __launch_bounds__(256) void sumsq_kernel(ChunkTable tab, double* __re
         acc = fma((double)e.x, (double)e.x, acc); acc = fma((double)e.y, (double)e.y, acc);
         acc = fma((double)e.z, (double)e.z, acc); acc = fma((double)e.w, (double)e.w, acc);
     }
-    for (; i < hi; i += 256) {
+    for (; i < n4; i += kStride) {
         const f32x4 a = __builtin_nontemporal_load(G + i);
         acc = fma((double)a.x, (double)a.x, acc); acc = fma((double)a.y, (double)a.y, acc);
         acc = fma((double)a.z, (double)a.z, acc); acc = fma((double)a.w, (double)a.w, acc);

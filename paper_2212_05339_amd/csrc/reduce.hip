@@ -19,50 +19,37 @@ __device__ __forceinline__ float reduce_elem(float old, uint32_t bf16_bits, floa
     return old + t;
 }
 
-constexpr int kUnroll = 4;
+constexpr int kVecBlock = 128;  // one 4-element group per thread, one workgroup per 512 elements, no loop:
+                                // workgroups are dispatched in index order, so the three streams advance as
+                                // sequential fronts; with 128-bit accesses at full residency ~8 MB are in flight,
+                                // which measured best for this 1-2 read / 1 write stream mix
+constexpr int64_t kMaxBlocksPerLaunch = 1ll << 30;
 
 // dst 16-byte aligned, src 8-byte aligned; n4 complete groups of 4 elements.
 template <bool ACC>
-__global__ __launch_bounds__(256) void reduce_vec_kernel(float* __restrict__ dst, const uint16_t* __restrict__ src,
-                                                        int64_t n4, float scale) {
-    f32x4* D = reinterpret_cast<f32x4*>(dst);
-    const u32x2* S = reinterpret_cast<const u32x2*>(src);
-    constexpr int64_t kTile = 256 * kUnroll;
-    const int64_t n_tiles = (n4 + kTile - 1) / kTile;
-    for (int64_t tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
-        const int64_t base = tile * kTile + threadIdx.x;
-        u32x2 g[kUnroll];
-        f32x4 a[kUnroll];
-#pragma unroll
-        for (int u = 0; u < kUnroll; ++u) {
-            const int64_t i = base + (int64_t)u * 256;
-            if (i < n4) {
-                g[u] = __builtin_nontemporal_load(S + i);
-                if constexpr (ACC) a[u] = __builtin_nontemporal_load(D + i);
-                else a[u] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
-            }
-        }
-#pragma unroll
-        for (int u = 0; u < kUnroll; ++u) {
-            const int64_t i = base + (int64_t)u * 256;
-            if (i < n4) {
-                f32x4 r;
-                r.x = reduce_elem(a[u].x, g[u].x & 0xFFFFu, scale);
-                r.y = reduce_elem(a[u].y, g[u].x >> 16, scale);
-                r.z = reduce_elem(a[u].z, g[u].y & 0xFFFFu, scale);
-                r.w = reduce_elem(a[u].w, g[u].y >> 16, scale);
-                __builtin_nontemporal_store(r, D + i);
-            }
-        }
-    }
+__global__ __launch_bounds__(kVecBlock) void reduce_vec_kernel(float* __restrict__ dst, const uint16_t* __restrict__ src,
+                                                              int64_t n4, float scale) {
+    const int64_t i = (int64_t)blockIdx.x * kVecBlock + threadIdx.x;
+    if (i >= n4) return;
+    f32x4* D = reinterpret_cast<f32x4*>(dst) + i;
+    const u32x2 g = __builtin_nontemporal_load(reinterpret_cast<const u32x2*>(src) + i);
+    f32x4 a;
+    if constexpr (ACC) a = __builtin_nontemporal_load(D);
+    else a = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
+    f32x4 r;
+    r.x = reduce_elem(a.x, g.x & 0xFFFFu, scale);
+    r.y = reduce_elem(a.y, g.x >> 16, scale);
+    r.z = reduce_elem(a.z, g.y & 0xFFFFu, scale);
+    r.w = reduce_elem(a.w, g.y >> 16, scale);
+    __builtin_nontemporal_store(r, D);
 }
 
+// elements [first, n), any alignment
 template <bool ACC>
 __global__ __launch_bounds__(256) void reduce_scalar_kernel(float* dst, const uint16_t* src, int64_t first, int64_t n,
                                                            float scale) {
-    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
-    for (int64_t k = first + (int64_t)blockIdx.x * blockDim.x + threadIdx.x; k < n; k += stride)
-        dst[k] = reduce_elem(ACC ? dst[k] : 0.0f, src[k], scale);
+    const int64_t k = first + (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (k < n) dst[k] = reduce_elem(ACC ? dst[k] : 0.0f, src[k], scale);
 }
 
 }  // namespace
@@ -80,20 +67,26 @@ extern "C" int elixir_grad_reduce_into_chunk(float* d_grad_chunk, int64_t offset
     float* dst = d_grad_chunk + offset;
     int64_t done = 0;
     if (aligned(dst, 16) && aligned(d_grad_bf16, 8) && n >= 4) {
-        const int64_t n4 = n / 4;
-        const int64_t tiles = (n4 + 256 * kUnroll - 1) / (256 * kUnroll);
-        const unsigned grid = (unsigned)(tiles < 256 * 16 ? tiles : 256 * 16);
-        if (accumulate) hipLaunchKernelGGL(reduce_vec_kernel<true>, dim3(grid), dim3(256), 0, s, dst, d_grad_bf16, n4, scale);
-        else hipLaunchKernelGGL(reduce_vec_kernel<false>, dim3(grid), dim3(256), 0, s, dst, d_grad_bf16, n4, scale);
+        int64_t n4 = n / 4, at = 0;
+        while (at < n4) {
+            int64_t blocks = (n4 - at + kVecBlock - 1) / kVecBlock;
+            if (blocks > kMaxBlocksPerLaunch) blocks = kMaxBlocksPerLaunch;
+            const int64_t cnt = n4 - at < blocks * kVecBlock ? n4 - at : blocks * kVecBlock;
+            if (accumulate) hipLaunchKernelGGL(reduce_vec_kernel<true>, dim3((unsigned)blocks), dim3(kVecBlock), 0, s, dst + at * 4, d_grad_bf16 + at * 4, cnt, scale);
+            else hipLaunchKernelGGL(reduce_vec_kernel<false>, dim3((unsigned)blocks), dim3(kVecBlock), 0, s, dst + at * 4, d_grad_bf16 + at * 4, cnt, scale);
+            at += cnt;
+        }
         ELIXIR_LAUNCH_CHECK("reduce_vec_kernel");
         done = n4 * 4;
     }
-    if (done < n) {
+    while (done < n) {
         int64_t blocks = (n - done + 255) / 256;
-        if (blocks > 256 * 8) blocks = 256 * 8;
-        if (accumulate) hipLaunchKernelGGL(reduce_scalar_kernel<true>, dim3((unsigned)blocks), dim3(256), 0, s, dst, d_grad_bf16, done, n, scale);
-        else hipLaunchKernelGGL(reduce_scalar_kernel<false>, dim3((unsigned)blocks), dim3(256), 0, s, dst, d_grad_bf16, done, n, scale);
+        if (blocks > kMaxBlocksPerLaunch) blocks = kMaxBlocksPerLaunch;
+        const int64_t stop = done + blocks * 256 < n ? done + blocks * 256 : n;
+        if (accumulate) hipLaunchKernelGGL(reduce_scalar_kernel<true>, dim3((unsigned)blocks), dim3(256), 0, s, dst, d_grad_bf16, done, stop, scale);
+        else hipLaunchKernelGGL(reduce_scalar_kernel<false>, dim3((unsigned)blocks), dim3(256), 0, s, dst, d_grad_bf16, done, stop, scale);
         ELIXIR_LAUNCH_CHECK("reduce_scalar_kernel");
+        done = stop;
     }
     return ELIXIR_OK;
 }
