@@ -67,7 +67,7 @@ extern "C" int elixir_chunk_adam_step(float* d_master, float* d_exp_avg, float* 
     const double bc1 = 1.0 - pow(b1, (double)hp->step);
     const double bc2 = 1.0 - pow(b2, (double)hp->step);
     AdamConsts c;
-    c.decay = (float)(1.0 - lr * (double)hp->weight_decay);
+    c.lr_wd = (float)(lr * (double)hp->weight_decay);
     c.beta1 = hp->beta1;
     c.omb1 = (float)(1.0 - b1);
     c.beta2 = hp->beta2;

@@ -24,7 +24,7 @@ namespace elixir {
 
 // Constants of one step, derived on the host in double precision.
 struct AdamConsts {
-    float decay;         // 1 - lr*wd
+    float lr_wd;         // lr*wd (the decay factor 1 - lr*wd is not representable well enough in fp32)
     float beta1, omb1;   // beta1, 1 - beta1
     float beta2, omb2;   // beta2, 1 - beta2
     float step_size;     // lr / (1 - beta1^t)
@@ -51,7 +51,9 @@ __device__ __forceinline__ void adam_elem(float& p, float& m, float& v, float g,
     v = __builtin_fmaf(c.beta2, v, (c.omb2 * g) * g);
     const float denom = __builtin_fmaf(__builtin_amdgcn_sqrtf(v), c.inv_sqrt_bc2, c.eps);
     const float upd = (c.step_size * m) * __builtin_amdgcn_rcpf(denom);
-    p = __builtin_fmaf(p, c.decay, -upd);
+    // p*(1 - lr*wd) - upd as p + (-(lr*wd)*p - upd): both small terms are combined first, so p is rounded once
+    // and the fp32 rounding of the constant acts on a term of size 1e-6*p, not on p itself
+    p = p + __builtin_fmaf(p, -c.lr_wd, -upd);
 }
 
 typedef float f32x2 __attribute__((ext_vector_type(2)));

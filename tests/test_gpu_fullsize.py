@@ -1,0 +1,260 @@
+"""GPU parity at the benchmark's full sizes, in the launch configuration bench.py times: whole 64Mi- and
+128Mi-element chunks of the GPT-2-shaped 1.5B / 6B / 20B sets.  The oracle checks sampled whole chunks
+element by element (the update and the reduction are elementwise, so a chunk is a complete unit) and the
+global norm in full.  Gradients are generated on the device by the seeded generator; what the oracle gets
+is that buffer copied back, after slices of it have been checked against the host generator."""
+import ctypes
+from concurrent.futures import ThreadPoolExecutor
+
+import numpy as np
+import pytest
+
+import paper_2212_05339_amd as ex
+from oracle import elixir_oracle as orc
+from synth import gen
+from tests._util import HP, check_adam_close, check_bf16_copy, n_threads, oracle_adam_parallel
+
+torch = pytest.importorskip("torch")
+pytestmark = [pytest.mark.gpu, pytest.mark.timeout(400)]
+DEV = "cuda:0"
+
+
+def hp_struct(step):
+    return ex.make_hparams(HP["lr"], HP["beta1"], HP["beta2"], HP["eps"], HP["weight_decay"], step)
+
+
+def u16(t):
+    return t.cpu().numpy().view(np.uint16)
+
+
+def device_grads(buf, valid, key, idx0, std, zero_pct, rng):
+    """Fill buf[:valid] on the device (padding zero), copy back, and spot-check slices against the host generator."""
+    buf.zero_()
+    gen.fill_bf16_device(buf.data_ptr(), valid, key, idx0, std, zero_pct)
+    torch.cuda.synchronize()
+    h = u16(buf)
+    for a in [0, max(0, valid - 4096)] + [int(x) for x in rng.integers(0, max(1, valid - 4096), size=3)]:
+        n = min(4096, valid - a)
+        assert np.array_equal(h[a:a + n], gen.fill_bf16(key, idx0 + a, n, std, zero_pct)), "device generator differs from host"
+    assert not h[valid:].any()
+    return h
+
+
+def test_gpt2_1p5b_sampled_chunks_twenty_steps():
+    cfg = gen.CONFIGS["gpt2_1p5b"]
+    C = cfg.chunk_elems
+    cid, off, valid = ex.elixir_layout_plan(cfg.numels(), C, ex.ELIXIR_LAYOUT_NEXT_FIT, 1)
+    assert (cid, off, valid) == tuple(orc.layout_plan(cfg.numels(), C, orc.NEXT_FIT, 1))
+    nch = len(valid)
+    assert nch == 26 and sum(valid) == 1_557_611_200
+    rng = np.random.default_rng(2)
+    sampled = [0, 1, int(rng.integers(2, nch - 1)), nch - 1]   # wte's full chunk, wte's tail + small tensors, a middle one, the ragged last
+    assert valid[0] == C and valid[nch - 1] < C
+    pkey = gen.stream_key(gen.BASE_SEED, gen.TAG_PARAM, cfg=cfg.cfg_id)
+    state = torch.empty(3, C, dtype=torch.float32, device=DEV)
+    g = torch.empty(C, dtype=torch.int16, device=DEV)
+    out = torch.empty(C, dtype=torch.int16, device=DEV)
+    for c in sampled:
+        state.zero_()
+        gen.fill_f32_device(state[0].data_ptr(), valid[c], pkey, c * C, cfg.param_std)
+        torch.cuda.synchronize()
+        ref = state.cpu().numpy()
+        assert valid[c] >= 4096 and np.array_equal(ref[0, :4096], gen.fill_f32(pkey, c * C, 4096, cfg.param_std))
+        rp, rm, rv = ref[0].copy(), ref[1].copy(), ref[2].copy()
+        rout = np.zeros(C, np.uint16)
+        for step in range(1, cfg.steps + 1):
+            gkey = gen.stream_key(gen.BASE_SEED, gen.TAG_GRAD, step, 0, cfg.cfg_id)
+            hg = device_grads(g, valid[c], gkey, c * C, cfg.grad_std, cfg.grad_zero_pct, rng)
+            ex.elixir_chunk_adam_step(state[0], state[1], state[2], None, g, out, C, hp_struct(step))
+            oracle_adam_parallel(rp, rm, rv, hg, rout, step=step)
+        torch.cuda.synchronize()
+        got = state.cpu().numpy()
+        err = check_adam_close(got[0], got[1], got[2], rp, rm, rv, lr=HP["lr"], gmax=3.5e-3, steps=cfg.steps,
+                               what=f"1.5B chunk {c}")
+        same = check_bf16_copy(u16(out), got[0], rout, rp, lr=HP["lr"], steps=cfg.steps, what=f"1.5B chunk {c}")
+        assert not got[:, valid[c]:].view(np.uint32).any(), "padding moved"
+        print(f"chunk {c}: valid {valid[c]}, max rel err {err}, bf16 identical {same:.6f}")
+
+
+def _oracle_norm_streamed(chunks, valid):
+    """sqrt(sum of squares) with the oracle, one chunk at a time from device memory, chunks spread over threads."""
+    def one(i):
+        h = chunks[i][:valid[i]].cpu().numpy()
+        k = n_threads()
+        edges = np.linspace(0, h.size, k + 1).astype(np.int64)
+        return [orc.sum_squares(h[edges[j]:edges[j + 1]]) for j in range(k)]
+    import math
+    parts = []
+    with ThreadPoolExecutor(4) as pool:
+        for r in pool.map(one, range(len(chunks))):
+            parts += r
+    return math.sqrt(math.fsum(parts))
+
+
+def test_gpt2_6b_accumulate_norm_clip_step_full_size():
+    """Four micro-batches reduced into fp32 chunks (mean), global norm over all 50 chunks of 128Mi elements,
+    clip to max-norm 1, AdamW with the clip coefficient taken from device memory."""
+    cfg = gen.CONFIGS["gpt2_6b_clip"]
+    C = cfg.chunk_elems
+    cid, off, valid = ex.elixir_layout_plan(cfg.numels(), C, ex.ELIXIR_LAYOUT_NEXT_FIT, 1)
+    nch = len(valid)
+    assert nch == 50 and sum(valid) == 6_064_342_400
+    K, scale = cfg.micro_batches, 0.25
+    rng = np.random.default_rng(4)
+    sampled = sorted({0, 1, nch - 1, int(rng.integers(2, nch - 1))})
+    gch = torch.empty(nch, C, dtype=torch.float32, device=DEV)            # 26.8 GB
+    stage = torch.empty(C, dtype=torch.int16, device=DEV)
+    ref_g = {c: np.zeros(C, np.float32) for c in sampled}
+    for mb in range(K):
+        key = gen.stream_key(gen.BASE_SEED, gen.TAG_GRAD, 1, mb, cfg.cfg_id)
+        for c in range(nch):
+            if c in sampled:
+                hg = device_grads(stage, valid[c], key, c * C, cfg.grad_std, 0, rng)
+                orc.grad_reduce_into_chunk(ref_g[c], 0, hg, scale, mb > 0)
+            else:
+                stage.zero_()
+                gen.fill_bf16_device(stage.data_ptr(), valid[c], key, c * C, cfg.grad_std, 0)
+            ex.elixir_grad_reduce_into_chunk(gch[c], 0, stage, C, scale, mb > 0)
+    torch.cuda.synchronize()
+    for c in sampled:
+        assert np.array_equal(gch[c].cpu().numpy().view(np.uint32), ref_g[c].view(np.uint32)), f"reduced chunk {c} differs"
+    ctx = ex.elixir_ctx_create(0, C, nch)
+    try:
+        d_nc = torch.zeros(2, dtype=torch.float32, device=DEV)
+        ex.elixir_chunk_grad_norm(ctx, [gch[c] for c in range(nch)], valid, cfg.max_norm, d_nc[0:1], d_nc[1:2])
+        torch.cuda.synchronize()
+        first = d_nc.cpu().numpy().copy()
+        ex.elixir_chunk_grad_norm(ctx, [gch[c] for c in range(nch)], valid, cfg.max_norm, d_nc[0:1], d_nc[1:2])
+        torch.cuda.synchronize()
+        assert np.array_equal(first.view(np.uint32), d_nc.cpu().numpy().view(np.uint32)), "norm not reproducible"
+        want = _oracle_norm_streamed([gch[c] for c in range(nch)], valid)
+        want_coef = orc.clip_coef(want, cfg.max_norm)
+        print(f"6B norm: gpu {first[0]:.6f} oracle {want:.6f}; clip gpu {first[1]:.8f} oracle {want_coef:.8f}")
+        assert abs(first[0] - want) <= 1e-5 * want
+        assert abs(first[1] - want_coef) <= 1e-5 * want_coef
+        # mean of 4 gradients of sigma 1e-3 -> sigma 5e-4 per element -> norm ~ 5e-4*sqrt(6.06e9) ~ 38.9: clipping is active
+        assert 35.0 < want < 43.0 and want_coef < 0.03
+        # the norm of a single chunk (one-chunk call) against the oracle, and the per-chunk sums adding up to the global one
+        sq = 0.0
+        one = torch.zeros(1, dtype=torch.float32, device=DEV)
+        for c in range(nch):
+            ex.elixir_chunk_grad_norm(ctx, [gch[c]], [valid[c]], 0.0, one, None)
+            torch.cuda.synchronize()
+            sq += float(one.item()) ** 2
+        assert abs(np.sqrt(sq) - first[0]) <= 2e-6 * first[0]
+        # AdamW on the sampled chunks with the device-resident clip coefficient
+        coef = float(first[1])
+        pkey = gen.stream_key(gen.BASE_SEED, gen.TAG_PARAM, cfg=cfg.cfg_id)
+        state = torch.empty(3, C, dtype=torch.float32, device=DEV)
+        out = torch.empty(C, dtype=torch.int16, device=DEV)
+        for c in sampled:
+            state.zero_()
+            gen.fill_f32_device(state[0].data_ptr(), valid[c], pkey, c * C, cfg.param_std)
+            torch.cuda.synchronize()
+            ref = state.cpu().numpy()
+            ex.elixir_chunk_adam_step(state[0], state[1], state[2], gch[c], None, out, C, hp_struct(1), d_nc[1:2])
+            torch.cuda.synchronize()
+            rp, rm, rv, rout = ref[0].copy(), ref[1].copy(), ref[2].copy(), np.zeros(C, np.uint16)
+            oracle_adam_parallel(rp, rm, rv, ref_g[c], rout, step=1, grad_scale=coef)
+            got = state.cpu().numpy()
+            check_adam_close(got[0], got[1], got[2], rp, rm, rv, lr=HP["lr"], gmax=3e-3 * coef, what=f"6B chunk {c}")
+            check_bf16_copy(u16(out), got[0], rout, rp, lr=HP["lr"], what=f"6B chunk {c}")
+            assert np.array_equal(gch[c].cpu().numpy().view(np.uint32), ref_g[c].view(np.uint32)), "gradients were rewritten"
+    finally:
+        ex.elixir_ctx_destroy(ctx)
+
+
+def test_gpt2_20b_offload_mix_full_size_chunks():
+    """128Mi-element chunks of the 20B set: 60% of the sampled chunks live in pinned host memory (1.6 GB blocks),
+    the rest in HBM; one AdamW step through two staging slots.  Host-resident and resident chunks must end up
+    bitwise identical to the all-resident run, and that run matches the oracle on a sampled chunk."""
+    cfg = gen.CONFIGS["gpt2_20b_offload"]
+    C = cfg.chunk_elems
+    cid, off, valid = ex.elixir_layout_plan(cfg.numels(), C, ex.ELIXIR_LAYOUT_NEXT_FIT, 1)
+    nch = len(valid)
+    assert nch == 194 and sum(valid) == 20_399_488_000
+    rng = np.random.default_rng(5)
+    chunks = sorted({0, 1, nch - 1, *[int(x) for x in rng.integers(2, nch - 1, size=2)]})   # 5 sampled chunks
+    host_ids = chunks[:3]                                                               # 60% of them
+    pkey = gen.stream_key(gen.BASE_SEED, gen.TAG_PARAM, cfg=cfg.cfg_id)
+    gkey = gen.stream_key(gen.BASE_SEED, gen.TAG_GRAD, 1, 0, cfg.cfg_id)
+    nbytes = 3 * C * 4
+
+    def fresh_state(c, t):
+        t.zero_()
+        gen.fill_f32_device(t[0].data_ptr(), valid[c], pkey, c * C, cfg.param_std)
+
+    grads = {}
+    for c in chunks:
+        grads[c] = torch.zeros(C, dtype=torch.int16, device=DEV)
+        gen.fill_bf16_device(grads[c].data_ptr(), valid[c], gkey, c * C, cfg.grad_std, 0)
+    hp = hp_struct(1)
+    # all-resident reference run on the GPU
+    res = {c: torch.empty(3, C, dtype=torch.float32, device=DEV) for c in chunks}
+    res_out = {c: torch.zeros(C, dtype=torch.int16, device=DEV) for c in chunks}
+    for c in chunks:
+        fresh_state(c, res[c])
+        ex.elixir_chunk_adam_step(res[c][0], res[c][1], res[c][2], None, grads[c], res_out[c], C, hp)
+    torch.cuda.synchronize()
+    # oracle on one sampled chunk of the resident run
+    c0 = chunks[-2]
+    tmp = torch.empty(3, C, dtype=torch.float32, device=DEV)
+    fresh_state(c0, tmp)
+    torch.cuda.synchronize()
+    ref = tmp.cpu().numpy()
+    rout = np.zeros(C, np.uint16)
+    hg = u16(grads[c0])
+    assert np.array_equal(hg[:4096], gen.fill_bf16(gkey, c0 * C, 4096, cfg.grad_std))
+    oracle_adam_parallel(ref[0], ref[1], ref[2], hg, rout, step=1)
+    got = res[c0].cpu().numpy()
+    check_adam_close(got[0], got[1], got[2], ref[0], ref[1], ref[2], lr=HP["lr"], gmax=3.5e-3, what=f"20B chunk {c0}")
+    check_bf16_copy(u16(res_out[c0]), got[0], rout, ref[0], lr=HP["lr"], what=f"20B chunk {c0}")
+    del ref, got
+    # offloaded run
+    ctx = ex.elixir_ctx_create(0, C, 8)
+    blocks = {c: ex.elixir_host_alloc(nbytes) for c in host_ids}
+    try:
+        for c in host_ids:                                   # initial state goes to the host blocks
+            fresh_state(c, tmp)
+            torch.cuda.synchronize()
+            h = tmp.cpu().numpy()
+            ctypes.memmove(blocks[c], h.ctypes.data, nbytes)
+        resident = {}
+        for c in chunks:
+            if c not in host_ids:
+                resident[c] = torch.empty(3, C, dtype=torch.float32, device=DEV)
+                fresh_state(c, resident[c])
+        slots = [torch.full((3, C), float("nan"), dtype=torch.float32, device=DEV) for _ in range(2)]
+        ex.elixir_offload_register_slots(ctx, slots, nbytes)
+        out = {c: torch.zeros(C, dtype=torch.int16, device=DEV) for c in chunks}
+        compute, h2d, d2h = torch.cuda.Stream(), torch.cuda.Stream(), torch.cuda.Stream()
+        torch.cuda.synchronize()
+        pending, inflight = list(host_ids), []
+        for c in chunks:
+            while pending and len(inflight) < 2:
+                inflight.append((pending[0], ex.elixir_chunk_prefetch(ctx, blocks[pending.pop(0)], nbytes, h2d)))
+            if c in host_ids:
+                cc, s = inflight.pop(0)
+                assert cc == c
+                ex.elixir_chunk_wait_ready(ctx, s, compute)
+                ex.elixir_chunk_adam_step(slots[s][0], slots[s][1], slots[s][2], None, grads[c], out[c], C, hp, None, compute)
+                ex.elixir_chunk_evict(ctx, s, blocks[c], nbytes, compute, d2h)
+            else:
+                r = resident[c]
+                ex.elixir_chunk_adam_step(r[0], r[1], r[2], None, grads[c], out[c], C, hp, None, compute)
+        torch.cuda.synchronize()
+        for c in chunks:
+            want = res[c].cpu().numpy()
+            if c in host_ids:
+                got = np.empty((3, C), np.float32)
+                ctypes.memmove(got.ctypes.data, blocks[c], nbytes)
+            else:
+                got = resident[c].cpu().numpy()
+            assert np.array_equal(got.view(np.uint32), want.view(np.uint32)), f"chunk {c} differs from the resident run"
+            assert torch.equal(out[c], res_out[c])
+    finally:
+        torch.cuda.synchronize()
+        ex.elixir_offload_register_slots(ctx, [], 0)
+        for b in blocks.values():
+            ex.elixir_host_free(b)
+        ex.elixir_ctx_destroy(ctx)
