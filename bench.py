@@ -29,7 +29,9 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="gpt2_1p5b", help="gpt2_1p5b (default) or tiny")
+    ap.add_argument("--workload", default="gpt2_1p5b",
+                    help="gpt2_1p5b (default, the benchmark line), tiny, sweep (chunk sizes 8Mi..256Mi), gpt2_6b_clip, gpt2_20b_offload")
+    ap.add_argument("--host-chunks", type=int, default=0, help="gpt2_20b_offload: allocate only about this many host-resident chunks")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-rows", action="store_true", help="skip the per-row side measurements")
     return ap.parse_args()
@@ -112,6 +114,7 @@ def side_rows(ex, gen, torch, cfg, C, nch, valid, state, grads, out, stream, ste
         slots = [torch.zeros(3, C, dtype=torch.float32, device=dev) for _ in range(n_slots)]
         ex.elixir_offload_register_slots(ctx, slots, nbytes)
         h2d, d2h = torch.cuda.Stream(), torch.cuda.Stream()
+        overlapped = ex.elixir_offload_bind_streams(ctx, h2d, d2h)
         hp = ex.make_hparams(cfg.lr, cfg.beta1, cfg.beta2, cfg.eps, cfg.weight_decay, 1)
         try:
             for b in blocks:                                   # touch the host blocks once (first-touch, zero state)
@@ -174,7 +177,7 @@ def side_rows(ex, gen, torch, cfg, C, nch, valid, state, grads, out, stream, ste
             rows["offload"] = {
                 "what": f"{n_host} host-resident chunks of {C} elements ([master|m|v], {nbytes} bytes each) through {n_slots} "
                         f"staging slots, prefetch / AdamW / evict on three streams, with the {nch} resident chunks updated meanwhile",
-                "h2d_alone_GB/s": moved / t_h2d / 1e9, "d2h_alone_GB/s": moved / t_d2h / 1e9,
+                "copy_engines_separate": overlapped, "h2d_alone_GB/s": moved / t_h2d / 1e9, "d2h_alone_GB/s": moved / t_d2h / 1e9,
                 "pipeline_ms": t_off * 1e3, "pipeline_GB/s_each_way": moved / t_off / 1e9,
                 "bidirectional_GB/s_each_way": (n_host // 2) * nbytes / t_both / 1e9,
                 "pipeline_frac_of_one_way_link": t_dma / t_off,
@@ -192,6 +195,234 @@ def side_rows(ex, gen, torch, cfg, C, nch, valid, state, grads, out, stream, ste
     return rows
 
 
+def _event_time(torch, stream, fn, reps, warm=1):
+    for _ in range(warm):
+        fn()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    e0.record(stream)
+    for _ in range(reps):
+        fn()
+    e1.record(stream)
+    torch.cuda.synchronize()
+    return (time.perf_counter() - t0) / reps, e0.elapsed_time(e1) * 1e-3 / reps
+
+
+def run_sweep(args, torch, ex, gen):
+    """Chunk-size sweep on the 1.5B set: padding waste of the three grouping policies and AdamW throughput
+    (next-fit layout, ragged final chunks included) per chunk size.  One JSON line per size."""
+    cfg = gen.CONFIGS["gpt2_1p5b"]
+    dev = torch.device("cuda:0")
+    stream = torch.cuda.Stream()
+    sh = stream.cuda_stream
+    for C in gen.SWEEP_CHUNK_ELEMS:
+        plans = {name: ex.elixir_layout_plan(cfg.numels(), C, pol, 1)[2] for name, pol in
+                 (("next_fit", ex.ELIXIR_LAYOUT_NEXT_FIT), ("first_fit", ex.ELIXIR_LAYOUT_FIRST_FIT), ("dense", ex.ELIXIR_LAYOUT_DENSE))}
+        valid = plans["next_fit"]
+        nch = len(valid)
+        state = torch.zeros(nch, 3, C, dtype=torch.float32, device=dev)
+        grads = torch.zeros(nch, C, dtype=torch.int16, device=dev)
+        out = torch.empty(nch, C, dtype=torch.int16, device=dev)
+        pkey = gen.stream_key(gen.BASE_SEED, gen.TAG_PARAM, cfg=3)
+        gkey = gen.stream_key(gen.BASE_SEED, gen.TAG_GRAD, 1, 0, 3)
+        for c in range(nch):
+            gen.fill_f32_device(state[c, 0].data_ptr(), valid[c], pkey, c * C, cfg.param_std)
+            gen.fill_bf16_device(grads[c].data_ptr(), valid[c], gkey, c * C, cfg.grad_std, cfg.grad_zero_pct)
+        step_no = [0]
+
+        def step():
+            step_no[0] += 1
+            hp = ex.make_hparams(cfg.lr, cfg.beta1, cfg.beta2, cfg.eps, cfg.weight_decay, step_no[0])
+            for c in range(nch):
+                ex.elixir_chunk_adam_step(state[c, 0], state[c, 1], state[c, 2], None, grads[c], out[c], C, hp, None, sh)
+
+        wall, ev = _event_time(torch, stream, step, args.steps, args.warmup)
+        print(json.dumps({
+            "metric": "chunked AdamW params/sec", "value": sum(valid) / wall, "unit": "params/s", "n_gpus": 1,
+            "steps": args.steps, "warmup": args.warmup, "ms_per_step": wall * 1e3, "dtype": "f32", "data": "synthetic",
+            "config": {"workload": f"gpt2-1.5B sweep/C={C >> 20}Mi", "chunk_elems": C, "n_chunks": nch, "layout": "next-fit"},
+            "padding_waste": {k: 1.0 - sum(v) / (len(v) * C) for k, v in plans.items()},
+            "n_chunks_by_policy": {k: len(v) for k, v in plans.items()},
+            "elements_per_s": nch * C / wall,
+            "roofline": {"bound": "hbm", "achieved": BYTES_PER_ELEM * C / (ev / nch) / 1e9, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                         "frac": BYTES_PER_ELEM * C / (ev / nch) / 1e9 / HBM_PEAK_GBPS, "traffic": None,
+                         "launch_ms": ev / nch * 1e3}}), flush=True)
+        del state, grads, out
+        torch.cuda.empty_cache()
+
+
+def run_clip(args, torch, ex, gen):
+    """Gradient accumulation + clipping on the 6B set: 4 bf16 micro-batches reduced into fp32 chunks, global
+    norm, clip coefficient on the device, AdamW with fp32 gradients (30 bytes per element)."""
+    cfg = gen.CONFIGS["gpt2_6b_clip"]
+    dev = torch.device("cuda:0")
+    C = cfg.chunk_elems
+    valid = ex.elixir_layout_plan(cfg.numels(), C, ex.ELIXIR_LAYOUT_NEXT_FIT, 1)[2]
+    nch, K = len(valid), cfg.micro_batches
+    stream = torch.cuda.Stream()
+    sh = stream.cuda_stream
+    state = torch.zeros(nch, 3, C, dtype=torch.float32, device=dev)
+    gch = torch.empty(nch, C, dtype=torch.float32, device=dev)
+    out = torch.empty(nch, C, dtype=torch.int16, device=dev)
+    mbs = torch.zeros(K, nch, C, dtype=torch.int16, device=dev)
+    pkey = gen.stream_key(gen.BASE_SEED, gen.TAG_PARAM, cfg=cfg.cfg_id)
+    for c in range(nch):
+        gen.fill_f32_device(state[c, 0].data_ptr(), valid[c], pkey, c * C, cfg.param_std)
+        for mb in range(K):
+            gen.fill_bf16_device(mbs[mb, c].data_ptr(), valid[c], gen.stream_key(gen.BASE_SEED, gen.TAG_GRAD, 1, mb, cfg.cfg_id),
+                                 c * C, cfg.grad_std)
+    ctx = ex.elixir_ctx_create(0, C, nch)
+    d_nc = torch.zeros(2, dtype=torch.float32, device=dev)
+    chunks = [gch[c] for c in range(nch)]
+    step_no = [0]
+    parts = {}
+
+    def reduce_all():
+        for mb in range(K):
+            for c in range(nch):
+                ex.elixir_grad_reduce_into_chunk(gch[c], 0, mbs[mb, c], C, 1.0 / K, mb > 0, sh)
+
+    def norm():
+        ex.elixir_chunk_grad_norm(ctx, chunks, valid, cfg.max_norm, d_nc[0:1], d_nc[1:2], sh)
+
+    def adam():
+        step_no[0] += 1
+        hp = ex.make_hparams(cfg.lr, cfg.beta1, cfg.beta2, cfg.eps, cfg.weight_decay, step_no[0])
+        for c in range(nch):
+            ex.elixir_chunk_adam_step(state[c, 0], state[c, 1], state[c, 2], gch[c], None, out[c], C, hp, d_nc[1:2], sh)
+
+    def step():
+        reduce_all()
+        norm()
+        adam()
+
+    try:
+        wall, ev = _event_time(torch, stream, step, args.steps, args.warmup)
+        for name, fn in (("reduce", reduce_all), ("norm", norm), ("adam", adam)):
+            parts[name] = _event_time(torch, stream, fn, 2, 1)[1]
+        n_el = nch * C
+        print(json.dumps({
+            "metric": "chunked AdamW params/sec (4 micro-batches reduced, global norm, clip, step)", "value": sum(valid) / wall,
+            "unit": "params/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": wall * 1e3,
+            "dtype": "f32", "data": "synthetic",
+            "config": {"workload": cfg.name, "params": sum(valid), "chunk_elems": C, "n_chunks": nch, "micro_batches": K,
+                       "max_norm": cfg.max_norm},
+            "norm": float(d_nc[0].item()), "clip_coef": float(d_nc[1].item()),
+            "phase_ms": {k: v * 1e3 for k, v in parts.items()},
+            "phase_GB/s": {"reduce": (6 + 10 * (K - 1)) * n_el / parts["reduce"] / 1e9, "norm": 4 * sum(valid) / parts["norm"] / 1e9,
+                           "adam_fp32_grad": 30 * n_el / parts["adam"] / 1e9},
+            "roofline": {"bound": "hbm", "achieved": (6 + 10 * (K - 1) + 30) * n_el / 1e9 / ev + 4 * sum(valid) / 1e9 / ev,
+                         "peak": HBM_PEAK_GBPS, "unit": "GB/s", "traffic": None,
+                         "frac": ((6 + 10 * (K - 1) + 30) * n_el + 4 * sum(valid)) / 1e9 / ev / HBM_PEAK_GBPS,
+                         "note": "whole step: 6 + 3*10 (reduce) + 4 (norm) + 30 (AdamW, fp32 gradient) bytes per element"}}), flush=True)
+    finally:
+        ex.elixir_ctx_destroy(ctx)
+
+
+def run_offload(args, torch, ex, gen):
+    """Offload mix on the 20B set: dense layout, 128Mi-element chunks; 60% of the chunks keep [master|m|v] in pinned
+    host memory and are prefetched, updated on the GPU and evicted on side streams; 40% are updated in HBM meanwhile.
+    --host-chunks limits how many host-resident chunks are really allocated (the split stays 60/40)."""
+    cfg = gen.CONFIGS["gpt2_20b_offload"]
+    dev = torch.device("cuda:0")
+    C = cfg.chunk_elems
+    valid_all = ex.elixir_layout_plan(cfg.numels(), C, ex.ELIXIR_LAYOUT_DENSE, 1)[2]
+    n_all = len(valid_all)
+    is_host_all = [(3 * c) % 5 < 3 for c in range(n_all)]                      # 60% of the chunks, interleaved
+    if args.host_chunks > 0:                                                   # scaled run: first chunks only
+        keep, h = 0, 0
+        for c in range(n_all):
+            h += is_host_all[c]
+            keep = c + 1
+            if h >= args.host_chunks and keep % 5 == 0:
+                break
+        valid, is_host = valid_all[:keep], is_host_all[:keep]
+    else:
+        valid, is_host = valid_all, is_host_all
+    nch = len(valid)
+    host_ids = [c for c in range(nch) if is_host[c]]
+    nbytes = 3 * C * 4
+    n_slots = 3
+    compute, h2d, d2h = torch.cuda.Stream(), torch.cuda.Stream(), torch.cuda.Stream()
+    sh = compute.cuda_stream
+    pkey = gen.stream_key(gen.BASE_SEED, gen.TAG_PARAM, cfg=cfg.cfg_id)
+    gkey = gen.stream_key(gen.BASE_SEED, gen.TAG_GRAD, 1, 0, cfg.cfg_id)
+    grads = torch.zeros(nch, C, dtype=torch.int16, device=dev)
+    out = torch.empty(nch, C, dtype=torch.int16, device=dev)
+    resident = {c: torch.zeros(3, C, dtype=torch.float32, device=dev) for c in range(nch) if not is_host[c]}
+    slots = [torch.zeros(3, C, dtype=torch.float32, device=dev) for _ in range(n_slots)]
+    ctx = ex.elixir_ctx_create(0, C, 8)
+    t0 = time.perf_counter()
+    blocks = {c: ex.elixir_host_alloc(nbytes) for c in host_ids}
+    t_alloc = time.perf_counter() - t0
+    try:
+        ex.elixir_offload_register_slots(ctx, slots, nbytes)
+        overlapped = ex.elixir_offload_bind_streams(ctx, h2d, d2h)
+        for c in range(nch):
+            gen.fill_bf16_device(grads[c].data_ptr(), valid[c], gkey, c * C, cfg.grad_std)
+            if is_host[c]:                                     # initial state: generated in a slot, evicted to the host block
+                s = ex.elixir_chunk_prefetch(ctx, blocks[c], 4096, h2d)
+                ex.elixir_chunk_wait_ready(ctx, s, compute)
+                with torch.cuda.stream(compute):
+                    slots[s].zero_()
+                gen.fill_f32_device(slots[s][0].data_ptr(), valid[c], pkey, c * C, cfg.param_std, 0, sh)
+                ex.elixir_chunk_evict(ctx, s, blocks[c], nbytes, compute, d2h)
+            else:
+                gen.fill_f32_device(resident[c][0].data_ptr(), valid[c], pkey, c * C, cfg.param_std)
+        torch.cuda.synchronize()
+        step_no = [0]
+
+        def step():
+            step_no[0] += 1
+            hp = ex.make_hparams(cfg.lr, cfg.beta1, cfg.beta2, cfg.eps, cfg.weight_decay, step_no[0])
+            pending, inflight = list(host_ids), []
+            for c in range(nch):
+                while pending and len(inflight) < n_slots:
+                    try:
+                        inflight.append((pending[0], ex.elixir_chunk_prefetch(ctx, blocks[pending[0]], nbytes, h2d)))
+                    except ex.ElixirError as e:
+                        if e.code != ex.ELIXIR_ENOSLOT:
+                            raise
+                        break
+                    pending.pop(0)
+                if is_host[c]:
+                    cc, s = inflight.pop(0)
+                    ex.elixir_chunk_wait_ready(ctx, s, compute)
+                    ex.elixir_chunk_adam_step(slots[s][0], slots[s][1], slots[s][2], None, grads[c], out[c], C, hp, None, sh)
+                    ex.elixir_chunk_evict(ctx, s, blocks[c], nbytes, compute, d2h)
+                else:
+                    r = resident[c]
+                    ex.elixir_chunk_adam_step(r[0], r[1], r[2], None, grads[c], out[c], C, hp, None, sh)
+
+        for _ in range(args.warmup):
+            step()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            step()
+        torch.cuda.synchronize()
+        wall = (time.perf_counter() - t0) / args.steps
+        moved = len(host_ids) * nbytes
+        print(json.dumps({
+            "metric": "chunked AdamW params/sec with 60% of the chunks streamed from pinned host memory", "value": sum(valid) / wall,
+            "unit": "params/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": wall * 1e3, "dtype": "f32",
+            "data": "synthetic",
+            "config": {"workload": cfg.name, "layout": "dense", "chunk_elems": C, "n_chunks": nch, "n_chunks_full_set": n_all,
+                       "host_chunks": len(host_ids), "resident_chunks": nch - len(host_ids), "slots": n_slots,
+                       "params": sum(valid), "pinned_GB": moved / 1e9, "pinned_alloc_s": t_alloc,
+                       "copy_engines_separate": overlapped},
+            "offload_GB/s_each_way": moved / wall / 1e9,
+            "roofline": {"bound": "host link", "achieved": moved / wall / 1e9, "unit": "GB/s each way, both directions concurrent",
+                         "peak": None, "frac": None, "traffic": None}}), flush=True)
+    finally:
+        torch.cuda.synchronize()
+        ex.elixir_offload_register_slots(ctx, [], 0)
+        for b in blocks.values():
+            ex.elixir_host_free(b)
+        ex.elixir_ctx_destroy(ctx)
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -207,6 +438,9 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs an MI355X"
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
+    if args.workload in ("sweep", "gpt2_6b_clip", "gpt2_20b_offload"):
+        {"sweep": run_sweep, "gpt2_6b_clip": run_clip, "gpt2_20b_offload": run_offload}[args.workload](args, torch, ex, gen)
+        return
     cfg = gen.CONFIGS[args.workload]
     C = cfg.chunk_elems
     numels = cfg.numels()

@@ -25,12 +25,13 @@
  *     default stream).  The caller's current device must be the one that owns
  *     the stream and buffers.
  *   - The caller owns every buffer it passes in.  The library owns only what
- *     elixir_ctx_create and elixir_host_alloc allocate.  No entry point other
- *     than those two allocates memory.
- *   - Pointers must be naturally aligned for their element type.  16-byte
- *     alignment (which whole chunks from any allocator have) selects the
- *     128-bit vector kernels; other alignments take a slower scalar kernel with
- *     identical results.
+ *     elixir_ctx_create and elixir_host_alloc allocate.  No other entry point
+ *     allocates device or pinned memory that outlives the call.
+ *   - Pointers must be naturally aligned for their element type.  Whole
+ *     chunks from any allocator are aligned far beyond what the vector kernels
+ *     need (8 bytes for the AdamW state, 16 for reduce and pack); slices at
+ *     other alignments take a one-element-per-thread kernel with identical
+ *     results.
  */
 #ifndef ELIXIR_CHUNK_H
 #define ELIXIR_CHUNK_H
@@ -101,8 +102,8 @@ int elixir_layout_plan(const int64_t* numel, int T, int64_t chunk_elems, int pol
                        int64_t valid_cap);
 
 /*
- * Pack / unpack (paper Fig. 3, left: "the data of each parameter is compacted
- * into a parameter chunk").  Bit copies, elem_size 2 or 4 bytes.
+ * Pack / unpack (paper Fig. 3, left panel: every parameter's data sits in a
+ * slice of its parameter chunk).  Bit copies, elem_size 2 or 4 bytes.
  *   pack  : d_chunk[offset[i] + k] = tensors[i][k] for k < numel[i]; every
  *           element of the chunk not covered by a slice is set to zero bits.
  *   unpack: tensors[i][k] = d_chunk[offset[i] + k].
@@ -185,12 +186,19 @@ int elixir_chunk_adam_step(float* d_master, float* d_exp_avg, float* d_exp_avg_s
  *       compute_stream, enqueues the device-to-host copy of `bytes` into
  *       h_block (h_block NULL: no copy, the slot is only released), and marks
  *       the slot free for the next prefetch.
- * No call blocks the host.  h_block should be pinned (elixir_host_alloc) for
+ *   elixir_offload_bind_streams : call once per pair of copy streams, before their first copies and
+ *       after registering slots.  The runtime assigns a DMA engine to a stream at its first copy; this
+ *       call issues the first copies so that uploads and downloads land on different engines and can
+ *       run at the same time, then measures whether they do (*overlapped_out = 1/0, may be NULL).
+ *       It overwrites slot 0, allocates and frees a pinned scratch buffer, and waits for both streams.
+ * No other call blocks the host.  h_block should be pinned (elixir_host_alloc) for
  * the copies to be asynchronous and at link speed.
  */
 int elixir_host_alloc(void** h_out, size_t bytes);
 int elixir_host_free(void* h_ptr);
 int elixir_offload_register_slots(elixir_ctx* ctx, void* const* d_slots, int n_slots, size_t slot_bytes);
+int elixir_offload_bind_streams(elixir_ctx* ctx, elixir_stream_t h2d_stream, elixir_stream_t d2h_stream,
+                                int* overlapped_out);
 int elixir_chunk_prefetch(elixir_ctx* ctx, const void* h_block, size_t bytes, int* slot_out,
                           elixir_stream_t h2d_stream);
 int elixir_chunk_wait_ready(elixir_ctx* ctx, int slot, elixir_stream_t compute_stream);

@@ -20,7 +20,8 @@ ELIXIR_LAYOUT_NEXT_FIT, ELIXIR_LAYOUT_FIRST_FIT, ELIXIR_LAYOUT_DENSE = 0, 1, 2
 EXPORTS = (
     "elixir_last_error", "elixir_ctx_create", "elixir_ctx_destroy", "elixir_layout_plan", "elixir_chunk_pack",
     "elixir_chunk_unpack", "elixir_grad_reduce_into_chunk", "elixir_chunk_grad_norm", "elixir_chunk_adam_step",
-    "elixir_host_alloc", "elixir_host_free", "elixir_offload_register_slots", "elixir_chunk_prefetch",
+    "elixir_host_alloc", "elixir_host_free", "elixir_offload_register_slots", "elixir_offload_bind_streams",
+    "elixir_chunk_prefetch",
     "elixir_chunk_wait_ready", "elixir_chunk_evict",
 )
 
@@ -63,6 +64,7 @@ def lib() -> ctypes.CDLL:
             "elixir_host_alloc": [ctypes.POINTER(vp), sz],
             "elixir_host_free": [vp],
             "elixir_offload_register_slots": [vp, ctypes.POINTER(vp), ci, sz],
+            "elixir_offload_bind_streams": [vp, vp, vp, ctypes.POINTER(ci)],
             "elixir_chunk_prefetch": [vp, vp, sz, ctypes.POINTER(ci), vp],
             "elixir_chunk_wait_ready": [vp, ci, vp],
             "elixir_chunk_evict": [vp, ci, vp, sz, vp, vp],
@@ -201,6 +203,13 @@ def elixir_host_free(ptr: int) -> None:
 
 def elixir_offload_register_slots(ctx: Ctx, d_slots, slot_bytes: int) -> None:
     _check(lib().elixir_offload_register_slots(ctx.handle, _ptr_array(d_slots), len(d_slots), slot_bytes))
+
+
+def elixir_offload_bind_streams(ctx: Ctx, h2d_stream, d2h_stream) -> bool:
+    """Returns True if uploads and downloads were measured to run concurrently afterwards."""
+    ok = ctypes.c_int(0)
+    _check(lib().elixir_offload_bind_streams(ctx.handle, _stream(h2d_stream), _stream(d2h_stream), ctypes.byref(ok)))
+    return bool(ok.value)
 
 
 def elixir_chunk_prefetch(ctx: Ctx, h_block: int, nbytes: int, h2d_stream) -> int:

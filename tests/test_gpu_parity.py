@@ -504,6 +504,8 @@ def test_offload_is_bitwise_identical_to_resident(ctx, n_slots):
         ex.elixir_offload_register_slots(ctx, slots, nbytes)
         out = torch.zeros(n_chunks, C, dtype=torch.int16, device=DEV)
         compute, h2d, d2h = torch.cuda.Stream(), torch.cuda.Stream(), torch.cuda.Stream()
+        ex.elixir_offload_bind_streams(ctx, h2d, d2h)              # overwrites slot 0: poison it again
+        slots[0].fill_(float("nan"))
         sync()
         pending = list(host_ids)
         inflight = []                                            # (chunk, slot) prefetched, not yet updated
@@ -575,3 +577,45 @@ def test_offload_slot_exhaustion_and_release(ctx):
         sync()
         ex.elixir_offload_register_slots(ctx, [], 0)
         ex.elixir_host_free(blk)
+
+
+def test_offload_bind_streams_makes_copies_overlap(ctx):
+    nbytes = 256 << 20
+    slots = [torch.zeros(nbytes // 4, dtype=torch.float32, device=DEV) for _ in range(2)]
+    h2d, d2h = torch.cuda.Stream(), torch.cuda.Stream()
+    with pytest.raises(ex.ElixirError) as e:
+        ex.elixir_offload_bind_streams(ctx, h2d, d2h)                 # no slots yet
+    assert e.value.code == ex.ELIXIR_ESTATE
+    ex.elixir_offload_register_slots(ctx, slots, nbytes)
+    try:
+        with pytest.raises(ex.ElixirError) as e:
+            ex.elixir_offload_bind_streams(ctx, h2d, h2d)
+        assert e.value.code == ex.ELIXIR_EINVAL
+        assert ex.elixir_offload_bind_streams(ctx, h2d, d2h) is True, "uploads and downloads do not run concurrently"
+        # and they really do: 4 uploads + 4 downloads together take clearly less than one after the other
+        blk = [ex.elixir_host_alloc(nbytes) for _ in range(2)]
+        try:
+            import time
+
+            def run(both):
+                sync()
+                t0 = time.perf_counter()
+                for _ in range(4):
+                    s = ex.elixir_chunk_prefetch(ctx, blk[0], nbytes, h2d)
+                    ex.elixir_chunk_evict(ctx, s, None, 0, h2d, h2d)
+                    if both:
+                        s = ex.elixir_chunk_prefetch(ctx, blk[1], 4096, d2h)
+                        ex.elixir_chunk_evict(ctx, s, blk[1], nbytes, d2h, d2h)
+                sync()
+                return time.perf_counter() - t0
+
+            run(True)
+            t_up, t_both = run(False), run(True)
+            assert t_both < 1.5 * t_up, (t_up, t_both)
+        finally:
+            sync()
+            for b in blk:
+                ex.elixir_host_free(b)
+    finally:
+        sync()
+        ex.elixir_offload_register_slots(ctx, [], 0)
