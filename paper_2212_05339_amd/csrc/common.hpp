@@ -17,7 +17,10 @@ inline bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_
 #define ELIXIR_HIP_TRY(expr)                                                                         \
     do {                                                                                             \
         hipError_t e_ = (expr);                                                                      \
-        if (e_ != hipSuccess) return ::elixir::fail(ELIXIR_EHIP, "%s: %s", #expr, hipGetErrorString(e_)); \
+        if (e_ != hipSuccess) {                                                                      \
+            (void)hipGetLastError(); /* reported here; do not leave it for the caller's next HIP call */ \
+            return ::elixir::fail(ELIXIR_EHIP, "%s: %s", #expr, hipGetErrorString(e_));             \
+        }                                                                                            \
     } while (0)
 
 // Launch check: hipGetLastError after a kernel launch.
