@@ -24,6 +24,28 @@ HBM_PEAK_GBPS = 8000.0      # MI355X published HBM3E bandwidth
 BYTES_PER_ELEM = 28         # 2 (bf16 grad) + 12 (read p, m, v) + 12 (write p, m, v) + 2 (bf16 param)
 
 
+STAGGER_BYTES = (4 << 20) + 8192   # gap between the arrays of a chunk, see chunk_buffers()
+
+
+def chunk_buffers(torch, dev, nch, C):
+    """Device buffers of nch chunks: fp32 master, m, v and two bf16 arrays (gradient, parameter copy) per chunk.
+    Where the buffers sit is the caller's choice; arrays that start at the same offset modulo a few MiB make the
+    eight streams of the AdamW kernel cross DRAM pages in phase and cost ~2% of bandwidth (measured), so every
+    array is followed by a 4 MiB + 8 KiB gap.  Returns (state[c] = (master, m, v), grad16[c], out16[c])."""
+    gap32, gap16 = STAGGER_BYTES // 4, STAGGER_BYTES // 2
+    flat32 = torch.zeros(nch * 3 * (C + gap32), dtype=torch.float32, device=dev)
+    flat16 = torch.zeros(nch * 2 * (C + gap16) + gap16, dtype=torch.int16, device=dev)
+    state, g16, o16 = [], [], []
+    for c in range(nch):
+        b = c * 3 * (C + gap32)
+        state.append(tuple(flat32[b + j * (C + gap32): b + j * (C + gap32) + C] for j in range(3)))
+        g = c * (C + gap16)
+        g16.append(flat16[g: g + C])
+        o = nch * (C + gap16) + gap16 // 2 + c * (C + gap16)
+        o16.append(flat16[o: o + C])
+    return state, g16, o16, (flat32, flat16)
+
+
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -77,7 +99,7 @@ def side_rows(ex, gen, torch, cfg, C, nch, valid, state, grads, out, stream, ste
     """Throughput of the other rows of the path, measured after (outside) the timed region on the same
     buffers: pack (a plain copy), gradient reduction, global norm, and the offload pipeline."""
     sh = stream.cuda_stream
-    dev = state.device
+    dev = out[0].device
 
     def timed(fn, reps):
         fn()
@@ -95,7 +117,7 @@ def side_rows(ex, gen, torch, cfg, C, nch, valid, state, grads, out, stream, ste
     src, dst = scratch[0], scratch[1]
     t = timed(lambda: ex.elixir_chunk_pack(dst, C, 4, [src], [C], [0], sh), 10)
     rows["pack"] = {"what": f"one fp32 tensor of {C} elements into a chunk (plain copy)", "bytes": 8 * C, "GB/s": 8 * C / t / 1e9}
-    g16 = grads[0, 0]
+    g16 = grads[0][0]
     t = timed(lambda: ex.elixir_grad_reduce_into_chunk(dst, 0, g16, C, 0.25, False, sh), 10)
     rows["grad_reduce_first"] = {"what": "bf16 -> fp32 chunk, overwrite", "bytes": 6 * C, "GB/s": 6 * C / t / 1e9}
     t = timed(lambda: ex.elixir_grad_reduce_into_chunk(dst, 0, g16, C, 0.25, True, sh), 10)
@@ -103,7 +125,7 @@ def side_rows(ex, gen, torch, cfg, C, nch, valid, state, grads, out, stream, ste
     ctx = ex.elixir_ctx_create(0, C, nch)
     try:
         d_nc = torch.zeros(2, dtype=torch.float32, device=dev)
-        chunks = [state[c, 1] for c in range(nch)]          # the momentum buffers stand in for fp32 gradient chunks
+        chunks = [state[c][1] for c in range(nch)]          # the momentum buffers stand in for fp32 gradient chunks
         t = timed(lambda: ex.elixir_chunk_grad_norm(ctx, chunks, valid, 1.0, d_nc[0:1], d_nc[1:2], sh), 5)
         rows["grad_norm"] = {"what": f"{nch} fp32 chunks, {sum(valid)} valid elements, two-stage fp64 tree",
                              "bytes": 4 * sum(valid), "GB/s": 4 * sum(valid) / t / 1e9, "ms": t * 1e3}
@@ -151,7 +173,7 @@ def side_rows(ex, gen, torch, cfg, C, nch, valid, state, grads, out, stream, ste
 
             def resident_step():
                 for c in range(nch):
-                    ex.elixir_chunk_adam_step(state[c, 0], state[c, 1], state[c, 2], None, grads[0, c], out[c], C, hp, None, sh)
+                    ex.elixir_chunk_adam_step(state[c][0], state[c][1], state[c][2], None, grads[0][c], out[c], C, hp, None, sh)
 
             def offload_step(with_resident):
                 pending, inflight = list(range(n_host)), []
@@ -160,11 +182,11 @@ def side_rows(ex, gen, torch, cfg, C, nch, valid, state, grads, out, stream, ste
                         inflight.append((pending[0], ex.elixir_chunk_prefetch(ctx, blocks[pending.pop(0)], nbytes, h2d)))
                     j, s = inflight.pop(0)
                     ex.elixir_chunk_wait_ready(ctx, s, sh)
-                    ex.elixir_chunk_adam_step(slots[s][0], slots[s][1], slots[s][2], None, grads[0, j % nch], out[j % nch], C, hp, None, sh)
+                    ex.elixir_chunk_adam_step(slots[s][0], slots[s][1], slots[s][2], None, grads[0][j % nch], out[j % nch], C, hp, None, sh)
                     ex.elixir_chunk_evict(ctx, s, blocks[j], nbytes, sh, d2h)
                     if with_resident:                           # resident chunks are updated between offloaded ones
                         for c in range(k * nch // n_host, (k + 1) * nch // n_host):
-                            ex.elixir_chunk_adam_step(state[c, 0], state[c, 1], state[c, 2], None, grads[0, c], out[c], C, hp, None, sh)
+                            ex.elixir_chunk_adam_step(state[c][0], state[c][1], state[c][2], None, grads[0][c], out[c], C, hp, None, sh)
 
             t_h2d = min(wall(only_h2d) for _ in range(2))
             t_d2h = min(wall(only_d2h) for _ in range(2))
@@ -221,13 +243,11 @@ def run_sweep(args, torch, ex, gen):
                  (("next_fit", ex.ELIXIR_LAYOUT_NEXT_FIT), ("first_fit", ex.ELIXIR_LAYOUT_FIRST_FIT), ("dense", ex.ELIXIR_LAYOUT_DENSE))}
         valid = plans["next_fit"]
         nch = len(valid)
-        state = torch.zeros(nch, 3, C, dtype=torch.float32, device=dev)
-        grads = torch.zeros(nch, C, dtype=torch.int16, device=dev)
-        out = torch.empty(nch, C, dtype=torch.int16, device=dev)
+        state, grads, out, keep = chunk_buffers(torch, dev, nch, C)
         pkey = gen.stream_key(gen.BASE_SEED, gen.TAG_PARAM, cfg=3)
         gkey = gen.stream_key(gen.BASE_SEED, gen.TAG_GRAD, 1, 0, 3)
         for c in range(nch):
-            gen.fill_f32_device(state[c, 0].data_ptr(), valid[c], pkey, c * C, cfg.param_std)
+            gen.fill_f32_device(state[c][0].data_ptr(), valid[c], pkey, c * C, cfg.param_std)
             gen.fill_bf16_device(grads[c].data_ptr(), valid[c], gkey, c * C, cfg.grad_std, cfg.grad_zero_pct)
         step_no = [0]
 
@@ -235,7 +255,7 @@ def run_sweep(args, torch, ex, gen):
             step_no[0] += 1
             hp = ex.make_hparams(cfg.lr, cfg.beta1, cfg.beta2, cfg.eps, cfg.weight_decay, step_no[0])
             for c in range(nch):
-                ex.elixir_chunk_adam_step(state[c, 0], state[c, 1], state[c, 2], None, grads[c], out[c], C, hp, None, sh)
+                ex.elixir_chunk_adam_step(state[c][0], state[c][1], state[c][2], None, grads[c], out[c], C, hp, None, sh)
 
         wall, ev = _event_time(torch, stream, step, args.steps, args.warmup)
         print(json.dumps({
@@ -248,7 +268,7 @@ def run_sweep(args, torch, ex, gen):
             "roofline": {"bound": "hbm", "achieved": BYTES_PER_ELEM * C / (ev / nch) / 1e9, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                          "frac": BYTES_PER_ELEM * C / (ev / nch) / 1e9 / HBM_PEAK_GBPS, "traffic": None,
                          "launch_ms": ev / nch * 1e3}}), flush=True)
-        del state, grads, out
+        del state, grads, out, keep
         torch.cuda.empty_cache()
 
 
@@ -262,13 +282,14 @@ def run_clip(args, torch, ex, gen):
     nch, K = len(valid), cfg.micro_batches
     stream = torch.cuda.Stream()
     sh = stream.cuda_stream
-    state = torch.zeros(nch, 3, C, dtype=torch.float32, device=dev)
-    gch = torch.empty(nch, C, dtype=torch.float32, device=dev)
-    out = torch.empty(nch, C, dtype=torch.int16, device=dev)
+    state, _unused16, out, _keep = chunk_buffers(torch, dev, nch, C)
+    gstride32 = C + STAGGER_BYTES // 4 + 2048
+    gflat = torch.empty(nch * gstride32, dtype=torch.float32, device=dev)
+    gch = [gflat[c * gstride32: c * gstride32 + C] for c in range(nch)]
     mbs = torch.zeros(K, nch, C, dtype=torch.int16, device=dev)
     pkey = gen.stream_key(gen.BASE_SEED, gen.TAG_PARAM, cfg=cfg.cfg_id)
     for c in range(nch):
-        gen.fill_f32_device(state[c, 0].data_ptr(), valid[c], pkey, c * C, cfg.param_std)
+        gen.fill_f32_device(state[c][0].data_ptr(), valid[c], pkey, c * C, cfg.param_std)
         for mb in range(K):
             gen.fill_bf16_device(mbs[mb, c].data_ptr(), valid[c], gen.stream_key(gen.BASE_SEED, gen.TAG_GRAD, 1, mb, cfg.cfg_id),
                                  c * C, cfg.grad_std)
@@ -290,7 +311,7 @@ def run_clip(args, torch, ex, gen):
         step_no[0] += 1
         hp = ex.make_hparams(cfg.lr, cfg.beta1, cfg.beta2, cfg.eps, cfg.weight_decay, step_no[0])
         for c in range(nch):
-            ex.elixir_chunk_adam_step(state[c, 0], state[c, 1], state[c, 2], gch[c], None, out[c], C, hp, d_nc[1:2], sh)
+            ex.elixir_chunk_adam_step(state[c][0], state[c][1], state[c][2], gch[c], None, out[c], C, hp, d_nc[1:2], sh)
 
     def step():
         reduce_all()
@@ -465,28 +486,28 @@ def main():
     stream = torch.cuda.Stream()
     sh = stream.cuda_stream
     # ---- state, resident in HBM ----
-    state = torch.empty(nch, 3, C, dtype=torch.float32, device=dev)     # [chunk][master | m | v]
-    state.zero_()
-    out = torch.empty(nch, C, dtype=torch.int16, device=dev)
+    state, g_first, out, _keep = chunk_buffers(torch, dev, nch, C)
     pkey = gen.stream_key(gen.BASE_SEED, gen.TAG_PARAM, cfg=cfg.cfg_id)
     for c in range(nch):
-        gen.fill_f32_device(state[c, 0].data_ptr(), valid[c], pkey, c * C, cfg.param_std)
+        gen.fill_f32_device(state[c][0].data_ptr(), valid[c], pkey, c * C, cfg.param_std)
     # ---- gradients: one set per step where memory allows, else a ring that is cycled ----
     free_b, _ = torch.cuda.mem_get_info()
-    set_bytes = nch * C * 2
+    gstride = C + STAGGER_BYTES // 2
+    set_bytes = nch * gstride * 2
     n_sets = max(1, min(K + W, int(0.8 * free_b // set_bytes)))
-    grads = torch.zeros(n_sets, nch, C, dtype=torch.int16, device=dev)   # padding stays zero
+    gflat = torch.zeros(n_sets * nch * gstride, dtype=torch.int16, device=dev)   # padding stays zero
+    grads = [[gflat[(s * nch + c) * gstride: (s * nch + c) * gstride + C] for c in range(nch)] for s in range(n_sets)]
     for s in range(n_sets):
         gkey = gen.stream_key(gen.BASE_SEED, gen.TAG_GRAD, s + 1, 0, cfg.cfg_id)
         for c in range(nch):
-            gen.fill_bf16_device(grads[s, c].data_ptr(), valid[c], gkey, c * C, cfg.grad_std, cfg.grad_zero_pct)
+            gen.fill_bf16_device(grads[s][c].data_ptr(), valid[c], gkey, c * C, cfg.grad_std, cfg.grad_zero_pct)
     torch.cuda.synchronize()
 
     def one_step(step_no):
         hp = ex.make_hparams(cfg.lr, cfg.beta1, cfg.beta2, cfg.eps, cfg.weight_decay, step_no)
         g = grads[(step_no - 1) % n_sets]
         for c in range(nch):
-            ex.elixir_chunk_adam_step(state[c, 0], state[c, 1], state[c, 2], None, g[c], out[c], C, hp, None, sh)
+            ex.elixir_chunk_adam_step(state[c][0], state[c][1], state[c][2], None, g[c], out[c], C, hp, None, sh)
 
     for w in range(W):
         one_step(w + 1)
