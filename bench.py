@@ -54,6 +54,9 @@ def parse():
     ap.add_argument("--workload", default="gpt2_1p5b",
                     help="gpt2_1p5b (default, the benchmark line), tiny, sweep (chunk sizes 8Mi..256Mi), gpt2_6b_clip, gpt2_20b_offload")
     ap.add_argument("--host-chunks", type=int, default=0, help="gpt2_20b_offload: allocate only about this many host-resident chunks")
+    ap.add_argument("--multi", action="store_true",
+                    help="update all chunks of a step with elixir_chunk_adam_step_multi (always done for chunks of <= 16Mi elements, "
+                         "which are launch-bound one call at a time)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-rows", action="store_true", help="skip the per-row side measurements")
     return ap.parse_args()
@@ -250,10 +253,15 @@ def run_sweep(args, torch, ex, gen):
             gen.fill_f32_device(state[c][0].data_ptr(), valid[c], pkey, c * C, cfg.param_std)
             gen.fill_bf16_device(grads[c].data_ptr(), valid[c], gkey, c * C, cfg.grad_std, cfg.grad_zero_pct)
         step_no = [0]
+        use_multi = args.multi or C <= 16 * gen.Mi
 
         def step():
             step_no[0] += 1
             hp = ex.make_hparams(cfg.lr, cfg.beta1, cfg.beta2, cfg.eps, cfg.weight_decay, step_no[0])
+            if use_multi:
+                ex.elixir_chunk_adam_step_multi([st[0] for st in state], [st[1] for st in state], [st[2] for st in state], None,
+                                                grads, out, [C] * nch, hp, None, sh)
+                return
             for c in range(nch):
                 ex.elixir_chunk_adam_step(state[c][0], state[c][1], state[c][2], None, grads[c], out[c], C, hp, None, sh)
 
@@ -261,13 +269,14 @@ def run_sweep(args, torch, ex, gen):
         print(json.dumps({
             "metric": "chunked AdamW params/sec", "value": sum(valid) / wall, "unit": "params/s", "n_gpus": 1,
             "steps": args.steps, "warmup": args.warmup, "ms_per_step": wall * 1e3, "dtype": "f32", "data": "synthetic",
-            "config": {"workload": f"gpt2-1.5B sweep/C={C >> 20}Mi", "chunk_elems": C, "n_chunks": nch, "layout": "next-fit"},
+            "config": {"workload": f"gpt2-1.5B sweep/C={C >> 20}Mi", "chunk_elems": C, "n_chunks": nch, "layout": "next-fit",
+                       "launch": "multi" if use_multi else "per chunk"},
             "padding_waste": {k: 1.0 - sum(v) / (len(v) * C) for k, v in plans.items()},
             "n_chunks_by_policy": {k: len(v) for k, v in plans.items()},
             "elements_per_s": nch * C / wall,
             "roofline": {"bound": "hbm", "achieved": BYTES_PER_ELEM * C / (ev / nch) / 1e9, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                          "frac": BYTES_PER_ELEM * C / (ev / nch) / 1e9 / HBM_PEAK_GBPS, "traffic": None,
-                         "launch_ms": ev / nch * 1e3}}), flush=True)
+                         "ms_per_chunk": ev / nch * 1e3}}), flush=True)
         del state, grads, out, keep
         torch.cuda.empty_cache()
 
@@ -482,6 +491,8 @@ def main():
     cid, off, valid = ex.elixir_layout_plan(numels, C, ex.ELIXIR_LAYOUT_NEXT_FIT, 1)
     nch = len(valid)
     K, W = args.steps, args.warmup
+    if C <= 16 * gen.Mi:
+        args.multi = True
 
     stream = torch.cuda.Stream()
     sh = stream.cuda_stream
@@ -503,9 +514,14 @@ def main():
             gen.fill_bf16_device(grads[s][c].data_ptr(), valid[c], gkey, c * C, cfg.grad_std, cfg.grad_zero_pct)
     torch.cuda.synchronize()
 
+    p_list, m_list, v_list = [st[0] for st in state], [st[1] for st in state], [st[2] for st in state]
+
     def one_step(step_no):
         hp = ex.make_hparams(cfg.lr, cfg.beta1, cfg.beta2, cfg.eps, cfg.weight_decay, step_no)
         g = grads[(step_no - 1) % n_sets]
+        if args.multi:
+            ex.elixir_chunk_adam_step_multi(p_list, m_list, v_list, None, g, out, [C] * nch, hp, None, sh)
+            return
         for c in range(nch):
             ex.elixir_chunk_adam_step(state[c][0], state[c][1], state[c][2], None, g[c], out[c], C, hp, None, sh)
 
@@ -523,9 +539,10 @@ def main():
     ev_ms = e0.elapsed_time(e1)
 
     total_params = sum(valid)
-    launches = K * nch
+    launches = K * (-(-nch // 64) if args.multi else nch)
+    per_launch_elems = nch * C / (-(-nch // 64)) if args.multi else C
     launch_s = ev_ms * 1e-3 / launches                      # average duration of one launch of the AdamW kernel
-    achieved = BYTES_PER_ELEM * C / launch_s / 1e9          # GB/s, algorithmic bytes of one launch
+    achieved = BYTES_PER_ELEM * per_launch_elems / launch_s / 1e9          # GB/s, algorithmic bytes of one launch
     traffic = None
     tpath = os.path.join(ROOT, "profiles", "adam_step_traffic.json")
     if os.path.exists(tpath) and args.workload == "gpt2_1p5b":
@@ -543,7 +560,8 @@ def main():
         "elements_per_s": nch * C * K / wall,
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBPS, "traffic": traffic,
-                     "kernel": "adam_vec_kernel<bf16 grad, bf16 out>", "bytes_per_launch": BYTES_PER_ELEM * C,
+                     "kernel": "adam_multi_kernel<bf16 grad, bf16 out>" if args.multi else "adam_vec_kernel<bf16 grad, bf16 out>",
+                     "bytes_per_launch": BYTES_PER_ELEM * per_launch_elems,
                      "launch_ms": launch_s * 1e3, "launches_timed": launches,
                      "timing": "HIP events on the launch stream around the timed region / launches"},
     }

@@ -165,6 +165,20 @@ int elixir_chunk_adam_step(float* d_master, float* d_exp_avg, float* d_exp_avg_s
                            const elixir_adam_hparams* hp, const float* d_grad_scale, elixir_stream_t stream);
 
 /*
+ * The same update for n_chunks chunk pairs in as few launches as possible (one
+ * per 64 chunks): chunks much shorter than ~16Mi elements are launch-bound when
+ * updated one call at a time.  All tables are HOST arrays of n_chunks entries;
+ * the step constants and d_grad_scale are shared.  Exactly one of the two
+ * gradient tables is non-NULL; d_param_bf16 may be NULL (no low-precision
+ * copies).  Results are bit-identical to n_chunks calls of
+ * elixir_chunk_adam_step.  Chunks must not overlap.
+ */
+int elixir_chunk_adam_step_multi(int n_chunks, float* const* d_master, float* const* d_exp_avg,
+                                 float* const* d_exp_avg_sq, const float* const* d_grad_fp32,
+                                 const uint16_t* const* d_grad_bf16, uint16_t* const* d_param_bf16, const int64_t* n,
+                                 const elixir_adam_hparams* hp, const float* d_grad_scale, elixir_stream_t stream);
+
+/*
  * Offload pipeline for chunks whose optimizer chunk lives in host memory (the
  * paper keeps a searched number of chunks in CPU memory, Sec. 3 "Search
  * Engine", and overlaps chunk movement with computation by running it on

@@ -20,6 +20,7 @@ ELIXIR_LAYOUT_NEXT_FIT, ELIXIR_LAYOUT_FIRST_FIT, ELIXIR_LAYOUT_DENSE = 0, 1, 2
 EXPORTS = (
     "elixir_last_error", "elixir_ctx_create", "elixir_ctx_destroy", "elixir_layout_plan", "elixir_chunk_pack",
     "elixir_chunk_unpack", "elixir_grad_reduce_into_chunk", "elixir_chunk_grad_norm", "elixir_chunk_adam_step",
+    "elixir_chunk_adam_step_multi",
     "elixir_host_alloc", "elixir_host_free", "elixir_offload_register_slots", "elixir_offload_bind_streams",
     "elixir_chunk_prefetch",
     "elixir_chunk_wait_ready", "elixir_chunk_evict",
@@ -61,6 +62,8 @@ def lib() -> ctypes.CDLL:
             "elixir_grad_reduce_into_chunk": [vp, i64, vp, i64, f32, ci, vp],
             "elixir_chunk_grad_norm": [vp, ctypes.POINTER(vp), pi64, ci, f32, vp, vp, vp],
             "elixir_chunk_adam_step": [vp, vp, vp, vp, vp, vp, i64, ctypes.POINTER(elixir_adam_hparams), vp, vp],
+            "elixir_chunk_adam_step_multi": [ci, ctypes.POINTER(vp), ctypes.POINTER(vp), ctypes.POINTER(vp), ctypes.POINTER(vp),
+                                             ctypes.POINTER(vp), ctypes.POINTER(vp), pi64, ctypes.POINTER(elixir_adam_hparams), vp, vp],
             "elixir_host_alloc": [ctypes.POINTER(vp), sz],
             "elixir_host_free": [vp],
             "elixir_offload_register_slots": [vp, ctypes.POINTER(vp), ci, sz],
@@ -187,6 +190,16 @@ def elixir_chunk_adam_step(master, exp_avg, exp_avg_sq, grad_fp32, grad_bf16, pa
     _check(lib().elixir_chunk_adam_step(_addr(master), _addr(exp_avg), _addr(exp_avg_sq), _addr(grad_fp32),
                                         _addr(grad_bf16), _addr(param_bf16), n, ctypes.byref(hp), _addr(d_grad_scale),
                                         _stream(stream)))
+
+
+def elixir_chunk_adam_step_multi(master, exp_avg, exp_avg_sq, grad_fp32, grad_bf16, param_bf16, n, hp: elixir_adam_hparams,
+                                 d_grad_scale=None, stream=None) -> None:
+    """Lists of per-chunk buffers (grad_fp32 / grad_bf16 / param_bf16 may be None as a whole)."""
+    k = len(master)
+    tab = lambda xs: None if xs is None else _ptr_array(xs)
+    _check(lib().elixir_chunk_adam_step_multi(k, _ptr_array(master), _ptr_array(exp_avg), _ptr_array(exp_avg_sq), tab(grad_fp32),
+                                              tab(grad_bf16), tab(param_bf16), _i64_array(n), ctypes.byref(hp),
+                                              _addr(d_grad_scale), _stream(stream)))
 
 
 # --------------------------------------------------------------------------- offload

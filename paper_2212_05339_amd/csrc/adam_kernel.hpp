@@ -98,6 +98,55 @@ __global__ __launch_bounds__(kAdamBlock) void adam_vec_kernel(float* __restrict_
         __builtin_nontemporal_store(bf16_rne_bits(p0) | (bf16_rne_bits(p1) << 16), reinterpret_cast<uint32_t*>(out) + i);
 }
 
+// Several chunks in one launch (same step constants for all).  The table travels as a kernel argument.
+// grid = (workgroups of the longest chunk, chunks): workgroups are dispatched x-first, so chunk after chunk
+// is swept front to back exactly as by adam_vec_kernel, without the drain and refill between launches --
+// what makes small chunks launch-bound otherwise.  Workgroups past the end of a shorter chunk exit at once.
+constexpr int kAdamMultiMax = 64;
+struct AdamMultiTable {
+    float* master[kAdamMultiMax];
+    float* exp_avg[kAdamMultiMax];
+    float* exp_avg_sq[kAdamMultiMax];
+    const void* grad[kAdamMultiMax];
+    uint16_t* out[kAdamMultiMax];
+    int64_t n2[kAdamMultiMax];             // complete pairs per chunk
+};
+
+template <bool GRAD_BF16, bool HAS_OUT>
+__global__ __launch_bounds__(kAdamBlock) void adam_multi_kernel(AdamMultiTable tab, AdamConsts c,
+                                                               const float* __restrict__ d_grad_scale) {
+    const int lo = blockIdx.y;
+    const int64_t i = (int64_t)blockIdx.x * kAdamBlock + threadIdx.x;
+    if (i >= tab.n2[lo]) return;
+    f32x2* P = reinterpret_cast<f32x2*>(tab.master[lo]) + i;
+    f32x2* M = reinterpret_cast<f32x2*>(tab.exp_avg[lo]) + i;
+    f32x2* V = reinterpret_cast<f32x2*>(tab.exp_avg_sq[lo]) + i;
+    float g0, g1;
+    if constexpr (GRAD_BF16) {
+        const uint32_t gb = __builtin_nontemporal_load(reinterpret_cast<const uint32_t*>(tab.grad[lo]) + i);
+        g0 = bf16_bits_to_float(gb & 0xFFFFu);
+        g1 = __uint_as_float(gb & 0xFFFF0000u);
+    } else {
+        const f32x2 gf = __builtin_nontemporal_load(reinterpret_cast<const f32x2*>(tab.grad[lo]) + i);
+        g0 = gf.x;
+        g1 = gf.y;
+    }
+    f32x2 p = __builtin_nontemporal_load(P), m = __builtin_nontemporal_load(M), v = __builtin_nontemporal_load(V);
+    if (d_grad_scale) {
+        const float gs = *d_grad_scale;
+        g0 *= gs;
+        g1 *= gs;
+    }
+    float p0 = p.x, m0 = m.x, v0 = v.x, p1 = p.y, m1 = m.y, v1 = v.y;
+    adam_elem(p0, m0, v0, g0, c);
+    adam_elem(p1, m1, v1, g1, c);
+    __builtin_nontemporal_store(f32x2{p0, p1}, P);
+    __builtin_nontemporal_store(f32x2{m0, m1}, M);
+    __builtin_nontemporal_store(f32x2{v0, v1}, V);
+    if constexpr (HAS_OUT)
+        __builtin_nontemporal_store(bf16_rne_bits(p0) | (bf16_rne_bits(p1) << 16), reinterpret_cast<uint32_t*>(tab.out[lo]) + i);
+}
+
 // Scalar kernel: elements [first, n), any alignment, one element per thread.  Same arithmetic.
 template <bool GRAD_BF16>
 __global__ __launch_bounds__(256) void adam_scalar_kernel(float* master, float* exp_avg, float* exp_avg_sq,

@@ -347,6 +347,81 @@ def test_adam_non_finite_inputs_propagate_like_the_oracle():
     assert np.array_equal(np.isfinite(orc.bf16_to_f32(gb)), np.isfinite(orc.bf16_to_f32(rb)))
 
 
+@pytest.mark.parametrize("grad_kind", ["bf16", "fp32"])
+def test_adam_multi_is_bit_identical_to_single_calls_and_matches_the_oracle(grad_kind):
+    # 70 chunks (more than one launch's table), ragged and odd lengths, an empty one, one slice at an odd offset
+    rng = np.random.default_rng(12)
+    lens = [int(x) for x in rng.integers(1, 40_000, size=66)] + [0, 1, 262_144, 99_999]
+    total = sum(lens) + 2 * len(lens) + 8
+    p, m, v = _adam_state(total, 40, zero_moments=False)
+    gb = gen.fill_bf16(gen.stream_key(40, gen.TAG_GRAD, 3), 0, total, 1e-3, zero_pct=1)
+    g = gb if grad_kind == "bf16" else (orc.bf16_to_f32(gb) * np.float32(0.7)).astype(np.float32)
+    starts, at = [], 0
+    for i, n in enumerate(lens):
+        at += at % 2                         # even start ...
+        if i == 5:
+            at += 1                          # ... except one chunk that starts on an odd element
+        starts.append(at)
+        at += n
+    coef = np.float32(0.37)
+    d_scale = dev(np.array([coef], np.float32))
+
+    def run(multi):
+        d_p, d_m, d_v, d_g = dev(p), dev(m), dev(v), dev(g)
+        d_o = torch.zeros(total, dtype=torch.int16, device=DEV)
+        sl = [slice(a, a + n) for a, n in zip(starts, lens)]
+        hp = hp_struct(3)
+        if multi:
+            gl = [d_g[s] for s in sl]
+            ex.elixir_chunk_adam_step_multi([d_p[s] for s in sl], [d_m[s] for s in sl], [d_v[s] for s in sl],
+                                            gl if grad_kind == "fp32" else None, gl if grad_kind == "bf16" else None,
+                                            [d_o[s] for s in sl], lens, hp, d_scale)
+        else:
+            for s, n in zip(sl, lens):
+                ex.elixir_chunk_adam_step(d_p[s], d_m[s], d_v[s], d_g[s] if grad_kind == "fp32" else None,
+                                          d_g[s] if grad_kind == "bf16" else None, d_o[s], n, hp, d_scale)
+        sync()
+        return host(d_p), host(d_m), host(d_v), host(d_o, np.uint16)
+
+    one, many = run(False), run(True)
+    for a, b in zip(one, many):
+        assert np.array_equal(a.view(np.uint8), b.view(np.uint8)), "multi-chunk launch differs from single calls"
+    rp, rm, rv, ro = p.copy(), m.copy(), v.copy(), np.zeros(total, np.uint16)
+    for a, n in zip(starts, lens):
+        if n:
+            orc.chunk_adam_step(rp[a:a + n], rm[a:a + n], rv[a:a + n], np.ascontiguousarray(g[a:a + n]), ro[a:a + n], step=3,
+                                grad_scale=float(coef), **HP)
+    check_adam_close(many[0], many[1], many[2], rp, rm, rv, lr=HP["lr"], gmax=5e-3)
+    covered = np.zeros(total, bool)
+    for a, n in zip(starts, lens):
+        covered[a:a + n] = True
+    check_bf16_copy(many[3][covered], many[0][covered], ro[covered], rp[covered], lr=HP["lr"])
+    assert not many[3][~covered].any()                         # nothing outside the chunks was written
+    for got, ref in zip(many[:3], (p, m, v)):
+        assert np.array_equal(got[~covered].view(np.uint32), ref[~covered].view(np.uint32))
+
+
+def test_adam_multi_without_bf16_copy_and_errors():
+    n = 5000
+    p, m, v = _adam_state(2 * n, 41, zero_moments=True)
+    g = gen.fill_f32(gen.stream_key(41, gen.TAG_GRAD, 1), 0, 2 * n, 1e-3)
+    d_p, d_m, d_v, d_g = dev(p), dev(m), dev(v), dev(g)
+    hp = hp_struct(1)
+    ex.elixir_chunk_adam_step_multi([d_p[:n], d_p[n:]], [d_m[:n], d_m[n:]], [d_v[:n], d_v[n:]], [d_g[:n], d_g[n:]], None, None,
+                                    [n, n], hp)
+    sync()
+    orc.chunk_adam_step(p, m, v, g, None, step=1, **HP)
+    check_adam_close(host(d_p), host(d_m), host(d_v), p, m, v, lr=HP["lr"], gmax=5e-3)
+    for bad in (lambda: ex.elixir_chunk_adam_step_multi([d_p], [d_m], [d_v], None, None, None, [n], hp),              # no gradients
+                lambda: ex.elixir_chunk_adam_step_multi([d_p], [d_m], [d_v], [d_g], [d_g], None, [n], hp),            # both kinds
+                lambda: ex.elixir_chunk_adam_step_multi([d_p], [d_m], [d_v], [d_g], None, None, [-1], hp),            # negative length
+                lambda: ex.elixir_chunk_adam_step_multi([d_p], [None], [d_v], [d_g], None, None, [n], hp)):           # NULL pointer
+        with pytest.raises(ex.ElixirError) as e:
+            bad()
+        assert e.value.code == ex.ELIXIR_EINVAL
+    ex.elixir_chunk_adam_step_multi([], [], [], [], None, None, [], hp)
+
+
 # --------------------------------------------------------------------------- whole configurations
 
 def test_config_tiny_gpt2_ten_steps_end_to_end():
