@@ -52,7 +52,8 @@ def parse():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="gpt2_1p5b",
-                    help="gpt2_1p5b (default, the benchmark line), tiny, sweep (chunk sizes 8Mi..256Mi), gpt2_6b_clip, gpt2_20b_offload")
+                    help="gpt2_1p5b (default, the benchmark line), tiny, sweep (chunk sizes 8Mi..256Mi), gpt2_6b_clip, gpt2_20b_offload, gpt2_20b_hybrid (CPU update + streaming)")
+    ap.add_argument("--host-threads", type=int, default=0, help="gpt2_20b_hybrid: threads of the CPU update (default: all cores)")
     ap.add_argument("--host-chunks", type=int, default=0, help="gpt2_20b_offload: allocate only about this many host-resident chunks")
     ap.add_argument("--multi", action="store_true",
                     help="update all chunks of a step with elixir_chunk_adam_step_multi (always done for chunks of <= 16Mi elements, "
@@ -467,6 +468,131 @@ def run_offload(args, torch, ex, gen):
         ex.elixir_ctx_destroy(ctx)
 
 
+def run_hybrid(args, torch, ex, gen):
+    """Host-resident chunks of the 20B set (128Mi elements) updated two ways at once: some are streamed to the GPU and
+    back ([master|m|v], 12 + 12 bytes per element over the link), the others are updated by the host cores in place,
+    the paper's own treatment (only bf16 gradients come down and bf16 parameters go up: 2 + 2 bytes per element).
+    Sweeps the share of host chunks given to the CPU; the resident chunks are updated on the GPU meanwhile."""
+    import threading
+
+    cfg = gen.CONFIGS["gpt2_20b_offload"]
+    dev = torch.device("cuda:0")
+    C = cfg.chunk_elems
+    n_host = args.host_chunks if args.host_chunks > 0 else 16
+    n_res = max(1, round(n_host * 2 / 3))                                  # 60 / 40
+    nbytes = 3 * C * 4
+    threads = args.host_threads if args.host_threads > 0 else len(os.sched_getaffinity(0))
+    compute, h2d, d2h, gdown, pup = (torch.cuda.Stream() for _ in range(5))
+    sh = compute.cuda_stream
+    ctx = ex.elixir_ctx_create(0, C, 8)
+    blocks = [ex.elixir_host_alloc(nbytes) for _ in range(n_host)]
+    hgrad = [ex.elixir_host_alloc(2 * C) for _ in range(2)]
+    hparam = [ex.elixir_host_alloc(2 * C) for _ in range(2)]
+    slots = [torch.zeros(3, C, dtype=torch.float32, device=dev) for _ in range(3)]
+    grads = torch.zeros(n_host + n_res, C, dtype=torch.int16, device=dev)
+    out = torch.zeros(n_host + n_res, C, dtype=torch.int16, device=dev)
+    resident = [torch.zeros(3, C, dtype=torch.float32, device=dev) for _ in range(n_res)]
+    pkey = gen.stream_key(gen.BASE_SEED, gen.TAG_PARAM, cfg=cfg.cfg_id)
+    gkey = gen.stream_key(gen.BASE_SEED, gen.TAG_GRAD, 1, 0, cfg.cfg_id)
+    try:
+        ex.elixir_offload_register_slots(ctx, slots, nbytes)
+        overlapped = ex.elixir_offload_bind_streams(ctx, h2d, d2h)
+        for c in range(n_host + n_res):
+            gen.fill_bf16_device(grads[c].data_ptr(), C, gkey, c * C, cfg.grad_std)
+        for c in range(n_res):
+            gen.fill_f32_device(resident[c][0].data_ptr(), C, pkey, (n_host + c) * C, cfg.param_std)
+        for c in range(n_host):                                            # initial state of the host blocks
+            slots[0].zero_()
+            gen.fill_f32_device(slots[0][0].data_ptr(), C, pkey, c * C, cfg.param_std)
+            torch.cuda.synchronize()
+            ex.elixir_copy_d2h_async(blocks[c], slots[0], nbytes, d2h.cuda_stream)
+            torch.cuda.synchronize()
+        step_no = [0]
+
+        def cpu_path(chunks, hp):
+            # double-buffered: gradients of the next chunk come down while the cores update the current one
+            if not chunks:
+                return
+            ex.elixir_copy_d2h_async(hgrad[0], grads[chunks[0]], 2 * C, gdown.cuda_stream)
+            for i, c in enumerate(chunks):
+                b = i % 2
+                ex.elixir_stream_synchronize(gdown.cuda_stream)            # gradients of chunk c are in hgrad[b]
+                if i + 1 < len(chunks):
+                    ex.elixir_copy_d2h_async(hgrad[1 - b], grads[chunks[i + 1]], 2 * C, gdown.cuda_stream)
+                if i >= 2:
+                    ex.elixir_stream_synchronize(pup.cuda_stream)          # hparam[b] has left for the GPU
+                ex.elixir_host_adam_step(blocks[c], blocks[c] + 4 * C, blocks[c] + 8 * C, None, hgrad[b], hparam[b], C, hp, 1.0, threads)
+                ex.elixir_copy_h2d_async(out[c], hparam[b], 2 * C, pup.cuda_stream)
+            ex.elixir_stream_synchronize(pup.cuda_stream)
+
+        def step(n_cpu):
+            step_no[0] += 1
+            hp = ex.make_hparams(cfg.lr, cfg.beta1, cfg.beta2, cfg.eps, cfg.weight_decay, step_no[0])
+            cpu_chunks = list(range(n_cpu))
+            gpu_chunks = list(range(n_cpu, n_host))
+            worker = threading.Thread(target=cpu_path, args=(cpu_chunks, hp))
+            worker.start()
+            pending, inflight, r = list(gpu_chunks), [], 0
+            per = -(-n_res // max(1, len(gpu_chunks)))
+            for k in range(max(len(gpu_chunks), 1)):
+                while pending and len(inflight) < 3:
+                    inflight.append((pending[0], ex.elixir_chunk_prefetch(ctx, blocks[pending.pop(0)], nbytes, h2d)))
+                if inflight:
+                    c, s = inflight.pop(0)
+                    ex.elixir_chunk_wait_ready(ctx, s, compute)
+                    ex.elixir_chunk_adam_step(slots[s][0], slots[s][1], slots[s][2], None, grads[c], out[c], C, hp, None, sh)
+                    ex.elixir_chunk_evict(ctx, s, blocks[c], nbytes, compute, d2h)
+                for _ in range(per):                                       # resident chunks in between
+                    if r < n_res:
+                        st = resident[r]
+                        ex.elixir_chunk_adam_step(st[0], st[1], st[2], None, grads[n_host + r], out[n_host + r], C, hp, None, sh)
+                        r += 1
+            while r < n_res:
+                st = resident[r]
+                ex.elixir_chunk_adam_step(st[0], st[1], st[2], None, grads[n_host + r], out[n_host + r], C, hp, None, sh)
+                r += 1
+            worker.join()
+            torch.cuda.synchronize()
+
+        results = []
+        for n_cpu in sorted({0, n_host // 4, n_host // 2, 2 * n_host // 3, 3 * n_host // 4, 5 * n_host // 6, n_host}):
+            step(n_cpu)
+            t = []
+            for _ in range(args.steps):
+                torch.cuda.synchronize()
+                t0 = time.perf_counter()
+                step(n_cpu)
+                t.append(time.perf_counter() - t0)
+            results.append({"cpu_chunks": n_cpu, "streamed_chunks": n_host - n_cpu, "ms_per_step": min(t) * 1e3,
+                            "host_resident_G_elements_per_s": n_host * C / min(t) / 1e9})
+        # the CPU update alone: this box's V_c
+        hp = ex.make_hparams(cfg.lr, cfg.beta1, cfg.beta2, cfg.eps, cfg.weight_decay, 1)
+        vc = {}
+        for T in sorted({1, threads // 2, threads}):
+            if T < 1:
+                continue
+            ex.elixir_host_adam_step(blocks[0], blocks[0] + 4 * C, blocks[0] + 8 * C, None, hgrad[0], hparam[0], C, hp, 1.0, T)
+            t0 = time.perf_counter()
+            ex.elixir_host_adam_step(blocks[0], blocks[0] + 4 * C, blocks[0] + 8 * C, None, hgrad[0], hparam[0], C, hp, 1.0, T)
+            dt = time.perf_counter() - t0
+            vc[str(T)] = {"G_elements_per_s": C / dt / 1e9, "host_GB/s": 28 * C / dt / 1e9}
+        best = min(results, key=lambda r: r["ms_per_step"])
+        print(json.dumps({
+            "metric": "host-resident chunk update rate, CPU update and GPU streaming combined", "value": best["host_resident_G_elements_per_s"] * 1e9,
+            "unit": "params/s", "n_gpus": 1, "steps": args.steps, "warmup": 1, "ms_per_step": best["ms_per_step"], "dtype": "f32",
+            "data": "synthetic",
+            "config": {"workload": "gpt2-20B/C=128Mi hybrid offload", "chunk_elems": C, "host_chunks": n_host, "resident_chunks": n_res,
+                       "host_threads": threads, "host_isa": ex.elixir_host_adam_isa(), "copy_engines_separate": overlapped},
+            "sweep": results, "cpu_update_alone": vc,
+            "roofline": {"bound": "host memory / host link", "achieved": None, "peak": None, "frac": None, "traffic": None}}), flush=True)
+    finally:
+        torch.cuda.synchronize()
+        ex.elixir_offload_register_slots(ctx, [], 0)
+        for b in blocks + hgrad + hparam:
+            ex.elixir_host_free(b)
+        ex.elixir_ctx_destroy(ctx)
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -482,8 +608,9 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs an MI355X"
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
-    if args.workload in ("sweep", "gpt2_6b_clip", "gpt2_20b_offload"):
-        {"sweep": run_sweep, "gpt2_6b_clip": run_clip, "gpt2_20b_offload": run_offload}[args.workload](args, torch, ex, gen)
+    if args.workload in ("sweep", "gpt2_6b_clip", "gpt2_20b_offload", "gpt2_20b_hybrid"):
+        {"sweep": run_sweep, "gpt2_6b_clip": run_clip, "gpt2_20b_offload": run_offload,
+         "gpt2_20b_hybrid": run_hybrid}[args.workload](args, torch, ex, gen)
         return
     cfg = gen.CONFIGS[args.workload]
     C = cfg.chunk_elems

@@ -21,7 +21,8 @@
  *   - bf16 values are passed as their 16-bit patterns (uint16_t).
  *   - Every GPU operation is enqueued on the caller's stream and returns
  *     without waiting for it; no entry point synchronises the device except
- *     elixir_ctx_destroy.  elixir_stream_t is a hipStream_t (NULL = the
+ *     elixir_ctx_destroy (elixir_stream_synchronize and elixir_offload_bind_streams
+ *     wait for the streams they are given).  elixir_stream_t is a hipStream_t (NULL = the
  *     default stream).  The caller's current device must be the one that owns
  *     the stream and buffers.
  *   - The caller owns every buffer it passes in.  The library owns only what
@@ -218,6 +219,28 @@ int elixir_chunk_prefetch(elixir_ctx* ctx, const void* h_block, size_t bytes, in
 int elixir_chunk_wait_ready(elixir_ctx* ctx, int slot, elixir_stream_t compute_stream);
 int elixir_chunk_evict(elixir_ctx* ctx, int slot, void* h_block, size_t bytes, elixir_stream_t compute_stream,
                        elixir_stream_t d2h_stream);
+
+/*
+ * CPU update of a host-resident chunk, the paper's own treatment of chunks kept in CPU memory: the
+ * optimizer chunk never leaves the host, only low-precision gradients come down and low-precision
+ * parameters go up (paper Sec. 2 "Memory Offloading"; CPU update velocity V_c in Sec. 5 and App. B).
+ *   elixir_host_adam_step : the arithmetic of elixir_chunk_adam_step on HOST buffers, vectorised (AVX-512,
+ *       AVX2 or scalar, chosen at run time) and spread over n_threads threads (<= 0: every core the process
+ *       may run on).  Blocks until done.  grad_scale is a plain float (1 for no clipping).  Exactly one of
+ *       h_grad_fp32 / h_grad_bf16 is non-NULL; h_param_bf16 may be NULL.
+ *   elixir_host_adam_isa : "avx512", "avx2" or "scalar".
+ *   elixir_copy_h2d_async / elixir_copy_d2h_async : asynchronous copies between pinned host memory and
+ *       device memory on the caller's stream.  elixir_stream_synchronize : waits for a stream (the host
+ *       must see the gradients before it updates, and the copy engines must be done with a host buffer
+ *       before the CPU rewrites it).
+ */
+int elixir_host_adam_step(float* h_master, float* h_exp_avg, float* h_exp_avg_sq, const float* h_grad_fp32,
+                          const uint16_t* h_grad_bf16, uint16_t* h_param_bf16, int64_t n,
+                          const elixir_adam_hparams* hp, float grad_scale, int n_threads);
+const char* elixir_host_adam_isa(void);
+int elixir_copy_h2d_async(void* d_dst, const void* h_src, size_t bytes, elixir_stream_t stream);
+int elixir_copy_d2h_async(void* h_dst, const void* d_src, size_t bytes, elixir_stream_t stream);
+int elixir_stream_synchronize(elixir_stream_t stream);
 
 #ifdef __cplusplus
 }

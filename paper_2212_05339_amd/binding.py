@@ -23,7 +23,8 @@ EXPORTS = (
     "elixir_chunk_adam_step_multi",
     "elixir_host_alloc", "elixir_host_free", "elixir_offload_register_slots", "elixir_offload_bind_streams",
     "elixir_chunk_prefetch",
-    "elixir_chunk_wait_ready", "elixir_chunk_evict",
+    "elixir_chunk_wait_ready", "elixir_chunk_evict", "elixir_host_adam_step", "elixir_host_adam_isa", "elixir_copy_h2d_async",
+    "elixir_copy_d2h_async", "elixir_stream_synchronize",
 )
 
 
@@ -72,6 +73,12 @@ def lib() -> ctypes.CDLL:
             "elixir_chunk_wait_ready": [vp, ci, vp],
             "elixir_chunk_evict": [vp, ci, vp, sz, vp, vp],
         }
+        sigs["elixir_host_adam_step"] = [vp, vp, vp, vp, vp, vp, i64, ctypes.POINTER(elixir_adam_hparams), f32, ci]
+        sigs["elixir_copy_h2d_async"] = [vp, vp, sz, vp]
+        sigs["elixir_copy_d2h_async"] = [vp, vp, sz, vp]
+        sigs["elixir_stream_synchronize"] = [vp]
+        L.elixir_host_adam_isa.restype = ctypes.c_char_p
+        L.elixir_host_adam_isa.argtypes = []
         for name, argtypes in sigs.items():
             f = getattr(L, name)
             f.restype = ci
@@ -237,3 +244,35 @@ def elixir_chunk_wait_ready(ctx: Ctx, slot: int, compute_stream=None) -> None:
 
 def elixir_chunk_evict(ctx: Ctx, slot: int, h_block: Optional[int], nbytes: int, compute_stream, d2h_stream) -> None:
     _check(lib().elixir_chunk_evict(ctx.handle, slot, h_block, nbytes, _stream(compute_stream), _stream(d2h_stream)))
+
+
+# --------------------------------------------------------------------------- CPU update of host-resident chunks
+
+def _host_addr(x):
+    """Address of a numpy array, a raw integer address, or None."""
+    if x is None or isinstance(x, int):
+        return x
+    return x.ctypes.data
+
+
+def elixir_host_adam_step(master, exp_avg, exp_avg_sq, grad_fp32, grad_bf16, param_bf16, n: int, hp: elixir_adam_hparams,
+                          grad_scale: float = 1.0, n_threads: int = 0) -> None:
+    """Host buffers are numpy arrays or raw addresses (e.g. from elixir_host_alloc)."""
+    _check(lib().elixir_host_adam_step(_host_addr(master), _host_addr(exp_avg), _host_addr(exp_avg_sq), _host_addr(grad_fp32),
+                                       _host_addr(grad_bf16), _host_addr(param_bf16), n, ctypes.byref(hp), grad_scale, n_threads))
+
+
+def elixir_host_adam_isa() -> str:
+    return lib().elixir_host_adam_isa().decode()
+
+
+def elixir_copy_h2d_async(d_dst, h_src: int, nbytes: int, stream=None) -> None:
+    _check(lib().elixir_copy_h2d_async(_addr(d_dst), h_src, nbytes, _stream(stream)))
+
+
+def elixir_copy_d2h_async(h_dst: int, d_src, nbytes: int, stream=None) -> None:
+    _check(lib().elixir_copy_d2h_async(h_dst, _addr(d_src), nbytes, _stream(stream)))
+
+
+def elixir_stream_synchronize(stream=None) -> None:
+    _check(lib().elixir_stream_synchronize(_stream(stream)))

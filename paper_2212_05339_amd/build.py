@@ -8,6 +8,7 @@ _PKG = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(_PKG, "csrc")
 LIB = os.path.join(_PKG, "libelixir_chunk.so")
 SOURCES = ["ctx.cpp", "layout.cpp", "offload.cpp", "pack.hip", "reduce.hip", "norm.hip", "adam.hip"]
+HOST_SOURCES = ["host_adam.cpp"]   # plain C++ (x86 intrinsics, threads): compiled by g++, linked into the same library
 
 # -ffp-contract=off: fused multiply-adds appear only where the source asks for them, so the
 #   separately rounded multiply/add of the gradient reduction stay separate.
@@ -19,10 +20,24 @@ HIPCC_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
 def build_library(verbose: bool = False) -> str:
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
     tmp = LIB + f".tmp{os.getpid()}"
-    cmd = [hipcc, *HIPCC_FLAGS, "-x", "hip", *[os.path.join(CSRC, s) for s in SOURCES], "-o", tmp]
-    if verbose:
-        print(" ".join(cmd), flush=True)
-    subprocess.check_call(cmd)
+    objs = []
+    for src in HOST_SOURCES:
+        obj = os.path.join(CSRC, src + f".{os.getpid()}.o")
+        cmd = ["g++", "-O3", "-std=c++17", "-fPIC", "-ffp-contract=off", "-fno-fast-math", "-pthread", "-Wall", "-c",
+               os.path.join(CSRC, src), "-o", obj]
+        if verbose:
+            print(" ".join(cmd), flush=True)
+        subprocess.check_call(cmd)
+        objs.append(obj)
+    try:
+        cmd = [hipcc, *HIPCC_FLAGS, "-x", "hip", *[os.path.join(CSRC, s) for s in SOURCES], "-x", "none", *objs, "-pthread", "-o", tmp]
+        if verbose:
+            print(" ".join(cmd), flush=True)
+        subprocess.check_call(cmd)
+    finally:
+        for o in objs:
+            if os.path.exists(o):
+                os.remove(o)
     os.replace(tmp, LIB)
     return LIB
 

@@ -7,10 +7,9 @@
 
 #include "../../include/elixir_chunk.h"
 
-namespace elixir {
+#include "status.hpp"
 
-// Stores the per-thread message returned by elixir_last_error() and hands back `code`.
-int fail(int code, const char* fmt, ...) __attribute__((format(printf, 2, 3)));
+namespace elixir {
 
 inline bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
 

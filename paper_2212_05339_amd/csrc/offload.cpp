@@ -19,6 +19,28 @@ void destroy_slots(elixir_ctx* c);
 }
 using namespace elixir;
 
+namespace {
+
+// Block copies are issued in pieces: a DMA engine serves the streams that share it one command at a time, so a
+// 1.6 GB command would make a small copy on another stream (the gradients of a CPU-updated chunk) wait 30 ms.
+constexpr size_t kDmaPiece = (size_t)256 << 20;
+
+hipError_t copy_in_pieces(void* dst, const void* src, size_t bytes, hipMemcpyKind kind, hipStream_t s) {
+    char* d = static_cast<char*>(dst);
+    const char* q = static_cast<const char*>(src);
+    while (bytes > 0) {
+        const size_t n = bytes < kDmaPiece ? bytes : kDmaPiece;
+        const hipError_t e = hipMemcpyAsync(d, q, n, kind, s);
+        if (e != hipSuccess) return e;
+        d += n;
+        q += n;
+        bytes -= n;
+    }
+    return hipSuccess;
+}
+
+}  // namespace
+
 extern "C" int elixir_offload_register_slots(elixir_ctx* ctx, void* const* d_slots, int n_slots, size_t slot_bytes) {
     if (!ctx) return fail(ELIXIR_EINVAL, "elixir_offload_register_slots: ctx is NULL");
     if (n_slots < 0 || (n_slots > 0 && (!d_slots || slot_bytes == 0)))
@@ -64,7 +86,7 @@ extern "C" int elixir_chunk_prefetch(elixir_ctx* ctx, const void* h_block, size_
     Slot& sl = ctx->slots[slot];
     hipStream_t s = (hipStream_t)h2d_stream;
     if (sl.evict_pending) ELIXIR_HIP_TRY(hipStreamWaitEvent(s, sl.evicted, 0));
-    ELIXIR_HIP_TRY(hipMemcpyAsync(sl.d_ptr, h_block, bytes, hipMemcpyHostToDevice, s));
+    ELIXIR_HIP_TRY(copy_in_pieces(sl.d_ptr, h_block, bytes, hipMemcpyHostToDevice, s));
     ELIXIR_HIP_TRY(hipEventRecord(sl.ready, s));
     sl.held = true;
     ctx->next_slot = (slot + 1) % ctx->n_slots;
@@ -92,7 +114,7 @@ extern "C" int elixir_chunk_evict(elixir_ctx* ctx, int slot, void* h_block, size
     // everything enqueued so far on the compute stream (the update of this slot) must finish first
     ELIXIR_HIP_TRY(hipEventRecord(sl.updated, cs));
     ELIXIR_HIP_TRY(hipStreamWaitEvent(ds, sl.updated, 0));
-    if (h_block) ELIXIR_HIP_TRY(hipMemcpyAsync(h_block, sl.d_ptr, bytes, hipMemcpyDeviceToHost, ds));
+    if (h_block) ELIXIR_HIP_TRY(copy_in_pieces(h_block, sl.d_ptr, bytes, hipMemcpyDeviceToHost, ds));
     ELIXIR_HIP_TRY(hipEventRecord(sl.evicted, ds));
     sl.evict_pending = true;
     sl.held = false;
@@ -146,5 +168,26 @@ extern "C" int elixir_offload_bind_streams(elixir_ctx* ctx, elixir_stream_t h2d_
     if ((e = hipGetLastError()) != hipSuccess) return bail(e, "timed copies");
     if (overlapped_out) *overlapped_out = t_both < 1.6 * t_up ? 1 : 0;
     ELIXIR_HIP_TRY(hipHostFree(h));
+    return ELIXIR_OK;
+}
+
+// Plain asynchronous copies between pinned host memory and device memory on the caller's stream: what the
+// CPU-update path needs (low-precision gradients down, low-precision parameters up).
+extern "C" int elixir_copy_h2d_async(void* d_dst, const void* h_src, size_t bytes, elixir_stream_t stream) {
+    if (bytes == 0) return ELIXIR_OK;
+    if (!d_dst || !h_src) return fail(ELIXIR_EINVAL, "elixir_copy_h2d_async: NULL pointer");
+    ELIXIR_HIP_TRY(hipMemcpyAsync(d_dst, h_src, bytes, hipMemcpyHostToDevice, (hipStream_t)stream));
+    return ELIXIR_OK;
+}
+
+extern "C" int elixir_copy_d2h_async(void* h_dst, const void* d_src, size_t bytes, elixir_stream_t stream) {
+    if (bytes == 0) return ELIXIR_OK;
+    if (!h_dst || !d_src) return fail(ELIXIR_EINVAL, "elixir_copy_d2h_async: NULL pointer");
+    ELIXIR_HIP_TRY(hipMemcpyAsync(h_dst, d_src, bytes, hipMemcpyDeviceToHost, (hipStream_t)stream));
+    return ELIXIR_OK;
+}
+
+extern "C" int elixir_stream_synchronize(elixir_stream_t stream) {
+    ELIXIR_HIP_TRY(hipStreamSynchronize((hipStream_t)stream));
     return ELIXIR_OK;
 }

@@ -1,0 +1,112 @@
+"""The CPU update of host-resident chunks (elixir_host_adam_step) against the oracle.  Host code only: runs without a
+GPU.  Every instruction-set variant the machine supports is exercised through ELIXIR_HOST_ISA."""
+import os
+import subprocess
+import sys
+
+import numpy as np
+import pytest
+
+import paper_2212_05339_amd as ex
+from oracle import elixir_oracle as orc
+from synth import gen
+from tests._util import HP, check_adam_close, check_bf16_copy
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def hp_struct(step, **over):
+    h = dict(HP, **over)
+    return ex.make_hparams(h["lr"], h["beta1"], h["beta2"], h["eps"], h["weight_decay"], step)
+
+
+def state(n, seed):
+    p = gen.fill_f32(gen.stream_key(seed, gen.TAG_PARAM), 0, n, 0.02)
+    m = gen.fill_f32(gen.stream_key(seed, gen.TAG_MOMENT, 0), 0, n, 3e-4)
+    v = np.square(np.abs(m) + np.abs(gen.fill_f32(gen.stream_key(seed, gen.TAG_MOMENT, 1), 0, n, 1e-3)))
+    return p, m, v
+
+
+def run_case(n, shift, grad_kind, threads, steps=1, with_out=True):
+    p, m, v = state(n + 40, 50 + n % 7)
+    gb = gen.fill_bf16(gen.stream_key(51, gen.TAG_GRAD, 1), 0, n + 40, 1e-3, zero_pct=1)
+    g = gb if grad_kind == "bf16" else (orc.bf16_to_f32(gb) * np.float32(1.3)).astype(np.float32)
+    s = slice(shift, shift + n)
+    a = [p.copy(), m.copy(), v.copy()]
+    r = [p.copy(), m.copy(), v.copy()]
+    out = np.full(n + 40, 7, np.uint16)
+    ro = np.full(n + 40, 7, np.uint16)
+    for t in range(1, steps + 1):
+        ex.elixir_host_adam_step(a[0][s], a[1][s], a[2][s], g[s] if grad_kind == "fp32" else None,
+                                 g[s] if grad_kind == "bf16" else None, out[s] if with_out else None, n, hp_struct(t), 0.5, threads)
+        if n:
+            orc.chunk_adam_step(r[0][s], r[1][s], r[2][s], np.ascontiguousarray(g[s]), ro[s] if with_out else None, step=t,
+                                grad_scale=0.5, **HP)
+    check_adam_close(a[0], a[1], a[2], r[0], r[1], r[2], lr=HP["lr"], gmax=5e-3, steps=steps, what=f"n={n} shift={shift}")
+    if with_out:
+        check_bf16_copy(out[s], a[0][s], ro[s], r[0][s], lr=HP["lr"], steps=steps)
+    # nothing outside the slice was touched
+    for x, y in zip(a, (p, m, v)):
+        assert np.array_equal(x[:shift].view(np.uint32), y[:shift].view(np.uint32))
+        assert np.array_equal(x[shift + n:].view(np.uint32), y[shift + n:].view(np.uint32))
+    assert np.all(out[:shift] == 7) and np.all(out[shift + n:] == 7)
+
+
+@pytest.mark.parametrize("grad_kind", ["bf16", "fp32"])
+@pytest.mark.parametrize("n,shift", [(0, 0), (1, 0), (15, 3), (16, 0), (17, 1), (1000, 5), (65_536 * 3 + 11, 2), (1_000_003, 0)])
+def test_host_adam_matches_oracle(grad_kind, n, shift):
+    run_case(n, shift, grad_kind, threads=0)
+    run_case(n, shift, grad_kind, threads=1, with_out=False)
+
+
+def test_host_adam_many_threads_and_steps():
+    run_case(700_001, 7, "bf16", threads=5, steps=10)
+
+
+def test_host_adam_first_step_closed_form():
+    n = 100_000
+    p = gen.fill_f32(gen.stream_key(60, gen.TAG_PARAM), 0, n, 0.02)
+    gb = gen.fill_bf16(gen.stream_key(60, gen.TAG_GRAD, 1), 0, n, 1e-3, zero_pct=1)
+    p0 = p.copy()
+    m, v = np.zeros(n, np.float32), np.zeros(n, np.float32)
+    ex.elixir_host_adam_step(p, m, v, None, gb, None, n, hp_struct(1, weight_decay=0.0))
+    gf = orc.bf16_to_f32(gb).astype(np.float64)
+    lr, eps = float(np.float32(HP["lr"])), float(np.float32(HP["eps"]))
+    want = p0.astype(np.float64) - lr * gf / (np.abs(gf) + eps)
+    assert np.max(np.abs(p.astype(np.float64) - want)) <= 1e-6 * lr + 2.0 ** -24 * 0.1
+    assert np.array_equal(p[gf == 0], p0[gf == 0])
+
+
+def test_host_adam_errors():
+    z = np.zeros(8, np.float32)
+    g = np.zeros(8, np.uint16)
+    hp = hp_struct(1)
+    for call, code in ((lambda: ex.elixir_host_adam_step(z, z, z, None, None, None, 8, hp), ex.ELIXIR_EINVAL),
+                       (lambda: ex.elixir_host_adam_step(z, z, z, z, g, None, 8, hp), ex.ELIXIR_EINVAL),
+                       (lambda: ex.elixir_host_adam_step(None, z, z, None, g, None, 8, hp), ex.ELIXIR_EINVAL),
+                       (lambda: ex.elixir_host_adam_step(z, z, z, None, g, None, -1, hp), ex.ELIXIR_EINVAL),
+                       (lambda: ex.elixir_host_adam_step(z, z, z, None, g, None, 8, hp_struct(0)), ex.ELIXIR_EINVAL),
+                       (lambda: ex.elixir_host_adam_step(z.ctypes.data + 2, z, z, None, g, None, 4, hp), ex.ELIXIR_EALIGN)):
+        with pytest.raises(ex.ElixirError) as e:
+            call()
+        assert e.value.code == code
+
+
+@pytest.mark.parametrize("isa", ["scalar", "avx2", "avx512"])
+def test_every_isa_variant_in_a_fresh_process(isa):
+    """The variant is chosen once per process from the CPU's features; the environment variable can only lower it."""
+    best = ex.elixir_host_adam_isa()
+    order = ["scalar", "avx2", "avx512"]
+    if order.index(isa) > order.index(best):
+        pytest.skip(f"this CPU offers {best}")
+    code = ("import sys; sys.path.insert(0, %r)\n"
+            "import paper_2212_05339_amd as ex\n"
+            "assert ex.elixir_host_adam_isa() == %r, ex.elixir_host_adam_isa()\n"
+            "from tests import test_host_adam as t\n"
+            "for kind in ('bf16', 'fp32'):\n"
+            "    for n, shift in ((17, 1), (70001, 3), (262144, 0)):\n"
+            "        t.run_case(n, shift, kind, threads=3)\n"
+            "print('ok')\n") % (ROOT, isa)
+    env = dict(os.environ, ELIXIR_HOST_ISA=isa)
+    r = subprocess.run([sys.executable, "-c", code], env=env, capture_output=True, text=True, timeout=300)
+    assert r.returncode == 0 and "ok" in r.stdout, r.stderr[-2000:]
