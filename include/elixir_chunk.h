@@ -242,6 +242,30 @@ int elixir_copy_h2d_async(void* d_dst, const void* h_src, size_t bytes, elixir_s
 int elixir_copy_d2h_async(void* h_dst, const void* d_src, size_t bytes, elixir_stream_t stream);
 int elixir_stream_synchronize(elixir_stream_t stream);
 
+/*
+ * Offloading benefit model (paper Sec. 5.1, Eq. 1 and Eq. 2) and the placement rule built on it.  Host only.
+ *   hw : aggregate bandwidths in BYTES per second (GPU to CPU, CPU to GPU) and aggregate update
+ *        velocities in ELEMENTS per second (GPU, CPU) of the n_procs processes.
+ *   elixir_offload_benefit : *I_out = I(n), the normalised time saved by one more rCache block;
+ *        *J_out = J(n), the normalised time saved by moving one chunk and its update to the GPU.
+ *        L_c, L_os: precision lengths in bytes (2 and 4); F_os: optimizer-state factor (3 for Adam).
+ *   elixir_offload_plan : starts from min_blocks rCache blocks (the activation-checkpointing buffer
+ *        size of App. A.3, at least 1) and all n_chunks chunks in CPU memory, and spends allowed_bytes
+ *        (U_allowed, per GPU) on what has the larger benefit first: chunks moved to the GPU cost
+ *        (L_c + L_os*F_os)*C/n_procs bytes each, rCache blocks L_c*C bytes each (at most n_chunks
+ *        blocks: every chunk cached).  If allowed_bytes does not cover the mandatory blocks they are
+ *        kept and nothing is moved.
+ */
+typedef struct {
+    double b_g2c, b_c2g; /* bytes per second */
+    double v_g, v_c;     /* elements per second */
+} elixir_hw_profile;
+int elixir_offload_benefit(int n_procs, int64_t chunk_elems, int L_c, int L_os, int F_os, const elixir_hw_profile* hw,
+                           double* I_out, double* J_out);
+int elixir_offload_plan(int n_procs, int64_t chunk_elems, int64_t n_chunks, int64_t min_blocks, int L_c, int L_os,
+                        int F_os, const elixir_hw_profile* hw, double allowed_bytes, int64_t* n_blocks_out,
+                        int64_t* n_gpu_chunks_out);
+
 #ifdef __cplusplus
 }
 #endif

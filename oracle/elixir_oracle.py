@@ -242,3 +242,42 @@ def chunk_adam_step(master, exp_avg, exp_avg_sq, grad, param_bf16, *, lr, beta1,
     out = _ptr(param_bf16, np.uint16) if param_bf16 is not None else None
     _L().orc_chunk_adam_step(_ptr(master, np.float32), _ptr(exp_avg, np.float32), _ptr(exp_avg_sq, np.float32),
                              g32, g16, out, n, lr, beta1, beta2, eps, weight_decay, step, float(grad_scale))
+
+
+# ---------------------------------------------------------------------------
+# Offloading benefit model (paper Sec. 5.1, Eq. 1 and Eq. 2), in exact rationals.
+#   I(n) = 1/L_c * ( L_c C / B_g2c + L_c C / B_c2g )
+#   J(n) = n / (L_c + L_os F_os) * [ ( L_os C / B_c2g + L_c I + L_c C / B_g2c ) + ( C / V_c - C / V_g ) ]
+# and the placement rule of the same section: what has the larger benefit gets the spare GPU memory first.
+# ---------------------------------------------------------------------------
+
+def offload_benefit(n, C, b_g2c, b_c2g, v_g, v_c, L_c=2, L_os=4, F_os=3):
+    from fractions import Fraction as Fr
+    C, b_g2c, b_c2g, v_g, v_c = (Fr(x) for x in (C, b_g2c, b_c2g, v_g, v_c))
+    I = Fr(1, L_c) * (L_c * C / b_g2c + L_c * C / b_c2g)
+    J = Fr(n, L_c + L_os * F_os) * ((L_os * C / b_c2g + L_c * I + L_c * C / b_g2c) + (C / v_c - C / v_g))
+    return I, J
+
+
+def offload_plan(n, C, n_chunks, min_blocks, allowed_bytes, b_g2c, b_c2g, v_g, v_c, L_c=2, L_os=4, F_os=3):
+    """(rCache blocks, chunks moved to the GPU): start from min_blocks blocks and every chunk in CPU memory."""
+    from fractions import Fraction as Fr
+    I, J = offload_benefit(n, C, b_g2c, b_c2g, v_g, v_c, L_c, L_os, F_os)
+    block = Fr(L_c * C)
+    chunk = Fr((L_c + L_os * F_os) * C, n)
+    blocks = max(1, min(min_blocks, n_chunks) if n_chunks else min_blocks)
+    left = Fr(allowed_bytes) - blocks * block
+    if left < 0:
+        return blocks, 0
+    up = 0
+    order = ("chunks", "blocks") if J > I else ("blocks", "chunks")
+    for what in order:
+        if what == "chunks":
+            k = max(0, min(n_chunks, int(left // chunk)))
+            up += k
+            left -= k * chunk
+        else:
+            k = max(0, min(n_chunks - blocks, int(left // block)))
+            blocks += k
+            left -= k * block
+    return blocks, up

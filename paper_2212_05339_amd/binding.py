@@ -24,7 +24,7 @@ EXPORTS = (
     "elixir_host_alloc", "elixir_host_free", "elixir_offload_register_slots", "elixir_offload_bind_streams",
     "elixir_chunk_prefetch",
     "elixir_chunk_wait_ready", "elixir_chunk_evict", "elixir_host_adam_step", "elixir_host_adam_isa", "elixir_copy_h2d_async",
-    "elixir_copy_d2h_async", "elixir_stream_synchronize",
+    "elixir_copy_d2h_async", "elixir_stream_synchronize", "elixir_offload_benefit", "elixir_offload_plan",
 )
 
 
@@ -32,6 +32,10 @@ class ElixirError(RuntimeError):
     def __init__(self, code: int, message: str):
         super().__init__(f"libelixir_chunk status {code}: {message}")
         self.code = code
+
+
+class elixir_hw_profile(ctypes.Structure):
+    _fields_ = [("b_g2c", ctypes.c_double), ("b_c2g", ctypes.c_double), ("v_g", ctypes.c_double), ("v_c", ctypes.c_double)]
 
 
 class elixir_adam_hparams(ctypes.Structure):
@@ -77,6 +81,9 @@ def lib() -> ctypes.CDLL:
         sigs["elixir_copy_h2d_async"] = [vp, vp, sz, vp]
         sigs["elixir_copy_d2h_async"] = [vp, vp, sz, vp]
         sigs["elixir_stream_synchronize"] = [vp]
+        pd = ctypes.POINTER(ctypes.c_double)
+        sigs["elixir_offload_benefit"] = [ci, i64, ci, ci, ci, ctypes.POINTER(elixir_hw_profile), pd, pd]
+        sigs["elixir_offload_plan"] = [ci, i64, i64, i64, ci, ci, ci, ctypes.POINTER(elixir_hw_profile), ctypes.c_double, pi64, pi64]
         L.elixir_host_adam_isa.restype = ctypes.c_char_p
         L.elixir_host_adam_isa.argtypes = []
         for name, argtypes in sigs.items():
@@ -276,3 +283,24 @@ def elixir_copy_d2h_async(h_dst: int, d_src, nbytes: int, stream=None) -> None:
 
 def elixir_stream_synchronize(stream=None) -> None:
     _check(lib().elixir_stream_synchronize(_stream(stream)))
+
+
+# --------------------------------------------------------------------------- benefit model
+
+def elixir_offload_benefit(n_procs: int, chunk_elems: int, b_g2c: float, b_c2g: float, v_g: float, v_c: float,
+                           L_c: int = 2, L_os: int = 4, F_os: int = 3):
+    """Returns (I, J).  Bandwidths in bytes/s, velocities in elements/s."""
+    hw = elixir_hw_profile(b_g2c, b_c2g, v_g, v_c)
+    i, j = ctypes.c_double(), ctypes.c_double()
+    _check(lib().elixir_offload_benefit(n_procs, chunk_elems, L_c, L_os, F_os, ctypes.byref(hw), ctypes.byref(i), ctypes.byref(j)))
+    return i.value, j.value
+
+
+def elixir_offload_plan(n_procs: int, chunk_elems: int, n_chunks: int, min_blocks: int, allowed_bytes: float, b_g2c: float,
+                        b_c2g: float, v_g: float, v_c: float, L_c: int = 2, L_os: int = 4, F_os: int = 3):
+    """Returns (n_blocks, n_gpu_chunks)."""
+    hw = elixir_hw_profile(b_g2c, b_c2g, v_g, v_c)
+    nb, ng = ctypes.c_int64(), ctypes.c_int64()
+    _check(lib().elixir_offload_plan(n_procs, chunk_elems, n_chunks, min_blocks, L_c, L_os, F_os, ctypes.byref(hw), allowed_bytes,
+                                     ctypes.byref(nb), ctypes.byref(ng)))
+    return nb.value, ng.value
