@@ -266,6 +266,27 @@ int elixir_offload_plan(int n_procs, int64_t chunk_elems, int64_t n_chunks, int6
                         int F_os, const elixir_hw_profile* hw, double allowed_bytes, int64_t* n_blocks_out,
                         int64_t* n_gpu_chunks_out);
 
+/*
+ * rCache replacement simulation and chunk-size search (paper Sec. 3 "rCache": n_block equal blocks, Belady's
+ * replacement from the known order of use; App. A.2: the chunk length that minimises the bytes replaced in
+ * the rCache during one training step, found by simulating candidates).  Host only, integers.
+ *   elixir_rcache_simulate : replays seq[0..len) (chunk ids, >= 0, dense) through n_blocks blocks, evicting
+ *       the cached chunk whose next use lies farthest ahead (never used again first; ties: lowest id).
+ *       *misses_out = accesses that found their chunk absent, *evictions_out = misses that displaced a chunk.
+ *   elixir_chunk_size_search : for every candidate length plans the layout (policy, align_elems as for
+ *       elixir_layout_plan), builds the access sequence of one step (parameters in order, then in reverse
+ *       order; a parameter touches every chunk it spans; repeated accesses to the same chunk in a row
+ *       count once), gives the cache floor(cache_bytes / (L_c * C)) blocks (at least 1) and records
+ *       replaced_bytes_out[k] = evictions * L_c * C and, if padding_out is non-NULL, the padding elements.
+ *       *best_out = index of the candidate with the fewest replaced bytes (ties: less padding, then the
+ *       longer chunk).
+ */
+int elixir_rcache_simulate(const int64_t* seq, int64_t len, int64_t n_blocks, int64_t* misses_out,
+                           int64_t* evictions_out);
+int elixir_chunk_size_search(const int64_t* numel, int T, const int64_t* candidates, int n_cand, int policy,
+                             int64_t align_elems, double cache_bytes, int L_c, int* best_out,
+                             int64_t* replaced_bytes_out, int64_t* padding_out);
+
 #ifdef __cplusplus
 }
 #endif

@@ -281,3 +281,65 @@ def offload_plan(n, C, n_chunks, min_blocks, allowed_bytes, b_g2c, b_c2g, v_g, v
             blocks += k
             left -= k * block
     return blocks, up
+
+
+# ---------------------------------------------------------------------------
+# rCache with Belady's replacement (paper Sec. 3 "rCache") and the chunk-size search of App. A.2, written as
+# the definitions read: on a miss with a full cache, look ahead in the sequence for every cached chunk and
+# evict the one used farthest in the future (never again first; ties: lowest id).
+# ---------------------------------------------------------------------------
+
+def rcache_simulate(seq, n_blocks):
+    """(misses, evictions)."""
+    if n_blocks < 1:
+        raise ValueError("at least one block")
+    cache, misses, evictions = [], 0, 0
+    for i, c in enumerate(seq):
+        if c in cache:
+            continue
+        misses += 1
+        if len(cache) == n_blocks:
+            def next_use(x):
+                for j in range(i + 1, len(seq)):
+                    if seq[j] == x:
+                        return j
+                return float("inf")
+            victim = max(sorted(cache), key=next_use)      # max() keeps the first (lowest id) among equals
+            cache.remove(victim)
+            evictions += 1
+        cache.append(c)
+    return misses, evictions
+
+
+def step_access_sequence(numels, chunk_elems, chunk_id, offset):
+    """Chunks touched by one training step: parameters in order of use, then in reverse (paper Sec. 5.1)."""
+    C = chunk_elems
+    seq = []
+
+    def touch(c):
+        if not seq or seq[-1] != c:
+            seq.append(c)
+
+    spans = [(chunk_id[i], chunk_id[i] + (offset[i] + n - 1) // C) for i, n in enumerate(numels) if n > 0]
+    for a, b in spans:
+        for c in range(a, b + 1):
+            touch(c)
+    for a, b in reversed(spans):
+        for c in range(b, a - 1, -1):
+            touch(c)
+    return seq
+
+
+def chunk_size_search(numels, candidates, cache_bytes, policy=NEXT_FIT, align=1, L_c=2):
+    """(best index, replaced bytes per candidate, padding per candidate): fewest bytes replaced in the rCache in one
+    step; ties go to less padding, then to the longer chunk."""
+    replaced, padding = [], []
+    for C in candidates:
+        cid, off, valid = layout_plan(numels, C, policy, align)
+        seq = step_access_sequence(numels, C, cid, off)
+        blocks = max(1, int(cache_bytes // (L_c * C)))
+        _, ev = rcache_simulate(seq, blocks)
+        replaced.append(ev * L_c * C)
+        padding.append(len(valid) * C - sum(numels))
+    best = min(range(len(candidates)), key=lambda k: (replaced[k], padding[k], -candidates[k]))
+    return best, replaced, padding

@@ -25,6 +25,7 @@ EXPORTS = (
     "elixir_chunk_prefetch",
     "elixir_chunk_wait_ready", "elixir_chunk_evict", "elixir_host_adam_step", "elixir_host_adam_isa", "elixir_copy_h2d_async",
     "elixir_copy_d2h_async", "elixir_stream_synchronize", "elixir_offload_benefit", "elixir_offload_plan",
+    "elixir_rcache_simulate", "elixir_chunk_size_search",
 )
 
 
@@ -82,6 +83,8 @@ def lib() -> ctypes.CDLL:
         sigs["elixir_copy_d2h_async"] = [vp, vp, sz, vp]
         sigs["elixir_stream_synchronize"] = [vp]
         pd = ctypes.POINTER(ctypes.c_double)
+        sigs["elixir_rcache_simulate"] = [pi64, i64, i64, pi64, pi64]
+        sigs["elixir_chunk_size_search"] = [pi64, ci, pi64, ci, ci, i64, ctypes.c_double, ci, ctypes.POINTER(ci), pi64, pi64]
         sigs["elixir_offload_benefit"] = [ci, i64, ci, ci, ci, ctypes.POINTER(elixir_hw_profile), pd, pd]
         sigs["elixir_offload_plan"] = [ci, i64, i64, i64, ci, ci, ci, ctypes.POINTER(elixir_hw_profile), ctypes.c_double, pi64, pi64]
         L.elixir_host_adam_isa.restype = ctypes.c_char_p
@@ -304,3 +307,23 @@ def elixir_offload_plan(n_procs: int, chunk_elems: int, n_chunks: int, min_block
     _check(lib().elixir_offload_plan(n_procs, chunk_elems, n_chunks, min_blocks, L_c, L_os, F_os, ctypes.byref(hw), allowed_bytes,
                                      ctypes.byref(nb), ctypes.byref(ng)))
     return nb.value, ng.value
+
+
+# --------------------------------------------------------------------------- rCache simulation, chunk-size search
+
+def elixir_rcache_simulate(seq: Sequence[int], n_blocks: int):
+    """Returns (misses, evictions) of Belady's replacement."""
+    m, e = ctypes.c_int64(), ctypes.c_int64()
+    _check(lib().elixir_rcache_simulate(_i64_array(seq), len(seq), n_blocks, ctypes.byref(m), ctypes.byref(e)))
+    return m.value, e.value
+
+
+def elixir_chunk_size_search(numel: Sequence[int], candidates: Sequence[int], cache_bytes: float, policy: int = ELIXIR_LAYOUT_NEXT_FIT,
+                             align_elems: int = 1, L_c: int = 2):
+    """Returns (best index, replaced bytes per candidate, padding elements per candidate)."""
+    k = len(candidates)
+    best = ctypes.c_int(-1)
+    rep, pad = (ctypes.c_int64 * k)(), (ctypes.c_int64 * k)()
+    _check(lib().elixir_chunk_size_search(_i64_array(numel), len(numel), _i64_array(candidates), k, policy, align_elems, cache_bytes,
+                                          L_c, ctypes.byref(best), rep, pad))
+    return best.value, list(rep), list(pad)
