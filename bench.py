@@ -126,6 +126,15 @@ def side_rows(ex, gen, torch, cfg, C, nch, valid, state, grads, out, stream, ste
     rows["grad_reduce_first"] = {"what": "bf16 -> fp32 chunk, overwrite", "bytes": 6 * C, "GB/s": 6 * C / t / 1e9}
     t = timed(lambda: ex.elixir_grad_reduce_into_chunk(dst, 0, g16, C, 0.25, True, sh), 10)
     rows["grad_reduce_accumulate"] = {"what": "bf16 + fp32 chunk -> fp32 chunk", "bytes": 10 * C, "GB/s": 10 * C / t / 1e9}
+    # the fp16 variant of the update (same traffic: 16-bit gradient in, 16-bit copy out), with the loss-scale state on the device
+    lss = torch.zeros(4, dtype=torch.float32, device=dev)
+    ex.elixir_loss_scale_init(lss, 65536.0, sh)
+    hp16 = ex.make_hparams(cfg.lr, cfg.beta1, cfg.beta2, cfg.eps, cfg.weight_decay, 1)
+    st0 = state[0]
+    t = timed(lambda: ex.elixir_chunk_adam_step_lp(st0[0], st0[1], st0[2], None, g16, out[0], ex.ELIXIR_LOWP_FP16, C, hp16, lss[3:4],
+                                                  lss[2:3].view(torch.int32), sh), 10)
+    rows["adam_fp16_loss_scaled"] = {"what": "fp16 gradient in, fp16 copy out, grad_scale and skip flag read from the device state",
+                                     "bytes": 28 * C, "GB/s": 28 * C / t / 1e9}
     ctx = ex.elixir_ctx_create(0, C, nch)
     try:
         d_nc = torch.zeros(2, dtype=torch.float32, device=dev)
@@ -687,7 +696,7 @@ def main():
         "elements_per_s": nch * C * K / wall,
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBPS, "traffic": traffic,
-                     "kernel": "adam_multi_kernel<bf16 grad, bf16 out>" if args.multi else "adam_vec_kernel<bf16 grad, bf16 out>",
+                     "kernel": ("adam_multi_kernel" if args.multi else "adam_vec_kernel") + "<1, 1> (bf16 gradient in, bf16 copy out)",
                      "bytes_per_launch": BYTES_PER_ELEM * per_launch_elems,
                      "launch_ms": launch_s * 1e3, "launches_timed": launches,
                      "timing": "HIP events on the launch stream around the timed region / launches"},

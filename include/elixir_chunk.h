@@ -68,6 +68,12 @@ enum {
     ELIXIR_LAYOUT_DENSE = 2      /* parameters may straddle chunk boundaries */
 };
 
+/* Low-precision formats of gradients and parameter copies (16-bit patterns either way). */
+enum {
+    ELIXIR_LOWP_BF16 = 0, /* what the benchmark configurations use */
+    ELIXIR_LOWP_FP16 = 1  /* IEEE binary16, the paper's format (Sec. 2 "Mixed Precision Training") */
+};
+
 /* Per-thread message describing the last non-OK status returned on this thread ("" if none). */
 const char* elixir_last_error(void);
 
@@ -219,6 +225,43 @@ int elixir_chunk_prefetch(elixir_ctx* ctx, const void* h_block, size_t bytes, in
 int elixir_chunk_wait_ready(elixir_ctx* ctx, int slot, elixir_stream_t compute_stream);
 int elixir_chunk_evict(elixir_ctx* ctx, int slot, void* h_block, size_t bytes, elixir_stream_t compute_stream,
                        elixir_stream_t d2h_stream);
+
+/*
+ * The paper's own low-precision format, FP16 (Sec. 2 "Mixed Precision Training"), with dynamic loss scaling
+ * (Micikevicius et al., "Mixed Precision Training", which the paper cites for its set-up; the paper gives no
+ * rule of its own).  The *_lp entry points take the format as an argument and are otherwise the functions
+ * above (which are the ELIXIR_LOWP_BF16 case).
+ *   d_skip : DEVICE flag or NULL; when it is non-zero the update does nothing (master, moments and the
+ *       low-precision copy keep their values): a step skipped because the scaled gradients overflowed.
+ *   Loss-scale state, 16 bytes of DEVICE memory: scale S (the factor the caller multiplied the loss with),
+ *       good_steps, skip, grad_scale.  elixir_loss_scale_init sets S.  elixir_loss_scale_update reads the
+ *       norm of the SCALED gradients that elixir_chunk_grad_norm left in *d_norm_scaled (call it with
+ *       max_norm <= 0) and, in a one-thread kernel: if the norm is Inf/NaN sets skip = 1, grad_scale = 0,
+ *       S *= backoff_factor, good_steps = 0; otherwise skip = 0,
+ *       grad_scale = min(1, max_norm / (norm/S + 1e-6)) / S  (max_norm <= 0: 1/S), good_steps += 1 and,
+ *       when good_steps reaches growth_interval, S *= growth_factor and good_steps = 0.  Pass
+ *       &state->grad_scale and &state->skip to the update; the new S is for the next iteration.
+ */
+typedef struct {
+    float scale;
+    int32_t good_steps;
+    int32_t skip;
+    float grad_scale;
+} elixir_loss_scale_state;
+int elixir_grad_reduce_into_chunk_lp(float* d_grad_chunk, int64_t offset, const uint16_t* d_grad_lowp, int lowp_format,
+                                     int64_t n, float scale, int accumulate, elixir_stream_t stream);
+int elixir_chunk_adam_step_lp(float* d_master, float* d_exp_avg, float* d_exp_avg_sq, const float* d_grad_fp32,
+                              const uint16_t* d_grad_lowp, uint16_t* d_param_lowp, int lowp_format, int64_t n,
+                              const elixir_adam_hparams* hp, const float* d_grad_scale, const int32_t* d_skip,
+                              elixir_stream_t stream);
+int elixir_chunk_adam_step_multi_lp(int n_chunks, float* const* d_master, float* const* d_exp_avg,
+                                    float* const* d_exp_avg_sq, const float* const* d_grad_fp32,
+                                    const uint16_t* const* d_grad_lowp, uint16_t* const* d_param_lowp, int lowp_format,
+                                    const int64_t* n, const elixir_adam_hparams* hp, const float* d_grad_scale,
+                                    const int32_t* d_skip, elixir_stream_t stream);
+int elixir_loss_scale_init(elixir_loss_scale_state* d_state, float init_scale, elixir_stream_t stream);
+int elixir_loss_scale_update(elixir_loss_scale_state* d_state, const float* d_norm_scaled, float max_norm,
+                             float growth_factor, float backoff_factor, int growth_interval, elixir_stream_t stream);
 
 /*
  * CPU update of a host-resident chunk, the paper's own treatment of chunks kept in CPU memory: the

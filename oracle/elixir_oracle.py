@@ -60,8 +60,13 @@ def _L():
         L.orc_clip_coef.argtypes = [f64, f64]
         L.orc_clip_coef.restype = f64
         L.orc_chunk_adam_step.argtypes = [vp, vp, vp, vp, vp, vp, i64, f32, f32, f32, f32, f32, i64, f64]
+        L.orc_chunk_adam_step_lp.argtypes = [vp, vp, vp, vp, vp, vp, ci, i64, f32, f32, f32, f32, f32, i64, f64]
+        L.orc_grad_reduce_into_chunk_lp.argtypes = [vp, i64, vp, ci, i64, f32, ci]
+        L.orc_f16_to_f32_array.argtypes = [vp, vp, i64]
+        L.orc_f32_to_f16_array.argtypes = [vp, vp, i64]
         for n in ("orc_bf16_to_f32_array", "orc_f32_to_bf16_array", "orc_chunk_pack", "orc_chunk_unpack",
-                  "orc_grad_reduce_into_chunk", "orc_chunk_adam_step"):
+                  "orc_grad_reduce_into_chunk", "orc_chunk_adam_step", "orc_chunk_adam_step_lp", "orc_grad_reduce_into_chunk_lp",
+                  "orc_f16_to_f32_array", "orc_f32_to_f16_array"):
             getattr(L, n).restype = None
         _lib = L
     return _lib
@@ -86,6 +91,21 @@ def bf16_to_f32(bits: np.ndarray) -> np.ndarray:
 def f32_to_bf16(x: np.ndarray) -> np.ndarray:
     out = np.empty(x.shape, np.uint16)
     _L().orc_f32_to_bf16_array(_ptr(x, np.float32), out.ctypes.data, x.size)
+    return out
+
+
+BF16, FP16 = 0, 1   # low-precision formats: the benchmark's and the paper's
+
+
+def f16_to_f32(bits: np.ndarray) -> np.ndarray:
+    out = np.empty(bits.shape, np.float32)
+    _L().orc_f16_to_f32_array(_ptr(bits, np.uint16), out.ctypes.data, bits.size)
+    return out
+
+
+def f32_to_f16(x: np.ndarray) -> np.ndarray:
+    out = np.empty(x.shape, np.uint16)
+    _L().orc_f32_to_f16_array(_ptr(x, np.float32), out.ctypes.data, x.size)
     return out
 
 
@@ -203,11 +223,12 @@ def chunk_unpack(chunk: np.ndarray, tensors, offsets) -> None:
 # gradient reduction, norm, clip
 # ---------------------------------------------------------------------------
 
-def grad_reduce_into_chunk(gchunk: np.ndarray, offset: int, g_bf16: np.ndarray, scale: float, accumulate: bool) -> None:
+def grad_reduce_into_chunk(gchunk: np.ndarray, offset: int, g_bf16: np.ndarray, scale: float, accumulate: bool,
+                           fmt: int = BF16) -> None:
     if offset < 0 or offset + g_bf16.size > gchunk.size:
         raise ValueError("slice outside the chunk")
-    _L().orc_grad_reduce_into_chunk(_ptr(gchunk, np.float32), offset, _ptr(g_bf16, np.uint16), g_bf16.size,
-                                    scale, 1 if accumulate else 0)
+    _L().orc_grad_reduce_into_chunk_lp(_ptr(gchunk, np.float32), offset, _ptr(g_bf16, np.uint16), fmt, g_bf16.size,
+                                       scale, 1 if accumulate else 0)
 
 
 def sum_squares(g: np.ndarray) -> float:
@@ -228,7 +249,7 @@ def clip_coef(norm: float, max_norm: float) -> float:
 # ---------------------------------------------------------------------------
 
 def chunk_adam_step(master, exp_avg, exp_avg_sq, grad, param_bf16, *, lr, beta1, beta2, eps, weight_decay, step,
-                    grad_scale: float = 1.0) -> None:
+                    grad_scale: float = 1.0, fmt: int = BF16) -> None:
     """In-place AdamW on fp32 master/m/v; `grad` is fp32 or bf16 bits (uint16); param_bf16 (uint16) may be None."""
     n = master.size
     if exp_avg.size != n or exp_avg_sq.size != n or grad.size != n or (param_bf16 is not None and param_bf16.size != n):
@@ -240,8 +261,8 @@ def chunk_adam_step(master, exp_avg, exp_avg_sq, grad, param_bf16, *, lr, beta1,
     if g32 is None and g16 is None:
         raise TypeError("grad must be float32 or uint16 (bf16 bits)")
     out = _ptr(param_bf16, np.uint16) if param_bf16 is not None else None
-    _L().orc_chunk_adam_step(_ptr(master, np.float32), _ptr(exp_avg, np.float32), _ptr(exp_avg_sq, np.float32),
-                             g32, g16, out, n, lr, beta1, beta2, eps, weight_decay, step, float(grad_scale))
+    _L().orc_chunk_adam_step_lp(_ptr(master, np.float32), _ptr(exp_avg, np.float32), _ptr(exp_avg_sq, np.float32),
+                                g32, g16, out, fmt, n, lr, beta1, beta2, eps, weight_decay, step, float(grad_scale))
 
 
 # ---------------------------------------------------------------------------
@@ -343,3 +364,24 @@ def chunk_size_search(numels, candidates, cache_bytes, policy=NEXT_FIT, align=1,
         padding.append(len(valid) * C - sum(numels))
     best = min(range(len(candidates)), key=lambda k: (replaced[k], padding[k], -candidates[k]))
     return best, replaced, padding
+
+
+# ---------------------------------------------------------------------------
+# Dynamic loss scaling for fp16 gradients (Micikevicius et al., "Mixed Precision Training", Sec. 3.2, which the
+# paper cites for its mixed-precision set-up; the paper itself gives no rule).  The loss is multiplied by S, so
+# every gradient arrives multiplied by S.  A step whose gradients contain Inf/NaN is skipped and S shrinks;
+# after `growth_interval` clean steps in a row S grows.
+# ---------------------------------------------------------------------------
+
+def loss_scale_step(scale, good_steps, norm_scaled, max_norm, growth_factor=2.0, backoff_factor=0.5, growth_interval=2000):
+    """One step of the state machine.  norm_scaled = L2 norm of the (scaled) gradients; non-finite means overflow.
+    Returns (new_scale, new_good_steps, skip, grad_scale) where grad_scale = clip_coef / scale multiplies the
+    scaled gradients inside the update (clip_coef from the unscaled norm) and is 0 when the step is skipped."""
+    if not math.isfinite(norm_scaled):
+        return scale * backoff_factor, 0, True, 0.0
+    coef = clip_coef(norm_scaled / scale, max_norm)
+    good = good_steps + 1
+    new_scale = scale
+    if good >= growth_interval:
+        new_scale, good = scale * growth_factor, 0
+    return new_scale, good, False, coef / scale

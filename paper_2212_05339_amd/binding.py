@@ -16,6 +16,7 @@ LIB_PATH = os.path.join(_PKG, "libelixir_chunk.so")
 
 ELIXIR_OK, ELIXIR_EINVAL, ELIXIR_EALIGN, ELIXIR_ENOSLOT, ELIXIR_EHIP, ELIXIR_ESTATE, ELIXIR_ECAP = 0, -1, -2, -3, -4, -5, -6
 ELIXIR_LAYOUT_NEXT_FIT, ELIXIR_LAYOUT_FIRST_FIT, ELIXIR_LAYOUT_DENSE = 0, 1, 2
+ELIXIR_LOWP_BF16, ELIXIR_LOWP_FP16 = 0, 1
 
 EXPORTS = (
     "elixir_last_error", "elixir_ctx_create", "elixir_ctx_destroy", "elixir_layout_plan", "elixir_chunk_pack",
@@ -25,7 +26,8 @@ EXPORTS = (
     "elixir_chunk_prefetch",
     "elixir_chunk_wait_ready", "elixir_chunk_evict", "elixir_host_adam_step", "elixir_host_adam_isa", "elixir_copy_h2d_async",
     "elixir_copy_d2h_async", "elixir_stream_synchronize", "elixir_offload_benefit", "elixir_offload_plan",
-    "elixir_rcache_simulate", "elixir_chunk_size_search",
+    "elixir_rcache_simulate", "elixir_chunk_size_search", "elixir_grad_reduce_into_chunk_lp", "elixir_chunk_adam_step_lp",
+    "elixir_chunk_adam_step_multi_lp", "elixir_loss_scale_init", "elixir_loss_scale_update",
 )
 
 
@@ -83,6 +85,13 @@ def lib() -> ctypes.CDLL:
         sigs["elixir_copy_d2h_async"] = [vp, vp, sz, vp]
         sigs["elixir_stream_synchronize"] = [vp]
         pd = ctypes.POINTER(ctypes.c_double)
+        sigs["elixir_grad_reduce_into_chunk_lp"] = [vp, i64, vp, ci, i64, f32, ci, vp]
+        sigs["elixir_chunk_adam_step_lp"] = [vp, vp, vp, vp, vp, vp, ci, i64, ctypes.POINTER(elixir_adam_hparams), vp, vp, vp]
+        sigs["elixir_chunk_adam_step_multi_lp"] = [ci, ctypes.POINTER(vp), ctypes.POINTER(vp), ctypes.POINTER(vp), ctypes.POINTER(vp),
+                                                   ctypes.POINTER(vp), ctypes.POINTER(vp), ci, pi64,
+                                                   ctypes.POINTER(elixir_adam_hparams), vp, vp, vp]
+        sigs["elixir_loss_scale_init"] = [vp, f32, vp]
+        sigs["elixir_loss_scale_update"] = [vp, vp, f32, f32, f32, ci, vp]
         sigs["elixir_rcache_simulate"] = [pi64, i64, i64, pi64, pi64]
         sigs["elixir_chunk_size_search"] = [pi64, ci, pi64, ci, ci, i64, ctypes.c_double, ci, ctypes.POINTER(ci), pi64, pi64]
         sigs["elixir_offload_benefit"] = [ci, i64, ci, ci, ci, ctypes.POINTER(elixir_hw_profile), pd, pd]
@@ -327,3 +336,40 @@ def elixir_chunk_size_search(numel: Sequence[int], candidates: Sequence[int], ca
     _check(lib().elixir_chunk_size_search(_i64_array(numel), len(numel), _i64_array(candidates), k, policy, align_elems, cache_bytes,
                                           L_c, ctypes.byref(best), rep, pad))
     return best.value, list(rep), list(pad)
+
+
+# --------------------------------------------------------------------------- fp16 / loss scaling
+
+def elixir_grad_reduce_into_chunk_lp(grad_chunk, offset: int, grad_lowp, lowp_format: int, n: int, scale: float, accumulate: bool,
+                                     stream=None) -> None:
+    _check(lib().elixir_grad_reduce_into_chunk_lp(_addr(grad_chunk), offset, _addr(grad_lowp), lowp_format, n, scale,
+                                                  1 if accumulate else 0, _stream(stream)))
+
+
+def elixir_chunk_adam_step_lp(master, exp_avg, exp_avg_sq, grad_fp32, grad_lowp, param_lowp, lowp_format: int, n: int,
+                              hp: elixir_adam_hparams, d_grad_scale=None, d_skip=None, stream=None) -> None:
+    _check(lib().elixir_chunk_adam_step_lp(_addr(master), _addr(exp_avg), _addr(exp_avg_sq), _addr(grad_fp32), _addr(grad_lowp),
+                                           _addr(param_lowp), lowp_format, n, ctypes.byref(hp), _addr(d_grad_scale), _addr(d_skip),
+                                           _stream(stream)))
+
+
+def elixir_chunk_adam_step_multi_lp(master, exp_avg, exp_avg_sq, grad_fp32, grad_lowp, param_lowp, lowp_format: int, n,
+                                    hp: elixir_adam_hparams, d_grad_scale=None, d_skip=None, stream=None) -> None:
+    tab = lambda xs: None if xs is None else _ptr_array(xs)
+    _check(lib().elixir_chunk_adam_step_multi_lp(len(master), _ptr_array(master), _ptr_array(exp_avg), _ptr_array(exp_avg_sq),
+                                                 tab(grad_fp32), tab(grad_lowp), tab(param_lowp), lowp_format, _i64_array(n),
+                                                 ctypes.byref(hp), _addr(d_grad_scale), _addr(d_skip), _stream(stream)))
+
+
+LOSS_SCALE_STATE_BYTES = 16   # float scale, int32 good_steps, int32 skip, float grad_scale
+LOSS_SCALE_SKIP_OFFSET, LOSS_SCALE_GRAD_SCALE_OFFSET = 8, 12
+
+
+def elixir_loss_scale_init(d_state, init_scale: float, stream=None) -> None:
+    _check(lib().elixir_loss_scale_init(_addr(d_state), init_scale, _stream(stream)))
+
+
+def elixir_loss_scale_update(d_state, d_norm_scaled, max_norm: float, growth_factor: float = 2.0, backoff_factor: float = 0.5,
+                             growth_interval: int = 2000, stream=None) -> None:
+    _check(lib().elixir_loss_scale_update(_addr(d_state), _addr(d_norm_scaled), max_norm, growth_factor, backoff_factor,
+                                          growth_interval, _stream(stream)))

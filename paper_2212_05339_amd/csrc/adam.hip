@@ -1,4 +1,4 @@
-// elixir_chunk_adam_step: host side of the fused AdamW update.
+// elixir_chunk_adam_step and its variants: host side of the fused AdamW update.
 #include <math.h>
 
 #include "adam_kernel.hpp"
@@ -10,33 +10,75 @@ namespace {
 
 constexpr int64_t kMaxBlocksPerLaunch = 1ll << 30;  // grid.x stays far below its 2^31 limit; longer chunks take several launches
 
-// Elements [first, first + count) with the vector kernel; count is even and the pointers at `first` are aligned.
-template <bool GRAD_BF16, bool HAS_OUT>
-void launch_vec(float* p, float* m, float* v, const void* g, uint16_t* out, int64_t first, int64_t count,
-                const AdamConsts& c, const float* d_scale, hipStream_t s) {
-    const int64_t gsz = GRAD_BF16 ? 2 : 4;
-    while (count > 0) {
-        const int64_t pairs_all = count / kAdamVec;
-        int64_t blocks = (pairs_all + kAdamBlock - 1) / kAdamBlock;
-        if (blocks > kMaxBlocksPerLaunch) blocks = kMaxBlocksPerLaunch;
-        const int64_t pairs = pairs_all < blocks * kAdamBlock ? pairs_all : blocks * kAdamBlock;
-        hipLaunchKernelGGL((adam_vec_kernel<GRAD_BF16, HAS_OUT>), dim3((unsigned)blocks), dim3(kAdamBlock), kAdamLdsBytes, s,
-                           p + first, m + first, v + first, (const void*)((const char*)g + first * gsz),
-                           HAS_OUT ? out + first : nullptr, pairs, c, d_scale);
-        first += pairs * kAdamVec;
-        count -= pairs * kAdamVec;
+// One request, after validation: element kinds and raw pointers.
+struct Req {
+    float *p, *m, *v;
+    const void* g;
+    uint16_t* out;
+    int grad_kind;  // kF32 / kBF16 / kF16
+    int out_kind;   // kNone / kBF16 / kF16
+    const float* d_scale;
+    const int32_t* d_skip;
+    hipStream_t s;
+};
+
+// Calls f.template operator()<GRAD, OUT>() for the run-time (grad_kind, out_kind).
+template <typename F>
+void dispatch(int grad_kind, int out_kind, F&& f) {
+#define ELIXIR_CASE(G, O)                  \
+    if (grad_kind == G && out_kind == O) { \
+        f.template operator()<G, O>();     \
+        return;                            \
     }
+    ELIXIR_CASE(kF32, kNone)
+    ELIXIR_CASE(kF32, kBF16)
+    ELIXIR_CASE(kF32, kF16)
+    ELIXIR_CASE(kBF16, kNone)
+    ELIXIR_CASE(kBF16, kBF16)
+    ELIXIR_CASE(kF16, kNone)
+    ELIXIR_CASE(kF16, kF16)
+#undef ELIXIR_CASE
 }
 
-template <bool GRAD_BF16>
-void launch_scalar(float* p, float* m, float* v, const void* g, uint16_t* out, int64_t first, int64_t end,
-                   const AdamConsts& c, const float* d_scale, hipStream_t s) {
+int64_t grad_elem_size(int grad_kind) { return grad_kind == kF32 ? 4 : 2; }
+
+// Elements [first, first + count) with the vector kernel; count is even and the pointers at `first` are aligned.
+struct LaunchVec {
+    const Req& r;
+    int64_t first, count;
+    const AdamConsts& c;
+    template <int GRAD, int OUT>
+    void operator()() const {
+        int64_t at = first, left = count;
+        while (left > 0) {
+            const int64_t pairs_all = left / kAdamVec;
+            int64_t blocks = (pairs_all + kAdamBlock - 1) / kAdamBlock;
+            if (blocks > kMaxBlocksPerLaunch) blocks = kMaxBlocksPerLaunch;
+            const int64_t pairs = pairs_all < blocks * kAdamBlock ? pairs_all : blocks * kAdamBlock;
+            hipLaunchKernelGGL((adam_vec_kernel<GRAD, OUT>), dim3((unsigned)blocks), dim3(kAdamBlock), kAdamLdsBytes, r.s,
+                               r.p + at, r.m + at, r.v + at, (const void*)((const char*)r.g + at * grad_elem_size(GRAD)),
+                               OUT != kNone ? r.out + at : nullptr, pairs, c, r.d_scale, r.d_skip);
+            at += pairs * kAdamVec;
+            left -= pairs * kAdamVec;
+        }
+    }
+};
+
+void launch_scalar(const Req& r, int64_t first, int64_t end, const AdamConsts& c) {
     while (first < end) {
         int64_t blocks = (end - first + 255) / 256;
         if (blocks > kMaxBlocksPerLaunch) blocks = kMaxBlocksPerLaunch;
         const int64_t stop = first + blocks * 256 < end ? first + blocks * 256 : end;
-        hipLaunchKernelGGL(adam_scalar_kernel<GRAD_BF16>, dim3((unsigned)blocks), dim3(256), 0, s, p, m, v, g, out, first,
-                           stop, c, d_scale);
+        const dim3 grid((unsigned)blocks), block(256);
+        if (r.grad_kind == kBF16)
+            hipLaunchKernelGGL(adam_scalar_kernel<kBF16>, grid, block, 0, r.s, r.p, r.m, r.v, r.g, r.out, r.out_kind, first, stop, c,
+                               r.d_scale, r.d_skip);
+        else if (r.grad_kind == kF16)
+            hipLaunchKernelGGL(adam_scalar_kernel<kF16>, grid, block, 0, r.s, r.p, r.m, r.v, r.g, r.out, r.out_kind, first, stop, c,
+                               r.d_scale, r.d_skip);
+        else
+            hipLaunchKernelGGL(adam_scalar_kernel<kF32>, grid, block, 0, r.s, r.p, r.m, r.v, r.g, r.out, r.out_kind, first, stop, c,
+                               r.d_scale, r.d_skip);
         first = stop;
     }
 }
@@ -71,85 +113,126 @@ AdamConsts make_consts(const elixir_adam_hparams* hp) {
 // 0 if q sits on a boundary of two elements of size `elem`, 1 if it is one element past such a boundary
 int phase(const void* q, size_t elem) { return (int)((reinterpret_cast<uintptr_t>(q) / elem) & 1); }
 
-}  // namespace
+int lowp_kind(const char* what, int lowp_format, int* kind) {
+    if (lowp_format == ELIXIR_LOWP_BF16) *kind = kBF16;
+    else if (lowp_format == ELIXIR_LOWP_FP16) *kind = kF16;
+    else return fail(ELIXIR_EINVAL, "%s: lowp_format=%d is neither ELIXIR_LOWP_BF16 nor ELIXIR_LOWP_FP16", what, lowp_format);
+    return ELIXIR_OK;
+}
 
-extern "C" int elixir_chunk_adam_step(float* d_master, float* d_exp_avg, float* d_exp_avg_sq, const float* d_grad_fp32,
-                                      const uint16_t* d_grad_bf16, uint16_t* d_param_bf16, int64_t n,
-                                      const elixir_adam_hparams* hp, const float* d_grad_scale,
-                                      elixir_stream_t stream) {
-    static const char* what = "elixir_chunk_adam_step";
-    if (n < 0) return fail(ELIXIR_EINVAL, "%s: n=%lld is negative", what, (long long)n);
-    if (const int rc = check_hparams(what, hp)) return rc;
-    if (n == 0) return ELIXIR_OK;
-    if ((d_grad_fp32 != nullptr) == (d_grad_bf16 != nullptr))
-        return fail(ELIXIR_EINVAL, "%s: exactly one of d_grad_fp32 / d_grad_bf16 must be given", what);
-    if (!d_master || !d_exp_avg || !d_exp_avg_sq)
-        return fail(ELIXIR_EINVAL, "%s: master / exp_avg / exp_avg_sq must not be NULL", what);
-    if (!aligned(d_master, 4) || !aligned(d_exp_avg, 4) || !aligned(d_exp_avg_sq, 4) || !aligned(d_grad_fp32, 4) ||
-        !aligned(d_grad_bf16, 2) || !aligned(d_param_bf16, 2) || !aligned(d_grad_scale, 4))
-        return fail(ELIXIR_EALIGN, "%s: a pointer is not aligned for its element type", what);
-    const AdamConsts c = make_consts(hp);
-
-    hipStream_t s = (hipStream_t)stream;
-    const bool bf16 = d_grad_bf16 != nullptr;
-    const void* g = bf16 ? (const void*)d_grad_bf16 : (const void*)d_grad_fp32;
+// The single-chunk update after argument checks.
+int run_single(const Req& r, int64_t n, const AdamConsts& c) {
     // Vector path: after peeling `head` (0 or 1) elements every fp32 pointer must sit on an 8-byte and every
-    // bf16 pointer on a 4-byte boundary.  Whole chunks always do (head = 0).  Anything else, and the odd
+    // 16-bit pointer on a 4-byte boundary.  Whole chunks always do (head = 0).  Anything else, and the odd
     // elements at either end, go to the one-element-per-thread kernel, which computes the same values.
-    const int head = phase(d_master, 4);
-    const bool vec = phase(d_exp_avg, 4) == head && phase(d_exp_avg_sq, 4) == head && phase(g, bf16 ? 2 : 4) == head &&
-                     (!d_param_bf16 || phase(d_param_bf16, 2) == head);
+    const int head = phase(r.p, 4);
+    const bool vec = phase(r.m, 4) == head && phase(r.v, 4) == head && phase(r.g, (size_t)grad_elem_size(r.grad_kind)) == head &&
+                     (!r.out || phase(r.out, 2) == head);
     int64_t vec_first = 0, vec_count = 0;
     if (vec && n - head >= kAdamVec) {
         vec_first = head;
         vec_count = (n - head) / kAdamVec * kAdamVec;
-        if (bf16) {
-            if (d_param_bf16) launch_vec<true, true>(d_master, d_exp_avg, d_exp_avg_sq, g, d_param_bf16, vec_first, vec_count, c, d_grad_scale, s);
-            else launch_vec<true, false>(d_master, d_exp_avg, d_exp_avg_sq, g, nullptr, vec_first, vec_count, c, d_grad_scale, s);
-        } else {
-            if (d_param_bf16) launch_vec<false, true>(d_master, d_exp_avg, d_exp_avg_sq, g, d_param_bf16, vec_first, vec_count, c, d_grad_scale, s);
-            else launch_vec<false, false>(d_master, d_exp_avg, d_exp_avg_sq, g, nullptr, vec_first, vec_count, c, d_grad_scale, s);
-        }
+        dispatch(r.grad_kind, r.out_kind, LaunchVec{r, vec_first, vec_count, c});
         ELIXIR_LAUNCH_CHECK("adam_vec_kernel");
     }
-    // [0, vec_first) and [vec_first + vec_count, n)
     const int64_t ranges[2][2] = {{0, vec_first}, {vec_first + vec_count, n}};
-    for (const auto& r : ranges) {
-        if (r[0] >= r[1]) continue;
-        if (bf16) launch_scalar<true>(d_master, d_exp_avg, d_exp_avg_sq, g, d_param_bf16, r[0], r[1], c, d_grad_scale, s);
-        else launch_scalar<false>(d_master, d_exp_avg, d_exp_avg_sq, g, d_param_bf16, r[0], r[1], c, d_grad_scale, s);
+    for (const auto& rg : ranges) {
+        if (rg[0] >= rg[1]) continue;
+        launch_scalar(r, rg[0], rg[1], c);
         ELIXIR_LAUNCH_CHECK("adam_scalar_kernel");
     }
     return ELIXIR_OK;
 }
 
-extern "C" int elixir_chunk_adam_step_multi(int n_chunks, float* const* d_master, float* const* d_exp_avg,
-                                            float* const* d_exp_avg_sq, const float* const* d_grad_fp32,
-                                            const uint16_t* const* d_grad_bf16, uint16_t* const* d_param_bf16,
-                                            const int64_t* n, const elixir_adam_hparams* hp, const float* d_grad_scale,
-                                            elixir_stream_t stream) {
+}  // namespace
+
+extern "C" int elixir_chunk_adam_step_lp(float* d_master, float* d_exp_avg, float* d_exp_avg_sq, const float* d_grad_fp32,
+                                         const uint16_t* d_grad_lowp, uint16_t* d_param_lowp, int lowp_format, int64_t n,
+                                         const elixir_adam_hparams* hp, const float* d_grad_scale, const int32_t* d_skip,
+                                         elixir_stream_t stream) {
+    static const char* what = "elixir_chunk_adam_step";
+    if (n < 0) return fail(ELIXIR_EINVAL, "%s: n=%lld is negative", what, (long long)n);
+    if (const int rc = check_hparams(what, hp)) return rc;
+    int lk;
+    if (const int rc = lowp_kind(what, lowp_format, &lk)) return rc;
+    if (n == 0) return ELIXIR_OK;
+    if ((d_grad_fp32 != nullptr) == (d_grad_lowp != nullptr))
+        return fail(ELIXIR_EINVAL, "%s: exactly one of the fp32 and the 16-bit gradient pointer must be given", what);
+    if (!d_master || !d_exp_avg || !d_exp_avg_sq)
+        return fail(ELIXIR_EINVAL, "%s: master / exp_avg / exp_avg_sq must not be NULL", what);
+    if (!aligned(d_master, 4) || !aligned(d_exp_avg, 4) || !aligned(d_exp_avg_sq, 4) || !aligned(d_grad_fp32, 4) ||
+        !aligned(d_grad_lowp, 2) || !aligned(d_param_lowp, 2) || !aligned(d_grad_scale, 4) || !aligned(d_skip, 4))
+        return fail(ELIXIR_EALIGN, "%s: a pointer is not aligned for its element type", what);
+    Req r;
+    r.p = d_master;
+    r.m = d_exp_avg;
+    r.v = d_exp_avg_sq;
+    r.g = d_grad_lowp ? (const void*)d_grad_lowp : (const void*)d_grad_fp32;
+    r.out = d_param_lowp;
+    r.grad_kind = d_grad_lowp ? lk : kF32;
+    r.out_kind = d_param_lowp ? lk : kNone;
+    r.d_scale = d_grad_scale;
+    r.d_skip = d_skip;
+    r.s = (hipStream_t)stream;
+    return run_single(r, n, make_consts(hp));
+}
+
+extern "C" int elixir_chunk_adam_step(float* d_master, float* d_exp_avg, float* d_exp_avg_sq, const float* d_grad_fp32,
+                                      const uint16_t* d_grad_bf16, uint16_t* d_param_bf16, int64_t n,
+                                      const elixir_adam_hparams* hp, const float* d_grad_scale,
+                                      elixir_stream_t stream) {
+    return elixir_chunk_adam_step_lp(d_master, d_exp_avg, d_exp_avg_sq, d_grad_fp32, d_grad_bf16, d_param_bf16,
+                                     ELIXIR_LOWP_BF16, n, hp, d_grad_scale, nullptr, stream);
+}
+
+namespace {
+
+struct LaunchMulti {
+    const AdamMultiTable& tab;
+    dim3 grid;
+    const AdamConsts& c;
+    const float* d_scale;
+    const int32_t* d_skip;
+    hipStream_t s;
+    template <int GRAD, int OUT>
+    void operator()() const {
+        hipLaunchKernelGGL((adam_multi_kernel<GRAD, OUT>), grid, dim3(kAdamBlock), kAdamLdsBytes, s, tab, c, d_scale, d_skip);
+    }
+};
+
+}  // namespace
+
+extern "C" int elixir_chunk_adam_step_multi_lp(int n_chunks, float* const* d_master, float* const* d_exp_avg,
+                                               float* const* d_exp_avg_sq, const float* const* d_grad_fp32,
+                                               const uint16_t* const* d_grad_lowp, uint16_t* const* d_param_lowp,
+                                               int lowp_format, const int64_t* n, const elixir_adam_hparams* hp,
+                                               const float* d_grad_scale, const int32_t* d_skip, elixir_stream_t stream) {
     static const char* what = "elixir_chunk_adam_step_multi";
     if (n_chunks < 0) return fail(ELIXIR_EINVAL, "%s: n_chunks is negative", what);
     if (const int rc = check_hparams(what, hp)) return rc;
+    int lk;
+    if (const int rc = lowp_kind(what, lowp_format, &lk)) return rc;
     if (n_chunks == 0) return ELIXIR_OK;
     if (!d_master || !d_exp_avg || !d_exp_avg_sq || !n) return fail(ELIXIR_EINVAL, "%s: NULL table", what);
-    if ((d_grad_fp32 != nullptr) == (d_grad_bf16 != nullptr))
-        return fail(ELIXIR_EINVAL, "%s: exactly one of d_grad_fp32 / d_grad_bf16 must be given", what);
-    if (!aligned(d_grad_scale, 4)) return fail(ELIXIR_EALIGN, "%s: d_grad_scale not 4-byte aligned", what);
-    const bool bf16 = d_grad_bf16 != nullptr;
+    if ((d_grad_fp32 != nullptr) == (d_grad_lowp != nullptr))
+        return fail(ELIXIR_EINVAL, "%s: exactly one of the fp32 and the 16-bit gradient table must be given", what);
+    if (!aligned(d_grad_scale, 4) || !aligned(d_skip, 4)) return fail(ELIXIR_EALIGN, "%s: d_grad_scale / d_skip not 4-byte aligned", what);
+    const bool lowp_grad = d_grad_lowp != nullptr;
+    const int grad_kind = lowp_grad ? lk : kF32;
+    const int out_kind = d_param_lowp ? lk : kNone;
+    const size_t gsz = (size_t)grad_elem_size(grad_kind);
     for (int k = 0; k < n_chunks; ++k) {
         if (n[k] < 0) return fail(ELIXIR_EINVAL, "%s: n[%d] is negative", what, k);
         if (n[k] == 0) continue;
-        const void* g = bf16 ? (const void*)d_grad_bf16[k] : (const void*)d_grad_fp32[k];
+        const void* g = lowp_grad ? (const void*)d_grad_lowp[k] : (const void*)d_grad_fp32[k];
         if (!d_master[k] || !d_exp_avg[k] || !d_exp_avg_sq[k] || !g) return fail(ELIXIR_EINVAL, "%s: NULL pointer in chunk %d", what, k);
-        if (!aligned(d_master[k], 4) || !aligned(d_exp_avg[k], 4) || !aligned(d_exp_avg_sq[k], 4) || !aligned(g, bf16 ? 2 : 4) ||
-            (d_param_bf16 && !aligned(d_param_bf16[k], 2)))
+        if (!aligned(d_master[k], 4) || !aligned(d_exp_avg[k], 4) || !aligned(d_exp_avg_sq[k], 4) || !aligned(g, gsz) ||
+            (d_param_lowp && !aligned(d_param_lowp[k], 2)))
             return fail(ELIXIR_EALIGN, "%s: a pointer of chunk %d is not aligned for its element type", what, k);
-        if (d_param_bf16 && !d_param_bf16[k]) return fail(ELIXIR_EINVAL, "%s: d_param_bf16[%d] is NULL", what, k);
+        if (d_param_lowp && !d_param_lowp[k]) return fail(ELIXIR_EINVAL, "%s: the parameter-copy pointer of chunk %d is NULL", what, k);
     }
     const AdamConsts c = make_consts(hp);
     hipStream_t s = (hipStream_t)stream;
-    const bool has_out = d_param_bf16 != nullptr;
     AdamMultiTable tab;
     int in_table = 0;
     int64_t max_blocks = 0, used_blocks = 0;  // grid row length; workgroups that have work
@@ -161,14 +244,7 @@ extern "C" int elixir_chunk_adam_step_multi(int n_chunks, float* const* d_master
             tab.out[j] = nullptr;
             tab.n2[j] = 0;
         }
-        const dim3 grid((unsigned)max_blocks, (unsigned)in_table), block(kAdamBlock);
-        if (bf16) {
-            if (has_out) hipLaunchKernelGGL((adam_multi_kernel<true, true>), grid, block, kAdamLdsBytes, s, tab, c, d_grad_scale);
-            else hipLaunchKernelGGL((adam_multi_kernel<true, false>), grid, block, kAdamLdsBytes, s, tab, c, d_grad_scale);
-        } else {
-            if (has_out) hipLaunchKernelGGL((adam_multi_kernel<false, true>), grid, block, kAdamLdsBytes, s, tab, c, d_grad_scale);
-            else hipLaunchKernelGGL((adam_multi_kernel<false, false>), grid, block, kAdamLdsBytes, s, tab, c, d_grad_scale);
-        }
+        dispatch(grad_kind, out_kind, LaunchMulti{tab, dim3((unsigned)max_blocks, (unsigned)in_table), c, d_grad_scale, d_skip, s});
         ELIXIR_LAUNCH_CHECK("adam_multi_kernel");
         in_table = 0;
         max_blocks = used_blocks = 0;
@@ -176,19 +252,25 @@ extern "C" int elixir_chunk_adam_step_multi(int n_chunks, float* const* d_master
     };
     for (int k = 0; k < n_chunks; ++k) {
         if (n[k] == 0) continue;
-        const void* g = bf16 ? (const void*)d_grad_bf16[k] : (const void*)d_grad_fp32[k];
-        uint16_t* out = has_out ? d_param_bf16[k] : nullptr;
-        const int head = phase(d_master[k], 4);
-        const bool vec = head == 0 && phase(d_exp_avg[k], 4) == 0 && phase(d_exp_avg_sq[k], 4) == 0 &&
-                         phase(g, bf16 ? 2 : 4) == 0 && (!out || phase(out, 2) == 0) && n[k] >= kAdamVec;
+        Req r;
+        r.p = d_master[k];
+        r.m = d_exp_avg[k];
+        r.v = d_exp_avg_sq[k];
+        r.g = lowp_grad ? (const void*)d_grad_lowp[k] : (const void*)d_grad_fp32[k];
+        r.out = d_param_lowp ? d_param_lowp[k] : nullptr;
+        r.grad_kind = grad_kind;
+        r.out_kind = out_kind;
+        r.d_scale = d_grad_scale;
+        r.d_skip = d_skip;
+        r.s = s;
+        const bool vec = phase(r.p, 4) == 0 && phase(r.m, 4) == 0 && phase(r.v, 4) == 0 && phase(r.g, gsz) == 0 &&
+                         (!r.out || phase(r.out, 2) == 0) && n[k] >= kAdamVec;
         const int64_t pairs = vec ? n[k] / kAdamVec : 0;
         const int64_t nb = (pairs + kAdamBlock - 1) / kAdamBlock;
         if (!vec || nb > kMaxBlocksPerLaunch) {
             // a slice at an odd offset, or a chunk too long for one grid row: the single-chunk path
             if (const int rc = flush()) return rc;
-            if (const int rc = elixir_chunk_adam_step(d_master[k], d_exp_avg[k], d_exp_avg_sq[k], bf16 ? nullptr : d_grad_fp32[k],
-                                                      bf16 ? d_grad_bf16[k] : nullptr, out, n[k], hp, d_grad_scale, stream))
-                return rc;
+            if (const int rc = run_single(r, n[k], c)) return rc;
             continue;
         }
         // every chunk gets a grid row as long as the longest one: start a new launch when the table is full or
@@ -198,19 +280,96 @@ extern "C" int elixir_chunk_adam_step_multi(int n_chunks, float* const* d_master
         if (in_table == kAdamMultiMax || (in_table > 0 && wasteful))
             if (const int rc = flush()) return rc;
         const int j = in_table++;
-        tab.master[j] = d_master[k];
-        tab.exp_avg[j] = d_exp_avg[k];
-        tab.exp_avg_sq[j] = d_exp_avg_sq[k];
-        tab.grad[j] = g;
-        tab.out[j] = out;
+        tab.master[j] = r.p;
+        tab.exp_avg[j] = r.m;
+        tab.exp_avg_sq[j] = r.v;
+        tab.grad[j] = r.g;
+        tab.out[j] = r.out;
         tab.n2[j] = pairs;
         if (nb > max_blocks) max_blocks = nb;
         used_blocks += nb;
         if (n[k] % kAdamVec) {  // the odd last element of this chunk
-            if (bf16) launch_scalar<true>(d_master[k], d_exp_avg[k], d_exp_avg_sq[k], g, out, pairs * kAdamVec, n[k], c, d_grad_scale, s);
-            else launch_scalar<false>(d_master[k], d_exp_avg[k], d_exp_avg_sq[k], g, out, pairs * kAdamVec, n[k], c, d_grad_scale, s);
+            launch_scalar(r, pairs * kAdamVec, n[k], c);
             ELIXIR_LAUNCH_CHECK("adam_scalar_kernel");
         }
     }
     return flush();
+}
+
+extern "C" int elixir_chunk_adam_step_multi(int n_chunks, float* const* d_master, float* const* d_exp_avg,
+                                            float* const* d_exp_avg_sq, const float* const* d_grad_fp32,
+                                            const uint16_t* const* d_grad_bf16, uint16_t* const* d_param_bf16,
+                                            const int64_t* n, const elixir_adam_hparams* hp, const float* d_grad_scale,
+                                            elixir_stream_t stream) {
+    return elixir_chunk_adam_step_multi_lp(n_chunks, d_master, d_exp_avg, d_exp_avg_sq, d_grad_fp32, d_grad_bf16, d_param_bf16,
+                                           ELIXIR_LOWP_BF16, n, hp, d_grad_scale, nullptr, stream);
+}
+
+// ---- dynamic loss scaling (fp16 gradients) -------------------------------------------------------------------
+//
+// Loss scaling as in Micikevicius et al., "Mixed Precision Training" (the reference the paper gives for its fp16
+// set-up): the loss is multiplied by S so that small gradients survive fp16; an Inf/NaN among the gradients means
+// S was too large -- the step is skipped and S shrinks; after growth_interval clean steps S grows.  The state
+// lives in device memory and is advanced by a one-thread kernel from the norm that elixir_chunk_grad_norm left
+// there (a non-finite norm is the overflow signal: the fp64 sum of finite fp32 squares cannot overflow), so the
+// host never waits.
+
+namespace {
+
+__global__ void loss_scale_init_kernel(elixir_loss_scale_state* st, float init_scale) {
+    st->scale = init_scale;
+    st->good_steps = 0;
+    st->skip = 0;
+    st->grad_scale = 1.0f / init_scale;
+}
+
+__global__ void loss_scale_update_kernel(elixir_loss_scale_state* st, const float* d_norm_scaled, float max_norm,
+                                         float growth_factor, float backoff_factor, int growth_interval) {
+    const float norm = *d_norm_scaled;
+    const float S = st->scale;
+    if (!(fabsf(norm) <= 3.402823466e38f)) {  // Inf or NaN
+        st->scale = S * backoff_factor;
+        st->good_steps = 0;
+        st->skip = 1;
+        st->grad_scale = 0.0f;
+        return;
+    }
+    double coef = 1.0;
+    if (max_norm > 0.0f) {
+        const double r = (double)max_norm / ((double)norm / (double)S + 1e-6);
+        coef = r < 1.0 ? r : 1.0;
+    }
+    st->grad_scale = (float)(coef / (double)S);
+    st->skip = 0;
+    int good = st->good_steps + 1;
+    if (good >= growth_interval) {
+        st->scale = S * growth_factor;
+        good = 0;
+    }
+    st->good_steps = good;
+}
+
+}  // namespace
+
+extern "C" int elixir_loss_scale_init(elixir_loss_scale_state* d_state, float init_scale, elixir_stream_t stream) {
+    if (!d_state || !aligned(d_state, 4)) return fail(d_state ? ELIXIR_EALIGN : ELIXIR_EINVAL, "elixir_loss_scale_init: bad d_state");
+    if (!(init_scale > 0.0f) || !isfinite(init_scale))
+        return fail(ELIXIR_EINVAL, "elixir_loss_scale_init: init_scale must be positive and finite");
+    hipLaunchKernelGGL(loss_scale_init_kernel, dim3(1), dim3(1), 0, (hipStream_t)stream, d_state, init_scale);
+    ELIXIR_LAUNCH_CHECK("loss_scale_init_kernel");
+    return ELIXIR_OK;
+}
+
+extern "C" int elixir_loss_scale_update(elixir_loss_scale_state* d_state, const float* d_norm_scaled, float max_norm,
+                                        float growth_factor, float backoff_factor, int growth_interval,
+                                        elixir_stream_t stream) {
+    static const char* what = "elixir_loss_scale_update";
+    if (!d_state || !d_norm_scaled) return fail(ELIXIR_EINVAL, "%s: NULL pointer", what);
+    if (!aligned(d_state, 4) || !aligned(d_norm_scaled, 4)) return fail(ELIXIR_EALIGN, "%s: pointer not 4-byte aligned", what);
+    if (!(growth_factor >= 1.0f) || !(backoff_factor > 0.0f && backoff_factor <= 1.0f) || growth_interval < 1)
+        return fail(ELIXIR_EINVAL, "%s: need growth_factor >= 1, 0 < backoff_factor <= 1, growth_interval >= 1", what);
+    hipLaunchKernelGGL(loss_scale_update_kernel, dim3(1), dim3(1), 0, (hipStream_t)stream, d_state, d_norm_scaled, max_norm,
+                       growth_factor, backoff_factor, growth_interval);
+    ELIXIR_LAUNCH_CHECK("loss_scale_update_kernel");
+    return ELIXIR_OK;
 }

@@ -57,32 +57,62 @@ __device__ __forceinline__ void adam_elem(float& p, float& m, float& v, float g,
 }
 
 typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
 
-// Vector kernel: thread i owns elements 2i, 2i+1.  Host guarantees 8-byte aligned fp32
-// pointers, 4-byte aligned bf16 pointers, n2 complete pairs, gridDim.x * 128 >= n2.
-// GRAD_BF16: gradient is bf16 (else fp32).  HAS_OUT: write the bf16 parameter copy.
-template <bool GRAD_BF16, bool HAS_OUT>
-__global__ __launch_bounds__(kAdamBlock) void adam_vec_kernel(float* __restrict__ master, float* __restrict__ exp_avg,
-                                                             float* __restrict__ exp_avg_sq,
-                                                             const void* __restrict__ grad, uint16_t* __restrict__ out,
-                                                             int64_t n2, AdamConsts c,
-                                                             const float* __restrict__ d_grad_scale) {
-    const int64_t i = (int64_t)blockIdx.x * kAdamBlock + threadIdx.x;
-    if (i >= n2) return;
-    f32x2* P = reinterpret_cast<f32x2*>(master) + i;
-    f32x2* M = reinterpret_cast<f32x2*>(exp_avg) + i;
-    f32x2* V = reinterpret_cast<f32x2*>(exp_avg_sq) + i;
-    float g0, g1;
-    if constexpr (GRAD_BF16) {
+// Element kinds of the gradient input (GRAD) and of the low-precision parameter copy (OUT).
+enum { kF32 = 0, kBF16 = 1, kF16 = 2, kNone = 0 };
+
+// fp16: the hardware conversions (exact widening; round-to-nearest-even narrowing, subnormals kept).
+template <int GRAD>
+__device__ __forceinline__ void load_grad2(const void* grad, int64_t i, float& g0, float& g1) {
+    if constexpr (GRAD == kBF16) {
         const uint32_t gb = __builtin_nontemporal_load(reinterpret_cast<const uint32_t*>(grad) + i);
         g0 = bf16_bits_to_float(gb & 0xFFFFu);
         g1 = __uint_as_float(gb & 0xFFFF0000u);
+    } else if constexpr (GRAD == kF16) {
+        const uint32_t gb = __builtin_nontemporal_load(reinterpret_cast<const uint32_t*>(grad) + i);
+        const f16x2 h = __builtin_bit_cast(f16x2, gb);
+        g0 = (float)h.x;
+        g1 = (float)h.y;
     } else {
         const f32x2 gf = __builtin_nontemporal_load(reinterpret_cast<const f32x2*>(grad) + i);
         g0 = gf.x;
         g1 = gf.y;
     }
+}
+
+template <int GRAD>
+__device__ __forceinline__ float load_grad1(const void* grad, int64_t k) {
+    if constexpr (GRAD == kBF16) return bf16_bits_to_float(__builtin_nontemporal_load(reinterpret_cast<const uint16_t*>(grad) + k));
+    else if constexpr (GRAD == kF16) return (float)__builtin_bit_cast(_Float16, __builtin_nontemporal_load(reinterpret_cast<const uint16_t*>(grad) + k));
+    else return __builtin_nontemporal_load(reinterpret_cast<const float*>(grad) + k);
+}
+
+template <int OUT>
+__device__ __forceinline__ uint32_t lowp_bits(float p) {
+    if constexpr (OUT == kF16) return (uint32_t)__builtin_bit_cast(uint16_t, (_Float16)p);
+    else return bf16_rne_bits(p);
+}
+
+// The whole update of one pair of elements: shared by the single-chunk and the multi-chunk kernel.
+// A wave lives for one pair per lane, so what it waits for before its first memory instruction counts: the loads
+// are issued for every lane at once (lanes past the end re-read the last pair instead of branching on n2), and
+// the skip flag and the gradient scale are looked at only afterwards, so that all kernel-argument loads can go
+// out together instead of one dependent scalar load after the other.
+template <int GRAD, int OUT>
+__device__ __forceinline__ void adam_pair(float* master, float* exp_avg, float* exp_avg_sq, const void* grad, uint16_t* out,
+                                          int64_t i_raw, int64_t n2, const AdamConsts& c, const float* d_grad_scale,
+                                          const int32_t* d_skip) {
+    const bool live = i_raw < n2;
+    const int64_t i = live ? i_raw : n2 - 1;
+    f32x2* P = reinterpret_cast<f32x2*>(master) + i;
+    f32x2* M = reinterpret_cast<f32x2*>(exp_avg) + i;
+    f32x2* V = reinterpret_cast<f32x2*>(exp_avg_sq) + i;
+    float g0, g1;
+    load_grad2<GRAD>(grad, i, g0, g1);
     f32x2 p = __builtin_nontemporal_load(P), m = __builtin_nontemporal_load(M), v = __builtin_nontemporal_load(V);
+    if (!live) return;
+    if (d_skip && *d_skip) return;
     if (d_grad_scale) {
         const float gs = *d_grad_scale;
         g0 *= gs;
@@ -94,8 +124,23 @@ __global__ __launch_bounds__(kAdamBlock) void adam_vec_kernel(float* __restrict_
     __builtin_nontemporal_store(f32x2{p0, p1}, P);
     __builtin_nontemporal_store(f32x2{m0, m1}, M);
     __builtin_nontemporal_store(f32x2{v0, v1}, V);
-    if constexpr (HAS_OUT)
-        __builtin_nontemporal_store(bf16_rne_bits(p0) | (bf16_rne_bits(p1) << 16), reinterpret_cast<uint32_t*>(out) + i);
+    if constexpr (OUT != kNone)
+        __builtin_nontemporal_store(lowp_bits<OUT>(p0) | (lowp_bits<OUT>(p1) << 16), reinterpret_cast<uint32_t*>(out) + i);
+}
+
+// Vector kernel: thread i owns elements 2i, 2i+1.  Host guarantees 8-byte aligned fp32
+// pointers, 4-byte aligned 16-bit pointers, n2 >= 1 complete pairs, gridDim.x * 128 >= n2.
+// d_skip (may be NULL): a device flag; when it is non-zero the launch changes nothing (a step
+// skipped because of overflowed fp16 gradients).
+template <int GRAD, int OUT>
+__global__ __launch_bounds__(kAdamBlock) void adam_vec_kernel(float* __restrict__ master, float* __restrict__ exp_avg,
+                                                             float* __restrict__ exp_avg_sq,
+                                                             const void* __restrict__ grad, uint16_t* __restrict__ out,
+                                                             int64_t n2, AdamConsts c,
+                                                             const float* __restrict__ d_grad_scale,
+                                                             const int32_t* __restrict__ d_skip) {
+    const int64_t i = (int64_t)blockIdx.x * kAdamBlock + threadIdx.x;
+    adam_pair<GRAD, OUT>(master, exp_avg, exp_avg_sq, grad, out, i, n2, c, d_grad_scale, d_skip);
 }
 
 // Several chunks in one launch (same step constants for all).  The table travels as a kernel argument.
@@ -112,51 +157,28 @@ struct AdamMultiTable {
     int64_t n2[kAdamMultiMax];             // complete pairs per chunk
 };
 
-template <bool GRAD_BF16, bool HAS_OUT>
+template <int GRAD, int OUT>
 __global__ __launch_bounds__(kAdamBlock) void adam_multi_kernel(AdamMultiTable tab, AdamConsts c,
-                                                               const float* __restrict__ d_grad_scale) {
+                                                               const float* __restrict__ d_grad_scale,
+                                                               const int32_t* __restrict__ d_skip) {
     const int lo = blockIdx.y;
+    const int64_t n2 = tab.n2[lo];
+    if ((int64_t)blockIdx.x * kAdamBlock >= n2) return;  // a row past the end of a shorter chunk (uniform per workgroup)
     const int64_t i = (int64_t)blockIdx.x * kAdamBlock + threadIdx.x;
-    if (i >= tab.n2[lo]) return;
-    f32x2* P = reinterpret_cast<f32x2*>(tab.master[lo]) + i;
-    f32x2* M = reinterpret_cast<f32x2*>(tab.exp_avg[lo]) + i;
-    f32x2* V = reinterpret_cast<f32x2*>(tab.exp_avg_sq[lo]) + i;
-    float g0, g1;
-    if constexpr (GRAD_BF16) {
-        const uint32_t gb = __builtin_nontemporal_load(reinterpret_cast<const uint32_t*>(tab.grad[lo]) + i);
-        g0 = bf16_bits_to_float(gb & 0xFFFFu);
-        g1 = __uint_as_float(gb & 0xFFFF0000u);
-    } else {
-        const f32x2 gf = __builtin_nontemporal_load(reinterpret_cast<const f32x2*>(tab.grad[lo]) + i);
-        g0 = gf.x;
-        g1 = gf.y;
-    }
-    f32x2 p = __builtin_nontemporal_load(P), m = __builtin_nontemporal_load(M), v = __builtin_nontemporal_load(V);
-    if (d_grad_scale) {
-        const float gs = *d_grad_scale;
-        g0 *= gs;
-        g1 *= gs;
-    }
-    float p0 = p.x, m0 = m.x, v0 = v.x, p1 = p.y, m1 = m.y, v1 = v.y;
-    adam_elem(p0, m0, v0, g0, c);
-    adam_elem(p1, m1, v1, g1, c);
-    __builtin_nontemporal_store(f32x2{p0, p1}, P);
-    __builtin_nontemporal_store(f32x2{m0, m1}, M);
-    __builtin_nontemporal_store(f32x2{v0, v1}, V);
-    if constexpr (HAS_OUT)
-        __builtin_nontemporal_store(bf16_rne_bits(p0) | (bf16_rne_bits(p1) << 16), reinterpret_cast<uint32_t*>(tab.out[lo]) + i);
+    adam_pair<GRAD, OUT>(tab.master[lo], tab.exp_avg[lo], tab.exp_avg_sq[lo], tab.grad[lo], tab.out[lo], i, n2, c, d_grad_scale, d_skip);
 }
 
 // Scalar kernel: elements [first, n), any alignment, one element per thread.  Same arithmetic.
-template <bool GRAD_BF16>
+// out_kind: kNone / kBF16 / kF16 (run-time: this kernel only sees odd ends and misaligned slices).
+template <int GRAD>
 __global__ __launch_bounds__(256) void adam_scalar_kernel(float* master, float* exp_avg, float* exp_avg_sq,
-                                                         const void* grad, uint16_t* out, int64_t first, int64_t n,
-                                                         AdamConsts c, const float* d_grad_scale) {
+                                                         const void* grad, uint16_t* out, int out_kind, int64_t first,
+                                                         int64_t n, AdamConsts c, const float* d_grad_scale,
+                                                         const int32_t* d_skip) {
     const int64_t k = first + (int64_t)blockIdx.x * 256 + threadIdx.x;
     if (k >= n) return;
-    float g;
-    if constexpr (GRAD_BF16) g = bf16_bits_to_float(__builtin_nontemporal_load(reinterpret_cast<const uint16_t*>(grad) + k));
-    else g = __builtin_nontemporal_load(reinterpret_cast<const float*>(grad) + k);
+    if (d_skip && *d_skip) return;
+    float g = load_grad1<GRAD>(grad, k);
     float p = __builtin_nontemporal_load(master + k), m = __builtin_nontemporal_load(exp_avg + k),
           v = __builtin_nontemporal_load(exp_avg_sq + k);
     if (d_grad_scale) g *= *d_grad_scale;
@@ -164,7 +186,8 @@ __global__ __launch_bounds__(256) void adam_scalar_kernel(float* master, float* 
     __builtin_nontemporal_store(p, master + k);
     __builtin_nontemporal_store(m, exp_avg + k);
     __builtin_nontemporal_store(v, exp_avg_sq + k);
-    if (out) __builtin_nontemporal_store((uint16_t)bf16_rne_bits(p), out + k);
+    if (out_kind == kBF16) __builtin_nontemporal_store((uint16_t)bf16_rne_bits(p), out + k);
+    else if (out_kind == kF16) __builtin_nontemporal_store((uint16_t)lowp_bits<kF16>(p), out + k);
 }
 
 }  // namespace elixir

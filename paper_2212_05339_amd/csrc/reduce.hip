@@ -14,8 +14,16 @@ namespace {
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
-__device__ __forceinline__ float reduce_elem(float old, uint32_t bf16_bits, float scale) {
-    const float t = scale * __uint_as_float(bf16_bits << 16);
+// 16 gradient bits -> fp32: bf16 is the upper half of an fp32 pattern; fp16 takes the hardware conversion (exact).
+template <bool FP16>
+__device__ __forceinline__ float widen(uint32_t bits16) {
+    if constexpr (FP16) return (float)__builtin_bit_cast(_Float16, (uint16_t)bits16);
+    else return __uint_as_float(bits16 << 16);
+}
+
+template <bool FP16>
+__device__ __forceinline__ float reduce_elem(float old, uint32_t bits16, float scale) {
+    const float t = scale * widen<FP16>(bits16);
     return old + t;
 }
 
@@ -26,7 +34,7 @@ constexpr int kVecBlock = 128;  // one 4-element group per thread, one workgroup
 constexpr int64_t kMaxBlocksPerLaunch = 1ll << 30;
 
 // dst 16-byte aligned, src 8-byte aligned; n4 complete groups of 4 elements.
-template <bool ACC>
+template <bool ACC, bool FP16>
 __global__ __launch_bounds__(kVecBlock) void reduce_vec_kernel(float* __restrict__ dst, const uint16_t* __restrict__ src,
                                                               int64_t n4, float scale) {
     const int64_t i = (int64_t)blockIdx.x * kVecBlock + threadIdx.x;
@@ -37,56 +45,77 @@ __global__ __launch_bounds__(kVecBlock) void reduce_vec_kernel(float* __restrict
     if constexpr (ACC) a = __builtin_nontemporal_load(D);
     else a = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
     f32x4 r;
-    r.x = reduce_elem(a.x, g.x & 0xFFFFu, scale);
-    r.y = reduce_elem(a.y, g.x >> 16, scale);
-    r.z = reduce_elem(a.z, g.y & 0xFFFFu, scale);
-    r.w = reduce_elem(a.w, g.y >> 16, scale);
+    r.x = reduce_elem<FP16>(a.x, g.x & 0xFFFFu, scale);
+    r.y = reduce_elem<FP16>(a.y, g.x >> 16, scale);
+    r.z = reduce_elem<FP16>(a.z, g.y & 0xFFFFu, scale);
+    r.w = reduce_elem<FP16>(a.w, g.y >> 16, scale);
     __builtin_nontemporal_store(r, D);
 }
 
 // elements [first, n), any alignment
-template <bool ACC>
+template <bool ACC, bool FP16>
 __global__ __launch_bounds__(256) void reduce_scalar_kernel(float* dst, const uint16_t* src, int64_t first, int64_t n,
                                                            float scale) {
     const int64_t k = first + (int64_t)blockIdx.x * 256 + threadIdx.x;
-    if (k < n) dst[k] = reduce_elem(ACC ? dst[k] : 0.0f, src[k], scale);
+    if (k < n) dst[k] = reduce_elem<FP16>(ACC ? dst[k] : 0.0f, src[k], scale);
 }
 
 }  // namespace
 
-extern "C" int elixir_grad_reduce_into_chunk(float* d_grad_chunk, int64_t offset, const uint16_t* d_grad_bf16, int64_t n,
-                                             float scale, int accumulate, elixir_stream_t stream) {
-    if (n < 0 || offset < 0)
-        return fail(ELIXIR_EINVAL, "elixir_grad_reduce_into_chunk: n=%lld, offset=%lld must not be negative",
-                    (long long)n, (long long)offset);
-    if (n == 0) return ELIXIR_OK;
-    if (!d_grad_chunk || !d_grad_bf16) return fail(ELIXIR_EINVAL, "elixir_grad_reduce_into_chunk: NULL pointer");
-    if (!aligned(d_grad_chunk, 4) || !aligned(d_grad_bf16, 2))
-        return fail(ELIXIR_EALIGN, "elixir_grad_reduce_into_chunk: a pointer is not aligned for its element type");
-    hipStream_t s = (hipStream_t)stream;
-    float* dst = d_grad_chunk + offset;
+namespace {
+
+template <bool ACC, bool FP16>
+void launch_reduce(float* dst, const uint16_t* src, int64_t n, float scale, hipStream_t s) {
     int64_t done = 0;
-    if (aligned(dst, 16) && aligned(d_grad_bf16, 8) && n >= 4) {
-        int64_t n4 = n / 4, at = 0;
+    if (aligned(dst, 16) && aligned(src, 8) && n >= 4) {
+        const int64_t n4 = n / 4;
+        int64_t at = 0;
         while (at < n4) {
             int64_t blocks = (n4 - at + kVecBlock - 1) / kVecBlock;
             if (blocks > kMaxBlocksPerLaunch) blocks = kMaxBlocksPerLaunch;
             const int64_t cnt = n4 - at < blocks * kVecBlock ? n4 - at : blocks * kVecBlock;
-            if (accumulate) hipLaunchKernelGGL(reduce_vec_kernel<true>, dim3((unsigned)blocks), dim3(kVecBlock), 0, s, dst + at * 4, d_grad_bf16 + at * 4, cnt, scale);
-            else hipLaunchKernelGGL(reduce_vec_kernel<false>, dim3((unsigned)blocks), dim3(kVecBlock), 0, s, dst + at * 4, d_grad_bf16 + at * 4, cnt, scale);
+            hipLaunchKernelGGL((reduce_vec_kernel<ACC, FP16>), dim3((unsigned)blocks), dim3(kVecBlock), 0, s, dst + at * 4, src + at * 4, cnt, scale);
             at += cnt;
         }
-        ELIXIR_LAUNCH_CHECK("reduce_vec_kernel");
         done = n4 * 4;
     }
     while (done < n) {
         int64_t blocks = (n - done + 255) / 256;
         if (blocks > kMaxBlocksPerLaunch) blocks = kMaxBlocksPerLaunch;
         const int64_t stop = done + blocks * 256 < n ? done + blocks * 256 : n;
-        if (accumulate) hipLaunchKernelGGL(reduce_scalar_kernel<true>, dim3((unsigned)blocks), dim3(256), 0, s, dst, d_grad_bf16, done, stop, scale);
-        else hipLaunchKernelGGL(reduce_scalar_kernel<false>, dim3((unsigned)blocks), dim3(256), 0, s, dst, d_grad_bf16, done, stop, scale);
-        ELIXIR_LAUNCH_CHECK("reduce_scalar_kernel");
+        hipLaunchKernelGGL((reduce_scalar_kernel<ACC, FP16>), dim3((unsigned)blocks), dim3(256), 0, s, dst, src, done, stop, scale);
         done = stop;
     }
+}
+
+}  // namespace
+
+extern "C" int elixir_grad_reduce_into_chunk_lp(float* d_grad_chunk, int64_t offset, const uint16_t* d_grad_lowp, int lowp_format,
+                                                int64_t n, float scale, int accumulate, elixir_stream_t stream) {
+    static const char* what = "elixir_grad_reduce_into_chunk";
+    if (n < 0 || offset < 0)
+        return fail(ELIXIR_EINVAL, "%s: n=%lld, offset=%lld must not be negative", what, (long long)n, (long long)offset);
+    if (lowp_format != ELIXIR_LOWP_BF16 && lowp_format != ELIXIR_LOWP_FP16)
+        return fail(ELIXIR_EINVAL, "%s: lowp_format=%d is neither ELIXIR_LOWP_BF16 nor ELIXIR_LOWP_FP16", what, lowp_format);
+    if (n == 0) return ELIXIR_OK;
+    if (!d_grad_chunk || !d_grad_lowp) return fail(ELIXIR_EINVAL, "%s: NULL pointer", what);
+    if (!aligned(d_grad_chunk, 4) || !aligned(d_grad_lowp, 2))
+        return fail(ELIXIR_EALIGN, "%s: a pointer is not aligned for its element type", what);
+    hipStream_t s = (hipStream_t)stream;
+    float* dst = d_grad_chunk + offset;
+    const bool f16 = lowp_format == ELIXIR_LOWP_FP16;
+    if (accumulate) {
+        if (f16) launch_reduce<true, true>(dst, d_grad_lowp, n, scale, s);
+        else launch_reduce<true, false>(dst, d_grad_lowp, n, scale, s);
+    } else {
+        if (f16) launch_reduce<false, true>(dst, d_grad_lowp, n, scale, s);
+        else launch_reduce<false, false>(dst, d_grad_lowp, n, scale, s);
+    }
+    ELIXIR_LAUNCH_CHECK("reduce kernel");
     return ELIXIR_OK;
+}
+
+extern "C" int elixir_grad_reduce_into_chunk(float* d_grad_chunk, int64_t offset, const uint16_t* d_grad_bf16, int64_t n,
+                                             float scale, int accumulate, elixir_stream_t stream) {
+    return elixir_grad_reduce_into_chunk_lp(d_grad_chunk, offset, d_grad_bf16, ELIXIR_LOWP_BF16, n, scale, accumulate, stream);
 }

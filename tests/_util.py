@@ -56,14 +56,16 @@ def check_adam_close(got_p, got_m, got_v, ref_p, ref_m, ref_v, *, lr, gmax, step
     return out
 
 
-def check_bf16_copy(got_bits, got_p, ref_bits, ref_p, *, lr, steps=1, what=""):
-    """The low-precision copy: (a) it is exactly the round-to-nearest-even bf16 of the fp32 master the GPU
-    stored (checked bit for bit with the oracle's rounding); (b) it is within one bf16 ulp of the oracle's
-    copy wherever |p| is large enough for an ulp to exceed the fp32 tolerance (|p| > 1e-3 * steps * lr; below
-    that the master weight is a cancellation residue and only (a) and the fp32 bound apply)."""
-    own = orc.f32_to_bf16(np.ascontiguousarray(got_p))
-    assert np.array_equal(got_bits, own), f"{what}: bf16 copy is not the RNE rounding of the stored master weight"
-    big = np.abs(ref_p) > 1e-3 * steps * lr
+def check_bf16_copy(got_bits, got_p, ref_bits, ref_p, *, lr, steps=1, what="", fmt=0):
+    """The low-precision copy (fmt 0 = bf16, 1 = fp16): (a) it is exactly the round-to-nearest-even rounding of the fp32
+    master the GPU stored (checked bit for bit with the oracle's rounding); (b) it is within one low-precision ulp of
+    the oracle's copy wherever |p| is large enough for an ulp to exceed the fp32 tolerance (below that the master
+    weight is a cancellation residue and only (a) and the fp32 bound apply)."""
+    conv = orc.f32_to_f16 if fmt else orc.f32_to_bf16
+    own = conv(np.ascontiguousarray(got_p))
+    finite = np.isfinite(got_p)
+    assert np.array_equal(got_bits[finite], own[finite]), f"{what}: low-precision copy is not the RNE rounding of the stored master weight"
+    big = np.abs(ref_p) > (1e-2 if fmt else 1e-3) * steps * lr
     d = np.abs(sign_magnitude(got_bits[big]) - sign_magnitude(ref_bits[big]))
-    assert d.max(initial=0) <= 1, f"{what}: bf16 copy differs by {int(d.max())} ulp"
+    assert d.max(initial=0) <= 1, f"{what}: low-precision copy differs by {int(d.max())} ulp"
     return float((got_bits == ref_bits).mean()) if got_bits.size else 1.0

@@ -1,0 +1,199 @@
+"""GPU parity of the fp16 variants (the paper's low-precision format) and of dynamic loss scaling."""
+import numpy as np
+import pytest
+
+import paper_2212_05339_amd as ex
+from oracle import elixir_oracle as orc
+from synth import gen
+from tests._util import HP, check_adam_close, check_bf16_copy
+
+torch = pytest.importorskip("torch")
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+F16 = ex.ELIXIR_LOWP_FP16
+
+
+def dev(a):
+    if a.dtype == np.uint16:
+        return torch.from_numpy(a.view(np.int16).copy()).to(DEV)
+    return torch.from_numpy(a.copy()).to(DEV)
+
+
+def host(t, dtype=None):
+    a = t.detach().cpu().numpy()
+    return a.view(dtype) if dtype is not None else a
+
+
+def hp_struct(step):
+    return ex.make_hparams(HP["lr"], HP["beta1"], HP["beta2"], HP["eps"], HP["weight_decay"], step)
+
+
+def f16_grads(key, n, std, scale=1.0):
+    """fp16 patterns of seeded gradients multiplied by the loss scale (rounded by numpy's IEEE float16)."""
+    x = gen.fill_f32(key, 0, n, std, zero_pct=1) * np.float32(scale)
+    with np.errstate(over="ignore"):
+        return x.astype(np.float16).view(np.uint16)
+
+
+def state(n, seed):
+    p = gen.fill_f32(gen.stream_key(seed, gen.TAG_PARAM), 0, n, 0.02)
+    m = gen.fill_f32(gen.stream_key(seed, gen.TAG_MOMENT, 0), 0, n, 3e-4)
+    v = np.square(np.abs(m) + np.abs(gen.fill_f32(gen.stream_key(seed, gen.TAG_MOMENT, 1), 0, n, 1e-3)))
+    return p, m, v
+
+
+@pytest.mark.parametrize("scale", [1.0, 0.25, 0.3])
+def test_reduce_fp16_bit_exact_all_patterns_and_ragged(scale):
+    bits = np.arange(65536, dtype=np.uint16)
+    want = np.zeros(65536, np.float32)
+    d_g = dev(np.ones(65536, np.float32))
+    for acc in (False, True):
+        orc.grad_reduce_into_chunk(want, 0, bits, scale, acc, fmt=orc.FP16)
+        ex.elixir_grad_reduce_into_chunk_lp(d_g, 0, dev(bits), F16, 65536, scale, acc)
+    torch.cuda.synchronize()
+    got = host(d_g)
+    nan = np.isnan(want)
+    assert np.array_equal(np.isnan(got), nan) and np.array_equal(got[~nan].view(np.uint32), want[~nan].view(np.uint32))
+    for n, off in ((1, 0), (5, 3), (300_001, 7)):
+        g = f16_grads(gen.stream_key(70, gen.TAG_GRAD, 1), n, 1e-3, 1024.0)
+        ref = np.full(off + n + 5, -2.5, np.float32)
+        d = dev(ref)
+        for mb in range(3):
+            orc.grad_reduce_into_chunk(ref, off, g, scale, mb > 0, fmt=orc.FP16)
+            ex.elixir_grad_reduce_into_chunk_lp(d, off, dev(g), F16, n, scale, mb > 0)
+        torch.cuda.synchronize()
+        assert np.array_equal(host(d).view(np.uint32), ref.view(np.uint32))
+
+
+@pytest.mark.parametrize("n,shift", [(0, 0), (1, 0), (5, 0), (4096 * 3 + 2, 0), (70_001, 1), (1_000_003, 0)])
+def test_adam_fp16_matches_oracle(n, shift):
+    S = 1024.0
+    p, m, v = state(n + 8, 71)
+    g = f16_grads(gen.stream_key(71, gen.TAG_GRAD, 2), n + 8, 1e-3, S)
+    d_p, d_m, d_v, d_g = dev(p), dev(m), dev(v), dev(g)
+    d_out = torch.zeros(n + 8, dtype=torch.int16, device=DEV)
+    d_scale = dev(np.array([1.0 / S], np.float32))
+    s = slice(shift, shift + n)
+    ex.elixir_chunk_adam_step_lp(d_p[s], d_m[s], d_v[s], None, d_g[s], d_out[s], F16, n, hp_struct(4), d_scale, None)
+    torch.cuda.synchronize()
+    rp, rm, rv, ro = p.copy(), m.copy(), v.copy(), np.zeros(n + 8, np.uint16)
+    if n:
+        orc.chunk_adam_step(rp[s], rm[s], rv[s], np.ascontiguousarray(g[s]), ro[s], step=4, grad_scale=1.0 / S, fmt=orc.FP16, **HP)
+    check_adam_close(host(d_p), host(d_m), host(d_v), rp, rm, rv, lr=HP["lr"], gmax=5e-3, what=f"fp16 n={n}")
+    check_bf16_copy(host(d_out, np.uint16)[s], host(d_p)[s], ro[s], rp[s], lr=HP["lr"], fmt=1)
+    assert not host(d_out, np.uint16)[shift + n:].any()
+
+
+def test_adam_fp16_copy_exhaustive_rounding():
+    """Every fp16 value and the midpoints between neighbours as master weights: with zero gradient, moments and decay the
+    update leaves p alone, so the copy is the rounding of p itself."""
+    bits = np.arange(0x7C00, dtype=np.uint16)                            # all finite non-negative fp16
+    vals = orc.f16_to_f32(bits).astype(np.float64)
+    mids = ((vals[:-1] + vals[1:]) / 2).astype(np.float32)               # exact in fp32
+    p = np.concatenate([vals.astype(np.float32), mids, -mids, np.array([65519.0, 65520.0, 7e4, 1e-8, 3e-8], np.float32)])
+    n = p.size
+    d_p = dev(p)
+    z = torch.zeros(2, n, dtype=torch.float32, device=DEV)
+    zg = torch.zeros(n, dtype=torch.int16, device=DEV)
+    out = torch.zeros(n, dtype=torch.int16, device=DEV)
+    hp = ex.make_hparams(1e-4, 0.9, 0.999, 1e-8, 0.0, 1)
+    ex.elixir_chunk_adam_step_lp(d_p, z[0], z[1], None, zg, out, F16, n, hp, None, None)
+    torch.cuda.synchronize()
+    assert np.array_equal(host(d_p).view(np.uint32), p.view(np.uint32))
+    assert np.array_equal(host(out, np.uint16), orc.f32_to_f16(p))
+
+
+def test_skip_flag_leaves_everything_untouched():
+    n = 100_001
+    p, m, v = state(n, 72)
+    g = f16_grads(gen.stream_key(72, gen.TAG_GRAD, 1), n, 1e-3, 64.0)
+    d_p, d_m, d_v, d_g = dev(p), dev(m), dev(v), dev(g)
+    d_out = torch.full((n,), 77, dtype=torch.int16, device=DEV)
+    flag = torch.ones(1, dtype=torch.int32, device=DEV)
+    ex.elixir_chunk_adam_step_lp(d_p, d_m, d_v, None, d_g, d_out, F16, n, hp_struct(1), None, flag)
+    ex.elixir_chunk_adam_step_multi_lp([d_p[:50_000], d_p[50_000:]], [d_m[:50_000], d_m[50_000:]], [d_v[:50_000], d_v[50_000:]], None,
+                                       [d_g[:50_000], d_g[50_000:]], [d_out[:50_000], d_out[50_000:]], F16, [50_000, n - 50_000],
+                                       hp_struct(1), None, flag)
+    torch.cuda.synchronize()
+    for got, ref in ((d_p, p), (d_m, m), (d_v, v)):
+        assert np.array_equal(host(got).view(np.uint32), ref.view(np.uint32))
+    assert np.all(host(d_out) == 77)
+    flag.zero_()
+    ex.elixir_chunk_adam_step_lp(d_p, d_m, d_v, None, d_g, d_out, F16, n, hp_struct(1), None, flag)
+    torch.cuda.synchronize()
+    assert not np.array_equal(host(d_p), p)
+
+
+def test_loss_scale_state_machine_on_device_matches_oracle():
+    st = torch.zeros(4, dtype=torch.float32, device=DEV)
+    norm = torch.zeros(1, dtype=torch.float32, device=DEV)
+    ex.elixir_loss_scale_init(st, 8.0)
+    s, good = 8.0, 0
+    for nv, max_norm in ((3.0, 1.0), (100.0, 1.0), (2.0, 0.0), (float("inf"), 1.0), (float("nan"), 1.0), (1.0, 5.0), (4.0, 1.0), (4.0, 1.0),
+                         (4.0, 1.0), (4.0, 1.0)):
+        norm.fill_(nv)
+        ex.elixir_loss_scale_update(st, norm, max_norm, 2.0, 0.5, 3)
+        torch.cuda.synchronize()
+        raw = st.cpu().numpy()
+        s, good, skip, gs = orc.loss_scale_step(s, good, nv, max_norm, 2.0, 0.5, 3)
+        assert float(raw[0]) == s and int(raw.view(np.int32)[1]) == good and int(raw.view(np.int32)[2]) == int(skip)
+        assert float(raw[3]) == pytest.approx(gs, rel=1e-6)
+    for bad in (lambda: ex.elixir_loss_scale_init(st, 0.0), lambda: ex.elixir_loss_scale_update(st, norm, 1.0, 0.5, 0.5, 3),
+                lambda: ex.elixir_loss_scale_update(st, norm, 1.0, 2.0, 0.5, 0), lambda: ex.elixir_loss_scale_update(st, None, 1.0, 2.0, 0.5, 3)):
+        with pytest.raises(ex.ElixirError) as e:
+            bad()
+        assert e.value.code == ex.ELIXIR_EINVAL
+
+
+def test_fp16_training_steps_with_loss_scaling_end_to_end():
+    """Three iterations of the fp16 pipeline on 3 chunks: scaled fp16 gradients (2 micro-batches) -> fp32 chunks -> norm of the
+    scaled gradients -> loss-scale update (clip to max-norm 1) -> AdamW reading grad_scale and skip from the device state.
+    The second iteration carries an Inf and must be skipped; the scale halves; the third runs with the smaller scale."""
+    C, nch, K = 200_003, 3, 2
+    ctx = ex.elixir_ctx_create(0, C, nch)
+    try:
+        st = torch.zeros(4, dtype=torch.float32, device=DEV)
+        ex.elixir_loss_scale_init(st, 4096.0)
+        d_norm = torch.zeros(1, dtype=torch.float32, device=DEV)
+        p = np.stack([gen.fill_f32(gen.stream_key(80, gen.TAG_PARAM), c * C, C, 0.02) for c in range(nch)])
+        rm, rv = np.zeros_like(p), np.zeros_like(p)
+        d_p, d_m, d_v = dev(p), torch.zeros(nch, C, device=DEV), torch.zeros(nch, C, device=DEV)
+        d_g = torch.zeros(nch, C, dtype=torch.float32, device=DEV)
+        d_out = torch.zeros(nch, C, dtype=torch.int16, device=DEV)
+        ro = np.zeros((nch, C), np.uint16)
+        S, good, steps_done = 4096.0, 0, 0
+        for it in range(3):
+            ref_g = np.zeros((nch, C), np.float32)
+            for mb in range(K):
+                for c in range(nch):
+                    g = f16_grads(gen.stream_key(80, gen.TAG_GRAD, it, mb), C, 0.05, S)
+                    if it == 1 and mb == 1 and c == 2:
+                        g[12345] = 0x7C00                                   # +Inf: the scaled gradient overflowed
+                    ex.elixir_grad_reduce_into_chunk_lp(d_g[c], 0, dev(g), F16, C, 1.0 / K, mb > 0)
+                    orc.grad_reduce_into_chunk(ref_g[c], 0, g, 1.0 / K, mb > 0, fmt=orc.FP16)
+            ex.elixir_chunk_grad_norm(ctx, [d_g[c] for c in range(nch)], [C] * nch, 0.0, d_norm, None)
+            ex.elixir_loss_scale_update(st, d_norm, 1.0, 2.0, 0.5, 2000)
+            hp = hp_struct(steps_done + 1)
+            for c in range(nch):
+                ex.elixir_chunk_adam_step_lp(d_p[c], d_m[c], d_v[c], d_g[c], None, d_out[c], F16, C, hp, st[3:4], st[2:3].view(torch.int32))
+            torch.cuda.synchronize()
+            assert np.array_equal(host(d_g).view(np.uint32)[np.isfinite(ref_g)], ref_g.view(np.uint32)[np.isfinite(ref_g)])
+            norm = orc.grad_norm([ref_g[c] for c in range(nch)], [C] * nch)
+            S_used = S
+            S, good, skip, gs = orc.loss_scale_step(S, good, norm, 1.0, 2.0, 0.5, 2000)
+            raw = st.cpu().numpy()
+            assert float(raw[0]) == S and int(raw.view(np.int32)[2]) == int(skip)
+            assert skip == (it == 1)
+            if not skip:
+                assert float(host(d_norm)[0]) == pytest.approx(norm, rel=1e-5)
+                assert float(raw[3]) == pytest.approx(gs, rel=1e-5)
+                gpu_gs = float(raw[3])
+                for c in range(nch):
+                    orc.chunk_adam_step(p[c], rm[c], rv[c], ref_g[c], ro[c], step=steps_done + 1, grad_scale=gpu_gs, fmt=orc.FP16, **HP)
+                steps_done += 1
+                assert norm / S_used > 1.0                                  # clipping was active
+            check_adam_close(host(d_p), host(d_m), host(d_v), p, rm, rv, lr=HP["lr"], gmax=0.2 / 30, steps=max(1, steps_done), what=f"iteration {it}")
+            check_bf16_copy(host(d_out, np.uint16).ravel(), host(d_p).ravel(), ro.ravel(), p.ravel(), lr=HP["lr"], steps=max(1, steps_done), fmt=1)
+        assert steps_done == 2 and S == 2048.0
+    finally:
+        ex.elixir_ctx_destroy(ctx)

@@ -484,3 +484,67 @@ def test_adam_planted_mistakes_are_caught_by_the_closed_forms():
     assert np.allclose(variant(), closed, rtol=1e-12)
     assert not np.allclose(variant(eps_before_correction=True), closed, rtol=1e-7)   # differs where |g| ~ eps
     assert not np.allclose(variant(t_off=1), closed, rtol=1e-3)
+
+
+# --------------------------------------------------------------------------- fp16 (the paper's format) and loss scaling
+
+def test_f16_conversions_against_numpy_float16():
+    """numpy's float16 is IEEE binary16 with round-to-nearest-even conversions: an independent implementation."""
+    bits = np.arange(65536, dtype=np.uint16)
+    f = orc.f16_to_f32(bits)
+    ref = bits.view(np.float16).astype(np.float32)
+    nan = np.isnan(ref)
+    assert np.array_equal(f[~nan].view(np.uint32), ref[~nan].view(np.uint32)) and np.all(np.isnan(f[nan]))
+    assert np.array_equal(orc.f32_to_f16(f)[~nan], bits[~nan])
+    rng = np.random.default_rng(11)
+    x = rng.integers(0, 1 << 32, size=1_000_000, dtype=np.uint64).astype(np.uint32).view(np.float32)
+    y = (rng.standard_normal(1_000_000) * np.float32(10.0) ** rng.integers(-9, 6, size=1_000_000)).astype(np.float32)
+    for v in (x[np.isfinite(x)], y):
+        with np.errstate(over="ignore"):
+            want = v.astype(np.float16).view(np.uint16)
+        assert np.array_equal(orc.f32_to_f16(v), want)
+    # ties to even, overflow threshold, subnormals, specials
+    cases = {1.0 + 2.0 ** -11: 0x3C00, 1.0 + 3 * 2.0 ** -11: 0x3C02, 65504.0: 0x7BFF, 65519.996: 0x7BFF, 65520.0: 0x7C00,
+             2.0 ** -24: 0x0001, 2.0 ** -25: 0x0000, 1.5 * 2.0 ** -24: 0x0002, -0.0: 0x8000, float("inf"): 0x7C00, -float("inf"): 0xFC00}
+    for val, want in cases.items():
+        assert int(orc.f32_to_f16(np.array([val], np.float32))[0]) == want, val
+    assert np.isnan(orc.f16_to_f32(orc.f32_to_f16(np.array([np.nan], np.float32))))[0]
+
+
+def test_f16_reduce_and_adam_variants():
+    n = 3000
+    bits = np.random.default_rng(12).integers(0, 0x7C00, size=n).astype(np.uint16)       # finite positive fp16 patterns
+    bits[::2] |= 0x8000
+    g = np.zeros(n, np.float32)
+    orc.grad_reduce_into_chunk(g, 0, bits, 1.0, False, fmt=orc.FP16)
+    assert np.array_equal(g, bits.view(np.float16).astype(np.float32) + np.float32(0))
+    # fp16 gradients and fp32 gradients of the same values give the same update; the copy is the fp16 rounding of p
+    p, m, v, _ = _state(n, seed=30)
+    gh = (bits.view(np.float16).astype(np.float32) * np.float32(2.0 ** -8)).astype(np.float16)
+    a, b = [p.copy(), m.copy(), v.copy()], [p.copy(), m.copy(), v.copy()]
+    out = np.zeros(n, np.uint16)
+    orc.chunk_adam_step(*a, gh.view(np.uint16), out, step=1, fmt=orc.FP16, **HP)
+    orc.chunk_adam_step(*b, gh.astype(np.float32), None, step=1, **HP)
+    for x, y in zip(a, b):
+        assert np.array_equal(x.view(np.uint32), y.view(np.uint32))
+    assert np.array_equal(out, a[0].astype(np.float16).view(np.uint16))
+
+
+def test_loss_scale_state_machine():
+    # clean step: grad_scale = clip / S from the unscaled norm; counter advances
+    s, good, skip, gs = orc.loss_scale_step(65536.0, 0, 65536.0 * 38.9, 1.0, growth_interval=3)
+    assert (s, good, skip) == (65536.0, 1, False) and gs == pytest.approx(1.0 / (38.9 + 1e-6) / 65536.0, rel=1e-12)
+    # no clipping requested, or norm below max-norm: pure unscaling
+    assert orc.loss_scale_step(1024.0, 0, 1024.0 * 0.5, 1.0)[3] == 1.0 / 1024.0
+    assert orc.loss_scale_step(1024.0, 0, 1e9, 0.0)[3] == 1.0 / 1024.0
+    # overflow: skip, halve, reset
+    assert orc.loss_scale_step(65536.0, 7, float("inf"), 1.0) == (32768.0, 0, True, 0.0)
+    assert orc.loss_scale_step(65536.0, 7, float("nan"), 1.0) == (32768.0, 0, True, 0.0)
+    # growth after `growth_interval` clean steps in a row
+    s, good = 8.0, 0
+    trace = []
+    for norm in (1.0, 1.0, 1.0, float("inf"), 1.0, 1.0, 1.0, 1.0):
+        s, good, skip, _ = orc.loss_scale_step(s, good, norm, 0.0, growth_interval=3)
+        trace.append((s, good, skip))
+    assert trace == [(8.0, 1, False), (8.0, 2, False), (16.0, 0, False), (8.0, 0, True), (8.0, 1, False), (8.0, 2, False),
+                     (16.0, 0, False), (16.0, 1, False)]
