@@ -694,3 +694,82 @@ def test_offload_bind_streams_makes_copies_overlap(ctx):
     finally:
         sync()
         ex.elixir_offload_register_slots(ctx, [], 0)
+
+
+# --------------------------------------------------------------------------- determinism, graph capture
+
+def test_adam_and_reduce_are_bitwise_reproducible():
+    n = 500_003
+    p, m, v = _adam_state(n, 45, zero_moments=False)
+    gb = gen.fill_bf16(gen.stream_key(45, gen.TAG_GRAD, 1), 0, n, 1e-3)
+    runs = []
+    for _ in range(2):
+        d = [dev(x) for x in (p, m, v, gb)]
+        d_out = torch.zeros(n, dtype=torch.int16, device=DEV)
+        d_acc = torch.zeros(n, dtype=torch.float32, device=DEV)
+        ex.elixir_grad_reduce_into_chunk(d_acc, 0, d[3], n, 0.3, False)
+        ex.elixir_grad_reduce_into_chunk(d_acc, 0, d[3], n, 0.3, True)
+        ex.elixir_chunk_adam_step(d[0], d[1], d[2], None, d[3], d_out, n, hp_struct(2))
+        sync()
+        runs.append([host(x).copy() for x in (d[0], d[1], d[2], d_out, d_acc)])
+    for a, b in zip(*runs):
+        assert np.array_equal(a.view(np.uint8), b.view(np.uint8))
+
+
+def test_whole_step_replays_from_a_hip_graph(ctx):
+    """The step allocates nothing and never waits for the device, so it can be captured once and replayed: reduce two
+    micro-batches, global norm + clip coefficient, multi-chunk AdamW.  Every replay (with new gradients written into
+    the same buffers, and eager work and synchronisation in between) must match the eager run bit for bit."""
+    C, nch = 150_001, 3
+    key = gen.stream_key(gen.BASE_SEED, gen.TAG_PARAM, cfg=9)
+    p0 = np.stack([gen.fill_f32(key, c * C, C, 0.02) for c in range(nch)])
+
+    def fresh():
+        return dev(p0), torch.zeros(nch, C, device=DEV), torch.zeros(nch, C, device=DEV)
+
+    mb = [torch.zeros(nch, C, dtype=torch.int16, device=DEV) for _ in range(2)]
+    gch = torch.zeros(nch, C, dtype=torch.float32, device=DEV)
+    nc = torch.zeros(2, dtype=torch.float32, device=DEV)
+
+    def load_grads(it):
+        for k in range(2):
+            for c in range(nch):
+                gen.fill_bf16_device(mb[k][c].data_ptr(), C, gen.stream_key(gen.BASE_SEED, gen.TAG_GRAD, it, k, 9), c * C, 0.05)
+
+    def step(state, out, step_no):
+        for k in range(2):
+            for c in range(nch):
+                ex.elixir_grad_reduce_into_chunk(gch[c], 0, mb[k][c], C, 0.5, k > 0)
+        ex.elixir_chunk_grad_norm(ctx, [gch[c] for c in range(nch)], [C] * nch, 1.0, nc[0:1], nc[1:2])
+        ex.elixir_chunk_adam_step_multi([state[0][c] for c in range(nch)], [state[1][c] for c in range(nch)],
+                                        [state[2][c] for c in range(nch)], [gch[c] for c in range(nch)], None,
+                                        [out[c] for c in range(nch)], [C] * nch, hp_struct(step_no), nc[1:2])
+
+    # eager reference: three iterations with the same hyper-parameter step (the captured graph bakes it in)
+    eager = fresh()
+    eager_out = torch.zeros(nch, C, dtype=torch.int16, device=DEV)
+    want = []
+    for it in range(3):
+        load_grads(it)
+        step(eager, eager_out, 1)
+        sync()
+        want.append([host(x).copy() for x in (*eager, eager_out, nc)])
+    # captured once, replayed three times
+    graphed = fresh()
+    g_out = torch.zeros(nch, C, dtype=torch.int16, device=DEV)
+    load_grads(0)
+    sync()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        step(graphed, g_out, 1)
+    sync()
+    for x, y in zip(graphed, fresh()):          # capture itself executes nothing
+        assert torch.equal(x, y)
+    for it in range(3):
+        load_grads(it)                           # eager work between replays
+        sync()
+        graph.replay()
+        sync()
+        got = [host(x) for x in (*graphed, g_out, nc)]
+        for a, b in zip(got, want[it]):
+            assert np.array_equal(a.view(np.uint8), b.view(np.uint8)), f"replay {it} differs from the eager run"
