@@ -58,6 +58,7 @@ def parse():
     ap.add_argument("--multi", action="store_true",
                     help="update all chunks of a step with elixir_chunk_adam_step_multi (always done for chunks of <= 16Mi elements, "
                          "which are launch-bound one call at a time)")
+    ap.add_argument("--unfused-norm", action="store_true", help="gpt2_6b_clip: separate norm pass instead of the one fused into the last reduction")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-rows", action="store_true", help="skip the per-row side measurements")
     return ap.parse_args()
@@ -318,13 +319,21 @@ def run_clip(args, torch, ex, gen):
     step_no = [0]
     parts = {}
 
+    fused = not args.unfused_norm
+
     def reduce_all():
         for mb in range(K):
             for c in range(nch):
-                ex.elixir_grad_reduce_into_chunk(gch[c], 0, mbs[mb, c], C, 1.0 / K, mb > 0, sh)
+                if fused and mb == K - 1:       # the last pass also leaves the chunk's sum of squares in the context
+                    ex.elixir_grad_reduce_chunk_sumsq(ctx, c, gch[c], mbs[mb, c], ex.ELIXIR_LOWP_BF16, C, valid[c], 1.0 / K, mb > 0, sh)
+                else:
+                    ex.elixir_grad_reduce_into_chunk(gch[c], 0, mbs[mb, c], C, 1.0 / K, mb > 0, sh)
 
     def norm():
-        ex.elixir_chunk_grad_norm(ctx, chunks, valid, cfg.max_norm, d_nc[0:1], d_nc[1:2], sh)
+        if fused:
+            ex.elixir_chunk_grad_norm_finish(ctx, nch, cfg.max_norm, d_nc[0:1], d_nc[1:2], sh)
+        else:
+            ex.elixir_chunk_grad_norm(ctx, chunks, valid, cfg.max_norm, d_nc[0:1], d_nc[1:2], sh)
 
     def adam():
         step_no[0] += 1
@@ -342,6 +351,7 @@ def run_clip(args, torch, ex, gen):
         for name, fn in (("reduce", reduce_all), ("norm", norm), ("adam", adam)):
             parts[name] = _event_time(torch, stream, fn, 2, 1)[1]
         n_el = nch * C
+        step_bytes = (6 + 10 * (K - 1) + 30) * n_el + (0 if fused else 4 * sum(valid))
         print(json.dumps({
             "metric": "chunked AdamW params/sec (4 micro-batches reduced, global norm, clip, step)", "value": sum(valid) / wall,
             "unit": "params/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": wall * 1e3,
@@ -350,12 +360,14 @@ def run_clip(args, torch, ex, gen):
                        "max_norm": cfg.max_norm},
             "norm": float(d_nc[0].item()), "clip_coef": float(d_nc[1].item()),
             "phase_ms": {k: v * 1e3 for k, v in parts.items()},
-            "phase_GB/s": {"reduce": (6 + 10 * (K - 1)) * n_el / parts["reduce"] / 1e9, "norm": 4 * sum(valid) / parts["norm"] / 1e9,
+            "norm_fused_into_last_reduction": fused,
+            "phase_GB/s": {"reduce": (6 + 10 * (K - 1)) * n_el / parts["reduce"] / 1e9,
+                           "norm": None if fused else 4 * sum(valid) / parts["norm"] / 1e9,
                            "adam_fp32_grad": 30 * n_el / parts["adam"] / 1e9},
-            "roofline": {"bound": "hbm", "achieved": (6 + 10 * (K - 1) + 30) * n_el / 1e9 / ev + 4 * sum(valid) / 1e9 / ev,
-                         "peak": HBM_PEAK_GBPS, "unit": "GB/s", "traffic": None,
-                         "frac": ((6 + 10 * (K - 1) + 30) * n_el + 4 * sum(valid)) / 1e9 / ev / HBM_PEAK_GBPS,
-                         "note": "whole step: 6 + 3*10 (reduce) + 4 (norm) + 30 (AdamW, fp32 gradient) bytes per element"}}), flush=True)
+            "roofline": {"bound": "hbm", "achieved": step_bytes / 1e9 / ev, "peak": HBM_PEAK_GBPS, "unit": "GB/s", "traffic": None,
+                         "frac": step_bytes / 1e9 / ev / HBM_PEAK_GBPS,
+                         "note": "whole step: 6 + 3*10 (reduce) + 30 (AdamW, fp32 gradient) bytes per element"
+                                 + ("" if fused else " + 4 per valid element (norm)")}}), flush=True)
     finally:
         ex.elixir_ctx_destroy(ctx)
 

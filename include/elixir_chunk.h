@@ -152,6 +152,23 @@ int elixir_chunk_grad_norm(elixir_ctx* ctx, const float* const* grad_chunks, con
                            elixir_stream_t stream);
 
 /*
+ * The last pass of the reduction and the norm in one sweep.  elixir_grad_reduce_chunk_sumsq does what
+ * elixir_grad_reduce_into_chunk_lp does for a WHOLE chunk (offset 0, chunk_elems elements, 16-byte aligned chunk,
+ * 8-byte aligned gradients) and, from the values it is writing, leaves the chunk's sum of squares over its first
+ * valid_len elements in the context's slots for chunk number chunk_index (< max_chunks).  After every chunk of the
+ * step has gone through it (typically with the last micro-batch), elixir_chunk_grad_norm_finish(n_chunks) turns the
+ * slots of chunks 0 .. n_chunks-1 into the norm and the clip coefficient exactly as elixir_chunk_grad_norm does --
+ * without reading the gradients again (4 bytes per element saved).  Deterministic like the unfused path (its
+ * summation tree differs, so the two norms may differ in the last bit).  The calls of one step must be
+ * stream-ordered with each other (they share the context's workspace).
+ */
+int elixir_grad_reduce_chunk_sumsq(elixir_ctx* ctx, int chunk_index, float* d_grad_chunk, const uint16_t* d_grad_lowp,
+                                   int lowp_format, int64_t chunk_elems, int64_t valid_len, float scale, int accumulate,
+                                   elixir_stream_t stream);
+int elixir_chunk_grad_norm_finish(elixir_ctx* ctx, int n_chunks, float max_norm, float* d_norm_out,
+                                  float* d_clip_coef_out, elixir_stream_t stream);
+
+/*
  * Fused AdamW over one chunk pair (paper Sec. 4.1: one optimizer update per
  * gradient chunk + optimizer chunk; Sec. 2: fp32 master rounded to the
  * low-precision parameters).  Adam (Kingma & Ba, Alg. 1) with decoupled weight

@@ -28,6 +28,7 @@ EXPORTS = (
     "elixir_copy_d2h_async", "elixir_stream_synchronize", "elixir_offload_benefit", "elixir_offload_plan",
     "elixir_rcache_simulate", "elixir_chunk_size_search", "elixir_grad_reduce_into_chunk_lp", "elixir_chunk_adam_step_lp",
     "elixir_chunk_adam_step_multi_lp", "elixir_loss_scale_init", "elixir_loss_scale_update",
+    "elixir_grad_reduce_chunk_sumsq", "elixir_chunk_grad_norm_finish",
 )
 
 
@@ -90,6 +91,8 @@ def lib() -> ctypes.CDLL:
         sigs["elixir_chunk_adam_step_multi_lp"] = [ci, ctypes.POINTER(vp), ctypes.POINTER(vp), ctypes.POINTER(vp), ctypes.POINTER(vp),
                                                    ctypes.POINTER(vp), ctypes.POINTER(vp), ci, pi64,
                                                    ctypes.POINTER(elixir_adam_hparams), vp, vp, vp]
+        sigs["elixir_grad_reduce_chunk_sumsq"] = [vp, ci, vp, vp, ci, i64, i64, f32, ci, vp]
+        sigs["elixir_chunk_grad_norm_finish"] = [vp, ci, f32, vp, vp, vp]
         sigs["elixir_loss_scale_init"] = [vp, f32, vp]
         sigs["elixir_loss_scale_update"] = [vp, vp, f32, f32, f32, ci, vp]
         sigs["elixir_rcache_simulate"] = [pi64, i64, i64, pi64, pi64]
@@ -373,3 +376,16 @@ def elixir_loss_scale_update(d_state, d_norm_scaled, max_norm: float, growth_fac
                              growth_interval: int = 2000, stream=None) -> None:
     _check(lib().elixir_loss_scale_update(_addr(d_state), _addr(d_norm_scaled), max_norm, growth_factor, backoff_factor,
                                           growth_interval, _stream(stream)))
+
+
+# --------------------------------------------------------------------------- reduction fused with the norm
+
+def elixir_grad_reduce_chunk_sumsq(ctx: Ctx, chunk_index: int, grad_chunk, grad_lowp, lowp_format: int, chunk_elems: int,
+                                   valid_len: int, scale: float, accumulate: bool, stream=None) -> None:
+    _check(lib().elixir_grad_reduce_chunk_sumsq(ctx.handle, chunk_index, _addr(grad_chunk), _addr(grad_lowp), lowp_format,
+                                                chunk_elems, valid_len, scale, 1 if accumulate else 0, _stream(stream)))
+
+
+def elixir_chunk_grad_norm_finish(ctx: Ctx, n_chunks: int, max_norm: float, d_norm_out, d_clip_coef_out, stream=None) -> None:
+    _check(lib().elixir_chunk_grad_norm_finish(ctx.handle, n_chunks, max_norm, _addr(d_norm_out), _addr(d_clip_coef_out),
+                                               _stream(stream)))

@@ -31,6 +31,7 @@ inline bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_
 
 constexpr int kBlock = 256;          // threads per workgroup: 4 wavefronts of 64
 constexpr int kNormBlocksPerChunk = 1024;  // fixed, so the reduction tree never depends on the launch
+constexpr int kReduceBlock = 128;          // threads per workgroup of the gradient reduction (4 elements per thread)
 
 struct Slot {
     void* d_ptr = nullptr;
@@ -48,6 +49,8 @@ struct elixir_ctx {
     int64_t max_chunk_elems = 0;
     int max_chunks = 0;
     double* d_partials = nullptr;  // max_chunks * kNormBlocksPerChunk
+    double* d_stage = nullptr;     // one double per wavefront of the fused reduce + sum-of-squares pass (one chunk at a time)
+    int64_t stage_len = 0;
     elixir::Slot* slots = nullptr;
     int n_slots = 0;
     size_t slot_bytes = 0;

@@ -52,8 +52,11 @@ extern "C" int elixir_ctx_create(elixir_ctx** out, int device, int64_t max_chunk
     c->max_chunk_elems = max_chunk_elems;
     c->max_chunks = max_chunks;
     hipError_t e = hipMalloc((void**)&c->d_partials, sizeof(double) * (size_t)max_chunks * kNormBlocksPerChunk);
+    c->stage_len = (max_chunk_elems + 255) / 256 + 1;  // one entry per 256 elements (a wavefront's 4 x 64) + 1 for the odd elements after the last group of 4
+    if (e == hipSuccess) e = hipMalloc((void**)&c->d_stage, sizeof(double) * (size_t)c->stage_len);
     if (e != hipSuccess) {
         if (c->d_partials) (void)hipFree(c->d_partials);
+        if (c->d_stage) (void)hipFree(c->d_stage);
         delete c;
         return fail(ELIXIR_EHIP, "elixir_ctx_create: %s", hipGetErrorString(e));
     }
@@ -82,6 +85,7 @@ extern "C" int elixir_ctx_destroy(elixir_ctx* c) {
     hipError_t e = hipDeviceSynchronize();
     destroy_slots(c);
     if (c->d_partials) (void)hipFree(c->d_partials);
+    if (c->d_stage) (void)hipFree(c->d_stage);
     delete c;
     if (e != hipSuccess) return fail(ELIXIR_EHIP, "elixir_ctx_destroy: hipDeviceSynchronize: %s", hipGetErrorString(e));
     return ELIXIR_OK;

@@ -10,15 +10,16 @@
 //   subset in index order, then the same tree) and writes sqrt(sum) and the
 //   clip coefficient.
 // No atomics: the tree is a function of (chunk lengths) only, never of timing.
-// Traffic: 4 bytes per element.  Double-precision arithmetic (2 ops/element)
+// Traffic: 4 bytes per element.  When the gradients are being written anyway -- the last micro-batch of the
+// reduction -- elixir_grad_reduce_chunk_sumsq produces the same per-chunk slots from the values in registers and the
+// 4-byte re-read disappears (stage 1b below).  Double-precision arithmetic (2 ops/element)
 // stays far below the fp64 vector rate at HBM speed.
 #include "common.hpp"
+#include "reduce_elem.hpp"
 
 using namespace elixir;
 
 namespace {
-
-typedef float f32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int kMaxBatch = 128;  // chunks per stage-1 launch (pointer table travels as kernel argument)
 
@@ -106,6 +107,92 @@ __global__ __launch_bounds__(1024) void finish_kernel(const double* __restrict__
     }
 }
 
+// Stage 1b: the gradient reduction of reduce.hip that also leaves the sum of squares of the values it writes, over
+// the valid part of the chunk, in stage[blockIdx.x].  One wavefront per workgroup (256 elements): the 64 lanes are
+// combined with the fixed shuffle tree alone, no LDS and no barrier, so the pass stays as fast as the plain
+// reduction.  A lane adds its four squares in fp32 (a 4-term sum; the norm's tolerance is 1e-5) and everything
+// after that is double.  stage[] depends on the data only.
+constexpr int kFusedBlock = 64;
+
+template <bool ACC, bool FP16>
+__global__ __launch_bounds__(kFusedBlock) void reduce_sumsq_kernel(float* __restrict__ dst, const uint16_t* __restrict__ src,
+                                                                  int64_t n4, int64_t valid, float scale,
+                                                                  double* __restrict__ stage) {
+    const int64_t i = (int64_t)blockIdx.x * kFusedBlock + threadIdx.x;
+    float sq = 0.0f;
+    if (i < n4) {
+        f32x4* D = reinterpret_cast<f32x4*>(dst) + i;
+        const u32x2 g = __builtin_nontemporal_load(reinterpret_cast<const u32x2*>(src) + i);
+        f32x4 a;
+        if constexpr (ACC) a = __builtin_nontemporal_load(D);
+        else a = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
+        f32x4 r;
+        r.x = reduce_elem<FP16>(a.x, g.x & 0xFFFFu, scale);
+        r.y = reduce_elem<FP16>(a.y, g.x >> 16, scale);
+        r.z = reduce_elem<FP16>(a.z, g.y & 0xFFFFu, scale);
+        r.w = reduce_elem<FP16>(a.w, g.y >> 16, scale);
+        __builtin_nontemporal_store(r, D);
+        const int64_t k = i * 4;
+        if (k + 3 < valid) {
+            sq = r.x * r.x + r.y * r.y + (r.z * r.z + r.w * r.w);
+        } else {
+            if (k + 0 < valid) sq += r.x * r.x;
+            if (k + 1 < valid) sq += r.y * r.y;
+            if (k + 2 < valid) sq += r.z * r.z;
+        }
+    }
+    double x = (double)sq;
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) x += __shfl_down(x, off, 64);
+    if (threadIdx.x == 0) stage[blockIdx.x] = x;
+}
+
+// The at most 3 elements after the last complete group of 4 (one thread each), added to the last stage entry's
+// successor so that the fold below sees them.
+template <bool ACC, bool FP16>
+__global__ void reduce_sumsq_tail_kernel(float* dst, const uint16_t* src, int64_t first, int64_t n, int64_t valid, float scale,
+                                         double* stage_slot) {
+    double sq = 0.0;
+    for (int64_t k = first; k < n; ++k) {
+        const float r = reduce_elem<FP16>(ACC ? dst[k] : 0.0f, src[k], scale);
+        dst[k] = r;
+        if (k < valid) sq = fma((double)r, (double)r, sq);
+    }
+    *stage_slot = sq;
+}
+
+// Folds the stage entries of one chunk into its kNormBlocksPerChunk slots: slot j is the sum of the j-th of 1024
+// equal contiguous runs of entries, taken by one wavefront (lane l adds entries l, l + 64, ... of the run in order,
+// then the fixed shuffle tree).  grid = 256 workgroups of 4 wavefronts.
+__global__ __launch_bounds__(256) void fold_stage_kernel(const double* __restrict__ stage, int64_t count, double* __restrict__ slots) {
+    const int lane = threadIdx.x & 63;
+    const int j = blockIdx.x * 4 + (threadIdx.x >> 6);
+    const int64_t run = (count + kNormBlocksPerChunk - 1) / kNormBlocksPerChunk;
+    const int64_t lo = (int64_t)j * run;
+    int64_t hi = lo + run;
+    if (hi > count) hi = count;
+    double acc = 0.0;
+    for (int64_t i = lo + lane; i < hi; i += 64) acc += stage[i];
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) acc += __shfl_down(acc, off, 64);
+    if (lane == 0) slots[j] = acc;
+}
+
+template <bool ACC, bool FP16>
+void launch_fused(float* dst, const uint16_t* src, int64_t n, int64_t valid, float scale, double* stage, double* slots,
+                  hipStream_t s) {
+    const int64_t n4 = n / 4;
+    const int64_t blocks = (n4 + kFusedBlock - 1) / kFusedBlock;
+    if (blocks > 0)
+        hipLaunchKernelGGL((reduce_sumsq_kernel<ACC, FP16>), dim3((unsigned)blocks), dim3(kFusedBlock), 0, s, dst, src, n4, valid, scale, stage);
+    int64_t count = blocks;
+    if (n4 * 4 < n) {
+        hipLaunchKernelGGL((reduce_sumsq_tail_kernel<ACC, FP16>), dim3(1), dim3(1), 0, s, dst, src, n4 * 4, n, valid, scale, stage + blocks);
+        ++count;
+    }
+    hipLaunchKernelGGL(fold_stage_kernel, dim3(kNormBlocksPerChunk / 4), dim3(256), 0, s, stage, count, slots);
+}
+
 }  // namespace
 
 extern "C" int elixir_chunk_grad_norm(elixir_ctx* ctx, const float* const* grad_chunks, const int64_t* valid_len,
@@ -139,6 +226,54 @@ extern "C" int elixir_chunk_grad_norm(elixir_ctx* ctx, const float* const* grad_
         ELIXIR_LAUNCH_CHECK("sumsq_kernel");
     }
     hipLaunchKernelGGL(finish_kernel, dim3(1), dim3(1024), 0, s, ctx->d_partials,
+                       (int64_t)n_chunks * kNormBlocksPerChunk, max_norm, d_norm_out, d_clip_coef_out);
+    ELIXIR_LAUNCH_CHECK("finish_kernel");
+    return ELIXIR_OK;
+}
+
+extern "C" int elixir_grad_reduce_chunk_sumsq(elixir_ctx* ctx, int chunk_index, float* d_grad_chunk, const uint16_t* d_grad_lowp,
+                                              int lowp_format, int64_t chunk_elems, int64_t valid_len, float scale,
+                                              int accumulate, elixir_stream_t stream) {
+    static const char* what = "elixir_grad_reduce_chunk_sumsq";
+    if (!ctx) return fail(ELIXIR_EINVAL, "%s: ctx is NULL", what);
+    if (chunk_index < 0 || chunk_index >= ctx->max_chunks)
+        return fail(ELIXIR_ECAP, "%s: chunk_index=%d, context sized for %d chunks", what, chunk_index, ctx->max_chunks);
+    if (chunk_elems < 0 || valid_len < 0 || valid_len > chunk_elems)
+        return fail(ELIXIR_EINVAL, "%s: need 0 <= valid_len <= chunk_elems", what);
+    if (chunk_elems > ctx->max_chunk_elems)
+        return fail(ELIXIR_ECAP, "%s: chunk of %lld elements, context sized for %lld", what, (long long)chunk_elems, (long long)ctx->max_chunk_elems);
+    if (lowp_format != ELIXIR_LOWP_BF16 && lowp_format != ELIXIR_LOWP_FP16)
+        return fail(ELIXIR_EINVAL, "%s: lowp_format=%d is neither ELIXIR_LOWP_BF16 nor ELIXIR_LOWP_FP16", what, lowp_format);
+    hipStream_t s = (hipStream_t)stream;
+    double* slots = ctx->d_partials + (int64_t)chunk_index * kNormBlocksPerChunk;
+    if (chunk_elems == 0) {  // nothing to reduce: the chunk contributes zero
+        hipLaunchKernelGGL(fold_stage_kernel, dim3(kNormBlocksPerChunk / 4), dim3(256), 0, s, ctx->d_stage, (int64_t)0, slots);
+        ELIXIR_LAUNCH_CHECK("fold_stage_kernel");
+        return ELIXIR_OK;
+    }
+    if (!d_grad_chunk || !d_grad_lowp) return fail(ELIXIR_EINVAL, "%s: NULL pointer", what);
+    if (!aligned(d_grad_chunk, 16) || !aligned(d_grad_lowp, 8))
+        return fail(ELIXIR_EALIGN, "%s: whole chunks are expected: the fp32 chunk 16-byte and the 16-bit gradients 8-byte aligned", what);
+    const bool f16 = lowp_format == ELIXIR_LOWP_FP16;
+    if (accumulate) {
+        if (f16) launch_fused<true, true>(d_grad_chunk, d_grad_lowp, chunk_elems, valid_len, scale, ctx->d_stage, slots, s);
+        else launch_fused<true, false>(d_grad_chunk, d_grad_lowp, chunk_elems, valid_len, scale, ctx->d_stage, slots, s);
+    } else {
+        if (f16) launch_fused<false, true>(d_grad_chunk, d_grad_lowp, chunk_elems, valid_len, scale, ctx->d_stage, slots, s);
+        else launch_fused<false, false>(d_grad_chunk, d_grad_lowp, chunk_elems, valid_len, scale, ctx->d_stage, slots, s);
+    }
+    ELIXIR_LAUNCH_CHECK("reduce_sumsq_kernel");
+    return ELIXIR_OK;
+}
+
+extern "C" int elixir_chunk_grad_norm_finish(elixir_ctx* ctx, int n_chunks, float max_norm, float* d_norm_out,
+                                             float* d_clip_coef_out, elixir_stream_t stream) {
+    static const char* what = "elixir_chunk_grad_norm_finish";
+    if (!ctx) return fail(ELIXIR_EINVAL, "%s: ctx is NULL", what);
+    if (n_chunks < 0) return fail(ELIXIR_EINVAL, "%s: n_chunks is negative", what);
+    if (n_chunks > ctx->max_chunks) return fail(ELIXIR_ECAP, "%s: %d chunks, context sized for %d", what, n_chunks, ctx->max_chunks);
+    if (!aligned(d_norm_out, 4) || !aligned(d_clip_coef_out, 4)) return fail(ELIXIR_EALIGN, "%s: output pointer not 4-byte aligned", what);
+    hipLaunchKernelGGL(finish_kernel, dim3(1), dim3(1024), 0, (hipStream_t)stream, ctx->d_partials,
                        (int64_t)n_chunks * kNormBlocksPerChunk, max_norm, d_norm_out, d_clip_coef_out);
     ELIXIR_LAUNCH_CHECK("finish_kernel");
     return ELIXIR_OK;

@@ -6,28 +6,13 @@
 // the compiler would have formed a fused multiply-add.
 // Traffic per element: 2 bytes read + 4 written, plus 4 read when accumulating.
 #include "common.hpp"
+#include "reduce_elem.hpp"
 
 using namespace elixir;
 
 namespace {
 
-typedef float f32x4 __attribute__((ext_vector_type(4)));
-typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
-
-// 16 gradient bits -> fp32: bf16 is the upper half of an fp32 pattern; fp16 takes the hardware conversion (exact).
-template <bool FP16>
-__device__ __forceinline__ float widen(uint32_t bits16) {
-    if constexpr (FP16) return (float)__builtin_bit_cast(_Float16, (uint16_t)bits16);
-    else return __uint_as_float(bits16 << 16);
-}
-
-template <bool FP16>
-__device__ __forceinline__ float reduce_elem(float old, uint32_t bits16, float scale) {
-    const float t = scale * widen<FP16>(bits16);
-    return old + t;
-}
-
-constexpr int kVecBlock = 128;  // one 4-element group per thread, one workgroup per 512 elements, no loop:
+constexpr int kVecBlock = kReduceBlock;  // one 4-element group per thread, one workgroup per 512 elements, no loop:
                                 // workgroups are dispatched in index order, so the three streams advance as
                                 // sequential fronts; with 128-bit accesses at full residency ~8 MB are in flight,
                                 // which measured best for this 1-2 read / 1 write stream mix

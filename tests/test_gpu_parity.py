@@ -773,3 +773,57 @@ def test_whole_step_replays_from_a_hip_graph(ctx):
         got = [host(x) for x in (*graphed, g_out, nc)]
         for a, b in zip(got, want[it]):
             assert np.array_equal(a.view(np.uint8), b.view(np.uint8)), f"replay {it} differs from the eager run"
+
+
+# --------------------------------------------------------------------------- reduction fused with the norm
+
+@pytest.mark.parametrize("fmt", [0, 1])
+def test_fused_reduce_sumsq_matches_plain_reduce_and_oracle_norm(ctx, fmt):
+    lens = [(1 << 20, 1 << 20), (777_777, 700_001), (511, 511), (513, 2), (4, 0), (0, 0), (300_003, 300_003)]
+    nch, K = len(lens), 3
+    d_nc = torch.zeros(2, dtype=torch.float32, device=DEV)
+    d_ref_nc = torch.zeros(2, dtype=torch.float32, device=DEV)
+    fused = [torch.full((max(n, 1),), 3.0, dtype=torch.float32, device=DEV) for n, _ in lens]
+    plain = [torch.full((max(n, 1),), 3.0, dtype=torch.float32, device=DEV) for n, _ in lens]
+    ref = [np.zeros(n, np.float32) for n, _ in lens]
+    for mb in range(K):
+        for c, (n, valid) in enumerate(lens):
+            x = gen.fill_f32(gen.stream_key(90, gen.TAG_GRAD, mb, c), 0, n, 0.03)
+            g = x.astype(np.float16).view(np.uint16) if fmt else gen.fill_bf16(gen.stream_key(90, gen.TAG_GRAD, mb, c), 0, n, 0.03)
+            d_g = dev(g) if n else torch.zeros(1, dtype=torch.int16, device=DEV)
+            ex.elixir_grad_reduce_into_chunk_lp(plain[c], 0, d_g, fmt, n, 0.3, mb > 0)
+            if mb < K - 1:
+                ex.elixir_grad_reduce_into_chunk_lp(fused[c], 0, d_g, fmt, n, 0.3, mb > 0)
+            else:
+                ex.elixir_grad_reduce_chunk_sumsq(ctx, c, fused[c], d_g, fmt, n, valid, 0.3, True)
+            if n:
+                orc.grad_reduce_into_chunk(ref[c], 0, g, 0.3, mb > 0, fmt=fmt)
+    ex.elixir_chunk_grad_norm_finish(ctx, nch, 1.0, d_nc[0:1], d_nc[1:2])
+    ex.elixir_chunk_grad_norm(ctx, plain, [v for _, v in lens], 1.0, d_ref_nc[0:1], d_ref_nc[1:2])
+    sync()
+    for c, (n, _) in enumerate(lens):
+        assert np.array_equal(host(fused[c])[:n].view(np.uint32), ref[c].view(np.uint32)), f"chunk {c}"
+        assert np.array_equal(host(fused[c])[:n].view(np.uint32), host(plain[c])[:n].view(np.uint32))
+    want = orc.grad_norm(ref, [v for _, v in lens])
+    got, got_ref = host(d_nc), host(d_ref_nc)
+    assert got[0] == pytest.approx(want, rel=1e-5) and got[1] == pytest.approx(orc.clip_coef(want, 1.0), rel=1e-5)
+    assert abs(float(got[0]) - float(got_ref[0])) <= 2e-7 * want
+    # reproducible: the same last pass again (accumulating once more) twice gives identical bits
+    outs = []
+    for _ in range(2):
+        tmp = [p.clone() for p in plain]
+        for c, (n, valid) in enumerate(lens):
+            d_g = dev(gen.fill_bf16(gen.stream_key(91, gen.TAG_GRAD, 0, c), 0, n, 0.03)) if n else torch.zeros(1, dtype=torch.int16, device=DEV)
+            ex.elixir_grad_reduce_chunk_sumsq(ctx, c, tmp[c], d_g, 0, n, valid, 0.25, True)
+        ex.elixir_chunk_grad_norm_finish(ctx, nch, 0.0, d_nc[0:1], d_nc[1:2])
+        sync()
+        outs.append(host(d_nc).copy())
+    assert np.array_equal(outs[0].view(np.uint32), outs[1].view(np.uint32))
+    # errors
+    for call, code in ((lambda: ex.elixir_grad_reduce_chunk_sumsq(ctx, 999, fused[0], fused[0], 0, 8, 8, 1.0, False), ex.ELIXIR_ECAP),
+                       (lambda: ex.elixir_grad_reduce_chunk_sumsq(ctx, 0, fused[0], fused[0], 0, 8, 9, 1.0, False), ex.ELIXIR_EINVAL),
+                       (lambda: ex.elixir_grad_reduce_chunk_sumsq(ctx, 0, fused[0][1:], fused[0], 0, 8, 8, 1.0, False), ex.ELIXIR_EALIGN),
+                       (lambda: ex.elixir_chunk_grad_norm_finish(ctx, 100_000, 1.0, d_nc[0:1], None), ex.ELIXIR_ECAP)):
+        with pytest.raises(ex.ElixirError) as e:
+            call()
+        assert e.value.code == code
