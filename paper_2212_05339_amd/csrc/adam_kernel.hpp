@@ -15,10 +15,12 @@
 //     512 contiguous bytes per wavefront instruction), 128-thread workgroups,
 //     and a dynamic-LDS reservation that caps residency at 5 wavefronts per
 //     SIMD (the LDS itself is not used);
-//   * streaming (non-temporal) loads and stores: nothing is read twice.
+//   * streaming (non-temporal) loads and write-through streaming stores: nothing is read twice.
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+
+#include "stream_store.hpp"
 
 namespace elixir {
 
@@ -121,11 +123,11 @@ __device__ __forceinline__ void adam_pair(float* master, float* exp_avg, float* 
     float p0 = p.x, m0 = m.x, v0 = v.x, p1 = p.y, m1 = m.y, v1 = v.y;
     adam_elem(p0, m0, v0, g0, c);
     adam_elem(p1, m1, v1, g1, c);
-    __builtin_nontemporal_store(f32x2{p0, p1}, P);
-    __builtin_nontemporal_store(f32x2{m0, m1}, M);
-    __builtin_nontemporal_store(f32x2{v0, v1}, V);
+    stream_store(f32x2{p0, p1}, P);
+    stream_store(f32x2{m0, m1}, M);
+    stream_store(f32x2{v0, v1}, V);
     if constexpr (OUT != kNone)
-        __builtin_nontemporal_store(lowp_bits<OUT>(p0) | (lowp_bits<OUT>(p1) << 16), reinterpret_cast<uint32_t*>(out) + i);
+        stream_store(lowp_bits<OUT>(p0) | (lowp_bits<OUT>(p1) << 16), reinterpret_cast<uint32_t*>(out) + i);
 }
 
 // Vector kernel: thread i owns elements 2i, 2i+1.  Host guarantees 8-byte aligned fp32
