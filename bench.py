@@ -59,6 +59,8 @@ def parse():
                     help="update all chunks of a step with elixir_chunk_adam_step_multi (always done for chunks of <= 16Mi elements, "
                          "which are launch-bound one call at a time)")
     ap.add_argument("--unfused-norm", action="store_true", help="gpt2_6b_clip: separate norm pass instead of the one fused into the last reduction")
+    ap.add_argument("--host-order", choices=["interleaved", "first"], default="interleaved",
+                    help="gpt2_20b_offload: which 60%% of the chunks live in host memory (every 3 of 5, or the first 60%% in schedule order)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-rows", action="store_true", help="skip the per-row side measurements")
     return ap.parse_args()
@@ -95,9 +97,15 @@ def cpu_baseline(cfg, valid0, budget_elems):
         for step in range(1, steps + 1):
             list(ex.map(work, [(i, step) for i in range(threads)]))
     dt = time.perf_counter() - t0
+    n1 = min(n, 4 * gen.Mi)                                    # one thread alone, on the head of the same chunk
+    t1 = time.perf_counter()
+    for step in range(steps + 1, steps + 5):
+        orc.chunk_adam_step(p[:n1], m[:n1], v[:n1], g[:n1], out[:n1], step=step, **hp)
+    dt1 = time.perf_counter() - t1
     return {"value": n * steps / dt, "unit": "params/s", "cores": threads, "kind": "oracle",
             "sample": f"chunk 0 of the workload ({n} elements), {steps} consecutive AdamW steps with bf16 write-back, "
-                      f"{dt:.2f} s wall on {threads} threads"}
+                      f"{dt:.2f} s wall on {threads} threads",
+            "single_thread_value": 4 * n1 / dt1, "single_thread_sample": f"4 steps on the first {n1} elements, {dt1:.2f} s"}
 
 
 def side_rows(ex, gen, torch, cfg, C, nch, valid, state, grads, out, stream, step_ms):
@@ -381,7 +389,11 @@ def run_offload(args, torch, ex, gen):
     C = cfg.chunk_elems
     valid_all = ex.elixir_layout_plan(cfg.numels(), C, ex.ELIXIR_LAYOUT_DENSE, 1)[2]
     n_all = len(valid_all)
-    is_host_all = [(3 * c) % 5 < 3 for c in range(n_all)]                      # 60% of the chunks, interleaved
+    n_host_all = -(-3 * n_all // 5)
+    if args.host_order == "first":
+        is_host_all = [c < n_host_all for c in range(n_all)]                   # the first 60% in schedule order
+    else:
+        is_host_all = [(3 * c) % 5 < 3 for c in range(n_all)]                  # 60% of the chunks, interleaved
     nbytes = 3 * C * 4
     # pin host memory first: if the box refuses the full amount, the same 60/40 mix runs on as many chunks as fit
     want = args.host_chunks if args.host_chunks > 0 else sum(is_host_all)
@@ -397,15 +409,20 @@ def run_offload(args, torch, ex, gen):
         print(f"bench.py: the box pins at most {pinned_limit} blocks of {nbytes} bytes; running with {len(pinned)} host chunks",
               file=sys.stderr, flush=True)
     t_alloc = time.perf_counter() - t0
-    keep, h = 0, 0
-    for c in range(n_all):                                                     # first chunks, whole groups of 5
-        h += is_host_all[c]
-        keep = c + 1
-        if h >= len(pinned) and (keep % 5 == 0 or keep == n_all):
-            break
-    valid, is_host = valid_all[:keep], is_host_all[:keep]
-    while sum(is_host) > len(pinned):                                          # a partial last group: make its tail resident
-        is_host[max(c for c in range(keep) if is_host[c])] = False
+    if args.host_order == "first":                                             # H host chunks, then 2H/3 resident ones
+        H = min(len(pinned), n_host_all)
+        keep = n_all if H == n_host_all else min(n_all, H + round(H * 2 / 3))
+        valid, is_host = valid_all[:keep], [c < H for c in range(keep)]
+    else:
+        keep, h = 0, 0
+        for c in range(n_all):                                                 # first chunks, whole groups of 5
+            h += is_host_all[c]
+            keep = c + 1
+            if h >= len(pinned) and (keep % 5 == 0 or keep == n_all):
+                break
+        valid, is_host = valid_all[:keep], is_host_all[:keep]
+        while sum(is_host) > len(pinned):                                      # a partial last group: make its tail resident
+            is_host[max(c for c in range(keep) if is_host[c])] = False
     nch = len(valid)
     host_ids = [c for c in range(nch) if is_host[c]]
     n_slots = 3
@@ -424,6 +441,41 @@ def run_offload(args, torch, ex, gen):
     try:
         ex.elixir_offload_register_slots(ctx, slots, nbytes)
         overlapped = ex.elixir_offload_bind_streams(ctx, h2d, d2h)
+
+        def wall_of(fn):
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            fn()
+            torch.cuda.synchronize()
+            return time.perf_counter() - t0
+
+        # ---- the link itself, before any state exists: bare pinned copies of whole blocks, each direction alone and both at once
+        probe = [blocks[c] for c in host_ids[:min(8, len(host_ids) // 2 * 2)]]
+        half = len(probe) // 2
+
+        def only_h2d():
+            for k, b in enumerate(probe):
+                ex.elixir_copy_h2d_async(slots[k % n_slots], b, nbytes, h2d)
+
+        def only_d2h():
+            for k, b in enumerate(probe):
+                ex.elixir_copy_d2h_async(b, slots[k % n_slots], nbytes, d2h)
+
+        def both_ways():
+            for k in range(half):
+                ex.elixir_copy_h2d_async(slots[0], probe[k], nbytes, h2d)
+                ex.elixir_copy_d2h_async(probe[half + k], slots[1], nbytes, d2h)
+
+        link = None
+        if half >= 1:
+            only_d2h()                                                          # first touch of the host pages
+            t_up = min(wall_of(only_h2d) for _ in range(3))
+            t_down = min(wall_of(only_d2h) for _ in range(3))
+            t_bi = min(wall_of(both_ways) for _ in range(3))
+            link = {"h2d_alone_GB/s": len(probe) * nbytes / t_up / 1e9, "d2h_alone_GB/s": len(probe) * nbytes / t_down / 1e9,
+                    "bidirectional_GB/s_each_way": half * nbytes / t_bi / 1e9,
+                    "what": f"bare pinned copies of {len(probe)} blocks of {nbytes} bytes"}
+
         for c in range(nch):
             gen.fill_bf16_device(grads[c].data_ptr(), valid[c], gkey, c * C, cfg.grad_std)
             if is_host[c]:                                     # initial state: generated in a slot, evicted to the host block
@@ -438,9 +490,9 @@ def run_offload(args, torch, ex, gen):
         torch.cuda.synchronize()
         step_no = [0]
 
-        def step():
-            step_no[0] += 1
-            hp = ex.make_hparams(cfg.lr, cfg.beta1, cfg.beta2, cfg.eps, cfg.weight_decay, step_no[0])
+        def step(update=True):
+            step_no[0] += update
+            hp = ex.make_hparams(cfg.lr, cfg.beta1, cfg.beta2, cfg.eps, cfg.weight_decay, max(step_no[0], 1))
             pending, inflight = list(host_ids), []
             for c in range(nch):
                 while pending and len(inflight) < n_slots:
@@ -454,11 +506,19 @@ def run_offload(args, torch, ex, gen):
                 if is_host[c]:
                     cc, s = inflight.pop(0)
                     ex.elixir_chunk_wait_ready(ctx, s, compute)
-                    ex.elixir_chunk_adam_step(slots[s][0], slots[s][1], slots[s][2], None, grads[c], out[c], C, hp, None, sh)
+                    if update:
+                        ex.elixir_chunk_adam_step(slots[s][0], slots[s][1], slots[s][2], None, grads[c], out[c], C, hp, None, sh)
                     ex.elixir_chunk_evict(ctx, s, blocks[c], nbytes, compute, d2h)
-                else:
+                elif update:
                     r = resident[c]
                     ex.elixir_chunk_adam_step(r[0], r[1], r[2], None, grads[c], out[c], C, hp, None, sh)
+
+        def compute_only():
+            # the same updates with nothing to wait for: host-resident chunks are updated in whatever a slot holds
+            hp = ex.make_hparams(cfg.lr, cfg.beta1, cfg.beta2, cfg.eps, cfg.weight_decay, 1)
+            for c in range(nch):
+                r = slots[c % n_slots] if is_host[c] else resident[c]
+                ex.elixir_chunk_adam_step(r[0], r[1], r[2], None, grads[c], out[c], C, hp, None, sh)
 
         for _ in range(args.warmup):
             step()
@@ -469,6 +529,10 @@ def run_offload(args, torch, ex, gen):
         torch.cuda.synchronize()
         wall = (time.perf_counter() - t0) / args.steps
         moved = len(host_ids) * nbytes
+        t_compute = min(wall_of(compute_only) for _ in range(2))
+        t_dma = wall_of(lambda: step(update=False))                             # the same schedule of copies, no kernels
+        overlap = min(1.0, 1.0 - (wall - max(t_dma, t_compute)) / min(t_dma, t_compute))   # 1: the shorter of the two is hidden
+        frac = (moved / wall / 1e9) / link["bidirectional_GB/s_each_way"] if link else None
         print(json.dumps({
             "metric": "chunked AdamW params/sec with 60% of the chunks streamed from pinned host memory", "value": sum(valid) / wall,
             "unit": "params/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": wall * 1e3, "dtype": "f32",
@@ -476,11 +540,14 @@ def run_offload(args, torch, ex, gen):
             "config": {"workload": cfg.name, "layout": "dense", "chunk_elems": C, "n_chunks": nch, "n_chunks_full_set": n_all,
                        "host_chunks": len(host_ids), "resident_chunks": nch - len(host_ids), "slots": n_slots,
                        "params": sum(valid), "pinned_GB": moved / 1e9, "pinned_alloc_s": t_alloc,
-                       "copy_engines_separate": overlapped,
+                       "copy_engines_separate": overlapped, "host_order": args.host_order,
                        "pinned_blocks_the_box_allowed": pinned_limit},
-            "offload_GB/s_each_way": moved / wall / 1e9,
+            "offload_GB/s_each_way": moved / wall / 1e9, "link": link,
+            "frac_of_one_way_link": (moved / wall / 1e9) / max(link["h2d_alone_GB/s"], link["d2h_alone_GB/s"]) if link else None,
+            "compute_only_ms": t_compute * 1e3, "copies_only_ms": t_dma * 1e3, "overlap": overlap,
             "roofline": {"bound": "host link", "achieved": moved / wall / 1e9, "unit": "GB/s each way, both directions concurrent",
-                         "peak": None, "frac": None, "traffic": None}}), flush=True)
+                         "peak": link["bidirectional_GB/s_each_way"] if link else None, "frac": frac, "traffic": None,
+                         "note": "peak = bare bidirectional pinned copies measured in this run"}}), flush=True)
     finally:
         torch.cuda.synchronize()
         ex.elixir_offload_register_slots(ctx, [], 0)
@@ -686,6 +753,15 @@ def main():
     wall = time.perf_counter() - t0
     ev_ms = e0.elapsed_time(e1)
 
+    # the same steps once more with an event after each, for the spread (kept out of the timed region above)
+    marks = [torch.cuda.Event(enable_timing=True) for _ in range(K + 1)]
+    marks[0].record(stream)
+    for k in range(K):
+        one_step(W + K + k + 1)
+        marks[k + 1].record(stream)
+    torch.cuda.synchronize()
+    per_step = sorted(marks[k].elapsed_time(marks[k + 1]) for k in range(K))
+
     total_params = sum(valid)
     launches = K * (-(-nch // 64) if args.multi else nch)
     per_launch_elems = nch * C / (-(-nch // 64)) if args.multi else C
@@ -706,6 +782,8 @@ def main():
                    "grad_sets_resident": n_sets, "hparams": {"lr": cfg.lr, "betas": [cfg.beta1, cfg.beta2],
                                                              "eps": cfg.eps, "weight_decay": cfg.weight_decay}},
         "elements_per_s": nch * C * K / wall,
+        "step_ms_device": {"median": per_step[K // 2], "min": per_step[0], "max": per_step[-1],
+                           "what": "HIP events around each of K further steps"},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBPS, "traffic": traffic,
                      "kernel": ("adam_multi_kernel" if args.multi else "adam_vec_kernel") + "<1, 1> (bf16 gradient in, bf16 copy out)",
@@ -715,6 +793,8 @@ def main():
     }
     if not args.no_rows:
         line["rows"] = side_rows(ex, gen, torch, cfg, C, nch, valid, state, grads, out, stream, wall * 1e3 / K)
+        if "pack" in line["rows"]:   # the plain device copy of this library, measured in the same run
+            line["roofline"]["frac_of_measured_device_copy"] = achieved / line["rows"]["pack"]["GB/s"]
     if not args.no_cpu_baseline:
         line["cpu_baseline"] = cpu_baseline(cfg, valid[0], budget_elems=32 * 64 * gen.Mi)
     print(json.dumps(line), flush=True)

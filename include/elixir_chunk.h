@@ -227,7 +227,9 @@ int elixir_chunk_adam_step_multi(int n_chunks, float* const* d_master, float* co
  *   elixir_offload_bind_streams : call once per pair of copy streams, before their first copies and
  *       after registering slots.  The runtime assigns a DMA engine to a stream at its first copy; this
  *       call issues the first copies so that uploads and downloads land on different engines and can
- *       run at the same time, then measures whether they do (*overlapped_out = 1/0, may be NULL).
+ *       run at the same time, then measures whether they do (*overlapped_out = 1/0, may be NULL; up to
+ *       three attempts).  The flag describes the moment of the call: the runtime may move a stream to
+ *       another engine later, and pipelines whose bind reported 0 have still reached the bidirectional rate.
  *       It overwrites slot 0, allocates and frees a pinned scratch buffer, and waits for both streams.
  * No other call blocks the host.  h_block should be pinned (elixir_host_alloc) for
  * the copies to be asynchronous and at link speed.
