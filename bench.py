@@ -27,18 +27,19 @@ BYTES_PER_ELEM = 28         # 2 (bf16 grad) + 12 (read p, m, v) + 12 (write p, m
 STAGGER_BYTES = (4 << 20) + 8192   # gap between the arrays of a chunk, see chunk_buffers()
 
 
-def chunk_buffers(torch, dev, nch, C):
-    """Device buffers of nch chunks: fp32 master, m, v and two bf16 arrays (gradient, parameter copy) per chunk.
+def chunk_buffers(torch, dev, nch, C, n32=3):
+    """Device buffers of nch chunks: n32 fp32 arrays (master, m, v and, with n32=4, the fp32 gradient chunk) and two
+    bf16 arrays (gradient, parameter copy) per chunk.
     Where the buffers sit is the caller's choice; arrays that start at the same offset modulo a few MiB make the
     eight streams of the AdamW kernel cross DRAM pages in phase and cost ~2% of bandwidth (measured), so every
-    array is followed by a 4 MiB + 8 KiB gap.  Returns (state[c] = (master, m, v), grad16[c], out16[c])."""
+    array is followed by a 4 MiB + 8 KiB gap.  Returns (state[c] = (master, m, v[, grad32]), grad16[c], out16[c])."""
     gap32, gap16 = STAGGER_BYTES // 4, STAGGER_BYTES // 2
-    flat32 = torch.zeros(nch * 3 * (C + gap32), dtype=torch.float32, device=dev)
+    flat32 = torch.zeros(nch * n32 * (C + gap32), dtype=torch.float32, device=dev)
     flat16 = torch.zeros(nch * 2 * (C + gap16) + gap16, dtype=torch.int16, device=dev)
     state, g16, o16 = [], [], []
     for c in range(nch):
-        b = c * 3 * (C + gap32)
-        state.append(tuple(flat32[b + j * (C + gap32): b + j * (C + gap32) + C] for j in range(3)))
+        b = c * n32 * (C + gap32)
+        state.append(tuple(flat32[b + j * (C + gap32): b + j * (C + gap32) + C] for j in range(n32)))
         g = c * (C + gap16)
         g16.append(flat16[g: g + C])
         o = nch * (C + gap16) + gap16 // 2 + c * (C + gap16)
@@ -310,10 +311,8 @@ def run_clip(args, torch, ex, gen):
     nch, K = len(valid), cfg.micro_batches
     stream = torch.cuda.Stream()
     sh = stream.cuda_stream
-    state, _unused16, out, _keep = chunk_buffers(torch, dev, nch, C)
-    gstride32 = C + STAGGER_BYTES // 4 + 2048
-    gflat = torch.empty(nch * gstride32, dtype=torch.float32, device=dev)
-    gch = [gflat[c * gstride32: c * gstride32 + C] for c in range(nch)]
+    state, _unused16, out, _keep = chunk_buffers(torch, dev, nch, C, n32=4)     # [master | m | v | fp32 gradient chunk]
+    gch = [st[3] for st in state]
     mbs = torch.zeros(K, nch, C, dtype=torch.int16, device=dev)
     pkey = gen.stream_key(gen.BASE_SEED, gen.TAG_PARAM, cfg=cfg.cfg_id)
     for c in range(nch):
