@@ -29,7 +29,6 @@ inline bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_
         if (e_ != hipSuccess) return ::elixir::fail(ELIXIR_EHIP, "launch of %s: %s", what, hipGetErrorString(e_)); \
     } while (0)
 
-constexpr int kBlock = 256;          // threads per workgroup: 4 wavefronts of 64
 constexpr int kNormBlocksPerChunk = 1024;  // fixed, so the reduction tree never depends on the launch
 constexpr int kReduceBlock = 128;          // threads per workgroup of the gradient reduction (4 elements per thread)
 

@@ -1,6 +1,8 @@
 // Context life cycle, error reporting, pinned host memory.
 #include <stdarg.h>
 
+#include <new>
+
 #include "common.hpp"
 
 namespace elixir {

@@ -110,8 +110,9 @@ __global__ __launch_bounds__(1024) void finish_kernel(const double* __restrict__
 // Stage 1b: the gradient reduction of reduce.hip that also leaves the sum of squares of the values it writes, over
 // the valid part of the chunk, in stage[blockIdx.x].  One wavefront per workgroup (256 elements): the 64 lanes are
 // combined with the fixed shuffle tree alone, no LDS and no barrier, so the pass stays as fast as the plain
-// reduction.  A lane adds its four squares in fp32 (a 4-term sum; the norm's tolerance is 1e-5) and everything
-// after that is double.  stage[] depends on the data only.
+// reduction.  Squares and sums are double from the first operation on, as in stage 1 (finite fp32 gradients
+// cannot overflow the sum, so a non-finite norm always means a non-finite gradient).  stage[] depends on the
+// data only.
 constexpr int kFusedBlock = 64;
 
 template <bool ACC, bool FP16>
@@ -119,7 +120,7 @@ __global__ __launch_bounds__(kFusedBlock) void reduce_sumsq_kernel(float* __rest
                                                                   int64_t n4, int64_t valid, float scale,
                                                                   double* __restrict__ stage) {
     const int64_t i = (int64_t)blockIdx.x * kFusedBlock + threadIdx.x;
-    float sq = 0.0f;
+    double x = 0.0;
     if (i < n4) {
         f32x4* D = reinterpret_cast<f32x4*>(dst) + i;
         const u32x2 g = __builtin_nontemporal_load(reinterpret_cast<const u32x2*>(src) + i);
@@ -133,15 +134,11 @@ __global__ __launch_bounds__(kFusedBlock) void reduce_sumsq_kernel(float* __rest
         r.w = reduce_elem<FP16>(a.w, g.y >> 16, scale);
         __builtin_nontemporal_store(r, D);
         const int64_t k = i * 4;
-        if (k + 3 < valid) {
-            sq = r.x * r.x + r.y * r.y + (r.z * r.z + r.w * r.w);
-        } else {
-            if (k + 0 < valid) sq += r.x * r.x;
-            if (k + 1 < valid) sq += r.y * r.y;
-            if (k + 2 < valid) sq += r.z * r.z;
-        }
+        if (k + 0 < valid) x = fma((double)r.x, (double)r.x, x);
+        if (k + 1 < valid) x = fma((double)r.y, (double)r.y, x);
+        if (k + 2 < valid) x = fma((double)r.z, (double)r.z, x);
+        if (k + 3 < valid) x = fma((double)r.w, (double)r.w, x);
     }
-    double x = (double)sq;
 #pragma unroll
     for (int off = 32; off > 0; off >>= 1) x += __shfl_down(x, off, 64);
     if (threadIdx.x == 0) stage[blockIdx.x] = x;
@@ -182,7 +179,7 @@ template <bool ACC, bool FP16>
 void launch_fused(float* dst, const uint16_t* src, int64_t n, int64_t valid, float scale, double* stage, double* slots,
                   hipStream_t s) {
     const int64_t n4 = n / 4;
-    const int64_t blocks = (n4 + kFusedBlock - 1) / kFusedBlock;
+    const int64_t blocks = (n4 + kFusedBlock - 1) / kFusedBlock;  // < 2^31: the caller checked chunk_elems
     if (blocks > 0)
         hipLaunchKernelGGL((reduce_sumsq_kernel<ACC, FP16>), dim3((unsigned)blocks), dim3(kFusedBlock), 0, s, dst, src, n4, valid, scale, stage);
     int64_t count = blocks;
@@ -244,6 +241,8 @@ extern "C" int elixir_grad_reduce_chunk_sumsq(elixir_ctx* ctx, int chunk_index, 
         return fail(ELIXIR_ECAP, "%s: chunk of %lld elements, context sized for %lld", what, (long long)chunk_elems, (long long)ctx->max_chunk_elems);
     if (lowp_format != ELIXIR_LOWP_BF16 && lowp_format != ELIXIR_LOWP_FP16)
         return fail(ELIXIR_EINVAL, "%s: lowp_format=%d is neither ELIXIR_LOWP_BF16 nor ELIXIR_LOWP_FP16", what, lowp_format);
+    if (chunk_elems / (4 * kFusedBlock) >= 0x7FFFFFFFll)
+        return fail(ELIXIR_ECAP, "%s: a chunk of %lld elements does not fit one launch", what, (long long)chunk_elems);
     hipStream_t s = (hipStream_t)stream;
     double* slots = ctx->d_partials + (int64_t)chunk_index * kNormBlocksPerChunk;
     if (chunk_elems == 0) {  // nothing to reduce: the chunk contributes zero

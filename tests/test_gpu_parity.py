@@ -777,6 +777,36 @@ def test_whole_step_replays_from_a_hip_graph(ctx):
 
 # --------------------------------------------------------------------------- reduction fused with the norm
 
+def test_norm_paths_agree_on_huge_and_non_finite_gradients(ctx):
+    """Finite gradients whose squares overflow fp32 still give a finite norm (the sums are double from the first
+    operation), on both paths; one Inf or NaN makes both norms non-finite (the overflow signal of loss scaling)."""
+    n = 100_000
+    big = np.full(n, 0x6A00, np.uint16)                       # bf16 2^85: the square overflows fp32
+    want = (2.0 ** 85) * np.sqrt(n)
+    for poison in (None, 0x7F80, 0x7FC0):                     # nothing, +Inf, NaN in one element
+        g = big.copy()
+        if poison is not None:
+            g[n // 3] = poison
+        d_g = dev(g)
+        plain = torch.zeros(n, dtype=torch.float32, device=DEV)
+        fused = torch.zeros(n, dtype=torch.float32, device=DEV)
+        d_a = torch.zeros(2, dtype=torch.float32, device=DEV)
+        d_b = torch.zeros(2, dtype=torch.float32, device=DEV)
+        ex.elixir_grad_reduce_into_chunk(plain, 0, d_g, n, 1.0, False)
+        ex.elixir_chunk_grad_norm(ctx, [plain], [n], 1.0, d_a[0:1], d_a[1:2])
+        ex.elixir_grad_reduce_chunk_sumsq(ctx, 0, fused, d_g, 0, n, n, 1.0, False)
+        ex.elixir_chunk_grad_norm_finish(ctx, 1, 1.0, d_b[0:1], d_b[1:2])
+        sync()
+        a, b = host(d_a), host(d_b)
+        if poison is None:
+            assert np.isfinite(a[0]) and np.isfinite(b[0])
+            assert a[0] == pytest.approx(want, rel=1e-6) and b[0] == pytest.approx(want, rel=1e-6)
+            assert a[1] == pytest.approx(1.0 / want, rel=1e-5) and b[1] == pytest.approx(1.0 / want, rel=1e-5)
+        else:
+            assert not np.isfinite(a[0]) and not np.isfinite(b[0])
+            assert np.isnan(a[0]) == np.isnan(b[0])
+
+
 @pytest.mark.parametrize("fmt", [0, 1])
 def test_fused_reduce_sumsq_matches_plain_reduce_and_oracle_norm(ctx, fmt):
     lens = [(1 << 20, 1 << 20), (777_777, 700_001), (511, 511), (513, 2), (4, 0), (0, 0), (300_003, 300_003)]
