@@ -136,6 +136,28 @@ def side_rows(ex, gen, torch, cfg, C, nch, valid, state, grads, out, stream, ste
     rows["grad_reduce_first"] = {"what": "bf16 -> fp32 chunk, overwrite", "bytes": 6 * C, "GB/s": 6 * C / t / 1e9}
     t = timed(lambda: ex.elixir_grad_reduce_into_chunk(dst, 0, g16, C, 0.25, True, sh), 10)
     rows["grad_reduce_accumulate"] = {"what": "bf16 + fp32 chunk -> fp32 chunk", "bytes": 10 * C, "GB/s": 10 * C / t / 1e9}
+    # the reduction as gradients really arrive, tensor by tensor (a tensor that spans chunks in pieces): one call each against
+    # one batched call for all of them; the momentum buffers stand in for the fp32 gradient chunks
+    cid, off, _ = ex.elixir_layout_plan(cfg.numels(), C, ex.ELIXIR_LAYOUT_NEXT_FIT, 1)
+    pieces = []
+    for i, n in enumerate(cfg.numels()):
+        c, o, left = cid[i], off[i], n
+        while left > 0:
+            take = min(left, C - o)
+            pieces.append((state[c][1][o:o + take], grads[0][c][o:o + take], take))
+            left, c, o = left - take, c + 1, 0
+    p_dst, p_src, p_n = [p[0] for p in pieces], [p[1] for p in pieces], [p[2] for p in pieces]
+
+    def per_tensor():
+        for d, g, n in pieces:
+            ex.elixir_grad_reduce_into_chunk(d, 0, g, n, 0.25, False, sh)
+
+    t_each = timed(per_tensor, 3)
+    t_multi = timed(lambda: ex.elixir_grad_reduce_multi_lp(p_dst, p_src, p_n, ex.ELIXIR_LOWP_BF16, 0.25, False, sh), 3)
+    rows["grad_reduce_per_tensor"] = {"what": f"bf16 -> fp32, overwrite, the {len(pieces)} tensor pieces of the set: one call per tensor against "
+                                              "one elixir_grad_reduce_multi_lp call", "bytes": 6 * sum(p_n),
+                                      "one_call_per_tensor_ms": t_each * 1e3, "one_call_per_tensor_GB/s": 6 * sum(p_n) / t_each / 1e9,
+                                      "ms": t_multi * 1e3, "GB/s": 6 * sum(p_n) / t_multi / 1e9}
     # the fp16 variant of the update (same traffic: 16-bit gradient in, 16-bit copy out), with the loss-scale state on the device
     lss = torch.zeros(4, dtype=torch.float32, device=dev)
     ex.elixir_loss_scale_init(lss, 65536.0, sh)

@@ -269,6 +269,15 @@ typedef struct {
 } elixir_loss_scale_state;
 int elixir_grad_reduce_into_chunk_lp(float* d_grad_chunk, int64_t offset, const uint16_t* d_grad_lowp, int lowp_format,
                                      int64_t n, float scale, int accumulate, elixir_stream_t stream);
+/*
+ * The reduction for many tensors in as few launches as possible (one per 64 tensors): gradients arrive tensor by
+ * tensor and most tensors are small, so one launch each leaves the GPU idle in between.  d_dst[i] points at the
+ * tensor's place inside its fp32 gradient chunk (chunk base + offset, computed by the caller), d_grad_lowp[i] at its
+ * n[i] low-precision gradients; all three tables are HOST arrays.  Destinations must not overlap.  Results are
+ * bit-identical to n_tensors calls of elixir_grad_reduce_into_chunk_lp.
+ */
+int elixir_grad_reduce_multi_lp(int n_tensors, float* const* d_dst, const uint16_t* const* d_grad_lowp, const int64_t* n,
+                                int lowp_format, float scale, int accumulate, elixir_stream_t stream);
 int elixir_chunk_adam_step_lp(float* d_master, float* d_exp_avg, float* d_exp_avg_sq, const float* d_grad_fp32,
                               const uint16_t* d_grad_lowp, uint16_t* d_param_lowp, int lowp_format, int64_t n,
                               const elixir_adam_hparams* hp, const float* d_grad_scale, const int32_t* d_skip,

@@ -28,7 +28,7 @@ EXPORTS = (
     "elixir_copy_d2h_async", "elixir_stream_synchronize", "elixir_offload_benefit", "elixir_offload_plan",
     "elixir_rcache_simulate", "elixir_chunk_size_search", "elixir_grad_reduce_into_chunk_lp", "elixir_chunk_adam_step_lp",
     "elixir_chunk_adam_step_multi_lp", "elixir_loss_scale_init", "elixir_loss_scale_update",
-    "elixir_grad_reduce_chunk_sumsq", "elixir_chunk_grad_norm_finish",
+    "elixir_grad_reduce_chunk_sumsq", "elixir_chunk_grad_norm_finish", "elixir_grad_reduce_multi_lp",
 )
 
 
@@ -93,6 +93,7 @@ def lib() -> ctypes.CDLL:
                                                    ctypes.POINTER(elixir_adam_hparams), vp, vp, vp]
         sigs["elixir_grad_reduce_chunk_sumsq"] = [vp, ci, vp, vp, ci, i64, i64, f32, ci, vp]
         sigs["elixir_chunk_grad_norm_finish"] = [vp, ci, f32, vp, vp, vp]
+        sigs["elixir_grad_reduce_multi_lp"] = [ci, ctypes.POINTER(vp), ctypes.POINTER(vp), pi64, ci, f32, ci, vp]
         sigs["elixir_loss_scale_init"] = [vp, f32, vp]
         sigs["elixir_loss_scale_update"] = [vp, vp, f32, f32, f32, ci, vp]
         sigs["elixir_rcache_simulate"] = [pi64, i64, i64, pi64, pi64]
@@ -362,6 +363,12 @@ def elixir_chunk_adam_step_multi_lp(master, exp_avg, exp_avg_sq, grad_fp32, grad
     _check(lib().elixir_chunk_adam_step_multi_lp(len(master), _ptr_array(master), _ptr_array(exp_avg), _ptr_array(exp_avg_sq),
                                                  tab(grad_fp32), tab(grad_lowp), tab(param_lowp), lowp_format, _i64_array(n),
                                                  ctypes.byref(hp), _addr(d_grad_scale), _addr(d_skip), _stream(stream)))
+
+
+def elixir_grad_reduce_multi_lp(dst, grad_lowp, n, lowp_format: int, scale: float, accumulate: bool, stream=None) -> None:
+    """dst[i]: the tensor's slice of its fp32 gradient chunk; grad_lowp[i]: its n[i] 16-bit gradients."""
+    _check(lib().elixir_grad_reduce_multi_lp(len(dst), _ptr_array(dst), _ptr_array(grad_lowp), _i64_array(n), lowp_format, scale,
+                                             1 if accumulate else 0, _stream(stream)))
 
 
 LOSS_SCALE_STATE_BYTES = 16   # float scale, int32 good_steps, int32 skip, float grad_scale

@@ -8,10 +8,12 @@
 //   wait     : compute stream waits for `ready`
 //   evict    : d2h stream waits for an event recorded on the compute stream,
 //              copies back, records `evicted`
-// The two copy directions run on different streams and therefore on different
-// DMA engines, so uploads, downloads and kernels proceed concurrently.
+// The two copy directions run on different streams so that they can use different
+// DMA engines (elixir_offload_bind_streams sees to it) and uploads, downloads and
+// kernels proceed concurrently.
 #include <algorithm>
 #include <chrono>
+#include <new>
 #include <thread>
 
 #include "common.hpp"

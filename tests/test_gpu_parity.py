@@ -170,6 +170,53 @@ def test_grad_reduce_special_values():
     assert np.array_equal(got[~nan].view(np.uint32), want[~nan].view(np.uint32))   # incl. denormals, -0, +-Inf
 
 
+@pytest.mark.parametrize("fmt", [0, 1])
+def test_grad_reduce_multi_is_bit_identical_to_single_calls_and_the_oracle(fmt):
+    """Tensors of very different lengths (a table of more than 64 entries, empty ones, fewer than 4 elements, odd
+    lengths, slices at odd offsets and misaligned gradient pointers) packed back to back into one fp32 chunk."""
+    rng = np.random.default_rng(5)
+    lens = [1 << 20, 0, 3, 1600, 1601, 513, 4, 7, 64, 300_003] + [int(x) for x in rng.integers(1, 5000, size=70)] + [2, 1 << 18]
+    offs = np.concatenate([[0], np.cumsum(lens)])[:-1] + 4            # the chunk starts with 4 untouched elements
+    C = int(offs[-1] + lens[-1] + 5)
+    K = 3
+    want = np.full(C, 1.5, np.float32)
+    d_multi, d_single = dev(want), dev(want)
+    for mb in range(K):
+        gs, d_gs = [], []
+        for i, n in enumerate(lens):
+            x = gen.fill_f32(gen.stream_key(77, gen.TAG_GRAD, mb, i), 0, n, 0.02)
+            g = x.astype(np.float16).view(np.uint16) if fmt else gen.fill_bf16(gen.stream_key(77, gen.TAG_GRAD, mb, i), 0, n, 0.02, zero_pct=2)
+            gs.append(g)
+            pad = np.zeros(n + 1, np.uint16)                         # every third gradient starts 2 bytes off an 8-byte boundary
+            pad[1:] = g
+            d_gs.append(dev(pad)[1:] if i % 3 == 2 else (dev(g) if n else torch.zeros(1, dtype=torch.int16, device=DEV)))
+        ex.elixir_grad_reduce_multi_lp([d_multi[int(o):] for o in offs], d_gs, lens, fmt, 0.3, mb > 0)
+        for i, n in enumerate(lens):
+            ex.elixir_grad_reduce_into_chunk_lp(d_single, int(offs[i]), d_gs[i], fmt, n, 0.3, mb > 0)
+            orc.grad_reduce_into_chunk(want, int(offs[i]), gs[i], 0.3, mb > 0, fmt=fmt)
+    sync()
+    got = host(d_multi)
+    assert np.array_equal(got.view(np.uint32), host(d_single).view(np.uint32))
+    assert np.array_equal(got.view(np.uint32), want.view(np.uint32))
+    assert np.all(got[:4] == 1.5) and np.all(got[-5:] == 1.5)        # nothing outside the slices was touched
+
+
+def test_grad_reduce_multi_errors_and_empty():
+    d = torch.zeros(64, dtype=torch.float32, device=DEV)
+    g = torch.zeros(64, dtype=torch.int16, device=DEV)
+    ex.elixir_grad_reduce_multi_lp([], [], [], 0, 1.0, False)
+    ex.elixir_grad_reduce_multi_lp([d], [g], [0], 0, 1.0, False)
+    for call, code in ((lambda: ex.elixir_grad_reduce_multi_lp([d], [g], [-1], 0, 1.0, False), ex.ELIXIR_EINVAL),
+                       (lambda: ex.elixir_grad_reduce_multi_lp([d], [g], [8], 7, 1.0, False), ex.ELIXIR_EINVAL),
+                       (lambda: ex.elixir_grad_reduce_multi_lp([0], [g], [8], 0, 1.0, False), ex.ELIXIR_EINVAL),
+                       (lambda: ex.elixir_grad_reduce_multi_lp([d.data_ptr() + 2], [g], [8], 0, 1.0, False), ex.ELIXIR_EALIGN)):
+        with pytest.raises(ex.ElixirError) as e:
+            call()
+        assert e.value.code == code
+    sync()
+    assert not host(d).any()
+
+
 # --------------------------------------------------------------------------- norm + clip
 
 def _norm_case(ctx, chunks, valid, max_norm):
