@@ -105,21 +105,27 @@ def test_gpt2_6b_accumulate_norm_clip_step_full_size():
     gch = torch.empty(nch, C, dtype=torch.float32, device=DEV)            # 26.8 GB
     stage = torch.empty(C, dtype=torch.int16, device=DEV)
     ref_g = {c: np.zeros(C, np.float32) for c in sampled}
-    for mb in range(K):
-        key = gen.stream_key(gen.BASE_SEED, gen.TAG_GRAD, 1, mb, cfg.cfg_id)
-        for c in range(nch):
-            if c in sampled:
-                hg = device_grads(stage, valid[c], key, c * C, cfg.grad_std, 0, rng)
-                orc.grad_reduce_into_chunk(ref_g[c], 0, hg, scale, mb > 0)
-            else:
-                stage.zero_()
-                gen.fill_bf16_device(stage.data_ptr(), valid[c], key, c * C, cfg.grad_std, 0)
-            ex.elixir_grad_reduce_into_chunk(gch[c], 0, stage, C, scale, mb > 0)
-    torch.cuda.synchronize()
-    for c in sampled:
-        assert np.array_equal(gch[c].cpu().numpy().view(np.uint32), ref_g[c].view(np.uint32)), f"reduced chunk {c} differs"
     ctx = ex.elixir_ctx_create(0, C, nch)
     try:
+        for mb in range(K):
+            key = gen.stream_key(gen.BASE_SEED, gen.TAG_GRAD, 1, mb, cfg.cfg_id)
+            for c in range(nch):
+                if c in sampled:
+                    hg = device_grads(stage, valid[c], key, c * C, cfg.grad_std, 0, rng)
+                    orc.grad_reduce_into_chunk(ref_g[c], 0, hg, scale, mb > 0)
+                else:
+                    stage.zero_()
+                    gen.fill_bf16_device(stage.data_ptr(), valid[c], key, c * C, cfg.grad_std, 0)
+                if mb < K - 1:
+                    ex.elixir_grad_reduce_into_chunk(gch[c], 0, stage, C, scale, mb > 0)
+                else:   # as bench.py runs it: the last pass also leaves the chunk's sum of squares in the context
+                    ex.elixir_grad_reduce_chunk_sumsq(ctx, c, gch[c], stage, ex.ELIXIR_LOWP_BF16, C, valid[c], scale, True)
+        d_fused = torch.zeros(2, dtype=torch.float32, device=DEV)
+        ex.elixir_chunk_grad_norm_finish(ctx, nch, cfg.max_norm, d_fused[0:1], d_fused[1:2])
+        torch.cuda.synchronize()
+        fused_nc = d_fused.cpu().numpy().copy()
+        for c in sampled:
+            assert np.array_equal(gch[c].cpu().numpy().view(np.uint32), ref_g[c].view(np.uint32)), f"reduced chunk {c} differs"
         d_nc = torch.zeros(2, dtype=torch.float32, device=DEV)
         ex.elixir_chunk_grad_norm(ctx, [gch[c] for c in range(nch)], valid, cfg.max_norm, d_nc[0:1], d_nc[1:2])
         torch.cuda.synchronize()
@@ -132,6 +138,9 @@ def test_gpt2_6b_accumulate_norm_clip_step_full_size():
         print(f"6B norm: gpu {first[0]:.6f} oracle {want:.6f}; clip gpu {first[1]:.8f} oracle {want_coef:.8f}")
         assert abs(first[0] - want) <= 1e-5 * want
         assert abs(first[1] - want_coef) <= 1e-5 * want_coef
+        print(f"6B norm fused into the last reduction pass: {fused_nc[0]:.6f}, clip {fused_nc[1]:.8f}")
+        assert abs(fused_nc[0] - want) <= 1e-5 * want and abs(fused_nc[1] - want_coef) <= 1e-5 * want_coef
+        assert abs(float(fused_nc[0]) - float(first[0])) <= 2e-7 * want
         # mean of 4 gradients of sigma 1e-3 -> sigma 5e-4 per element -> norm ~ 5e-4*sqrt(6.06e9) ~ 38.9: clipping is active
         assert 35.0 < want < 43.0 and want_coef < 0.03
         # the norm of a single chunk (one-chunk call) against the oracle, and the per-chunk sums adding up to the global one
