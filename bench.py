@@ -590,8 +590,10 @@ def run_hybrid(args, torch, ex, gen):
     n_host = args.host_chunks if args.host_chunks > 0 else 16
     n_res = max(1, round(n_host * 2 / 3))                                  # 60 / 40
     nbytes = 3 * C * 4
-    threads = args.host_threads if args.host_threads > 0 else len(os.sched_getaffinity(0))
-    compute, h2d, d2h, gdown, pup = (torch.cuda.Stream() for _ in range(5))
+    cores = len(os.sched_getaffinity(0))
+    threads = args.host_threads if args.host_threads > 0 else max(1, cores - 1)   # one core stays with the thread that drives the copies
+    compute, h2d, d2h, gdown = (torch.cuda.Stream() for _ in range(4))
+    pup = [torch.cuda.Stream(), torch.cuda.Stream()]                              # one upload stream per parameter buffer
     sh = compute.cuda_stream
     ctx = ex.elixir_ctx_create(0, C, 8)
     blocks = [ex.elixir_host_alloc(nbytes) for _ in range(n_host)]
@@ -629,10 +631,11 @@ def run_hybrid(args, torch, ex, gen):
                 if i + 1 < len(chunks):
                     ex.elixir_copy_d2h_async(hgrad[1 - b], grads[chunks[i + 1]], 2 * C, gdown.cuda_stream)
                 if i >= 2:
-                    ex.elixir_stream_synchronize(pup.cuda_stream)          # hparam[b] has left for the GPU
+                    ex.elixir_stream_synchronize(pup[b].cuda_stream)       # hparam[b] (chunk i-2) has left for the GPU
                 ex.elixir_host_adam_step(blocks[c], blocks[c] + 4 * C, blocks[c] + 8 * C, None, hgrad[b], hparam[b], C, hp, 1.0, threads)
-                ex.elixir_copy_h2d_async(out[c], hparam[b], 2 * C, pup.cuda_stream)
-            ex.elixir_stream_synchronize(pup.cuda_stream)
+                ex.elixir_copy_h2d_async(out[c], hparam[b], 2 * C, pup[b].cuda_stream)
+            for q in pup:
+                ex.elixir_stream_synchronize(q.cuda_stream)
 
         def step(n_cpu):
             step_no[0] += 1
@@ -677,7 +680,7 @@ def run_hybrid(args, torch, ex, gen):
         # the CPU update alone: this box's V_c
         hp = ex.make_hparams(cfg.lr, cfg.beta1, cfg.beta2, cfg.eps, cfg.weight_decay, 1)
         vc = {}
-        for T in sorted({1, threads // 2, threads}):
+        for T in sorted({1, threads // 2, threads, cores}):
             if T < 1:
                 continue
             ex.elixir_host_adam_step(blocks[0], blocks[0] + 4 * C, blocks[0] + 8 * C, None, hgrad[0], hparam[0], C, hp, 1.0, T)
