@@ -701,6 +701,49 @@ def test_offload_slot_exhaustion_and_release(ctx):
         ex.elixir_host_free(blk)
 
 
+def test_cpu_update_of_a_host_resident_chunk_through_the_copy_entry_points():
+    """The paper's own treatment of a CPU-resident chunk, end to end on the GPU machine: bf16 gradients come down
+    (elixir_copy_d2h_async), the host cores update the pinned [master|m|v] block (elixir_host_adam_step), the bf16
+    parameters go up (elixir_copy_h2d_async).  Checked against the oracle and against the GPU update of the same chunk."""
+    n = 3 * (1 << 20) + 17
+    steps = 3
+    p0 = gen.fill_f32(gen.stream_key(31, gen.TAG_PARAM), 0, n, 0.02)
+    ref = [p0.copy(), np.zeros(n, np.float32), np.zeros(n, np.float32)]
+    ref_out = np.zeros(n, np.uint16)
+    d_state = [dev(p0), torch.zeros(n, dtype=torch.float32, device=DEV), torch.zeros(n, dtype=torch.float32, device=DEV)]
+    d_out_gpu = torch.zeros(n, dtype=torch.int16, device=DEV)
+    d_out_cpu = torch.zeros(n, dtype=torch.int16, device=DEV)
+    side = torch.cuda.Stream()
+    block = ex.elixir_host_alloc(12 * n)
+    hgrad, hparam = ex.elixir_host_alloc(2 * n), ex.elixir_host_alloc(2 * n)
+    try:
+        hb = np.ctypeslib.as_array(ctypes.cast(block, ctypes.POINTER(ctypes.c_float)), shape=(3, n))
+        hb[0], hb[1:] = p0, 0.0
+        for t in range(1, steps + 1):
+            g = gen.fill_bf16(gen.stream_key(31, gen.TAG_GRAD, t), 0, n, 1e-3, zero_pct=1)
+            d_g = dev(g)
+            sync()
+            ex.elixir_copy_d2h_async(hgrad, d_g, 2 * n, side)
+            ex.elixir_stream_synchronize(side)
+            ex.elixir_host_adam_step(block, block + 4 * n, block + 8 * n, None, hgrad, hparam, n, hp_struct(t), 1.0, 4)
+            ex.elixir_copy_h2d_async(d_out_cpu, hparam, 2 * n, side)
+            ex.elixir_stream_synchronize(side)
+            ex.elixir_chunk_adam_step(d_state[0], d_state[1], d_state[2], None, d_g, d_out_gpu, n, hp_struct(t))
+            oracle_adam_parallel(ref[0], ref[1], ref[2], g, ref_out, step=t)
+        sync()
+        got = [hb[0].copy(), hb[1].copy(), hb[2].copy()]
+        check_adam_close(*got, *ref, lr=HP["lr"], gmax=4e-3, steps=steps, what="CPU-updated block")
+        cpu_bits = host(d_out_cpu).view(np.uint16)
+        check_bf16_copy(cpu_bits, got[0], ref_out, ref[0], lr=HP["lr"], steps=steps, what="parameters sent up by the host")
+        # the GPU's update of the same chunk agrees with the host's to twice the tolerance each has against the oracle
+        gp = host(d_state[0]).astype(np.float64)
+        assert np.all(np.abs(gp - got[0]) <= 2e-6 * (np.abs(ref[0]) + steps * HP["lr"]))
+    finally:
+        sync()
+        for b in (block, hgrad, hparam):
+            ex.elixir_host_free(b)
+
+
 def test_offload_bind_streams_makes_copies_overlap(ctx):
     nbytes = 256 << 20
     slots = [torch.zeros(nbytes // 4, dtype=torch.float32, device=DEV) for _ in range(2)]
