@@ -277,8 +277,9 @@ def _event_time(torch, stream, fn, reps, warm=1):
 
 
 def run_sweep(args, torch, ex, gen):
-    """Chunk-size sweep on the 1.5B set: padding waste of the three grouping policies and AdamW throughput
-    (next-fit layout, ragged final chunks included) per chunk size.  One JSON line per size."""
+    """Chunk-size sweep on the 1.5B set: padding waste of the three grouping policies and AdamW throughput per chunk size
+    with the tensors placed first-fit in declaration order (what the benchmark definition asks for) and next-fit (the
+    paper's grouping); ragged final chunks included.  One JSON line per size; `value` is the first-fit figure."""
     cfg = gen.CONFIGS["gpt2_1p5b"]
     dev = torch.device("cuda:0")
     stream = torch.cuda.Stream()
@@ -286,41 +287,50 @@ def run_sweep(args, torch, ex, gen):
     for C in gen.SWEEP_CHUNK_ELEMS:
         plans = {name: ex.elixir_layout_plan(cfg.numels(), C, pol, 1)[2] for name, pol in
                  (("next_fit", ex.ELIXIR_LAYOUT_NEXT_FIT), ("first_fit", ex.ELIXIR_LAYOUT_FIRST_FIT), ("dense", ex.ELIXIR_LAYOUT_DENSE))}
-        valid = plans["next_fit"]
-        nch = len(valid)
-        state, grads, out, keep = chunk_buffers(torch, dev, nch, C)
-        pkey = gen.stream_key(gen.BASE_SEED, gen.TAG_PARAM, cfg=3)
-        gkey = gen.stream_key(gen.BASE_SEED, gen.TAG_GRAD, 1, 0, 3)
-        for c in range(nch):
-            gen.fill_f32_device(state[c][0].data_ptr(), valid[c], pkey, c * C, cfg.param_std)
-            gen.fill_bf16_device(grads[c].data_ptr(), valid[c], gkey, c * C, cfg.grad_std, cfg.grad_zero_pct)
-        step_no = [0]
         use_multi = args.multi or C <= 16 * gen.Mi
-
-        def step():
-            step_no[0] += 1
-            hp = ex.make_hparams(cfg.lr, cfg.beta1, cfg.beta2, cfg.eps, cfg.weight_decay, step_no[0])
-            if use_multi:
-                ex.elixir_chunk_adam_step_multi([st[0] for st in state], [st[1] for st in state], [st[2] for st in state], None,
-                                                grads, out, [C] * nch, hp, None, sh)
-                return
+        timed = {}
+        for policy in ("first_fit", "next_fit"):
+            valid = plans[policy]
+            same = [k for k, v in timed.items() if plans[k] == valid]
+            if same:                                   # the same chunks: nothing new to time
+                timed[policy] = dict(timed[same[0]], same_layout_as=same[0])
+                continue
+            nch = len(valid)
+            state, grads, out, keep = chunk_buffers(torch, dev, nch, C)
+            pkey = gen.stream_key(gen.BASE_SEED, gen.TAG_PARAM, cfg=3)
+            gkey = gen.stream_key(gen.BASE_SEED, gen.TAG_GRAD, 1, 0, 3)
             for c in range(nch):
-                ex.elixir_chunk_adam_step(state[c][0], state[c][1], state[c][2], None, grads[c], out[c], C, hp, None, sh)
+                gen.fill_f32_device(state[c][0].data_ptr(), valid[c], pkey, c * C, cfg.param_std)
+                gen.fill_bf16_device(grads[c].data_ptr(), valid[c], gkey, c * C, cfg.grad_std, cfg.grad_zero_pct)
+            step_no = [0]
 
-        wall, ev = _event_time(torch, stream, step, args.steps, args.warmup)
+            def step():
+                step_no[0] += 1
+                hp = ex.make_hparams(cfg.lr, cfg.beta1, cfg.beta2, cfg.eps, cfg.weight_decay, step_no[0])
+                if use_multi:
+                    ex.elixir_chunk_adam_step_multi([st[0] for st in state], [st[1] for st in state], [st[2] for st in state], None,
+                                                    grads, out, [C] * nch, hp, None, sh)
+                    return
+                for c in range(nch):
+                    ex.elixir_chunk_adam_step(state[c][0], state[c][1], state[c][2], None, grads[c], out[c], C, hp, None, sh)
+
+            wall, ev = _event_time(torch, stream, step, args.steps, args.warmup)
+            timed[policy] = {"n_chunks": nch, "ms_per_step": wall * 1e3, "params_per_s": sum(valid) / wall,
+                             "elements_per_s": nch * C / wall, "ms_per_chunk": ev / nch * 1e3,
+                             "GB/s": BYTES_PER_ELEM * C / (ev / nch) / 1e9}
+            del state, grads, out, keep
+            torch.cuda.empty_cache()
+        ff = timed["first_fit"]
         print(json.dumps({
-            "metric": "chunked AdamW params/sec", "value": sum(valid) / wall, "unit": "params/s", "n_gpus": 1,
-            "steps": args.steps, "warmup": args.warmup, "ms_per_step": wall * 1e3, "dtype": "f32", "data": "synthetic",
-            "config": {"workload": f"gpt2-1.5B sweep/C={C >> 20}Mi", "chunk_elems": C, "n_chunks": nch, "layout": "next-fit",
+            "metric": "chunked AdamW params/sec", "value": ff["params_per_s"], "unit": "params/s", "n_gpus": 1,
+            "steps": args.steps, "warmup": args.warmup, "ms_per_step": ff["ms_per_step"], "dtype": "f32", "data": "synthetic",
+            "config": {"workload": f"gpt2-1.5B sweep/C={C >> 20}Mi", "chunk_elems": C, "n_chunks": ff["n_chunks"], "layout": "first-fit",
                        "launch": "multi" if use_multi else "per chunk"},
             "padding_waste": {k: 1.0 - sum(v) / (len(v) * C) for k, v in plans.items()},
             "n_chunks_by_policy": {k: len(v) for k, v in plans.items()},
-            "elements_per_s": nch * C / wall,
-            "roofline": {"bound": "hbm", "achieved": BYTES_PER_ELEM * C / (ev / nch) / 1e9, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                         "frac": BYTES_PER_ELEM * C / (ev / nch) / 1e9 / HBM_PEAK_GBPS, "traffic": None,
-                         "ms_per_chunk": ev / nch * 1e3}}), flush=True)
-        del state, grads, out, keep
-        torch.cuda.empty_cache()
+            "elements_per_s": ff["elements_per_s"], "by_layout": timed,
+            "roofline": {"bound": "hbm", "achieved": ff["GB/s"], "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                         "frac": ff["GB/s"] / HBM_PEAK_GBPS, "traffic": None, "ms_per_chunk": ff["ms_per_chunk"]}}), flush=True)
 
 
 def run_clip(args, torch, ex, gen):
