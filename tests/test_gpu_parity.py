@@ -311,6 +311,64 @@ def test_adam_single_step_sizes(grad_kind, n):
     check_bf16_copy(host(d_out, np.uint16)[:n], host(d[0]), out, p, lr=HP["lr"])
 
 
+def test_adam_randomized_call_configurations():
+    """Forty seeded draws over everything a call can vary: length, where each of the five buffers starts relative to
+    an 8-byte boundary (equal shifts take the vector kernel after a peeled head, unequal ones the one-element kernel),
+    gradient kind, format, with and without the low-precision copy, gradient scale, skip flag, step number -- through
+    the single-chunk call and, for the same inputs, the batched call.  Each against the oracle."""
+    rng = np.random.default_rng(20221205)
+    for case in range(40):
+        n = int(rng.choice([1, 2, 3, 5, 127, 128, 129, 255, 4097, int(rng.integers(6, 150_000))]))
+        fmt = int(rng.integers(0, 2))
+        grad_fp32 = bool(rng.integers(0, 2))
+        with_out = bool(rng.integers(0, 4))
+        shifts = [int(rng.integers(0, 2))] * 5 if rng.integers(0, 3) else [int(x) for x in rng.integers(0, 4, size=5)]
+        scale = float(rng.choice([1.0, 0.0257, 3.0])) if rng.integers(0, 2) else None
+        skip = int(rng.integers(0, 4) == 0)
+        step = int(rng.integers(1, 3000))
+        what = f"case {case}: n={n} fmt={fmt} grad_fp32={grad_fp32} out={with_out} shifts={shifts} scale={scale} skip={skip} step={step}"
+        N = n + 4
+        p, m, v = _adam_state(N, 1000 + case, zero_moments=False)
+        x = gen.fill_f32(gen.stream_key(1000 + case, gen.TAG_GRAD, 1), 0, N, 1e-3)
+        g16 = x.astype(np.float16).view(np.uint16) if fmt else gen.fill_bf16(gen.stream_key(1000 + case, gen.TAG_GRAD, 1), 0, N, 1e-3, zero_pct=2)
+        g = x if grad_fp32 else g16
+        sl = [slice(sh, sh + n) for sh in shifts]
+        gmax = 6e-3 * (scale or 1.0)
+        for multi in (False, True):
+            d_p, d_m, d_v, d_g = dev(p), dev(m), dev(v), dev(g)
+            d_out = torch.full((N,), 0x1234, dtype=torch.int16, device=DEV)
+            d_scale = dev(np.array([scale], np.float32)) if scale is not None else None
+            d_skip = dev(np.array([skip], np.int32))
+            hp = hp_struct(step)
+            args = (d_p[sl[0]], d_m[sl[1]], d_v[sl[2]], d_g[sl[3]] if grad_fp32 else None, None if grad_fp32 else d_g[sl[3]],
+                    d_out[sl[4]] if with_out else None)
+            if multi:
+                ex.elixir_chunk_adam_step_multi_lp(*[None if a is None else [a] for a in args], fmt, [n], hp, d_scale, d_skip)
+            else:
+                ex.elixir_chunk_adam_step_lp(*args, fmt, n, hp, d_scale, d_skip)
+            sync()
+            rp, rm, rv, rout = p.copy(), m.copy(), v.copy(), np.full(N, 0x1234, np.uint16)
+            if not skip:
+                orc.chunk_adam_step(rp[sl[0]], rm[sl[1]], rv[sl[2]], np.ascontiguousarray(g[sl[3]]), rout[sl[4]] if with_out else None,
+                                    step=step, grad_scale=scale or 1.0, fmt=fmt, **HP)
+            gp, gm, gv, gout = host(d_p), host(d_m), host(d_v), host(d_out, np.uint16)
+            if skip:                                                      # a skipped step changes nothing, bit for bit
+                assert np.array_equal(gp.view(np.uint32), p.view(np.uint32)) and np.array_equal(gm.view(np.uint32), m.view(np.uint32)), what
+                assert np.array_equal(gv.view(np.uint32), v.view(np.uint32)) and np.all(gout == 0x1234), what
+                continue
+            check_adam_close(gp, gm, gv, rp, rm, rv, lr=HP["lr"], gmax=gmax, what=what)
+            if with_out:
+                check_bf16_copy(gout[sl[4]], gp[sl[0]], rout[sl[4]], rp[sl[0]], lr=HP["lr"], what=what, fmt=fmt)
+            for got, ref, k in ((gp, p, 0), (gm, m, 1), (gv, v, 2)):     # nothing outside the slices was written
+                keep = np.ones(N, bool)
+                keep[sl[k]] = False
+                assert np.array_equal(got[keep].view(np.uint32), ref[keep].view(np.uint32)), what
+            keep = np.ones(N, bool)
+            if with_out:
+                keep[sl[4]] = False
+            assert np.all(gout[keep] == 0x1234), what
+
+
 @pytest.mark.parametrize("shift", [1, 2, 3])
 def test_adam_misaligned_buffers_take_the_scalar_kernel(shift):
     n = 70_001
