@@ -62,6 +62,8 @@ def parse():
     ap.add_argument("--unfused-norm", action="store_true", help="gpt2_6b_clip: separate norm pass instead of the one fused into the last reduction")
     ap.add_argument("--host-order", choices=["interleaved", "first"], default="interleaved",
                     help="gpt2_20b_offload: which 60%% of the chunks live in host memory (every 3 of 5, or the first 60%% in schedule order)")
+    ap.add_argument("--whole-chunks", action="store_true", help="update the zero padding behind a chunk's last tensor as well "
+                                                                "(default: a launch covers the valid prefix of its chunk)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-rows", action="store_true", help="skip the per-row side measurements")
     return ap.parse_args()
@@ -303,21 +305,22 @@ def run_sweep(args, torch, ex, gen):
                 gen.fill_f32_device(state[c][0].data_ptr(), valid[c], pkey, c * C, cfg.param_std)
                 gen.fill_bf16_device(grads[c].data_ptr(), valid[c], gkey, c * C, cfg.grad_std, cfg.grad_zero_pct)
             step_no = [0]
+            lens = [C] * nch if args.whole_chunks else list(valid)     # padding is never touched unless asked for
 
             def step():
                 step_no[0] += 1
                 hp = ex.make_hparams(cfg.lr, cfg.beta1, cfg.beta2, cfg.eps, cfg.weight_decay, step_no[0])
                 if use_multi:
                     ex.elixir_chunk_adam_step_multi([st[0] for st in state], [st[1] for st in state], [st[2] for st in state], None,
-                                                    grads, out, [C] * nch, hp, None, sh)
+                                                    grads, out, lens, hp, None, sh)
                     return
                 for c in range(nch):
-                    ex.elixir_chunk_adam_step(state[c][0], state[c][1], state[c][2], None, grads[c], out[c], C, hp, None, sh)
+                    ex.elixir_chunk_adam_step(state[c][0], state[c][1], state[c][2], None, grads[c], out[c], lens[c], hp, None, sh)
 
             wall, ev = _event_time(torch, stream, step, args.steps, args.warmup)
             timed[policy] = {"n_chunks": nch, "ms_per_step": wall * 1e3, "params_per_s": sum(valid) / wall,
-                             "elements_per_s": nch * C / wall, "ms_per_chunk": ev / nch * 1e3,
-                             "GB/s": BYTES_PER_ELEM * C / (ev / nch) / 1e9}
+                             "elements_per_s": sum(lens) / wall, "ms_per_chunk": ev / nch * 1e3,
+                             "GB/s": BYTES_PER_ELEM * sum(lens) / ev / 1e9}
             del state, grads, out, keep
             torch.cuda.empty_cache()
         ff = timed["first_fit"]
@@ -359,14 +362,15 @@ def run_clip(args, torch, ex, gen):
     parts = {}
 
     fused = not args.unfused_norm
+    lens = [C] * nch if args.whole_chunks else list(valid)     # padding (all-zero gradients and state) is never touched unless asked for
 
     def reduce_all():
         for mb in range(K):
             for c in range(nch):
                 if fused and mb == K - 1:       # the last pass also leaves the chunk's sum of squares in the context
-                    ex.elixir_grad_reduce_chunk_sumsq(ctx, c, gch[c], mbs[mb, c], ex.ELIXIR_LOWP_BF16, C, valid[c], 1.0 / K, mb > 0, sh)
+                    ex.elixir_grad_reduce_chunk_sumsq(ctx, c, gch[c], mbs[mb, c], ex.ELIXIR_LOWP_BF16, lens[c], valid[c], 1.0 / K, mb > 0, sh)
                 else:
-                    ex.elixir_grad_reduce_into_chunk(gch[c], 0, mbs[mb, c], C, 1.0 / K, mb > 0, sh)
+                    ex.elixir_grad_reduce_into_chunk(gch[c], 0, mbs[mb, c], lens[c], 1.0 / K, mb > 0, sh)
 
     def norm():
         if fused:
@@ -378,7 +382,7 @@ def run_clip(args, torch, ex, gen):
         step_no[0] += 1
         hp = ex.make_hparams(cfg.lr, cfg.beta1, cfg.beta2, cfg.eps, cfg.weight_decay, step_no[0])
         for c in range(nch):
-            ex.elixir_chunk_adam_step(state[c][0], state[c][1], state[c][2], gch[c], None, out[c], C, hp, d_nc[1:2], sh)
+            ex.elixir_chunk_adam_step(state[c][0], state[c][1], state[c][2], gch[c], None, out[c], lens[c], hp, d_nc[1:2], sh)
 
     def step():
         reduce_all()
@@ -389,13 +393,14 @@ def run_clip(args, torch, ex, gen):
         wall, ev = _event_time(torch, stream, step, args.steps, args.warmup)
         for name, fn in (("reduce", reduce_all), ("norm", norm), ("adam", adam)):
             parts[name] = _event_time(torch, stream, fn, 2, 1)[1]
-        n_el = nch * C
+        n_el = sum(lens)
         step_bytes = (6 + 10 * (K - 1) + 30) * n_el + (0 if fused else 4 * sum(valid))
         print(json.dumps({
             "metric": "chunked AdamW params/sec (4 micro-batches reduced, global norm, clip, step)", "value": sum(valid) / wall,
             "unit": "params/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": wall * 1e3,
             "dtype": "f32", "data": "synthetic",
             "config": {"workload": cfg.name, "params": sum(valid), "chunk_elems": C, "n_chunks": nch, "micro_batches": K,
+                       "processed_elems_per_step": n_el, "padding_updated": bool(args.whole_chunks),
                        "max_norm": cfg.max_norm},
             "norm": float(d_nc[0].item()), "clip_coef": float(d_nc[1].item()),
             "phase_ms": {k: v * 1e3 for k, v in parts.items()},
@@ -764,15 +769,18 @@ def main():
     torch.cuda.synchronize()
 
     p_list, m_list, v_list = [st[0] for st in state], [st[1] for st in state], [st[2] for st in state]
+    # what a launch covers: the chunk's valid prefix (padding is all-zero bits and an update would leave it so: never touched),
+    # or, with --whole-chunks, the padding as well
+    lens = [C] * nch if args.whole_chunks else list(valid)
 
     def one_step(step_no):
         hp = ex.make_hparams(cfg.lr, cfg.beta1, cfg.beta2, cfg.eps, cfg.weight_decay, step_no)
         g = grads[(step_no - 1) % n_sets]
         if args.multi:
-            ex.elixir_chunk_adam_step_multi(p_list, m_list, v_list, None, g, out, [C] * nch, hp, None, sh)
+            ex.elixir_chunk_adam_step_multi(p_list, m_list, v_list, None, g, out, lens, hp, None, sh)
             return
         for c in range(nch):
-            ex.elixir_chunk_adam_step(state[c][0], state[c][1], state[c][2], None, g[c], out[c], C, hp, None, sh)
+            ex.elixir_chunk_adam_step(state[c][0], state[c][1], state[c][2], None, g[c], out[c], lens[c], hp, None, sh)
 
     for w in range(W):
         one_step(w + 1)
@@ -798,24 +806,25 @@ def main():
 
     total_params = sum(valid)
     launches = K * (-(-nch // 64) if args.multi else nch)
-    per_launch_elems = nch * C / (-(-nch // 64)) if args.multi else C
+    per_launch_elems = sum(lens) / (-(-nch // 64) if args.multi else nch)      # average over the launches of a step
     launch_s = ev_ms * 1e-3 / launches                      # average duration of one launch of the AdamW kernel
     achieved = BYTES_PER_ELEM * per_launch_elems / launch_s / 1e9          # GB/s, algorithmic bytes of one launch
     traffic = None
     tpath = os.path.join(ROOT, "profiles", "adam_step_traffic.json")
     if os.path.exists(tpath) and args.workload == "gpt2_1p5b":
-        with open(tpath) as f:
-            traffic = json.load(f).get("hbm_bytes_per_launch")
+        with open(tpath) as f:                                 # counters were read on whole-chunk launches: scale to this run's average launch
+            t = json.load(f)
+            traffic = round(t["hbm_bytes_per_launch"] / t["algorithmic_bytes_per_launch"] * BYTES_PER_ELEM * per_launch_elems)
 
     line = {
         "metric": "chunked AdamW params/sec", "value": total_params * K / wall, "unit": "params/s",
         "n_gpus": 1, "steps": K, "warmup": W, "ms_per_step": wall * 1e3 / K, "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
         "config": {"workload": cfg.name, "params": total_params, "chunk_elems": C, "n_chunks": nch,
-                   "processed_elems_per_step": nch * C, "layout": "next-fit", "grad_dtype": "bf16",
+                   "processed_elems_per_step": sum(lens), "padding_updated": bool(args.whole_chunks), "layout": "next-fit", "grad_dtype": "bf16",
                    "grad_sets_resident": n_sets, "hparams": {"lr": cfg.lr, "betas": [cfg.beta1, cfg.beta2],
                                                              "eps": cfg.eps, "weight_decay": cfg.weight_decay}},
-        "elements_per_s": nch * C * K / wall,
+        "elements_per_s": sum(lens) * K / wall,
         "step_ms_device": {"median": per_step[K // 2], "min": per_step[0], "max": per_step[-1],
                            "what": "HIP events around each of K further steps"},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",

@@ -1,6 +1,9 @@
 // elixir_chunk_adam_step and its variants: host side of the fused AdamW update.
 #include <math.h>
 
+#include <algorithm>
+#include <vector>
+
 #include "adam_kernel.hpp"
 #include "common.hpp"
 
@@ -250,8 +253,7 @@ extern "C" int elixir_chunk_adam_step_multi_lp(int n_chunks, float* const* d_mas
         max_blocks = used_blocks = 0;
         return ELIXIR_OK;
     };
-    for (int k = 0; k < n_chunks; ++k) {
-        if (n[k] == 0) continue;
+    auto make_req = [&](int k) {
         Req r;
         r.p = d_master[k];
         r.m = d_exp_avg[k];
@@ -263,19 +265,33 @@ extern "C" int elixir_chunk_adam_step_multi_lp(int n_chunks, float* const* d_mas
         r.d_scale = d_grad_scale;
         r.d_skip = d_skip;
         r.s = s;
+        return r;
+    };
+    // chunks that qualify for the vector kernel, longest first, so that a table holds chunks of similar length
+    // (the chunks are independent: their order is free)
+    std::vector<int> order;
+    order.reserve((size_t)n_chunks);
+    for (int k = 0; k < n_chunks; ++k) {
+        if (n[k] == 0) continue;
+        const Req r = make_req(k);
         const bool vec = phase(r.p, 4) == 0 && phase(r.m, 4) == 0 && phase(r.v, 4) == 0 && phase(r.g, gsz) == 0 &&
                          (!r.out || phase(r.out, 2) == 0) && n[k] >= kAdamVec;
-        const int64_t pairs = vec ? n[k] / kAdamVec : 0;
-        const int64_t nb = (pairs + kAdamBlock - 1) / kAdamBlock;
+        const int64_t nb = (n[k] / kAdamVec + kAdamBlock - 1) / kAdamBlock;
         if (!vec || nb > kMaxBlocksPerLaunch) {
             // a slice at an odd offset, or a chunk too long for one grid row: the single-chunk path
-            if (const int rc = flush()) return rc;
             if (const int rc = run_single(r, n[k], c)) return rc;
             continue;
         }
-        // every chunk gets a grid row as long as the longest one: start a new launch when the table is full or
-        // when rows of very different length would leave more than ~a quarter of the workgroups without work
-        const int64_t row = nb > max_blocks ? nb : max_blocks;
+        order.push_back(k);
+    }
+    std::stable_sort(order.begin(), order.end(), [&](int a, int b) { return n[a] > n[b]; });
+    for (const int k : order) {
+        const Req r = make_req(k);
+        const int64_t pairs = n[k] / kAdamVec;
+        const int64_t nb = (pairs + kAdamBlock - 1) / kAdamBlock;
+        // every chunk gets a grid row as long as the first (longest) one of its table: start a new launch when the
+        // table is full or when more than ~a quarter of the workgroups would find no work
+        const int64_t row = in_table ? max_blocks : nb;
         const bool wasteful = row * (in_table + 1) - (used_blocks + nb) > (used_blocks + nb) / 4 + 1024;
         if (in_table == kAdamMultiMax || (in_table > 0 && wasteful))
             if (const int rc = flush()) return rc;

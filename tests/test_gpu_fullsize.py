@@ -56,6 +56,10 @@ def test_gpt2_1p5b_sampled_chunks_twenty_steps():
     out = torch.empty(C, dtype=torch.int16, device=DEV)
     for c in sampled:
         state.zero_()
+        out.zero_()
+        # as bench.py launches it: over the chunk's valid prefix (the padding is never touched); the ragged last chunk is
+        # launched over its padding as well, which pins that an update leaves all-zero padding all-zero
+        n_launch = C if c == nch - 1 else valid[c]
         gen.fill_f32_device(state[0].data_ptr(), valid[c], pkey, c * C, cfg.param_std)
         torch.cuda.synchronize()
         ref = state.cpu().numpy()
@@ -65,7 +69,7 @@ def test_gpt2_1p5b_sampled_chunks_twenty_steps():
         for step in range(1, cfg.steps + 1):
             gkey = gen.stream_key(gen.BASE_SEED, gen.TAG_GRAD, step, 0, cfg.cfg_id)
             hg = device_grads(g, valid[c], gkey, c * C, cfg.grad_std, cfg.grad_zero_pct, rng)
-            ex.elixir_chunk_adam_step(state[0], state[1], state[2], None, g, out, C, hp_struct(step))
+            ex.elixir_chunk_adam_step(state[0], state[1], state[2], None, g, out, n_launch, hp_struct(step))
             oracle_adam_parallel(rp, rm, rv, hg, rout, step=step)
         torch.cuda.synchronize()
         got = state.cpu().numpy()
