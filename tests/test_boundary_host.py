@@ -121,3 +121,17 @@ def test_product_does_not_import_the_oracle():
     for f in ("elixir_oracle.py", "elixir_oracle.c"):
         text = open(os.path.join(ROOT, "oracle", f)).read()
         assert "paper_2212_05339_amd" not in text and "libelixir_chunk" not in text
+
+
+def test_bench_refuses_more_than_one_gpu_and_the_product_fails_loudly_without_its_library():
+    import subprocess
+    import sys
+
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True, timeout=120)
+    assert r.returncode == 2 and "one GPU only" in r.stderr and r.stdout == ""
+    # a missing library is an error, never a fallback: load the binding with the path pointing nowhere
+    code = ("import paper_2212_05339_amd.binding as b\n"
+            "b.LIB_PATH = '/nonexistent/libelixir_chunk.so'\n"
+            "try:\n    b.lib()\nexcept RuntimeError as e:\n    print('raised:', e)\n")
+    r = subprocess.run([sys.executable, "-c", code], capture_output=True, text=True, timeout=120, cwd=ROOT)
+    assert r.returncode == 0 and "raised:" in r.stdout and "no fallback" in r.stdout
