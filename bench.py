@@ -731,7 +731,9 @@ def main():
     import paper_2212_05339_amd as ex
     from synth import gen
 
-    ex.lib()   # fail loudly if the HIP library is not built
+    from paper_2212_05339_amd.build import ensure_built
+    ensure_built()   # compiles only if no library is there
+    ex.lib()         # fail loudly if the HIP library is still missing: there is no other path
     assert torch.cuda.is_available(), "bench.py needs an MI355X"
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)

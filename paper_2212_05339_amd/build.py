@@ -61,3 +61,12 @@ def build_synth(verbose: bool = False) -> str:
 if __name__ == "__main__":
     print(build_library(verbose=True))
     print(build_synth(verbose=True))
+
+
+def ensure_built(verbose: bool = False) -> None:
+    """Builds what is missing and nothing else: callers that only want to run (tests, the smoke check, the
+    benchmark) load the libraries that are there and compile only when there are none."""
+    if not os.path.exists(LIB):
+        build_library(verbose)
+    if not os.path.exists(os.path.join(os.path.dirname(_PKG), "synth", "libsynth_gen.so")):
+        build_synth(verbose)

@@ -12,6 +12,12 @@ def pytest_configure(config):
     config.addinivalue_line("markers", "gpu: needs a real MI355X (run with -m gpu)")
 
 
+def pytest_sessionstart(session):
+    # the tests load the libraries that are built; only when there are none they are compiled first
+    from paper_2212_05339_amd.build import ensure_built
+    ensure_built()
+
+
 def _have_gpu():
     try:
         import torch
