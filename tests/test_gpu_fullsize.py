@@ -273,3 +273,73 @@ def test_gpt2_20b_offload_mix_full_size_chunks():
         for b in blocks.values():
             ex.elixir_host_free(b)
         ex.elixir_ctx_destroy(ctx)
+
+
+def test_one_chunk_past_four_gib_per_array():
+    """A single chunk of 1.25 Gi + 3 elements: every fp32 array is longer than 4 GiB, so any 32-bit byte or element
+    arithmetic in a kernel or in the host code would show.  Reduce (plain and fused with the sum of squares), norm,
+    AdamW with fp32 and with bf16 gradients, and pack are run over the whole chunk; results are compared with the
+    oracle on windows at the start, across the 4 GiB byte boundary, and at the odd end, and the norm in full."""
+    n = (1 << 30) + (1 << 28) + 3
+    W = 1 << 19
+    windows = [(0, W), ((1 << 30) - W // 2, W), ((1 << 30) + 12345, W), (n - W - 3, W + 3)]
+    pkey, gkey = gen.stream_key(99, gen.TAG_PARAM), gen.stream_key(99, gen.TAG_GRAD, 1)
+    state = torch.zeros(3, n, dtype=torch.float32, device=DEV)
+    g16 = torch.empty(n, dtype=torch.int16, device=DEV)
+    gch = torch.full((n,), 7.0, dtype=torch.float32, device=DEV)
+    out = torch.zeros(n, dtype=torch.int16, device=DEV)
+    gen.fill_f32_device(state[0].data_ptr(), n, pkey, 0, 0.02)
+    gen.fill_bf16_device(g16.data_ptr(), n, gkey, 0, 1e-3, 1)
+    ctx = ex.elixir_ctx_create(0, n, 2)
+    try:
+        d_a = torch.zeros(2, dtype=torch.float32, device=DEV)
+        d_b = torch.zeros(2, dtype=torch.float32, device=DEV)
+        ex.elixir_grad_reduce_into_chunk(gch, 0, g16, n, 0.5, False)
+        ex.elixir_grad_reduce_into_chunk(gch, 0, g16, n, 0.25, True)
+        ex.elixir_grad_reduce_chunk_sumsq(ctx, 0, gch, g16, ex.ELIXIR_LOWP_BF16, 0, 0, 0.25, True)   # chunk 0 of the step is empty
+        ex.elixir_grad_reduce_chunk_sumsq(ctx, 1, gch, g16, ex.ELIXIR_LOWP_BF16, n, n, 0.25, True)
+        ex.elixir_chunk_grad_norm_finish(ctx, 2, 1.0, d_a[0:1], d_a[1:2])
+        ex.elixir_chunk_grad_norm(ctx, [gch], [n], 1.0, d_b[0:1], d_b[1:2])
+        torch.cuda.synchronize()
+        ref_g = {}
+        for a, w in windows:
+            hg = u16(g16[a:a + w])
+            assert np.array_equal(hg, gen.fill_bf16(gkey, a, w, 1e-3, 1)), f"gradients at {a}"
+            r = np.full(w, 7.0, np.float32)
+            orc.grad_reduce_into_chunk(r, 0, hg, 0.5, False)
+            orc.grad_reduce_into_chunk(r, 0, hg, 0.25, True)
+            orc.grad_reduce_into_chunk(r, 0, hg, 0.25, True)
+            assert np.array_equal(gch[a:a + w].cpu().numpy().view(np.uint32), r.view(np.uint32)), f"reduced window at {a}"
+            ref_g[a] = r
+        want = _oracle_norm_streamed([gch], [n])
+        fused, plain = d_a.cpu().numpy(), d_b.cpu().numpy()
+        print(f"norm of {n} elements: oracle {want:.6f}, fused {fused[0]:.6f}, plain {plain[0]:.6f}")
+        assert abs(fused[0] - want) <= 1e-5 * want and abs(plain[0] - want) <= 1e-5 * want
+        assert abs(float(fused[0]) - float(plain[0])) <= 2e-7 * want
+        assert want == pytest.approx(1e-3 * np.sqrt(0.99 * n), rel=0.01)       # sum of the three passes is 1.0 x g, 1% zeros
+        coef = float(plain[1])
+        # AdamW with the fp32 gradient chunk and the clip coefficient from device memory, then a second step with bf16 gradients
+        before = {a: state[:, a:a + w].cpu().numpy() for a, w in windows}
+        ex.elixir_chunk_adam_step(state[0], state[1], state[2], gch, None, out, n, hp_struct(1), d_b[1:2])
+        ex.elixir_chunk_adam_step(state[0], state[1], state[2], None, g16, out, n, hp_struct(2))
+        torch.cuda.synchronize()
+        for a, w in windows:
+            rp, rm, rv = (before[a][k].copy() for k in range(3))
+            assert np.array_equal(rp, gen.fill_f32(pkey, a, w, 0.02)) and not rm.any() and not rv.any()
+            rout = np.zeros(w, np.uint16)
+            oracle_adam_parallel(rp, rm, rv, ref_g[a], rout, step=1, grad_scale=coef)
+            oracle_adam_parallel(rp, rm, rv, u16(g16[a:a + w]), rout, step=2)
+            got = state[:, a:a + w].cpu().numpy()
+            check_adam_close(got[0], got[1], got[2], rp, rm, rv, lr=HP["lr"], gmax=4e-3, steps=2, what=f"window at {a}")
+            check_bf16_copy(u16(out[a:a + w]), got[0], rout, rp, lr=HP["lr"], steps=2, what=f"window at {a}")
+        # pack: the master array as one tensor into a chunk that starts 5 elements in (an unaligned 5 GiB copy)
+        del gch
+        torch.cuda.empty_cache()
+        chunk = torch.zeros(n + 16, dtype=torch.float32, device=DEV)
+        ex.elixir_chunk_pack(chunk, n + 16, 4, [state[0]], [n], [5])
+        torch.cuda.synchronize()
+        for a, w in windows:
+            assert torch.equal(chunk[5 + a:5 + a + w], state[0, a:a + w]), f"packed window at {a}"
+        assert not chunk[:5].any() and not chunk[5 + n:].any()
+    finally:
+        ex.elixir_ctx_destroy(ctx)
