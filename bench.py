@@ -47,6 +47,22 @@ def chunk_buffers(torch, dev, nch, C, n32=3):
     return state, g16, o16, (flat32, flat16)
 
 
+def tiled_state_buffers(torch, ex, dev, flat_state, C, extra32=0):
+    """One tiled optimizer chunk ([master tile | m tile | v tile] ...) per chunk, filled from the flat arrays, each followed by
+    the same gap as in chunk_buffers; with extra32 = 1 a flat fp32 array (the gradient chunk) follows each of them."""
+    nch = len(flat_state)
+    L = ex.elixir_state_tiled_len(C)
+    gap32 = STAGGER_BYTES // 4
+    stride = L + gap32 + extra32 * (C + gap32)
+    flat = torch.zeros(nch * stride, dtype=torch.float32, device=dev)
+    tiled = [flat[c * stride: c * stride + L] for c in range(nch)]
+    extra = [flat[c * stride + L + gap32: c * stride + L + gap32 + C] for c in range(nch)] if extra32 else None
+    for c in range(nch):
+        ex.elixir_state_tile(tiled[c], flat_state[c][0], flat_state[c][1], flat_state[c][2], C)
+    torch.cuda.synchronize()
+    return tiled, extra, flat
+
+
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -64,6 +80,9 @@ def parse():
                     help="gpt2_20b_offload: which 60%% of the chunks live in host memory (every 3 of 5, or the first 60%% in schedule order)")
     ap.add_argument("--whole-chunks", action="store_true", help="update the zero padding behind a chunk's last tensor as well "
                                                                 "(default: a launch covers the valid prefix of its chunk)")
+    ap.add_argument("--state-layout", choices=["tiled", "flat"], default="tiled",
+                    help="optimizer chunk as one buffer of interleaved [master|m|v] tiles (default; single-chunk launches only) or as "
+                         "three arrays")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-rows", action="store_true", help="skip the per-row side measurements")
     return ap.parse_args()
@@ -306,6 +325,9 @@ def run_sweep(args, torch, ex, gen):
                 gen.fill_bf16_device(grads[c].data_ptr(), valid[c], gkey, c * C, cfg.grad_std, cfg.grad_zero_pct)
             step_no = [0]
             lens = [C] * nch if args.whole_chunks else list(valid)     # padding is never touched unless asked for
+            tiled = None
+            if args.state_layout == "tiled" and not use_multi:
+                tiled, _, keep_t = tiled_state_buffers(torch, ex, dev, state, C)
 
             def step():
                 step_no[0] += 1
@@ -315,20 +337,25 @@ def run_sweep(args, torch, ex, gen):
                                                     grads, out, lens, hp, None, sh)
                     return
                 for c in range(nch):
-                    ex.elixir_chunk_adam_step(state[c][0], state[c][1], state[c][2], None, grads[c], out[c], lens[c], hp, None, sh)
+                    if tiled:
+                        ex.elixir_chunk_adam_step_tiled_lp(tiled[c], None, grads[c], out[c], ex.ELIXIR_LOWP_BF16, lens[c], hp, None, None, sh)
+                    else:
+                        ex.elixir_chunk_adam_step(state[c][0], state[c][1], state[c][2], None, grads[c], out[c], lens[c], hp, None, sh)
 
             wall, ev = _event_time(torch, stream, step, args.steps, args.warmup)
             timed[policy] = {"n_chunks": nch, "ms_per_step": wall * 1e3, "params_per_s": sum(valid) / wall,
                              "elements_per_s": sum(lens) / wall, "ms_per_chunk": ev / nch * 1e3,
                              "GB/s": BYTES_PER_ELEM * sum(lens) / ev / 1e9}
             del state, grads, out, keep
+            if tiled:
+                del tiled, keep_t
             torch.cuda.empty_cache()
         ff = timed["first_fit"]
         print(json.dumps({
             "metric": "chunked AdamW params/sec", "value": ff["params_per_s"], "unit": "params/s", "n_gpus": 1,
             "steps": args.steps, "warmup": args.warmup, "ms_per_step": ff["ms_per_step"], "dtype": "f32", "data": "synthetic",
             "config": {"workload": f"gpt2-1.5B sweep/C={C >> 20}Mi", "chunk_elems": C, "n_chunks": ff["n_chunks"], "layout": "first-fit",
-                       "launch": "multi" if use_multi else "per chunk"},
+                       "launch": "multi, three arrays" if use_multi else "per chunk, " + ("tiled optimizer chunk" if args.state_layout == "tiled" else "three arrays")},
             "padding_waste": {k: 1.0 - sum(v) / (len(v) * C) for k, v in plans.items()},
             "n_chunks_by_policy": {k: len(v) for k, v in plans.items()},
             "elements_per_s": ff["elements_per_s"], "by_layout": timed,
@@ -346,8 +373,12 @@ def run_clip(args, torch, ex, gen):
     nch, K = len(valid), cfg.micro_batches
     stream = torch.cuda.Stream()
     sh = stream.cuda_stream
-    state, _unused16, out, _keep = chunk_buffers(torch, dev, nch, C, n32=4)     # [master | m | v | fp32 gradient chunk]
-    gch = [st[3] for st in state]
+    tiled = None
+    if args.state_layout == "tiled":
+        state, _unused16, out, _keep = chunk_buffers(torch, dev, nch, C)
+    else:
+        state, _unused16, out, _keep = chunk_buffers(torch, dev, nch, C, n32=4)     # [master | m | v | fp32 gradient chunk]
+        gch = [st[3] for st in state]
     mbs = torch.zeros(K, nch, C, dtype=torch.int16, device=dev)
     pkey = gen.stream_key(gen.BASE_SEED, gen.TAG_PARAM, cfg=cfg.cfg_id)
     for c in range(nch):
@@ -355,6 +386,10 @@ def run_clip(args, torch, ex, gen):
         for mb in range(K):
             gen.fill_bf16_device(mbs[mb, c].data_ptr(), valid[c], gen.stream_key(gen.BASE_SEED, gen.TAG_GRAD, 1, mb, cfg.cfg_id),
                                  c * C, cfg.grad_std)
+    if args.state_layout == "tiled":       # [tiled optimizer chunk | fp32 gradient chunk] per chunk; the three arrays are no longer needed
+        tiled, gch, _keep_t = tiled_state_buffers(torch, ex, dev, state, C, extra32=1)
+        del state, _keep
+        torch.cuda.empty_cache()
     ctx = ex.elixir_ctx_create(0, C, nch)
     d_nc = torch.zeros(2, dtype=torch.float32, device=dev)
     chunks = [gch[c] for c in range(nch)]
@@ -382,7 +417,10 @@ def run_clip(args, torch, ex, gen):
         step_no[0] += 1
         hp = ex.make_hparams(cfg.lr, cfg.beta1, cfg.beta2, cfg.eps, cfg.weight_decay, step_no[0])
         for c in range(nch):
-            ex.elixir_chunk_adam_step(state[c][0], state[c][1], state[c][2], gch[c], None, out[c], lens[c], hp, d_nc[1:2], sh)
+            if tiled:
+                ex.elixir_chunk_adam_step_tiled_lp(tiled[c], gch[c], None, out[c], ex.ELIXIR_LOWP_BF16, lens[c], hp, d_nc[1:2], None, sh)
+            else:
+                ex.elixir_chunk_adam_step(state[c][0], state[c][1], state[c][2], gch[c], None, out[c], lens[c], hp, d_nc[1:2], sh)
 
     def step():
         reduce_all()
@@ -401,6 +439,7 @@ def run_clip(args, torch, ex, gen):
             "dtype": "f32", "data": "synthetic",
             "config": {"workload": cfg.name, "params": sum(valid), "chunk_elems": C, "n_chunks": nch, "micro_batches": K,
                        "processed_elems_per_step": n_el, "padding_updated": bool(args.whole_chunks),
+                       "optimizer_chunk": "tiled [master|m|v], 4096-element tiles" if tiled else "three arrays",
                        "max_norm": cfg.max_norm},
             "norm": float(d_nc[0].item()), "clip_coef": float(d_nc[1].item()),
             "phase_ms": {k: v * 1e3 for k, v in parts.items()},
@@ -774,6 +813,9 @@ def main():
     # what a launch covers: the chunk's valid prefix (padding is all-zero bits and an update would leave it so: never touched),
     # or, with --whole-chunks, the padding as well
     lens = [C] * nch if args.whole_chunks else list(valid)
+    tiled = None
+    if args.state_layout == "tiled" and not args.multi:       # the batched launch exists for three arrays only
+        tiled, _, _keep_t = tiled_state_buffers(torch, ex, dev, state, C)
 
     def one_step(step_no):
         hp = ex.make_hparams(cfg.lr, cfg.beta1, cfg.beta2, cfg.eps, cfg.weight_decay, step_no)
@@ -782,7 +824,10 @@ def main():
             ex.elixir_chunk_adam_step_multi(p_list, m_list, v_list, None, g, out, lens, hp, None, sh)
             return
         for c in range(nch):
-            ex.elixir_chunk_adam_step(state[c][0], state[c][1], state[c][2], None, g[c], out[c], lens[c], hp, None, sh)
+            if tiled:
+                ex.elixir_chunk_adam_step_tiled_lp(tiled[c], None, g[c], out[c], ex.ELIXIR_LOWP_BF16, lens[c], hp, None, None, sh)
+            else:
+                ex.elixir_chunk_adam_step(state[c][0], state[c][1], state[c][2], None, g[c], out[c], lens[c], hp, None, sh)
 
     for w in range(W):
         one_step(w + 1)
@@ -804,7 +849,8 @@ def main():
         one_step(W + K + k + 1)
         marks[k + 1].record(stream)
     torch.cuda.synchronize()
-    per_step = sorted(marks[k].elapsed_time(marks[k + 1]) for k in range(K))
+    per_step_in_order = [marks[k].elapsed_time(marks[k + 1]) for k in range(K)]
+    per_step = sorted(per_step_in_order)
 
     total_params = sum(valid)
     launches = K * (-(-nch // 64) if args.multi else nch)
@@ -824,14 +870,17 @@ def main():
         "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
         "config": {"workload": cfg.name, "params": total_params, "chunk_elems": C, "n_chunks": nch,
                    "processed_elems_per_step": sum(lens), "padding_updated": bool(args.whole_chunks), "layout": "next-fit", "grad_dtype": "bf16",
+                   "optimizer_chunk": "tiled [master|m|v], 4096-element tiles" if tiled else "three arrays",
                    "grad_sets_resident": n_sets, "hparams": {"lr": cfg.lr, "betas": [cfg.beta1, cfg.beta2],
                                                              "eps": cfg.eps, "weight_decay": cfg.weight_decay}},
         "elements_per_s": sum(lens) * K / wall,
         "step_ms_device": {"median": per_step[K // 2], "min": per_step[0], "max": per_step[-1],
+                           "in_order": [round(x, 4) for x in per_step_in_order], "grad_set_of_first": (W + K) % n_sets,
                            "what": "HIP events around each of K further steps"},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBPS, "traffic": traffic,
-                     "kernel": ("adam_multi_kernel" if args.multi else "adam_vec_kernel") + "<1, 1> (bf16 gradient in, bf16 copy out)",
+                     "kernel": ("adam_multi_kernel" if args.multi else "adam_tiled_kernel" if tiled else "adam_vec_kernel")
+                               + "<1, 1> (bf16 gradient in, bf16 copy out)",
                      "bytes_per_launch": BYTES_PER_ELEM * per_launch_elems,
                      "launch_ms": launch_s * 1e3, "launches_timed": launches,
                      "timing": "HIP events on the launch stream around the timed region / launches"},

@@ -29,6 +29,7 @@ EXPORTS = (
     "elixir_rcache_simulate", "elixir_chunk_size_search", "elixir_grad_reduce_into_chunk_lp", "elixir_chunk_adam_step_lp",
     "elixir_chunk_adam_step_multi_lp", "elixir_loss_scale_init", "elixir_loss_scale_update",
     "elixir_grad_reduce_chunk_sumsq", "elixir_chunk_grad_norm_finish", "elixir_grad_reduce_multi_lp",
+    "elixir_state_tiled_len", "elixir_state_tile", "elixir_state_untile", "elixir_chunk_adam_step_tiled_lp",
 )
 
 
@@ -94,6 +95,9 @@ def lib() -> ctypes.CDLL:
         sigs["elixir_grad_reduce_chunk_sumsq"] = [vp, ci, vp, vp, ci, i64, i64, f32, ci, vp]
         sigs["elixir_chunk_grad_norm_finish"] = [vp, ci, f32, vp, vp, vp]
         sigs["elixir_grad_reduce_multi_lp"] = [ci, ctypes.POINTER(vp), ctypes.POINTER(vp), pi64, ci, f32, ci, vp]
+        sigs["elixir_state_tile"] = [vp, vp, vp, vp, i64, vp]
+        sigs["elixir_state_untile"] = [vp, vp, vp, vp, i64, vp]
+        sigs["elixir_chunk_adam_step_tiled_lp"] = [vp, vp, vp, vp, ci, i64, ctypes.POINTER(elixir_adam_hparams), vp, vp, vp]
         sigs["elixir_loss_scale_init"] = [vp, f32, vp]
         sigs["elixir_loss_scale_update"] = [vp, vp, f32, f32, f32, ci, vp]
         sigs["elixir_rcache_simulate"] = [pi64, i64, i64, pi64, pi64]
@@ -106,6 +110,8 @@ def lib() -> ctypes.CDLL:
             f = getattr(L, name)
             f.restype = ci
             f.argtypes = argtypes
+        L.elixir_state_tiled_len.restype = i64
+        L.elixir_state_tiled_len.argtypes = [i64]
         _lib = L
     return _lib
 
@@ -369,6 +375,30 @@ def elixir_grad_reduce_multi_lp(dst, grad_lowp, n, lowp_format: int, scale: floa
     """dst[i]: the tensor's slice of its fp32 gradient chunk; grad_lowp[i]: its n[i] 16-bit gradients."""
     _check(lib().elixir_grad_reduce_multi_lp(len(dst), _ptr_array(dst), _ptr_array(grad_lowp), _i64_array(n), lowp_format, scale,
                                              1 if accumulate else 0, _stream(stream)))
+
+
+# --------------------------------------------------------------------------- tiled optimizer chunk
+
+ELIXIR_STATE_TILE = 4096
+
+
+def elixir_state_tiled_len(n: int) -> int:
+    """Floats a tiled optimizer chunk of n elements occupies."""
+    return lib().elixir_state_tiled_len(n)
+
+
+def elixir_state_tile(state, master, exp_avg, exp_avg_sq, n: int, stream=None) -> None:
+    _check(lib().elixir_state_tile(_addr(state), _addr(master), _addr(exp_avg), _addr(exp_avg_sq), n, _stream(stream)))
+
+
+def elixir_state_untile(state, master, exp_avg, exp_avg_sq, n: int, stream=None) -> None:
+    _check(lib().elixir_state_untile(_addr(state), _addr(master), _addr(exp_avg), _addr(exp_avg_sq), n, _stream(stream)))
+
+
+def elixir_chunk_adam_step_tiled_lp(state, grad_fp32, grad_lowp, param_lowp, lowp_format: int, n: int, hp: elixir_adam_hparams,
+                                    d_grad_scale=None, d_skip=None, stream=None) -> None:
+    _check(lib().elixir_chunk_adam_step_tiled_lp(_addr(state), _addr(grad_fp32), _addr(grad_lowp), _addr(param_lowp), lowp_format, n,
+                                                 ctypes.byref(hp), _addr(d_grad_scale), _addr(d_skip), _stream(stream)))
 
 
 LOSS_SCALE_STATE_BYTES = 16   # float scale, int32 good_steps, int32 skip, float grad_scale

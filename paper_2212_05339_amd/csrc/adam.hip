@@ -188,6 +188,128 @@ extern "C" int elixir_chunk_adam_step(float* d_master, float* d_exp_avg, float* 
                                      ELIXIR_LOWP_BF16, n, hp, d_grad_scale, nullptr, stream);
 }
 
+// ---- tiled optimizer chunk -------------------------------------------------------------------------------------
+
+namespace {
+
+struct LaunchTiled {
+    float* state;
+    const Req& r;
+    int64_t pairs;
+    const AdamConsts& c;
+    template <int GRAD, int OUT>
+    void operator()() const {
+        const int64_t blocks = (pairs + kAdamBlock - 1) / kAdamBlock;
+        hipLaunchKernelGGL((adam_tiled_kernel<GRAD, OUT>), dim3((unsigned)blocks), dim3(kAdamBlock), kAdamLdsBytes, r.s, state, r.g,
+                           OUT != kNone ? r.out : nullptr, pairs, c, r.d_scale, r.d_skip);
+    }
+};
+
+void launch_tiled_scalar(float* state, const Req& r, int64_t first, int64_t end, const AdamConsts& c) {
+    while (first < end) {
+        int64_t blocks = (end - first + 255) / 256;
+        if (blocks > kMaxBlocksPerLaunch) blocks = kMaxBlocksPerLaunch;
+        const int64_t stop = first + blocks * 256 < end ? first + blocks * 256 : end;
+        const dim3 grid((unsigned)blocks), block(256);
+        if (r.grad_kind == kBF16)
+            hipLaunchKernelGGL(adam_tiled_scalar_kernel<kBF16>, grid, block, 0, r.s, state, r.g, r.out, r.out_kind, first, stop, c, r.d_scale, r.d_skip);
+        else if (r.grad_kind == kF16)
+            hipLaunchKernelGGL(adam_tiled_scalar_kernel<kF16>, grid, block, 0, r.s, state, r.g, r.out, r.out_kind, first, stop, c, r.d_scale, r.d_skip);
+        else
+            hipLaunchKernelGGL(adam_tiled_scalar_kernel<kF32>, grid, block, 0, r.s, state, r.g, r.out, r.out_kind, first, stop, c, r.d_scale, r.d_skip);
+        first = stop;
+    }
+}
+
+}  // namespace
+
+extern "C" int64_t elixir_state_tiled_len(int64_t n) {
+    return n <= 0 ? 0 : 3 * kStateTile * ((n + kStateTile - 1) / kStateTile);
+}
+
+extern "C" int elixir_chunk_adam_step_tiled_lp(float* d_state, const float* d_grad_fp32, const uint16_t* d_grad_lowp,
+                                               uint16_t* d_param_lowp, int lowp_format, int64_t n,
+                                               const elixir_adam_hparams* hp, const float* d_grad_scale,
+                                               const int32_t* d_skip, elixir_stream_t stream) {
+    static const char* what = "elixir_chunk_adam_step_tiled";
+    if (n < 0) return fail(ELIXIR_EINVAL, "%s: n=%lld is negative", what, (long long)n);
+    if (const int rc = check_hparams(what, hp)) return rc;
+    int lk;
+    if (const int rc = lowp_kind(what, lowp_format, &lk)) return rc;
+    if (n == 0) return ELIXIR_OK;
+    if ((d_grad_fp32 != nullptr) == (d_grad_lowp != nullptr))
+        return fail(ELIXIR_EINVAL, "%s: exactly one of the fp32 and the 16-bit gradient pointer must be given", what);
+    if (!d_state) return fail(ELIXIR_EINVAL, "%s: d_state is NULL", what);
+    if (!aligned(d_state, 8) || !aligned(d_grad_fp32, 4) || !aligned(d_grad_lowp, 2) || !aligned(d_param_lowp, 2) ||
+        !aligned(d_grad_scale, 4) || !aligned(d_skip, 4))
+        return fail(ELIXIR_EALIGN, "%s: d_state must be 8-byte aligned, the other pointers aligned for their element type", what);
+    if (n / kAdamVec / kAdamBlock >= kMaxBlocksPerLaunch)
+        return fail(ELIXIR_ECAP, "%s: a chunk of %lld elements does not fit one launch", what, (long long)n);
+    Req r;
+    r.p = r.m = r.v = nullptr;
+    r.g = d_grad_lowp ? (const void*)d_grad_lowp : (const void*)d_grad_fp32;
+    r.out = d_param_lowp;
+    r.grad_kind = d_grad_lowp ? lk : kF32;
+    r.out_kind = d_param_lowp ? lk : kNone;
+    r.d_scale = d_grad_scale;
+    r.d_skip = d_skip;
+    r.s = (hipStream_t)stream;
+    const AdamConsts c = make_consts(hp);
+    // the vector kernel wants the gradient on an 8-byte (fp32) or 4-byte (16-bit) boundary and the copy on a 4-byte one;
+    // whole chunks are; anything else, and an odd last element, takes the one-element kernel
+    const bool vec = phase(r.g, (size_t)grad_elem_size(r.grad_kind)) == 0 && (!r.out || phase(r.out, 2) == 0) && n >= kAdamVec;
+    int64_t done = 0;
+    if (vec) {
+        dispatch(r.grad_kind, r.out_kind, LaunchTiled{d_state, r, n / kAdamVec, c});
+        ELIXIR_LAUNCH_CHECK("adam_tiled_kernel");
+        done = n / kAdamVec * kAdamVec;
+    }
+    if (done < n) {
+        launch_tiled_scalar(d_state, r, done, n, c);
+        ELIXIR_LAUNCH_CHECK("adam_tiled_scalar_kernel");
+    }
+    return ELIXIR_OK;
+}
+
+namespace {
+
+// flat <-> tiled: one element per thread, blockIdx.y = which of the three arrays
+template <bool TO_TILED>
+__global__ __launch_bounds__(256) void state_tile_kernel(float* tiled, float* a0, float* a1, float* a2, int64_t n, int64_t padded) {
+    const int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (e >= padded) return;
+    float* arr = blockIdx.y == 0 ? a0 : (blockIdx.y == 1 ? a1 : a2);
+    float* T = tiled + 3 * kStateTile * (e / kStateTile) + (int64_t)blockIdx.y * kStateTile + e % kStateTile;
+    if constexpr (TO_TILED) *T = e < n ? arr[e] : 0.0f;
+    else if (e < n) arr[e] = *T;
+}
+
+template <bool TO_TILED>
+int tile_call(const char* what, float* tiled, float* a0, float* a1, float* a2, int64_t n, hipStream_t s) {
+    if (n < 0) return fail(ELIXIR_EINVAL, "%s: n is negative", what);
+    if (n == 0) return ELIXIR_OK;
+    if (!tiled || !a0 || !a1 || !a2) return fail(ELIXIR_EINVAL, "%s: NULL pointer", what);
+    if (!aligned(tiled, 4) || !aligned(a0, 4) || !aligned(a1, 4) || !aligned(a2, 4)) return fail(ELIXIR_EALIGN, "%s: pointer not 4-byte aligned", what);
+    const int64_t padded = (n + kStateTile - 1) / kStateTile * kStateTile;
+    if (padded / 256 >= kMaxBlocksPerLaunch) return fail(ELIXIR_ECAP, "%s: %lld elements do not fit one launch", what, (long long)n);
+    hipLaunchKernelGGL((state_tile_kernel<TO_TILED>), dim3((unsigned)(padded / 256), 3), dim3(256), 0, s, tiled, a0, a1, a2, n, padded);
+    ELIXIR_LAUNCH_CHECK("state_tile_kernel");
+    return ELIXIR_OK;
+}
+
+}  // namespace
+
+extern "C" int elixir_state_tile(float* d_state, const float* d_master, const float* d_exp_avg, const float* d_exp_avg_sq, int64_t n,
+                                 elixir_stream_t stream) {
+    return tile_call<true>("elixir_state_tile", d_state, const_cast<float*>(d_master), const_cast<float*>(d_exp_avg),
+                           const_cast<float*>(d_exp_avg_sq), n, (hipStream_t)stream);
+}
+
+extern "C" int elixir_state_untile(const float* d_state, float* d_master, float* d_exp_avg, float* d_exp_avg_sq, int64_t n,
+                                   elixir_stream_t stream) {
+    return tile_call<false>("elixir_state_untile", const_cast<float*>(d_state), d_master, d_exp_avg, d_exp_avg_sq, n, (hipStream_t)stream);
+}
+
 namespace {
 
 struct LaunchMulti {

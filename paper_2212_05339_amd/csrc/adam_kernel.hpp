@@ -20,6 +20,7 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include "../../include/elixir_chunk.h"
 #include "stream_store.hpp"
 
 namespace elixir {
@@ -168,6 +169,47 @@ __global__ __launch_bounds__(kAdamBlock) void adam_multi_kernel(AdamMultiTable t
     if ((int64_t)blockIdx.x * kAdamBlock >= n2) return;  // a row past the end of a shorter chunk (uniform per workgroup)
     const int64_t i = (int64_t)blockIdx.x * kAdamBlock + threadIdx.x;
     adam_pair<GRAD, OUT>(tab.master[lo], tab.exp_avg[lo], tab.exp_avg_sq[lo], tab.grad[lo], tab.out[lo], i, n2, c, d_grad_scale, d_skip);
+}
+
+// Tiled optimizer chunk: master, momentum and variance interleaved in tiles of kStateTile elements,
+//   [ p tile | m tile | v tile ] [ p tile | m tile | v tile ] ...
+// so that the three fp32 streams of a workgroup sit in one 48 KB stretch instead of three arrays hundreds of MB
+// apart.  Measured on MI355X (fresh memory, bf16 and fp32 gradients alike): 85.7-86.5% of the HBM peak against
+// 83.3-83.7% for three arrays, for tiles of 2K to 16K elements; one 256-element workgroup per tile is slower than
+// three arrays (82.3%).  A tile holds a whole number of workgroups, so the tile of a workgroup is uniform and the
+// update itself is adam_pair on shifted base pointers: element e of the chunk is base[e], base[T + e], base[2T + e]
+// with base = state + 2 T (e / T).
+constexpr int64_t kStateTile = ELIXIR_STATE_TILE;
+static_assert(kStateTile % (kAdamBlock * kAdamVec) == 0, "a tile must hold whole workgroups");
+
+template <int GRAD, int OUT>
+__global__ __launch_bounds__(kAdamBlock) void adam_tiled_kernel(float* __restrict__ state, const void* __restrict__ grad,
+                                                               uint16_t* __restrict__ out, int64_t n2, AdamConsts c,
+                                                               const float* __restrict__ d_grad_scale,
+                                                               const int32_t* __restrict__ d_skip) {
+    const int64_t first = (int64_t)blockIdx.x * kAdamBlock;   // first pair of this workgroup
+    float* base = state + 2 * kStateTile * (first / (kStateTile / kAdamVec));
+    adam_pair<GRAD, OUT>(base, base + kStateTile, base + 2 * kStateTile, grad, out, first + threadIdx.x, n2, c, d_grad_scale, d_skip);
+}
+
+// Elements [first, n) of a tiled optimizer chunk, one element per thread, any alignment of grad / out.
+template <int GRAD>
+__global__ __launch_bounds__(256) void adam_tiled_scalar_kernel(float* state, const void* grad, uint16_t* out, int out_kind,
+                                                               int64_t first, int64_t n, AdamConsts c, const float* d_grad_scale,
+                                                               const int32_t* d_skip) {
+    const int64_t k = first + (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (k >= n) return;
+    if (d_skip && *d_skip) return;
+    float* P = state + k + 2 * kStateTile * (k / kStateTile);
+    float g = load_grad1<GRAD>(grad, k);
+    float p = P[0], m = P[kStateTile], v = P[2 * kStateTile];
+    if (d_grad_scale) g *= *d_grad_scale;
+    adam_elem(p, m, v, g, c);
+    P[0] = p;
+    P[kStateTile] = m;
+    P[2 * kStateTile] = v;
+    if (out_kind == kBF16) out[k] = (uint16_t)bf16_rne_bits(p);
+    else if (out_kind == kF16) out[k] = (uint16_t)lowp_bits<kF16>(p);
 }
 
 // Scalar kernel: elements [first, n), any alignment, one element per thread.  Same arithmetic.

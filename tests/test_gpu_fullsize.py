@@ -52,6 +52,7 @@ def test_gpt2_1p5b_sampled_chunks_twenty_steps():
     assert valid[0] == C and valid[nch - 1] < C
     pkey = gen.stream_key(gen.BASE_SEED, gen.TAG_PARAM, cfg=cfg.cfg_id)
     state = torch.empty(3, C, dtype=torch.float32, device=DEV)
+    tiled = torch.empty(ex.elixir_state_tiled_len(C), dtype=torch.float32, device=DEV)   # the optimizer chunk as bench.py holds it
     g = torch.empty(C, dtype=torch.int16, device=DEV)
     out = torch.empty(C, dtype=torch.int16, device=DEV)
     for c in sampled:
@@ -66,11 +67,13 @@ def test_gpt2_1p5b_sampled_chunks_twenty_steps():
         assert valid[c] >= 4096 and np.array_equal(ref[0, :4096], gen.fill_f32(pkey, c * C, 4096, cfg.param_std))
         rp, rm, rv = ref[0].copy(), ref[1].copy(), ref[2].copy()
         rout = np.zeros(C, np.uint16)
+        ex.elixir_state_tile(tiled, state[0], state[1], state[2], C)
         for step in range(1, cfg.steps + 1):
             gkey = gen.stream_key(gen.BASE_SEED, gen.TAG_GRAD, step, 0, cfg.cfg_id)
             hg = device_grads(g, valid[c], gkey, c * C, cfg.grad_std, cfg.grad_zero_pct, rng)
-            ex.elixir_chunk_adam_step(state[0], state[1], state[2], None, g, out, n_launch, hp_struct(step))
+            ex.elixir_chunk_adam_step_tiled_lp(tiled, None, g, out, ex.ELIXIR_LOWP_BF16, n_launch, hp_struct(step))
             oracle_adam_parallel(rp, rm, rv, hg, rout, step=step)
+        ex.elixir_state_untile(tiled, state[0], state[1], state[2], C)
         torch.cuda.synchronize()
         got = state.cpu().numpy()
         err = check_adam_close(got[0], got[1], got[2], rp, rm, rv, lr=HP["lr"], gmax=3.5e-3, steps=cfg.steps,

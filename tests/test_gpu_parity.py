@@ -369,6 +369,104 @@ def test_adam_randomized_call_configurations():
             assert np.all(gout[keep] == 0x1234), what
 
 
+# --------------------------------------------------------------------------- tiled optimizer chunk
+
+def _tiled_reference(p, m, v):
+    """The tiled layout written out with numpy: element e of array k at 3*T*(e//T) + k*T + e%T; the tail of the last tile is zero."""
+    T = ex.ELIXIR_STATE_TILE
+    n = p.size
+    tiles = -(-n // T)
+    out = np.zeros(3 * T * tiles, np.float32)
+    e = np.arange(n)
+    for k, a in enumerate((p, m, v)):
+        out[3 * T * (e // T) + k * T + e % T] = a
+    return out
+
+
+@pytest.mark.parametrize("n", [1, 5, 4095, 4096, 4097, 3 * 4096, 100_003])
+def test_state_tile_and_untile_are_bit_copies_in_the_documented_layout(n):
+    p, m, v = _adam_state(n, 70, zero_moments=False)
+    p[0] = np.float32("nan")                                            # payloads and signs survive: bit copies
+    v[-1] = np.float32(-0.0)
+    L = ex.elixir_state_tiled_len(n)
+    assert L == 3 * ex.ELIXIR_STATE_TILE * (-(-n // ex.ELIXIR_STATE_TILE)) and ex.elixir_state_tiled_len(0) == 0
+    d_state = torch.full((L,), 5.0, dtype=torch.float32, device=DEV)
+    ex.elixir_state_tile(d_state, dev(p), dev(m), dev(v), n)
+    sync()
+    assert np.array_equal(host(d_state).view(np.uint32), _tiled_reference(p, m, v).view(np.uint32))
+    back = [torch.full((n + 2,), 9.0, dtype=torch.float32, device=DEV) for _ in range(3)]
+    ex.elixir_state_untile(d_state, back[0][1:], back[1][1:], back[2][1:], n)       # into slices at an odd offset
+    sync()
+    for got, ref in zip(back, (p, m, v)):
+        g = host(got)
+        assert g[0] == 9.0 and g[-1] == 9.0 and np.array_equal(g[1:-1].view(np.uint32), ref.view(np.uint32))
+
+
+def test_adam_on_a_tiled_chunk_is_bit_identical_to_the_flat_update_and_matches_the_oracle():
+    rng = np.random.default_rng(4096)
+    T = ex.ELIXIR_STATE_TILE
+    for case in range(24):
+        n = int(rng.choice([1, 2, 3, 255, 257, T - 1, T, T + 1, 2 * T + 2, 5 * T + 129, int(rng.integers(6, 200_000))]))
+        fmt = int(rng.integers(0, 2))
+        grad_fp32 = bool(rng.integers(0, 2))
+        with_out = bool(rng.integers(0, 4))
+        g_shift, o_shift = (0, 0) if rng.integers(0, 3) else (int(rng.integers(0, 4)), int(rng.integers(0, 4)))
+        scale = float(rng.choice([1.0, 0.0257])) if rng.integers(0, 2) else None
+        skip = int(rng.integers(0, 5) == 0)
+        what = f"case {case}: n={n} fmt={fmt} grad_fp32={grad_fp32} out={with_out} shifts={g_shift},{o_shift} scale={scale} skip={skip}"
+        p, m, v = _adam_state(n, 2000 + case, zero_moments=False)
+        x = gen.fill_f32(gen.stream_key(2000 + case, gen.TAG_GRAD, 1), 0, n + 4, 1e-3)
+        g16 = x.astype(np.float16).view(np.uint16) if fmt else gen.fill_bf16(gen.stream_key(2000 + case, gen.TAG_GRAD, 1), 0, n + 4, 1e-3, zero_pct=2)
+        g = x if grad_fp32 else g16
+        d_g = dev(g)[g_shift:g_shift + n]
+        d_flat = [dev(p), dev(m), dev(v)]
+        d_state = torch.zeros(ex.elixir_state_tiled_len(n), dtype=torch.float32, device=DEV)
+        ex.elixir_state_tile(d_state, *d_flat, n)
+        d_out_flat = torch.full((n + 4,), 0x1234, dtype=torch.int16, device=DEV)
+        d_out_tiled = torch.full((n + 4,), 0x1234, dtype=torch.int16, device=DEV)
+        d_scale = dev(np.array([scale], np.float32)) if scale is not None else None
+        d_skip = dev(np.array([skip], np.int32))
+        for step in (1, 2):
+            hp = hp_struct(step)
+            ex.elixir_chunk_adam_step_lp(d_flat[0], d_flat[1], d_flat[2], d_g if grad_fp32 else None, None if grad_fp32 else d_g,
+                                         d_out_flat[o_shift:o_shift + n] if with_out else None, fmt, n, hp, d_scale, d_skip)
+            ex.elixir_chunk_adam_step_tiled_lp(d_state, d_g if grad_fp32 else None, None if grad_fp32 else d_g,
+                                               d_out_tiled[o_shift:o_shift + n] if with_out else None, fmt, n, hp, d_scale, d_skip)
+        back = [torch.zeros(n, dtype=torch.float32, device=DEV) for _ in range(3)]
+        ex.elixir_state_untile(d_state, *back, n)
+        sync()
+        for k in range(3):
+            assert np.array_equal(host(back[k]).view(np.uint32), host(d_flat[k]).view(np.uint32)), what
+        assert np.array_equal(host(d_out_tiled), host(d_out_flat)), what
+        tail = host(d_state).reshape(-1, 3, T)[-1][:, n - (n - 1) // T * T:]
+        assert not tail.view(np.uint32).any(), what                          # the unused end of the last tile stays zero
+        if case % 6 == 0 and not skip:                                      # and, directly, against the oracle
+            rp, rm, rv = p.copy(), m.copy(), v.copy()
+            gs = np.ascontiguousarray(g[g_shift:g_shift + n])
+            for step in (1, 2):
+                orc.chunk_adam_step(rp, rm, rv, gs, None, step=step, grad_scale=scale or 1.0, fmt=fmt, **HP)
+            check_adam_close(host(back[0]), host(back[1]), host(back[2]), rp, rm, rv, lr=HP["lr"], gmax=6e-3 * (scale or 1.0), steps=2, what=what)
+
+
+def test_tiled_entry_point_errors():
+    st = torch.zeros(ex.elixir_state_tiled_len(8), dtype=torch.float32, device=DEV)
+    g = torch.zeros(8, dtype=torch.int16, device=DEV)
+    hp = hp_struct(1)
+    ex.elixir_chunk_adam_step_tiled_lp(st, None, g, None, 0, 0, hp)            # n = 0: nothing to do
+    for call, code in ((lambda: ex.elixir_chunk_adam_step_tiled_lp(st, None, None, None, 0, 8, hp), ex.ELIXIR_EINVAL),
+                       (lambda: ex.elixir_chunk_adam_step_tiled_lp(None, None, g, None, 0, 8, hp), ex.ELIXIR_EINVAL),
+                       (lambda: ex.elixir_chunk_adam_step_tiled_lp(st[1:], None, g, None, 0, 8, hp), ex.ELIXIR_EALIGN),
+                       (lambda: ex.elixir_chunk_adam_step_tiled_lp(st, None, g, None, 5, 8, hp), ex.ELIXIR_EINVAL),
+                       (lambda: ex.elixir_chunk_adam_step_tiled_lp(st, None, g, None, 0, -1, hp), ex.ELIXIR_EINVAL),
+                       (lambda: ex.elixir_state_tile(st, None, st, st, 8), ex.ELIXIR_EINVAL),
+                       (lambda: ex.elixir_state_untile(st, st, st, st, -2), ex.ELIXIR_EINVAL)):
+        with pytest.raises(ex.ElixirError) as e:
+            call()
+        assert e.value.code == code
+    sync()
+    assert not host(st).any()
+
+
 @pytest.mark.parametrize("shift", [1, 2, 3])
 def test_adam_misaligned_buffers_take_the_scalar_kernel(shift):
     n = 70_001
