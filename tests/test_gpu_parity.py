@@ -828,6 +828,52 @@ def test_offload_is_bitwise_identical_to_resident(ctx, n_slots):
             ex.elixir_host_free(b)
 
 
+def test_offload_of_tiled_optimizer_chunks_is_bitwise_identical_to_the_flat_resident_update(ctx):
+    """A host block is just bits: tiled optimizer chunks go through the same prefetch / update / evict pipeline."""
+    C, n_chunks = 3 * ex.ELIXIR_STATE_TILE + 1001, 4
+    L = ex.elixir_state_tiled_len(C)
+    nbytes = 4 * L
+    key = gen.stream_key(gen.BASE_SEED, gen.TAG_PARAM, cfg=6)
+    flat = [[gen.fill_f32(key, (3 * c + j) * C, C, 0.02) for j in range(3)] for c in range(n_chunks)]
+    for c in range(n_chunks):
+        flat[c][2] = np.square(flat[c][2])
+    grads = [dev(gen.fill_bf16(gen.stream_key(gen.BASE_SEED, gen.TAG_GRAD, 2, 0, 6), c * C, C, 1e-3)) for c in range(n_chunks)]
+    ref = [[dev(a) for a in flat[c]] for c in range(n_chunks)]
+    ref_out = torch.zeros(n_chunks, C, dtype=torch.int16, device=DEV)
+    out = torch.zeros(n_chunks, C, dtype=torch.int16, device=DEV)
+    blocks = [ex.elixir_host_alloc(nbytes) for _ in range(n_chunks)]
+    slots = [torch.full((L,), float("nan"), dtype=torch.float32, device=DEV) for _ in range(2)]
+    compute, h2d, d2h = torch.cuda.Stream(), torch.cuda.Stream(), torch.cuda.Stream()
+    try:
+        for c in range(n_chunks):
+            tiled0 = _tiled_reference(*flat[c])                   # held in a name: the address must stay valid during the copy
+            ctypes.memmove(blocks[c], tiled0.ctypes.data, nbytes)
+        ex.elixir_offload_register_slots(ctx, slots, nbytes)
+        for step in (1, 2):
+            hp = hp_struct(step)
+            for c in range(n_chunks):
+                ex.elixir_chunk_adam_step(ref[c][0], ref[c][1], ref[c][2], None, grads[c], ref_out[c], C, hp)
+            sync()
+            with torch.cuda.stream(compute):
+                for c in range(n_chunks):
+                    s_ = ex.elixir_chunk_prefetch(ctx, blocks[c], nbytes, h2d)
+                    ex.elixir_chunk_wait_ready(ctx, s_, compute)
+                    ex.elixir_chunk_adam_step_tiled_lp(slots[s_], None, grads[c], out[c], 0, C, hp, None, None, compute)
+                    ex.elixir_chunk_evict(ctx, s_, blocks[c], nbytes, compute, d2h)
+            sync()
+        for c in range(n_chunks):
+            got = np.empty(L, np.float32)
+            ctypes.memmove(got.ctypes.data, blocks[c], nbytes)
+            want = _tiled_reference(*[host(a) for a in ref[c]])
+            assert np.array_equal(got.view(np.uint32), want.view(np.uint32)), f"chunk {c}"
+        assert np.array_equal(host(out), host(ref_out))
+    finally:
+        sync()
+        ex.elixir_offload_register_slots(ctx, [], 0)
+        for b in blocks:
+            ex.elixir_host_free(b)
+
+
 def test_offload_slot_exhaustion_and_release(ctx):
     nbytes = 4096
     slots = [torch.zeros(1024, dtype=torch.float32, device=DEV) for _ in range(2)]
