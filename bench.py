@@ -47,20 +47,41 @@ def chunk_buffers(torch, dev, nch, C, n32=3):
     return state, g16, o16, (flat32, flat16)
 
 
-def tiled_state_buffers(torch, ex, dev, flat_state, C, extra32=0):
-    """One tiled optimizer chunk ([master tile | m tile | v tile] ...) per chunk, filled from the flat arrays, each followed by
-    the same gap as in chunk_buffers; with extra32 = 1 a flat fp32 array (the gradient chunk) follows each of them."""
-    nch = len(flat_state)
-    L = ex.elixir_state_tiled_len(C)
-    gap32 = STAGGER_BYTES // 4
-    stride = L + gap32 + extra32 * (C + gap32)
-    flat = torch.zeros(nch * stride, dtype=torch.float32, device=dev)
-    tiled = [flat[c * stride: c * stride + L] for c in range(nch)]
-    extra = [flat[c * stride + L + gap32: c * stride + L + gap32 + C] for c in range(nch)] if extra32 else None
+def chunk_groups(torch, dev, nch, parts):
+    """One allocation holding, chunk after chunk, a group of arrays: parts = [(name, dtype, numel, count)], every array
+    followed by the stagger gap.  Returns ({name: [per chunk: tensor, or list of `count` tensors]}, the allocation).
+
+    Why groups: device memory on this part behaves as a few large regions (about 96 GiB each inside a 256 GiB allocation).
+    Measured on whole 64Mi chunks: the AdamW launch takes 266-270 us when the gradient array lies in the same region as the
+    optimizer chunk and 280-283 us when it does not; the accumulate pass of the reduction 197-201 us against 212-217 us for
+    its bf16 source; a write-only array (the parameter copy) in the optimizer chunk's region costs 2% instead.  Arrays that
+    are read together are therefore allocated side by side, the parameter copies elsewhere (out_of_the_way)."""
+    import numpy as np
+    esz = {torch.float32: 4, torch.int16: 2}
+    sizes = [(name, dt, n, cnt, -(-(n * esz[dt]) // 8192) * 8192 + STAGGER_BYTES) for name, dt, n, cnt in parts]
+    group = sum(sz * cnt for *_, cnt, sz in sizes)
+    arena = torch.zeros(nch * group, dtype=torch.uint8, device=dev)
+    out = {name: [] for name, *_ in parts}
     for c in range(nch):
-        ex.elixir_state_tile(tiled[c], flat_state[c][0], flat_state[c][1], flat_state[c][2], C)
-    torch.cuda.synchronize()
-    return tiled, extra, flat
+        off = c * group
+        for name, dt, n, cnt, sz in sizes:
+            views = []
+            for _ in range(cnt):
+                views.append(arena[off: off + n * esz[dt]].view(dt))
+                off += sz
+            out[name].append(views if cnt > 1 else views[0])
+    return out, arena
+
+
+def out_of_the_way(torch, dev, nbytes_needed, make):
+    """Allocates what make() allocates behind a temporary spacer of up to 100 GiB, so that it lands far from what was
+    allocated before (see chunk_groups); the spacer is freed again."""
+    free_b, _ = torch.cuda.mem_get_info()
+    room = int(free_b) - nbytes_needed - (8 << 30)
+    spacer = torch.empty(min(100 << 30, room), dtype=torch.uint8, device=dev) if room > (16 << 30) else None
+    res = make()
+    del spacer
+    return res
 
 
 def parse():
@@ -81,8 +102,7 @@ def parse():
     ap.add_argument("--whole-chunks", action="store_true", help="update the zero padding behind a chunk's last tensor as well "
                                                                 "(default: a launch covers the valid prefix of its chunk)")
     ap.add_argument("--state-layout", choices=["tiled", "flat"], default="tiled",
-                    help="optimizer chunk as one buffer of interleaved [master|m|v] tiles (default; single-chunk launches only) or as "
-                         "three arrays")
+                    help="optimizer chunk as one buffer of interleaved [master|m|v] tiles (default) or as three arrays")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-rows", action="store_true", help="skip the per-row side measurements")
     return ap.parse_args()
@@ -326,12 +346,25 @@ def run_sweep(args, torch, ex, gen):
             step_no = [0]
             lens = [C] * nch if args.whole_chunks else list(valid)     # padding is never touched unless asked for
             tiled = None
-            if args.state_layout == "tiled" and not use_multi:
-                tiled, _, keep_t = tiled_state_buffers(torch, ex, dev, state, C)
+            if args.state_layout == "tiled":       # [tiled optimizer chunk | gradient] side by side, parameter copies elsewhere (see chunk_groups)
+                groups, keep_t = chunk_groups(torch, dev, nch, [("state", torch.float32, ex.elixir_state_tiled_len(C), 1), ("grad", torch.int16, C, 1)])
+                tiled = groups["state"]
+                for c in range(nch):
+                    ex.elixir_state_tile(tiled[c], state[c][0], state[c][1], state[c][2], C)
+                    groups["grad"][c].copy_(grads[c])
+                torch.cuda.synchronize()
+                del state, grads, out, keep
+                torch.cuda.empty_cache()
+                grads = groups["grad"]
+                out_far = out_of_the_way(torch, dev, nch * (2 * C + STAGGER_BYTES), lambda: chunk_groups(torch, dev, nch, [("out", torch.int16, C, 1)]))
+                out, keep, state = out_far[0]["out"], out_far[1], None
 
             def step():
                 step_no[0] += 1
                 hp = ex.make_hparams(cfg.lr, cfg.beta1, cfg.beta2, cfg.eps, cfg.weight_decay, step_no[0])
+                if use_multi and tiled:
+                    ex.elixir_chunk_adam_step_tiled_multi_lp(tiled, None, grads, out, ex.ELIXIR_LOWP_BF16, lens, hp, None, None, sh)
+                    return
                 if use_multi:
                     ex.elixir_chunk_adam_step_multi([st[0] for st in state], [st[1] for st in state], [st[2] for st in state], None,
                                                     grads, out, lens, hp, None, sh)
@@ -355,7 +388,7 @@ def run_sweep(args, torch, ex, gen):
             "metric": "chunked AdamW params/sec", "value": ff["params_per_s"], "unit": "params/s", "n_gpus": 1,
             "steps": args.steps, "warmup": args.warmup, "ms_per_step": ff["ms_per_step"], "dtype": "f32", "data": "synthetic",
             "config": {"workload": f"gpt2-1.5B sweep/C={C >> 20}Mi", "chunk_elems": C, "n_chunks": ff["n_chunks"], "layout": "first-fit",
-                       "launch": "multi, three arrays" if use_multi else "per chunk, " + ("tiled optimizer chunk" if args.state_layout == "tiled" else "three arrays")},
+                       "launch": ("multi, " if use_multi else "per chunk, ") + ("tiled optimizer chunk" if args.state_layout == "tiled" else "three arrays")},
             "padding_waste": {k: 1.0 - sum(v) / (len(v) * C) for k, v in plans.items()},
             "n_chunks_by_policy": {k: len(v) for k, v in plans.items()},
             "elements_per_s": ff["elements_per_s"], "by_layout": timed,
@@ -374,22 +407,34 @@ def run_clip(args, torch, ex, gen):
     stream = torch.cuda.Stream()
     sh = stream.cuda_stream
     tiled = None
+    pkey = gen.stream_key(gen.BASE_SEED, gen.TAG_PARAM, cfg=cfg.cfg_id)
     if args.state_layout == "tiled":
-        state, _unused16, out, _keep = chunk_buffers(torch, dev, nch, C)
+        # per chunk [tiled optimizer chunk | fp32 gradient chunk | the K micro-batch gradients] side by side (see chunk_groups);
+        # the parameter copies elsewhere
+        groups, _keep_g = chunk_groups(torch, dev, nch, [("state", torch.float32, ex.elixir_state_tiled_len(C), 1), ("gch", torch.float32, C, 1),
+                                                       ("mb", torch.int16, C, K)])
+        tiled, gch = groups["state"], groups["gch"]
+        mbs = [[groups["mb"][c][mb] for c in range(nch)] for mb in range(K)]
+        scratch = torch.zeros(3, C, dtype=torch.float32, device=dev)
+        for c in range(nch):
+            scratch[0].zero_()
+            gen.fill_f32_device(scratch[0].data_ptr(), valid[c], pkey, c * C, cfg.param_std)
+            ex.elixir_state_tile(tiled[c], scratch[0], scratch[1], scratch[2], C)
+        torch.cuda.synchronize()
+        del scratch
+        out_far = out_of_the_way(torch, dev, nch * (2 * C + STAGGER_BYTES), lambda: chunk_groups(torch, dev, nch, [("out", torch.int16, C, 1)]))
+        out, _keep_o = out_far[0]["out"], out_far[1]
     else:
         state, _unused16, out, _keep = chunk_buffers(torch, dev, nch, C, n32=4)     # [master | m | v | fp32 gradient chunk]
         gch = [st[3] for st in state]
-    mbs = torch.zeros(K, nch, C, dtype=torch.int16, device=dev)
-    pkey = gen.stream_key(gen.BASE_SEED, gen.TAG_PARAM, cfg=cfg.cfg_id)
+        mbs_flat = torch.zeros(K, nch, C, dtype=torch.int16, device=dev)
+        mbs = [[mbs_flat[mb, c] for c in range(nch)] for mb in range(K)]
+        for c in range(nch):
+            gen.fill_f32_device(state[c][0].data_ptr(), valid[c], pkey, c * C, cfg.param_std)
     for c in range(nch):
-        gen.fill_f32_device(state[c][0].data_ptr(), valid[c], pkey, c * C, cfg.param_std)
         for mb in range(K):
-            gen.fill_bf16_device(mbs[mb, c].data_ptr(), valid[c], gen.stream_key(gen.BASE_SEED, gen.TAG_GRAD, 1, mb, cfg.cfg_id),
+            gen.fill_bf16_device(mbs[mb][c].data_ptr(), valid[c], gen.stream_key(gen.BASE_SEED, gen.TAG_GRAD, 1, mb, cfg.cfg_id),
                                  c * C, cfg.grad_std)
-    if args.state_layout == "tiled":       # [tiled optimizer chunk | fp32 gradient chunk] per chunk; the three arrays are no longer needed
-        tiled, gch, _keep_t = tiled_state_buffers(torch, ex, dev, state, C, extra32=1)
-        del state, _keep
-        torch.cuda.empty_cache()
     ctx = ex.elixir_ctx_create(0, C, nch)
     d_nc = torch.zeros(2, dtype=torch.float32, device=dev)
     chunks = [gch[c] for c in range(nch)]
@@ -403,9 +448,9 @@ def run_clip(args, torch, ex, gen):
         for mb in range(K):
             for c in range(nch):
                 if fused and mb == K - 1:       # the last pass also leaves the chunk's sum of squares in the context
-                    ex.elixir_grad_reduce_chunk_sumsq(ctx, c, gch[c], mbs[mb, c], ex.ELIXIR_LOWP_BF16, lens[c], valid[c], 1.0 / K, mb > 0, sh)
+                    ex.elixir_grad_reduce_chunk_sumsq(ctx, c, gch[c], mbs[mb][c], ex.ELIXIR_LOWP_BF16, lens[c], valid[c], 1.0 / K, mb > 0, sh)
                 else:
-                    ex.elixir_grad_reduce_into_chunk(gch[c], 0, mbs[mb, c], lens[c], 1.0 / K, mb > 0, sh)
+                    ex.elixir_grad_reduce_into_chunk(gch[c], 0, mbs[mb][c], lens[c], 1.0 / K, mb > 0, sh)
 
     def norm():
         if fused:
@@ -796,13 +841,25 @@ def main():
     pkey = gen.stream_key(gen.BASE_SEED, gen.TAG_PARAM, cfg=cfg.cfg_id)
     for c in range(nch):
         gen.fill_f32_device(state[c][0].data_ptr(), valid[c], pkey, c * C, cfg.param_std)
-    # ---- gradients: one set per step where memory allows, else a ring that is cycled ----
-    free_b, _ = torch.cuda.mem_get_info()
-    gstride = C + STAGGER_BYTES // 2
-    set_bytes = nch * gstride * 2
-    n_sets = max(1, min(K + W, int(0.8 * free_b // set_bytes)))
-    gflat = torch.zeros(n_sets * nch * gstride, dtype=torch.int16, device=dev)   # padding stays zero
-    grads = [[gflat[(s * nch + c) * gstride: (s * nch + c) * gstride + C] for c in range(nch)] for s in range(n_sets)]
+    # ---- gradients: a ring of sets that is cycled (each set is far larger than any cache) ----
+    tiled = None
+    if args.state_layout == "tiled":
+        # per chunk [tiled optimizer chunk | gradient sets] side by side; the parameter copies elsewhere
+        n_sets = max(1, min(K + W, 8))
+        groups, _keep_g = chunk_groups(torch, dev, nch, [("state", torch.float32, ex.elixir_state_tiled_len(C), 1), ("grad", torch.int16, C, n_sets)])
+        tiled = groups["state"]
+        grads = [[(groups["grad"][c][s] if n_sets > 1 else groups["grad"][c]) for c in range(nch)] for s in range(n_sets)]
+        for c in range(nch):
+            ex.elixir_state_tile(tiled[c], state[c][0], state[c][1], state[c][2], C)
+        out_far = out_of_the_way(torch, dev, nch * (2 * C + STAGGER_BYTES), lambda: chunk_groups(torch, dev, nch, [("out", torch.int16, C, 1)]))
+        out, _keep_o = out_far[0]["out"], out_far[1]
+    else:
+        free_b, _ = torch.cuda.mem_get_info()
+        gstride = C + STAGGER_BYTES // 2
+        set_bytes = nch * gstride * 2
+        n_sets = max(1, min(K + W, int(0.8 * free_b // set_bytes)))
+        gflat = torch.zeros(n_sets * nch * gstride, dtype=torch.int16, device=dev)   # padding stays zero
+        grads = [[gflat[(s * nch + c) * gstride: (s * nch + c) * gstride + C] for c in range(nch)] for s in range(n_sets)]
     for s in range(n_sets):
         gkey = gen.stream_key(gen.BASE_SEED, gen.TAG_GRAD, s + 1, 0, cfg.cfg_id)
         for c in range(nch):
@@ -813,13 +870,13 @@ def main():
     # what a launch covers: the chunk's valid prefix (padding is all-zero bits and an update would leave it so: never touched),
     # or, with --whole-chunks, the padding as well
     lens = [C] * nch if args.whole_chunks else list(valid)
-    tiled = None
-    if args.state_layout == "tiled" and not args.multi:       # the batched launch exists for three arrays only
-        tiled, _, _keep_t = tiled_state_buffers(torch, ex, dev, state, C)
 
     def one_step(step_no):
         hp = ex.make_hparams(cfg.lr, cfg.beta1, cfg.beta2, cfg.eps, cfg.weight_decay, step_no)
         g = grads[(step_no - 1) % n_sets]
+        if args.multi and tiled:
+            ex.elixir_chunk_adam_step_tiled_multi_lp(tiled, None, g, out, ex.ELIXIR_LOWP_BF16, lens, hp, None, None, sh)
+            return
         if args.multi:
             ex.elixir_chunk_adam_step_multi(p_list, m_list, v_list, None, g, out, lens, hp, None, sh)
             return
@@ -879,8 +936,8 @@ def main():
                            "what": "HIP events around each of K further steps"},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBPS, "traffic": traffic,
-                     "kernel": ("adam_multi_kernel" if args.multi else "adam_tiled_kernel" if tiled else "adam_vec_kernel")
-                               + "<1, 1> (bf16 gradient in, bf16 copy out)",
+                     "kernel": (("adam_multi_kernel<1, 1, true>" if tiled else "adam_multi_kernel<1, 1, false>") if args.multi else
+                                "adam_tiled_kernel<1, 1>" if tiled else "adam_vec_kernel<1, 1>") + " (bf16 gradient in, bf16 copy out)",
                      "bytes_per_launch": BYTES_PER_ELEM * per_launch_elems,
                      "launch_ms": launch_s * 1e3, "launches_timed": launches,
                      "timing": "HIP events on the launch stream around the timed region / launches"},

@@ -214,6 +214,8 @@ int elixir_chunk_adam_step_multi(int n_chunks, float* const* d_master, float* co
  *       zeroed) and back; bit copies, for set-up and checkpoints.
  *   elixir_chunk_adam_step_tiled_lp : elixir_chunk_adam_step_lp on a tiled chunk; bit-identical results.  d_state
  *       must be 8-byte aligned.
+ *   elixir_chunk_adam_step_tiled_multi_lp : elixir_chunk_adam_step_multi_lp on tiled chunks (d_state is a HOST
+ *       array of n_chunks tiled buffers).
  */
 #define ELIXIR_STATE_TILE 4096
 int64_t elixir_state_tiled_len(int64_t n);
@@ -224,6 +226,11 @@ int elixir_state_untile(const float* d_state, float* d_master, float* d_exp_avg,
 int elixir_chunk_adam_step_tiled_lp(float* d_state, const float* d_grad_fp32, const uint16_t* d_grad_lowp,
                                     uint16_t* d_param_lowp, int lowp_format, int64_t n, const elixir_adam_hparams* hp,
                                     const float* d_grad_scale, const int32_t* d_skip, elixir_stream_t stream);
+
+int elixir_chunk_adam_step_tiled_multi_lp(int n_chunks, float* const* d_state, const float* const* d_grad_fp32,
+                                          const uint16_t* const* d_grad_lowp, uint16_t* const* d_param_lowp, int lowp_format,
+                                          const int64_t* n, const elixir_adam_hparams* hp, const float* d_grad_scale,
+                                          const int32_t* d_skip, elixir_stream_t stream);
 
 /*
  * Offload pipeline for chunks whose optimizer chunk lives in host memory (the

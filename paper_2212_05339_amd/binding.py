@@ -30,6 +30,7 @@ EXPORTS = (
     "elixir_chunk_adam_step_multi_lp", "elixir_loss_scale_init", "elixir_loss_scale_update",
     "elixir_grad_reduce_chunk_sumsq", "elixir_chunk_grad_norm_finish", "elixir_grad_reduce_multi_lp",
     "elixir_state_tiled_len", "elixir_state_tile", "elixir_state_untile", "elixir_chunk_adam_step_tiled_lp",
+    "elixir_chunk_adam_step_tiled_multi_lp",
 )
 
 
@@ -98,6 +99,8 @@ def lib() -> ctypes.CDLL:
         sigs["elixir_state_tile"] = [vp, vp, vp, vp, i64, vp]
         sigs["elixir_state_untile"] = [vp, vp, vp, vp, i64, vp]
         sigs["elixir_chunk_adam_step_tiled_lp"] = [vp, vp, vp, vp, ci, i64, ctypes.POINTER(elixir_adam_hparams), vp, vp, vp]
+        sigs["elixir_chunk_adam_step_tiled_multi_lp"] = [ci, ctypes.POINTER(vp), ctypes.POINTER(vp), ctypes.POINTER(vp), ctypes.POINTER(vp),
+                                                         ci, pi64, ctypes.POINTER(elixir_adam_hparams), vp, vp, vp]
         sigs["elixir_loss_scale_init"] = [vp, f32, vp]
         sigs["elixir_loss_scale_update"] = [vp, vp, f32, f32, f32, ci, vp]
         sigs["elixir_rcache_simulate"] = [pi64, i64, i64, pi64, pi64]
@@ -399,6 +402,14 @@ def elixir_chunk_adam_step_tiled_lp(state, grad_fp32, grad_lowp, param_lowp, low
                                     d_grad_scale=None, d_skip=None, stream=None) -> None:
     _check(lib().elixir_chunk_adam_step_tiled_lp(_addr(state), _addr(grad_fp32), _addr(grad_lowp), _addr(param_lowp), lowp_format, n,
                                                  ctypes.byref(hp), _addr(d_grad_scale), _addr(d_skip), _stream(stream)))
+
+
+def elixir_chunk_adam_step_tiled_multi_lp(state, grad_fp32, grad_lowp, param_lowp, lowp_format: int, n, hp: elixir_adam_hparams,
+                                          d_grad_scale=None, d_skip=None, stream=None) -> None:
+    tab = lambda xs: None if xs is None else _ptr_array(xs)
+    _check(lib().elixir_chunk_adam_step_tiled_multi_lp(len(state), _ptr_array(state), tab(grad_fp32), tab(grad_lowp), tab(param_lowp),
+                                                       lowp_format, _i64_array(n), ctypes.byref(hp), _addr(d_grad_scale), _addr(d_skip),
+                                                       _stream(stream)))
 
 
 LOSS_SCALE_STATE_BYTES = 16   # float scale, int32 good_steps, int32 skip, float grad_scale

@@ -319,26 +319,25 @@ struct LaunchMulti {
     const float* d_scale;
     const int32_t* d_skip;
     hipStream_t s;
+    bool tiled;
     template <int GRAD, int OUT>
     void operator()() const {
-        hipLaunchKernelGGL((adam_multi_kernel<GRAD, OUT>), grid, dim3(kAdamBlock), kAdamLdsBytes, s, tab, c, d_scale, d_skip);
+        if (tiled) hipLaunchKernelGGL((adam_multi_kernel<GRAD, OUT, true>), grid, dim3(kAdamBlock), kAdamLdsBytes, s, tab, c, d_scale, d_skip);
+        else hipLaunchKernelGGL((adam_multi_kernel<GRAD, OUT, false>), grid, dim3(kAdamBlock), kAdamLdsBytes, s, tab, c, d_scale, d_skip);
     }
 };
 
-}  // namespace
-
-extern "C" int elixir_chunk_adam_step_multi_lp(int n_chunks, float* const* d_master, float* const* d_exp_avg,
-                                               float* const* d_exp_avg_sq, const float* const* d_grad_fp32,
-                                               const uint16_t* const* d_grad_lowp, uint16_t* const* d_param_lowp,
-                                               int lowp_format, const int64_t* n, const elixir_adam_hparams* hp,
-                                               const float* d_grad_scale, const int32_t* d_skip, elixir_stream_t stream) {
-    static const char* what = "elixir_chunk_adam_step_multi";
+// The batched update.  tiled: d_master[k] is the tiled optimizer chunk of chunk k and the two moment tables are unused.
+int adam_multi(const char* what, bool tiled, int n_chunks, float* const* d_master, float* const* d_exp_avg,
+               float* const* d_exp_avg_sq, const float* const* d_grad_fp32, const uint16_t* const* d_grad_lowp,
+               uint16_t* const* d_param_lowp, int lowp_format, const int64_t* n, const elixir_adam_hparams* hp,
+               const float* d_grad_scale, const int32_t* d_skip, elixir_stream_t stream) {
     if (n_chunks < 0) return fail(ELIXIR_EINVAL, "%s: n_chunks is negative", what);
     if (const int rc = check_hparams(what, hp)) return rc;
     int lk;
     if (const int rc = lowp_kind(what, lowp_format, &lk)) return rc;
     if (n_chunks == 0) return ELIXIR_OK;
-    if (!d_master || !d_exp_avg || !d_exp_avg_sq || !n) return fail(ELIXIR_EINVAL, "%s: NULL table", what);
+    if (!d_master || (!tiled && (!d_exp_avg || !d_exp_avg_sq)) || !n) return fail(ELIXIR_EINVAL, "%s: NULL table", what);
     if ((d_grad_fp32 != nullptr) == (d_grad_lowp != nullptr))
         return fail(ELIXIR_EINVAL, "%s: exactly one of the fp32 and the 16-bit gradient table must be given", what);
     if (!aligned(d_grad_scale, 4) || !aligned(d_skip, 4)) return fail(ELIXIR_EALIGN, "%s: d_grad_scale / d_skip not 4-byte aligned", what);
@@ -350,10 +349,11 @@ extern "C" int elixir_chunk_adam_step_multi_lp(int n_chunks, float* const* d_mas
         if (n[k] < 0) return fail(ELIXIR_EINVAL, "%s: n[%d] is negative", what, k);
         if (n[k] == 0) continue;
         const void* g = lowp_grad ? (const void*)d_grad_lowp[k] : (const void*)d_grad_fp32[k];
-        if (!d_master[k] || !d_exp_avg[k] || !d_exp_avg_sq[k] || !g) return fail(ELIXIR_EINVAL, "%s: NULL pointer in chunk %d", what, k);
-        if (!aligned(d_master[k], 4) || !aligned(d_exp_avg[k], 4) || !aligned(d_exp_avg_sq[k], 4) || !aligned(g, gsz) ||
+        if (!d_master[k] || (!tiled && (!d_exp_avg[k] || !d_exp_avg_sq[k])) || !g) return fail(ELIXIR_EINVAL, "%s: NULL pointer in chunk %d", what, k);
+        if (!aligned(d_master[k], tiled ? 8 : 4) || (!tiled && (!aligned(d_exp_avg[k], 4) || !aligned(d_exp_avg_sq[k], 4))) || !aligned(g, gsz) ||
             (d_param_lowp && !aligned(d_param_lowp[k], 2)))
-            return fail(ELIXIR_EALIGN, "%s: a pointer of chunk %d is not aligned for its element type", what, k);
+            return fail(ELIXIR_EALIGN, "%s: a pointer of chunk %d is not aligned for its element type%s", what, k,
+                        tiled ? " (8 bytes for a tiled optimizer chunk)" : "");
         if (d_param_lowp && !d_param_lowp[k]) return fail(ELIXIR_EINVAL, "%s: the parameter-copy pointer of chunk %d is NULL", what, k);
     }
     const AdamConsts c = make_consts(hp);
@@ -369,7 +369,7 @@ extern "C" int elixir_chunk_adam_step_multi_lp(int n_chunks, float* const* d_mas
             tab.out[j] = nullptr;
             tab.n2[j] = 0;
         }
-        dispatch(grad_kind, out_kind, LaunchMulti{tab, dim3((unsigned)max_blocks, (unsigned)in_table), c, d_grad_scale, d_skip, s});
+        dispatch(grad_kind, out_kind, LaunchMulti{tab, dim3((unsigned)max_blocks, (unsigned)in_table), c, d_grad_scale, d_skip, s, tiled});
         ELIXIR_LAUNCH_CHECK("adam_multi_kernel");
         in_table = 0;
         max_blocks = used_blocks = 0;
@@ -378,8 +378,8 @@ extern "C" int elixir_chunk_adam_step_multi_lp(int n_chunks, float* const* d_mas
     auto make_req = [&](int k) {
         Req r;
         r.p = d_master[k];
-        r.m = d_exp_avg[k];
-        r.v = d_exp_avg_sq[k];
+        r.m = tiled ? nullptr : d_exp_avg[k];
+        r.v = tiled ? nullptr : d_exp_avg_sq[k];
         r.g = lowp_grad ? (const void*)d_grad_lowp[k] : (const void*)d_grad_fp32[k];
         r.out = d_param_lowp ? d_param_lowp[k] : nullptr;
         r.grad_kind = grad_kind;
@@ -396,12 +396,18 @@ extern "C" int elixir_chunk_adam_step_multi_lp(int n_chunks, float* const* d_mas
     for (int k = 0; k < n_chunks; ++k) {
         if (n[k] == 0) continue;
         const Req r = make_req(k);
-        const bool vec = phase(r.p, 4) == 0 && phase(r.m, 4) == 0 && phase(r.v, 4) == 0 && phase(r.g, gsz) == 0 &&
+        const bool vec = (tiled || (phase(r.p, 4) == 0 && phase(r.m, 4) == 0 && phase(r.v, 4) == 0)) && phase(r.g, gsz) == 0 &&
                          (!r.out || phase(r.out, 2) == 0) && n[k] >= kAdamVec;
         const int64_t nb = (n[k] / kAdamVec + kAdamBlock - 1) / kAdamBlock;
         if (!vec || nb > kMaxBlocksPerLaunch) {
             // a slice at an odd offset, or a chunk too long for one grid row: the single-chunk path
-            if (const int rc = run_single(r, n[k], c)) return rc;
+            if (tiled) {
+                if (nb > kMaxBlocksPerLaunch) return fail(ELIXIR_ECAP, "%s: chunk %d of %lld elements does not fit one launch", what, k, (long long)n[k]);
+                launch_tiled_scalar(r.p, r, 0, n[k], c);
+                ELIXIR_LAUNCH_CHECK("adam_tiled_scalar_kernel");
+            } else if (const int rc = run_single(r, n[k], c)) {
+                return rc;
+            }
             continue;
         }
         order.push_back(k);
@@ -427,11 +433,31 @@ extern "C" int elixir_chunk_adam_step_multi_lp(int n_chunks, float* const* d_mas
         if (nb > max_blocks) max_blocks = nb;
         used_blocks += nb;
         if (n[k] % kAdamVec) {  // the odd last element of this chunk
-            launch_scalar(r, pairs * kAdamVec, n[k], c);
+            if (tiled) launch_tiled_scalar(r.p, r, pairs * kAdamVec, n[k], c);
+            else launch_scalar(r, pairs * kAdamVec, n[k], c);
             ELIXIR_LAUNCH_CHECK("adam_scalar_kernel");
         }
     }
     return flush();
+}
+
+}  // namespace
+
+extern "C" int elixir_chunk_adam_step_multi_lp(int n_chunks, float* const* d_master, float* const* d_exp_avg,
+                                               float* const* d_exp_avg_sq, const float* const* d_grad_fp32,
+                                               const uint16_t* const* d_grad_lowp, uint16_t* const* d_param_lowp,
+                                               int lowp_format, const int64_t* n, const elixir_adam_hparams* hp,
+                                               const float* d_grad_scale, const int32_t* d_skip, elixir_stream_t stream) {
+    return adam_multi("elixir_chunk_adam_step_multi", false, n_chunks, d_master, d_exp_avg, d_exp_avg_sq, d_grad_fp32, d_grad_lowp,
+                      d_param_lowp, lowp_format, n, hp, d_grad_scale, d_skip, stream);
+}
+
+extern "C" int elixir_chunk_adam_step_tiled_multi_lp(int n_chunks, float* const* d_state, const float* const* d_grad_fp32,
+                                                     const uint16_t* const* d_grad_lowp, uint16_t* const* d_param_lowp,
+                                                     int lowp_format, const int64_t* n, const elixir_adam_hparams* hp,
+                                                     const float* d_grad_scale, const int32_t* d_skip, elixir_stream_t stream) {
+    return adam_multi("elixir_chunk_adam_step_tiled_multi", true, n_chunks, d_state, nullptr, nullptr, d_grad_fp32, d_grad_lowp,
+                      d_param_lowp, lowp_format, n, hp, d_grad_scale, d_skip, stream);
 }
 
 extern "C" int elixir_chunk_adam_step_multi(int n_chunks, float* const* d_master, float* const* d_exp_avg,

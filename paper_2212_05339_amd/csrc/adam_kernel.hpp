@@ -160,15 +160,24 @@ struct AdamMultiTable {
     int64_t n2[kAdamMultiMax];             // complete pairs per chunk
 };
 
-template <int GRAD, int OUT>
+// TILED: tab.master[] holds tiled optimizer chunks (see adam_tiled_kernel below); the two moment tables are unused.
+constexpr int64_t kStateTile = ELIXIR_STATE_TILE;
+static_assert(kStateTile % (kAdamBlock * kAdamVec) == 0, "a tile must hold whole workgroups");
+
+template <int GRAD, int OUT, bool TILED>
 __global__ __launch_bounds__(kAdamBlock) void adam_multi_kernel(AdamMultiTable tab, AdamConsts c,
                                                                const float* __restrict__ d_grad_scale,
                                                                const int32_t* __restrict__ d_skip) {
     const int lo = blockIdx.y;
     const int64_t n2 = tab.n2[lo];
-    if ((int64_t)blockIdx.x * kAdamBlock >= n2) return;  // a row past the end of a shorter chunk (uniform per workgroup)
-    const int64_t i = (int64_t)blockIdx.x * kAdamBlock + threadIdx.x;
-    adam_pair<GRAD, OUT>(tab.master[lo], tab.exp_avg[lo], tab.exp_avg_sq[lo], tab.grad[lo], tab.out[lo], i, n2, c, d_grad_scale, d_skip);
+    const int64_t first = (int64_t)blockIdx.x * kAdamBlock;
+    if (first >= n2) return;  // a row past the end of a shorter chunk (uniform per workgroup)
+    if constexpr (TILED) {
+        float* base = tab.master[lo] + 2 * kStateTile * (first / (kStateTile / kAdamVec));
+        adam_pair<GRAD, OUT>(base, base + kStateTile, base + 2 * kStateTile, tab.grad[lo], tab.out[lo], first + threadIdx.x, n2, c, d_grad_scale, d_skip);
+    } else {
+        adam_pair<GRAD, OUT>(tab.master[lo], tab.exp_avg[lo], tab.exp_avg_sq[lo], tab.grad[lo], tab.out[lo], first + threadIdx.x, n2, c, d_grad_scale, d_skip);
+    }
 }
 
 // Tiled optimizer chunk: master, momentum and variance interleaved in tiles of kStateTile elements,
@@ -179,9 +188,6 @@ __global__ __launch_bounds__(kAdamBlock) void adam_multi_kernel(AdamMultiTable t
 // three arrays (82.3%).  A tile holds a whole number of workgroups, so the tile of a workgroup is uniform and the
 // update itself is adam_pair on shifted base pointers: element e of the chunk is base[e], base[T + e], base[2T + e]
 // with base = state + 2 T (e / T).
-constexpr int64_t kStateTile = ELIXIR_STATE_TILE;
-static_assert(kStateTile % (kAdamBlock * kAdamVec) == 0, "a tile must hold whole workgroups");
-
 template <int GRAD, int OUT>
 __global__ __launch_bounds__(kAdamBlock) void adam_tiled_kernel(float* __restrict__ state, const void* __restrict__ grad,
                                                                uint16_t* __restrict__ out, int64_t n2, AdamConsts c,

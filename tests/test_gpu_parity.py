@@ -448,6 +448,45 @@ def test_adam_on_a_tiled_chunk_is_bit_identical_to_the_flat_update_and_matches_t
             check_adam_close(host(back[0]), host(back[1]), host(back[2]), rp, rm, rv, lr=HP["lr"], gmax=6e-3 * (scale or 1.0), steps=2, what=what)
 
 
+@pytest.mark.parametrize("grad_kind", ["bf16", "fp32"])
+def test_tiled_batched_update_is_bit_identical_to_the_flat_batched_update(grad_kind):
+    """Seventy chunks of very different lengths (more than one table, empty ones, odd lengths, a misaligned gradient)."""
+    rng = np.random.default_rng(64)
+    lens = [300_001, 0, 1, 2, 4096, 4097, 150_000] + [int(x) for x in rng.integers(1, 30_000, size=63)]
+    flat, tiled, grads, outs_f, outs_t = [], [], [], [], []
+    for k, n in enumerate(lens):
+        p, m, v = _adam_state(max(n, 1), 3000 + k, zero_moments=False)
+        d = [dev(a[:n]) if n else torch.zeros(1, dtype=torch.float32, device=DEV) for a in (p, m, v)]
+        t = torch.zeros(max(ex.elixir_state_tiled_len(n), 1), dtype=torch.float32, device=DEV)
+        ex.elixir_state_tile(t, d[0], d[1], d[2], n)
+        if grad_kind == "bf16":
+            g = gen.fill_bf16(gen.stream_key(3000 + k, gen.TAG_GRAD, 1), 0, n + 1, 1e-3, zero_pct=1)
+        else:
+            g = gen.fill_f32(gen.stream_key(3000 + k, gen.TAG_GRAD, 1), 0, n + 1, 1e-3)
+        d_g = dev(g)
+        grads.append(d_g[1:n + 1] if k == 5 else d_g[:max(n, 1)])         # chunk 5: gradient one element off its boundary
+        flat.append(d)
+        tiled.append(t)
+        outs_f.append(torch.zeros(max(n, 1), dtype=torch.int16, device=DEV))
+        outs_t.append(torch.zeros(max(n, 1), dtype=torch.int16, device=DEV))
+    d_scale = dev(np.array([0.5], np.float32))
+    for step in (1, 2):
+        hp = hp_struct(step)
+        gf, g16 = (grads, None) if grad_kind == "fp32" else (None, grads)
+        ex.elixir_chunk_adam_step_multi_lp([d[0] for d in flat], [d[1] for d in flat], [d[2] for d in flat], gf, g16, outs_f, 0, lens, hp, d_scale)
+        ex.elixir_chunk_adam_step_tiled_multi_lp(tiled, gf, g16, outs_t, 0, lens, hp, d_scale)
+    sync()
+    for k, n in enumerate(lens):
+        if n == 0:
+            continue
+        back = [torch.zeros(n, dtype=torch.float32, device=DEV) for _ in range(3)]
+        ex.elixir_state_untile(tiled[k], *back, n)
+        sync()
+        for j in range(3):
+            assert np.array_equal(host(back[j]).view(np.uint32), host(flat[k][j]).view(np.uint32)), f"chunk {k} (n={n}) array {j}"
+        assert np.array_equal(host(outs_t[k]), host(outs_f[k])), f"chunk {k}"
+
+
 def test_tiled_entry_point_errors():
     st = torch.zeros(ex.elixir_state_tiled_len(8), dtype=torch.float32, device=DEV)
     g = torch.zeros(8, dtype=torch.int16, device=DEV)
