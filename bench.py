@@ -168,11 +168,12 @@ def side_rows(ex, gen, torch, cfg, C, nch, valid, state, grads, out, stream, ste
         return e0.elapsed_time(e1) * 1e-3 / reps
 
     rows = {}
-    scratch = torch.empty(2, C, dtype=torch.float32, device=dev)
-    src, dst = scratch[0], scratch[1]
+    # an fp32 chunk with an fp32 tensor and a bf16 gradient array allocated next to it (see chunk_groups)
+    side, _keep_side = chunk_groups(torch, dev, 1, [("dst", torch.float32, C, 1), ("src", torch.float32, C, 1), ("g16", torch.int16, C, 1)])
+    src, dst, g16 = side["src"][0], side["dst"][0], side["g16"][0]
+    g16.copy_(grads[0][0])
     t = timed(lambda: ex.elixir_chunk_pack(dst, C, 4, [src], [C], [0], sh), 10)
     rows["pack"] = {"what": f"one fp32 tensor of {C} elements into a chunk (plain copy)", "bytes": 8 * C, "GB/s": 8 * C / t / 1e9}
-    g16 = grads[0][0]
     t = timed(lambda: ex.elixir_grad_reduce_into_chunk(dst, 0, g16, C, 0.25, False, sh), 10)
     rows["grad_reduce_first"] = {"what": "bf16 -> fp32 chunk, overwrite", "bytes": 6 * C, "GB/s": 6 * C / t / 1e9}
     t = timed(lambda: ex.elixir_grad_reduce_into_chunk(dst, 0, g16, C, 0.25, True, sh), 10)
