@@ -338,6 +338,9 @@ int elixir_loss_scale_update(elixir_loss_scale_state* d_state, const float* d_no
 int elixir_host_adam_step(float* h_master, float* h_exp_avg, float* h_exp_avg_sq, const float* h_grad_fp32,
                           const uint16_t* h_grad_bf16, uint16_t* h_param_bf16, int64_t n,
                           const elixir_adam_hparams* hp, float grad_scale, int n_threads);
+/* elixir_host_adam_step on a tiled optimizer chunk in host memory (the layout of elixir_state_tile). */
+int elixir_host_adam_step_tiled(float* h_state, const float* h_grad_fp32, const uint16_t* h_grad_bf16, uint16_t* h_param_bf16,
+                                int64_t n, const elixir_adam_hparams* hp, float grad_scale, int n_threads);
 const char* elixir_host_adam_isa(void);
 int elixir_copy_h2d_async(void* d_dst, const void* h_src, size_t bytes, elixir_stream_t stream);
 int elixir_copy_d2h_async(void* h_dst, const void* d_src, size_t bytes, elixir_stream_t stream);

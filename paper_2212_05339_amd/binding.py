@@ -30,7 +30,7 @@ EXPORTS = (
     "elixir_chunk_adam_step_multi_lp", "elixir_loss_scale_init", "elixir_loss_scale_update",
     "elixir_grad_reduce_chunk_sumsq", "elixir_chunk_grad_norm_finish", "elixir_grad_reduce_multi_lp",
     "elixir_state_tiled_len", "elixir_state_tile", "elixir_state_untile", "elixir_chunk_adam_step_tiled_lp",
-    "elixir_chunk_adam_step_tiled_multi_lp",
+    "elixir_chunk_adam_step_tiled_multi_lp", "elixir_host_adam_step_tiled",
 )
 
 
@@ -84,6 +84,7 @@ def lib() -> ctypes.CDLL:
             "elixir_chunk_evict": [vp, ci, vp, sz, vp, vp],
         }
         sigs["elixir_host_adam_step"] = [vp, vp, vp, vp, vp, vp, i64, ctypes.POINTER(elixir_adam_hparams), f32, ci]
+        sigs["elixir_host_adam_step_tiled"] = [vp, vp, vp, vp, i64, ctypes.POINTER(elixir_adam_hparams), f32, ci]
         sigs["elixir_copy_h2d_async"] = [vp, vp, sz, vp]
         sigs["elixir_copy_d2h_async"] = [vp, vp, sz, vp]
         sigs["elixir_stream_synchronize"] = [vp]
@@ -292,6 +293,13 @@ def elixir_host_adam_step(master, exp_avg, exp_avg_sq, grad_fp32, grad_bf16, par
     """Host buffers are numpy arrays or raw addresses (e.g. from elixir_host_alloc)."""
     _check(lib().elixir_host_adam_step(_host_addr(master), _host_addr(exp_avg), _host_addr(exp_avg_sq), _host_addr(grad_fp32),
                                        _host_addr(grad_bf16), _host_addr(param_bf16), n, ctypes.byref(hp), grad_scale, n_threads))
+
+
+def elixir_host_adam_step_tiled(state, grad_fp32, grad_bf16, param_bf16, n: int, hp: elixir_adam_hparams, grad_scale: float = 1.0,
+                                n_threads: int = 0) -> None:
+    """The CPU update on a tiled optimizer chunk in host memory (numpy array or raw address)."""
+    _check(lib().elixir_host_adam_step_tiled(_host_addr(state), _host_addr(grad_fp32), _host_addr(grad_bf16), _host_addr(param_bf16), n,
+                                             ctypes.byref(hp), grad_scale, n_threads))
 
 
 def elixir_host_adam_isa() -> str:

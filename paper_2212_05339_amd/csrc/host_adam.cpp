@@ -184,10 +184,9 @@ extern "C" const char* elixir_host_adam_isa(void) {
     return name;
 }
 
-extern "C" int elixir_host_adam_step(float* h_master, float* h_exp_avg, float* h_exp_avg_sq, const float* h_grad_fp32,
-                                     const uint16_t* h_grad_bf16, uint16_t* h_param_bf16, int64_t n,
-                                     const elixir_adam_hparams* hp, float grad_scale, int n_threads) {
-    static const char* what = "elixir_host_adam_step";
+namespace {
+
+int check_hparams_host(const char* what, int64_t n, const elixir_adam_hparams* hp) {
     if (n < 0) return fail(ELIXIR_EINVAL, "%s: n=%lld is negative", what, (long long)n);
     if (!hp) return fail(ELIXIR_EINVAL, "%s: hp is NULL", what);
     if (hp->step < 1) return fail(ELIXIR_EINVAL, "%s: step=%lld, steps count from 1", what, (long long)hp->step);
@@ -195,14 +194,10 @@ extern "C" int elixir_host_adam_step(float* h_master, float* h_exp_avg, float* h
         return fail(ELIXIR_EINVAL, "%s: betas must lie in [0, 1)", what);
     if (!(hp->eps >= 0.0f) || !isfinite(hp->lr) || !isfinite(hp->weight_decay))
         return fail(ELIXIR_EINVAL, "%s: eps must be >= 0 and lr, weight_decay finite", what);
-    if (n == 0) return ELIXIR_OK;
-    if ((h_grad_fp32 != nullptr) == (h_grad_bf16 != nullptr))
-        return fail(ELIXIR_EINVAL, "%s: exactly one of h_grad_fp32 / h_grad_bf16 must be given", what);
-    if (!h_master || !h_exp_avg || !h_exp_avg_sq) return fail(ELIXIR_EINVAL, "%s: master / exp_avg / exp_avg_sq must not be NULL", what);
-    const uintptr_t a4 = (uintptr_t)h_master | (uintptr_t)h_exp_avg | (uintptr_t)h_exp_avg_sq | (uintptr_t)h_grad_fp32;
-    const uintptr_t a2 = (uintptr_t)h_grad_bf16 | (uintptr_t)h_param_bf16;
-    if ((a4 & 3) || (a2 & 1)) return fail(ELIXIR_EALIGN, "%s: a pointer is not aligned for its element type", what);
+    return ELIXIR_OK;
+}
 
+Consts make_consts(const elixir_adam_hparams* hp, float grad_scale) {
     const double lr = hp->lr, b1 = hp->beta1, b2 = hp->beta2;
     const double bc1 = 1.0 - pow(b1, (double)hp->step), bc2 = 1.0 - pow(b2, (double)hp->step);
     Consts c;
@@ -215,25 +210,12 @@ extern "C" int elixir_host_adam_step(float* h_master, float* h_exp_avg, float* h
     c.inv_sqrt_bc2 = (float)(1.0 / sqrt(bc2));
     c.eps = hp->eps;
     c.grad_scale = grad_scale;
+    return c;
+}
 
-    const char* isa;
-    const AdamFn fn = pick_kernel(&isa);
-    int T = n_threads > 0 ? n_threads : available_cores();
-    const int64_t min_slice = 1 << 16;  // below this a thread costs more than it saves
-    if ((int64_t)T > (n + min_slice - 1) / min_slice) T = (int)((n + min_slice - 1) / min_slice);
-    if (T < 1) T = 1;
-    // contiguous slices, boundaries on multiples of 16 elements so that every slice but the first starts 64-byte
-    // aligned relative to the chunk
-    auto bound = [&](int t) -> int64_t {
-        if (t >= T) return n;
-        return (n / T * t) & ~(int64_t)15;
-    };
-    auto work = [&](int t) {
-        const int64_t a = bound(t), b = bound(t + 1);
-        if (a < b)
-            fn(h_master + a, h_exp_avg + a, h_exp_avg_sq + a, h_grad_fp32 ? h_grad_fp32 + a : nullptr,
-               h_grad_bf16 ? h_grad_bf16 + a : nullptr, h_param_bf16 ? h_param_bf16 + a : nullptr, b - a, c);
-    };
+// Runs work(t) for t = 0 .. T-1 on T threads (the caller's thread takes t = 0).
+template <typename W>
+int run_threads(const char* what, int T, W&& work) {
     if (T == 1) {
         work(0);
         return ELIXIR_OK;
@@ -249,4 +231,71 @@ extern "C" int elixir_host_adam_step(float* h_master, float* h_exp_avg, float* h
     work(0);
     for (auto& th : pool) th.join();
     return ELIXIR_OK;
+}
+
+}  // namespace
+
+extern "C" int elixir_host_adam_step(float* h_master, float* h_exp_avg, float* h_exp_avg_sq, const float* h_grad_fp32,
+                                     const uint16_t* h_grad_bf16, uint16_t* h_param_bf16, int64_t n,
+                                     const elixir_adam_hparams* hp, float grad_scale, int n_threads) {
+    static const char* what = "elixir_host_adam_step";
+    if (const int rc = check_hparams_host(what, n, hp)) return rc;
+    if (n == 0) return ELIXIR_OK;
+    if ((h_grad_fp32 != nullptr) == (h_grad_bf16 != nullptr))
+        return fail(ELIXIR_EINVAL, "%s: exactly one of h_grad_fp32 / h_grad_bf16 must be given", what);
+    if (!h_master || !h_exp_avg || !h_exp_avg_sq) return fail(ELIXIR_EINVAL, "%s: master / exp_avg / exp_avg_sq must not be NULL", what);
+    const uintptr_t a4 = (uintptr_t)h_master | (uintptr_t)h_exp_avg | (uintptr_t)h_exp_avg_sq | (uintptr_t)h_grad_fp32;
+    const uintptr_t a2 = (uintptr_t)h_grad_bf16 | (uintptr_t)h_param_bf16;
+    if ((a4 & 3) || (a2 & 1)) return fail(ELIXIR_EALIGN, "%s: a pointer is not aligned for its element type", what);
+    const Consts c = make_consts(hp, grad_scale);
+    const char* isa;
+    const AdamFn fn = pick_kernel(&isa);
+    int T = n_threads > 0 ? n_threads : available_cores();
+    const int64_t min_slice = 1 << 16;  // below this a thread costs more than it saves
+    if ((int64_t)T > (n + min_slice - 1) / min_slice) T = (int)((n + min_slice - 1) / min_slice);
+    if (T < 1) T = 1;
+    // contiguous slices, boundaries on multiples of 16 elements so that every slice but the first starts 64-byte
+    // aligned relative to the chunk
+    auto bound = [&](int t) -> int64_t {
+        if (t >= T) return n;
+        return (n / T * t) & ~(int64_t)15;
+    };
+    return run_threads(what, T, [&](int t) {
+        const int64_t a = bound(t), b = bound(t + 1);
+        if (a < b)
+            fn(h_master + a, h_exp_avg + a, h_exp_avg_sq + a, h_grad_fp32 ? h_grad_fp32 + a : nullptr,
+               h_grad_bf16 ? h_grad_bf16 + a : nullptr, h_param_bf16 ? h_param_bf16 + a : nullptr, b - a, c);
+    });
+}
+
+// The same update on a tiled optimizer chunk ([master tile | m tile | v tile] of ELIXIR_STATE_TILE elements each): a
+// chunk that the plan moves between host and device is then updated in place by either side.  Threads take whole tiles.
+extern "C" int elixir_host_adam_step_tiled(float* h_state, const float* h_grad_fp32, const uint16_t* h_grad_bf16,
+                                           uint16_t* h_param_bf16, int64_t n, const elixir_adam_hparams* hp, float grad_scale,
+                                           int n_threads) {
+    static const char* what = "elixir_host_adam_step_tiled";
+    if (const int rc = check_hparams_host(what, n, hp)) return rc;
+    if (n == 0) return ELIXIR_OK;
+    if ((h_grad_fp32 != nullptr) == (h_grad_bf16 != nullptr))
+        return fail(ELIXIR_EINVAL, "%s: exactly one of h_grad_fp32 / h_grad_bf16 must be given", what);
+    if (!h_state) return fail(ELIXIR_EINVAL, "%s: h_state is NULL", what);
+    if ((((uintptr_t)h_state | (uintptr_t)h_grad_fp32) & 3) || (((uintptr_t)h_grad_bf16 | (uintptr_t)h_param_bf16) & 1))
+        return fail(ELIXIR_EALIGN, "%s: a pointer is not aligned for its element type", what);
+    const Consts c = make_consts(hp, grad_scale);
+    const char* isa;
+    const AdamFn fn = pick_kernel(&isa);
+    constexpr int64_t kTile = ELIXIR_STATE_TILE;
+    const int64_t tiles = (n + kTile - 1) / kTile;
+    int T = n_threads > 0 ? n_threads : available_cores();
+    if ((int64_t)T > (tiles + 15) / 16) T = (int)((tiles + 15) / 16);   // at least 16 tiles (64Ki elements) per thread
+    if (T < 1) T = 1;
+    return run_threads(what, T, [&](int t) {
+        const int64_t t0 = tiles * t / T, t1 = tiles * (t + 1) / T;
+        for (int64_t i = t0; i < t1; ++i) {
+            const int64_t e = i * kTile, cnt = n - e < kTile ? n - e : kTile;
+            float* base = h_state + 3 * kTile * i;
+            fn(base, base + kTile, base + 2 * kTile, h_grad_fp32 ? h_grad_fp32 + e : nullptr, h_grad_bf16 ? h_grad_bf16 + e : nullptr,
+               h_param_bf16 ? h_param_bf16 + e : nullptr, cnt, c);
+        }
+    });
 }

@@ -110,3 +110,37 @@ def test_every_isa_variant_in_a_fresh_process(isa):
     env = dict(os.environ, ELIXIR_HOST_ISA=isa)
     r = subprocess.run([sys.executable, "-c", code], env=env, capture_output=True, text=True, timeout=300)
     assert r.returncode == 0 and "ok" in r.stdout, r.stderr[-2000:]
+
+
+@pytest.mark.parametrize("grad_kind", ["bf16", "fp32"])
+@pytest.mark.parametrize("n", [1, 4095, 4096, 4097, 5 * 4096 + 777, 300_001])
+def test_tiled_host_update_is_bit_identical_to_the_flat_host_update(grad_kind, n):
+    """The tiled layout written out with numpy (element e of array k at 3*T*(e//T) + k*T + e%T), updated in place by the
+    tiled entry point, against the three arrays updated by the flat one: same bits, for several thread counts."""
+    T = 4096
+    rng = np.random.default_rng(n)
+    p = (rng.standard_normal(n) * 0.02).astype(np.float32)
+    m = (rng.standard_normal(n) * 3e-4).astype(np.float32)
+    v = np.square(np.abs(m) + np.abs(rng.standard_normal(n).astype(np.float32)) * 1e-3).astype(np.float32)
+    g32 = (rng.standard_normal(n) * 1e-3).astype(np.float32)
+    g16 = (g32.view(np.uint32) >> 16).astype(np.uint16)
+    tiles = -(-n // T)
+    e = np.arange(n)
+    for threads in (1, 3, 0):
+        flat = [p.copy(), m.copy(), v.copy()]
+        tiled = np.zeros(3 * T * tiles, np.float32)
+        for k, a in enumerate(flat):
+            tiled[3 * T * (e // T) + k * T + e % T] = a
+        out_f, out_t = np.zeros(n, np.uint16), np.zeros(n, np.uint16)
+        for step in (1, 2):
+            hp = hp_struct(step)
+            gf, gb = (g32, None) if grad_kind == "fp32" else (None, g16)
+            ex.elixir_host_adam_step(flat[0], flat[1], flat[2], gf, gb, out_f, n, hp, 0.5, threads)
+            ex.elixir_host_adam_step_tiled(tiled, gf, gb, out_t, n, hp, 0.5, threads)
+        for k, a in enumerate(flat):
+            assert np.array_equal(tiled[3 * T * (e // T) + k * T + e % T].view(np.uint32), a.view(np.uint32))
+        assert np.array_equal(out_t, out_f)
+        used = np.zeros(tiled.size, bool)
+        for k in range(3):
+            used[3 * T * (e // T) + k * T + e % T] = True
+        assert not tiled[~used].view(np.uint32).any()           # the unused end of the last tile stays zero
