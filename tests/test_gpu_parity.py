@@ -913,6 +913,39 @@ def test_offload_of_tiled_optimizer_chunks_is_bitwise_identical_to_the_flat_resi
             ex.elixir_host_free(b)
 
 
+def test_a_tiled_chunk_is_updated_in_place_by_gpu_and_cpu_in_turn():
+    """The plan may move a chunk between device and host from one step to the next: the same tiled block is updated
+    by the GPU (step 1), copied down and updated by the host cores (step 2), copied up and updated by the GPU again
+    (step 3).  Three oracle steps are the reference."""
+    n = 2 * ex.ELIXIR_STATE_TILE + 1234
+    L = ex.elixir_state_tiled_len(n)
+    p, m, v = _adam_state(n, 88, zero_moments=True)
+    gs = [gen.fill_bf16(gen.stream_key(88, gen.TAG_GRAD, t), 0, n, 1e-3, zero_pct=1) for t in (1, 2, 3)]
+    d_state = torch.zeros(L, dtype=torch.float32, device=DEV)
+    ex.elixir_state_tile(d_state, dev(p), dev(m), dev(v), n)
+    d_out = torch.zeros(n, dtype=torch.int16, device=DEV)
+    block = ex.elixir_host_alloc(4 * L)
+    try:
+        ex.elixir_chunk_adam_step_tiled_lp(d_state, None, dev(gs[0]), d_out, 0, n, hp_struct(1))
+        ex.elixir_copy_d2h_async(block, d_state, 4 * L)
+        ex.elixir_stream_synchronize()
+        h_out = np.zeros(n, np.uint16)
+        ex.elixir_host_adam_step_tiled(block, None, gs[1], h_out, n, hp_struct(2), 1.0, 3)
+        ex.elixir_copy_h2d_async(d_state, block, 4 * L)
+        ex.elixir_chunk_adam_step_tiled_lp(d_state, None, dev(gs[2]), d_out, 0, n, hp_struct(3))
+        back = [torch.zeros(n, dtype=torch.float32, device=DEV) for _ in range(3)]
+        ex.elixir_state_untile(d_state, *back, n)
+        sync()
+    finally:
+        sync()
+        ex.elixir_host_free(block)
+    rp, rm, rv, rout = p.copy(), m.copy(), v.copy(), np.zeros(n, np.uint16)
+    for t in (1, 2, 3):
+        orc.chunk_adam_step(rp, rm, rv, gs[t - 1], rout, step=t, **HP)
+    check_adam_close(host(back[0]), host(back[1]), host(back[2]), rp, rm, rv, lr=HP["lr"], gmax=4e-3, steps=3)
+    check_bf16_copy(host(d_out, np.uint16), host(back[0]), rout, rp, lr=HP["lr"], steps=3)
+
+
 def test_offload_slot_exhaustion_and_release(ctx):
     nbytes = 4096
     slots = [torch.zeros(1024, dtype=torch.float32, device=DEV) for _ in range(2)]
