@@ -329,10 +329,11 @@ def test_adam_randomized_call_configurations():
         what = f"case {case}: n={n} fmt={fmt} grad_fp32={grad_fp32} out={with_out} shifts={shifts} scale={scale} skip={skip} step={step}"
         N = n + 4
         p, m, v = _adam_state(N, 1000 + case, zero_moments=False)
+        sl = [slice(sh, sh + n) for sh in shifts]
+        v[sl[2]] = np.square(np.abs(m[sl[1]]) + np.sqrt(v[sl[2]]))     # |m| <= sqrt(v) element by element AFTER the (unequal) shifts
         x = gen.fill_f32(gen.stream_key(1000 + case, gen.TAG_GRAD, 1), 0, N, 1e-3)
         g16 = x.astype(np.float16).view(np.uint16) if fmt else gen.fill_bf16(gen.stream_key(1000 + case, gen.TAG_GRAD, 1), 0, N, 1e-3, zero_pct=2)
         g = x if grad_fp32 else g16
-        sl = [slice(sh, sh + n) for sh in shifts]
         gmax = 6e-3 * (scale or 1.0)
         for multi in (False, True):
             d_p, d_m, d_v, d_g = dev(p), dev(m), dev(v), dev(g)
