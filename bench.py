@@ -90,7 +90,7 @@ def parse():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="gpt2_1p5b",
-                    help="gpt2_1p5b (default, the benchmark line), tiny, sweep (chunk sizes 8Mi..256Mi), gpt2_6b_clip, gpt2_20b_offload, gpt2_20b_hybrid (CPU update + streaming)")
+                    help="gpt2_1p5b (default, the benchmark line), tiny, sweep (chunk sizes 8Mi..256Mi), gpt2_6b_clip, gpt2_20b_offload, gpt2_20b_hybrid (CPU update + streaming), placement (launch times against where the operands lie)")
     ap.add_argument("--host-threads", type=int, default=0, help="gpt2_20b_hybrid: threads of the CPU update (default: all cores)")
     ap.add_argument("--host-chunks", type=int, default=0, help="gpt2_20b_offload: allocate only about this many host-resident chunks")
     ap.add_argument("--multi", action="store_true",
@@ -805,6 +805,47 @@ def run_hybrid(args, torch, ex, gen):
         ex.elixir_ctx_destroy(ctx)
 
 
+def run_placement(args, torch, ex, gen):
+    """Where arrays lie relative to each other: launch times of the tiled AdamW update and of the accumulate pass of the
+    reduction (whole 64Mi-element launches) while one operand is moved through a single 240 GiB allocation in 8 GiB steps.
+    The evidence behind chunk_groups(); prints one JSON line."""
+    dev = torch.device("cuda:0")
+    GiB, TOT, C = 1 << 30, 240, 64 * gen.Mi
+    arena = torch.zeros(TOT * GiB, dtype=torch.uint8, device=dev)
+    base = arena.data_ptr()
+    stream = torch.cuda.Stream()
+    sh = stream.cuda_stream
+    hp = ex.make_hparams(1e-4, 0.9, 0.999, 1e-8, 0.01, 1)
+
+    def us(fn):
+        fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(stream)
+        for _ in range(3):
+            fn()
+        e1.record(stream)
+        torch.cuda.synchronize()
+        return round(e0.elapsed_time(e1) / 3 * 1e3, 1)
+
+    def adam(state_gib, grad_gib, out_gib):
+        return us(lambda: ex.elixir_chunk_adam_step_tiled_lp(base + int(state_gib * GiB), None, base + int(grad_gib * GiB),
+                                                             base + int(out_gib * GiB), ex.ELIXIR_LOWP_BF16, C, hp, None, None, sh))
+
+    def accumulate(dst_gib, src_gib):
+        return us(lambda: ex.elixir_grad_reduce_into_chunk(base + int(dst_gib * GiB), 0, base + int(src_gib * GiB), C, 0.25, True, sh))
+
+    pos = list(range(8, TOT - 8, 8))
+    print(json.dumps({
+        "metric": "launch time against operand placement", "unit": "us", "n_gpus": 1, "data": "zero-filled",
+        "config": {"workload": "placement scan", "allocation_GiB": TOT, "elements_per_launch": C, "positions_GiB": pos},
+        "adam_tiled_state_scanned_grad_at_1_out_at_2_GiB": [adam(s, 1, 2) for s in pos],
+        "adam_tiled_state_at_100_grad_scanned_out_at_2_GiB": [adam(100, g, 2) if abs(g - 100) >= 4 else None for g in pos],
+        "adam_tiled_state_at_100_grad_at_104_out_scanned": [adam(100, 104, o) if abs(o - 102) >= 6 else None for o in pos],
+        "accumulate_dst_scanned_src_at_1_GiB": [accumulate(d, 1) for d in pos],
+        "accumulate_dst_at_100_src_scanned": [accumulate(100, s_) if abs(s_ - 100) >= 4 else None for s_ in pos]}), flush=True)
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -822,9 +863,9 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs an MI355X"
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
-    if args.workload in ("sweep", "gpt2_6b_clip", "gpt2_20b_offload", "gpt2_20b_hybrid"):
+    if args.workload in ("sweep", "gpt2_6b_clip", "gpt2_20b_offload", "gpt2_20b_hybrid", "placement"):
         {"sweep": run_sweep, "gpt2_6b_clip": run_clip, "gpt2_20b_offload": run_offload,
-         "gpt2_20b_hybrid": run_hybrid}[args.workload](args, torch, ex, gen)
+         "gpt2_20b_hybrid": run_hybrid, "placement": run_placement}[args.workload](args, torch, ex, gen)
         return
     cfg = gen.CONFIGS[args.workload]
     C = cfg.chunk_elems
