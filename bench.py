@@ -101,6 +101,10 @@ def parse():
                     help="gpt2_20b_offload: which 60%% of the chunks live in host memory (every 3 of 5, or the first 60%% in schedule order)")
     ap.add_argument("--whole-chunks", action="store_true", help="update the zero padding behind a chunk's last tensor as well "
                                                                 "(default: a launch covers the valid prefix of its chunk)")
+    ap.add_argument("--params-over-grads", action="store_true",
+                    help="gpt2_1p5b / tiny: write the bf16 parameters over the bf16 gradients they were computed from (the paper's "
+                         "parameter chunk, which holds the gradients after the backward pass) instead of into an array of their own; "
+                         "a gradient set then holds parameters when the ring comes round to it again, which the timing does not see")
     ap.add_argument("--state-layout", choices=["tiled", "flat"], default="tiled",
                     help="optimizer chunk as one buffer of interleaved [master|m|v] tiles (default) or as three arrays")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -916,17 +920,18 @@ def main():
     def one_step(step_no):
         hp = ex.make_hparams(cfg.lr, cfg.beta1, cfg.beta2, cfg.eps, cfg.weight_decay, step_no)
         g = grads[(step_no - 1) % n_sets]
+        o = g if args.params_over_grads else out
         if args.multi and tiled:
-            ex.elixir_chunk_adam_step_tiled_multi_lp(tiled, None, g, out, ex.ELIXIR_LOWP_BF16, lens, hp, None, None, sh)
+            ex.elixir_chunk_adam_step_tiled_multi_lp(tiled, None, g, o, ex.ELIXIR_LOWP_BF16, lens, hp, None, None, sh)
             return
         if args.multi:
-            ex.elixir_chunk_adam_step_multi(p_list, m_list, v_list, None, g, out, lens, hp, None, sh)
+            ex.elixir_chunk_adam_step_multi(p_list, m_list, v_list, None, g, o, lens, hp, None, sh)
             return
         for c in range(nch):
             if tiled:
-                ex.elixir_chunk_adam_step_tiled_lp(tiled[c], None, g[c], out[c], ex.ELIXIR_LOWP_BF16, lens[c], hp, None, None, sh)
+                ex.elixir_chunk_adam_step_tiled_lp(tiled[c], None, g[c], o[c], ex.ELIXIR_LOWP_BF16, lens[c], hp, None, None, sh)
             else:
-                ex.elixir_chunk_adam_step(state[c][0], state[c][1], state[c][2], None, g[c], out[c], lens[c], hp, None, sh)
+                ex.elixir_chunk_adam_step(state[c][0], state[c][1], state[c][2], None, g[c], o[c], lens[c], hp, None, sh)
 
     for w in range(W):
         one_step(w + 1)
@@ -970,6 +975,7 @@ def main():
         "config": {"workload": cfg.name, "params": total_params, "chunk_elems": C, "n_chunks": nch,
                    "processed_elems_per_step": sum(lens), "padding_updated": bool(args.whole_chunks), "layout": "next-fit", "grad_dtype": "bf16",
                    "optimizer_chunk": "tiled [master|m|v], 4096-element tiles" if tiled else "three arrays",
+                   "lowp_params": "written over the gradients" if args.params_over_grads else "an array of their own",
                    "grad_sets_resident": n_sets, "hparams": {"lr": cfg.lr, "betas": [cfg.beta1, cfg.beta2],
                                                              "eps": cfg.eps, "weight_decay": cfg.weight_decay}},
         "elements_per_s": sum(lens) * K / wall,

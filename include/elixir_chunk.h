@@ -181,6 +181,13 @@ int elixir_chunk_grad_norm_finish(elixir_ctx* ctx, int n_chunks, float max_norm,
  *   master[k] = p;  exp_avg[k] = m;  exp_avg_sq[k] = v;  param_bf16[k] = round-to-nearest-even bf16(p)
  * Exactly one of d_grad_fp32 / d_grad_bf16 is non-NULL.  d_param_bf16 may be
  * NULL (no low-precision copy).  d_grad_scale is a DEVICE float or NULL.
+ * d_param_bf16 may be EQUAL to d_grad_bf16: in the paper the gradient of a
+ * parameter takes the place of the parameter in its low-precision chunk during
+ * the backward pass (Sec. 4.1), so the update reads the gradients from the
+ * parameter chunk and writes the new parameters over them (same speed, 2 bytes
+ * per parameter saved).  This holds for every AdamW entry point of this header,
+ * device and host; any other overlap between the arrays of a call is an error
+ * of the caller and is not detected.
  * Arithmetic is fp32; algorithmic traffic is 28 bytes per element with bf16
  * gradients (2 + 12 read, 12 + 2 written), 30 with fp32 gradients.
  */

@@ -102,6 +102,9 @@ __device__ __forceinline__ uint32_t lowp_bits(float p) {
 // are issued for every lane at once (lanes past the end re-read the last pair instead of branching on n2), and
 // the skip flag and the gradient scale are looked at only afterwards, so that all kernel-argument loads can go
 // out together instead of one dependent scalar load after the other.
+// grad and out may be one and the same array of 16-bit elements (the paper's parameter chunk, which holds the
+// gradients after the backward pass, Sec. 4.1): every lane reads its pair before it writes it, and the pair that
+// the lanes past the end re-read is never used by them.
 template <int GRAD, int OUT>
 __device__ __forceinline__ void adam_pair(float* master, float* exp_avg, float* exp_avg_sq, const void* grad, uint16_t* out,
                                           int64_t i_raw, int64_t n2, const AdamConsts& c, const float* d_grad_scale,
@@ -138,7 +141,7 @@ __device__ __forceinline__ void adam_pair(float* master, float* exp_avg, float* 
 template <int GRAD, int OUT>
 __global__ __launch_bounds__(kAdamBlock) void adam_vec_kernel(float* __restrict__ master, float* __restrict__ exp_avg,
                                                              float* __restrict__ exp_avg_sq,
-                                                             const void* __restrict__ grad, uint16_t* __restrict__ out,
+                                                             const void* grad, uint16_t* out,  // may be the same array
                                                              int64_t n2, AdamConsts c,
                                                              const float* __restrict__ d_grad_scale,
                                                              const int32_t* __restrict__ d_skip) {
@@ -189,8 +192,8 @@ __global__ __launch_bounds__(kAdamBlock) void adam_multi_kernel(AdamMultiTable t
 // update itself is adam_pair on shifted base pointers: element e of the chunk is base[e], base[T + e], base[2T + e]
 // with base = state + 2 T (e / T).
 template <int GRAD, int OUT>
-__global__ __launch_bounds__(kAdamBlock) void adam_tiled_kernel(float* __restrict__ state, const void* __restrict__ grad,
-                                                               uint16_t* __restrict__ out, int64_t n2, AdamConsts c,
+__global__ __launch_bounds__(kAdamBlock) void adam_tiled_kernel(float* __restrict__ state, const void* grad,
+                                                               uint16_t* out, int64_t n2, AdamConsts c,
                                                                const float* __restrict__ d_grad_scale,
                                                                const int32_t* __restrict__ d_skip) {
     const int64_t first = (int64_t)blockIdx.x * kAdamBlock;   // first pair of this workgroup

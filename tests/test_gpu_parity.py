@@ -449,6 +449,67 @@ def test_adam_on_a_tiled_chunk_is_bit_identical_to_the_flat_update_and_matches_t
             check_adam_close(host(back[0]), host(back[1]), host(back[2]), rp, rm, rv, lr=HP["lr"], gmax=6e-3 * (scale or 1.0), steps=2, what=what)
 
 
+@pytest.mark.parametrize("fmt", [ex.ELIXIR_LOWP_BF16, ex.ELIXIR_LOWP_FP16])
+def test_parameters_written_over_their_gradients_give_the_same_bits_as_a_separate_copy(fmt):
+    """The parameter chunk of the paper holds the gradients after the backward pass (Sec. 4.1): every AdamW entry point
+    accepts the low-precision output array equal to the low-precision gradient array.  Flat, tiled, batched flat and
+    batched tiled; vector and one-element kernels (odd lengths, an odd start); one call each, compared bit for bit with
+    the same call writing to a separate array, and once with the oracle."""
+    T = ex.ELIXIR_STATE_TILE
+    sizes = [1, 2, 7, 256, 257, T + 3, 3 * T, 5 * T + 130, 300_001]
+    hp = hp_struct(3)
+    runs = {}
+    for in_place in (False, True):
+        res = []
+        for which in ("flat", "tiled", "multi", "tiled_multi"):
+            states, grads, outs = [], [], []
+            for j, n in enumerate(sizes):
+                p, m, v = _adam_state(n, 3100 + j, zero_moments=False)
+                x = gen.fill_f32(gen.stream_key(3100 + j, gen.TAG_GRAD, 1), 0, n + 2, 1e-3)
+                g16 = x.astype(np.float16).view(np.uint16) if fmt else gen.fill_bf16(gen.stream_key(3100 + j, gen.TAG_GRAD, 1), 0, n + 2, 1e-3, zero_pct=2)
+                shift = j % 2 if which in ("flat", "multi") else 2 * (j % 2)     # an odd start takes the one-element kernel (flat only)
+                d_g = dev(g16)[shift:shift + n]
+                d_o = d_g if in_place else torch.zeros(n + 2, dtype=torch.int16, device=DEV)[shift:shift + n]
+                if which in ("flat", "multi"):
+                    st = [dev(p), dev(m), dev(v)]
+                else:
+                    st = torch.zeros(ex.elixir_state_tiled_len(n), dtype=torch.float32, device=DEV)
+                    ex.elixir_state_tile(st, dev(p), dev(m), dev(v), n)
+                states.append(st); grads.append(d_g); outs.append(d_o)
+            if which == "flat":
+                for st, g, o, n in zip(states, grads, outs, sizes):
+                    ex.elixir_chunk_adam_step_lp(st[0], st[1], st[2], None, g, o, fmt, n, hp)
+            elif which == "tiled":
+                for st, g, o, n in zip(states, grads, outs, sizes):
+                    ex.elixir_chunk_adam_step_tiled_lp(st, None, g, o, fmt, n, hp)
+            elif which == "multi":
+                ex.elixir_chunk_adam_step_multi_lp([s_[0] for s_ in states], [s_[1] for s_ in states], [s_[2] for s_ in states], None, grads, outs, fmt, sizes, hp)
+            else:
+                ex.elixir_chunk_adam_step_tiled_multi_lp(states, None, grads, outs, fmt, sizes, hp)
+            sync()
+            for st, o in zip(states, outs):
+                flat = [host(a).view(np.uint32).copy() for a in (st if isinstance(st, list) else [st])]
+                res.append((which, flat, host(o, np.uint16).copy()))
+        runs[in_place] = res
+    for (which, st_a, out_a), (_, st_b, out_b) in zip(runs[False], runs[True]):
+        for a, b in zip(st_a, st_b):
+            assert np.array_equal(a, b), which
+        assert np.array_equal(out_a, out_b), which
+    # the oracle on the longest flat case
+    j, n = len(sizes) - 1, sizes[-1]
+    p, m, v = _adam_state(n, 3100 + j, zero_moments=False)
+    x = gen.fill_f32(gen.stream_key(3100 + j, gen.TAG_GRAD, 1), 0, n + 2, 1e-3)
+    g16 = x.astype(np.float16).view(np.uint16) if fmt else gen.fill_bf16(gen.stream_key(3100 + j, gen.TAG_GRAD, 1), 0, n + 2, 1e-3, zero_pct=2)
+    shift = j % 2
+    ref_out = np.zeros(n, np.uint16)
+    orc.chunk_adam_step(p, m, v, np.ascontiguousarray(g16[shift:shift + n]), ref_out, step=3, fmt=fmt, **HP)
+    which, st, out = runs[True][j]
+    assert which == "flat"
+    check_adam_close(st[0].view(np.float32), st[1].view(np.float32), st[2].view(np.float32), p, m, v, lr=HP["lr"], gmax=6e-3, what="in place")
+    if fmt == ex.ELIXIR_LOWP_BF16:
+        check_bf16_copy(out, st[0].view(np.float32), ref_out, p, lr=HP["lr"])
+
+
 @pytest.mark.parametrize("grad_kind", ["bf16", "fp32"])
 def test_tiled_batched_update_is_bit_identical_to_the_flat_batched_update(grad_kind):
     """Seventy chunks of very different lengths (more than one table, empty ones, odd lengths, a misaligned gradient)."""

@@ -144,3 +144,33 @@ def test_tiled_host_update_is_bit_identical_to_the_flat_host_update(grad_kind, n
         for k in range(3):
             used[3 * T * (e // T) + k * T + e % T] = True
         assert not tiled[~used].view(np.uint32).any()           # the unused end of the last tile stays zero
+
+
+@pytest.mark.parametrize("n,shift", [(1, 0), (17, 1), (4097, 0), (5 * 4096 + 777, 3), (300_001, 0)])
+def test_host_update_writes_the_parameters_over_their_gradients(n, shift):
+    """The paper's parameter chunk holds the gradients after the backward pass (Sec. 4.1): with the output array equal to
+    the bf16 gradient array the flat and the tiled host update leave the same bits as with a separate output array."""
+    T = 4096
+    p, m, v = state(n, 77)
+    g16 = gen.fill_bf16(gen.stream_key(78, gen.TAG_GRAD, 1), 0, n + 8, 1e-3, zero_pct=1)
+    e = np.arange(n)
+    hp = hp_struct(2)
+    for threads in (1, 0):
+        sep = [p.copy(), m.copy(), v.copy()]
+        out = np.zeros(n, np.uint16)
+        ex.elixir_host_adam_step(sep[0], sep[1], sep[2], None, g16[shift:shift + n], out, n, hp, 0.5, threads)
+        same = [p.copy(), m.copy(), v.copy()]
+        buf = g16.copy()
+        ex.elixir_host_adam_step(same[0], same[1], same[2], None, buf[shift:shift + n], buf[shift:shift + n], n, hp, 0.5, threads)
+        for a, b in zip(sep, same):
+            assert np.array_equal(a.view(np.uint32), b.view(np.uint32))
+        assert np.array_equal(buf[shift:shift + n], out)
+        assert np.array_equal(buf[:shift], g16[:shift]) and np.array_equal(buf[shift + n:], g16[shift + n:])
+        tiled = np.zeros(3 * T * -(-n // T), np.float32)
+        for k, a in enumerate((p, m, v)):
+            tiled[3 * T * (e // T) + k * T + e % T] = a
+        buf = g16.copy()
+        ex.elixir_host_adam_step_tiled(tiled, None, buf[shift:shift + n], buf[shift:shift + n], n, hp, 0.5, threads)
+        for k, a in enumerate(sep):
+            assert np.array_equal(tiled[3 * T * (e // T) + k * T + e % T].view(np.uint32), a.view(np.uint32))
+        assert np.array_equal(buf[shift:shift + n], out)
