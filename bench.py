@@ -51,11 +51,12 @@ def chunk_groups(torch, dev, nch, parts):
     """One allocation holding, chunk after chunk, a group of arrays: parts = [(name, dtype, numel, count)], every array
     followed by the stagger gap.  Returns ({name: [per chunk: tensor, or list of `count` tensors]}, the allocation).
 
-    Why groups: device memory on this part behaves as a few large regions (about 96 GiB each inside a 256 GiB allocation).
-    Measured on whole 64Mi chunks: the AdamW launch takes 266-270 us when the gradient array lies in the same region as the
-    optimizer chunk and 280-283 us when it does not; the accumulate pass of the reduction 197-201 us against 212-217 us for
-    its bf16 source; a write-only array (the parameter copy) in the optimizer chunk's region costs 2% instead.  Arrays that
-    are read together are therefore allocated side by side, the parameter copies elsewhere (out_of_the_way)."""
+    Why groups: device memory on this part behaves as a few classes of large address ranges (32 GiB granularity; which
+    range belongs to which class moves with the allocation: --workload placement scans it).  Measured on whole 64Mi
+    chunks: the AdamW launch takes 266-272 us when the gradient array lies in the class of the optimizer chunk and
+    280-283 us when it does not; the accumulate pass of the reduction 99-102 us against 106-109 us for its bf16 source; a
+    write-only array (the parameter copy) in the optimizer chunk's class costs 2% instead.  Arrays that are read together
+    are therefore allocated side by side, the parameter copies elsewhere (out_of_the_way)."""
     import numpy as np
     esz = {torch.float32: 4, torch.int16: 2}
     sizes = [(name, dt, n, cnt, -(-(n * esz[dt]) // 8192) * 8192 + STAGGER_BYTES) for name, dt, n, cnt in parts]
@@ -208,11 +209,14 @@ def side_rows(ex, gen, torch, cfg, C, nch, valid, state, grads, out, stream, ste
     lss = torch.zeros(4, dtype=torch.float32, device=dev)
     ex.elixir_loss_scale_init(lss, 65536.0, sh)
     hp16 = ex.make_hparams(cfg.lr, cfg.beta1, cfg.beta2, cfg.eps, cfg.weight_decay, 1)
-    st0 = state[0]
-    t = timed(lambda: ex.elixir_chunk_adam_step_lp(st0[0], st0[1], st0[2], None, g16, out[0], ex.ELIXIR_LOWP_FP16, C, hp16, lss[3:4],
-                                                  lss[2:3].view(torch.int32), sh), 10)
-    rows["adam_fp16_loss_scaled"] = {"what": "fp16 gradient in, fp16 copy out, grad_scale and skip flag read from the device state",
+    f16g, _keep_f16 = chunk_groups(torch, dev, 1, [("state", torch.float32, ex.elixir_state_tiled_len(C), 1), ("g", torch.int16, C, 1)])
+    ex.elixir_state_tile(f16g["state"][0], state[0][0], state[0][1], state[0][2], C, sh)
+    f16g["g"][0].copy_(g16)
+    t = timed(lambda: ex.elixir_chunk_adam_step_tiled_lp(f16g["state"][0], None, f16g["g"][0], out[0], ex.ELIXIR_LOWP_FP16, C, hp16, lss[3:4],
+                                                        lss[2:3].view(torch.int32), sh), 10)
+    rows["adam_fp16_loss_scaled"] = {"what": "tiled optimizer chunk, fp16 gradient in, fp16 copy out, grad_scale and skip flag read from the device state",
                                      "bytes": 28 * C, "GB/s": 28 * C / t / 1e9}
+    del f16g, _keep_f16
     ctx = ex.elixir_ctx_create(0, C, nch)
     try:
         d_nc = torch.zeros(2, dtype=torch.float32, device=dev)
@@ -220,6 +224,9 @@ def side_rows(ex, gen, torch, cfg, C, nch, valid, state, grads, out, stream, ste
         t = timed(lambda: ex.elixir_chunk_grad_norm(ctx, chunks, valid, 1.0, d_nc[0:1], d_nc[1:2], sh), 5)
         rows["grad_norm"] = {"what": f"{nch} fp32 chunks, {sum(valid)} valid elements, two-stage fp64 tree",
                              "bytes": 4 * sum(valid), "GB/s": 4 * sum(valid) / t / 1e9, "ms": t * 1e3}
+        t = timed(lambda: ex.elixir_chunk_grad_norm_lp(ctx, grads[0], ex.ELIXIR_LOWP_BF16, valid, 1.0, 1.0, d_nc[0:1], d_nc[1:2], sh), 5)
+        rows["grad_norm_lowp"] = {"what": f"the same norm taken directly over the {nch} bf16 gradient chunks (single micro-batch: no fp32 gradient chunk)",
+                                  "bytes": 2 * sum(valid), "GB/s": 2 * sum(valid) / t / 1e9, "ms": t * 1e3}
         # ---- offload pipeline: n_host chunks live in pinned host memory, the nch resident chunks are updated meanwhile
         n_host, n_slots = 12, 3
         nbytes = 3 * C * 4

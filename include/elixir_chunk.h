@@ -152,6 +152,23 @@ int elixir_chunk_grad_norm(elixir_ctx* ctx, const float* const* grad_chunks, con
                            elixir_stream_t stream);
 
 /*
+ * The same norm taken directly over 16-bit gradient chunks.  The paper's gradient chunk IS a low-precision chunk (the
+ * gradients take the place of the parameters in it, Sec. 4.1); with a single micro-batch nothing has to be summed in
+ * fp32 first, and norm + update then move 2 + 28 bytes per element instead of 6 (widening pass) + 30.  Every element
+ * is widened exactly and squared and summed in double over the same fixed tree:
+ *   norm = |scale| * sqrt(sum g^2),   coef = max_norm > 0 ? min(1, max_norm/(norm + 1e-6)) : 1,
+ *   *d_norm_out = norm,   *d_grad_scale_out = scale * coef
+ * scale is the factor the stored gradients still have to be multiplied by (1/micro-batches, 1/ranks; 1 if none), so
+ * *d_grad_scale_out is what the AdamW entry points take as d_grad_scale.  With fp16 gradients under loss scaling pass
+ * scale = 1 and hand *d_norm_out to elixir_loss_scale_update (an Inf/NaN gradient gives a non-finite norm).
+ * grad_chunks_lowp and valid_len are HOST arrays; chunk pointers need 2-byte alignment only.  Same workspace rule as
+ * elixir_chunk_grad_norm.
+ */
+int elixir_chunk_grad_norm_lp(elixir_ctx* ctx, const uint16_t* const* grad_chunks_lowp, int lowp_format,
+                              const int64_t* valid_len, int n_chunks, float scale, float max_norm, float* d_norm_out,
+                              float* d_grad_scale_out, elixir_stream_t stream);
+
+/*
  * The last pass of the reduction and the norm in one sweep.  elixir_grad_reduce_chunk_sumsq does what
  * elixir_grad_reduce_into_chunk_lp does for a WHOLE chunk (offset 0, chunk_elems elements, 16-byte aligned chunk,
  * 8-byte aligned gradients) and, from the values it is writing, leaves the chunk's sum of squares over its first

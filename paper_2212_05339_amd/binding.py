@@ -28,7 +28,7 @@ EXPORTS = (
     "elixir_copy_d2h_async", "elixir_stream_synchronize", "elixir_offload_benefit", "elixir_offload_plan",
     "elixir_rcache_simulate", "elixir_chunk_size_search", "elixir_grad_reduce_into_chunk_lp", "elixir_chunk_adam_step_lp",
     "elixir_chunk_adam_step_multi_lp", "elixir_loss_scale_init", "elixir_loss_scale_update",
-    "elixir_grad_reduce_chunk_sumsq", "elixir_chunk_grad_norm_finish", "elixir_grad_reduce_multi_lp",
+    "elixir_grad_reduce_chunk_sumsq", "elixir_chunk_grad_norm_finish", "elixir_grad_reduce_multi_lp", "elixir_chunk_grad_norm_lp",
     "elixir_state_tiled_len", "elixir_state_tile", "elixir_state_untile", "elixir_chunk_adam_step_tiled_lp",
     "elixir_chunk_adam_step_tiled_multi_lp", "elixir_host_adam_step_tiled",
 )
@@ -96,6 +96,7 @@ def lib() -> ctypes.CDLL:
                                                    ctypes.POINTER(elixir_adam_hparams), vp, vp, vp]
         sigs["elixir_grad_reduce_chunk_sumsq"] = [vp, ci, vp, vp, ci, i64, i64, f32, ci, vp]
         sigs["elixir_chunk_grad_norm_finish"] = [vp, ci, f32, vp, vp, vp]
+        sigs["elixir_chunk_grad_norm_lp"] = [vp, ctypes.POINTER(vp), ci, pi64, ci, f32, f32, vp, vp, vp]
         sigs["elixir_grad_reduce_multi_lp"] = [ci, ctypes.POINTER(vp), ctypes.POINTER(vp), pi64, ci, f32, ci, vp]
         sigs["elixir_state_tile"] = [vp, vp, vp, vp, i64, vp]
         sigs["elixir_state_untile"] = [vp, vp, vp, vp, i64, vp]
@@ -219,6 +220,13 @@ def elixir_chunk_grad_norm(ctx: Ctx, grad_chunks, valid_len, max_norm: float, d_
     n = len(grad_chunks)
     _check(lib().elixir_chunk_grad_norm(ctx.handle, _ptr_array(grad_chunks), _i64_array(valid_len), n, max_norm,
                                         _addr(d_norm_out), _addr(d_clip_coef_out), _stream(stream)))
+
+
+def elixir_chunk_grad_norm_lp(ctx: Ctx, grad_chunks_lowp, lowp_format: int, valid_len, scale: float, max_norm: float, d_norm_out,
+                              d_grad_scale_out, stream=None) -> None:
+    _check(lib().elixir_chunk_grad_norm_lp(ctx.handle, _ptr_array(grad_chunks_lowp), lowp_format, _i64_array(valid_len),
+                                           len(grad_chunks_lowp), scale, max_norm, _addr(d_norm_out), _addr(d_grad_scale_out),
+                                           _stream(stream)))
 
 
 def make_hparams(lr: float, beta1: float, beta2: float, eps: float, weight_decay: float, step: int) -> elixir_adam_hparams:

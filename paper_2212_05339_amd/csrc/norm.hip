@@ -1,5 +1,6 @@
 // elixir_chunk_grad_norm: deterministic global L2 norm of the fp32 gradient chunks
-// and the clipping coefficient, both left in device memory.
+// (elixir_chunk_grad_norm_lp: of 16-bit gradient chunks) and the clipping coefficient,
+// both left in device memory.
 //
 // Stage 1: kNormBlocksPerChunk single-wavefront workgroups per chunk; workgroup b sums, in double
 //   precision, the squares of the elements it meets striding through the chunk
@@ -94,14 +95,17 @@ __global__ __launch_bounds__(kSumsqBlock) void sumsq_kernel(ChunkTable tab, doub
     if (threadIdx.x == 0) partials[(int64_t)c * kNormBlocksPerChunk + blockIdx.x] = x;
 }
 
+// scale: the factor the caller applies to the stored gradients before they count (1 for the fp32 chunks, whose
+// reduction has applied it already): the norm is that of scale * g and the coefficient written is scale * clip, the
+// factor an update has to apply to the stored gradients.  With scale = 1 both products are exact.
 __global__ __launch_bounds__(1024) void finish_kernel(const double* __restrict__ partials, int64_t n_partials,
-                                                     float max_norm, float* d_norm_out, float* d_clip_out) {
+                                                     float max_norm, double scale, float* d_norm_out, float* d_clip_out) {
     __shared__ double lds[16];
     double acc = 0.0;
     for (int64_t i = threadIdx.x; i < n_partials; i += 1024) acc += partials[i];
     const double s = block_sum(acc, lds);
     if (threadIdx.x == 0) {
-        const double norm = sqrt(s);
+        const double norm = fabs(scale) * sqrt(s);
         if (d_norm_out) *d_norm_out = (float)norm;
         if (d_clip_out) {
             double coef = 1.0;
@@ -109,9 +113,72 @@ __global__ __launch_bounds__(1024) void finish_kernel(const double* __restrict__
                 const double r = (double)max_norm / (norm + 1e-6);
                 coef = r < 1.0 ? r : 1.0;
             }
-            *d_clip_out = (float)coef;
+            *d_clip_out = (float)(scale * coef);
         }
     }
+}
+
+// Stage 1 for 16-bit gradient chunks (the paper's gradient chunk is a low-precision chunk, Sec. 4.1): the same
+// sliding window and the same fixed tree as sumsq_kernel, eight elements per 128-bit load, widened exactly and
+// squared and summed in double.  2 bytes per element.
+struct LowpChunkTable {
+    const uint16_t* ptr[kMaxBatch];
+    int64_t valid[kMaxBatch];
+};
+
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+template <bool FP16>
+__device__ __forceinline__ double sq_pair(uint32_t w, double acc) {
+    const double lo = (double)widen<FP16>(w & 0xFFFFu), hi = (double)widen<FP16>(w >> 16);
+    return fma(hi, hi, fma(lo, lo, acc));
+}
+
+template <bool FP16>
+__device__ __forceinline__ double sq_eight(u32x4 a, double acc) {
+    return sq_pair<FP16>(a.w, sq_pair<FP16>(a.z, sq_pair<FP16>(a.y, sq_pair<FP16>(a.x, acc))));
+}
+
+template <bool FP16>
+__global__ __launch_bounds__(kSumsqBlock) void sumsq_lowp_kernel(LowpChunkTable tab, double* __restrict__ partials) {
+    const int c = blockIdx.y;
+    const uint16_t* __restrict__ g = tab.ptr[c];
+    const int64_t n = tab.valid[c];
+    // leading elements up to the first 16-byte boundary (at most 7), complete groups of 8, trailing elements (at most 7)
+    int64_t head = (int64_t)(((16 - (reinterpret_cast<uintptr_t>(g) & 15)) & 15) >> 1);
+    if (head > n) head = n;
+    const int64_t n8 = (n - head) >> 3;
+    const int64_t tail0 = head + (n8 << 3);
+    const u32x4* __restrict__ G = reinterpret_cast<const u32x4*>(g + head);
+    constexpr int64_t kStride = (int64_t)kNormBlocksPerChunk * kSumsqBlock;
+    double acc0 = 0.0, acc1 = 0.0, acc2 = 0.0, acc3 = 0.0;
+    int64_t i = (int64_t)blockIdx.x * kSumsqBlock + threadIdx.x;
+    for (; i + 3 * kStride < n8; i += 4 * kStride) {
+        const u32x4 a = __builtin_nontemporal_load(G + i);
+        const u32x4 b = __builtin_nontemporal_load(G + i + kStride);
+        const u32x4 d = __builtin_nontemporal_load(G + i + 2 * kStride);
+        const u32x4 e = __builtin_nontemporal_load(G + i + 3 * kStride);
+        acc0 = sq_eight<FP16>(a, acc0);
+        acc1 = sq_eight<FP16>(b, acc1);
+        acc2 = sq_eight<FP16>(d, acc2);
+        acc3 = sq_eight<FP16>(e, acc3);
+    }
+    for (; i < n8; i += kStride) acc0 = sq_eight<FP16>(__builtin_nontemporal_load(G + i), acc0);
+    if (blockIdx.x == 0) {
+        if ((int64_t)threadIdx.x < head) {
+            const double x = (double)widen<FP16>(g[threadIdx.x]);
+            acc0 = fma(x, x, acc0);
+        }
+        const int64_t k = tail0 + threadIdx.x;
+        if (k < n) {
+            const double x = (double)widen<FP16>(g[k]);
+            acc0 = fma(x, x, acc0);
+        }
+    }
+    double x = (acc0 + acc1) + (acc2 + acc3);
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) x += __shfl_down(x, off, 64);
+    if (threadIdx.x == 0) partials[(int64_t)c * kNormBlocksPerChunk + blockIdx.x] = x;
 }
 
 // Stage 1b: the gradient reduction of reduce.hip that also leaves the sum of squares of the values it writes, over
@@ -230,7 +297,46 @@ extern "C" int elixir_chunk_grad_norm(elixir_ctx* ctx, const float* const* grad_
         ELIXIR_LAUNCH_CHECK("sumsq_kernel");
     }
     hipLaunchKernelGGL(finish_kernel, dim3(1), dim3(1024), 0, s, ctx->d_partials,
-                       (int64_t)n_chunks * kNormBlocksPerChunk, max_norm, d_norm_out, d_clip_coef_out);
+                       (int64_t)n_chunks * kNormBlocksPerChunk, max_norm, 1.0, d_norm_out, d_clip_coef_out);
+    ELIXIR_LAUNCH_CHECK("finish_kernel");
+    return ELIXIR_OK;
+}
+
+extern "C" int elixir_chunk_grad_norm_lp(elixir_ctx* ctx, const uint16_t* const* grad_chunks_lowp, int lowp_format,
+                                         const int64_t* valid_len, int n_chunks, float scale, float max_norm,
+                                         float* d_norm_out, float* d_grad_scale_out, elixir_stream_t stream) {
+    static const char* what = "elixir_chunk_grad_norm_lp";
+    if (!ctx) return fail(ELIXIR_EINVAL, "%s: ctx is NULL", what);
+    if (n_chunks < 0 || (n_chunks > 0 && (!grad_chunks_lowp || !valid_len))) return fail(ELIXIR_EINVAL, "%s: NULL table or negative n_chunks", what);
+    if (lowp_format != ELIXIR_LOWP_BF16 && lowp_format != ELIXIR_LOWP_FP16)
+        return fail(ELIXIR_EINVAL, "%s: lowp_format=%d is neither ELIXIR_LOWP_BF16 nor ELIXIR_LOWP_FP16", what, lowp_format);
+    if (!(fabsf(scale) <= 3.402823466e38f)) return fail(ELIXIR_EINVAL, "%s: scale must be finite", what);
+    if (n_chunks > ctx->max_chunks) return fail(ELIXIR_ECAP, "%s: %d chunks, context sized for %d", what, n_chunks, ctx->max_chunks);
+    if (!aligned(d_norm_out, 4) || !aligned(d_grad_scale_out, 4)) return fail(ELIXIR_EALIGN, "%s: output pointer not 4-byte aligned", what);
+    for (int c = 0; c < n_chunks; ++c) {
+        if (valid_len[c] < 0 || valid_len[c] > ctx->max_chunk_elems)
+            return fail(valid_len[c] < 0 ? ELIXIR_EINVAL : ELIXIR_ECAP, "%s: valid_len[%d]=%lld outside [0, %lld]", what, c,
+                        (long long)valid_len[c], (long long)ctx->max_chunk_elems);
+        if (valid_len[c] > 0 && !grad_chunks_lowp[c]) return fail(ELIXIR_EINVAL, "%s: grad_chunks_lowp[%d] is NULL", what, c);
+        if (!aligned(grad_chunks_lowp[c], 2)) return fail(ELIXIR_EALIGN, "%s: grad_chunks_lowp[%d] not 2-byte aligned", what, c);
+    }
+    hipStream_t s = (hipStream_t)stream;
+    for (int c0 = 0; c0 < n_chunks; c0 += kMaxBatch) {
+        const int nb = n_chunks - c0 < kMaxBatch ? n_chunks - c0 : kMaxBatch;
+        LowpChunkTable tab;
+        for (int j = 0; j < kMaxBatch; ++j) {
+            tab.ptr[j] = j < nb ? grad_chunks_lowp[c0 + j] : nullptr;
+            tab.valid[j] = j < nb ? valid_len[c0 + j] : 0;
+        }
+        double* partials = ctx->d_partials + (int64_t)c0 * kNormBlocksPerChunk;
+        if (lowp_format == ELIXIR_LOWP_FP16)
+            hipLaunchKernelGGL(sumsq_lowp_kernel<true>, dim3(kNormBlocksPerChunk, nb), dim3(kSumsqBlock), 0, s, tab, partials);
+        else
+            hipLaunchKernelGGL(sumsq_lowp_kernel<false>, dim3(kNormBlocksPerChunk, nb), dim3(kSumsqBlock), 0, s, tab, partials);
+        ELIXIR_LAUNCH_CHECK("sumsq_lowp_kernel");
+    }
+    hipLaunchKernelGGL(finish_kernel, dim3(1), dim3(1024), 0, s, ctx->d_partials, (int64_t)n_chunks * kNormBlocksPerChunk, max_norm,
+                       (double)scale, d_norm_out, d_grad_scale_out);
     ELIXIR_LAUNCH_CHECK("finish_kernel");
     return ELIXIR_OK;
 }
@@ -280,7 +386,7 @@ extern "C" int elixir_chunk_grad_norm_finish(elixir_ctx* ctx, int n_chunks, floa
     if (n_chunks > ctx->max_chunks) return fail(ELIXIR_ECAP, "%s: %d chunks, context sized for %d", what, n_chunks, ctx->max_chunks);
     if (!aligned(d_norm_out, 4) || !aligned(d_clip_coef_out, 4)) return fail(ELIXIR_EALIGN, "%s: output pointer not 4-byte aligned", what);
     hipLaunchKernelGGL(finish_kernel, dim3(1), dim3(1024), 0, (hipStream_t)stream, ctx->d_partials,
-                       (int64_t)n_chunks * kNormBlocksPerChunk, max_norm, d_norm_out, d_clip_coef_out);
+                       (int64_t)n_chunks * kNormBlocksPerChunk, max_norm, 1.0, d_norm_out, d_clip_coef_out);
     ELIXIR_LAUNCH_CHECK("finish_kernel");
     return ELIXIR_OK;
 }

@@ -98,6 +98,70 @@ def _oracle_norm_streamed(chunks, valid):
     return math.sqrt(math.fsum(parts))
 
 
+def test_gpt2_1p5b_clip_on_bf16_gradient_chunks_full_size():
+    """One micro-batch with clipping, the paper's arrangement: the gradients sit in low-precision chunks (Sec. 4.1), the
+    norm is taken over those 26 chunks directly (full, against the oracle on the widened values), and the tiled update
+    reads them with the device-resident factor and writes the new parameters over them."""
+    cfg = gen.CONFIGS["gpt2_1p5b"]
+    C = cfg.chunk_elems
+    _, _, valid = ex.elixir_layout_plan(cfg.numels(), C, ex.ELIXIR_LAYOUT_NEXT_FIT, 1)
+    nch = len(valid)
+    rng = np.random.default_rng(6)
+    gkey = gen.stream_key(gen.BASE_SEED, gen.TAG_GRAD, 1, 0, cfg.cfg_id)
+    g = torch.zeros(nch, C, dtype=torch.int16, device=DEV)
+    for c in range(nch):
+        gen.fill_bf16_device(g[c].data_ptr(), valid[c], gkey, c * C, cfg.grad_std, cfg.grad_zero_pct)
+    torch.cuda.synchronize()
+    ctx = ex.elixir_ctx_create(0, C, nch)
+    try:
+        d_nc = torch.zeros(2, dtype=torch.float32, device=DEV)
+        ex.elixir_chunk_grad_norm_lp(ctx, [g[c] for c in range(nch)], ex.ELIXIR_LOWP_BF16, valid, 1.0, 1.0, d_nc[0:1], d_nc[1:2])
+        torch.cuda.synchronize()
+        first = d_nc.cpu().numpy().copy()
+        ex.elixir_chunk_grad_norm_lp(ctx, [g[c] for c in range(nch)], ex.ELIXIR_LOWP_BF16, valid, 1.0, 1.0, d_nc[0:1], d_nc[1:2])
+        torch.cuda.synchronize()
+        assert np.array_equal(first.view(np.uint32), d_nc.cpu().numpy().view(np.uint32)), "norm not reproducible"
+
+        def one(c):
+            h = orc.bf16_to_f32(u16(g[c][:valid[c]]))
+            k = n_threads()
+            edges = np.linspace(0, h.size, k + 1).astype(np.int64)
+            return [orc.sum_squares(h[edges[j]:edges[j + 1]]) for j in range(k)]
+        import math
+        parts = []
+        with ThreadPoolExecutor(4) as pool:
+            for r in pool.map(one, range(nch)):
+                parts += r
+        want = math.sqrt(math.fsum(parts))
+        want_coef = orc.clip_coef(want, 1.0)
+        print(f"1.5B norm over bf16 chunks: gpu {first[0]:.6f} oracle {want:.6f}; factor gpu {first[1]:.8f} oracle {want_coef:.8f}")
+        assert abs(first[0] - want) <= 1e-6 * want and abs(first[1] - want_coef) <= 1e-6 * want_coef
+        assert 36.0 < want < 42.0                      # sigma 1e-3 on 99% of 1.56e9 elements: the clip is active
+        pkey = gen.stream_key(gen.BASE_SEED, gen.TAG_PARAM, cfg=cfg.cfg_id)
+        state = torch.empty(3, C, dtype=torch.float32, device=DEV)
+        tiled = torch.empty(ex.elixir_state_tiled_len(C), dtype=torch.float32, device=DEV)
+        for c in (1, nch - 1):
+            state.zero_()
+            gen.fill_f32_device(state[0].data_ptr(), valid[c], pkey, c * C, cfg.param_std)
+            torch.cuda.synchronize()
+            ref = state.cpu().numpy()
+            hg = u16(g[c]).copy()
+            assert np.array_equal(hg[:4096], gen.fill_bf16(gkey, c * C, 4096, cfg.grad_std, cfg.grad_zero_pct))
+            ex.elixir_state_tile(tiled, state[0], state[1], state[2], C)
+            ex.elixir_chunk_adam_step_tiled_lp(tiled, None, g[c], g[c], ex.ELIXIR_LOWP_BF16, valid[c], hp_struct(1), d_nc[1:2])
+            ex.elixir_state_untile(tiled, state[0], state[1], state[2], C)
+            torch.cuda.synchronize()
+            rp, rm, rv, rout = ref[0].copy(), ref[1].copy(), ref[2].copy(), np.zeros(C, np.uint16)
+            oracle_adam_parallel(rp, rm, rv, hg, rout, step=1, grad_scale=float(first[1]))
+            got = state.cpu().numpy()
+            check_adam_close(got[0], got[1], got[2], rp, rm, rv, lr=HP["lr"], gmax=3.5e-3 * float(first[1]), what=f"1.5B clip chunk {c}")
+            now = u16(g[c])
+            check_bf16_copy(now[:valid[c]], got[0][:valid[c]], rout[:valid[c]], rp[:valid[c]], lr=HP["lr"], what=f"1.5B clip chunk {c}")
+            assert not now[valid[c]:].any() and not got[:, valid[c]:].view(np.uint32).any()     # padding untouched
+    finally:
+        ex.elixir_ctx_destroy(ctx)
+
+
 def test_gpt2_6b_accumulate_norm_clip_step_full_size():
     """Four micro-batches reduced into fp32 chunks (mean), global norm over all 50 chunks of 128Mi elements,
     clip to max-norm 1, AdamW with the clip coefficient taken from device memory."""

@@ -282,6 +282,118 @@ def test_norm_closed_forms_and_no_clip(ctx):
     assert e.value.code == ex.ELIXIR_ECAP
 
 
+def _lowp_bits(fmt, key, n, std):
+    """n gradient values as 16-bit patterns of the given format, and their exact fp32 values."""
+    if fmt == ex.ELIXIR_LOWP_FP16:
+        bits = gen.fill_f32(key, 0, n, std).astype(np.float16).view(np.uint16)
+        return bits, orc.f16_to_f32(bits)
+    bits = gen.fill_bf16(key, 0, n, std, zero_pct=1)
+    return bits, orc.bf16_to_f32(bits)
+
+
+@pytest.mark.parametrize("fmt", [ex.ELIXIR_LOWP_BF16, ex.ELIXIR_LOWP_FP16])
+def test_lowp_norm_ragged_and_misaligned_chunks_against_the_oracle(ctx, fmt):
+    """The norm taken directly over 16-bit gradient chunks: every start phase within a 16-byte line, lengths around the
+    group of eight, one chunk long enough for the four-loads-per-lane loop; whatever lies behind valid_len (Inf bits
+    here) does not count; a scale that is folded into both outputs; bitwise reproducible."""
+    lens = [0, 1, 7, 8, 9, 15, 16, 17, 1023, 65_536, 777_777, 4 * 65_536 * 8 + 3]
+    bits, vals, views = [], [], []
+    for i, n in enumerate(lens):
+        b, v = _lowp_bits(fmt, gen.stream_key(70 + fmt, gen.TAG_GRAD, 0, i), n + 24, 5e-4)
+        start = i % 8
+        b[start + n:] = 0x7C00 if fmt == ex.ELIXIR_LOWP_FP16 else 0x7F80          # +Inf behind the valid part
+        bits.append(b)
+        vals.append(np.ascontiguousarray(v[start:start + n]))
+        views.append(dev(b)[start:start + max(n, 1)])
+    want = orc.grad_norm(vals, lens)
+    d_out = torch.zeros(2, dtype=torch.float32, device=DEV)
+    for scale, max_norm in ((1.0, 0.0), (1.0, 0.01), (0.25, 0.002), (-0.5, 1e9)):
+        ex.elixir_chunk_grad_norm_lp(ctx, views, fmt, lens, scale, max_norm, d_out[0:1], d_out[1:2])
+        sync()
+        first = host(d_out).copy()
+        ex.elixir_chunk_grad_norm_lp(ctx, views, fmt, lens, scale, max_norm, d_out[0:1], d_out[1:2])
+        sync()
+        assert np.array_equal(first.view(np.uint32), host(d_out).view(np.uint32))
+        assert first[0] == pytest.approx(abs(scale) * want, rel=2e-7)
+        assert first[1] == pytest.approx(scale * orc.clip_coef(abs(scale) * want, max_norm), rel=1e-6)
+    # the fp32 path on the widened values: same sum, another grouping of the lanes' elements
+    d32 = torch.zeros(2, dtype=torch.float32, device=DEV)
+    ex.elixir_chunk_grad_norm(ctx, [dev(v) if v.size else dev(np.zeros(1, np.float32)) for v in vals], lens, 0.01, d32[0:1], d32[1:2])
+    ex.elixir_chunk_grad_norm_lp(ctx, views, fmt, lens, 1.0, 0.01, d_out[0:1], d_out[1:2])
+    sync()
+    assert host(d_out) == pytest.approx(host(d32), rel=2e-7)
+
+
+def test_lowp_norm_special_values_empty_and_errors(ctx):
+    d_out = torch.full((2,), 9.0, dtype=torch.float32, device=DEV)
+    ex.elixir_chunk_grad_norm_lp(ctx, [], ex.ELIXIR_LOWP_BF16, [], 1.0, 1.0, d_out[0:1], d_out[1:2])
+    sync()
+    assert host(d_out)[0] == 0.0 and host(d_out)[1] == 1.0
+    n = 10_000
+    for fmt, inf, nan, big in ((ex.ELIXIR_LOWP_FP16, 0x7C00, 0x7E01, 0x7BFF), (ex.ELIXIR_LOWP_BF16, 0xFF80, 0x7FC1, 0x7F7F)):
+        for special, check in ((inf, np.isinf), (nan, np.isnan)):
+            b = np.zeros(n, np.uint16)
+            b[n - 3] = special
+            ex.elixir_chunk_grad_norm_lp(ctx, [dev(b)], fmt, [n], 1.0, 1.0, d_out[0:1], d_out[1:2])
+            sync()
+            got = host(d_out)
+            assert check(got[0])
+            assert got[1] == (1.0 if special == nan else 0.0)      # r < 1 ? r : 1 with r = NaN or 0
+            ex.elixir_chunk_grad_norm_lp(ctx, [dev(b)], fmt, [n - 3], 1.0, 1.0, d_out[0:1], d_out[1:2])   # the special value is padding now
+            sync()
+            assert host(d_out)[0] == 0.0
+        b = np.full(n, big, np.uint16)                                  # the largest finite value everywhere: no overflow of the double sum
+        ex.elixir_chunk_grad_norm_lp(ctx, [dev(b)], fmt, [n], 1.0, 0.0, d_out[0:1], d_out[1:2])
+        sync()
+        one = float(orc.f16_to_f32(b[:1])[0] if fmt == ex.ELIXIR_LOWP_FP16 else orc.bf16_to_f32(b[:1])[0])
+        want = one * 100.0
+        got = float(host(d_out)[0])
+        assert (np.isinf(got) and want > 3.4028235e38) or got == pytest.approx(want, rel=1e-6)
+    z = dev(np.zeros(16, np.uint16))
+    for args, code in (((ctx, [z], 7, [16], 1.0, 1.0), ex.ELIXIR_EINVAL), ((ctx, [z], 0, [16], float("inf"), 1.0), ex.ELIXIR_EINVAL),
+                       ((ctx, [z], 0, [-1], 1.0, 1.0), ex.ELIXIR_EINVAL), ((ctx, [z] * 300, 0, [16] * 300, 1.0, 1.0), ex.ELIXIR_ECAP),
+                       ((ctx, [z], 0, [1 << 40], 1.0, 1.0), ex.ELIXIR_ECAP)):
+        with pytest.raises(ex.ElixirError) as e:
+            ex.elixir_chunk_grad_norm_lp(*args, d_out[0:1], d_out[1:2])
+        assert e.value.code == code
+
+
+@pytest.mark.parametrize("fmt", [ex.ELIXIR_LOWP_BF16, ex.ELIXIR_LOWP_FP16])
+def test_single_micro_batch_clip_step_on_low_precision_gradient_chunks(ctx, fmt):
+    """norm over the 16-bit gradient chunks -> scale * clip coefficient on the device -> tiled AdamW that reads the same
+    16-bit gradients and writes the parameters over them: the paper's arrangement (low-precision gradient chunk, Sec. 4.1)
+    with clipping, no fp32 gradient chunk anywhere.  Against the oracle run step by step on the widened values."""
+    lens = [70_001, 4096 * 5, 333]
+    scale, max_norm = 0.5, 0.05
+    states, ref = [], []
+    for i, n in enumerate(lens):
+        p, m, v = _adam_state(n, 900 + i, zero_moments=False)
+        st = torch.zeros(ex.elixir_state_tiled_len(n), dtype=torch.float32, device=DEV)
+        ex.elixir_state_tile(st, dev(p), dev(m), dev(v), n)
+        states.append(st)
+        ref.append([p, m, v])
+    d_out = torch.zeros(2, dtype=torch.float32, device=DEV)
+    for step in (1, 2, 3):
+        bits, vals = zip(*[_lowp_bits(fmt, gen.stream_key(910 + fmt, gen.TAG_GRAD, step, i), n, 2e-3) for i, n in enumerate(lens)])
+        d_g = [dev(b) for b in bits]
+        ex.elixir_chunk_grad_norm_lp(ctx, d_g, fmt, lens, scale, max_norm, d_out[0:1], d_out[1:2])
+        ex.elixir_chunk_adam_step_tiled_multi_lp(states, None, d_g, d_g, fmt, lens, hp_struct(step), d_out[1:2], None)
+        sync()
+        norm = scale * orc.grad_norm(list(vals), lens)
+        gs = scale * orc.clip_coef(norm, max_norm)
+        assert gs < scale                                               # the clip is active
+        assert host(d_out)[0] == pytest.approx(norm, rel=1e-6) and host(d_out)[1] == pytest.approx(gs, rel=1e-6)
+        for i, n in enumerate(lens):
+            want_lowp = np.zeros(n, np.uint16)
+            orc.chunk_adam_step(ref[i][0], ref[i][1], ref[i][2], bits[i], want_lowp, step=step, grad_scale=gs, fmt=fmt, **HP)
+            back = [torch.zeros(n, dtype=torch.float32, device=DEV) for _ in range(3)]
+            ex.elixir_state_untile(states[i], *back, n)
+            sync()
+            check_adam_close(host(back[0]), host(back[1]), host(back[2]), *ref[i], lr=HP["lr"], gmax=1e-2, steps=step, what=f"step {step} chunk {i}")
+            if fmt == ex.ELIXIR_LOWP_BF16:
+                check_bf16_copy(host(d_g[i], np.uint16), host(back[0]), want_lowp, ref[i][0], lr=HP["lr"], steps=step)
+
+
 # --------------------------------------------------------------------------- AdamW
 
 def _adam_state(n, seed, zero_moments):
