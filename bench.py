@@ -106,6 +106,9 @@ def parse():
                     help="gpt2_1p5b / tiny: write the bf16 parameters over the bf16 gradients they were computed from (the paper's "
                          "parameter chunk, which holds the gradients after the backward pass) instead of into an array of their own; "
                          "a gradient set then holds parameters when the ring comes round to it again, which the timing does not see")
+    ap.add_argument("--max-norm", type=float, default=0.0,
+                    help="gpt2_1p5b / tiny: clip every step to this gradient norm; the norm is taken directly over the bf16 gradient "
+                         "chunks (2 more bytes per element) and the update reads the factor from device memory")
     ap.add_argument("--state-layout", choices=["tiled", "flat"], default="tiled",
                     help="optimizer chunk as one buffer of interleaved [master|m|v] tiles (default) or as three arrays")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -924,21 +927,27 @@ def main():
     # or, with --whole-chunks, the padding as well
     lens = [C] * nch if args.whole_chunks else list(valid)
 
+    clip_ctx = ex.elixir_ctx_create(0, C, nch) if args.max_norm > 0 else None
+    d_nc = torch.zeros(2, dtype=torch.float32, device=dev)
+    gscale = d_nc[1:2] if clip_ctx is not None else None
+
     def one_step(step_no):
         hp = ex.make_hparams(cfg.lr, cfg.beta1, cfg.beta2, cfg.eps, cfg.weight_decay, step_no)
         g = grads[(step_no - 1) % n_sets]
         o = g if args.params_over_grads else out
+        if clip_ctx is not None:
+            ex.elixir_chunk_grad_norm_lp(clip_ctx, g, ex.ELIXIR_LOWP_BF16, valid, 1.0, args.max_norm, d_nc[0:1], d_nc[1:2], sh)
         if args.multi and tiled:
-            ex.elixir_chunk_adam_step_tiled_multi_lp(tiled, None, g, o, ex.ELIXIR_LOWP_BF16, lens, hp, None, None, sh)
+            ex.elixir_chunk_adam_step_tiled_multi_lp(tiled, None, g, o, ex.ELIXIR_LOWP_BF16, lens, hp, gscale, None, sh)
             return
         if args.multi:
-            ex.elixir_chunk_adam_step_multi(p_list, m_list, v_list, None, g, o, lens, hp, None, sh)
+            ex.elixir_chunk_adam_step_multi(p_list, m_list, v_list, None, g, o, lens, hp, gscale, sh)
             return
         for c in range(nch):
             if tiled:
-                ex.elixir_chunk_adam_step_tiled_lp(tiled[c], None, g[c], o[c], ex.ELIXIR_LOWP_BF16, lens[c], hp, None, None, sh)
+                ex.elixir_chunk_adam_step_tiled_lp(tiled[c], None, g[c], o[c], ex.ELIXIR_LOWP_BF16, lens[c], hp, gscale, None, sh)
             else:
-                ex.elixir_chunk_adam_step(state[c][0], state[c][1], state[c][2], None, g[c], o[c], lens[c], hp, None, sh)
+                ex.elixir_chunk_adam_step(state[c][0], state[c][1], state[c][2], None, g[c], o[c], lens[c], hp, gscale, sh)
 
     for w in range(W):
         one_step(w + 1)
@@ -967,10 +976,11 @@ def main():
     launches = K * (-(-nch // 64) if args.multi else nch)
     per_launch_elems = sum(lens) / (-(-nch // 64) if args.multi else nch)      # average over the launches of a step
     launch_s = ev_ms * 1e-3 / launches                      # average duration of one launch of the AdamW kernel
-    achieved = BYTES_PER_ELEM * per_launch_elems / launch_s / 1e9          # GB/s, algorithmic bytes of one launch
+    bpe = BYTES_PER_ELEM + (2 if clip_ctx is not None else 0)   # with clipping the norm's read of the bf16 gradients is in the region too
+    achieved = bpe * per_launch_elems / launch_s / 1e9          # GB/s, algorithmic bytes of one launch
     traffic = None
     tpath = os.path.join(ROOT, "profiles", "adam_step_traffic.json")
-    if os.path.exists(tpath) and args.workload == "gpt2_1p5b":
+    if os.path.exists(tpath) and args.workload == "gpt2_1p5b" and clip_ctx is None:
         with open(tpath) as f:                                 # counters were read on whole-chunk launches: scale to this run's average launch
             t = json.load(f)
             traffic = round(t["hbm_bytes_per_launch"] / t["algorithmic_bytes_per_launch"] * BYTES_PER_ELEM * per_launch_elems)
@@ -983,6 +993,8 @@ def main():
                    "processed_elems_per_step": sum(lens), "padding_updated": bool(args.whole_chunks), "layout": "next-fit", "grad_dtype": "bf16",
                    "optimizer_chunk": "tiled [master|m|v], 4096-element tiles" if tiled else "three arrays",
                    "lowp_params": "written over the gradients" if args.params_over_grads else "an array of their own",
+                   "clip": (f"max-norm {args.max_norm}: norm over the bf16 gradient chunks every step (2 more bytes per element, "
+                            f"inside the timed region; last norm {float(d_nc[0].item()):.4f})") if clip_ctx is not None else "none",
                    "grad_sets_resident": n_sets, "hparams": {"lr": cfg.lr, "betas": [cfg.beta1, cfg.beta2],
                                                              "eps": cfg.eps, "weight_decay": cfg.weight_decay}},
         "elements_per_s": sum(lens) * K / wall,
@@ -992,11 +1004,14 @@ def main():
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBPS, "traffic": traffic,
                      "kernel": (("adam_multi_kernel<1, 1, true>" if tiled else "adam_multi_kernel<1, 1, false>") if args.multi else
-                                "adam_tiled_kernel<1, 1>" if tiled else "adam_vec_kernel<1, 1>") + " (bf16 gradient in, bf16 copy out)",
-                     "bytes_per_launch": BYTES_PER_ELEM * per_launch_elems,
+                                "adam_tiled_kernel<1, 1>" if tiled else "adam_vec_kernel<1, 1>") + " (bf16 gradient in, bf16 copy out)" +
+                               (" with the step's sumsq_lowp_kernel<false> shared out over its launches" if clip_ctx is not None else ""),
+                     "bytes_per_launch": bpe * per_launch_elems,
                      "launch_ms": launch_s * 1e3, "launches_timed": launches,
                      "timing": "HIP events on the launch stream around the timed region / launches"},
     }
+    if clip_ctx is not None:
+        ex.elixir_ctx_destroy(clip_ctx)
     if not args.no_rows:
         line["rows"] = side_rows(ex, gen, torch, cfg, C, nch, valid, state, grads, out, stream, wall * 1e3 / K)
         if "pack" in line["rows"]:   # the plain device copy of this library, measured in the same run
