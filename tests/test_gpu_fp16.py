@@ -197,3 +197,59 @@ def test_fp16_training_steps_with_loss_scaling_end_to_end():
         assert steps_done == 2 and S == 2048.0
     finally:
         ex.elixir_ctx_destroy(ctx)
+
+
+def test_fp16_gradient_chunks_with_loss_scaling_and_no_fp32_gradients():
+    """The paper's arrangement end to end (fp16 parameter chunk that holds the scaled gradients after the backward pass,
+    Sec. 2 and 4.1): norm directly over the fp16 gradient chunks -> loss-scale update -> tiled AdamW reading grad_scale
+    and skip from the device state and writing the new fp16 parameters over the gradients.  The second iteration carries
+    an Inf: it is skipped, the chunk keeps its gradients (nothing is written), and the scale halves."""
+    lens = [150_001, 4096 * 7, 77]
+    nch = len(lens)
+    ctx = ex.elixir_ctx_create(0, max(lens), nch)
+    try:
+        st = torch.zeros(4, dtype=torch.float32, device=DEV)
+        ex.elixir_loss_scale_init(st, 1024.0)
+        d_norm = torch.zeros(1, dtype=torch.float32, device=DEV)
+        ref = []
+        states = []
+        for c, n in enumerate(lens):
+            p = gen.fill_f32(gen.stream_key(81, gen.TAG_PARAM, c), 0, n, 0.02)
+            ref.append([p, np.zeros(n, np.float32), np.zeros(n, np.float32)])
+            t = torch.zeros(ex.elixir_state_tiled_len(n), dtype=torch.float32, device=DEV)
+            ex.elixir_state_tile(t, dev(p), torch.zeros(n, device=DEV), torch.zeros(n, device=DEV), n)
+            states.append(t)
+        S, good, steps_done = 1024.0, 0, 0
+        for it in range(3):
+            bits = [f16_grads(gen.stream_key(81, gen.TAG_GRAD, it, c), n, 0.03, S) for c, n in enumerate(lens)]
+            if it == 1:
+                bits[1][4097] = 0xFC00                                       # -Inf
+            d_g = [dev(b) for b in bits]
+            ex.elixir_chunk_grad_norm_lp(ctx, d_g, F16, lens, 1.0, 0.0, d_norm, None)
+            ex.elixir_loss_scale_update(st, d_norm, 1.0, 2.0, 0.5, 2000)
+            ex.elixir_chunk_adam_step_tiled_multi_lp(states, None, d_g, d_g, F16, lens, hp_struct(steps_done + 1), st[3:4], st[2:3].view(torch.int32))
+            torch.cuda.synchronize()
+            vals = [orc.f16_to_f32(b) for b in bits]
+            norm = orc.grad_norm(vals, lens)
+            S_used = S
+            S, good, skip, gs = orc.loss_scale_step(S, good, norm, 1.0, 2.0, 0.5, 2000)
+            raw = st.cpu().numpy()
+            assert float(raw[0]) == S and int(raw.view(np.int32)[2]) == int(skip) and skip == (it == 1)
+            if skip:
+                for c in range(nch):                                          # the gradients are still there, bit for bit
+                    assert np.array_equal(host(d_g[c], np.uint16), bits[c])
+            else:
+                assert float(host(d_norm)[0]) == pytest.approx(norm, rel=1e-6) and float(raw[3]) == pytest.approx(gs, rel=1e-5)
+                assert norm / S_used > 1.0                                    # clipping was active
+                for c, n in enumerate(lens):
+                    want = np.zeros(n, np.uint16)
+                    orc.chunk_adam_step(ref[c][0], ref[c][1], ref[c][2], bits[c], want, step=steps_done + 1, grad_scale=float(raw[3]), fmt=orc.FP16, **HP)
+                    back = [torch.zeros(n, dtype=torch.float32, device=DEV) for _ in range(3)]
+                    ex.elixir_state_untile(states[c], *back, n)
+                    torch.cuda.synchronize()
+                    check_adam_close(host(back[0]), host(back[1]), host(back[2]), *ref[c], lr=HP["lr"], gmax=float(np.abs(vals[c]).max()) * float(raw[3]), steps=steps_done + 1, what=f"iteration {it} chunk {c}")
+                    check_bf16_copy(host(d_g[c], np.uint16), host(back[0]), want, ref[c][0], lr=HP["lr"], steps=steps_done + 1, fmt=1)
+                steps_done += 1
+        assert steps_done == 2 and S == 512.0
+    finally:
+        ex.elixir_ctx_destroy(ctx)
