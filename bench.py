@@ -1013,11 +1013,19 @@ def main():
     if clip_ctx is not None:
         ex.elixir_ctx_destroy(clip_ctx)
     if not args.no_rows:
-        line["rows"] = side_rows(ex, gen, torch, cfg, C, nch, valid, state, grads, out, stream, wall * 1e3 / K)
-        if "pack" in line["rows"]:   # the plain device copy of this library, measured in the same run
-            line["roofline"]["frac_of_measured_device_copy"] = achieved / line["rows"]["pack"]["GB/s"]
+        # the side measurements come after the timed region: if one of them cannot run on this machine (e.g. no pinned memory
+        # left for the offload row) the benchmark line above still stands and says what happened
+        try:
+            line["rows"] = side_rows(ex, gen, torch, cfg, C, nch, valid, state, grads, out, stream, wall * 1e3 / K)
+            if "pack" in line["rows"]:   # the plain device copy of this library, measured in the same run
+                line["roofline"]["frac_of_measured_device_copy"] = achieved / line["rows"]["pack"]["GB/s"]
+        except Exception as e:  # noqa: BLE001
+            line["rows_error"] = f"{type(e).__name__}: {e}"
     if not args.no_cpu_baseline:
-        line["cpu_baseline"] = cpu_baseline(cfg, valid[0], budget_elems=32 * 64 * gen.Mi)
+        try:
+            line["cpu_baseline"] = cpu_baseline(cfg, valid[0], budget_elems=32 * 64 * gen.Mi)
+        except Exception as e:  # noqa: BLE001
+            line["cpu_baseline_error"] = f"{type(e).__name__}: {e}"
     print(json.dumps(line), flush=True)
 
 

@@ -21,12 +21,9 @@ constexpr int kVecBlock = kReduceBlock;  // one 4-element group per thread, one 
                                 // which measured best for this 1-2 read / 1 write stream mix
 constexpr int64_t kMaxBlocksPerLaunch = 1ll << 30;
 
-// dst 16-byte aligned, src 8-byte aligned; n4 complete groups of 4 elements.
+// Group i (4 elements) of one tensor: dst 16-byte aligned, src 8-byte aligned.
 template <bool ACC, bool FP16>
-__global__ __launch_bounds__(kVecBlock) void reduce_vec_kernel(float* __restrict__ dst, const uint16_t* __restrict__ src,
-                                                              int64_t n4, float scale) {
-    const int64_t i = (int64_t)blockIdx.x * kVecBlock + threadIdx.x;
-    if (i >= n4) return;
+__device__ __forceinline__ void reduce_group(float* __restrict__ dst, const uint16_t* __restrict__ src, int64_t i, float scale) {
     f32x4* D = reinterpret_cast<f32x4*>(dst) + i;
     const u32x2 g = __builtin_nontemporal_load(reinterpret_cast<const u32x2*>(src) + i);
     f32x4 a;
@@ -38,6 +35,14 @@ __global__ __launch_bounds__(kVecBlock) void reduce_vec_kernel(float* __restrict
     r.z = reduce_elem<FP16>(a.z, g.y & 0xFFFFu, scale);
     r.w = reduce_elem<FP16>(a.w, g.y >> 16, scale);
     __builtin_nontemporal_store(r, D);
+}
+
+// n4 complete groups of 4 elements, one per thread.
+template <bool ACC, bool FP16>
+__global__ __launch_bounds__(kVecBlock) void reduce_vec_kernel(float* __restrict__ dst, const uint16_t* __restrict__ src,
+                                                              int64_t n4, float scale) {
+    const int64_t i = (int64_t)blockIdx.x * kVecBlock + threadIdx.x;
+    if (i < n4) reduce_group<ACC, FP16>(dst, src, i, scale);
 }
 
 // elements [first, n), any alignment
@@ -70,23 +75,8 @@ __global__ __launch_bounds__(kVecBlock) void reduce_multi_kernel(ReduceMultiTabl
     const int64_t n4 = tab.n4[seg];
     if ((int64_t)blockIdx.x * kVecBlock >= n4) return;  // a row past the end of a shorter tensor (uniform per workgroup)
     const int64_t i = (int64_t)blockIdx.x * kVecBlock + threadIdx.x;
-    if (i >= n4) return;
-    f32x4* D = reinterpret_cast<f32x4*>(tab.dst[seg]) + i;
-    const u32x2 g = __builtin_nontemporal_load(reinterpret_cast<const u32x2*>(tab.src[seg]) + i);
-    f32x4 a;
-    if constexpr (ACC) a = __builtin_nontemporal_load(D);
-    else a = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
-    f32x4 r;
-    r.x = reduce_elem<FP16>(a.x, g.x & 0xFFFFu, scale);
-    r.y = reduce_elem<FP16>(a.y, g.x >> 16, scale);
-    r.z = reduce_elem<FP16>(a.z, g.y & 0xFFFFu, scale);
-    r.w = reduce_elem<FP16>(a.w, g.y >> 16, scale);
-    __builtin_nontemporal_store(r, D);
+    if (i < n4) reduce_group<ACC, FP16>(tab.dst[seg], tab.src[seg], i, scale);
 }
-
-}  // namespace
-
-namespace {
 
 template <bool ACC, bool FP16>
 void launch_reduce(float* dst, const uint16_t* src, int64_t n, float scale, hipStream_t s) {
