@@ -97,6 +97,10 @@ def parse():
     ap.add_argument("--multi", action="store_true",
                     help="update all chunks of a step with elixir_chunk_adam_step_multi (always done for chunks of <= 16Mi elements, "
                          "which are launch-bound one call at a time)")
+    ap.add_argument("--sources-per-pass", type=int, default=1,
+                    help="gpt2_6b_clip: how many micro-batches one reduction pass takes (1 = one pass per micro-batch, as gradients "
+                         "arrive; 2 or 4 need that many bf16 gradient sets resident at once and save the re-reads and re-writes of "
+                         "the fp32 chunk in between: same bits)")
     ap.add_argument("--unfused-norm", action="store_true", help="gpt2_6b_clip: separate norm pass instead of the one fused into the last reduction")
     ap.add_argument("--host-order", choices=["interleaved", "first"], default="interleaved",
                     help="gpt2_20b_offload: which 60%% of the chunks live in host memory (every 3 of 5, or the first 60%% in schedule order)")
@@ -459,13 +463,18 @@ def run_clip(args, torch, ex, gen):
     fused = not args.unfused_norm
     lens = [C] * nch if args.whole_chunks else list(valid)     # padding (all-zero gradients and state) is never touched unless asked for
 
+    spp = max(1, min(args.sources_per_pass, K))
+    passes = [list(range(a, min(a + spp, K))) for a in range(0, K, spp)]          # micro-batches taken by each pass
+
     def reduce_all():
-        for mb in range(K):
+        for which in passes:
+            first, last = which[0] == 0, which[-1] == K - 1
             for c in range(nch):
-                if fused and mb == K - 1:       # the last pass also leaves the chunk's sum of squares in the context
-                    ex.elixir_grad_reduce_chunk_sumsq(ctx, c, gch[c], mbs[mb][c], ex.ELIXIR_LOWP_BF16, lens[c], valid[c], 1.0 / K, mb > 0, sh)
+                srcs = [mbs[mb][c] for mb in which]
+                if fused and last:              # the last pass also leaves the chunk's sum of squares in the context
+                    ex.elixir_grad_reduce_sources_chunk_sumsq(ctx, c, gch[c], srcs, ex.ELIXIR_LOWP_BF16, lens[c], valid[c], 1.0 / K, not first, sh)
                 else:
-                    ex.elixir_grad_reduce_into_chunk(gch[c], 0, mbs[mb][c], lens[c], 1.0 / K, mb > 0, sh)
+                    ex.elixir_grad_reduce_sources_lp(gch[c], 0, srcs, ex.ELIXIR_LOWP_BF16, lens[c], 1.0 / K, not first, sh)
 
     def norm():
         if fused:
@@ -492,7 +501,8 @@ def run_clip(args, torch, ex, gen):
         for name, fn in (("reduce", reduce_all), ("norm", norm), ("adam", adam)):
             parts[name] = _event_time(torch, stream, fn, 2, 1)[1]
         n_el = sum(lens)
-        step_bytes = (6 + 10 * (K - 1) + 30) * n_el + (0 if fused else 4 * sum(valid))
+        reduce_bytes = sum(2 * len(w) + 4 + (4 if w[0] > 0 else 0) for w in passes)     # per element: sources read, chunk written (+ read)
+        step_bytes = (reduce_bytes + 30) * n_el + (0 if fused else 4 * sum(valid))
         print(json.dumps({
             "metric": "chunked AdamW params/sec (4 micro-batches reduced, global norm, clip, step)", "value": sum(valid) / wall,
             "unit": "params/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": wall * 1e3,
@@ -500,16 +510,16 @@ def run_clip(args, torch, ex, gen):
             "config": {"workload": cfg.name, "params": sum(valid), "chunk_elems": C, "n_chunks": nch, "micro_batches": K,
                        "processed_elems_per_step": n_el, "padding_updated": bool(args.whole_chunks),
                        "optimizer_chunk": "tiled [master|m|v], 4096-element tiles" if tiled else "three arrays",
-                       "max_norm": cfg.max_norm},
+                       "micro_batches_per_reduction_pass": spp, "max_norm": cfg.max_norm},
             "norm": float(d_nc[0].item()), "clip_coef": float(d_nc[1].item()),
             "phase_ms": {k: v * 1e3 for k, v in parts.items()},
             "norm_fused_into_last_reduction": fused,
-            "phase_GB/s": {"reduce": (6 + 10 * (K - 1)) * n_el / parts["reduce"] / 1e9,
+            "phase_GB/s": {"reduce": reduce_bytes * n_el / parts["reduce"] / 1e9,
                            "norm": None if fused else 4 * sum(valid) / parts["norm"] / 1e9,
                            "adam_fp32_grad": 30 * n_el / parts["adam"] / 1e9},
             "roofline": {"bound": "hbm", "achieved": step_bytes / 1e9 / ev, "peak": HBM_PEAK_GBPS, "unit": "GB/s", "traffic": None,
                          "frac": step_bytes / 1e9 / ev / HBM_PEAK_GBPS,
-                         "note": "whole step: 6 + 3*10 (reduce) + 30 (AdamW, fp32 gradient) bytes per element"
+                         "note": f"whole step: {reduce_bytes} (reduce, {len(passes)} pass{'es' if len(passes) > 1 else ''}) + 30 (AdamW, fp32 gradient) bytes per element"
                                  + ("" if fused else " + 4 per valid element (norm)")}}), flush=True)
     finally:
         ex.elixir_ctx_destroy(ctx)

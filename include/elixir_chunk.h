@@ -332,6 +332,26 @@ int elixir_grad_reduce_into_chunk_lp(float* d_grad_chunk, int64_t offset, const 
  */
 int elixir_grad_reduce_multi_lp(int n_tensors, float* const* d_dst, const uint16_t* const* d_grad_lowp, const int64_t* n,
                                 int lowp_format, float scale, int accumulate, elixir_stream_t stream);
+
+/*
+ * Several gradient arrays summed into the chunk in one pass.  With room for more than one set of low-precision
+ * gradients (the next micro-batch's gradients while the previous ones are still there; on several GPUs the pieces
+ * the other ranks sent for this rank's share of the chunk) the fp32 chunk need not be re-read and re-written once per
+ * array:  for k < n, in this order,
+ *   x = accumulate ? d_grad_chunk[offset+k] : 0;   for j = 0 .. n_sources-1:  x = fl32(x + fl32(scale * widen(d_grad_lowp[j][k])));
+ *   d_grad_chunk[offset+k] = x
+ * i.e. bit for bit what n_sources consecutive calls of elixir_grad_reduce_into_chunk_lp leave, at
+ * 2*n_sources + 4 bytes per element instead of 10*n_sources - 4 (4 more on either side when accumulating).  d_grad_lowp is a HOST
+ * array of n_sources device pointers; up to four arrays go into one pass, more are taken four at a time.
+ * elixir_grad_reduce_sources_chunk_sumsq is elixir_grad_reduce_chunk_sumsq for several arrays (whole chunks, the sum
+ * of squares of the final values left for elixir_chunk_grad_norm_finish).
+ */
+int elixir_grad_reduce_sources_lp(float* d_grad_chunk, int64_t offset, const uint16_t* const* d_grad_lowp, int n_sources,
+                                  int lowp_format, int64_t n, float scale, int accumulate, elixir_stream_t stream);
+int elixir_grad_reduce_sources_chunk_sumsq(elixir_ctx* ctx, int chunk_index, float* d_grad_chunk,
+                                           const uint16_t* const* d_grad_lowp, int n_sources, int lowp_format,
+                                           int64_t chunk_elems, int64_t valid_len, float scale, int accumulate,
+                                           elixir_stream_t stream);
 int elixir_chunk_adam_step_lp(float* d_master, float* d_exp_avg, float* d_exp_avg_sq, const float* d_grad_fp32,
                               const uint16_t* d_grad_lowp, uint16_t* d_param_lowp, int lowp_format, int64_t n,
                               const elixir_adam_hparams* hp, const float* d_grad_scale, const int32_t* d_skip,

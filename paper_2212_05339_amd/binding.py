@@ -28,7 +28,7 @@ EXPORTS = (
     "elixir_copy_d2h_async", "elixir_stream_synchronize", "elixir_offload_benefit", "elixir_offload_plan",
     "elixir_rcache_simulate", "elixir_chunk_size_search", "elixir_grad_reduce_into_chunk_lp", "elixir_chunk_adam_step_lp",
     "elixir_chunk_adam_step_multi_lp", "elixir_loss_scale_init", "elixir_loss_scale_update",
-    "elixir_grad_reduce_chunk_sumsq", "elixir_chunk_grad_norm_finish", "elixir_grad_reduce_multi_lp", "elixir_chunk_grad_norm_lp",
+    "elixir_grad_reduce_chunk_sumsq", "elixir_chunk_grad_norm_finish", "elixir_grad_reduce_multi_lp", "elixir_chunk_grad_norm_lp", "elixir_grad_reduce_sources_lp", "elixir_grad_reduce_sources_chunk_sumsq",
     "elixir_state_tiled_len", "elixir_state_tile", "elixir_state_untile", "elixir_chunk_adam_step_tiled_lp",
     "elixir_chunk_adam_step_tiled_multi_lp", "elixir_host_adam_step_tiled",
 )
@@ -96,6 +96,8 @@ def lib() -> ctypes.CDLL:
                                                    ctypes.POINTER(elixir_adam_hparams), vp, vp, vp]
         sigs["elixir_grad_reduce_chunk_sumsq"] = [vp, ci, vp, vp, ci, i64, i64, f32, ci, vp]
         sigs["elixir_chunk_grad_norm_finish"] = [vp, ci, f32, vp, vp, vp]
+        sigs["elixir_grad_reduce_sources_lp"] = [vp, i64, ctypes.POINTER(vp), ci, ci, i64, f32, ci, vp]
+        sigs["elixir_grad_reduce_sources_chunk_sumsq"] = [vp, ci, vp, ctypes.POINTER(vp), ci, ci, i64, i64, f32, ci, vp]
         sigs["elixir_chunk_grad_norm_lp"] = [vp, ctypes.POINTER(vp), ci, pi64, ci, f32, f32, vp, vp, vp]
         sigs["elixir_grad_reduce_multi_lp"] = [ci, ctypes.POINTER(vp), ctypes.POINTER(vp), pi64, ci, f32, ci, vp]
         sigs["elixir_state_tile"] = [vp, vp, vp, vp, i64, vp]
@@ -448,6 +450,20 @@ def elixir_grad_reduce_chunk_sumsq(ctx: Ctx, chunk_index: int, grad_chunk, grad_
                                    valid_len: int, scale: float, accumulate: bool, stream=None) -> None:
     _check(lib().elixir_grad_reduce_chunk_sumsq(ctx.handle, chunk_index, _addr(grad_chunk), _addr(grad_lowp), lowp_format,
                                                 chunk_elems, valid_len, scale, 1 if accumulate else 0, _stream(stream)))
+
+
+def elixir_grad_reduce_sources_lp(grad_chunk, offset: int, grads_lowp, lowp_format: int, n: int, scale: float, accumulate: bool,
+                                  stream=None) -> None:
+    """Several low-precision gradient arrays (a list) summed into the fp32 chunk in one pass."""
+    _check(lib().elixir_grad_reduce_sources_lp(_addr(grad_chunk), offset, _ptr_array(grads_lowp), len(grads_lowp), lowp_format, n, scale,
+                                               1 if accumulate else 0, _stream(stream)))
+
+
+def elixir_grad_reduce_sources_chunk_sumsq(ctx: Ctx, chunk_index: int, grad_chunk, grads_lowp, lowp_format: int, chunk_elems: int,
+                                           valid_len: int, scale: float, accumulate: bool, stream=None) -> None:
+    _check(lib().elixir_grad_reduce_sources_chunk_sumsq(ctx.handle, chunk_index, _addr(grad_chunk), _ptr_array(grads_lowp), len(grads_lowp),
+                                                        lowp_format, chunk_elems, valid_len, scale, 1 if accumulate else 0,
+                                                        _stream(stream)))
 
 
 def elixir_chunk_grad_norm_finish(ctx: Ctx, n_chunks: int, max_norm: float, d_norm_out, d_clip_coef_out, stream=None) -> None:

@@ -189,24 +189,13 @@ __global__ __launch_bounds__(kSumsqBlock) void sumsq_lowp_kernel(LowpChunkTable 
 // data only.
 constexpr int kFusedBlock = 64;
 
-template <bool ACC, bool FP16>
-__global__ __launch_bounds__(kFusedBlock) void reduce_sumsq_kernel(float* __restrict__ dst, const uint16_t* __restrict__ src,
-                                                                  int64_t n4, int64_t valid, float scale,
-                                                                  double* __restrict__ stage) {
+template <bool ACC, bool FP16, int NSRC>
+__global__ __launch_bounds__(kFusedBlock) void reduce_sumsq_kernel(float* __restrict__ dst, SrcTable srcs, int64_t n4, int64_t valid,
+                                                                  float scale, double* __restrict__ stage) {
     const int64_t i = (int64_t)blockIdx.x * kFusedBlock + threadIdx.x;
     double x = 0.0;
     if (i < n4) {
-        f32x4* D = reinterpret_cast<f32x4*>(dst) + i;
-        const u32x2 g = __builtin_nontemporal_load(reinterpret_cast<const u32x2*>(src) + i);
-        f32x4 a;
-        if constexpr (ACC) a = __builtin_nontemporal_load(D);
-        else a = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
-        f32x4 r;
-        r.x = reduce_elem<FP16>(a.x, g.x & 0xFFFFu, scale);
-        r.y = reduce_elem<FP16>(a.y, g.x >> 16, scale);
-        r.z = reduce_elem<FP16>(a.z, g.y & 0xFFFFu, scale);
-        r.w = reduce_elem<FP16>(a.w, g.y >> 16, scale);
-        __builtin_nontemporal_store(r, D);
+        const f32x4 r = reduce_group<ACC, FP16, NSRC>(dst, srcs, i, scale);
         const int64_t k = i * 4;
         if (k + 0 < valid) x = fma((double)r.x, (double)r.x, x);
         if (k + 1 < valid) x = fma((double)r.y, (double)r.y, x);
@@ -218,14 +207,15 @@ __global__ __launch_bounds__(kFusedBlock) void reduce_sumsq_kernel(float* __rest
     if (threadIdx.x == 0) stage[blockIdx.x] = x;
 }
 
-// The at most 3 elements after the last complete group of 4 (one thread each), added to the last stage entry's
-// successor so that the fold below sees them.
+// The at most 3 elements after the last complete group of 4 (one thread), all sources in order; their squares go to
+// the stage entry after the last wavefront's so that the fold below sees them.
 template <bool ACC, bool FP16>
-__global__ void reduce_sumsq_tail_kernel(float* dst, const uint16_t* src, int64_t first, int64_t n, int64_t valid, float scale,
+__global__ void reduce_sumsq_tail_kernel(float* dst, SrcTable srcs, int n_src, int64_t first, int64_t n, int64_t valid, float scale,
                                          double* stage_slot) {
     double sq = 0.0;
     for (int64_t k = first; k < n; ++k) {
-        const float r = reduce_elem<FP16>(ACC ? dst[k] : 0.0f, src[k], scale);
+        float r = ACC ? dst[k] : 0.0f;
+        for (int j = 0; j < n_src; ++j) r = reduce_elem<FP16>(r, srcs.p[j][k], scale);
         dst[k] = r;
         if (k < valid) sq = fma((double)r, (double)r, sq);
     }
@@ -250,15 +240,22 @@ __global__ __launch_bounds__(256) void fold_stage_kernel(const double* __restric
 }
 
 template <bool ACC, bool FP16>
-void launch_fused(float* dst, const uint16_t* src, int64_t n, int64_t valid, float scale, double* stage, double* slots,
+void launch_fused(float* dst, const SrcTable& srcs, int n_src, int64_t n, int64_t valid, float scale, double* stage, double* slots,
                   hipStream_t s) {
     const int64_t n4 = n / 4;
     const int64_t blocks = (n4 + kFusedBlock - 1) / kFusedBlock;  // < 2^31: the caller checked chunk_elems
-    if (blocks > 0)
-        hipLaunchKernelGGL((reduce_sumsq_kernel<ACC, FP16>), dim3((unsigned)blocks), dim3(kFusedBlock), 0, s, dst, src, n4, valid, scale, stage);
+    if (blocks > 0) {
+        const dim3 grid((unsigned)blocks), block(kFusedBlock);
+        switch (n_src) {
+            case 1: hipLaunchKernelGGL((reduce_sumsq_kernel<ACC, FP16, 1>), grid, block, 0, s, dst, srcs, n4, valid, scale, stage); break;
+            case 2: hipLaunchKernelGGL((reduce_sumsq_kernel<ACC, FP16, 2>), grid, block, 0, s, dst, srcs, n4, valid, scale, stage); break;
+            case 3: hipLaunchKernelGGL((reduce_sumsq_kernel<ACC, FP16, 3>), grid, block, 0, s, dst, srcs, n4, valid, scale, stage); break;
+            default: hipLaunchKernelGGL((reduce_sumsq_kernel<ACC, FP16, 4>), grid, block, 0, s, dst, srcs, n4, valid, scale, stage); break;
+        }
+    }
     int64_t count = blocks;
     if (n4 * 4 < n) {
-        hipLaunchKernelGGL((reduce_sumsq_tail_kernel<ACC, FP16>), dim3(1), dim3(1), 0, s, dst, src, n4 * 4, n, valid, scale, stage + blocks);
+        hipLaunchKernelGGL((reduce_sumsq_tail_kernel<ACC, FP16>), dim3(1), dim3(1), 0, s, dst, srcs, n_src, n4 * 4, n, valid, scale, stage + blocks);
         ++count;
     }
     hipLaunchKernelGGL(fold_stage_kernel, dim3(kNormBlocksPerChunk / 4), dim3(256), 0, s, stage, count, slots);
@@ -341,15 +338,17 @@ extern "C" int elixir_chunk_grad_norm_lp(elixir_ctx* ctx, const uint16_t* const*
     return ELIXIR_OK;
 }
 
-extern "C" int elixir_grad_reduce_chunk_sumsq(elixir_ctx* ctx, int chunk_index, float* d_grad_chunk, const uint16_t* d_grad_lowp,
-                                              int lowp_format, int64_t chunk_elems, int64_t valid_len, float scale,
-                                              int accumulate, elixir_stream_t stream) {
+extern "C" int elixir_grad_reduce_sources_chunk_sumsq(elixir_ctx* ctx, int chunk_index, float* d_grad_chunk,
+                                                      const uint16_t* const* d_grad_lowp, int n_sources, int lowp_format,
+                                                      int64_t chunk_elems, int64_t valid_len, float scale, int accumulate,
+                                                      elixir_stream_t stream) {
     static const char* what = "elixir_grad_reduce_chunk_sumsq";
     if (!ctx) return fail(ELIXIR_EINVAL, "%s: ctx is NULL", what);
     if (chunk_index < 0 || chunk_index >= ctx->max_chunks)
         return fail(ELIXIR_ECAP, "%s: chunk_index=%d, context sized for %d chunks", what, chunk_index, ctx->max_chunks);
     if (chunk_elems < 0 || valid_len < 0 || valid_len > chunk_elems)
         return fail(ELIXIR_EINVAL, "%s: need 0 <= valid_len <= chunk_elems", what);
+    if (n_sources < 1) return fail(ELIXIR_EINVAL, "%s: n_sources=%d, at least one gradient array is needed", what, n_sources);
     if (chunk_elems > ctx->max_chunk_elems)
         return fail(ELIXIR_ECAP, "%s: chunk of %lld elements, context sized for %lld", what, (long long)chunk_elems, (long long)ctx->max_chunk_elems);
     if (lowp_format != ELIXIR_LOWP_BF16 && lowp_format != ELIXIR_LOWP_FP16)
@@ -364,18 +363,38 @@ extern "C" int elixir_grad_reduce_chunk_sumsq(elixir_ctx* ctx, int chunk_index, 
         return ELIXIR_OK;
     }
     if (!d_grad_chunk || !d_grad_lowp) return fail(ELIXIR_EINVAL, "%s: NULL pointer", what);
-    if (!aligned(d_grad_chunk, 16) || !aligned(d_grad_lowp, 8))
-        return fail(ELIXIR_EALIGN, "%s: whole chunks are expected: the fp32 chunk 16-byte and the 16-bit gradients 8-byte aligned", what);
+    if (!aligned(d_grad_chunk, 16)) return fail(ELIXIR_EALIGN, "%s: whole chunks are expected: the fp32 chunk 16-byte aligned", what);
+    for (int k = 0; k < n_sources; ++k) {
+        if (!d_grad_lowp[k]) return fail(ELIXIR_EINVAL, "%s: gradient array %d is NULL", what, k);
+        if (!aligned(d_grad_lowp[k], 8)) return fail(ELIXIR_EALIGN, "%s: whole chunks are expected: the 16-bit gradients 8-byte aligned", what);
+    }
     const bool f16 = lowp_format == ELIXIR_LOWP_FP16;
-    if (accumulate) {
-        if (f16) launch_fused<true, true>(d_grad_chunk, d_grad_lowp, chunk_elems, valid_len, scale, ctx->d_stage, slots, s);
-        else launch_fused<true, false>(d_grad_chunk, d_grad_lowp, chunk_elems, valid_len, scale, ctx->d_stage, slots, s);
+    // all but the last kMaxSources (or fewer) sources go through the plain reduction; the last pass carries the sum of squares
+    const int last = (n_sources - 1) / kMaxSources * kMaxSources;
+    if (last > 0) {
+        const int rc = elixir_grad_reduce_sources_lp(d_grad_chunk, 0, d_grad_lowp, last, lowp_format, chunk_elems, scale, accumulate, stream);
+        if (rc != ELIXIR_OK) return rc;
+    }
+    const int cnt = n_sources - last;
+    SrcTable t;
+    for (int k = 0; k < kMaxSources; ++k) t.p[k] = k < cnt ? d_grad_lowp[last + k] : nullptr;
+    if (accumulate || last > 0) {
+        if (f16) launch_fused<true, true>(d_grad_chunk, t, cnt, chunk_elems, valid_len, scale, ctx->d_stage, slots, s);
+        else launch_fused<true, false>(d_grad_chunk, t, cnt, chunk_elems, valid_len, scale, ctx->d_stage, slots, s);
     } else {
-        if (f16) launch_fused<false, true>(d_grad_chunk, d_grad_lowp, chunk_elems, valid_len, scale, ctx->d_stage, slots, s);
-        else launch_fused<false, false>(d_grad_chunk, d_grad_lowp, chunk_elems, valid_len, scale, ctx->d_stage, slots, s);
+        if (f16) launch_fused<false, true>(d_grad_chunk, t, cnt, chunk_elems, valid_len, scale, ctx->d_stage, slots, s);
+        else launch_fused<false, false>(d_grad_chunk, t, cnt, chunk_elems, valid_len, scale, ctx->d_stage, slots, s);
     }
     ELIXIR_LAUNCH_CHECK("reduce_sumsq_kernel");
     return ELIXIR_OK;
+}
+
+extern "C" int elixir_grad_reduce_chunk_sumsq(elixir_ctx* ctx, int chunk_index, float* d_grad_chunk, const uint16_t* d_grad_lowp,
+                                              int lowp_format, int64_t chunk_elems, int64_t valid_len, float scale,
+                                              int accumulate, elixir_stream_t stream) {
+    if (chunk_elems > 0 && !d_grad_lowp) return fail(ELIXIR_EINVAL, "elixir_grad_reduce_chunk_sumsq: NULL pointer");
+    return elixir_grad_reduce_sources_chunk_sumsq(ctx, chunk_index, d_grad_chunk, &d_grad_lowp, 1, lowp_format, chunk_elems, valid_len,
+                                                  scale, accumulate, stream);
 }
 
 extern "C" int elixir_chunk_grad_norm_finish(elixir_ctx* ctx, int n_chunks, float max_norm, float* d_norm_out,

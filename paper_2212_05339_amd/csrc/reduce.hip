@@ -21,28 +21,11 @@ constexpr int kVecBlock = kReduceBlock;  // one 4-element group per thread, one 
                                 // which measured best for this 1-2 read / 1 write stream mix
 constexpr int64_t kMaxBlocksPerLaunch = 1ll << 30;
 
-// Group i (4 elements) of one tensor: dst 16-byte aligned, src 8-byte aligned.
-template <bool ACC, bool FP16>
-__device__ __forceinline__ void reduce_group(float* __restrict__ dst, const uint16_t* __restrict__ src, int64_t i, float scale) {
-    f32x4* D = reinterpret_cast<f32x4*>(dst) + i;
-    const u32x2 g = __builtin_nontemporal_load(reinterpret_cast<const u32x2*>(src) + i);
-    f32x4 a;
-    if constexpr (ACC) a = __builtin_nontemporal_load(D);
-    else a = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
-    f32x4 r;
-    r.x = reduce_elem<FP16>(a.x, g.x & 0xFFFFu, scale);
-    r.y = reduce_elem<FP16>(a.y, g.x >> 16, scale);
-    r.z = reduce_elem<FP16>(a.z, g.y & 0xFFFFu, scale);
-    r.w = reduce_elem<FP16>(a.w, g.y >> 16, scale);
-    __builtin_nontemporal_store(r, D);
-}
-
-// n4 complete groups of 4 elements, one per thread.
-template <bool ACC, bool FP16>
-__global__ __launch_bounds__(kVecBlock) void reduce_vec_kernel(float* __restrict__ dst, const uint16_t* __restrict__ src,
-                                                              int64_t n4, float scale) {
+// n4 complete groups of 4 elements, one per thread; NSRC gradient arrays in one pass.
+template <bool ACC, bool FP16, int NSRC>
+__global__ __launch_bounds__(kVecBlock) void reduce_vec_kernel(float* __restrict__ dst, SrcTable srcs, int64_t n4, float scale) {
     const int64_t i = (int64_t)blockIdx.x * kVecBlock + threadIdx.x;
-    if (i < n4) reduce_group<ACC, FP16>(dst, src, i, scale);
+    if (i < n4) (void)reduce_group<ACC, FP16, NSRC>(dst, srcs, i, scale);
 }
 
 // elements [first, n), any alignment
@@ -75,30 +58,79 @@ __global__ __launch_bounds__(kVecBlock) void reduce_multi_kernel(ReduceMultiTabl
     const int64_t n4 = tab.n4[seg];
     if ((int64_t)blockIdx.x * kVecBlock >= n4) return;  // a row past the end of a shorter tensor (uniform per workgroup)
     const int64_t i = (int64_t)blockIdx.x * kVecBlock + threadIdx.x;
-    if (i < n4) reduce_group<ACC, FP16>(tab.dst[seg], tab.src[seg], i, scale);
+    if (i < n4) (void)reduce_group<ACC, FP16, 1>(tab.dst[seg], SrcTable{{tab.src[seg]}}, i, scale);
+}
+
+// The vector part of a pass over NSRC sources: n4 groups of 4 elements starting at dst / srcs.
+template <bool ACC, bool FP16, int NSRC>
+void launch_vec(float* dst, const SrcTable& srcs, int64_t n4, float scale, hipStream_t s) {
+    int64_t at = 0;
+    while (at < n4) {
+        int64_t blocks = (n4 - at + kVecBlock - 1) / kVecBlock;
+        if (blocks > kMaxBlocksPerLaunch) blocks = kMaxBlocksPerLaunch;
+        const int64_t cnt = n4 - at < blocks * kVecBlock ? n4 - at : blocks * kVecBlock;
+        SrcTable t;
+        for (int k = 0; k < kMaxSources; ++k) t.p[k] = k < NSRC ? srcs.p[k] + at * 4 : nullptr;
+        hipLaunchKernelGGL((reduce_vec_kernel<ACC, FP16, NSRC>), dim3((unsigned)blocks), dim3(kVecBlock), 0, s, dst + at * 4, t, cnt, scale);
+        at += cnt;
+    }
+}
+
+template <bool ACC, bool FP16>
+void launch_scalar(float* dst, const uint16_t* src, int64_t first, int64_t n, float scale, hipStream_t s) {
+    while (first < n) {
+        int64_t blocks = (n - first + 255) / 256;
+        if (blocks > kMaxBlocksPerLaunch) blocks = kMaxBlocksPerLaunch;
+        const int64_t stop = first + blocks * 256 < n ? first + blocks * 256 : n;
+        hipLaunchKernelGGL((reduce_scalar_kernel<ACC, FP16>), dim3((unsigned)blocks), dim3(256), 0, s, dst, src, first, stop, scale);
+        first = stop;
+    }
 }
 
 template <bool ACC, bool FP16>
 void launch_reduce(float* dst, const uint16_t* src, int64_t n, float scale, hipStream_t s) {
     int64_t done = 0;
     if (aligned(dst, 16) && aligned(src, 8) && n >= 4) {
-        const int64_t n4 = n / 4;
-        int64_t at = 0;
-        while (at < n4) {
-            int64_t blocks = (n4 - at + kVecBlock - 1) / kVecBlock;
-            if (blocks > kMaxBlocksPerLaunch) blocks = kMaxBlocksPerLaunch;
-            const int64_t cnt = n4 - at < blocks * kVecBlock ? n4 - at : blocks * kVecBlock;
-            hipLaunchKernelGGL((reduce_vec_kernel<ACC, FP16>), dim3((unsigned)blocks), dim3(kVecBlock), 0, s, dst + at * 4, src + at * 4, cnt, scale);
-            at += cnt;
-        }
-        done = n4 * 4;
+        launch_vec<ACC, FP16, 1>(dst, SrcTable{{src}}, n / 4, scale, s);
+        done = n / 4 * 4;
     }
-    while (done < n) {
-        int64_t blocks = (n - done + 255) / 256;
-        if (blocks > kMaxBlocksPerLaunch) blocks = kMaxBlocksPerLaunch;
-        const int64_t stop = done + blocks * 256 < n ? done + blocks * 256 : n;
-        hipLaunchKernelGGL((reduce_scalar_kernel<ACC, FP16>), dim3((unsigned)blocks), dim3(256), 0, s, dst, src, done, stop, scale);
-        done = stop;
+    launch_scalar<ACC, FP16>(dst, src, done, n, scale, s);
+}
+
+// n_src >= 1 sources into dst, in order, at most kMaxSources per pass; the first pass overwrites unless `acc`.
+template <bool FP16>
+void launch_sources(float* dst, const uint16_t* const* src, int n_src, int64_t n, float scale, bool acc, hipStream_t s) {
+    bool vec = aligned(dst, 16) && n >= 4;
+    for (int k = 0; k < n_src; ++k) vec = vec && aligned(src[k], 8);
+    if (!vec) {  // a slice at an odd offset: one source per pass through the single-source path
+        for (int k = 0; k < n_src; ++k) {
+            if (acc || k > 0) launch_reduce<true, FP16>(dst, src[k], n, scale, s);
+            else launch_reduce<false, FP16>(dst, src[k], n, scale, s);
+        }
+        return;
+    }
+    const int64_t n4 = n / 4;
+    for (int k0 = 0; k0 < n_src; k0 += kMaxSources) {
+        const int cnt = n_src - k0 < kMaxSources ? n_src - k0 : kMaxSources;
+        SrcTable t;
+        for (int k = 0; k < kMaxSources; ++k) t.p[k] = k < cnt ? src[k0 + k] : nullptr;
+        const bool a = acc || k0 > 0;
+#define ELIXIR_SRC_CASE(N)                                            \
+    case N:                                                           \
+        if (a) launch_vec<true, FP16, N>(dst, t, n4, scale, s);       \
+        else launch_vec<false, FP16, N>(dst, t, n4, scale, s);        \
+        break;
+        switch (cnt) {
+            ELIXIR_SRC_CASE(1)
+            ELIXIR_SRC_CASE(2)
+            ELIXIR_SRC_CASE(3)
+            ELIXIR_SRC_CASE(4)
+        }
+#undef ELIXIR_SRC_CASE
+    }
+    for (int k = 0; k < n_src && n4 * 4 < n; ++k) {  // the at most 3 elements after the last complete group, source by source
+        if (acc || k > 0) launch_scalar<true, FP16>(dst, src[k], n4 * 4, n, scale, s);
+        else launch_scalar<false, FP16>(dst, src[k], n4 * 4, n, scale, s);
     }
 }
 
@@ -132,6 +164,27 @@ extern "C" int elixir_grad_reduce_into_chunk_lp(float* d_grad_chunk, int64_t off
 extern "C" int elixir_grad_reduce_into_chunk(float* d_grad_chunk, int64_t offset, const uint16_t* d_grad_bf16, int64_t n,
                                              float scale, int accumulate, elixir_stream_t stream) {
     return elixir_grad_reduce_into_chunk_lp(d_grad_chunk, offset, d_grad_bf16, ELIXIR_LOWP_BF16, n, scale, accumulate, stream);
+}
+
+extern "C" int elixir_grad_reduce_sources_lp(float* d_grad_chunk, int64_t offset, const uint16_t* const* d_grad_lowp, int n_sources,
+                                             int lowp_format, int64_t n, float scale, int accumulate, elixir_stream_t stream) {
+    static const char* what = "elixir_grad_reduce_sources";
+    if (n < 0 || offset < 0 || n_sources < 0)
+        return fail(ELIXIR_EINVAL, "%s: n=%lld, offset=%lld, n_sources=%d must not be negative", what, (long long)n, (long long)offset, n_sources);
+    if (lowp_format != ELIXIR_LOWP_BF16 && lowp_format != ELIXIR_LOWP_FP16)
+        return fail(ELIXIR_EINVAL, "%s: lowp_format=%d is neither ELIXIR_LOWP_BF16 nor ELIXIR_LOWP_FP16", what, lowp_format);
+    if (n == 0 || n_sources == 0) return ELIXIR_OK;
+    if (!d_grad_chunk || !d_grad_lowp) return fail(ELIXIR_EINVAL, "%s: NULL pointer", what);
+    if (!aligned(d_grad_chunk, 4)) return fail(ELIXIR_EALIGN, "%s: d_grad_chunk is not 4-byte aligned", what);
+    for (int k = 0; k < n_sources; ++k) {
+        if (!d_grad_lowp[k]) return fail(ELIXIR_EINVAL, "%s: source %d is NULL", what, k);
+        if (!aligned(d_grad_lowp[k], 2)) return fail(ELIXIR_EALIGN, "%s: source %d is not 2-byte aligned", what, k);
+    }
+    hipStream_t s = (hipStream_t)stream;
+    if (lowp_format == ELIXIR_LOWP_FP16) launch_sources<true>(d_grad_chunk + offset, d_grad_lowp, n_sources, n, scale, accumulate != 0, s);
+    else launch_sources<false>(d_grad_chunk + offset, d_grad_lowp, n_sources, n, scale, accumulate != 0, s);
+    ELIXIR_LAUNCH_CHECK("reduce kernel");
+    return ELIXIR_OK;
 }
 
 namespace {

@@ -217,6 +217,81 @@ def test_grad_reduce_multi_errors_and_empty():
     assert not host(d).any()
 
 
+@pytest.mark.parametrize("fmt", [ex.ELIXIR_LOWP_BF16, ex.ELIXIR_LOWP_FP16])
+def test_grad_reduce_of_several_sources_is_bit_identical_to_consecutive_passes(fmt):
+    """1 to 9 gradient arrays in one call (four per pass inside): the same bits as one call per array in the same order,
+    on the GPU and in the oracle; aligned whole slices (vector kernel), odd offsets and odd source starts (one-element
+    kernel), lengths around the group of four, overwrite and accumulate."""
+    rng = np.random.default_rng(77 + fmt)
+    for case in range(36):
+        n_src = 1 + case % 9
+        n = int(rng.choice([1, 3, 4, 5, 511, 512, 513, 4096 * 3 + 2, int(rng.integers(6, 300_000))]))
+        offset = int(rng.choice([0, 4, 8, 1, 3])) if case % 3 else 0
+        shifts = [0] * n_src if case % 4 else [int(x) for x in rng.integers(0, 4, size=n_src)]
+        accumulate = bool(case % 2)
+        scale = float(rng.choice([1.0, 0.25, 0.3, 1.0 / n_src]))
+        what = f"case {case}: n_src={n_src} n={n} offset={offset} shifts={shifts} acc={accumulate} scale={scale}"
+        base = gen.fill_f32(gen.stream_key(500 + case, gen.TAG_GRAD, 9), 0, n + 16, 1e-3)
+        srcs = [_lowp_bits(fmt, gen.stream_key(500 + case, gen.TAG_GRAD, j), n + 8, 1e-3)[0] for j in range(n_src)]
+        d_srcs = [dev(b)[sh:sh + n] for b, sh in zip(srcs, shifts)]
+        d_one, d_seq = dev(base), dev(base)
+        ex.elixir_grad_reduce_sources_lp(d_one, offset, d_srcs, fmt, n, scale, accumulate)
+        want = base.copy()
+        for j in range(n_src):
+            ex.elixir_grad_reduce_into_chunk_lp(d_seq, offset, d_srcs[j], fmt, n, scale, accumulate or j > 0)
+            orc.grad_reduce_into_chunk(want, offset, np.ascontiguousarray(srcs[j][shifts[j]:shifts[j] + n]), scale, accumulate or j > 0, fmt=fmt)
+        sync()
+        assert np.array_equal(host(d_one).view(np.uint32), host(d_seq).view(np.uint32)), what
+        assert np.array_equal(host(d_one).view(np.uint32), want.view(np.uint32)), what
+    d = dev(np.zeros(16, np.float32))
+    g = dev(np.zeros(16, np.uint16))
+    ex.elixir_grad_reduce_sources_lp(d, 0, [], fmt, 16, 1.0, False)            # no source: nothing happens
+    ex.elixir_grad_reduce_sources_lp(d, 0, [g, g], fmt, 0, 1.0, False)
+    for args, code in (((d, -1, [g], fmt, 4, 1.0, False), ex.ELIXIR_EINVAL), ((d, 0, [g], 9, 4, 1.0, False), ex.ELIXIR_EINVAL),
+                       ((d, 0, [g, None], fmt, 4, 1.0, False), ex.ELIXIR_EINVAL), ((d, 0, [g, g.data_ptr() + 1], fmt, 4, 1.0, False), ex.ELIXIR_EALIGN)):
+        with pytest.raises(ex.ElixirError) as e:
+            ex.elixir_grad_reduce_sources_lp(*args)
+        assert e.value.code == code
+
+
+@pytest.mark.parametrize("n_src", [2, 4, 7])
+def test_fused_reduce_sumsq_of_several_sources(ctx, n_src):
+    """The last pass with several gradient arrays and the sum of squares: chunk bits as after one pass per array, and the
+    norm bit-identical to the single-array fused pass run last (same final values, same tree), close to the oracle's."""
+    lens = [(200_003, 150_001), (4096, 4096), (1_000_000, 0), (7, 5)]
+    d_norm = torch.zeros(4, dtype=torch.float32, device=DEV)
+    ref_chunks, valid = [], []
+    for variant in ("sources", "single"):
+        for c, (n, v) in enumerate(lens):
+            srcs = [gen.fill_bf16(gen.stream_key(640 + c, gen.TAG_GRAD, j), 0, n, 2e-3, zero_pct=1) for j in range(n_src)]
+            d_srcs = [dev(b) for b in srcs]
+            d_chunk = torch.full((n,), 3.0, dtype=torch.float32, device=DEV)
+            if variant == "sources":
+                ex.elixir_grad_reduce_sources_chunk_sumsq(ctx, c, d_chunk, d_srcs, ex.ELIXIR_LOWP_BF16, n, v, 0.5, False)
+                want = np.zeros(n, np.float32)
+                for j in range(n_src):
+                    orc.grad_reduce_into_chunk(want, 0, srcs[j], 0.5, j > 0)
+                sync()
+                assert np.array_equal(host(d_chunk).view(np.uint32), want.view(np.uint32)), (c, n)
+                ref_chunks.append(want)
+                valid.append(v)
+            else:
+                for j in range(n_src - 1):
+                    ex.elixir_grad_reduce_into_chunk(d_chunk, 0, d_srcs[j], n, 0.5, j > 0)
+                ex.elixir_grad_reduce_chunk_sumsq(ctx, c, d_chunk, d_srcs[-1], ex.ELIXIR_LOWP_BF16, n, v, 0.5, True)
+                sync()
+        k = 0 if variant == "sources" else 2
+        ex.elixir_chunk_grad_norm_finish(ctx, len(lens), 0.05, d_norm[k:k + 1], d_norm[k + 1:k + 2])
+        sync()
+    got = host(d_norm)
+    assert np.array_equal(got[0:2].view(np.uint32), got[2:4].view(np.uint32))
+    want = orc.grad_norm(ref_chunks, valid)
+    assert got[0] == pytest.approx(want, rel=1e-6) and got[1] == pytest.approx(orc.clip_coef(want, 0.05), rel=1e-6)
+    with pytest.raises(ex.ElixirError) as e:
+        ex.elixir_grad_reduce_sources_chunk_sumsq(ctx, 0, d_chunk, [], ex.ELIXIR_LOWP_BF16, 7, 5, 0.5, False)
+    assert e.value.code == ex.ELIXIR_EINVAL
+
+
 # --------------------------------------------------------------------------- norm + clip
 
 def _norm_case(ctx, chunks, valid, max_norm):
