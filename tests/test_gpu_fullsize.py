@@ -240,6 +240,22 @@ def test_gpt2_6b_accumulate_norm_clip_step_full_size():
             check_adam_close(got[0], got[1], got[2], rp, rm, rv, lr=HP["lr"], gmax=3e-3 * coef, what=f"6B chunk {c}")
             check_bf16_copy(u16(out), got[0], rout, rp, lr=HP["lr"], what=f"6B chunk {c}")
             assert np.array_equal(gch[c].cpu().numpy().view(np.uint32), ref_g[c].view(np.uint32)), "gradients were rewritten"
+        # all four micro-batches in ONE pass (bench.py --sources-per-pass 4), on the sampled chunks: the chunk bits of the
+        # one-at-a-time order, and, the pass having refilled the chunk's slots with the same sums, the same fused norm
+        del state, out
+        four = torch.empty(K, C, dtype=torch.int16, device=DEV)
+        once = torch.empty(C, dtype=torch.float32, device=DEV)
+        for c in sampled:
+            four.zero_()
+            for mb in range(K):
+                gen.fill_bf16_device(four[mb].data_ptr(), valid[c], gen.stream_key(gen.BASE_SEED, gen.TAG_GRAD, 1, mb, cfg.cfg_id), c * C, cfg.grad_std, 0)
+            once.fill_(7.0)
+            ex.elixir_grad_reduce_sources_chunk_sumsq(ctx, c, once, [four[mb] for mb in range(K)], ex.ELIXIR_LOWP_BF16, C, valid[c], scale, False)
+            torch.cuda.synchronize()
+            assert torch.equal(once.view(torch.int32), gch[c].view(torch.int32)), f"one pass over four micro-batches differs on chunk {c}"
+        ex.elixir_chunk_grad_norm_finish(ctx, nch, cfg.max_norm, d_fused[0:1], d_fused[1:2])
+        torch.cuda.synchronize()
+        assert np.array_equal(d_fused.cpu().numpy().view(np.uint32), fused_nc.view(np.uint32))
     finally:
         ex.elixir_ctx_destroy(ctx)
 
