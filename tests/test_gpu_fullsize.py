@@ -162,6 +162,69 @@ def test_gpt2_1p5b_clip_on_bf16_gradient_chunks_full_size():
         ex.elixir_ctx_destroy(ctx)
 
 
+def test_gpt2_1p5b_sweep_shape_first_fit_8mi_chunks_in_batched_launches():
+    """The launch shape of the chunk-size sweep at its smallest size: the 1.5B set placed first-fit into 8Mi-element chunks
+    (251 of them, ragged), every chunk a tiled optimizer chunk, ONE batched call per step over the valid prefixes (four
+    launches of up to 64 chunks inside, chunks regrouped by length).  Two steps; sampled chunks against the oracle, and
+    every chunk's padding still all-zero bits."""
+    cfg = gen.CONFIGS["gpt2_1p5b"]
+    C = 8 * gen.Mi
+    _, _, valid = ex.elixir_layout_plan(cfg.numels(), C, ex.ELIXIR_LAYOUT_FIRST_FIT, 1)
+    assert tuple(valid) == tuple(orc.layout_plan(cfg.numels(), C, orc.FIRST_FIT, 1)[2])
+    nch = len(valid)
+    assert nch == 251 and sum(valid) == 1_557_611_200
+    rng = np.random.default_rng(8)
+    shortest = int(np.argmin(valid))
+    sampled = sorted({0, nch - 1, shortest, *[int(x) for x in rng.integers(1, nch - 1, size=3)]})
+    L = ex.elixir_state_tiled_len(C)
+    tiled = torch.zeros(nch, L, dtype=torch.float32, device=DEV)                 # 25 GB
+    g = torch.zeros(nch, C, dtype=torch.int16, device=DEV)
+    out = torch.zeros(nch, C, dtype=torch.int16, device=DEV)
+    pkey = gen.stream_key(gen.BASE_SEED, gen.TAG_PARAM, cfg=cfg.cfg_id)
+    flat = torch.zeros(3, C, dtype=torch.float32, device=DEV)
+    ref = {}
+    for c in range(nch):
+        flat[0].zero_()
+        gen.fill_f32_device(flat[0].data_ptr(), valid[c], pkey, c * C, cfg.param_std)
+        ex.elixir_state_tile(tiled[c], flat[0], flat[1], flat[2], C)
+        if c in sampled:
+            torch.cuda.synchronize()
+            p = flat[0].cpu().numpy().copy()
+            k = min(1024, valid[c])
+            assert np.array_equal(p[:k], gen.fill_f32(pkey, c * C, k, cfg.param_std)), "device generator differs from host"
+            ref[c] = [p, np.zeros(C, np.float32), np.zeros(C, np.float32), np.zeros(C, np.uint16)]
+    for step in (1, 2):
+        gkey = gen.stream_key(gen.BASE_SEED, gen.TAG_GRAD, step, 0, cfg.cfg_id)
+        g.zero_()
+        for c in range(nch):
+            gen.fill_bf16_device(g[c].data_ptr(), valid[c], gkey, c * C, cfg.grad_std, cfg.grad_zero_pct)
+        ex.elixir_chunk_adam_step_tiled_multi_lp([tiled[c] for c in range(nch)], None, [g[c] for c in range(nch)], [out[c] for c in range(nch)],
+                                                 ex.ELIXIR_LOWP_BF16, valid, hp_struct(step))
+        torch.cuda.synchronize()
+        for c in sampled:
+            hg = u16(g[c])
+            a = int(rng.integers(0, max(1, valid[c] - 4096)))
+            k = min(4096, valid[c] - a)
+            assert np.array_equal(hg[a:a + k], gen.fill_bf16(gkey, c * C + a, k, cfg.grad_std, cfg.grad_zero_pct)), "device generator differs from host"
+            oracle_adam_parallel(ref[c][0], ref[c][1], ref[c][2], hg, ref[c][3], step=step)
+    for c in sampled:
+        ex.elixir_state_untile(tiled[c], flat[0], flat[1], flat[2], C)
+        torch.cuda.synchronize()
+        got = flat.cpu().numpy()
+        check_adam_close(got[0], got[1], got[2], ref[c][0], ref[c][1], ref[c][2], lr=HP["lr"], gmax=3.5e-3, steps=2, what=f"8Mi chunk {c}")
+        check_bf16_copy(u16(out[c])[:valid[c]], got[0][:valid[c]], ref[c][3][:valid[c]], ref[c][0][:valid[c]], lr=HP["lr"], steps=2, what=f"8Mi chunk {c}")
+    # padding: behind every chunk's valid prefix the state tiles and the parameter copy are still all-zero bits
+    T = ex.ELIXIR_STATE_TILE
+    e = torch.arange(C, device=DEV)
+    for c in range(nch):
+        if valid[c] == C:
+            continue
+        pad = e[valid[c]:]
+        idx = 3 * T * (pad // T) + pad % T
+        assert not bool(tiled[c].view(torch.int32)[idx].any()) and not bool(tiled[c].view(torch.int32)[idx + T].any()) \
+            and not bool(tiled[c].view(torch.int32)[idx + 2 * T].any()) and not bool(out[c][valid[c]:].any()), f"padding of chunk {c} moved"
+
+
 def test_gpt2_6b_accumulate_norm_clip_step_full_size():
     """Four micro-batches reduced into fp32 chunks (mean), global norm over all 50 chunks of 128Mi elements,
     clip to max-norm 1, AdamW with the clip coefficient taken from device memory."""
