@@ -958,12 +958,20 @@ def test_config_tiny_gpt2_ten_steps_end_to_end():
     ref_m, ref_v = np.zeros_like(ref_master), np.zeros_like(ref_master)
     ref_out = np.zeros((nch, C), np.uint16)
     worst = {"p": 0.0, "m": 0.0, "v": 0.0}
+    # the same ten steps as `bench.py --workload tiny` launches them: tiled optimizer chunks, one batched call per step
+    # over the valid prefixes; compared bit for bit with the per-chunk flat path at the end
+    tiled = torch.zeros(nch, ex.elixir_state_tiled_len(C), dtype=torch.float32, device=DEV)
+    out_tiled = torch.zeros(nch, C, dtype=torch.int16, device=DEV)
+    for c in range(nch):
+        ex.elixir_state_tile(tiled[c], master[c], m[c], v[c], C)
     for step in range(1, cfg.steps + 1):
         gkey = gen.stream_key(gen.BASE_SEED, gen.TAG_GRAD, step, 0, 1)
         hp = hp_struct(step)
         for c in range(nch):
             gen.fill_bf16_device(grads[c].data_ptr(), valid[c], gkey, c * C, cfg.grad_std)
             ex.elixir_chunk_adam_step(master[c], m[c], v[c], None, grads[c], out[c], C, hp)
+        ex.elixir_chunk_adam_step_tiled_multi_lp([tiled[c] for c in range(nch)], None, [grads[c] for c in range(nch)],
+                                                 [out_tiled[c] for c in range(nch)], ex.ELIXIR_LOWP_BF16, valid, hp)
         for c in range(nch):
             g = np.zeros(C, np.uint16)
             g[:valid[c]] = gen.fill_bf16(gkey, c * C, valid[c], cfg.grad_std)
@@ -978,6 +986,13 @@ def test_config_tiny_gpt2_ten_steps_end_to_end():
         # padding never moves
         assert not host(master[c])[valid[c]:].view(np.uint32).any()
     print("tiny config, 10 steps: max relative error", worst)
+    back = torch.zeros(3, C, dtype=torch.float32, device=DEV)
+    for c in range(nch):
+        ex.elixir_state_untile(tiled[c], back[0], back[1], back[2], C)
+        sync()
+        for k, flat in enumerate((master, m, v)):
+            assert torch.equal(back[k].view(torch.int32), flat[c].view(torch.int32)), f"tiled batched path differs on chunk {c}"
+    assert torch.equal(out_tiled, out)
     # unpack the low-precision parameters back into tensor shapes and compare with the oracle's unpack
     d_params = [torch.zeros(n, dtype=torch.int16, device=DEV) for n in numels]
     ref_params = [np.zeros(n, np.uint16) for n in numels]
