@@ -344,6 +344,7 @@ def run_sweep(args, torch, ex, gen):
     dev = torch.device("cuda:0")
     stream = torch.cuda.Stream()
     sh = stream.cuda_stream
+    measured = {}
     for C in gen.SWEEP_CHUNK_ELEMS:
         plans = {name: ex.elixir_layout_plan(cfg.numels(), C, pol, 1)[2] for name, pol in
                  (("next_fit", ex.ELIXIR_LAYOUT_NEXT_FIT), ("first_fit", ex.ELIXIR_LAYOUT_FIRST_FIT), ("dense", ex.ELIXIR_LAYOUT_DENSE))}
@@ -403,6 +404,7 @@ def run_sweep(args, torch, ex, gen):
                 del tiled, keep_t
             torch.cuda.empty_cache()
         ff = timed["first_fit"]
+        measured[C] = timed["next_fit"]["params_per_s"]
         print(json.dumps({
             "metric": "chunked AdamW params/sec", "value": ff["params_per_s"], "unit": "params/s", "n_gpus": 1,
             "steps": args.steps, "warmup": args.warmup, "ms_per_step": ff["ms_per_step"], "dtype": "f32", "data": "synthetic",
@@ -413,6 +415,16 @@ def run_sweep(args, torch, ex, gen):
             "elements_per_s": ff["elements_per_s"], "by_layout": timed,
             "roofline": {"bound": "hbm", "achieved": ff["GB/s"], "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                          "frac": ff["GB/s"] / HBM_PEAK_GBPS, "traffic": None, "ms_per_chunk": ff["ms_per_chunk"]}}), flush=True)
+    # from report to choice: the paper picks the chunk length whose simulated rCache replaces the fewest bytes per step
+    # (App. A.2; the paper's grouping, forward + backward sweep, Belady's replacement); the update throughput measured above
+    # is printed beside it
+    cache_bytes = float(2 << 30)
+    sizes = list(gen.SWEEP_CHUNK_ELEMS)
+    best, replaced, padding = ex.elixir_chunk_size_search(cfg.numels(), sizes, cache_bytes, ex.ELIXIR_LAYOUT_NEXT_FIT, 1, 2)
+    print(json.dumps({"metric": "chunk-size search (bytes replaced in the rCache per step)", "config": {"workload": "gpt2-1.5B sweep", "layout": "next-fit",
+                      "rcache_bytes": cache_bytes, "candidates_elems": sizes},
+                      "replaced_bytes_per_step": replaced, "padding_elems": padding, "chosen_chunk_elems": sizes[best],
+                      "measured_update_params_per_s_next_fit": {str(c): measured[c] for c in sizes}}), flush=True)
 
 
 def run_clip(args, torch, ex, gen):
