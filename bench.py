@@ -825,13 +825,31 @@ def run_hybrid(args, torch, ex, gen):
             dt = time.perf_counter() - t0
             vc[str(T)] = {"G_elements_per_s": C / dt / 1e9, "host_GB/s": 28 * C / dt / 1e9}
         best = min(results, key=lambda r: r["ms_per_step"])
+        # the paper's benefit model (Sec. 5.1, Eq. 1 and 2) on what this run measured: the link rate of the all-streamed row,
+        # the GPU update rate of the resident chunks, the CPU update rate on all cores
+        hp = ex.make_hparams(cfg.lr, cfg.beta1, cfg.beta2, cfg.eps, cfg.weight_decay, 2)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(compute)
+        for st_, r_ in zip(resident, range(n_res)):
+            ex.elixir_chunk_adam_step(st_[0], st_[1], st_[2], None, grads[n_host + r_], out[n_host + r_], C, hp, None, sh)
+        e1.record(compute)
+        torch.cuda.synchronize()
+        v_g = n_res * C / (e0.elapsed_time(e1) * 1e-3)
+        streamed = [r for r in results if r["cpu_chunks"] == 0][0]
+        link = 12.0 * n_host * C / (streamed["ms_per_step"] * 1e-3)                 # bytes/s in each direction, fill and drain included
+        v_c = vc[str(cores)]["G_elements_per_s"] * 1e9
+        I, J = ex.elixir_offload_benefit(1, C, link, link, v_g, v_c)
+        benefit = {"B_g2c_and_B_c2g_GB/s": link / 1e9, "V_g_G_elements_per_s": v_g / 1e9, "V_c_G_elements_per_s": v_c / 1e9,
+                   "I": I, "J": J, "unit_of_I_and_J": "seconds saved per step for each byte per element of GPU memory spent (chunks of C elements)",
+                   "reading": "I > J: a further rCache block saves more time per byte of GPU memory than moving a chunk's update to the GPU"
+                              if I > J else "J > I: moving a chunk's update to the GPU saves more time per byte of GPU memory than a further rCache block"}
         print(json.dumps({
             "metric": "host-resident chunk update rate, CPU update and GPU streaming combined", "value": best["host_resident_G_elements_per_s"] * 1e9,
             "unit": "params/s", "n_gpus": 1, "steps": args.steps, "warmup": 1, "ms_per_step": best["ms_per_step"], "dtype": "f32",
             "data": "synthetic",
             "config": {"workload": "gpt2-20B/C=128Mi hybrid offload", "chunk_elems": C, "host_chunks": n_host, "resident_chunks": n_res,
                        "host_threads": threads, "host_isa": ex.elixir_host_adam_isa(), "copy_engines_separate": overlapped},
-            "sweep": results, "cpu_update_alone": vc,
+            "sweep": results, "cpu_update_alone": vc, "benefit_model": benefit,
             "roofline": {"bound": "host memory / host link", "achieved": None, "peak": None, "frac": None, "traffic": None}}), flush=True)
     finally:
         torch.cuda.synchronize()
