@@ -98,6 +98,14 @@ def test_argument_errors_return_before_any_launch():
         (lambda: ex.elixir_chunk_wait_ready(ex.Ctx(None), 0, 0), ex.ELIXIR_EINVAL),
         (lambda: ex.elixir_chunk_evict(ex.Ctx(None), 0, a, 64, 0, 0), ex.ELIXIR_EINVAL),
         (lambda: ex.elixir_host_alloc(0), ex.ELIXIR_EINVAL),
+        (lambda: ex.elixir_chunk_grad_norm_lp(ex.Ctx(None), [a], 0, [4], 1.0, 1.0, a, a, 0), ex.ELIXIR_EINVAL),   # NULL ctx
+        (lambda: ex.elixir_grad_reduce_sources_lp(a, 0, [a, a], 5, 8, 1.0, False, 0), ex.ELIXIR_EINVAL),          # unknown format
+        (lambda: ex.elixir_grad_reduce_sources_lp(a, 0, [a, None], 0, 8, 1.0, False, 0), ex.ELIXIR_EINVAL),       # NULL source
+        (lambda: ex.elixir_grad_reduce_sources_lp(a, 0, [a, a + 1], 0, 8, 1.0, False, 0), ex.ELIXIR_EALIGN),
+        (lambda: ex.elixir_grad_reduce_sources_lp(a + 2, 0, [a], 0, 8, 1.0, False, 0), ex.ELIXIR_EALIGN),
+        (lambda: ex.elixir_grad_reduce_sources_chunk_sumsq(ex.Ctx(None), 0, a, [a], 0, 8, 8, 1.0, False, 0), ex.ELIXIR_EINVAL),
+        (lambda: ex.elixir_chunk_adam_step_tiled_lp(a + 4, None, a, a, 0, 8, hp, None, None, 0), ex.ELIXIR_EALIGN),   # tiled chunk at 4 mod 8
+        (lambda: ex.elixir_chunk_adam_step_tiled_lp(a, None, a, a, 3, 8, hp, None, None, 0), ex.ELIXIR_EINVAL),       # unknown format
     ]
     for i, (call, code) in enumerate(cases):
         with pytest.raises(ex.ElixirError) as e:
@@ -109,6 +117,9 @@ def test_argument_errors_return_before_any_launch():
     ex.elixir_grad_reduce_into_chunk(a, 0, a, 0, 1.0, False, 0)
     ex.elixir_chunk_pack(None, 0, 4, [], [], [], 0)
     ex.elixir_host_free(0)
+    ex.elixir_grad_reduce_sources_lp(a, 0, [], 0, 8, 1.0, False, 0)
+    ex.elixir_grad_reduce_sources_lp(a, 0, [a, a], 0, 0, 1.0, False, 0)
+    ex.elixir_chunk_adam_step_tiled_lp(a, None, a, a, 0, 0, hp, None, None, 0)
 
 
 def test_product_does_not_import_the_oracle():
