@@ -58,11 +58,6 @@ def build_synth(verbose: bool = False) -> str:
     return out
 
 
-if __name__ == "__main__":
-    print(build_library(verbose=True))
-    print(build_synth(verbose=True))
-
-
 def ensure_built(verbose: bool = False) -> None:
     """Builds what is missing and nothing else: callers that only want to run (tests, the smoke check, the
     benchmark) load the libraries that are there and compile only when there are none."""
@@ -70,3 +65,8 @@ def ensure_built(verbose: bool = False) -> None:
         build_library(verbose)
     if not os.path.exists(os.path.join(os.path.dirname(_PKG), "synth", "libsynth_gen.so")):
         build_synth(verbose)
+
+
+if __name__ == "__main__":
+    print(build_library(verbose=True))
+    print(build_synth(verbose=True))
