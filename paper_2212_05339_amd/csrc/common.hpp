@@ -30,7 +30,6 @@ inline bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_
     } while (0)
 
 constexpr int kNormBlocksPerChunk = 1024;  // fixed, so the reduction tree never depends on the launch
-constexpr int kReduceBlock = 128;          // threads per workgroup of the gradient reduction (4 elements per thread)
 
 struct Slot {
     void* d_ptr = nullptr;
