@@ -284,6 +284,29 @@ __global__ __launch_bounds__(256) void state_tile_kernel(float* tiled, float* a0
     else if (e < n) arr[e] = *T;
 }
 
+// The same with one 128-bit access per lane in single-wavefront workgroups (all four pointers 16-byte aligned): group
+// g holds elements 4g .. 4g+3, which lie in one tile (a tile is a multiple of 4 elements); the group that straddles n
+// goes element by element.
+typedef float tile_f32x4 __attribute__((ext_vector_type(4)));
+
+template <bool TO_TILED>
+__global__ __launch_bounds__(64) void state_tile_vec_kernel(float* tiled, float* a0, float* a1, float* a2, int64_t n, int64_t padded) {
+    const int64_t e = ((int64_t)blockIdx.x * 64 + threadIdx.x) * 4;
+    if (e >= padded) return;
+    float* arr = blockIdx.y == 0 ? a0 : (blockIdx.y == 1 ? a1 : a2);
+    float* T = tiled + 3 * kStateTile * (e / kStateTile) + (int64_t)blockIdx.y * kStateTile + e % kStateTile;
+    if (e + 4 <= n) {
+        if constexpr (TO_TILED) __builtin_nontemporal_store(__builtin_nontemporal_load(reinterpret_cast<const tile_f32x4*>(arr + e)), reinterpret_cast<tile_f32x4*>(T));
+        else __builtin_nontemporal_store(__builtin_nontemporal_load(reinterpret_cast<const tile_f32x4*>(T)), reinterpret_cast<tile_f32x4*>(arr + e));
+        return;
+    }
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        if constexpr (TO_TILED) T[j] = e + j < n ? arr[e + j] : 0.0f;
+        else if (e + j < n) arr[e + j] = T[j];
+    }
+}
+
 template <bool TO_TILED>
 int tile_call(const char* what, float* tiled, float* a0, float* a1, float* a2, int64_t n, hipStream_t s) {
     if (n < 0) return fail(ELIXIR_EINVAL, "%s: n is negative", what);
@@ -292,7 +315,10 @@ int tile_call(const char* what, float* tiled, float* a0, float* a1, float* a2, i
     if (!aligned(tiled, 4) || !aligned(a0, 4) || !aligned(a1, 4) || !aligned(a2, 4)) return fail(ELIXIR_EALIGN, "%s: pointer not 4-byte aligned", what);
     const int64_t padded = (n + kStateTile - 1) / kStateTile * kStateTile;
     if (padded / 256 >= kMaxBlocksPerLaunch) return fail(ELIXIR_ECAP, "%s: %lld elements do not fit one launch", what, (long long)n);
-    hipLaunchKernelGGL((state_tile_kernel<TO_TILED>), dim3((unsigned)(padded / 256), 3), dim3(256), 0, s, tiled, a0, a1, a2, n, padded);
+    if (aligned(tiled, 16) && aligned(a0, 16) && aligned(a1, 16) && aligned(a2, 16))
+        hipLaunchKernelGGL((state_tile_vec_kernel<TO_TILED>), dim3((unsigned)(padded / 256), 3), dim3(64), 0, s, tiled, a0, a1, a2, n, padded);
+    else
+        hipLaunchKernelGGL((state_tile_kernel<TO_TILED>), dim3((unsigned)(padded / 256), 3), dim3(256), 0, s, tiled, a0, a1, a2, n, padded);
     ELIXIR_LAUNCH_CHECK("state_tile_kernel");
     return ELIXIR_OK;
 }

@@ -588,6 +588,18 @@ def test_state_tile_and_untile_are_bit_copies_in_the_documented_layout(n):
     for got, ref in zip(back, (p, m, v)):
         g = host(got)
         assert g[0] == 9.0 and g[-1] == 9.0 and np.array_equal(g[1:-1].view(np.uint32), ref.view(np.uint32))
+    # the other two combinations: aligned destinations (128-bit kernel) with guard elements behind them, and sources at an
+    # odd offset (one-element kernel)
+    back = [torch.full((n + 5,), 9.0, dtype=torch.float32, device=DEV) for _ in range(3)]
+    ex.elixir_state_untile(d_state, back[0], back[1], back[2], n)
+    d_state2 = torch.full((L,), 5.0, dtype=torch.float32, device=DEV)
+    shifted = [dev(np.concatenate([[np.float32(7.0)], a])) for a in (p, m, v)]
+    ex.elixir_state_tile(d_state2, shifted[0][1:], shifted[1][1:], shifted[2][1:], n)
+    sync()
+    for got, ref in zip(back, (p, m, v)):
+        g = host(got)
+        assert np.all(g[n:] == 9.0) and np.array_equal(g[:n].view(np.uint32), ref.view(np.uint32))
+    assert np.array_equal(host(d_state2).view(np.uint32), host(d_state).view(np.uint32))
 
 
 def test_adam_on_a_tiled_chunk_is_bit_identical_to_the_flat_update_and_matches_the_oracle():
