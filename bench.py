@@ -661,7 +661,7 @@ def run_offload(args, torch, ex, gen):
                         break
                     pending.pop(0)
                 if is_host[c]:
-                    cc, s = inflight.pop(0)
+                    _, s = inflight.pop(0)
                     ex.elixir_chunk_wait_ready(ctx, s, compute)
                     if update:
                         ex.elixir_chunk_adam_step(slots[s][0], slots[s][1], slots[s][2], None, grads[c], out[c], C, hp, None, sh)
@@ -782,7 +782,7 @@ def run_hybrid(args, torch, ex, gen):
             worker.start()
             pending, inflight, r = list(gpu_chunks), [], 0
             per = -(-n_res // max(1, len(gpu_chunks)))
-            for k in range(max(len(gpu_chunks), 1)):
+            for _ in range(max(len(gpu_chunks), 1)):
                 while pending and len(inflight) < 3:
                     inflight.append((pending[0], ex.elixir_chunk_prefetch(ctx, blocks[pending.pop(0)], nbytes, h2d)))
                 if inflight:
@@ -924,7 +924,7 @@ def main():
     cfg = gen.CONFIGS[args.workload]
     C = cfg.chunk_elems
     numels = cfg.numels()
-    cid, off, valid = ex.elixir_layout_plan(numels, C, ex.ELIXIR_LAYOUT_NEXT_FIT, 1)
+    valid = ex.elixir_layout_plan(numels, C, ex.ELIXIR_LAYOUT_NEXT_FIT, 1)[2]
     nch = len(valid)
     K, W = args.steps, args.warmup
     if C <= 16 * gen.Mi:
@@ -933,7 +933,7 @@ def main():
     stream = torch.cuda.Stream()
     sh = stream.cuda_stream
     # ---- state, resident in HBM ----
-    state, g_first, out, _keep = chunk_buffers(torch, dev, nch, C)
+    state, _g_unused, out, _keep = chunk_buffers(torch, dev, nch, C)
     pkey = gen.stream_key(gen.BASE_SEED, gen.TAG_PARAM, cfg=cfg.cfg_id)
     for c in range(nch):
         gen.fill_f32_device(state[c][0].data_ptr(), valid[c], pkey, c * C, cfg.param_std)

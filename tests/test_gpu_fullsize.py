@@ -106,7 +106,6 @@ def test_gpt2_1p5b_clip_on_bf16_gradient_chunks_full_size():
     C = cfg.chunk_elems
     _, _, valid = ex.elixir_layout_plan(cfg.numels(), C, ex.ELIXIR_LAYOUT_NEXT_FIT, 1)
     nch = len(valid)
-    rng = np.random.default_rng(6)
     gkey = gen.stream_key(gen.BASE_SEED, gen.TAG_GRAD, 1, 0, cfg.cfg_id)
     g = torch.zeros(nch, C, dtype=torch.int16, device=DEV)
     for c in range(nch):
