@@ -424,6 +424,12 @@ def test_lowp_norm_special_values_empty_and_errors(ctx):
         want = one * 100.0
         got = float(host(d_out)[0])
         assert (np.isinf(got) and want > 3.4028235e38) or got == pytest.approx(want, rel=1e-6)
+    # more chunks than the pointer table of one launch holds (128)
+    lens = [3000 + 17 * i for i in range(200)]
+    pairs = [_lowp_bits(ex.ELIXIR_LOWP_BF16, gen.stream_key(75, gen.TAG_GRAD, 0, i), n, 1e-3) for i, n in enumerate(lens)]
+    ex.elixir_chunk_grad_norm_lp(ctx, [dev(b) for b, _ in pairs], ex.ELIXIR_LOWP_BF16, lens, 1.0, 0.0, d_out[0:1], d_out[1:2])
+    sync()
+    assert host(d_out)[0] == pytest.approx(orc.grad_norm([v for _, v in pairs], lens), rel=1e-6) and host(d_out)[1] == 1.0
     z = dev(np.zeros(16, np.uint16))
     for args, code in (((ctx, [z], 7, [16], 1.0, 1.0), ex.ELIXIR_EINVAL), ((ctx, [z], 0, [16], float("inf"), 1.0), ex.ELIXIR_EINVAL),
                        ((ctx, [z], 0, [-1], 1.0, 1.0), ex.ELIXIR_EINVAL), ((ctx, [z] * 300, 0, [16] * 300, 1.0, 1.0), ex.ELIXIR_ECAP),
