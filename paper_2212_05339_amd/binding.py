@@ -138,6 +138,8 @@ def _addr(x) -> Optional[int]:
         return None
     if isinstance(x, int):
         return x
+    if not x.is_contiguous():       # the library sees a base address and an element count: a strided view would be read as dense
+        raise ValueError("elixir: a non-contiguous tensor was passed where a dense buffer is expected")
     return x.data_ptr()
 
 

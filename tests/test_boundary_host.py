@@ -146,3 +146,11 @@ def test_bench_refuses_more_than_one_gpu_and_the_product_fails_loudly_without_it
             "try:\n    b.lib()\nexcept RuntimeError as e:\n    print('raised:', e)\n")
     r = subprocess.run([sys.executable, "-c", code], capture_output=True, text=True, timeout=120, cwd=ROOT)
     assert r.returncode == 0 and "raised:" in r.stdout and "no fallback" in r.stdout
+
+
+def test_binding_refuses_strided_tensors():
+    torch = pytest.importorskip("torch")
+    t = torch.zeros(8, 8)
+    hp = ex.make_hparams(1e-4, 0.9, 0.999, 1e-8, 0.01, 1)
+    with pytest.raises(ValueError):
+        ex.elixir_chunk_adam_step(t[:, 0], t[:, 1], t[:, 2], t[:, 3], None, None, 8, hp, None, 0)
