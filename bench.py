@@ -85,6 +85,14 @@ def out_of_the_way(torch, dev, nbytes_needed, make):
     return res
 
 
+def emit(line):
+    """Prints one JSON line; the keys every line of this program carries get their common values where a workload did not
+    set them (one GPU, larger is better, nothing of the paper to compare with, synthetic inputs)."""
+    for key, val in (("n_gpus", 1), ("higher_is_better", True), ("scaling", "weak"), ("vs_baseline", None), ("data", "synthetic")):
+        line.setdefault(key, val)
+    print(json.dumps(line), flush=True)
+
+
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -405,7 +413,7 @@ def run_sweep(args, torch, ex, gen):
             torch.cuda.empty_cache()
         ff = timed["first_fit"]
         measured[C] = timed["next_fit"]["params_per_s"]
-        print(json.dumps({
+        emit({
             "metric": "chunked AdamW params/sec", "value": ff["params_per_s"], "unit": "params/s", "n_gpus": 1,
             "steps": args.steps, "warmup": args.warmup, "ms_per_step": ff["ms_per_step"], "dtype": "f32", "data": "synthetic",
             "config": {"workload": f"gpt2-1.5B sweep/C={C >> 20}Mi", "chunk_elems": C, "n_chunks": ff["n_chunks"], "layout": "first-fit",
@@ -414,17 +422,17 @@ def run_sweep(args, torch, ex, gen):
             "n_chunks_by_policy": {k: len(v) for k, v in plans.items()},
             "elements_per_s": ff["elements_per_s"], "by_layout": timed,
             "roofline": {"bound": "hbm", "achieved": ff["GB/s"], "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                         "frac": ff["GB/s"] / HBM_PEAK_GBPS, "traffic": None, "ms_per_chunk": ff["ms_per_chunk"]}}), flush=True)
+                         "frac": ff["GB/s"] / HBM_PEAK_GBPS, "traffic": None, "ms_per_chunk": ff["ms_per_chunk"]}})
     # from report to choice: the paper picks the chunk length whose simulated rCache replaces the fewest bytes per step
     # (App. A.2; the paper's grouping, forward + backward sweep, Belady's replacement); the update throughput measured above
     # is printed beside it
     cache_bytes = float(2 << 30)
     sizes = list(gen.SWEEP_CHUNK_ELEMS)
     best, replaced, padding = ex.elixir_chunk_size_search(cfg.numels(), sizes, cache_bytes, ex.ELIXIR_LAYOUT_NEXT_FIT, 1, 2)
-    print(json.dumps({"metric": "chunk-size search (bytes replaced in the rCache per step)", "config": {"workload": "gpt2-1.5B sweep", "layout": "next-fit",
+    emit({"metric": "chunk-size search (bytes replaced in the rCache per step)", "config": {"workload": "gpt2-1.5B sweep", "layout": "next-fit",
                       "rcache_bytes": cache_bytes, "candidates_elems": sizes},
                       "replaced_bytes_per_step": replaced, "padding_elems": padding, "chosen_chunk_elems": sizes[best],
-                      "measured_update_params_per_s_next_fit": {str(c): measured[c] for c in sizes}}), flush=True)
+                      "measured_update_params_per_s_next_fit": {str(c): measured[c] for c in sizes}})
 
 
 def run_clip(args, torch, ex, gen):
@@ -515,7 +523,7 @@ def run_clip(args, torch, ex, gen):
         n_el = sum(lens)
         reduce_bytes = sum(2 * len(w) + 4 + (4 if w[0] > 0 else 0) for w in passes)     # per element: sources read, chunk written (+ read)
         step_bytes = (reduce_bytes + 30) * n_el + (0 if fused else 4 * sum(valid))
-        print(json.dumps({
+        emit({
             "metric": "chunked AdamW params/sec (4 micro-batches reduced, global norm, clip, step)", "value": sum(valid) / wall,
             "unit": "params/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": wall * 1e3,
             "dtype": "f32", "data": "synthetic",
@@ -532,7 +540,7 @@ def run_clip(args, torch, ex, gen):
             "roofline": {"bound": "hbm", "achieved": step_bytes / 1e9 / ev, "peak": HBM_PEAK_GBPS, "unit": "GB/s", "traffic": None,
                          "frac": step_bytes / 1e9 / ev / HBM_PEAK_GBPS,
                          "note": f"whole step: {reduce_bytes} (reduce, {len(passes)} pass{'es' if len(passes) > 1 else ''}) + 30 (AdamW, fp32 gradient) bytes per element"
-                                 + ("" if fused else " + 4 per valid element (norm)")}}), flush=True)
+                                 + ("" if fused else " + 4 per valid element (norm)")}})
     finally:
         ex.elixir_ctx_destroy(ctx)
 
@@ -690,7 +698,7 @@ def run_offload(args, torch, ex, gen):
         t_dma = wall_of(lambda: step(update=False))                             # the same schedule of copies, no kernels
         overlap = min(1.0, 1.0 - (wall - max(t_dma, t_compute)) / min(t_dma, t_compute))   # 1: the shorter of the two is hidden
         frac = (moved / wall / 1e9) / link["bidirectional_GB/s_each_way"] if link else None
-        print(json.dumps({
+        emit({
             "metric": "chunked AdamW params/sec with 60% of the chunks streamed from pinned host memory", "value": sum(valid) / wall,
             "unit": "params/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": wall * 1e3, "dtype": "f32",
             "data": "synthetic",
@@ -704,7 +712,7 @@ def run_offload(args, torch, ex, gen):
             "compute_only_ms": t_compute * 1e3, "copies_only_ms": t_dma * 1e3, "overlap": overlap,
             "roofline": {"bound": "host link", "achieved": moved / wall / 1e9, "unit": "GB/s each way, both directions concurrent",
                          "peak": link["bidirectional_GB/s_each_way"] if link else None, "frac": frac, "traffic": None,
-                         "note": "peak = bare bidirectional pinned copies measured in this run"}}), flush=True)
+                         "note": "peak = bare bidirectional pinned copies measured in this run"}})
     finally:
         torch.cuda.synchronize()
         ex.elixir_offload_register_slots(ctx, [], 0)
@@ -843,14 +851,14 @@ def run_hybrid(args, torch, ex, gen):
                    "I": I, "J": J, "unit_of_I_and_J": "seconds saved per step for each byte per element of GPU memory spent (chunks of C elements)",
                    "reading": "I > J: a further rCache block saves more time per byte of GPU memory than moving a chunk's update to the GPU"
                               if I > J else "J > I: moving a chunk's update to the GPU saves more time per byte of GPU memory than a further rCache block"}
-        print(json.dumps({
+        emit({
             "metric": "host-resident chunk update rate, CPU update and GPU streaming combined", "value": best["host_resident_G_elements_per_s"] * 1e9,
             "unit": "params/s", "n_gpus": 1, "steps": args.steps, "warmup": 1, "ms_per_step": best["ms_per_step"], "dtype": "f32",
             "data": "synthetic",
             "config": {"workload": "gpt2-20B/C=128Mi hybrid offload", "chunk_elems": C, "host_chunks": n_host, "resident_chunks": n_res,
                        "host_threads": threads, "host_isa": ex.elixir_host_adam_isa(), "copy_engines_separate": overlapped},
             "sweep": results, "cpu_update_alone": vc, "benefit_model": benefit,
-            "roofline": {"bound": "host memory / host link", "achieved": None, "peak": None, "frac": None, "traffic": None}}), flush=True)
+            "roofline": {"bound": "host memory / host link", "achieved": None, "peak": None, "frac": None, "traffic": None}})
     finally:
         torch.cuda.synchronize()
         ex.elixir_offload_register_slots(ctx, [], 0)
@@ -890,14 +898,14 @@ def run_placement(args, torch, ex, gen):
         return us(lambda: ex.elixir_grad_reduce_into_chunk(base + int(dst_gib * GiB), 0, base + int(src_gib * GiB), C, 0.25, True, sh))
 
     pos = list(range(8, TOT - 8, 8))
-    print(json.dumps({
-        "metric": "launch time against operand placement", "unit": "us", "n_gpus": 1, "data": "zero-filled",
+    emit({
+        "metric": "launch time against operand placement", "unit": "us", "higher_is_better": False, "n_gpus": 1, "data": "zero-filled",
         "config": {"workload": "placement scan", "allocation_GiB": TOT, "elements_per_launch": C, "positions_GiB": pos},
         "adam_tiled_state_scanned_grad_at_1_out_at_2_GiB": [adam(s, 1, 2) for s in pos],
         "adam_tiled_state_at_100_grad_scanned_out_at_2_GiB": [adam(100, g, 2) if abs(g - 100) >= 4 else None for g in pos],
         "adam_tiled_state_at_100_grad_at_104_out_scanned": [adam(100, 104, o) if abs(o - 102) >= 6 else None for o in pos],
         "accumulate_dst_scanned_src_at_1_GiB": [accumulate(d, 1) for d in pos],
-        "accumulate_dst_at_100_src_scanned": [accumulate(100, s_) if abs(s_ - 100) >= 4 else None for s_ in pos]}), flush=True)
+        "accumulate_dst_at_100_src_scanned": [accumulate(100, s_) if abs(s_ - 100) >= 4 else None for s_ in pos]})
 
 
 def main():
@@ -1066,7 +1074,7 @@ def main():
             line["cpu_baseline"] = cpu_baseline(cfg, valid[0], budget_elems=32 * 64 * gen.Mi)
         except Exception as e:  # noqa: BLE001
             line["cpu_baseline_error"] = f"{type(e).__name__}: {e}"
-    print(json.dumps(line), flush=True)
+    emit(line)
 
 
 if __name__ == "__main__":
