@@ -47,7 +47,7 @@ __global__ __launch_bounds__(256) void reduce_scalar_kernel(float* dst, const ui
 // table for the owner of a tile costs each of these short-lived waves ~200 scalar instructions or a chain of
 // dependent loads; measured, it was no faster than one launch per tensor.)
 constexpr int kReduceMultiMax = 64;
-constexpr int kMultiBlock = 128;  // measured on the 581 tensor pieces of the 1.5B set: 5.94 TB/s, against 5.74 TB/s with 64 threads
+constexpr int kMultiBlock = 128;  // measured on the 581 tensor pieces of the 1.5B set: 6.0-6.1 TB/s, against 5.97-6.03 TB/s with 64 threads
 struct ReduceMultiTable {
     float* dst[kReduceMultiMax];           // 16-byte aligned
     const uint16_t* src[kReduceMultiMax];  // 8-byte aligned
@@ -228,9 +228,11 @@ int reduce_multi(int T, float* const* d_dst, const uint16_t* const* d_src, const
         const int64_t n4 = n[k] / 4;
         const int64_t tiles = (n4 + kMultiBlock - 1) / kMultiBlock;
         // every tensor gets a grid row as long as the first (longest) one: start a new launch when the table is full
-        // or when more than ~a quarter of the workgroups would find no work
+        // or when the workgroups that would find no work exceed 1/64 of the working ones plus 16K (an idle workgroup
+        // costs about an eighth of a working one, a further launch about 20K of them; with a quarter allowed the
+        // tensors of the 1.5B set were reduced at 5.94 TB/s)
         const int64_t new_row = in_table ? row : tiles;
-        const bool wasteful = new_row * (in_table + 1) - (used + tiles) > (used + tiles) / 4 + 1024;
+        const bool wasteful = new_row * (in_table + 1) - (used + tiles) > (used + tiles) / 64 + 16384;
         if (in_table == kReduceMultiMax || (in_table > 0 && wasteful))
             if (const int rc = flush()) return rc;
         if (in_table == 0) row = tiles;
