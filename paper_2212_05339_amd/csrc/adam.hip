@@ -477,16 +477,20 @@ extern "C" int elixir_chunk_adam_step_multi_lp(int n_chunks, float* const* d_mas
                                                const uint16_t* const* d_grad_lowp, uint16_t* const* d_param_lowp,
                                                int lowp_format, const int64_t* n, const elixir_adam_hparams* hp,
                                                const float* d_grad_scale, const int32_t* d_skip, elixir_stream_t stream) {
-    return adam_multi("elixir_chunk_adam_step_multi", false, n_chunks, d_master, d_exp_avg, d_exp_avg_sq, d_grad_fp32, d_grad_lowp,
-                      d_param_lowp, lowp_format, n, hp, d_grad_scale, d_skip, stream);
+    return no_throw("elixir_chunk_adam_step_multi", [&] {
+        return adam_multi("elixir_chunk_adam_step_multi", false, n_chunks, d_master, d_exp_avg, d_exp_avg_sq, d_grad_fp32, d_grad_lowp,
+                          d_param_lowp, lowp_format, n, hp, d_grad_scale, d_skip, stream);
+    });
 }
 
 extern "C" int elixir_chunk_adam_step_tiled_multi_lp(int n_chunks, float* const* d_state, const float* const* d_grad_fp32,
                                                      const uint16_t* const* d_grad_lowp, uint16_t* const* d_param_lowp,
                                                      int lowp_format, const int64_t* n, const elixir_adam_hparams* hp,
                                                      const float* d_grad_scale, const int32_t* d_skip, elixir_stream_t stream) {
-    return adam_multi("elixir_chunk_adam_step_tiled_multi", true, n_chunks, d_state, nullptr, nullptr, d_grad_fp32, d_grad_lowp,
-                      d_param_lowp, lowp_format, n, hp, d_grad_scale, d_skip, stream);
+    return no_throw("elixir_chunk_adam_step_tiled_multi", [&] {
+        return adam_multi("elixir_chunk_adam_step_tiled_multi", true, n_chunks, d_state, nullptr, nullptr, d_grad_fp32, d_grad_lowp,
+                          d_param_lowp, lowp_format, n, hp, d_grad_scale, d_skip, stream);
+    });
 }
 
 extern "C" int elixir_chunk_adam_step_multi(int n_chunks, float* const* d_master, float* const* d_exp_avg,

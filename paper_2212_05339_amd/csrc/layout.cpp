@@ -73,11 +73,9 @@ struct Planner {
     }
 };
 
-}  // namespace
-
-extern "C" int elixir_layout_plan(const int64_t* numel, int T, int64_t chunk_elems, int policy, int64_t align_elems,
-                                  int64_t* chunk_id, int64_t* offset, int64_t* n_chunks, int64_t* valid_len,
-                                  int64_t valid_cap) {
+int elixir_layout_plan_impl(const int64_t* numel, int T, int64_t chunk_elems, int policy, int64_t align_elems,
+                            int64_t* chunk_id, int64_t* offset, int64_t* n_chunks, int64_t* valid_len,
+                            int64_t valid_cap) {
     if (T < 0 || (T > 0 && (!numel || !chunk_id || !offset)) || !n_chunks)
         return fail(ELIXIR_EINVAL, "elixir_layout_plan: NULL argument or negative T");
     if (chunk_elems <= 0 || align_elems <= 0 || chunk_elems % align_elems != 0)
@@ -98,4 +96,14 @@ extern "C" int elixir_layout_plan(const int64_t* numel, int T, int64_t chunk_ele
         for (size_t c = 0; c < pl.used.size(); ++c) valid_len[c] = pl.used[c];
     }
     return ELIXIR_OK;
+}
+}  // namespace
+
+extern "C" int elixir_layout_plan(const int64_t* numel, int T, int64_t chunk_elems, int policy, int64_t align_elems,
+                                  int64_t* chunk_id, int64_t* offset, int64_t* n_chunks, int64_t* valid_len,
+                                  int64_t valid_cap) {
+    return no_throw("elixir_layout_plan", [&] {
+        return elixir_layout_plan_impl(numel, T, chunk_elems, policy, align_elems, chunk_id, offset, n_chunks,
+                                       valid_len, valid_cap);
+    });
 }

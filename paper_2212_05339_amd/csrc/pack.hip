@@ -134,10 +134,8 @@ int check_slices(const char* what, const void* chunk, int64_t chunk_elems, int e
     return ELIXIR_OK;
 }
 
-}  // namespace
-
-extern "C" int elixir_chunk_pack(void* d_chunk, int64_t chunk_elems, int elem_size, const void* const* tensors,
-                                 const int64_t* numel, const int64_t* offset, int T, elixir_stream_t stream) {
+int elixir_chunk_pack_impl(void* d_chunk, int64_t chunk_elems, int elem_size, const void* const* tensors,
+                           const int64_t* numel, const int64_t* offset, int T, elixir_stream_t stream) {
     static const char* what = "elixir_chunk_pack";
     std::vector<int> order;
     const int rc = check_slices(what, d_chunk, chunk_elems, elem_size, tensors, numel, offset, T, &order);
@@ -155,9 +153,18 @@ extern "C" int elixir_chunk_pack(void* d_chunk, int64_t chunk_elems, int elem_si
     if (pos < chunk_elems) segs.push_back({nullptr, base + pos * es, (chunk_elems - pos) * es});
     return launch_segments(segs, (hipStream_t)stream, what);
 }
+}  // namespace
 
-extern "C" int elixir_chunk_unpack(const void* d_chunk, int64_t chunk_elems, int elem_size, void* const* tensors,
-                                   const int64_t* numel, const int64_t* offset, int T, elixir_stream_t stream) {
+extern "C" int elixir_chunk_pack(void* d_chunk, int64_t chunk_elems, int elem_size, const void* const* tensors,
+                                 const int64_t* numel, const int64_t* offset, int T, elixir_stream_t stream) {
+    return no_throw("elixir_chunk_pack", [&] {
+        return elixir_chunk_pack_impl(d_chunk, chunk_elems, elem_size, tensors, numel, offset, T, stream);
+    });
+}
+
+namespace {
+int elixir_chunk_unpack_impl(const void* d_chunk, int64_t chunk_elems, int elem_size, void* const* tensors,
+                             const int64_t* numel, const int64_t* offset, int T, elixir_stream_t stream) {
     static const char* what = "elixir_chunk_unpack";
     std::vector<int> order;
     const int rc = check_slices(what, d_chunk, chunk_elems, elem_size, tensors, numel, offset, T, &order);
@@ -168,4 +175,12 @@ extern "C" int elixir_chunk_unpack(const void* d_chunk, int64_t chunk_elems, int
     segs.reserve(order.size());
     for (int i : order) segs.push_back({base + offset[i] * es, static_cast<char*>(tensors[i]), numel[i] * es});
     return launch_segments(segs, (hipStream_t)stream, what);
+}
+}  // namespace
+
+extern "C" int elixir_chunk_unpack(const void* d_chunk, int64_t chunk_elems, int elem_size, void* const* tensors,
+                                   const int64_t* numel, const int64_t* offset, int T, elixir_stream_t stream) {
+    return no_throw("elixir_chunk_unpack", [&] {
+        return elixir_chunk_unpack_impl(d_chunk, chunk_elems, elem_size, tensors, numel, offset, T, stream);
+    });
 }

@@ -58,10 +58,8 @@ void replay(const std::vector<int64_t>& seq, int64_t n_ids, int64_t n_blocks, in
     *evictions = e;
 }
 
-}  // namespace
-
-extern "C" int elixir_rcache_simulate(const int64_t* seq, int64_t len, int64_t n_blocks, int64_t* misses_out,
-                                      int64_t* evictions_out) {
+int elixir_rcache_simulate_impl(const int64_t* seq, int64_t len, int64_t n_blocks, int64_t* misses_out,
+                                int64_t* evictions_out) {
     static const char* what = "elixir_rcache_simulate";
     if (len < 0 || (len > 0 && !seq) || !misses_out || !evictions_out) return fail(ELIXIR_EINVAL, "%s: bad arguments", what);
     if (n_blocks < 1) return fail(ELIXIR_EINVAL, "%s: n_blocks=%lld, at least one block is needed", what, (long long)n_blocks);
@@ -75,10 +73,19 @@ extern "C" int elixir_rcache_simulate(const int64_t* seq, int64_t len, int64_t n
     replay(s, max_id + 1, n_blocks, misses_out, evictions_out);
     return ELIXIR_OK;
 }
+}  // namespace
 
-extern "C" int elixir_chunk_size_search(const int64_t* numel, int T, const int64_t* candidates, int n_cand, int policy,
-                                        int64_t align_elems, double cache_bytes, int L_c, int* best_out,
-                                        int64_t* replaced_bytes_out, int64_t* padding_out) {
+extern "C" int elixir_rcache_simulate(const int64_t* seq, int64_t len, int64_t n_blocks, int64_t* misses_out,
+                                      int64_t* evictions_out) {
+    return no_throw("elixir_rcache_simulate", [&] {
+        return elixir_rcache_simulate_impl(seq, len, n_blocks, misses_out, evictions_out);
+    });
+}
+
+namespace {
+int elixir_chunk_size_search_impl(const int64_t* numel, int T, const int64_t* candidates, int n_cand, int policy,
+                                  int64_t align_elems, double cache_bytes, int L_c, int* best_out,
+                                  int64_t* replaced_bytes_out, int64_t* padding_out) {
     static const char* what = "elixir_chunk_size_search";
     if (T < 0 || n_cand < 1 || !candidates || !best_out || !replaced_bytes_out || (T > 0 && !numel))
         return fail(ELIXIR_EINVAL, "%s: bad arguments", what);
@@ -126,4 +133,14 @@ extern "C" int elixir_chunk_size_search(const int64_t* numel, int T, const int64
     }
     *best_out = best;
     return ELIXIR_OK;
+}
+}  // namespace
+
+extern "C" int elixir_chunk_size_search(const int64_t* numel, int T, const int64_t* candidates, int n_cand, int policy,
+                                        int64_t align_elems, double cache_bytes, int L_c, int* best_out,
+                                        int64_t* replaced_bytes_out, int64_t* padding_out) {
+    return no_throw("elixir_chunk_size_search", [&] {
+        return elixir_chunk_size_search_impl(numel, T, candidates, n_cand, policy, align_elems, cache_bytes, L_c,
+                                             best_out, replaced_bytes_out, padding_out);
+    });
 }

@@ -249,11 +249,9 @@ int reduce_multi(int T, float* const* d_dst, const uint16_t* const* d_src, const
     return flush();
 }
 
-}  // namespace
-
-extern "C" int elixir_grad_reduce_multi_lp(int n_tensors, float* const* d_dst, const uint16_t* const* d_grad_lowp,
-                                           const int64_t* n, int lowp_format, float scale, int accumulate,
-                                           elixir_stream_t stream) {
+int elixir_grad_reduce_multi_lp_impl(int n_tensors, float* const* d_dst, const uint16_t* const* d_grad_lowp,
+                                     const int64_t* n, int lowp_format, float scale, int accumulate,
+                                     elixir_stream_t stream) {
     static const char* what = "elixir_grad_reduce_multi";
     if (n_tensors < 0) return fail(ELIXIR_EINVAL, "%s: n_tensors is negative", what);
     if (lowp_format != ELIXIR_LOWP_BF16 && lowp_format != ELIXIR_LOWP_FP16)
@@ -273,4 +271,14 @@ extern "C" int elixir_grad_reduce_multi_lp(int n_tensors, float* const* d_dst, c
                                : reduce_multi<true, false>(n_tensors, d_dst, d_grad_lowp, n, scale, s);
     return f16 ? reduce_multi<false, true>(n_tensors, d_dst, d_grad_lowp, n, scale, s)
                : reduce_multi<false, false>(n_tensors, d_dst, d_grad_lowp, n, scale, s);
+}
+}  // namespace
+
+extern "C" int elixir_grad_reduce_multi_lp(int n_tensors, float* const* d_dst, const uint16_t* const* d_grad_lowp,
+                                           const int64_t* n, int lowp_format, float scale, int accumulate,
+                                           elixir_stream_t stream) {
+    return no_throw("elixir_grad_reduce_multi_lp", [&] {
+        return elixir_grad_reduce_multi_lp_impl(n_tensors, d_dst, d_grad_lowp, n, lowp_format, scale, accumulate,
+                                                stream);
+    });
 }
