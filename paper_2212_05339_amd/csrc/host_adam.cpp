@@ -221,8 +221,8 @@ int run_threads(const char* what, int T, W&& work) {
         return ELIXIR_OK;
     }
     std::vector<std::thread> pool;
-    pool.reserve(T - 1);
     try {
+        pool.reserve(T - 1);
         for (int t = 1; t < T; ++t) pool.emplace_back(work, t);
     } catch (...) {
         for (auto& th : pool) th.join();
