@@ -439,33 +439,74 @@ int adam_multi(const char* what, bool tiled, int n_chunks, float* const* d_maste
         order.push_back(k);
     }
     std::stable_sort(order.begin(), order.end(), [&](int a, int b) { return n[a] > n[b]; });
+    // A table row is a chunk, or, when there are few chunks, a piece of one: with a handful of ragged chunks every
+    // grid row is as long as the longest chunk and up to a third of the workgroups find no work (seven 4Mi-element
+    // chunks of a 21M-parameter set: 80.6% of the HBM peak).  Cutting the chunks into pieces of `piece` workgroups,
+    // as long as 64 rows allow, leaves whole pieces of equal length and one shorter piece per chunk.  A piece is a
+    // whole number of state tiles, so its base pointers are those of the chunk shifted.
+    constexpr int64_t kTileBlocks = kStateTile / (kAdamBlock * kAdamVec);
+    int64_t piece = 0;  // 0: rows are whole chunks
+    if (!order.empty() && order.size() * 4 <= (size_t)kAdamMultiMax) {
+        int64_t total = 0;
+        for (const int k : order) total += (n[k] / kAdamVec + kAdamBlock - 1) / kAdamBlock;
+        piece = (total / kAdamMultiMax / kTileBlocks + 1) * kTileBlocks;
+        for (;;) {
+            int64_t rows = 0;
+            for (const int k : order) rows += ((n[k] / kAdamVec + kAdamBlock - 1) / kAdamBlock + piece - 1) / piece;
+            if (rows <= kAdamMultiMax) break;
+            piece += kTileBlocks;
+        }
+    }
+    struct Row {
+        Req r;
+        int64_t pairs;
+    };
+    std::vector<Row> rows;
     for (const int k : order) {
         const Req r = make_req(k);
         const int64_t pairs = n[k] / kAdamVec;
-        const int64_t nb = (pairs + kAdamBlock - 1) / kAdamBlock;
-        // every chunk gets a grid row as long as the first (longest) one of its table: start a new launch when the
-        // table is full or when the workgroups that would find no work exceed 1/64 of the working ones plus 16K.
-        // Measured: a workgroup that only finds out that it has nothing to do costs about an eighth of a working
-        // one, a further launch about as much as 20K of them; with a quarter allowed the 251 8Mi-element chunks
-        // of the 1.5B set ran at 84.5% of the HBM peak, with this rule at 86.1%
-        const int64_t row = in_table ? max_blocks : nb;
-        const bool wasteful = row * (in_table + 1) - (used_blocks + nb) > (used_blocks + nb) / 64 + 16384;
-        if (in_table == kAdamMultiMax || (in_table > 0 && wasteful))
-            if (const int rc = flush()) return rc;
-        const int j = in_table++;
-        tab.master[j] = r.p;
-        tab.exp_avg[j] = r.m;
-        tab.exp_avg_sq[j] = r.v;
-        tab.grad[j] = r.g;
-        tab.out[j] = r.out;
-        tab.n2[j] = pairs;
-        if (nb > max_blocks) max_blocks = nb;
-        used_blocks += nb;
+        const int64_t step = piece ? piece * kAdamBlock : pairs;  // pairs per row
+        for (int64_t first = 0; first < pairs; first += step) {
+            Row row{r, pairs - first < step ? pairs - first : step};
+            const int64_t e0 = first * kAdamVec;  // first element of the row: a multiple of the state tile
+            if (tiled) {
+                row.r.p = r.p + 3 * e0;
+            } else {
+                row.r.p = r.p + e0;
+                row.r.m = r.m + e0;
+                row.r.v = r.v + e0;
+            }
+            row.r.g = (const char*)r.g + e0 * (int64_t)gsz;
+            if (r.out) row.r.out = r.out + e0;
+            rows.push_back(row);
+        }
         if (n[k] % kAdamVec) {  // the odd last element of this chunk
             if (tiled) launch_tiled_scalar(r.p, r, pairs * kAdamVec, n[k], c);
             else launch_scalar(r, pairs * kAdamVec, n[k], c);
             ELIXIR_LAUNCH_CHECK("adam_scalar_kernel");
         }
+    }
+    if (piece) std::stable_sort(rows.begin(), rows.end(), [](const Row& a, const Row& b) { return a.pairs > b.pairs; });
+    for (const Row& row : rows) {
+        const int64_t nb = (row.pairs + kAdamBlock - 1) / kAdamBlock;
+        // every row of the grid is as long as the first (longest) one of its table: start a new launch when the
+        // table is full or when the workgroups that would find no work exceed 1/64 of the working ones plus 16K.
+        // Measured: a workgroup that only finds out that it has nothing to do costs about an eighth of a working
+        // one, a further launch about as much as 20K of them; with a quarter allowed the 251 8Mi-element chunks
+        // of the 1.5B set ran at 84.5% of the HBM peak, with this rule at 86.1%
+        const int64_t len = in_table ? max_blocks : nb;
+        const bool wasteful = len * (in_table + 1) - (used_blocks + nb) > (used_blocks + nb) / 64 + 16384;
+        if (in_table == kAdamMultiMax || (in_table > 0 && wasteful))
+            if (const int rc = flush()) return rc;
+        const int j = in_table++;
+        tab.master[j] = row.r.p;
+        tab.exp_avg[j] = row.r.m;
+        tab.exp_avg_sq[j] = row.r.v;
+        tab.grad[j] = row.r.g;
+        tab.out[j] = row.r.out;
+        tab.n2[j] = row.pairs;
+        if (nb > max_blocks) max_blocks = nb;
+        used_blocks += nb;
     }
     return flush();
 }

@@ -910,6 +910,57 @@ def test_adam_multi_is_bit_identical_to_single_calls_and_matches_the_oracle(grad
         assert np.array_equal(got[~covered].view(np.uint32), ref[~covered].view(np.uint32))
 
 
+@pytest.mark.parametrize("tiled", [False, True])
+def test_batched_update_of_a_few_ragged_chunks_is_bit_identical_to_single_calls(tiled):
+    """With at most 16 chunks the batched call cuts the chunks into equal pieces so that no grid row is mostly empty:
+    random sets of 1 to 16 chunks (long enough for several pieces, odd lengths, lengths just around whole tiles, fp32
+    and 16-bit gradients, parameters written over the gradients or elsewhere) against one call per chunk, bit for bit."""
+    rng = np.random.default_rng(1616)
+    T = ex.ELIXIR_STATE_TILE
+    for case in range(12):
+        k = int(rng.integers(1, 17))
+        lens = [int(rng.choice([int(rng.integers(2, 3 * T)), int(rng.integers(50_000, 700_000)), T * int(rng.integers(1, 90)),
+                                T * int(rng.integers(1, 90)) + int(rng.choice([-1, 1, 2]))])) for _ in range(k)]
+        grad_fp32 = bool(rng.integers(0, 2))
+        in_place = (not grad_fp32) and bool(rng.integers(0, 2))
+        hp = hp_struct(1 + case)
+        what = f"case {case}: lens={lens} grad_fp32={grad_fp32} in_place={in_place}"
+        results = []
+        for batched in (False, True):
+            states, grads, outs = [], [], []
+            for j, n in enumerate(lens):
+                p, m, v = _adam_state(n, 7000 + 31 * case + j, zero_moments=False)
+                x = gen.fill_f32(gen.stream_key(7000 + 31 * case + j, gen.TAG_GRAD, 1), 0, n, 1e-3)
+                g = x if grad_fp32 else gen.fill_bf16(gen.stream_key(7000 + 31 * case + j, gen.TAG_GRAD, 1), 0, n, 1e-3, zero_pct=1)
+                d_g = dev(g)
+                if tiled:
+                    st = torch.zeros(ex.elixir_state_tiled_len(n), dtype=torch.float32, device=DEV)
+                    ex.elixir_state_tile(st, dev(p), dev(m), dev(v), n)
+                else:
+                    st = [dev(p), dev(m), dev(v)]
+                states.append(st); grads.append(d_g)
+                outs.append(d_g if in_place else torch.zeros(n, dtype=torch.int16, device=DEV))
+            gf, gl = (grads, None) if grad_fp32 else (None, grads)
+            if batched and tiled:
+                ex.elixir_chunk_adam_step_tiled_multi_lp(states, gf, gl, outs, ex.ELIXIR_LOWP_BF16, lens, hp)
+            elif batched:
+                ex.elixir_chunk_adam_step_multi_lp([s_[0] for s_ in states], [s_[1] for s_ in states], [s_[2] for s_ in states], gf, gl, outs,
+                                                   ex.ELIXIR_LOWP_BF16, lens, hp)
+            else:
+                for st, g_, o, n in zip(states, grads, outs, lens):
+                    if tiled:
+                        ex.elixir_chunk_adam_step_tiled_lp(st, g_ if grad_fp32 else None, None if grad_fp32 else g_, o, ex.ELIXIR_LOWP_BF16, n, hp)
+                    else:
+                        ex.elixir_chunk_adam_step_lp(st[0], st[1], st[2], g_ if grad_fp32 else None, None if grad_fp32 else g_, o,
+                                                     ex.ELIXIR_LOWP_BF16, n, hp)
+            sync()
+            results.append([[host(a).view(np.uint32).copy() for a in (st if isinstance(st, list) else [st])] + [host(o, np.uint16).copy()]
+                            for st, o in zip(states, outs)])
+        for one, many in zip(*results):
+            for a, b in zip(one, many):
+                assert np.array_equal(a, b), what
+
+
 def test_adam_multi_without_bf16_copy_and_errors():
     n = 5000
     p, m, v = _adam_state(2 * n, 41, zero_moments=True)
