@@ -152,6 +152,21 @@ int elixir_chunk_grad_norm(elixir_ctx* ctx, const float* const* grad_chunks, con
                            elixir_stream_t stream);
 
 /*
+ * elixir_chunk_grad_norm for callers that cannot allocate or hold a context: code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc.  Same arguments without the context, same kernels, bit-identical
+ * results.  The partial sums go to a static array inside the library's device code (4 MiB on every GPU the library
+ * runs on, held until the process ends) instead of a context's workspace; the call allocates and frees nothing, on
+ * the device or the host.  Limits: n_chunks <= 512 (ELIXIR_ECAP beyond; chunk lengths are not limited), HIP devices
+ * 0..63.  The array's device address is looked up once per device: by elixir_ctx_create for its device, else by the
+ * first call on that device (make that first call outside a graph capture).  All calls on one GPU share the one
+ * array: calls that overlap in time on the same GPU (different streams, different threads) race and give wrong
+ * norms; order them on one stream or with events.  Nothing has to be cleared between calls: every slot that is read
+ * is written first by the same call.
+ */
+int elixir_chunk_grad_norm_noalloc(const float* const* grad_chunks, const int64_t* valid_len, int n_chunks,
+                                   float max_norm, float* d_norm_out, float* d_clip_coef_out, elixir_stream_t stream);
+
+/*
  * The same norm taken directly over 16-bit gradient chunks.  The paper's gradient chunk IS a low-precision chunk (the
  * gradients take the place of the parameters in it, Sec. 4.1); with a single micro-batch nothing has to be summed in
  * fp32 first, and norm + update then move 2 + 28 bytes per element instead of 6 (widening pass) + 30.  Every element

@@ -30,7 +30,7 @@ EXPORTS = (
     "elixir_chunk_adam_step_multi_lp", "elixir_loss_scale_init", "elixir_loss_scale_update",
     "elixir_grad_reduce_chunk_sumsq", "elixir_chunk_grad_norm_finish", "elixir_grad_reduce_multi_lp", "elixir_chunk_grad_norm_lp", "elixir_grad_reduce_sources_lp", "elixir_grad_reduce_sources_chunk_sumsq",
     "elixir_state_tiled_len", "elixir_state_tile", "elixir_state_untile", "elixir_chunk_adam_step_tiled_lp",
-    "elixir_chunk_adam_step_tiled_multi_lp", "elixir_host_adam_step_tiled",
+    "elixir_chunk_adam_step_tiled_multi_lp", "elixir_host_adam_step_tiled", "elixir_chunk_grad_norm_noalloc",
 )
 
 
@@ -83,6 +83,7 @@ def lib() -> ctypes.CDLL:
             "elixir_chunk_wait_ready": [vp, ci, vp],
             "elixir_chunk_evict": [vp, ci, vp, sz, vp, vp],
         }
+        sigs["elixir_chunk_grad_norm_noalloc"] = [ctypes.POINTER(vp), pi64, ci, f32, vp, vp, vp]
         sigs["elixir_host_adam_step"] = [vp, vp, vp, vp, vp, vp, i64, ctypes.POINTER(elixir_adam_hparams), f32, ci]
         sigs["elixir_host_adam_step_tiled"] = [vp, vp, vp, vp, i64, ctypes.POINTER(elixir_adam_hparams), f32, ci]
         sigs["elixir_copy_h2d_async"] = [vp, vp, sz, vp]
@@ -224,6 +225,12 @@ def elixir_chunk_grad_norm(ctx: Ctx, grad_chunks, valid_len, max_norm: float, d_
     n = len(grad_chunks)
     _check(lib().elixir_chunk_grad_norm(ctx.handle, _ptr_array(grad_chunks), _i64_array(valid_len), n, max_norm,
                                         _addr(d_norm_out), _addr(d_clip_coef_out), _stream(stream)))
+
+
+def elixir_chunk_grad_norm_noalloc(grad_chunks, valid_len, max_norm: float, d_norm_out, d_clip_coef_out, stream=None) -> None:
+    """elixir_chunk_grad_norm without a context: the partial sums go to the library's static device array."""
+    _check(lib().elixir_chunk_grad_norm_noalloc(_ptr_array(grad_chunks), _i64_array(valid_len), len(grad_chunks), max_norm,
+                                                _addr(d_norm_out), _addr(d_clip_coef_out), _stream(stream)))
 
 
 def elixir_chunk_grad_norm_lp(ctx: Ctx, grad_chunks_lowp, lowp_format: int, valid_len, scale: float, max_norm: float, d_norm_out,

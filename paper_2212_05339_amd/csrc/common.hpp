@@ -31,6 +31,8 @@ inline bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_
 
 constexpr int kNormBlocksPerChunk = 1024;  // fixed, so the reduction tree never depends on the launch
 
+int norm_scratch_init();  // norm.hip: looks up the static norm workspace of the current device (idempotent)
+
 struct Slot {
     void* d_ptr = nullptr;
     bool held = false;          // prefetched and not yet evicted

@@ -48,6 +48,7 @@ extern "C" int elixir_ctx_create(elixir_ctx** out, int device, int64_t max_chunk
     if (device < 0 || device >= n_dev) return fail(ELIXIR_EINVAL, "elixir_ctx_create: device %d of %d", device, n_dev);
     DeviceGuard guard(device);
     if (!guard.ok) return fail(ELIXIR_EHIP, "elixir_ctx_create: cannot make device %d current", device);
+    if (const int rc = norm_scratch_init()) return rc;
     elixir_ctx* c = new (std::nothrow) elixir_ctx();
     if (!c) return fail(ELIXIR_EINVAL, "elixir_ctx_create: out of host memory");
     c->device = device;

@@ -15,6 +15,8 @@
 // reduction -- elixir_grad_reduce_chunk_sumsq produces the same per-chunk slots from the values in registers and the
 // 4-byte re-read disappears (stage 1b below).  Double-precision arithmetic (2 ops/element)
 // stays far below the fp64 vector rate at HBM speed.
+#include <mutex>
+
 #include "common.hpp"
 #include "reduce_elem.hpp"
 
@@ -28,6 +30,33 @@ struct ChunkTable {
     const float* ptr[kMaxBatch];
     int64_t valid[kMaxBatch];
 };
+
+// Workspace of elixir_chunk_grad_norm_noalloc: the per-chunk partial sums live in this array, which is part of the
+// library's code object (one copy per GPU that loads the library, kept until the process ends), so the call needs no
+// context and no allocation.  In host code the name below is only a handle: the array's device address is looked up
+// once per device (scratch_for_device) and that pointer is what kernels and host calls are given.
+constexpr int kNoAllocMaxChunks = 512;                                                          // 512 x 1024 doubles = 4 MiB
+static __device__ __align__(256) double scratch[(size_t)kNoAllocMaxChunks * kNormBlocksPerChunk];
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+double* g_scratch_ptr[kMaxDevices] = {};  // device address of `scratch` on device d, nullptr until looked up
+
+// Device address of `scratch` on the CURRENT device (looked up on first use, with that device current).
+int scratch_for_device(const char* what, double** out) {
+    int dev = -1;
+    ELIXIR_HIP_TRY(hipGetDevice(&dev));
+    if (dev < 0 || dev >= kMaxDevices) return fail(ELIXIR_ECAP, "%s: device %d, the library keeps workspaces for devices 0..%d", what, dev, kMaxDevices - 1);
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        double* p = nullptr;
+        ELIXIR_HIP_TRY(hipGetSymbolAddress((void**)&p, HIP_SYMBOL(scratch)));
+        if (!p) return fail(ELIXIR_EHIP, "%s: hipGetSymbolAddress returned a NULL address", what);
+        g_scratch_ptr[dev] = p;
+    }
+    *out = g_scratch_ptr[dev];
+    return ELIXIR_OK;
+}
 
 __device__ __forceinline__ double block_sum(double x, double* lds) {
 #pragma unroll
@@ -263,25 +292,22 @@ void launch_fused(float* dst, const SrcTable& srcs, int n_src, int64_t n, int64_
 
 }  // namespace
 
-extern "C" int elixir_chunk_grad_norm(elixir_ctx* ctx, const float* const* grad_chunks, const int64_t* valid_len,
-                                      int n_chunks, float max_norm, float* d_norm_out, float* d_clip_coef_out,
-                                      elixir_stream_t stream) {
-    if (!ctx) return fail(ELIXIR_EINVAL, "elixir_chunk_grad_norm: ctx is NULL");
-    if (n_chunks < 0 || (n_chunks > 0 && (!grad_chunks || !valid_len)))
-        return fail(ELIXIR_EINVAL, "elixir_chunk_grad_norm: NULL table or negative n_chunks");
-    if (n_chunks > ctx->max_chunks)
-        return fail(ELIXIR_ECAP, "elixir_chunk_grad_norm: %d chunks, context sized for %d", n_chunks, ctx->max_chunks);
+namespace {
+
+// Argument checks and launches shared by elixir_chunk_grad_norm and elixir_chunk_grad_norm_noalloc: the two differ
+// only in where the per-chunk partial sums go (max_elems < 0: no limit on a chunk's length).
+int norm_fp32_chunks(const char* what, const float* const* grad_chunks, const int64_t* valid_len, int n_chunks,
+                     int64_t max_elems, float max_norm, double* partials, float* d_norm_out, float* d_clip_coef_out,
+                     hipStream_t s) {
     if (!aligned(d_norm_out, 4) || !aligned(d_clip_coef_out, 4))
-        return fail(ELIXIR_EALIGN, "elixir_chunk_grad_norm: output pointer not 4-byte aligned");
+        return fail(ELIXIR_EALIGN, "%s: output pointer not 4-byte aligned", what);
     for (int c = 0; c < n_chunks; ++c) {
-        if (valid_len[c] < 0 || valid_len[c] > ctx->max_chunk_elems)
-            return fail(valid_len[c] < 0 ? ELIXIR_EINVAL : ELIXIR_ECAP,
-                        "elixir_chunk_grad_norm: valid_len[%d]=%lld outside [0, %lld]", c, (long long)valid_len[c],
-                        (long long)ctx->max_chunk_elems);
-        if (valid_len[c] > 0 && !grad_chunks[c]) return fail(ELIXIR_EINVAL, "elixir_chunk_grad_norm: grad_chunks[%d] is NULL", c);
-        if (!aligned(grad_chunks[c], 4)) return fail(ELIXIR_EALIGN, "elixir_chunk_grad_norm: grad_chunks[%d] not 4-byte aligned", c);
+        if (valid_len[c] < 0 || (max_elems >= 0 && valid_len[c] > max_elems))
+            return fail(valid_len[c] < 0 ? ELIXIR_EINVAL : ELIXIR_ECAP, "%s: valid_len[%d]=%lld outside [0, %lld]", what, c,
+                        (long long)valid_len[c], (long long)max_elems);
+        if (valid_len[c] > 0 && !grad_chunks[c]) return fail(ELIXIR_EINVAL, "%s: grad_chunks[%d] is NULL", what, c);
+        if (!aligned(grad_chunks[c], 4)) return fail(ELIXIR_EALIGN, "%s: grad_chunks[%d] not 4-byte aligned", what, c);
     }
-    hipStream_t s = (hipStream_t)stream;
     for (int c0 = 0; c0 < n_chunks; c0 += kMaxBatch) {
         const int nb = n_chunks - c0 < kMaxBatch ? n_chunks - c0 : kMaxBatch;
         ChunkTable tab;
@@ -290,13 +316,50 @@ extern "C" int elixir_chunk_grad_norm(elixir_ctx* ctx, const float* const* grad_
             tab.valid[j] = j < nb ? valid_len[c0 + j] : 0;
         }
         hipLaunchKernelGGL(sumsq_kernel, dim3(kNormBlocksPerChunk, nb), dim3(kSumsqBlock), 0, s, tab,
-                           ctx->d_partials + (int64_t)c0 * kNormBlocksPerChunk);
+                           partials + (int64_t)c0 * kNormBlocksPerChunk);
         ELIXIR_LAUNCH_CHECK("sumsq_kernel");
     }
-    hipLaunchKernelGGL(finish_kernel, dim3(1), dim3(1024), 0, s, ctx->d_partials,
-                       (int64_t)n_chunks * kNormBlocksPerChunk, max_norm, 1.0, d_norm_out, d_clip_coef_out);
+    hipLaunchKernelGGL(finish_kernel, dim3(1), dim3(1024), 0, s, partials, (int64_t)n_chunks * kNormBlocksPerChunk, max_norm, 1.0,
+                       d_norm_out, d_clip_coef_out);
     ELIXIR_LAUNCH_CHECK("finish_kernel");
     return ELIXIR_OK;
+}
+
+}  // namespace
+
+namespace elixir {
+// Called by elixir_ctx_create with the context's device current: the address of the static workspace on that device is
+// looked up at set-up, so that a later elixir_chunk_grad_norm_noalloc on that device does nothing but launch.
+int norm_scratch_init() {
+    double* ptr = nullptr;
+    return scratch_for_device("elixir_ctx_create", &ptr);
+}
+}  // namespace elixir
+
+extern "C" int elixir_chunk_grad_norm(elixir_ctx* ctx, const float* const* grad_chunks, const int64_t* valid_len,
+                                      int n_chunks, float max_norm, float* d_norm_out, float* d_clip_coef_out,
+                                      elixir_stream_t stream) {
+    static const char* what = "elixir_chunk_grad_norm";
+    if (!ctx) return fail(ELIXIR_EINVAL, "%s: ctx is NULL", what);
+    if (n_chunks < 0 || (n_chunks > 0 && (!grad_chunks || !valid_len))) return fail(ELIXIR_EINVAL, "%s: NULL table or negative n_chunks", what);
+    if (n_chunks > ctx->max_chunks) return fail(ELIXIR_ECAP, "%s: %d chunks, context sized for %d", what, n_chunks, ctx->max_chunks);
+    return norm_fp32_chunks(what, grad_chunks, valid_len, n_chunks, ctx->max_chunk_elems, max_norm, ctx->d_partials, d_norm_out,
+                            d_clip_coef_out, (hipStream_t)stream);
+}
+
+// The same norm with the partial sums in the library's own static device array: no context, no allocation.
+// Every slot the final stage reads is written by the first stage of the same call (a workgroup writes its slot even
+// when its chunk is empty), so what an earlier call left in the array never matters and nothing has to be cleared.
+extern "C" int elixir_chunk_grad_norm_noalloc(const float* const* grad_chunks, const int64_t* valid_len, int n_chunks,
+                                              float max_norm, float* d_norm_out, float* d_clip_coef_out,
+                                              elixir_stream_t stream) {
+    static const char* what = "elixir_chunk_grad_norm_noalloc";
+    if (n_chunks < 0 || (n_chunks > 0 && (!grad_chunks || !valid_len))) return fail(ELIXIR_EINVAL, "%s: NULL table or negative n_chunks", what);
+    if (n_chunks > kNoAllocMaxChunks)
+        return fail(ELIXIR_ECAP, "%s: %d chunks, the static workspace holds the partial sums of at most %d", what, n_chunks, kNoAllocMaxChunks);
+    double* ptr = nullptr;
+    if (const int rc = scratch_for_device(what, &ptr)) return rc;
+    return norm_fp32_chunks(what, grad_chunks, valid_len, n_chunks, -1, max_norm, ptr, d_norm_out, d_clip_coef_out, (hipStream_t)stream);
 }
 
 extern "C" int elixir_chunk_grad_norm_lp(elixir_ctx* ctx, const uint16_t* const* grad_chunks_lowp, int lowp_format,
