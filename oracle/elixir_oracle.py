@@ -13,8 +13,10 @@ Citations (paper = arXiv 2212.05339):
     Sec. 4.1;
   * fp32 master weight rounded to low precision after the update, 2+2+12
     bytes per parameter: Sec. 2 "Mixed Precision Training".
-Every function is pinned by tests in tests/test_oracle_pins.py (closed forms,
-brute force, a library special case); none is "parity unpinned".
+Every function is pinned by tests in tests/test_oracle_pins.py,
+tests/test_benefit_model.py and tests/test_rcache_sim.py (closed forms, brute
+force, hand-worked cases under tests/golden/, a library special case); none
+is "parity unpinned".
 """
 from __future__ import annotations
 

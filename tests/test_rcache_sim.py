@@ -1,5 +1,7 @@
 """rCache replacement simulation (Belady) and chunk-size search: oracle pins and product parity.  Host only."""
 import functools
+import inspect
+import os
 import time
 
 import numpy as np
@@ -73,6 +75,133 @@ def test_step_sequence_hand_case():
     numels = [3, 5, 4, 9, 2]
     cid, off, _ = orc.layout_plan(numels, 8, orc.NEXT_FIT)
     assert orc.step_access_sequence(numels, 8, cid, off) == [0, 1, 2, 3, 2, 1, 0]
+
+
+# --------------------------------------------------------------------------- the chunk-size search, pinned
+
+GOLDEN = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden", "chunk_size_search_hand_case.txt")
+
+
+def hand_cases():
+    """The cases of tests/golden/chunk_size_search_hand_case.txt (worked by hand from App. A.2) as dicts of int lists."""
+    cases, cur = [], None
+    for line in open(GOLDEN):
+        line = line.strip()
+        if not line or line.startswith("#"):
+            continue
+        key, *vals = line.split()
+        if key == "case":
+            cur = {"name": vals[0]}
+            cases.append(cur)
+        else:
+            cur[key] = [int(v) for v in vals]
+    assert [c["name"] for c in cases] == ["A", "B", "C"]
+    return cases
+
+
+def check_against_hand_cases(search, simulate=None, sequence=None):
+    """Raises AssertionError unless the given functions reproduce every hand-worked number."""
+    for c in hand_cases():
+        numels, cands, cache, L_c = c["numel"], c["candidates"], float(c["cache_bytes"][0]), c["L_c"][0]
+        for k, C in enumerate(cands):
+            cid, off, valid = orc.layout_plan(numels, C, orc.NEXT_FIT)
+            assert len(valid) * C - sum(numels) == c["padding"][k]
+            if sequence is not None:
+                assert sequence(numels, C, cid, off) == c[f"sequence_{C}"], (c["name"], C)
+            if simulate is not None:
+                assert simulate(c[f"sequence_{C}"], c["blocks"][k]) == (c["misses"][k], c["replacements"][k]), (c["name"], C)
+        best, replaced, padding = search(numels, cands, cache, orc.NEXT_FIT, 1, L_c)
+        assert (best, list(replaced), list(padding)) == (c["best"][0], c["replaced_bytes"], c["padding"]), c["name"]
+
+
+def test_oracle_search_reproduces_the_hand_worked_cases():
+    check_against_hand_cases(orc.chunk_size_search, orc.rcache_simulate, orc.step_access_sequence)
+
+
+def min_replaced_bytes_brute_force(seq, cache_bytes, block_bytes):
+    """Fewest bytes any replacement policy has to replace: a cache of cache_bytes bytes in which every chunk takes
+    block_bytes (always room for one chunk); a miss that finds no room throws one cached chunk out -- block_bytes
+    replaced -- and every choice of victim is tried."""
+    seq = tuple(seq)
+
+    @functools.lru_cache(maxsize=None)
+    def go(i, cache):
+        if i == len(seq):
+            return 0
+        c = seq[i]
+        if c in cache:
+            return go(i + 1, cache)
+        if not cache or (len(cache) + 1) * block_bytes <= cache_bytes:
+            return go(i + 1, tuple(sorted(cache + (c,))))
+        return block_bytes + min(go(i + 1, tuple(sorted(tuple(x for x in cache if x != v) + (c,)))) for v in cache)
+
+    return go(0, ())
+
+
+def forward_backward_sequence(numels, C, policy):
+    """The chunks one step touches, from the element ranges alone: parameter i covers the linear elements
+    [chunk_id*C + offset, + numel); forward in order, backward in reverse, repeats in a row dropped."""
+    cid, off, _ = orc.layout_plan(numels, C, policy)
+    touched = []
+    order = [i for i, n in enumerate(numels) if n > 0]
+    for i in order:
+        lo = cid[i] * C + off[i]
+        touched += sorted({e // C for e in range(lo, lo + numels[i])})
+    for i in reversed(order):
+        lo = cid[i] * C + off[i]
+        touched += sorted({e // C for e in range(lo, lo + numels[i])}, reverse=True)
+    return [c for k, c in enumerate(touched) if k == 0 or touched[k - 1] != c]
+
+
+@pytest.mark.parametrize("policy", [0, 1, 2])
+def test_oracle_search_matches_brute_force_over_all_replacement_choices(policy):
+    rng = np.random.default_rng(11 + policy)
+    checked = 0
+    for _ in range(400):
+        numels = [int(x) for x in rng.integers(0, 10, size=rng.integers(1, 7))]
+        if sum(numels) == 0:
+            continue
+        cands = sorted({int(x) for x in rng.integers(3, 13, size=3)})
+        L_c = int(rng.choice([1, 2, 4]))
+        cache = float(L_c * int(rng.integers(3, 40)))
+        seqs = [forward_backward_sequence(numels, C, policy) for C in cands]
+        if max(len(q) for q in seqs) > 13:          # keeps the exhaustive search small (it is exponential)
+            continue
+        want_rep = [min_replaced_bytes_brute_force(q, cache, L_c * C) for q, C in zip(seqs, cands)]
+        want_pad = [(max(q) + 1) * C - sum(numels) for q, C in zip(seqs, cands)]
+        want_best = min(range(len(cands)), key=lambda k: (want_rep[k], want_pad[k], -cands[k]))
+        best, rep, pad = orc.chunk_size_search(numels, cands, cache, policy, 1, L_c)
+        assert (list(rep), list(pad), best) == (want_rep, want_pad, want_best), (numels, cands, cache, L_c)
+        checked += 1
+    assert checked > 100
+
+
+def _mutated_search(old, new):
+    """The oracle's chunk_size_search with one planted mistake (a textual change of its source)."""
+    src = inspect.getsource(orc.chunk_size_search)
+    assert src.count(old) == 1, f"the oracle's source no longer contains {old!r}"
+    ns = dict(vars(orc))
+    exec(src.replace(old, new), ns)
+    return ns["chunk_size_search"]
+
+
+@pytest.mark.parametrize("old,new", [
+    ("_, ev = rcache_simulate", "ev, _ = rcache_simulate"),            # bytes of every miss instead of every replacement
+    ("cache_bytes // (L_c * C)", "cache_bytes // C"),                  # block size without the element size
+    ("replaced.append(ev * L_c * C)", "replaced.append(ev * C)"),      # elements instead of bytes
+    ("replaced.append(ev * L_c * C)", "replaced.append(ev)"),          # replacements instead of bytes
+    ("padding[k], -candidates[k]", "-padding[k], -candidates[k]"),     # tie broken towards more padding
+])
+def test_planted_mistakes_in_the_search_fail_the_pins(old, new):
+    wrong = _mutated_search(old, new)
+    with pytest.raises(AssertionError):
+        check_against_hand_cases(wrong)
+    check_against_hand_cases(_mutated_search("_, ev = rcache_simulate", "_, ev  = rcache_simulate"))   # the harness itself passes an unchanged copy
+
+
+def test_product_search_reproduces_the_hand_worked_cases():
+    check_against_hand_cases(lambda numels, cands, cache, policy, align, L_c: ex.elixir_chunk_size_search(numels, cands, cache, policy, align, L_c),
+                             ex.elixir_rcache_simulate)
 
 
 @pytest.mark.parametrize("policy", [0, 1, 2])
