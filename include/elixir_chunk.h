@@ -284,7 +284,8 @@ int elixir_chunk_adam_step_tiled_multi_lp(int n_chunks, float* const* d_state, c
  *       buffers of slot_bytes each, owned by the caller; replaces any earlier
  *       registration (ELIXIR_ESTATE while a slot is held).
  *   elixir_chunk_prefetch : picks a slot that is not held, makes h2d_stream
- *       wait until that slot's previous eviction has finished, enqueues the
+ *       wait until that slot's previous eviction has finished (and any eviction
+ *       still on its way into h_block from another slot), enqueues the
  *       host-to-device copy of `bytes` (<= slot_bytes) from h_block and marks
  *       the slot held.  *slot_out receives the slot index.  ELIXIR_ENOSLOT if
  *       all slots are held.

@@ -40,6 +40,8 @@ struct Slot {
     hipEvent_t ready = nullptr;   // H2D copy finished
     hipEvent_t updated = nullptr; // compute stream reached the eviction request
     hipEvent_t evicted = nullptr; // D2H copy finished (slot reusable)
+    const char* evict_dst = nullptr;  // host range the last eviction writes (valid while evict_pending)
+    size_t evict_bytes = 0;
 };
 
 }  // namespace elixir

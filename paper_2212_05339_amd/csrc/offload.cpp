@@ -4,7 +4,8 @@
 // The paper overlaps chunk movement with computation by issuing it on separate
 // streams in the known order of use (Sec. 4.3).  Here ordering is expressed
 // only with events, so the host thread never blocks:
-//   prefetch : h2d stream waits for the slot's previous eviction, copies, records `ready`
+//   prefetch : h2d stream waits for the slot's previous eviction and for any pending eviction into the host block
+//              it is about to read, copies, records `ready`
 //   wait     : compute stream waits for `ready`
 //   evict    : d2h stream waits for an event recorded on the compute stream,
 //              copies back, records `evicted`
@@ -90,6 +91,15 @@ extern "C" int elixir_chunk_prefetch(elixir_ctx* ctx, const void* h_block, size_
     Slot& sl = ctx->slots[slot];
     hipStream_t s = (hipStream_t)h2d_stream;
     if (sl.evict_pending) ELIXIR_HIP_TRY(hipStreamWaitEvent(s, sl.evicted, 0));
+    // The host block may still be the target of an eviction from ANOTHER slot (few host chunks, slots taken round
+    // robin: a block evicted from slot 0 comes back through slot 1): the upload must not read it before that
+    // download has landed.
+    const char* src = static_cast<const char*>(h_block);
+    for (int i = 0; i < ctx->n_slots; ++i) {
+        const Slot& o = ctx->slots[i];
+        if (i == slot || !o.evict_pending || !o.evict_dst) continue;
+        if (src < o.evict_dst + o.evict_bytes && o.evict_dst < src + bytes) ELIXIR_HIP_TRY(hipStreamWaitEvent(s, o.evicted, 0));
+    }
     ELIXIR_HIP_TRY(copy_in_pieces(sl.d_ptr, h_block, bytes, hipMemcpyHostToDevice, s));
     ELIXIR_HIP_TRY(hipEventRecord(sl.ready, s));
     sl.held = true;
@@ -120,6 +130,8 @@ extern "C" int elixir_chunk_evict(elixir_ctx* ctx, int slot, void* h_block, size
     ELIXIR_HIP_TRY(hipStreamWaitEvent(ds, sl.updated, 0));
     if (h_block) ELIXIR_HIP_TRY(copy_in_pieces(h_block, sl.d_ptr, bytes, hipMemcpyDeviceToHost, ds));
     ELIXIR_HIP_TRY(hipEventRecord(sl.evicted, ds));
+    sl.evict_dst = static_cast<const char*>(h_block);
+    sl.evict_bytes = h_block ? bytes : 0;
     sl.evict_pending = true;
     sl.held = false;
     return ELIXIR_OK;

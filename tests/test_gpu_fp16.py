@@ -186,10 +186,10 @@ def test_fp16_training_steps_with_loss_scaling_end_to_end():
             assert skip == (it == 1)
             if not skip:
                 assert float(host(d_norm)[0]) == pytest.approx(norm, rel=1e-5)
-                assert float(raw[3]) == pytest.approx(gs, rel=1e-5)
-                gpu_gs = float(raw[3])
-                for c in range(nch):
-                    orc.chunk_adam_step(p[c], rm[c], rv[c], ref_g[c], ro[c], step=steps_done + 1, grad_scale=gpu_gs, fmt=orc.FP16, **HP)
+                # the device derives the factor from the norm it stored as fp32 and stores it as fp32: two roundings of 6e-8
+                assert abs(float(raw[3]) - gs) <= 2.5e-7 * gs
+                for c in range(nch):        # the oracle's update takes the oracle's own factor
+                    orc.chunk_adam_step(p[c], rm[c], rv[c], ref_g[c], ro[c], step=steps_done + 1, grad_scale=gs, fmt=orc.FP16, **HP)
                 steps_done += 1
                 assert norm / S_used > 1.0                                  # clipping was active
             check_adam_close(host(d_p), host(d_m), host(d_v), p, rm, rv, lr=HP["lr"], gmax=0.2 / 30, steps=max(1, steps_done), what=f"iteration {it}")
@@ -239,15 +239,15 @@ def test_fp16_gradient_chunks_with_loss_scaling_and_no_fp32_gradients():
                 for c in range(nch):                                          # the gradients are still there, bit for bit
                     assert np.array_equal(host(d_g[c], np.uint16), bits[c])
             else:
-                assert float(host(d_norm)[0]) == pytest.approx(norm, rel=1e-6) and float(raw[3]) == pytest.approx(gs, rel=1e-5)
+                assert float(host(d_norm)[0]) == pytest.approx(norm, rel=1e-6) and abs(float(raw[3]) - gs) <= 2.5e-7 * gs
                 assert norm / S_used > 1.0                                    # clipping was active
                 for c, n in enumerate(lens):
                     want = np.zeros(n, np.uint16)
-                    orc.chunk_adam_step(ref[c][0], ref[c][1], ref[c][2], bits[c], want, step=steps_done + 1, grad_scale=float(raw[3]), fmt=orc.FP16, **HP)
+                    orc.chunk_adam_step(ref[c][0], ref[c][1], ref[c][2], bits[c], want, step=steps_done + 1, grad_scale=gs, fmt=orc.FP16, **HP)
                     back = [torch.zeros(n, dtype=torch.float32, device=DEV) for _ in range(3)]
                     ex.elixir_state_untile(states[c], *back, n)
                     torch.cuda.synchronize()
-                    check_adam_close(host(back[0]), host(back[1]), host(back[2]), *ref[c], lr=HP["lr"], gmax=float(np.abs(vals[c]).max()) * float(raw[3]), steps=steps_done + 1, what=f"iteration {it} chunk {c}")
+                    check_adam_close(host(back[0]), host(back[1]), host(back[2]), *ref[c], lr=HP["lr"], gmax=float(np.abs(vals[c]).max()) * gs, steps=steps_done + 1, what=f"iteration {it} chunk {c}")
                     check_bf16_copy(host(d_g[c], np.uint16), host(back[0]), want, ref[c][0], lr=HP["lr"], steps=steps_done + 1, fmt=1)
                 steps_done += 1
         assert steps_done == 2 and S == 512.0

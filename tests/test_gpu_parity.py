@@ -1115,12 +1115,14 @@ def test_config_accumulate_clip_step_scaled_down(ctx):
     assert host(d_nc)[0] == pytest.approx(ref_norm, rel=1e-5)
     assert host(d_nc)[1] == pytest.approx(ref_coef, rel=1e-5)
     rm, rv, ro = np.zeros_like(p), np.zeros_like(p), np.zeros((nch, C), np.uint16)
-    gpu_coef = float(host(d_nc)[1])
+    # the device keeps the coefficient as one fp32 value: at most half an fp32 ulp (6e-8) from the oracle's double, plus
+    # the difference of the two summation orders of the norm (far below that)
+    assert abs(float(host(d_nc)[1]) - ref_coef) <= 1.2e-7 * ref_coef
     for c in range(nch):
-        # the clip coefficient is compared above to 1e-5; the update is checked with the coefficient the step used
-        oracle_adam_parallel(p[c], rm[c], rv[c], ref_g[c], ro[c], step=1, grad_scale=gpu_coef)
+        # the whole chain on the oracle's own numbers: its reduction, its norm, its coefficient, its update
+        oracle_adam_parallel(p[c], rm[c], rv[c], ref_g[c], ro[c], step=1, grad_scale=ref_coef)
         check_adam_close(host(d_p[c]), host(d_m[c]), host(d_v[c]), p[c], rm[c], rv[c], lr=HP["lr"],
-                         gmax=0.2 * gpu_coef, what=f"chunk {c}")
+                         gmax=0.2 * ref_coef, what=f"chunk {c}")
         check_bf16_copy(host(d_out[c], np.uint16), host(d_p[c]), ro[c], p[c], lr=HP["lr"])
     # gradients in memory stay unscaled
     assert np.array_equal(host(gchunks).view(np.uint32), ref_g.view(np.uint32))
@@ -1197,6 +1199,55 @@ def test_offload_is_bitwise_identical_to_resident(ctx, n_slots):
         sync()
         ex.elixir_offload_register_slots(ctx, [], 0)
         for b in blocks.values():
+            ex.elixir_host_free(b)
+
+
+def test_offload_with_fewer_host_chunks_than_slots_over_several_steps(ctx):
+    """Two host-resident chunks through three staging slots for four steps, enqueued without a host wait in between:
+    a block evicted from one slot comes back through another one right away, so its upload has to wait for the
+    download that is still writing the block.  Bitwise against the all-resident run."""
+    C, steps = 4 * gen.Mi + 77, 4
+    L = ex.elixir_state_tiled_len(C)
+    nbytes = 4 * L
+    key = gen.stream_key(gen.BASE_SEED, gen.TAG_PARAM, cfg=7)
+    grads = [[dev(gen.fill_bf16(gen.stream_key(gen.BASE_SEED, gen.TAG_GRAD, t, 0, 7), c * C, C, 1e-3)) for c in range(2)] for t in range(steps)]
+    ref = [torch.zeros(L, dtype=torch.float32, device=DEV) for _ in range(2)]
+    ref_out = torch.zeros(2, C, dtype=torch.int16, device=DEV)
+    out = torch.zeros(2, C, dtype=torch.int16, device=DEV)
+    blocks = [ex.elixir_host_alloc(nbytes) for _ in range(2)]
+    slots = [torch.full((L,), float("nan"), dtype=torch.float32, device=DEV) for _ in range(3)]
+    compute, h2d, d2h = torch.cuda.Stream(), torch.cuda.Stream(), torch.cuda.Stream()
+    try:
+        for c in range(2):
+            p = dev(gen.fill_f32(key, c * C, C, 0.02))
+            ex.elixir_state_tile(ref[c], p, torch.zeros_like(p), torch.zeros_like(p), C)
+            ex.elixir_copy_d2h_async(blocks[c], ref[c], nbytes)
+        sync()
+        for t in range(steps):
+            for c in range(2):
+                ex.elixir_chunk_adam_step_tiled_lp(ref[c], None, grads[t][c], ref_out[c], 0, C, hp_struct(t + 1))
+        sync()
+        ex.elixir_offload_register_slots(ctx, slots, nbytes)
+        used = []
+        with torch.cuda.stream(compute):
+            for t in range(steps):
+                for c in range(2):
+                    s_ = ex.elixir_chunk_prefetch(ctx, blocks[c], nbytes, h2d)
+                    used.append(s_)
+                    ex.elixir_chunk_wait_ready(ctx, s_, compute)
+                    ex.elixir_chunk_adam_step_tiled_lp(slots[s_], None, grads[t][c], out[c], 0, C, hp_struct(t + 1), None, None, compute)
+                    ex.elixir_chunk_evict(ctx, s_, blocks[c], nbytes, compute, d2h)
+        sync()
+        assert used == [0, 1, 2, 0, 1, 2, 0, 1]          # round robin: a block never comes back through the slot it left from
+        for c in range(2):
+            got = np.empty(L, np.float32)
+            ctypes.memmove(got.ctypes.data, blocks[c], nbytes)
+            assert np.array_equal(got.view(np.uint32), host(ref[c]).view(np.uint32)), f"chunk {c}"
+        assert torch.equal(out, ref_out)
+    finally:
+        sync()
+        ex.elixir_offload_register_slots(ctx, [], 0)
+        for b in blocks:
             ex.elixir_host_free(b)
 
 
