@@ -272,6 +272,33 @@ int elixir_chunk_adam_step_tiled_multi_lp(int n_chunks, float* const* d_state, c
                                           const int32_t* d_skip, elixir_stream_t stream);
 
 /*
+ * Placement of the long-lived chunk buffers.  The paper allocates what lives as long as the run (optimizer states,
+ * rCache blocks) once, before training (Sec. 3 "Pre-runtime Profiler", finding 2).  On MI355X where those buffers lie
+ * relative to each other is worth 2-7% of the update's bandwidth: arrays that one kernel reads together (a chunk's
+ * optimizer chunk, its gradient arrays, its fp32 gradient chunk) want to sit side by side in one allocation, arrays
+ * that are only written (the low-precision parameter copies) somewhere else, and no two arrays a multiple of a few MiB
+ * apart.  Host only, integers; allocates nothing.
+ *   arrays[a] : one kind of per-chunk array: its size in bytes, how many of them a chunk has (e.g. several gradient
+ *       sets), and its region (ELIXIR_ARENA_NEAR: laid out chunk after chunk, array after array, in region 0;
+ *       ELIXIR_ARENA_FAR: the same in region 1).
+ *   offset_out[c * K + k] : byte offset, from the start of its region, of the k-th array of chunk c, where k counts
+ *       the arrays of a chunk in the order given (array 0's `count` instances, then array 1's, ...; K = sum of the
+ *       counts).  Every offset is a multiple of 8192 and every array is followed by ELIXIR_ARENA_GAP_BYTES.
+ *       offset_cap is the capacity of offset_out in entries (ELIXIR_ECAP if it is too small; region_bytes_out is set).
+ *   region_bytes_out[2] : bytes the caller has to allocate for region 0 and region 1 -- two allocations, made as far
+ *       apart in the address space as the caller can arrange (e.g. region 1 first, before other large allocations).
+ */
+#define ELIXIR_ARENA_GAP_BYTES ((4 << 20) + 8192)
+enum { ELIXIR_ARENA_NEAR = 0, ELIXIR_ARENA_FAR = 1 };
+typedef struct {
+    int64_t bytes;
+    int32_t count;
+    int32_t region;
+} elixir_arena_array;
+int elixir_arena_plan(int n_chunks, const elixir_arena_array* arrays, int n_arrays, int64_t* offset_out,
+                      int64_t offset_cap, int64_t* region_bytes_out);
+
+/*
  * Offload pipeline for chunks whose optimizer chunk lives in host memory (the
  * paper keeps a searched number of chunks in CPU memory, Sec. 3 "Search
  * Engine", and overlaps chunk movement with computation by running it on

@@ -4,4 +4,4 @@ The product is libelixir_chunk.so (HIP kernels behind a C ABI, see include/elixi
 this package is its thin Python binding.
 """
 from .binding import *  # noqa: F401,F403
-from .binding import EXPORTS, LIB_PATH, Ctx, ElixirError, elixir_adam_hparams, elixir_hw_profile, lib, make_hparams  # noqa: F401
+from .binding import EXPORTS, LIB_PATH, Ctx, ElixirError, elixir_adam_hparams, elixir_arena_array, elixir_hw_profile, lib, make_hparams  # noqa: F401

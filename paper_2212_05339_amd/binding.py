@@ -30,7 +30,7 @@ EXPORTS = (
     "elixir_chunk_adam_step_multi_lp", "elixir_loss_scale_init", "elixir_loss_scale_update",
     "elixir_grad_reduce_chunk_sumsq", "elixir_chunk_grad_norm_finish", "elixir_grad_reduce_multi_lp", "elixir_chunk_grad_norm_lp", "elixir_grad_reduce_sources_lp", "elixir_grad_reduce_sources_chunk_sumsq",
     "elixir_state_tiled_len", "elixir_state_tile", "elixir_state_untile", "elixir_chunk_adam_step_tiled_lp",
-    "elixir_chunk_adam_step_tiled_multi_lp", "elixir_host_adam_step_tiled", "elixir_chunk_grad_norm_noalloc",
+    "elixir_chunk_adam_step_tiled_multi_lp", "elixir_host_adam_step_tiled", "elixir_chunk_grad_norm_noalloc", "elixir_arena_plan",
 )
 
 
@@ -42,6 +42,10 @@ class ElixirError(RuntimeError):
 
 class elixir_hw_profile(ctypes.Structure):
     _fields_ = [("b_g2c", ctypes.c_double), ("b_c2g", ctypes.c_double), ("v_g", ctypes.c_double), ("v_c", ctypes.c_double)]
+
+
+class elixir_arena_array(ctypes.Structure):
+    _fields_ = [("bytes", ctypes.c_int64), ("count", ctypes.c_int32), ("region", ctypes.c_int32)]
 
 
 class elixir_adam_hparams(ctypes.Structure):
@@ -84,6 +88,7 @@ def lib() -> ctypes.CDLL:
             "elixir_chunk_evict": [vp, ci, vp, sz, vp, vp],
         }
         sigs["elixir_chunk_grad_norm_noalloc"] = [ctypes.POINTER(vp), pi64, ci, f32, vp, vp, vp]
+        sigs["elixir_arena_plan"] = [ci, ctypes.POINTER(elixir_arena_array), ci, pi64, i64, pi64]
         sigs["elixir_host_adam_step"] = [vp, vp, vp, vp, vp, vp, i64, ctypes.POINTER(elixir_adam_hparams), f32, ci]
         sigs["elixir_host_adam_step_tiled"] = [vp, vp, vp, vp, i64, ctypes.POINTER(elixir_adam_hparams), f32, ci]
         sigs["elixir_copy_h2d_async"] = [vp, vp, sz, vp]
@@ -196,6 +201,23 @@ def elixir_layout_plan(numel: Sequence[int], chunk_elems: int, policy: int = ELI
     _check(lib().elixir_layout_plan(nm, T, chunk_elems, policy, align_elems, cid, off, ctypes.byref(n_chunks), valid,
                                     n_chunks.value))
     return list(cid[:T]), list(off[:T]), list(valid[:n_chunks.value])
+
+
+# --------------------------------------------------------------------------- placement of the chunk buffers
+
+ELIXIR_ARENA_NEAR, ELIXIR_ARENA_FAR = 0, 1
+ELIXIR_ARENA_GAP_BYTES = (4 << 20) + 8192
+
+
+def elixir_arena_plan(n_chunks: int, arrays):
+    """arrays: [(bytes, count, region)].  Returns (offsets[c][k], (region 0 bytes, region 1 bytes)); k counts the arrays
+    of a chunk in the order given, an array with count > 1 taking `count` consecutive k."""
+    arr = (elixir_arena_array * max(len(arrays), 1))(*[elixir_arena_array(int(b), int(n), int(r)) for b, n, r in arrays])
+    K = sum(int(n) for _, n, _ in arrays)
+    off = (ctypes.c_int64 * max(n_chunks * K, 1))()
+    region = (ctypes.c_int64 * 2)()
+    _check(lib().elixir_arena_plan(n_chunks, arr, len(arrays), off, n_chunks * K, region))
+    return [list(off[c * K:(c + 1) * K]) for c in range(n_chunks)], (region[0], region[1])
 
 
 # --------------------------------------------------------------------------- pack / unpack

@@ -8,7 +8,7 @@ _PKG = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(_PKG, "csrc")
 LIB = os.path.join(_PKG, "libelixir_chunk.so")
 SOURCES = ["ctx.cpp", "layout.cpp", "offload.cpp", "pack.hip", "reduce.hip", "norm.hip", "adam.hip"]
-HOST_SOURCES = ["host_adam.cpp", "benefit.cpp", "rcache_sim.cpp"]   # plain C++ (x86 intrinsics, threads): compiled by g++, linked into the same library
+HOST_SOURCES = ["host_adam.cpp", "benefit.cpp", "rcache_sim.cpp", "arena.cpp"]   # plain C++ (x86 intrinsics, threads): compiled by g++, linked into the same library
 
 # -ffp-contract=off: fused multiply-adds appear only where the source asks for them, so the
 #   separately rounded multiply/add of the gradient reduction stay separate.

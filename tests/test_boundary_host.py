@@ -154,3 +154,47 @@ def test_binding_refuses_strided_tensors():
     hp = ex.make_hparams(1e-4, 0.9, 0.999, 1e-8, 0.01, 1)
     with pytest.raises(ValueError):
         ex.elixir_chunk_adam_step(t[:, 0], t[:, 1], t[:, 2], t[:, 3], None, None, 8, hp, None, 0)
+
+
+# --------------------------------------------------------------------------- placement of the chunk buffers
+
+def test_arena_plan_offsets():
+    GAP, GRAIN = ex.ELIXIR_ARENA_GAP_BYTES, 8192
+    slot = lambda b: -(-b // GRAIN) * GRAIN + GAP
+    # per chunk: one optimizer chunk of 1,000,000 bytes, three gradient sets of 12,345 bytes (near), one parameter copy (far)
+    arrays = [(1_000_000, 1, ex.ELIXIR_ARENA_NEAR), (12_345, 3, ex.ELIXIR_ARENA_NEAR), (500_000, 1, ex.ELIXIR_ARENA_FAR)]
+    off, (near, far) = ex.elixir_arena_plan(4, arrays)
+    group = slot(1_000_000) + 3 * slot(12_345)
+    assert near == 4 * group and far == 4 * slot(500_000)
+    for c in range(4):
+        assert off[c] == [c * group, c * group + slot(1_000_000), c * group + slot(1_000_000) + slot(12_345),
+                          c * group + slot(1_000_000) + 2 * slot(12_345), c * slot(500_000)]
+    # invariants on a random description: aligned, inside the region, disjoint, every array followed by the gap
+    rng = np.random.default_rng(8)
+    for _ in range(50):
+        arrays = [(int(rng.integers(0, 1 << 28)), int(rng.integers(0, 4)), int(rng.integers(0, 2))) for _ in range(rng.integers(0, 6))]
+        n_chunks = int(rng.integers(0, 7))
+        off, region = ex.elixir_arena_plan(n_chunks, arrays)
+        sizes = [b for b, n, r in arrays for _ in range(n)]
+        regs = [r for b, n, r in arrays for _ in range(n)]
+        for r in (0, 1):
+            spans = sorted((off[c][k], sizes[k]) for c in range(n_chunks) for k in range(len(sizes)) if regs[k] == r)
+            for (a, sa), (b, _) in zip(spans, spans[1:]):
+                assert a + sa + GAP <= b
+            assert all(a % GRAIN == 0 for a, _ in spans)
+            assert (spans[-1][0] + spans[-1][1] + GAP <= region[r] + GRAIN) if spans else region[r] == 0
+        # arrays whose sizes are equal never start a multiple of 1 MiB apart within a chunk's group
+        for c in range(n_chunks):
+            near_k = [k for k in range(len(sizes)) if regs[k] == 0]
+            for i, j in zip(near_k, near_k[1:]):
+                if sizes[i] % (1 << 20) == 0:
+                    assert (off[c][j] - off[c][i]) % (1 << 20) != 0
+    with pytest.raises(ex.ElixirError) as e:
+        ex.elixir_arena_plan(2, [(16, 1, 7)])
+    assert e.value.code == ex.ELIXIR_EINVAL
+    with pytest.raises(ex.ElixirError) as e:
+        ex.elixir_arena_plan(-1, [(16, 1, 0)])
+    assert e.value.code == ex.ELIXIR_EINVAL
+    region = (ctypes.c_int64 * 2)()
+    arr = (ex.elixir_arena_array * 1)(ex.elixir_arena_array(100, 2, 0))
+    assert ex.lib().elixir_arena_plan(3, arr, 1, None, 0, region) == ex.ELIXIR_ECAP and region[0] == 6 * slot(100)   # sizes first, offsets later
