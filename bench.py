@@ -47,29 +47,28 @@ def chunk_buffers(torch, dev, nch, C, n32=3):
     return state, g16, o16, (flat32, flat16)
 
 
-def chunk_groups(torch, dev, nch, parts):
-    """One allocation holding, chunk after chunk, a group of arrays: parts = [(name, dtype, numel, count)], every array
-    followed by the stagger gap.  Returns ({name: [per chunk: tensor, or list of `count` tensors]}, the allocation).
+def chunk_groups(torch, dev, nch, parts, far=False):
+    """The arrays of nch chunks carved out of one allocation at the offsets elixir_arena_plan gives: parts =
+    [(name, dtype, numel, count)], chunk after chunk, array after array, every array followed by the stagger gap.
+    Returns ({name: [per chunk: tensor, or list of `count` tensors]}, the allocation).  far=True: the arrays are the
+    write-only ones (parameter copies), which the plan puts into a region of their own; the caller allocates that region
+    away from the others (out_of_the_way).
 
-    Why groups: device memory on this part behaves as a few classes of large address ranges (32 GiB granularity; which
-    range belongs to which class moves with the allocation: --workload placement scans it).  Measured on whole 64Mi
-    chunks: the AdamW launch takes 266-272 us when the gradient array lies in the class of the optimizer chunk and
-    280-283 us when it does not; the accumulate pass of the reduction 99-102 us against 106-109 us for its bf16 source; a
-    write-only array (the parameter copy) in the optimizer chunk's class costs 2% instead.  Arrays that are read together
-    are therefore allocated side by side, the parameter copies elsewhere (out_of_the_way)."""
-    import numpy as np
+    Why: device memory on this part behaves as a few classes of large address ranges.  Measured on whole 64Mi-element
+    launches: the AdamW launch takes 266-272 us when the gradient array lies next to the optimizer chunk and 280-283 us
+    when it lies tens of GiB away; the accumulate pass of the reduction 99-102 us against 106-109 us for its bf16
+    source; a write-only array next to the optimizer chunk costs 2% instead."""
+    import paper_2212_05339_amd as ex
     esz = {torch.float32: 4, torch.int16: 2}
-    sizes = [(name, dt, n, cnt, -(-(n * esz[dt]) // 8192) * 8192 + STAGGER_BYTES) for name, dt, n, cnt in parts]
-    group = sum(sz * cnt for *_, cnt, sz in sizes)
-    arena = torch.zeros(nch * group, dtype=torch.uint8, device=dev)
+    region = ex.ELIXIR_ARENA_FAR if far else ex.ELIXIR_ARENA_NEAR
+    offsets, region_bytes = ex.elixir_arena_plan(nch, [(n * esz[dt], cnt, region) for _, dt, n, cnt in parts])
+    arena = torch.zeros(region_bytes[region], dtype=torch.uint8, device=dev)
     out = {name: [] for name, *_ in parts}
     for c in range(nch):
-        off = c * group
-        for name, dt, n, cnt, sz in sizes:
-            views = []
-            for _ in range(cnt):
-                views.append(arena[off: off + n * esz[dt]].view(dt))
-                off += sz
+        k = 0
+        for name, dt, n, cnt in parts:
+            views = [arena[offsets[c][k + j]: offsets[c][k + j] + n * esz[dt]].view(dt) for j in range(cnt)]
+            k += cnt
             out[name].append(views if cnt > 1 else views[0])
     return out, arena
 
@@ -85,12 +84,19 @@ def out_of_the_way(torch, dev, nbytes_needed, make):
     return res
 
 
+SINK = None     # a list while the default run collects the lines of the other configurations, else lines are printed
+
+
 def emit(line):
-    """Prints one JSON line; the keys every line of this program carries get their common values where a workload did not
-    set them (one GPU, larger is better, nothing of the paper to compare with, synthetic inputs)."""
+    """Prints one JSON line (or hands it to the collecting run); the keys every line of this program carries get their
+    common values where a workload did not set them (one GPU, larger is better, nothing of the paper to compare with,
+    synthetic inputs)."""
     for key, val in (("n_gpus", 1), ("higher_is_better", True), ("scaling", "weak"), ("vs_baseline", None), ("data", "synthetic")):
         line.setdefault(key, val)
-    print(json.dumps(line), flush=True)
+    if SINK is not None:
+        SINK.append(line)
+    else:
+        print(json.dumps(line), flush=True)
 
 
 def parse():
@@ -99,7 +105,7 @@ def parse():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="gpt2_1p5b",
-                    help="gpt2_1p5b (default, the benchmark line), tiny, sweep (chunk sizes 8Mi..256Mi), gpt2_6b_clip, gpt2_20b_offload, gpt2_20b_hybrid (CPU update + streaming), placement (launch times against where the operands lie)")
+                    help="gpt2_1p5b (default, the benchmark line), tiny, sweep (chunk sizes 8Mi..256Mi), gpt2_6b_clip, gpt2_20b_offload, gpt2_20b_hybrid (CPU update + streaming), tensor_lists (pack / unpack / reduction over the 580 tensors of the 1.5B set)")
     ap.add_argument("--host-threads", type=int, default=0, help="gpt2_20b_hybrid: threads of the CPU update (default: all cores)")
     ap.add_argument("--host-chunks", type=int, default=0, help="gpt2_20b_offload: allocate only about this many host-resident chunks")
     ap.add_argument("--multi", action="store_true",
@@ -125,6 +131,8 @@ def parse():
                     help="optimizer chunk as one buffer of interleaved [master|m|v] tiles (default) or as three arrays")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-rows", action="store_true", help="skip the per-row side measurements")
+    ap.add_argument("--no-configs", action="store_true", help="gpt2_1p5b: skip the short runs of the other benchmark configurations "
+                                                               "(tiny, sweep, 6B accumulate + clip, 20B offload mix) that fill rows.config_*")
     return ap.parse_args()
 
 
@@ -384,7 +392,7 @@ def run_sweep(args, torch, ex, gen):
                 del state, grads, out, keep
                 torch.cuda.empty_cache()
                 grads = groups["grad"]
-                out_far = out_of_the_way(torch, dev, nch * (2 * C + STAGGER_BYTES), lambda: chunk_groups(torch, dev, nch, [("out", torch.int16, C, 1)]))
+                out_far = out_of_the_way(torch, dev, nch * (2 * C + STAGGER_BYTES), lambda: chunk_groups(torch, dev, nch, [("out", torch.int16, C, 1)], far=True))
                 out, keep, state = out_far[0]["out"], out_far[1], None
 
             def step():
@@ -461,7 +469,7 @@ def run_clip(args, torch, ex, gen):
             ex.elixir_state_tile(tiled[c], scratch[0], scratch[1], scratch[2], C)
         torch.cuda.synchronize()
         del scratch
-        out_far = out_of_the_way(torch, dev, nch * (2 * C + STAGGER_BYTES), lambda: chunk_groups(torch, dev, nch, [("out", torch.int16, C, 1)]))
+        out_far = out_of_the_way(torch, dev, nch * (2 * C + STAGGER_BYTES), lambda: chunk_groups(torch, dev, nch, [("out", torch.int16, C, 1)], far=True))
         out, _keep_o = out_far[0]["out"], out_far[1]
     else:
         state, _unused16, out, _keep = chunk_buffers(torch, dev, nch, C, n32=4)     # [master | m | v | fp32 gradient chunk]
@@ -867,45 +875,158 @@ def run_hybrid(args, torch, ex, gen):
         ex.elixir_ctx_destroy(ctx)
 
 
-def run_placement(args, torch, ex, gen):
-    """Where arrays lie relative to each other: launch times of the tiled AdamW update and of the accumulate pass of the
-    reduction (whole 64Mi-element launches) while one operand is moved through a single 240 GiB allocation in 8 GiB steps.
-    The evidence behind chunk_groups(); prints one JSON line."""
+def run_tensor_lists(args, torch, ex, gen):
+    """Pack / unpack and the gradient reduction over the REAL tensor list of the 1.5B set (580 tensors, 581 pieces in 26
+    chunks of 64Mi elements, next-fit): what a trainer calls when gradients arrive tensor by tensor and when parameters
+    are packed at set-up.  Each is timed next to the same bytes moved as whole chunks (one slice per chunk), which is the
+    ceiling the tensor list can reach.  One JSON line."""
+    cfg = gen.CONFIGS["gpt2_1p5b"]
     dev = torch.device("cuda:0")
-    GiB, TOT, C = 1 << 30, 240, 64 * gen.Mi
-    arena = torch.zeros(TOT * GiB, dtype=torch.uint8, device=dev)
-    base = arena.data_ptr()
+    C = cfg.chunk_elems
+    numels = cfg.numels()
+    cid, off, valid = ex.elixir_layout_plan(numels, C, ex.ELIXIR_LAYOUT_NEXT_FIT, 1)
+    nch = len(valid)
     stream = torch.cuda.Stream()
     sh = stream.cuda_stream
-    hp = ex.make_hparams(1e-4, 0.9, 0.999, 1e-8, 0.01, 1)
+    # per chunk, side by side: the fp32 chunk, an fp32 array and a bf16 array of the same length holding the tensors' data
+    groups, _keep = chunk_groups(torch, dev, nch, [("chunk", torch.float32, C, 1), ("t32", torch.float32, C, 1), ("t16", torch.int16, C, 1),
+                                                   ("c16", torch.int16, C, 1)])
+    gkey = gen.stream_key(gen.BASE_SEED, gen.TAG_GRAD, 1, 0, cfg.cfg_id)
+    for c in range(nch):
+        gen.fill_bf16_device(groups["t16"][c].data_ptr(), valid[c], gkey, c * C, cfg.grad_std, cfg.grad_zero_pct)
+        gen.fill_f32_device(groups["t32"][c].data_ptr(), valid[c], gkey, c * C, cfg.param_std)
+    torch.cuda.synchronize()
+    # the pieces: (chunk, offset, length); the data of a tensor lies in t32 / t16 at its chunk offset
+    pieces = []
+    for i, n in enumerate(numels):
+        c, o, left = cid[i], off[i], n
+        while left > 0:
+            take = min(left, C - o)
+            pieces.append((c, o, take))
+            left, c, o = left - take, c + 1, 0
+    by_chunk = [[p for p in pieces if p[0] == c] for c in range(nch)]
+    n_valid = sum(valid)
+    d32 = [groups["chunk"][c][o:o + n] for c, o, n in pieces]
+    s16 = [groups["t16"][c][o:o + n] for c, o, n in pieces]
+    p_n = [n for _, _, n in pieces]
+    reps = max(3, args.steps)
 
-    def us(fn):
-        fn()
-        torch.cuda.synchronize()
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        e0.record(stream)
-        for _ in range(3):
-            fn()
-        e1.record(stream)
-        torch.cuda.synchronize()
-        return round(e0.elapsed_time(e1) / 3 * 1e3, 1)
+    def t(fn):
+        return _event_time(torch, stream, fn, reps, 2)[1]
 
-    def adam(state_gib, grad_gib, out_gib):
-        return us(lambda: ex.elixir_chunk_adam_step_tiled_lp(base + int(state_gib * GiB), None, base + int(grad_gib * GiB),
-                                                             base + int(out_gib * GiB), ex.ELIXIR_LOWP_BF16, C, hp, None, None, sh))
+    def reduce_list(acc):
+        ex.elixir_grad_reduce_multi_lp(d32, s16, p_n, ex.ELIXIR_LOWP_BF16, 0.25, acc, sh)
 
-    def accumulate(dst_gib, src_gib):
-        return us(lambda: ex.elixir_grad_reduce_into_chunk(base + int(dst_gib * GiB), 0, base + int(src_gib * GiB), C, 0.25, True, sh))
+    def reduce_chunks(acc):
+        for c in range(nch):
+            ex.elixir_grad_reduce_into_chunk(groups["chunk"][c], 0, groups["t16"][c], valid[c], 0.25, acc, sh)
 
-    pos = list(range(8, TOT - 8, 8))
-    emit({
-        "metric": "launch time against operand placement", "unit": "us", "higher_is_better": False, "n_gpus": 1, "data": "zero-filled",
-        "config": {"workload": "placement scan", "allocation_GiB": TOT, "elements_per_launch": C, "positions_GiB": pos},
-        "adam_tiled_state_scanned_grad_at_1_out_at_2_GiB": [adam(s, 1, 2) for s in pos],
-        "adam_tiled_state_at_100_grad_scanned_out_at_2_GiB": [adam(100, g, 2) if abs(g - 100) >= 4 else None for g in pos],
-        "adam_tiled_state_at_100_grad_at_104_out_scanned": [adam(100, 104, o) if abs(o - 102) >= 6 else None for o in pos],
-        "accumulate_dst_scanned_src_at_1_GiB": [accumulate(d, 1) for d in pos],
-        "accumulate_dst_at_100_src_scanned": [accumulate(100, s_) if abs(s_ - 100) >= 4 else None for s_ in pos]})
+    def pack(esz, per_tensor, unpack=False):
+        chunks = groups["chunk"] if esz == 4 else groups["c16"]
+        data = groups["t32"] if esz == 4 else groups["t16"]
+        fn = ex.elixir_chunk_unpack if unpack else ex.elixir_chunk_pack
+        for c in range(nch):
+            segs = by_chunk[c] if per_tensor else [(c, 0, valid[c])]
+            fn(chunks[c], C, esz, [data[c][o:o + n] for _, o, n in segs], [n for _, _, n in segs], [o for _, o, _ in segs], sh)
+
+    res = {}
+    for name, fn, nbytes in (
+            ("reduce_overwrite_tensor_list", lambda: reduce_list(False), 6 * n_valid),
+            ("reduce_overwrite_whole_chunks", lambda: reduce_chunks(False), 6 * n_valid),
+            ("reduce_accumulate_tensor_list", lambda: reduce_list(True), 10 * n_valid),
+            ("reduce_accumulate_whole_chunks", lambda: reduce_chunks(True), 10 * n_valid),
+            ("pack_fp32_tensor_list", lambda: pack(4, True), 8 * n_valid + 4 * (nch * C - n_valid)),
+            ("pack_fp32_whole_chunks", lambda: pack(4, False), 8 * n_valid + 4 * (nch * C - n_valid)),
+            ("unpack_fp32_tensor_list", lambda: pack(4, True, True), 8 * n_valid),
+            ("unpack_fp32_whole_chunks", lambda: pack(4, False, True), 8 * n_valid),
+            ("pack_bf16_tensor_list", lambda: pack(2, True), 4 * n_valid + 2 * (nch * C - n_valid)),
+            ("pack_bf16_whole_chunks", lambda: pack(2, False), 4 * n_valid + 2 * (nch * C - n_valid)),
+            ("unpack_bf16_tensor_list", lambda: pack(2, True, True), 4 * n_valid),
+            ("unpack_bf16_whole_chunks", lambda: pack(2, False, True), 4 * n_valid)):
+        sec = t(fn)
+        res[name] = {"ms": sec * 1e3, "bytes": nbytes, "GB/s": nbytes / sec / 1e9, "frac": nbytes / sec / 1e9 / HBM_PEAK_GBPS}
+    head = res["reduce_overwrite_tensor_list"]
+    emit({"metric": "gradient reduction and pack / unpack over the tensor list of the set", "value": head["GB/s"], "unit": "GB/s",
+          "steps": reps, "warmup": 2, "ms_per_step": head["ms"], "dtype": "f32",
+          "config": {"workload": "gpt2-1.5B/C=64Mi tensor lists", "tensors": len(numels), "pieces": len(pieces), "n_chunks": nch,
+                     "params": n_valid, "placement": "elixir_arena_plan: per chunk [fp32 chunk | fp32 data | bf16 data | bf16 chunk] side by side"},
+          "rows": res,
+          "roofline": {"bound": "hbm", "achieved": head["GB/s"], "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": head["frac"], "traffic": None,
+                       "kernel": "reduce_multi_kernel<false, false> (bf16 -> fp32, overwrite, 6 bytes per element)"}})
+
+
+def naive_allocation_row(args, torch, ex, gen, cfg, valid, lens, dev, stream):
+    """The same step with every array an ordinary allocation of its own (what a caller gets who does not plan where its
+    buffers lie): per chunk one tiled optimizer chunk, two gradient sets, one parameter copy, each from torch's allocator."""
+    C, nch, sh = cfg.chunk_elems, len(valid), stream.cuda_stream
+    tiled = [torch.zeros(ex.elixir_state_tiled_len(C), dtype=torch.float32, device=dev) for _ in range(nch)]
+    out = [torch.zeros(C, dtype=torch.int16, device=dev) for _ in range(nch)]
+    sets = [[torch.zeros(C, dtype=torch.int16, device=dev) for _ in range(nch)] for _ in range(2)]
+    pkey = gen.stream_key(gen.BASE_SEED, gen.TAG_PARAM, cfg=cfg.cfg_id)
+    scratch = torch.zeros(3, C, dtype=torch.float32, device=dev)
+    for c in range(nch):
+        scratch[0].zero_()
+        gen.fill_f32_device(scratch[0].data_ptr(), valid[c], pkey, c * C, cfg.param_std)
+        ex.elixir_state_tile(tiled[c], scratch[0], scratch[1], scratch[2], C)
+        for s_, g in enumerate(sets):
+            gen.fill_bf16_device(g[c].data_ptr(), valid[c], gen.stream_key(gen.BASE_SEED, gen.TAG_GRAD, s_ + 1, 0, cfg.cfg_id), c * C,
+                                 cfg.grad_std, cfg.grad_zero_pct)
+    torch.cuda.synchronize()
+    del scratch
+    step_no = [0]
+
+    def step():
+        step_no[0] += 1
+        hp = ex.make_hparams(cfg.lr, cfg.beta1, cfg.beta2, cfg.eps, cfg.weight_decay, step_no[0])
+        g = sets[step_no[0] % 2]
+        for c in range(nch):
+            ex.elixir_chunk_adam_step_tiled_lp(tiled[c], None, g[c], out[c], ex.ELIXIR_LOWP_BF16, lens[c], hp, None, None, sh)
+
+    wall, ev = _event_time(torch, stream, step, 6, 2)
+    gbs = BYTES_PER_ELEM * sum(lens) / ev / 1e9
+    return {"what": "the benchmark step with one ordinary allocation per array (tiled optimizer chunk, 2 gradient sets, parameter copy per chunk)",
+            "ms_per_step": wall * 1e3, "params_per_s": sum(valid) / wall, "GB/s": gbs, "frac": gbs / HBM_PEAK_GBPS, "steps": 6}
+
+
+def other_configs(args, torch, ex, gen):
+    """Short runs of the other benchmark configurations, after the timed region of the benchmark line and with its buffers
+    freed: the tiny set (one batched launch per step), the chunk-size sweep, gradient accumulation + clipping on the 6B
+    set (one and four micro-batches per reduction pass) and the 20B offload mix (as many host chunks as the box pins).
+    Each is the workload `--workload <name>` runs, with fewer steps; a failure is recorded and does not touch the line."""
+    import gc
+    global SINK
+    rows = {}
+    drop = ("n_gpus", "higher_is_better", "scaling", "vs_baseline", "data", "dtype", "rows", "cpu_baseline")
+
+    def collect(name, fn, **over):
+        global SINK
+        sub = argparse.Namespace(**{**vars(args), **over})
+        SINK = []
+        t0 = time.perf_counter()
+        try:
+            r = fn(sub, torch, ex, gen)
+            if isinstance(r, dict):          # run_headline hands its line back instead of emitting it
+                SINK.append(r)
+            lines = [{k: v for k, v in ln.items() if k not in drop} for ln in SINK]
+            rows[name] = {"lines": lines, "took_s": round(time.perf_counter() - t0, 1)}
+        except Exception as e:  # noqa: BLE001
+            rows[name] = {"error": f"{type(e).__name__}: {e}", "lines": SINK}
+        finally:
+            SINK = None
+            gc.collect()
+            torch.cuda.synchronize()
+            torch.cuda.empty_cache()
+
+    dev = torch.device("cuda:0")
+    collect("config_1_tiny", lambda a, *rest: run_headline(a, *rest, dev), workload="tiny", no_rows=True, multi=True)
+    collect("config_3_sweep", run_sweep, steps=5, warmup=2)
+    collect("config_4_6b_accumulate_clip", run_clip, steps=3, warmup=1, sources_per_pass=1)
+    collect("config_4_6b_accumulate_clip_4_per_pass", run_clip, steps=3, warmup=1, sources_per_pass=4)
+    collect("config_5_20b_offload_mix", run_offload, steps=2, warmup=1)
+    return rows
+
+
+OTHER_WORKLOADS = {"tensor_lists": run_tensor_lists, "sweep": run_sweep, "gpt2_6b_clip": run_clip, "gpt2_20b_offload": run_offload, "gpt2_20b_hybrid": run_hybrid}
 
 
 def main():
@@ -925,10 +1046,26 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs an MI355X"
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
-    if args.workload in ("sweep", "gpt2_6b_clip", "gpt2_20b_offload", "gpt2_20b_hybrid", "placement"):
-        {"sweep": run_sweep, "gpt2_6b_clip": run_clip, "gpt2_20b_offload": run_offload,
-         "gpt2_20b_hybrid": run_hybrid, "placement": run_placement}[args.workload](args, torch, ex, gen)
+    if args.workload in OTHER_WORKLOADS:
+        OTHER_WORKLOADS[args.workload](args, torch, ex, gen)
         return
+    line = run_headline(args, torch, ex, gen, dev)
+    torch.cuda.empty_cache()
+    if args.workload == "gpt2_1p5b" and not args.no_rows and not args.no_configs:
+        line["rows"].update(other_configs(args, torch, ex, gen))
+    if not args.no_cpu_baseline:
+        try:
+            cfg = gen.CONFIGS[args.workload]
+            valid0 = ex.elixir_layout_plan(cfg.numels(), cfg.chunk_elems, ex.ELIXIR_LAYOUT_NEXT_FIT, 1)[2][0]
+            line["cpu_baseline"] = cpu_baseline(cfg, valid0, budget_elems=32 * 64 * gen.Mi)
+        except Exception as e:  # noqa: BLE001
+            line["cpu_baseline_error"] = f"{type(e).__name__}: {e}"
+    emit(line)
+
+
+def run_headline(args, torch, ex, gen, dev):
+    """The benchmark line: K AdamW steps over every chunk of the workload (gpt2_1p5b or tiny), then the side rows on the
+    same buffers.  Returns the line; its buffers are gone when it returns."""
     cfg = gen.CONFIGS[args.workload]
     C = cfg.chunk_elems
     numels = cfg.numels()
@@ -955,7 +1092,7 @@ def main():
         grads = [[(groups["grad"][c][s] if n_sets > 1 else groups["grad"][c]) for c in range(nch)] for s in range(n_sets)]
         for c in range(nch):
             ex.elixir_state_tile(tiled[c], state[c][0], state[c][1], state[c][2], C)
-        out_far = out_of_the_way(torch, dev, nch * (2 * C + STAGGER_BYTES), lambda: chunk_groups(torch, dev, nch, [("out", torch.int16, C, 1)]))
+        out_far = out_of_the_way(torch, dev, nch * (2 * C + STAGGER_BYTES), lambda: chunk_groups(torch, dev, nch, [("out", torch.int16, C, 1)], far=True))
         out, _keep_o = out_far[0]["out"], out_far[1]
     else:
         free_b, _ = torch.cuda.mem_get_info()
@@ -1021,17 +1158,25 @@ def main():
     per_step = sorted(per_step_in_order)
 
     total_params = sum(valid)
-    launches = K * (-(-nch // 64) if args.multi else nch)
-    per_launch_elems = sum(lens) / (-(-nch // 64) if args.multi else nch)      # average over the launches of a step
-    launch_s = ev_ms * 1e-3 / launches                      # average duration of one launch of the AdamW kernel
     bpe = BYTES_PER_ELEM + (2 if clip_ctx is not None else 0)   # with clipping the norm's read of the bf16 gradients is in the region too
-    achieved = bpe * per_launch_elems / launch_s / 1e9          # GB/s, algorithmic bytes of one launch
-    traffic = None
+    if args.multi:
+        # a batched call cuts the chunks into grid rows and may split a step over several launches: the library decides, so
+        # no per-launch figure is derived here; the rate over the whole timed region is the same number
+        launches, launch_s, per_launch_elems = None, None, None
+        achieved = bpe * sum(lens) * K / (ev_ms * 1e-3) / 1e9
+    else:
+        launches = K * nch
+        per_launch_elems = sum(lens) / nch                   # average over the launches of a step
+        launch_s = ev_ms * 1e-3 / launches                   # average duration of one launch of the AdamW kernel
+        achieved = bpe * per_launch_elems / launch_s / 1e9   # GB/s, algorithmic bytes of one launch
+    traffic, traffic_source = None, None
     tpath = os.path.join(ROOT, "profiles", "adam_step_traffic.json")
-    if os.path.exists(tpath) and args.workload == "gpt2_1p5b" and clip_ctx is None:
+    if os.path.exists(tpath) and args.workload == "gpt2_1p5b" and clip_ctx is None and not args.multi:
         with open(tpath) as f:                                 # counters were read on whole-chunk launches: scale to this run's average launch
             t = json.load(f)
             traffic = round(t["hbm_bytes_per_launch"] / t["algorithmic_bytes_per_launch"] * BYTES_PER_ELEM * per_launch_elems)
+            traffic_source = ("not read in this run: the HBM-bytes / algorithmic-bytes ratio of the rocprofv3 counter runs recorded in "
+                              "profiles/adam_step_traffic.json times this run's bytes per launch")
 
     line = {
         "metric": "chunked AdamW params/sec", "value": total_params * K / wall, "unit": "params/s",
@@ -1043,6 +1188,10 @@ def main():
                    "lowp_params": "written over the gradients" if args.params_over_grads else "an array of their own",
                    "clip": (f"max-norm {args.max_norm}: norm over the bf16 gradient chunks every step (2 more bytes per element, "
                             f"inside the timed region; last norm {float(d_nc[0].item()):.4f})") if clip_ctx is not None else "none",
+                   "placement": ("elixir_arena_plan: per chunk [optimizer chunk | gradient sets] side by side in one allocation with "
+                                 "4 MiB + 8 KiB gaps; the parameter copies in a second allocation made behind a temporary spacer of up to "
+                                 "100 GiB (rows.naive_allocation: every array an allocation of its own)") if tiled else
+                                "one allocation per kind of array, 4 MiB + 8 KiB gaps",
                    "grad_sets_resident": n_sets, "hparams": {"lr": cfg.lr, "betas": [cfg.beta1, cfg.beta2],
                                                              "eps": cfg.eps, "weight_decay": cfg.weight_decay}},
         "elements_per_s": sum(lens) * K / wall,
@@ -1050,16 +1199,18 @@ def main():
                            "in_order": [round(x, 4) for x in per_step_in_order], "grad_set_of_first": (W + K) % n_sets,
                            "what": "HIP events around each of K further steps"},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBPS, "traffic": traffic,
+                     "frac": achieved / HBM_PEAK_GBPS, "traffic": traffic, "traffic_source": traffic_source,
                      "kernel": (("adam_multi_kernel<1, 1, true>" if tiled else "adam_multi_kernel<1, 1, false>") if args.multi else
                                 "adam_tiled_kernel<1, 1>" if tiled else "adam_vec_kernel<1, 1>") + " (bf16 gradient in, bf16 copy out)" +
                                (" with the step's sumsq_lowp_kernel<false> shared out over its launches" if clip_ctx is not None else ""),
-                     "bytes_per_launch": bpe * per_launch_elems,
-                     "launch_ms": launch_s * 1e3, "launches_timed": launches,
-                     "timing": "HIP events on the launch stream around the timed region / launches"},
+                     "bytes_per_launch": bpe * per_launch_elems if launches else None,
+                     "launch_ms": launch_s * 1e3 if launches else None, "launches_timed": launches,
+                     "timing": "HIP events on the launch stream around the timed region" + (" / launches" if launches else
+                               " (batched calls: the library chooses the launches, the rate is bytes of the region / its duration)")},
     }
     if clip_ctx is not None:
         ex.elixir_ctx_destroy(clip_ctx)
+    line["rows"] = {}
     if not args.no_rows:
         # the side measurements come after the timed region: if one of them cannot run on this machine (e.g. no pinned memory
         # left for the offload row) the benchmark line above still stands and says what happened
@@ -1069,12 +1220,12 @@ def main():
                 line["roofline"]["frac_of_measured_device_copy"] = achieved / line["rows"]["pack"]["GB/s"]
         except Exception as e:  # noqa: BLE001
             line["rows_error"] = f"{type(e).__name__}: {e}"
-    if not args.no_cpu_baseline:
-        try:
-            line["cpu_baseline"] = cpu_baseline(cfg, valid[0], budget_elems=32 * 64 * gen.Mi)
-        except Exception as e:  # noqa: BLE001
-            line["cpu_baseline_error"] = f"{type(e).__name__}: {e}"
-    emit(line)
+        if args.workload == "gpt2_1p5b" and tiled:
+            try:
+                line["rows"]["naive_allocation"] = naive_allocation_row(args, torch, ex, gen, cfg, valid, lens, dev, stream)
+            except Exception as e:  # noqa: BLE001
+                line["rows"]["naive_allocation"] = {"error": f"{type(e).__name__}: {e}"}
+    return line
 
 
 if __name__ == "__main__":

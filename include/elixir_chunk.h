@@ -272,6 +272,38 @@ int elixir_chunk_adam_step_tiled_multi_lp(int n_chunks, float* const* d_state, c
                                           const int32_t* d_skip, elixir_stream_t stream);
 
 /*
+ * The step constants in device memory, so that one captured HIP graph replays step after step.  The entry points above
+ * take the step number in `hp` and turn it into kernel arguments (lr/(1-beta1^t), 1/sqrt(1-beta2^t)): a graph captured
+ * from them repeats that one step number.  Here the hyper-parameters, the number of steps done and the constants of the
+ * current step live in a 64-byte DEVICE struct:
+ *   elixir_adam_step_state_init    : one-thread kernel; copies hp and sets steps done = hp->step - 1.
+ *   elixir_adam_step_state_advance : one-thread kernel; unless *d_skip (DEVICE flag, may be NULL) is non-zero, counts
+ *       one step on and derives that step's constants in double precision, rounded once to fp32, as the host does
+ *       for the other entry points.  Call it once per step, before the step's updates, on the same stream.
+ *   elixir_chunk_adam_step_tiled_dev / _tiled_multi_dev : elixir_chunk_adam_step_tiled_lp / _tiled_multi_lp with the
+ *       constants read from *d_step_state.  Results are those of the hp entry points for the same step number
+ *       (bit-identical whenever the device's and the host's pow agree to the last bit of the rounded constants).
+ * A graph that holds advance + the step's updates replays as steps t, t+1, t+2, ...; the host can read the struct
+ * back to see the step count.  The struct must be 8-byte aligned.
+ */
+typedef struct {
+    float lr, beta1, beta2, eps, weight_decay;
+    int32_t reserved;
+    int64_t step;     /* steps done so far */
+    float consts[8];  /* constants of the current step, private to the library */
+} elixir_adam_step_state;
+int elixir_adam_step_state_init(elixir_adam_step_state* d_step_state, const elixir_adam_hparams* hp, elixir_stream_t stream);
+int elixir_adam_step_state_advance(elixir_adam_step_state* d_step_state, const int32_t* d_skip, elixir_stream_t stream);
+int elixir_chunk_adam_step_tiled_dev(float* d_state, const float* d_grad_fp32, const uint16_t* d_grad_lowp,
+                                     uint16_t* d_param_lowp, int lowp_format, int64_t n,
+                                     const elixir_adam_step_state* d_step_state, const float* d_grad_scale,
+                                     const int32_t* d_skip, elixir_stream_t stream);
+int elixir_chunk_adam_step_tiled_multi_dev(int n_chunks, float* const* d_state, const float* const* d_grad_fp32,
+                                           const uint16_t* const* d_grad_lowp, uint16_t* const* d_param_lowp, int lowp_format,
+                                           const int64_t* n, const elixir_adam_step_state* d_step_state,
+                                           const float* d_grad_scale, const int32_t* d_skip, elixir_stream_t stream);
+
+/*
  * Placement of the long-lived chunk buffers.  The paper allocates what lives as long as the run (optimizer states,
  * rCache blocks) once, before training (Sec. 3 "Pre-runtime Profiler", finding 2).  On MI355X where those buffers lie
  * relative to each other is worth 2-7% of the update's bandwidth: arrays that one kernel reads together (a chunk's

@@ -31,6 +31,7 @@ EXPORTS = (
     "elixir_grad_reduce_chunk_sumsq", "elixir_chunk_grad_norm_finish", "elixir_grad_reduce_multi_lp", "elixir_chunk_grad_norm_lp", "elixir_grad_reduce_sources_lp", "elixir_grad_reduce_sources_chunk_sumsq",
     "elixir_state_tiled_len", "elixir_state_tile", "elixir_state_untile", "elixir_chunk_adam_step_tiled_lp",
     "elixir_chunk_adam_step_tiled_multi_lp", "elixir_host_adam_step_tiled", "elixir_chunk_grad_norm_noalloc", "elixir_arena_plan",
+    "elixir_adam_step_state_init", "elixir_adam_step_state_advance", "elixir_chunk_adam_step_tiled_dev", "elixir_chunk_adam_step_tiled_multi_dev",
 )
 
 
@@ -89,6 +90,11 @@ def lib() -> ctypes.CDLL:
         }
         sigs["elixir_chunk_grad_norm_noalloc"] = [ctypes.POINTER(vp), pi64, ci, f32, vp, vp, vp]
         sigs["elixir_arena_plan"] = [ci, ctypes.POINTER(elixir_arena_array), ci, pi64, i64, pi64]
+        sigs["elixir_adam_step_state_init"] = [vp, ctypes.POINTER(elixir_adam_hparams), vp]
+        sigs["elixir_adam_step_state_advance"] = [vp, vp, vp]
+        sigs["elixir_chunk_adam_step_tiled_dev"] = [vp, vp, vp, vp, ci, i64, vp, vp, vp, vp]
+        sigs["elixir_chunk_adam_step_tiled_multi_dev"] = [ci, ctypes.POINTER(vp), ctypes.POINTER(vp), ctypes.POINTER(vp), ctypes.POINTER(vp),
+                                                          ci, pi64, vp, vp, vp, vp]
         sigs["elixir_host_adam_step"] = [vp, vp, vp, vp, vp, vp, i64, ctypes.POINTER(elixir_adam_hparams), f32, ci]
         sigs["elixir_host_adam_step_tiled"] = [vp, vp, vp, vp, i64, ctypes.POINTER(elixir_adam_hparams), f32, ci]
         sigs["elixir_copy_h2d_async"] = [vp, vp, sz, vp]
@@ -459,6 +465,32 @@ def elixir_chunk_adam_step_tiled_multi_lp(state, grad_fp32, grad_lowp, param_low
     _check(lib().elixir_chunk_adam_step_tiled_multi_lp(len(state), _ptr_array(state), tab(grad_fp32), tab(grad_lowp), tab(param_lowp),
                                                        lowp_format, _i64_array(n), ctypes.byref(hp), _addr(d_grad_scale), _addr(d_skip),
                                                        _stream(stream)))
+
+
+ADAM_STEP_STATE_BYTES = 64      # elixir_adam_step_state: 5 floats, pad, int64 steps done (byte 24), 8 floats of constants
+ADAM_STEP_STATE_STEP_OFFSET = 24
+
+
+def elixir_adam_step_state_init(d_step_state, hp: elixir_adam_hparams, stream=None) -> None:
+    _check(lib().elixir_adam_step_state_init(_addr(d_step_state), ctypes.byref(hp), _stream(stream)))
+
+
+def elixir_adam_step_state_advance(d_step_state, d_skip=None, stream=None) -> None:
+    _check(lib().elixir_adam_step_state_advance(_addr(d_step_state), _addr(d_skip), _stream(stream)))
+
+
+def elixir_chunk_adam_step_tiled_dev(state, grad_fp32, grad_lowp, param_lowp, lowp_format: int, n: int, d_step_state,
+                                     d_grad_scale=None, d_skip=None, stream=None) -> None:
+    _check(lib().elixir_chunk_adam_step_tiled_dev(_addr(state), _addr(grad_fp32), _addr(grad_lowp), _addr(param_lowp), lowp_format, n,
+                                                  _addr(d_step_state), _addr(d_grad_scale), _addr(d_skip), _stream(stream)))
+
+
+def elixir_chunk_adam_step_tiled_multi_dev(state, grad_fp32, grad_lowp, param_lowp, lowp_format: int, n, d_step_state,
+                                           d_grad_scale=None, d_skip=None, stream=None) -> None:
+    tab = lambda xs: None if xs is None else _ptr_array(xs)
+    _check(lib().elixir_chunk_adam_step_tiled_multi_dev(len(state), _ptr_array(state), tab(grad_fp32), tab(grad_lowp), tab(param_lowp),
+                                                        lowp_format, _i64_array(n), _addr(d_step_state), _addr(d_grad_scale),
+                                                        _addr(d_skip), _stream(stream)))
 
 
 LOSS_SCALE_STATE_BYTES = 16   # float scale, int32 good_steps, int32 skip, float grad_scale

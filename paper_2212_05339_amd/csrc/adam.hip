@@ -1,17 +1,18 @@
 // elixir_chunk_adam_step and its variants: host side of the fused AdamW update.
 #include <math.h>
 
-#include <algorithm>
-#include <vector>
-
 #include "adam_kernel.hpp"
 #include "common.hpp"
+#include "row_plan.hpp"
 
 using namespace elixir;
 
 namespace {
 
-constexpr int64_t kMaxBlocksPerLaunch = 1ll << 30;  // grid.x stays far below its 2^31 limit; longer chunks take several launches
+// HIP refuses a launch whose grid spans 2^32 threads or more in x (workgroups here have 128 or 256 threads): longer
+// chunks take several launches, and a row of a batched launch is at most kMaxRowBlocks workgroups long
+constexpr int64_t kMaxBlocksPerLaunch = ((1ll << 32) - 1) / 256;
+constexpr int64_t kMaxRowBlocks = 1ll << 22;
 
 // One request, after validation: element kinds and raw pointers.
 struct Req {
@@ -192,31 +193,37 @@ extern "C" int elixir_chunk_adam_step(float* d_master, float* d_exp_avg, float* 
 
 namespace {
 
+// d_c: NULL (the constants travel as kernel argument c) or the constants in device memory (c is ignored).
 struct LaunchTiled {
     float* state;
     const Req& r;
     int64_t pairs;
     const AdamConsts& c;
+    const AdamConsts* d_c;
     template <int GRAD, int OUT>
     void operator()() const {
         const int64_t blocks = (pairs + kAdamBlock - 1) / kAdamBlock;
-        hipLaunchKernelGGL((adam_tiled_kernel<GRAD, OUT>), dim3((unsigned)blocks), dim3(kAdamBlock), kAdamLdsBytes, r.s, state, r.g,
-                           OUT != kNone ? r.out : nullptr, pairs, c, r.d_scale, r.d_skip);
+        if (d_c)
+            hipLaunchKernelGGL((adam_tiled_dev_kernel<GRAD, OUT>), dim3((unsigned)blocks), dim3(kAdamBlock), kAdamLdsBytes, r.s, state, r.g,
+                               OUT != kNone ? r.out : nullptr, pairs, d_c, r.d_scale, r.d_skip);
+        else
+            hipLaunchKernelGGL((adam_tiled_kernel<GRAD, OUT>), dim3((unsigned)blocks), dim3(kAdamBlock), kAdamLdsBytes, r.s, state, r.g,
+                               OUT != kNone ? r.out : nullptr, pairs, c, r.d_scale, r.d_skip);
     }
 };
 
-void launch_tiled_scalar(float* state, const Req& r, int64_t first, int64_t end, const AdamConsts& c) {
+void launch_tiled_scalar(float* state, const Req& r, int64_t first, int64_t end, const AdamConsts& c, const AdamConsts* d_c = nullptr) {
     while (first < end) {
         int64_t blocks = (end - first + 255) / 256;
         if (blocks > kMaxBlocksPerLaunch) blocks = kMaxBlocksPerLaunch;
         const int64_t stop = first + blocks * 256 < end ? first + blocks * 256 : end;
         const dim3 grid((unsigned)blocks), block(256);
         if (r.grad_kind == kBF16)
-            hipLaunchKernelGGL(adam_tiled_scalar_kernel<kBF16>, grid, block, 0, r.s, state, r.g, r.out, r.out_kind, first, stop, c, r.d_scale, r.d_skip);
+            hipLaunchKernelGGL(adam_tiled_scalar_kernel<kBF16>, grid, block, 0, r.s, state, r.g, r.out, r.out_kind, first, stop, c, d_c, r.d_scale, r.d_skip);
         else if (r.grad_kind == kF16)
-            hipLaunchKernelGGL(adam_tiled_scalar_kernel<kF16>, grid, block, 0, r.s, state, r.g, r.out, r.out_kind, first, stop, c, r.d_scale, r.d_skip);
+            hipLaunchKernelGGL(adam_tiled_scalar_kernel<kF16>, grid, block, 0, r.s, state, r.g, r.out, r.out_kind, first, stop, c, d_c, r.d_scale, r.d_skip);
         else
-            hipLaunchKernelGGL(adam_tiled_scalar_kernel<kF32>, grid, block, 0, r.s, state, r.g, r.out, r.out_kind, first, stop, c, r.d_scale, r.d_skip);
+            hipLaunchKernelGGL(adam_tiled_scalar_kernel<kF32>, grid, block, 0, r.s, state, r.g, r.out, r.out_kind, first, stop, c, d_c, r.d_scale, r.d_skip);
         first = stop;
     }
 }
@@ -227,13 +234,17 @@ extern "C" int64_t elixir_state_tiled_len(int64_t n) {
     return n <= 0 ? 0 : 3 * kStateTile * ((n + kStateTile - 1) / kStateTile);
 }
 
-extern "C" int elixir_chunk_adam_step_tiled_lp(float* d_state, const float* d_grad_fp32, const uint16_t* d_grad_lowp,
-                                               uint16_t* d_param_lowp, int lowp_format, int64_t n,
-                                               const elixir_adam_hparams* hp, const float* d_grad_scale,
-                                               const int32_t* d_skip, elixir_stream_t stream) {
-    static const char* what = "elixir_chunk_adam_step_tiled";
+namespace {
+// hp (constants derived on the host, travelling as kernel argument) or d_st (constants in device memory): exactly one.
+int tiled_step(const char* what, float* d_state, const float* d_grad_fp32, const uint16_t* d_grad_lowp, uint16_t* d_param_lowp,
+               int lowp_format, int64_t n, const elixir_adam_hparams* hp, const elixir_adam_step_state* d_st,
+               const float* d_grad_scale, const int32_t* d_skip, elixir_stream_t stream) {
     if (n < 0) return fail(ELIXIR_EINVAL, "%s: n=%lld is negative", what, (long long)n);
-    if (const int rc = check_hparams(what, hp)) return rc;
+    if (!d_st) {
+        if (const int rc = check_hparams(what, hp)) return rc;
+    } else if (!aligned(d_st, 8)) {
+        return fail(ELIXIR_EALIGN, "%s: the step state must be 8-byte aligned", what);
+    }
     int lk;
     if (const int rc = lowp_kind(what, lowp_format, &lk)) return rc;
     if (n == 0) return ELIXIR_OK;
@@ -254,21 +265,41 @@ extern "C" int elixir_chunk_adam_step_tiled_lp(float* d_state, const float* d_gr
     r.d_scale = d_grad_scale;
     r.d_skip = d_skip;
     r.s = (hipStream_t)stream;
-    const AdamConsts c = make_consts(hp);
+    const AdamConsts c = d_st ? AdamConsts{} : make_consts(hp);
+    const AdamConsts* d_c = d_st ? reinterpret_cast<const AdamConsts*>(d_st->consts) : nullptr;   // an address, not a read: d_st is device memory
     // the vector kernel wants the gradient on an 8-byte (fp32) or 4-byte (16-bit) boundary and the copy on a 4-byte one;
     // whole chunks are; anything else, and an odd last element, takes the one-element kernel
     const bool vec = phase(r.g, (size_t)grad_elem_size(r.grad_kind)) == 0 && (!r.out || phase(r.out, 2) == 0) && n >= kAdamVec;
     int64_t done = 0;
     if (vec) {
-        dispatch(r.grad_kind, r.out_kind, LaunchTiled{d_state, r, n / kAdamVec, c});
+        dispatch(r.grad_kind, r.out_kind, LaunchTiled{d_state, r, n / kAdamVec, c, d_c});
         ELIXIR_LAUNCH_CHECK("adam_tiled_kernel");
         done = n / kAdamVec * kAdamVec;
     }
     if (done < n) {
-        launch_tiled_scalar(d_state, r, done, n, c);
+        launch_tiled_scalar(d_state, r, done, n, c, d_c);
         ELIXIR_LAUNCH_CHECK("adam_tiled_scalar_kernel");
     }
     return ELIXIR_OK;
+}
+}  // namespace
+
+extern "C" int elixir_chunk_adam_step_tiled_lp(float* d_state, const float* d_grad_fp32, const uint16_t* d_grad_lowp,
+                                               uint16_t* d_param_lowp, int lowp_format, int64_t n,
+                                               const elixir_adam_hparams* hp, const float* d_grad_scale,
+                                               const int32_t* d_skip, elixir_stream_t stream) {
+    return tiled_step("elixir_chunk_adam_step_tiled", d_state, d_grad_fp32, d_grad_lowp, d_param_lowp, lowp_format, n, hp, nullptr,
+                      d_grad_scale, d_skip, stream);
+}
+
+extern "C" int elixir_chunk_adam_step_tiled_dev(float* d_state, const float* d_grad_fp32, const uint16_t* d_grad_lowp,
+                                                uint16_t* d_param_lowp, int lowp_format, int64_t n,
+                                                const elixir_adam_step_state* d_step_state, const float* d_grad_scale,
+                                                const int32_t* d_skip, elixir_stream_t stream) {
+    static const char* what = "elixir_chunk_adam_step_tiled_dev";
+    if (!d_step_state) return fail(ELIXIR_EINVAL, "%s: d_step_state is NULL", what);
+    return tiled_step(what, d_state, d_grad_fp32, d_grad_lowp, d_param_lowp, lowp_format, n, nullptr, d_step_state, d_grad_scale,
+                      d_skip, stream);
 }
 
 namespace {
@@ -342,13 +373,15 @@ struct LaunchMulti {
     const AdamMultiTable& tab;
     dim3 grid;
     const AdamConsts& c;
+    const AdamConsts* d_c;  // tiled only: the constants in device memory, taken instead of c
     const float* d_scale;
     const int32_t* d_skip;
     hipStream_t s;
     bool tiled;
     template <int GRAD, int OUT>
     void operator()() const {
-        if (tiled) hipLaunchKernelGGL((adam_multi_kernel<GRAD, OUT, true>), grid, dim3(kAdamBlock), kAdamLdsBytes, s, tab, c, d_scale, d_skip);
+        if (tiled && d_c) hipLaunchKernelGGL((adam_multi_dev_kernel<GRAD, OUT>), grid, dim3(kAdamBlock), kAdamLdsBytes, s, tab, d_c, d_scale, d_skip);
+        else if (tiled) hipLaunchKernelGGL((adam_multi_kernel<GRAD, OUT, true>), grid, dim3(kAdamBlock), kAdamLdsBytes, s, tab, c, d_scale, d_skip);
         else hipLaunchKernelGGL((adam_multi_kernel<GRAD, OUT, false>), grid, dim3(kAdamBlock), kAdamLdsBytes, s, tab, c, d_scale, d_skip);
     }
 };
@@ -357,9 +390,14 @@ struct LaunchMulti {
 int adam_multi(const char* what, bool tiled, int n_chunks, float* const* d_master, float* const* d_exp_avg,
                float* const* d_exp_avg_sq, const float* const* d_grad_fp32, const uint16_t* const* d_grad_lowp,
                uint16_t* const* d_param_lowp, int lowp_format, const int64_t* n, const elixir_adam_hparams* hp,
-               const float* d_grad_scale, const int32_t* d_skip, elixir_stream_t stream) {
+               const float* d_grad_scale, const int32_t* d_skip, elixir_stream_t stream,
+               const elixir_adam_step_state* d_st = nullptr) {  // d_st (tiled only): constants from device memory, hp unused
     if (n_chunks < 0) return fail(ELIXIR_EINVAL, "%s: n_chunks is negative", what);
-    if (const int rc = check_hparams(what, hp)) return rc;
+    if (!d_st) {
+        if (const int rc = check_hparams(what, hp)) return rc;
+    } else if (!aligned(d_st, 8)) {
+        return fail(ELIXIR_EALIGN, "%s: the step state must be 8-byte aligned", what);
+    }
     int lk;
     if (const int rc = lowp_kind(what, lowp_format, &lk)) return rc;
     if (n_chunks == 0) return ELIXIR_OK;
@@ -382,11 +420,12 @@ int adam_multi(const char* what, bool tiled, int n_chunks, float* const* d_maste
                         tiled ? " (8 bytes for a tiled optimizer chunk)" : "");
         if (d_param_lowp && !d_param_lowp[k]) return fail(ELIXIR_EINVAL, "%s: the parameter-copy pointer of chunk %d is NULL", what, k);
     }
-    const AdamConsts c = make_consts(hp);
+    const AdamConsts c = d_st ? AdamConsts{} : make_consts(hp);
+    const AdamConsts* d_c = d_st ? reinterpret_cast<const AdamConsts*>(d_st->consts) : nullptr;  // an address, not a read
     hipStream_t s = (hipStream_t)stream;
     AdamMultiTable tab;
     int in_table = 0;
-    int64_t max_blocks = 0, used_blocks = 0;  // grid row length; workgroups that have work
+    int64_t max_blocks = 0;  // grid row length
     auto flush = [&]() -> int {
         if (in_table == 0) return ELIXIR_OK;
         for (int j = in_table; j < kAdamMultiMax; ++j) {
@@ -395,10 +434,10 @@ int adam_multi(const char* what, bool tiled, int n_chunks, float* const* d_maste
             tab.out[j] = nullptr;
             tab.n2[j] = 0;
         }
-        dispatch(grad_kind, out_kind, LaunchMulti{tab, dim3((unsigned)max_blocks, (unsigned)in_table), c, d_grad_scale, d_skip, s, tiled});
+        dispatch(grad_kind, out_kind, LaunchMulti{tab, dim3((unsigned)max_blocks, (unsigned)in_table), c, d_c, d_grad_scale, d_skip, s, tiled});
         ELIXIR_LAUNCH_CHECK("adam_multi_kernel");
         in_table = 0;
-        max_blocks = used_blocks = 0;
+        max_blocks = 0;
         return ELIXIR_OK;
     };
     auto make_req = [&](int k) {
@@ -415,100 +454,65 @@ int adam_multi(const char* what, bool tiled, int n_chunks, float* const* d_maste
         r.s = s;
         return r;
     };
-    // chunks that qualify for the vector kernel, longest first, so that a table holds chunks of similar length
-    // (the chunks are independent: their order is free)
-    std::vector<int> order;
-    order.reserve((size_t)n_chunks);
+    // chunks that qualify for the vector kernel go through the row plan (row_plan.hpp): grid rows are equal pieces of
+    // the chunks plus a tail each, tails of similar length share a launch.  With a handful of ragged chunks whole
+    // chunks as rows leave a third of the workgroups without work (seven 4Mi-element chunks of a 21M-parameter set:
+    // 80.6% of the HBM peak, 82.3% with pieces); with hundreds of chunks the rows are the chunks, grouped by length
+    // (the 251 8Mi-element chunks of the 1.5B set: 86.1%).  A piece is a whole number of state tiles, so its base
+    // pointers are those of the chunk shifted.
+    constexpr int64_t kTileBlocks = kStateTile / (kAdamBlock * kAdamVec);
+    auto vec_ok = [&](int k) {
+        if (n[k] < kAdamVec) return false;
+        const Req r = make_req(k);
+        return (tiled || (phase(r.p, 4) == 0 && phase(r.m, 4) == 0 && phase(r.v, 4) == 0)) && phase(r.g, gsz) == 0 &&
+               (!r.out || phase(r.out, 2) == 0);
+    };
     for (int k = 0; k < n_chunks; ++k) {
         if (n[k] == 0) continue;
         const Req r = make_req(k);
-        const bool vec = (tiled || (phase(r.p, 4) == 0 && phase(r.m, 4) == 0 && phase(r.v, 4) == 0)) && phase(r.g, gsz) == 0 &&
-                         (!r.out || phase(r.out, 2) == 0) && n[k] >= kAdamVec;
-        const int64_t nb = (n[k] / kAdamVec + kAdamBlock - 1) / kAdamBlock;
-        if (!vec || nb > kMaxBlocksPerLaunch) {
-            // a slice at an odd offset, or a chunk too long for one grid row: the single-chunk path
+        if (!vec_ok(k)) {  // a slice at an odd offset: the single-chunk path
             if (tiled) {
-                if (nb > kMaxBlocksPerLaunch) return fail(ELIXIR_ECAP, "%s: chunk %d of %lld elements does not fit one launch", what, k, (long long)n[k]);
-                launch_tiled_scalar(r.p, r, 0, n[k], c);
+                launch_tiled_scalar(r.p, r, 0, n[k], c, d_c);
                 ELIXIR_LAUNCH_CHECK("adam_tiled_scalar_kernel");
             } else if (const int rc = run_single(r, n[k], c)) {
                 return rc;
             }
-            continue;
-        }
-        order.push_back(k);
-    }
-    std::stable_sort(order.begin(), order.end(), [&](int a, int b) { return n[a] > n[b]; });
-    // A table row is a chunk, or, when there are few chunks, a piece of one: with a handful of ragged chunks every
-    // grid row is as long as the longest chunk and up to a third of the workgroups find no work (seven 4Mi-element
-    // chunks of a 21M-parameter set: 80.6% of the HBM peak).  Cutting the chunks into pieces of `piece` workgroups,
-    // as long as 64 rows allow, leaves whole pieces of equal length and one shorter piece per chunk.  A piece is a
-    // whole number of state tiles, so its base pointers are those of the chunk shifted.
-    constexpr int64_t kTileBlocks = kStateTile / (kAdamBlock * kAdamVec);
-    int64_t piece = 0;  // 0: rows are whole chunks
-    if (!order.empty() && order.size() * 4 <= (size_t)kAdamMultiMax) {
-        int64_t total = 0;
-        for (const int k : order) total += (n[k] / kAdamVec + kAdamBlock - 1) / kAdamBlock;
-        piece = (total / kAdamMultiMax / kTileBlocks + 1) * kTileBlocks;
-        for (;;) {
-            int64_t rows = 0;
-            for (const int k : order) rows += ((n[k] / kAdamVec + kAdamBlock - 1) / kAdamBlock + piece - 1) / piece;
-            if (rows <= kAdamMultiMax) break;
-            piece += kTileBlocks;
-        }
-    }
-    struct Row {
-        Req r;
-        int64_t pairs;
-    };
-    std::vector<Row> rows;
-    for (const int k : order) {
-        const Req r = make_req(k);
-        const int64_t pairs = n[k] / kAdamVec;
-        const int64_t step = piece ? piece * kAdamBlock : pairs;  // pairs per row
-        for (int64_t first = 0; first < pairs; first += step) {
-            Row row{r, pairs - first < step ? pairs - first : step};
-            const int64_t e0 = first * kAdamVec;  // first element of the row: a multiple of the state tile
-            if (tiled) {
-                row.r.p = r.p + 3 * e0;
-            } else {
-                row.r.p = r.p + e0;
-                row.r.m = r.m + e0;
-                row.r.v = r.v + e0;
-            }
-            row.r.g = (const char*)r.g + e0 * (int64_t)gsz;
-            if (r.out) row.r.out = r.out + e0;
-            rows.push_back(row);
-        }
-        if (n[k] % kAdamVec) {  // the odd last element of this chunk
-            if (tiled) launch_tiled_scalar(r.p, r, pairs * kAdamVec, n[k], c);
-            else launch_scalar(r, pairs * kAdamVec, n[k], c);
+        } else if (n[k] % kAdamVec) {  // the odd last element of this chunk
+            const int64_t done = n[k] / kAdamVec * kAdamVec;
+            if (tiled) launch_tiled_scalar(r.p, r, done, n[k], c, d_c);
+            else launch_scalar(r, done, n[k], c);
             ELIXIR_LAUNCH_CHECK("adam_scalar_kernel");
         }
     }
-    if (piece) std::stable_sort(rows.begin(), rows.end(), [](const Row& a, const Row& b) { return a.pairs > b.pairs; });
-    for (const Row& row : rows) {
-        const int64_t nb = (row.pairs + kAdamBlock - 1) / kAdamBlock;
-        // every row of the grid is as long as the first (longest) one of its table: start a new launch when the
-        // table is full or when the workgroups that would find no work exceed 1/64 of the working ones plus 16K.
-        // Measured: a workgroup that only finds out that it has nothing to do costs about an eighth of a working
-        // one, a further launch about as much as 20K of them; with a quarter allowed the 251 8Mi-element chunks
-        // of the 1.5B set ran at 84.5% of the HBM peak, with this rule at 86.1%
-        const int64_t len = in_table ? max_blocks : nb;
-        const bool wasteful = len * (in_table + 1) - (used_blocks + nb) > (used_blocks + nb) / 64 + 16384;
-        if (in_table == kAdamMultiMax || (in_table > 0 && wasteful))
-            if (const int rc = flush()) return rc;
-        const int j = in_table++;
-        tab.master[j] = row.r.p;
-        tab.exp_avg[j] = row.r.m;
-        tab.exp_avg_sq[j] = row.r.v;
-        tab.grad[j] = row.r.g;
-        tab.out[j] = row.r.out;
-        tab.n2[j] = row.pairs;
-        if (nb > max_blocks) max_blocks = nb;
-        used_blocks += nb;
-    }
-    return flush();
+    struct Rows {
+        decltype(make_req)& req;
+        decltype(flush)& flush_table;
+        AdamMultiTable& tab;
+        int& in_table;
+        int64_t& max_blocks;
+        const int64_t* n;
+        bool tiled;
+        size_t gsz;
+        void add(int k, int64_t first_block, int64_t n_blocks) {
+            const Req r = req(k);
+            const int64_t e0 = first_block * kAdamBlock * kAdamVec;  // first element of the piece: a multiple of the state tile
+            int64_t pairs = n[k] / kAdamVec - first_block * kAdamBlock;
+            if (pairs > n_blocks * kAdamBlock) pairs = n_blocks * kAdamBlock;
+            const int j = in_table++;
+            tab.master[j] = tiled ? r.p + 3 * e0 : r.p + e0;
+            tab.exp_avg[j] = tiled ? nullptr : r.m + e0;
+            tab.exp_avg_sq[j] = tiled ? nullptr : r.v + e0;
+            tab.grad[j] = (const char*)r.g + e0 * (int64_t)gsz;
+            tab.out[j] = r.out ? r.out + e0 : nullptr;
+            tab.n2[j] = pairs;
+        }
+        int flush(int64_t row_blocks) {
+            max_blocks = row_blocks;
+            return flush_table();
+        }
+    } rows{make_req, flush, tab, in_table, max_blocks, n, tiled, gsz};
+    auto blocks_of = [&](int k) -> int64_t { return vec_ok(k) ? (n[k] / kAdamVec + kAdamBlock - 1) / kAdamBlock : 0; };
+    return plan_rows(n_chunks, blocks_of, kTileBlocks, kAdamMultiMax, kMaxRowBlocks / kTileBlocks * kTileBlocks, rows);
 }
 
 }  // namespace
@@ -532,6 +536,79 @@ extern "C" int elixir_chunk_adam_step_tiled_multi_lp(int n_chunks, float* const*
         return adam_multi("elixir_chunk_adam_step_tiled_multi", true, n_chunks, d_state, nullptr, nullptr, d_grad_fp32, d_grad_lowp,
                           d_param_lowp, lowp_format, n, hp, d_grad_scale, d_skip, stream);
     });
+}
+
+extern "C" int elixir_chunk_adam_step_tiled_multi_dev(int n_chunks, float* const* d_state, const float* const* d_grad_fp32,
+                                                      const uint16_t* const* d_grad_lowp, uint16_t* const* d_param_lowp,
+                                                      int lowp_format, const int64_t* n, const elixir_adam_step_state* d_step_state,
+                                                      const float* d_grad_scale, const int32_t* d_skip, elixir_stream_t stream) {
+    if (!d_step_state) return fail(ELIXIR_EINVAL, "elixir_chunk_adam_step_tiled_multi_dev: d_step_state is NULL");
+    return no_throw("elixir_chunk_adam_step_tiled_multi_dev", [&] {
+        return adam_multi("elixir_chunk_adam_step_tiled_multi_dev", true, n_chunks, d_state, nullptr, nullptr, d_grad_fp32, d_grad_lowp,
+                          d_param_lowp, lowp_format, n, nullptr, d_grad_scale, d_skip, stream, d_step_state);
+    });
+}
+
+// ---- the step state in device memory ---------------------------------------------------------------------------
+//
+// A launch whose constants are kernel arguments belongs to one step number; a captured graph of such launches
+// replays that step number for ever.  The step state keeps the hyper-parameters, the count of steps done and the
+// constants of the current step in device memory: elixir_adam_step_state_advance (one thread) counts one step on and
+// derives the constants exactly as make_consts does on the host (double precision, rounded once to fp32), unless the
+// step is being skipped; the *_dev updates read them from there.  Captured together, advance + updates replay as
+// steps t, t+1, t+2, ...
+
+namespace {
+
+__global__ void adam_state_init_kernel(elixir_adam_step_state* st, elixir_adam_hparams hp) {
+    st->lr = hp.lr;
+    st->beta1 = hp.beta1;
+    st->beta2 = hp.beta2;
+    st->eps = hp.eps;
+    st->weight_decay = hp.weight_decay;
+    st->reserved = 0;
+    st->step = hp.step - 1;  // steps done: the first advance makes hp.step the current step
+    for (int k = 0; k < 8; ++k) st->consts[k] = 0.0f;
+}
+
+__global__ void adam_state_advance_kernel(elixir_adam_step_state* st, const int32_t* d_skip) {
+    if (d_skip && *d_skip) return;  // a skipped step does not count
+    const int64_t t = st->step + 1;
+    st->step = t;
+    const double lr = st->lr, b1 = st->beta1, b2 = st->beta2;
+    const double bc1 = 1.0 - pow(b1, (double)t);
+    const double bc2 = 1.0 - pow(b2, (double)t);
+    AdamConsts c;
+    c.lr_wd = (float)(lr * (double)st->weight_decay);
+    c.beta1 = st->beta1;
+    c.omb1 = (float)(1.0 - b1);
+    c.beta2 = st->beta2;
+    c.omb2 = (float)(1.0 - b2);
+    c.step_size = (float)(lr / bc1);
+    c.inv_sqrt_bc2 = (float)(1.0 / sqrt(bc2));
+    c.eps = st->eps;
+    *reinterpret_cast<AdamConsts*>(st->consts) = c;
+}
+
+}  // namespace
+
+extern "C" int elixir_adam_step_state_init(elixir_adam_step_state* d_step_state, const elixir_adam_hparams* hp, elixir_stream_t stream) {
+    static const char* what = "elixir_adam_step_state_init";
+    if (!d_step_state) return fail(ELIXIR_EINVAL, "%s: d_step_state is NULL", what);
+    if (!aligned(d_step_state, 8)) return fail(ELIXIR_EALIGN, "%s: d_step_state must be 8-byte aligned", what);
+    if (const int rc = check_hparams(what, hp)) return rc;
+    hipLaunchKernelGGL(adam_state_init_kernel, dim3(1), dim3(1), 0, (hipStream_t)stream, d_step_state, *hp);
+    ELIXIR_LAUNCH_CHECK("adam_state_init_kernel");
+    return ELIXIR_OK;
+}
+
+extern "C" int elixir_adam_step_state_advance(elixir_adam_step_state* d_step_state, const int32_t* d_skip, elixir_stream_t stream) {
+    static const char* what = "elixir_adam_step_state_advance";
+    if (!d_step_state) return fail(ELIXIR_EINVAL, "%s: d_step_state is NULL", what);
+    if (!aligned(d_step_state, 8) || !aligned(d_skip, 4)) return fail(ELIXIR_EALIGN, "%s: pointer not aligned", what);
+    hipLaunchKernelGGL(adam_state_advance_kernel, dim3(1), dim3(1), 0, (hipStream_t)stream, d_step_state, d_skip);
+    ELIXIR_LAUNCH_CHECK("adam_state_advance_kernel");
+    return ELIXIR_OK;
 }
 
 extern "C" int elixir_chunk_adam_step_multi(int n_chunks, float* const* d_master, float* const* d_exp_avg,

@@ -134,6 +134,22 @@ __device__ __forceinline__ void adam_pair(float* master, float* exp_avg, float* 
         stream_store(lowp_bits<OUT>(p0) | (lowp_bits<OUT>(p1) << 16), reinterpret_cast<uint32_t*>(out) + i);
 }
 
+// A wave of these kernels lives for one pair per lane, so every round trip it makes before its first vector load
+// costs bandwidth.  Left to itself the compiler fetches the length, tests it, and only then fetches the pointers
+// (and later the constants): dependent rounds of scalar loads.  fetch_together() makes the values it is given live at
+// one point, so their loads are issued back to back and waited for once.
+template <typename T>
+__device__ __forceinline__ void keep_scalar(T v) {
+    asm volatile("" ::"s"(v));
+}
+template <typename... T>
+__device__ __forceinline__ void fetch_together(T... v) {
+    (keep_scalar(v), ...);
+}
+__device__ __forceinline__ void fetch_together(const AdamConsts& c) {
+    fetch_together(c.lr_wd, c.beta1, c.omb1, c.beta2, c.omb2, c.step_size, c.inv_sqrt_bc2, c.eps);
+}
+
 // Vector kernel: thread i owns elements 2i, 2i+1.  Host guarantees 8-byte aligned fp32
 // pointers, 4-byte aligned 16-bit pointers, n2 >= 1 complete pairs, gridDim.x * 128 >= n2.
 // d_skip (may be NULL): a device flag; when it is non-zero the launch changes nothing (a step
@@ -145,6 +161,8 @@ __global__ __launch_bounds__(kAdamBlock) void adam_vec_kernel(float* __restrict_
                                                              int64_t n2, AdamConsts c,
                                                              const float* __restrict__ d_grad_scale,
                                                              const int32_t* __restrict__ d_skip) {
+    fetch_together(master, exp_avg, exp_avg_sq, grad, out, n2, d_grad_scale, d_skip);
+    fetch_together(c);
     const int64_t i = (int64_t)blockIdx.x * kAdamBlock + threadIdx.x;
     adam_pair<GRAD, OUT>(master, exp_avg, exp_avg_sq, grad, out, i, n2, c, d_grad_scale, d_skip);
 }
@@ -173,13 +191,21 @@ __global__ __launch_bounds__(kAdamBlock) void adam_multi_kernel(AdamMultiTable t
                                                                const int32_t* __restrict__ d_skip) {
     const int lo = blockIdx.y;
     const int64_t n2 = tab.n2[lo];
+    float* master = tab.master[lo];
+    const void* grad = tab.grad[lo];
+    uint16_t* out = tab.out[lo];
+    fetch_together(n2, master, grad, out, d_grad_scale, d_skip);
+    fetch_together(c);
     const int64_t first = (int64_t)blockIdx.x * kAdamBlock;
     if (first >= n2) return;  // a row past the end of a shorter chunk (uniform per workgroup)
     if constexpr (TILED) {
-        float* base = tab.master[lo] + 2 * kStateTile * (first / (kStateTile / kAdamVec));
-        adam_pair<GRAD, OUT>(base, base + kStateTile, base + 2 * kStateTile, tab.grad[lo], tab.out[lo], first + threadIdx.x, n2, c, d_grad_scale, d_skip);
+        float* base = master + 2 * kStateTile * (first / (kStateTile / kAdamVec));
+        adam_pair<GRAD, OUT>(base, base + kStateTile, base + 2 * kStateTile, grad, out, first + threadIdx.x, n2, c, d_grad_scale, d_skip);
     } else {
-        adam_pair<GRAD, OUT>(tab.master[lo], tab.exp_avg[lo], tab.exp_avg_sq[lo], tab.grad[lo], tab.out[lo], first + threadIdx.x, n2, c, d_grad_scale, d_skip);
+        float* exp_avg = tab.exp_avg[lo];
+        float* exp_avg_sq = tab.exp_avg_sq[lo];
+        fetch_together(exp_avg, exp_avg_sq);
+        adam_pair<GRAD, OUT>(master, exp_avg, exp_avg_sq, grad, out, first + threadIdx.x, n2, c, d_grad_scale, d_skip);
     }
 }
 
@@ -196,19 +222,59 @@ __global__ __launch_bounds__(kAdamBlock) void adam_tiled_kernel(float* __restric
                                                                uint16_t* out, int64_t n2, AdamConsts c,
                                                                const float* __restrict__ d_grad_scale,
                                                                const int32_t* __restrict__ d_skip) {
+    fetch_together(state, grad, out, n2, d_grad_scale, d_skip);
+    fetch_together(c);
     const int64_t first = (int64_t)blockIdx.x * kAdamBlock;   // first pair of this workgroup
     float* base = state + 2 * kStateTile * (first / (kStateTile / kAdamVec));
     adam_pair<GRAD, OUT>(base, base + kStateTile, base + 2 * kStateTile, grad, out, first + threadIdx.x, n2, c, d_grad_scale, d_skip);
 }
 
+// The same two kernels with the step constants read from device memory instead of the kernel arguments: the step
+// number is then not part of the launch, so one captured graph can be replayed for step after step (a one-thread
+// kernel advances the step counter and derives the constants, see adam.hip).  d_c is uniform: the constants arrive
+// through scalar loads that are issued next to the kernel-argument loads and waited for only after the vector loads
+// of the update are in flight.
+static_assert(sizeof(AdamConsts) == sizeof(((elixir_adam_step_state*)nullptr)->consts), "the step state holds one AdamConsts");
+
+template <int GRAD, int OUT>
+__global__ __launch_bounds__(kAdamBlock) void adam_tiled_dev_kernel(float* __restrict__ state, const void* grad, uint16_t* out, int64_t n2,
+                                                                   const AdamConsts* __restrict__ d_c,
+                                                                   const float* __restrict__ d_grad_scale,
+                                                                   const int32_t* __restrict__ d_skip) {
+    fetch_together(state, grad, out, n2, d_c, d_grad_scale, d_skip);
+    const AdamConsts c = *d_c;
+    const int64_t first = (int64_t)blockIdx.x * kAdamBlock;
+    float* base = state + 2 * kStateTile * (first / (kStateTile / kAdamVec));
+    adam_pair<GRAD, OUT>(base, base + kStateTile, base + 2 * kStateTile, grad, out, first + threadIdx.x, n2, c, d_grad_scale, d_skip);
+}
+
+template <int GRAD, int OUT>
+__global__ __launch_bounds__(kAdamBlock) void adam_multi_dev_kernel(AdamMultiTable tab, const AdamConsts* __restrict__ d_c,
+                                                                   const float* __restrict__ d_grad_scale,
+                                                                   const int32_t* __restrict__ d_skip) {
+    const int lo = blockIdx.y;
+    const int64_t n2 = tab.n2[lo];
+    float* master = tab.master[lo];
+    const void* grad = tab.grad[lo];
+    uint16_t* out = tab.out[lo];
+    fetch_together(n2, master, grad, out, d_c, d_grad_scale, d_skip);
+    const int64_t first = (int64_t)blockIdx.x * kAdamBlock;
+    if (first >= n2) return;
+    const AdamConsts c = *d_c;
+    float* base = master + 2 * kStateTile * (first / (kStateTile / kAdamVec));
+    adam_pair<GRAD, OUT>(base, base + kStateTile, base + 2 * kStateTile, grad, out, first + threadIdx.x, n2, c, d_grad_scale, d_skip);
+}
+
 // Elements [first, n) of a tiled optimizer chunk, one element per thread, any alignment of grad / out.
+// d_c (may be NULL): the step constants in device memory, taken instead of c.
 template <int GRAD>
 __global__ __launch_bounds__(256) void adam_tiled_scalar_kernel(float* state, const void* grad, uint16_t* out, int out_kind,
-                                                               int64_t first, int64_t n, AdamConsts c, const float* d_grad_scale,
-                                                               const int32_t* d_skip) {
+                                                               int64_t first, int64_t n, AdamConsts c, const AdamConsts* d_c,
+                                                               const float* d_grad_scale, const int32_t* d_skip) {
     const int64_t k = first + (int64_t)blockIdx.x * 256 + threadIdx.x;
     if (k >= n) return;
     if (d_skip && *d_skip) return;
+    if (d_c) c = *d_c;
     float* P = state + k + 2 * kStateTile * (k / kStateTile);
     float g = load_grad1<GRAD>(grad, k);
     float p = P[0], m = P[kStateTile], v = P[2 * kStateTile];

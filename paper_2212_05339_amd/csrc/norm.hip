@@ -272,7 +272,7 @@ template <bool ACC, bool FP16>
 void launch_fused(float* dst, const SrcTable& srcs, int n_src, int64_t n, int64_t valid, float scale, double* stage, double* slots,
                   hipStream_t s) {
     const int64_t n4 = n / 4;
-    const int64_t blocks = (n4 + kFusedBlock - 1) / kFusedBlock;  // < 2^31: the caller checked chunk_elems
+    const int64_t blocks = (n4 + kFusedBlock - 1) / kFusedBlock;  // blocks * 64 threads < 2^32: the caller checked chunk_elems
     if (blocks > 0) {
         const dim3 grid((unsigned)blocks), block(kFusedBlock);
         switch (n_src) {
@@ -416,7 +416,7 @@ extern "C" int elixir_grad_reduce_sources_chunk_sumsq(elixir_ctx* ctx, int chunk
         return fail(ELIXIR_ECAP, "%s: chunk of %lld elements, context sized for %lld", what, (long long)chunk_elems, (long long)ctx->max_chunk_elems);
     if (lowp_format != ELIXIR_LOWP_BF16 && lowp_format != ELIXIR_LOWP_FP16)
         return fail(ELIXIR_EINVAL, "%s: lowp_format=%d is neither ELIXIR_LOWP_BF16 nor ELIXIR_LOWP_FP16", what, lowp_format);
-    if (chunk_elems / (4 * kFusedBlock) >= 0x7FFFFFFFll)
+    if (chunk_elems / 4 >= (1ll << 32) - kFusedBlock)  // HIP refuses grids of 2^32 threads or more in x
         return fail(ELIXIR_ECAP, "%s: a chunk of %lld elements does not fit one launch", what, (long long)chunk_elems);
     hipStream_t s = (hipStream_t)stream;
     double* slots = ctx->d_partials + (int64_t)chunk_index * kNormBlocksPerChunk;

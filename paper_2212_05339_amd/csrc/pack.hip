@@ -12,8 +12,9 @@
 // are swept as two sequential fronts (measured: 6.8 TB/s; 6.6 TB/s with
 // 256-thread workgroups and 4 KiB tiles; ~5.4 TB/s for hipMemcpy D2D).
 // Traffic: read + write of every byte (write only for gaps).
+#include <stdlib.h>
+
 #include <algorithm>
-#include <vector>
 
 #include "common.hpp"
 
@@ -24,6 +25,7 @@ namespace {
 constexpr int kMaxSeg = 96;
 constexpr int kCopyBlock = 64;                     // one wavefront per workgroup
 constexpr int64_t kTileBytes = kCopyBlock * 16;   // one 128-bit access per lane, one workgroup per tile
+constexpr uint64_t kMaxTilesPerLaunch = ((1ull << 32) - 1) / kCopyBlock;  // HIP refuses grids of 2^32 threads or more in x (64 GiB per launch)
 
 struct SegTable {
     const char* src[kMaxSeg];  // nullptr: fill with zero bits
@@ -80,16 +82,45 @@ struct Seg {
     int64_t bytes;
 };
 
-int launch_segments(const std::vector<Seg>& segs, hipStream_t s, const char* what) {
+// The slice tables of a call: on the stack for up to N entries (a chunk holds a few dozen tensors), on the heap only
+// beyond that, so that the usual call allocates nothing.
+template <typename T, int N>
+struct Table {
+    T local[N];
+    T* p = local;
+    size_t n = 0, cap = N;
+    Table() = default;
+    Table(const Table&) = delete;
+    Table& operator=(const Table&) = delete;
+    ~Table() {
+        if (p != local) free(p);
+    }
+    bool reserve(size_t want) {
+        if (want <= cap) return true;
+        T* q = static_cast<T*>(malloc(want * sizeof(T)));
+        if (!q) return false;
+        for (size_t i = 0; i < n; ++i) q[i] = p[i];
+        if (p != local) free(p);
+        p = q;
+        cap = want;
+        return true;
+    }
+    void push(const T& v) { p[n++] = v; }  // the caller has reserved
+};
+constexpr int kStackSlices = 512;
+typedef Table<int, kStackSlices> OrderTable;
+typedef Table<Seg, 2 * kStackSlices + 1> SegTableHost;
+
+int launch_segments(const SegTableHost& segs, hipStream_t s, const char* what) {
     size_t i = 0;
-    while (i < segs.size()) {
+    while (i < segs.n) {
         SegTable tab;
         tab.n_seg = 0;
         uint64_t tiles = 0;
-        while (i < segs.size() && tab.n_seg < kMaxSeg) {
-            const Seg& g = segs[i];
+        while (i < segs.n && tab.n_seg < kMaxSeg) {
+            const Seg& g = segs.p[i];
             const uint64_t t = (uint64_t)((g.bytes + kTileBytes - 1) / kTileBytes);
-            if (tiles + t > 0x7FFFFFFFull) break;  // keep the grid within 31 bits; the rest goes to the next launch
+            if (tiles + t > kMaxTilesPerLaunch) break;  // the rest goes to the next launch
             tab.src[tab.n_seg] = g.src;
             tab.dst[tab.n_seg] = g.dst;
             tab.bytes[tab.n_seg] = g.bytes;
@@ -109,13 +140,17 @@ int launch_segments(const std::vector<Seg>& segs, hipStream_t s, const char* wha
 
 // Validates the slices and returns their indices ordered by offset (empty slices dropped).
 int check_slices(const char* what, const void* chunk, int64_t chunk_elems, int elem_size, const void* const* tensors,
-                 const int64_t* numel, const int64_t* offset, int T, std::vector<int>* order) {
+                 const int64_t* numel, const int64_t* offset, int T, OrderTable* order) {
     if (chunk_elems < 0 || T < 0) return fail(ELIXIR_EINVAL, "%s: negative chunk_elems or T", what);
     if (elem_size != 2 && elem_size != 4) return fail(ELIXIR_EINVAL, "%s: elem_size=%d, must be 2 or 4", what, elem_size);
+    if ((uint64_t)chunk_elems > kMaxTilesPerLaunch * (uint64_t)kTileBytes / (uint64_t)elem_size)  // no slice or gap can then exceed a launch
+        return fail(ELIXIR_ECAP, "%s: a chunk of %lld elements exceeds the %llu bytes one launch moves", what, (long long)chunk_elems,
+                    (unsigned long long)(kMaxTilesPerLaunch * (uint64_t)kTileBytes));
     if (chunk_elems > 0 && !chunk) return fail(ELIXIR_EINVAL, "%s: chunk is NULL", what);
     if (T > 0 && (!tensors || !numel || !offset)) return fail(ELIXIR_EINVAL, "%s: NULL table", what);
     if (!aligned(chunk, (size_t)elem_size)) return fail(ELIXIR_EALIGN, "%s: chunk not aligned to elem_size", what);
-    order->clear();
+    order->n = 0;
+    if (!order->reserve((size_t)T)) return fail(ELIXIR_EINVAL, "%s: out of host memory for %d slices", what, T);
     for (int i = 0; i < T; ++i) {
         if (numel[i] < 0 || offset[i] < 0 || offset[i] > chunk_elems || numel[i] > chunk_elems - offset[i])
             return fail(ELIXIR_EINVAL, "%s: slice %d (offset %lld, numel %lld) leaves the chunk of %lld elements", what, i,
@@ -123,11 +158,11 @@ int check_slices(const char* what, const void* chunk, int64_t chunk_elems, int e
         if (numel[i] == 0) continue;
         if (!tensors[i]) return fail(ELIXIR_EINVAL, "%s: tensors[%d] is NULL", what, i);
         if (!aligned(tensors[i], (size_t)elem_size)) return fail(ELIXIR_EALIGN, "%s: tensors[%d] not aligned to elem_size", what, i);
-        order->push_back(i);
+        order->push(i);
     }
-    std::sort(order->begin(), order->end(), [&](int a, int b) { return offset[a] < offset[b]; });
-    for (size_t k = 1; k < order->size(); ++k) {
-        const int a = (*order)[k - 1], b = (*order)[k];
+    std::sort(order->p, order->p + order->n, [&](int a, int b) { return offset[a] < offset[b]; });
+    for (size_t k = 1; k < order->n; ++k) {
+        const int a = order->p[k - 1], b = order->p[k];
         if (offset[a] + numel[a] > offset[b])
             return fail(ELIXIR_EINVAL, "%s: slices %d and %d overlap", what, a, b);
     }
@@ -137,20 +172,21 @@ int check_slices(const char* what, const void* chunk, int64_t chunk_elems, int e
 int elixir_chunk_pack_impl(void* d_chunk, int64_t chunk_elems, int elem_size, const void* const* tensors,
                            const int64_t* numel, const int64_t* offset, int T, elixir_stream_t stream) {
     static const char* what = "elixir_chunk_pack";
-    std::vector<int> order;
+    OrderTable order;
     const int rc = check_slices(what, d_chunk, chunk_elems, elem_size, tensors, numel, offset, T, &order);
     if (rc != ELIXIR_OK) return rc;
     char* base = static_cast<char*>(d_chunk);
     const int64_t es = elem_size;
-    std::vector<Seg> segs;
-    segs.reserve(2 * order.size() + 1);
+    SegTableHost segs;
+    if (!segs.reserve(2 * order.n + 1)) return fail(ELIXIR_EINVAL, "%s: out of host memory for %d slices", what, T);
     int64_t pos = 0;  // first element not yet covered
-    for (int i : order) {
-        if (offset[i] > pos) segs.push_back({nullptr, base + pos * es, (offset[i] - pos) * es});
-        segs.push_back({static_cast<const char*>(tensors[i]), base + offset[i] * es, numel[i] * es});
+    for (size_t k = 0; k < order.n; ++k) {
+        const int i = order.p[k];
+        if (offset[i] > pos) segs.push({nullptr, base + pos * es, (offset[i] - pos) * es});
+        segs.push({static_cast<const char*>(tensors[i]), base + offset[i] * es, numel[i] * es});
         pos = offset[i] + numel[i];
     }
-    if (pos < chunk_elems) segs.push_back({nullptr, base + pos * es, (chunk_elems - pos) * es});
+    if (pos < chunk_elems) segs.push({nullptr, base + pos * es, (chunk_elems - pos) * es});
     return launch_segments(segs, (hipStream_t)stream, what);
 }
 }  // namespace
@@ -166,14 +202,17 @@ namespace {
 int elixir_chunk_unpack_impl(const void* d_chunk, int64_t chunk_elems, int elem_size, void* const* tensors,
                              const int64_t* numel, const int64_t* offset, int T, elixir_stream_t stream) {
     static const char* what = "elixir_chunk_unpack";
-    std::vector<int> order;
+    OrderTable order;
     const int rc = check_slices(what, d_chunk, chunk_elems, elem_size, tensors, numel, offset, T, &order);
     if (rc != ELIXIR_OK) return rc;
     const char* base = static_cast<const char*>(d_chunk);
     const int64_t es = elem_size;
-    std::vector<Seg> segs;
-    segs.reserve(order.size());
-    for (int i : order) segs.push_back({base + offset[i] * es, static_cast<char*>(tensors[i]), numel[i] * es});
+    SegTableHost segs;
+    if (!segs.reserve(order.n)) return fail(ELIXIR_EINVAL, "%s: out of host memory for %d slices", what, T);
+    for (size_t k = 0; k < order.n; ++k) {
+        const int i = order.p[k];
+        segs.push({base + offset[i] * es, static_cast<char*>(tensors[i]), numel[i] * es});
+    }
     return launch_segments(segs, (hipStream_t)stream, what);
 }
 }  // namespace

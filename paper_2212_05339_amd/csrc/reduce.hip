@@ -5,11 +5,9 @@
 // floating-point contraction off), so the result does not depend on whether
 // the compiler would have formed a fused multiply-add.
 // Traffic per element: 2 bytes read + 4 written, plus 4 read when accumulating.
-#include <algorithm>
-#include <vector>
-
 #include "common.hpp"
 #include "reduce_elem.hpp"
+#include "row_plan.hpp"
 
 using namespace elixir;
 
@@ -20,7 +18,10 @@ constexpr int kVecBlock = 64;   // one 4-element group per thread, one single-wa
                                 // fronts, with 128-bit accesses at full residency.  Measured on 64Mi elements, 64 / 128 /
                                 // 256 threads per workgroup: overwrite 82.8 / 81.0 / 80.3%, accumulate 83.7 / 83.1 / 80.7%
                                 // of the HBM peak
-constexpr int64_t kMaxBlocksPerLaunch = 1ll << 30;
+// HIP refuses a launch whose grid spans 2^32 threads or more in x: single launches are cut below that, and a row of a
+// batched launch is at most kMaxRowTiles workgroups long (longer tensors become several rows)
+constexpr int64_t kMaxBlocksPerLaunch = ((1ll << 32) - 1) / 256;
+constexpr int64_t kMaxRowTiles = 1ll << 22;
 
 // n4 complete groups of 4 elements, one per thread; NSRC gradient arrays in one pass.
 template <bool ACC, bool FP16, int NSRC>
@@ -39,28 +40,35 @@ __global__ __launch_bounds__(256) void reduce_scalar_kernel(float* dst, const ui
 
 // Many tensors in one launch.  Gradients arrive tensor by tensor, and most tensors of a transformer are small
 // (biases, norms): one launch each leaves the chip idle between launches (the 580 tensors of the 1.5B set take
-// 3.1 ms that way, against 1.4 ms of memory time).  grid = (tiles of the longest tensor in the table, tensors):
-// workgroups are dispatched x-first, so tensor after tensor is swept front to back exactly as by
-// reduce_vec_kernel; workgroups past the end of a shorter tensor exit at once, and the host only puts tensors of
-// similar length into one table.  The table is a kernel argument and blockIdx.y indexes it directly: a wave's
-// kernel-argument loads all go out together.  (Numbering the tiles of all tensors consecutively and searching the
-// table for the owner of a tile costs each of these short-lived waves ~200 scalar instructions or a chain of
+// 2.6 ms that way, against 1.4 ms of memory time).  grid = (row length, rows): a row is a piece of one tensor
+// (row_plan.hpp cuts the tensors into equal pieces plus a tail each and groups rows of similar length), workgroups
+// are dispatched x-first, so piece after piece is swept front to back exactly as by reduce_vec_kernel; workgroups
+// past the end of a shorter row exit at once.  The table is a kernel argument and blockIdx.y indexes it directly: a
+// wave's kernel-argument loads all go out together.  (Numbering the tiles of all tensors consecutively and searching
+// the table for the owner of a tile costs each of these short-lived waves ~200 scalar instructions or a chain of
 // dependent loads; measured, it was no faster than one launch per tensor.)
-constexpr int kReduceMultiMax = 64;
-constexpr int kMultiBlock = 128;  // measured on the 581 tensor pieces of the 1.5B set: 6.0-6.1 TB/s, against 5.97-6.03 TB/s with 64 threads
+constexpr int kReduceMultiMax = 160;  // rows per launch: 160 x 24 bytes of table stay below the 4 KB of kernel arguments
+constexpr int kMultiBlock = 64;       // single-wavefront workgroups, as in reduce_vec_kernel
 struct ReduceMultiTable {
     float* dst[kReduceMultiMax];           // 16-byte aligned
     const uint16_t* src[kReduceMultiMax];  // 8-byte aligned
     int64_t n4[kReduceMultiMax];           // complete groups of 4 elements
 };
+static_assert(sizeof(ReduceMultiTable) + 16 <= 4096, "the table must fit the kernel arguments");
 
 template <bool ACC, bool FP16>
 __global__ __launch_bounds__(kMultiBlock) void reduce_multi_kernel(ReduceMultiTable tab, float scale) {
     const int seg = blockIdx.y;
+    // A wave lives for one group per lane, so what it waits for before its first memory instruction counts: the row's
+    // three table entries and the scale are fetched together, ahead of the test (left to itself the compiler fetches
+    // the length, tests, fetches the source, loads, fetches the destination: three round trips instead of one).
+    float* dst = tab.dst[seg];
+    const uint16_t* src = tab.src[seg];
     const int64_t n4 = tab.n4[seg];
-    if ((int64_t)blockIdx.x * kMultiBlock >= n4) return;  // a row past the end of a shorter tensor (uniform per workgroup)
+    asm volatile("" ::"s"(dst), "s"(src), "s"(n4), "s"(scale));
+    if ((int64_t)blockIdx.x * kMultiBlock >= n4) return;  // a row past the end of a shorter piece (uniform per workgroup)
     const int64_t i = (int64_t)blockIdx.x * kMultiBlock + threadIdx.x;
-    if (i < n4) (void)reduce_group<ACC, FP16, 1>(tab.dst[seg], SrcTable{{tab.src[seg]}}, i, scale);
+    if (i < n4) (void)reduce_group<ACC, FP16, 1>(dst, SrcTable{{src}}, i, scale);
 }
 
 // The vector part of a pass over NSRC sources: n4 groups of 4 elements starting at dst / srcs.
@@ -191,62 +199,57 @@ extern "C" int elixir_grad_reduce_sources_lp(float* d_grad_chunk, int64_t offset
 
 namespace {
 
+// Rows of the batched reduction: a tile is what one workgroup handles (kMultiBlock groups of 4 elements).
 template <bool ACC, bool FP16>
-int reduce_multi(int T, float* const* d_dst, const uint16_t* const* d_src, const int64_t* n, float scale, hipStream_t s) {
-    // tensors that qualify for the vector kernel, longest first: tables then hold tensors of similar length
-    std::vector<int> order;
-    order.reserve((size_t)T);
-    for (int k = 0; k < T; ++k) {
-        if (n[k] == 0) continue;
-        const int64_t tiles = (n[k] / 4 + kMultiBlock - 1) / kMultiBlock;
-        if (!aligned(d_dst[k], 16) || !aligned(d_src[k], 8) || n[k] < 4 || tiles > kMaxBlocksPerLaunch) {
-            // a slice at an odd offset, a handful of elements, or a tensor too long for one grid row: the single path
-            launch_reduce<ACC, FP16>(d_dst[k], d_src[k], n[k], scale, s);
-            ELIXIR_LAUNCH_CHECK("reduce kernel");
-            continue;
-        }
-        order.push_back(k);
-    }
-    std::stable_sort(order.begin(), order.end(), [&](int a, int b) { return n[a] > n[b]; });
+struct ReduceRows {
+    float* const* d_dst;
+    const uint16_t* const* d_src;
+    const int64_t* n;
+    float scale;
+    hipStream_t s;
     ReduceMultiTable tab;
     int in_table = 0;
-    int64_t row = 0, used = 0;  // tiles of the longest tensor in the table; tiles that have work
-    auto flush = [&]() -> int {
-        if (in_table == 0) return ELIXIR_OK;
+
+    void add(int k, int64_t first_tile, int64_t n_tiles) {
+        const int64_t e0 = first_tile * kMultiBlock * 4;             // first element of the piece
+        int64_t n4 = n[k] / 4 - first_tile * kMultiBlock;            // groups from there to the end of the tensor
+        if (n4 > n_tiles * kMultiBlock) n4 = n_tiles * kMultiBlock;
+        tab.dst[in_table] = d_dst[k] + e0;
+        tab.src[in_table] = d_src[k] + e0;
+        tab.n4[in_table] = n4;
+        ++in_table;
+    }
+    int flush(int64_t row_tiles) {
         for (int j = in_table; j < kReduceMultiMax; ++j) {
             tab.dst[j] = nullptr;
             tab.src[j] = nullptr;
             tab.n4[j] = 0;
         }
-        hipLaunchKernelGGL((reduce_multi_kernel<ACC, FP16>), dim3((unsigned)row, (unsigned)in_table), dim3(kMultiBlock), 0, s, tab, scale);
-        ELIXIR_LAUNCH_CHECK("reduce_multi_kernel");
+        hipLaunchKernelGGL((reduce_multi_kernel<ACC, FP16>), dim3((unsigned)row_tiles, (unsigned)in_table), dim3(kMultiBlock), 0, s, tab, scale);
         in_table = 0;
-        row = used = 0;
+        ELIXIR_LAUNCH_CHECK("reduce_multi_kernel");
         return ELIXIR_OK;
-    };
-    for (const int k : order) {
-        const int64_t n4 = n[k] / 4;
-        const int64_t tiles = (n4 + kMultiBlock - 1) / kMultiBlock;
-        // every tensor gets a grid row as long as the first (longest) one: start a new launch when the table is full
-        // or when the workgroups that would find no work exceed 1/64 of the working ones plus 16K (an idle workgroup
-        // costs about an eighth of a working one, a further launch about 20K of them; with a quarter allowed the
-        // tensors of the 1.5B set were reduced at 5.94 TB/s)
-        const int64_t new_row = in_table ? row : tiles;
-        const bool wasteful = new_row * (in_table + 1) - (used + tiles) > (used + tiles) / 64 + 16384;
-        if (in_table == kReduceMultiMax || (in_table > 0 && wasteful))
-            if (const int rc = flush()) return rc;
-        if (in_table == 0) row = tiles;
-        tab.dst[in_table] = d_dst[k];
-        tab.src[in_table] = d_src[k];
-        tab.n4[in_table] = n4;
-        used += tiles;
-        ++in_table;
-        if (n4 * 4 < n[k]) {  // the at most 3 elements after the last complete group
-            hipLaunchKernelGGL((reduce_scalar_kernel<ACC, FP16>), dim3(1), dim3(256), 0, s, d_dst[k], d_src[k], n4 * 4, n[k], scale);
+    }
+};
+
+template <bool ACC, bool FP16>
+int reduce_multi(int T, float* const* d_dst, const uint16_t* const* d_src, const int64_t* n, float scale, hipStream_t s) {
+    // tensors that qualify for the vector kernel go through the row plan; a slice at an odd offset or a handful of
+    // elements takes the single path, and so do the at most 3 elements after a tensor's last complete group
+    auto vec = [&](int k) { return n[k] >= 4 && aligned(d_dst[k], 16) && aligned(d_src[k], 8); };
+    for (int k = 0; k < T; ++k) {
+        if (n[k] == 0) continue;
+        if (!vec(k)) {
+            launch_reduce<ACC, FP16>(d_dst[k], d_src[k], n[k], scale, s);
+            ELIXIR_LAUNCH_CHECK("reduce kernel");
+        } else if (n[k] % 4) {
+            hipLaunchKernelGGL((reduce_scalar_kernel<ACC, FP16>), dim3(1), dim3(256), 0, s, d_dst[k], d_src[k], n[k] / 4 * 4, n[k], scale);
             ELIXIR_LAUNCH_CHECK("reduce_scalar_kernel");
         }
     }
-    return flush();
+    ReduceRows<ACC, FP16> rows{d_dst, d_src, n, scale, s};
+    auto tiles = [&](int k) -> int64_t { return vec(k) ? (n[k] / 4 + kMultiBlock - 1) / kMultiBlock : 0; };
+    return plan_rows(T, tiles, 1, kReduceMultiMax, kMaxRowTiles, rows);
 }
 
 int elixir_grad_reduce_multi_lp_impl(int n_tensors, float* const* d_dst, const uint16_t* const* d_grad_lowp,

@@ -1534,6 +1534,101 @@ def test_whole_step_replays_from_a_hip_graph(ctx):
             assert np.array_equal(a.view(np.uint8), b.view(np.uint8)), f"replay {it} differs from the eager run"
 
 
+def test_one_captured_graph_replays_consecutive_steps():
+    """The step constants come from the step state in device memory, so ONE captured graph (advance + batched update)
+    replays as steps 1, 2, 3: every replay must equal the eager step with that number through the hp entry point bit
+    for bit, the step counter must count, and the result must match three oracle steps."""
+    T = ex.ELIXIR_STATE_TILE
+    lens = [3 * T + 1001, 2 * T, T + 7]                      # an odd length and a one-tile-and-a-bit chunk: vector + one-element kernels
+    nch, C = len(lens), 4 * T
+    p0 = [gen.fill_f32(gen.stream_key(gen.BASE_SEED, gen.TAG_PARAM, cfg=11), c * C, lens[c], 0.02) for c in range(nch)]
+
+    def fresh():
+        st = [torch.zeros(ex.elixir_state_tiled_len(C), dtype=torch.float32, device=DEV) for _ in range(nch)]
+        for c in range(nch):
+            z = torch.zeros(lens[c], device=DEV)
+            ex.elixir_state_tile(st[c], dev(p0[c]), z, z, lens[c])
+        return st
+
+    grads = [torch.zeros(C, dtype=torch.int16, device=DEV) for _ in range(nch)]
+
+    def load_grads(t):
+        for c in range(nch):
+            gen.fill_bf16_device(grads[c].data_ptr(), lens[c], gen.stream_key(gen.BASE_SEED, gen.TAG_GRAD, t, 0, 11), c * C, 1e-3, 1)
+
+    eager, graphed = fresh(), fresh()
+    e_out = [torch.zeros(C, dtype=torch.int16, device=DEV) for _ in range(nch)]
+    g_out = [torch.zeros(C, dtype=torch.int16, device=DEV) for _ in range(nch)]
+    step_state = torch.zeros(ex.ADAM_STEP_STATE_BYTES // 4, dtype=torch.float32, device=DEV)
+    ex.elixir_adam_step_state_init(step_state, hp_struct(1))
+    load_grads(1)
+    sync()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        ex.elixir_adam_step_state_advance(step_state)
+        ex.elixir_chunk_adam_step_tiled_multi_dev(graphed, None, grads, g_out, ex.ELIXIR_LOWP_BF16, lens, step_state)
+    sync()
+    assert int(host(step_state).view(np.int64)[ex.ADAM_STEP_STATE_STEP_OFFSET // 8]) == 0          # capture executes nothing
+    ref = [[p0[c].copy(), np.zeros(lens[c], np.float32), np.zeros(lens[c], np.float32), np.zeros(lens[c], np.uint16)] for c in range(nch)]
+    for t in (1, 2, 3):
+        load_grads(t)                                        # eager work between the replays
+        ex.elixir_chunk_adam_step_tiled_multi_lp(eager, None, grads, e_out, ex.ELIXIR_LOWP_BF16, lens, hp_struct(t))
+        sync()
+        graph.replay()
+        sync()
+        assert int(host(step_state).view(np.int64)[ex.ADAM_STEP_STATE_STEP_OFFSET // 8]) == t
+        for c in range(nch):
+            assert torch.equal(graphed[c].view(torch.int32), eager[c].view(torch.int32)), f"replay {t}, chunk {c}: state differs from the eager step {t}"
+            assert torch.equal(g_out[c], e_out[c]), f"replay {t}, chunk {c}: parameter copy differs"
+            g = host(grads[c], np.uint16)[:lens[c]].copy()
+            orc.chunk_adam_step(ref[c][0], ref[c][1], ref[c][2], g, ref[c][3], step=t, **HP)
+    for c in range(nch):
+        back = [torch.zeros(lens[c], dtype=torch.float32, device=DEV) for _ in range(3)]
+        ex.elixir_state_untile(graphed[c], *back, lens[c])
+        sync()
+        check_adam_close(host(back[0]), host(back[1]), host(back[2]), ref[c][0], ref[c][1], ref[c][2], lr=HP["lr"], gmax=4e-3, steps=3,
+                         what=f"graph chunk {c}")
+        check_bf16_copy(host(g_out[c], np.uint16)[:lens[c]], host(back[0]), ref[c][3], ref[c][0], lr=HP["lr"], steps=3)
+
+
+def test_step_state_single_chunk_entry_point_and_skipped_steps():
+    """elixir_chunk_adam_step_tiled_dev against the hp entry point (fp32 gradients, a gradient scale), and a skipped step:
+    with the skip flag set neither the update nor the step counter moves."""
+    n = 2 * ex.ELIXIR_STATE_TILE + 333
+    p, m, v = _adam_state(n, 91, zero_moments=False)
+    g = gen.fill_f32(gen.stream_key(91, gen.TAG_GRAD, 1), 0, n, 2e-3)
+    a = torch.zeros(ex.elixir_state_tiled_len(n), dtype=torch.float32, device=DEV)
+    b = torch.zeros_like(a)
+    for st in (a, b):
+        ex.elixir_state_tile(st, dev(p), dev(m), dev(v), n)
+    out_a = torch.zeros(n, dtype=torch.int16, device=DEV)
+    out_b = torch.zeros(n, dtype=torch.int16, device=DEV)
+    d_g, d_scale = dev(g), dev(np.array([0.37], np.float32))
+    skip = torch.zeros(1, dtype=torch.int32, device=DEV)
+    step_state = torch.zeros(ex.ADAM_STEP_STATE_BYTES // 4, dtype=torch.float32, device=DEV)
+    ex.elixir_adam_step_state_init(step_state, hp_struct(5))           # the next step is number 5
+    counter = lambda: int(host(step_state).view(np.int64)[ex.ADAM_STEP_STATE_STEP_OFFSET // 8])
+    sync()
+    assert counter() == 4
+    skip.fill_(1)
+    before = a.clone()
+    ex.elixir_adam_step_state_advance(step_state, skip)
+    ex.elixir_chunk_adam_step_tiled_dev(a, d_g, None, out_a, ex.ELIXIR_LOWP_BF16, n, step_state, d_scale, skip)
+    sync()
+    assert counter() == 4 and torch.equal(a.view(torch.int32), before.view(torch.int32)) and not out_a.any()
+    skip.zero_()
+    for t in (5, 6):
+        ex.elixir_adam_step_state_advance(step_state, skip)
+        ex.elixir_chunk_adam_step_tiled_dev(a, d_g, None, out_a, ex.ELIXIR_LOWP_BF16, n, step_state, d_scale, skip)
+        ex.elixir_chunk_adam_step_tiled_lp(b, d_g, None, out_b, ex.ELIXIR_LOWP_BF16, n, hp_struct(t), d_scale, None)
+        sync()
+        assert counter() == t
+        assert torch.equal(a.view(torch.int32), b.view(torch.int32)) and torch.equal(out_a, out_b), f"step {t}"
+    with pytest.raises(ex.ElixirError) as e:
+        ex.elixir_chunk_adam_step_tiled_dev(a, d_g, None, out_a, ex.ELIXIR_LOWP_BF16, n, None)
+    assert e.value.code == ex.ELIXIR_EINVAL
+
+
 # --------------------------------------------------------------------------- reduction fused with the norm
 
 def test_norm_paths_agree_on_huge_and_non_finite_gradients(ctx):
