@@ -21,8 +21,8 @@
  *   - bf16 values are passed as their 16-bit patterns (uint16_t).
  *   - Every GPU operation is enqueued on the caller's stream and returns
  *     without waiting for it; no entry point synchronises the device except
- *     elixir_ctx_destroy (elixir_stream_synchronize and elixir_offload_bind_streams
- *     wait for the streams they are given).  elixir_stream_t is a hipStream_t (NULL = the
+ *     elixir_ctx_destroy (elixir_stream_synchronize waits for the stream it is given; elixir_offload_copy_streams,
+ *     a set-up call, waits for the probes it issues).  elixir_stream_t is a hipStream_t (NULL = the
  *     default stream).  The caller's current device must be the one that owns
  *     the stream and buffers.
  *   - The caller owns every buffer it passes in.  The library owns only what
@@ -353,21 +353,34 @@ int elixir_arena_plan(int n_chunks, const elixir_arena_array* arrays, int n_arra
  *       compute_stream, enqueues the device-to-host copy of `bytes` into
  *       h_block (h_block NULL: no copy, the slot is only released), and marks
  *       the slot free for the next prefetch.
- *   elixir_offload_bind_streams : call once per pair of copy streams, before their first copies and
- *       after registering slots.  The runtime assigns a DMA engine to a stream at its first copy; this
- *       call issues the first copies so that uploads and downloads land on different engines and can
- *       run at the same time, then measures whether they do (*overlapped_out = 1/0, may be NULL; up to
- *       three attempts).  The flag describes the moment of the call: the runtime may move a stream to
- *       another engine later, and pipelines whose bind reported 0 have still reached the bidirectional rate.
- *       It overwrites slot 0, allocates and frees a pinned scratch buffer, and waits for both streams.
+ *   elixir_offload_copy_streams : set-up call; hands out the two copy streams of the pipeline.  They belong to the
+ *       library, one pair per GPU, created by the first call and kept until the process ends (later calls verify the
+ *       pair against their compute_stream and return it again); ctx only names the GPU.  The HIP runtime feeds all
+ *       streams of a process through a few hardware queues (4 by default), and two streams that share one hold each
+ *       other back whenever one of them waits: uploads and downloads then take turns (measured: 28 GB/s each way
+ *       instead of 46-48), or kernels wait for block copies.  Which streams share a queue depends on how many streams
+ *       the process has created, so the call measures it: it creates streams until two of them are seen to run beside
+ *       compute_stream and beside each other (a marker on one stream must complete while a 64 MiB copy is still
+ *       pending on the other), keeps those and destroys the rest; ELIXIR_ESTATE if there are no two among 12
+ *       candidates.  Separate queues are necessary for uploads and downloads to overlap, not sufficient: the DMA
+ *       engines are shared by the whole process, and after a large device allocation has been freed (hipFree of 4 GiB
+ *       or more) an upload and a download issued together were seen to take turns whatever streams carry them, until
+ *       later copy traffic undoes it.  No choice of streams repairs that; *full_duplex_out (may be NULL) reports
+ *       whether an upload and a download issued together overlapped when the call looked (1) or took turns (0).
+ *       A process that wants the full-duplex rate allocates its long-lived buffers once and frees nothing large
+ *       while it streams.  The two streams keep their directions: pass the first wherever this header takes
+ *       h2d_stream and the second wherever it takes d2h_stream.  Allocates and frees 128 MiB of device and of pinned
+ *       memory and waits for its probe copies (about 30 ms).  ELIXIR_TRACE_STREAMS=1 in the environment prints
+ *       what was measured.  Streams of the caller's own making work with the pipeline as well, correctly but with no
+ *       such guarantee.
  * No other call blocks the host.  h_block should be pinned (elixir_host_alloc) for
  * the copies to be asynchronous and at link speed.
  */
 int elixir_host_alloc(void** h_out, size_t bytes);
 int elixir_host_free(void* h_ptr);
 int elixir_offload_register_slots(elixir_ctx* ctx, void* const* d_slots, int n_slots, size_t slot_bytes);
-int elixir_offload_bind_streams(elixir_ctx* ctx, elixir_stream_t h2d_stream, elixir_stream_t d2h_stream,
-                                int* overlapped_out);
+int elixir_offload_copy_streams(elixir_ctx* ctx, elixir_stream_t compute_stream, elixir_stream_t* h2d_out,
+                                elixir_stream_t* d2h_out, int* full_duplex_out);
 int elixir_chunk_prefetch(elixir_ctx* ctx, const void* h_block, size_t bytes, int* slot_out,
                           elixir_stream_t h2d_stream);
 int elixir_chunk_wait_ready(elixir_ctx* ctx, int slot, elixir_stream_t compute_stream);
@@ -457,6 +470,14 @@ int elixir_loss_scale_update(elixir_loss_scale_state* d_state, const float* d_no
 int elixir_host_adam_step(float* h_master, float* h_exp_avg, float* h_exp_avg_sq, const float* h_grad_fp32,
                           const uint16_t* h_grad_bf16, uint16_t* h_param_bf16, int64_t n,
                           const elixir_adam_hparams* hp, float grad_scale, int n_threads);
+/* The same with the low-precision format as an argument (ELIXIR_LOWP_FP16: the paper's own format, IEEE binary16
+ * gradients in, round-to-nearest-even binary16 parameters out, through the CPU's conversion instructions where it
+ * has them); grad_scale carries 1/S under loss scaling.  elixir_host_adam_step is the ELIXIR_LOWP_BF16 case. */
+int elixir_host_adam_step_lp(float* h_master, float* h_exp_avg, float* h_exp_avg_sq, const float* h_grad_fp32,
+                             const uint16_t* h_grad_lowp, uint16_t* h_param_lowp, int lowp_format, int64_t n,
+                             const elixir_adam_hparams* hp, float grad_scale, int n_threads);
+int elixir_host_adam_step_tiled_lp(float* h_state, const float* h_grad_fp32, const uint16_t* h_grad_lowp, uint16_t* h_param_lowp,
+                                   int lowp_format, int64_t n, const elixir_adam_hparams* hp, float grad_scale, int n_threads);
 /* elixir_host_adam_step on a tiled optimizer chunk in host memory (the layout of elixir_state_tile). */
 int elixir_host_adam_step_tiled(float* h_state, const float* h_grad_fp32, const uint16_t* h_grad_bf16, uint16_t* h_param_bf16,
                                 int64_t n, const elixir_adam_hparams* hp, float grad_scale, int n_threads);

@@ -22,7 +22,7 @@ EXPORTS = (
     "elixir_last_error", "elixir_ctx_create", "elixir_ctx_destroy", "elixir_layout_plan", "elixir_chunk_pack",
     "elixir_chunk_unpack", "elixir_grad_reduce_into_chunk", "elixir_chunk_grad_norm", "elixir_chunk_adam_step",
     "elixir_chunk_adam_step_multi",
-    "elixir_host_alloc", "elixir_host_free", "elixir_offload_register_slots", "elixir_offload_bind_streams",
+    "elixir_host_alloc", "elixir_host_free", "elixir_offload_register_slots", "elixir_offload_copy_streams",
     "elixir_chunk_prefetch",
     "elixir_chunk_wait_ready", "elixir_chunk_evict", "elixir_host_adam_step", "elixir_host_adam_isa", "elixir_copy_h2d_async",
     "elixir_copy_d2h_async", "elixir_stream_synchronize", "elixir_offload_benefit", "elixir_offload_plan",
@@ -31,7 +31,7 @@ EXPORTS = (
     "elixir_grad_reduce_chunk_sumsq", "elixir_chunk_grad_norm_finish", "elixir_grad_reduce_multi_lp", "elixir_chunk_grad_norm_lp", "elixir_grad_reduce_sources_lp", "elixir_grad_reduce_sources_chunk_sumsq",
     "elixir_state_tiled_len", "elixir_state_tile", "elixir_state_untile", "elixir_chunk_adam_step_tiled_lp",
     "elixir_chunk_adam_step_tiled_multi_lp", "elixir_host_adam_step_tiled", "elixir_chunk_grad_norm_noalloc", "elixir_arena_plan",
-    "elixir_adam_step_state_init", "elixir_adam_step_state_advance", "elixir_chunk_adam_step_tiled_dev", "elixir_chunk_adam_step_tiled_multi_dev",
+    "elixir_host_adam_step_lp", "elixir_host_adam_step_tiled_lp", "elixir_adam_step_state_init", "elixir_adam_step_state_advance", "elixir_chunk_adam_step_tiled_dev", "elixir_chunk_adam_step_tiled_multi_dev",
 )
 
 
@@ -83,7 +83,7 @@ def lib() -> ctypes.CDLL:
             "elixir_host_alloc": [ctypes.POINTER(vp), sz],
             "elixir_host_free": [vp],
             "elixir_offload_register_slots": [vp, ctypes.POINTER(vp), ci, sz],
-            "elixir_offload_bind_streams": [vp, vp, vp, ctypes.POINTER(ci)],
+            "elixir_offload_copy_streams": [vp, vp, ctypes.POINTER(vp), ctypes.POINTER(vp), ctypes.POINTER(ci)],
             "elixir_chunk_prefetch": [vp, vp, sz, ctypes.POINTER(ci), vp],
             "elixir_chunk_wait_ready": [vp, ci, vp],
             "elixir_chunk_evict": [vp, ci, vp, sz, vp, vp],
@@ -96,6 +96,8 @@ def lib() -> ctypes.CDLL:
         sigs["elixir_chunk_adam_step_tiled_multi_dev"] = [ci, ctypes.POINTER(vp), ctypes.POINTER(vp), ctypes.POINTER(vp), ctypes.POINTER(vp),
                                                           ci, pi64, vp, vp, vp, vp]
         sigs["elixir_host_adam_step"] = [vp, vp, vp, vp, vp, vp, i64, ctypes.POINTER(elixir_adam_hparams), f32, ci]
+        sigs["elixir_host_adam_step_lp"] = [vp, vp, vp, vp, vp, vp, ci, i64, ctypes.POINTER(elixir_adam_hparams), f32, ci]
+        sigs["elixir_host_adam_step_tiled_lp"] = [vp, vp, vp, vp, ci, i64, ctypes.POINTER(elixir_adam_hparams), f32, ci]
         sigs["elixir_host_adam_step_tiled"] = [vp, vp, vp, vp, i64, ctypes.POINTER(elixir_adam_hparams), f32, ci]
         sigs["elixir_copy_h2d_async"] = [vp, vp, sz, vp]
         sigs["elixir_copy_d2h_async"] = [vp, vp, sz, vp]
@@ -305,11 +307,13 @@ def elixir_offload_register_slots(ctx: Ctx, d_slots, slot_bytes: int) -> None:
     _check(lib().elixir_offload_register_slots(ctx.handle, _ptr_array(d_slots), len(d_slots), slot_bytes))
 
 
-def elixir_offload_bind_streams(ctx: Ctx, h2d_stream, d2h_stream) -> bool:
-    """Returns True if uploads and downloads were measured to run concurrently afterwards."""
-    ok = ctypes.c_int(0)
-    _check(lib().elixir_offload_bind_streams(ctx.handle, _stream(h2d_stream), _stream(d2h_stream), ctypes.byref(ok)))
-    return bool(ok.value)
+def elixir_offload_copy_streams(ctx: Ctx, compute_stream=None, with_flag: bool = False):
+    """Returns (h2d, d2h): raw handles of the library's two copy streams, measured to have hardware queues to themselves
+    beside compute_stream.  Pass them as h2d_stream / d2h_stream.  with_flag: (h2d, d2h, full_duplex) -- whether an
+    upload and a download issued together overlapped when the call looked."""
+    up, down, flag = ctypes.c_void_p(), ctypes.c_void_p(), ctypes.c_int(0)
+    _check(lib().elixir_offload_copy_streams(ctx.handle, _stream(compute_stream), ctypes.byref(up), ctypes.byref(down), ctypes.byref(flag)))
+    return (up.value, down.value, bool(flag.value)) if with_flag else (up.value, down.value)
 
 
 def elixir_chunk_prefetch(ctx: Ctx, h_block: int, nbytes: int, h2d_stream) -> int:
@@ -347,6 +351,19 @@ def elixir_host_adam_step_tiled(state, grad_fp32, grad_bf16, param_bf16, n: int,
     """The CPU update on a tiled optimizer chunk in host memory (numpy array or raw address)."""
     _check(lib().elixir_host_adam_step_tiled(_host_addr(state), _host_addr(grad_fp32), _host_addr(grad_bf16), _host_addr(param_bf16), n,
                                              ctypes.byref(hp), grad_scale, n_threads))
+
+
+def elixir_host_adam_step_lp(master, exp_avg, exp_avg_sq, grad_fp32, grad_lowp, param_lowp, lowp_format: int, n: int,
+                             hp: elixir_adam_hparams, grad_scale: float = 1.0, n_threads: int = 0) -> None:
+    _check(lib().elixir_host_adam_step_lp(_host_addr(master), _host_addr(exp_avg), _host_addr(exp_avg_sq), _host_addr(grad_fp32),
+                                          _host_addr(grad_lowp), _host_addr(param_lowp), lowp_format, n, ctypes.byref(hp), grad_scale,
+                                          n_threads))
+
+
+def elixir_host_adam_step_tiled_lp(state, grad_fp32, grad_lowp, param_lowp, lowp_format: int, n: int, hp: elixir_adam_hparams,
+                                   grad_scale: float = 1.0, n_threads: int = 0) -> None:
+    _check(lib().elixir_host_adam_step_tiled_lp(_host_addr(state), _host_addr(grad_fp32), _host_addr(grad_lowp), _host_addr(param_lowp),
+                                                lowp_format, n, ctypes.byref(hp), grad_scale, n_threads))
 
 
 def elixir_host_adam_isa() -> str:

@@ -42,10 +42,54 @@ inline uint16_t f32_to_bf16(float f) {
     return (uint16_t)((u + 0x7FFFu + ((u >> 16) & 1u)) >> 16);
 }
 
+// fp16 (IEEE binary16: 1 sign, 5 exponent, 10 fraction bits) for the scalar path, written out on the bit patterns;
+// the vector paths use the CPU's conversion instructions, which compute the same.  Widening is exact.
+inline float f16_to_f32(uint16_t b) {
+    const uint32_t sign = (uint32_t)(b & 0x8000u) << 16;
+    uint32_t exp = (b >> 10) & 0x1Fu, frac = b & 0x3FFu, u;
+    if (exp == 0x1Fu) {
+        u = sign | 0x7F800000u | (frac << 13);  // Inf, or NaN with its payload
+    } else if (exp != 0) {
+        u = sign | ((exp + 112u) << 23) | (frac << 13);
+    } else if (frac == 0) {
+        u = sign;
+    } else {  // subnormal: frac * 2^-24, normalised
+        int e = 113;
+        while (!(frac & 0x400u)) {
+            frac <<= 1;
+            --e;
+        }
+        u = sign | ((uint32_t)e << 23) | ((frac & 0x3FFu) << 13);
+    }
+    float f;
+    memcpy(&f, &u, 4);
+    return f;
+}
+
+// Narrowing rounds to nearest, ties to even; values beyond the largest finite fp16 become Inf; NaN stays a quiet NaN.
+inline uint16_t f32_to_f16(float f) {
+    uint32_t u;
+    memcpy(&u, &f, 4);
+    const uint16_t sign = (uint16_t)((u >> 16) & 0x8000u);
+    const uint32_t a = u & 0x7FFFFFFFu;
+    if (a > 0x7F800000u) return (uint16_t)(sign | 0x7E00u | ((a >> 13) & 0x3FFu));
+    if (a >= 0x38800000u) {  // at least 2^-14: a normal fp16, unless it rounds up to Inf
+        const uint32_t r = a + 0xFFFu + ((a >> 13) & 1u);
+        const uint32_t h = (r - 0x38000000u) >> 13;
+        return (uint16_t)(sign | (h > 0x7C00u ? 0x7C00u : h));
+    }
+    if (a < 0x33000000u) return sign;  // below 2^-25: rounds to zero (2^-25 itself is a tie and goes to the even 0)
+    const uint32_t m = (a & 0x7FFFFFu) | 0x800000u;
+    const uint32_t shift = 126u - (a >> 23);  // 14 .. 24
+    const uint32_t lsb = (m >> shift) & 1u;
+    return (uint16_t)(sign | ((m + ((1u << (shift - 1)) - 1u) + lsb) >> shift));
+}
+
+template <bool FP16>
 void adam_scalar(float* p, float* m, float* v, const float* g32, const uint16_t* g16, uint16_t* out, int64_t n,
                  const Consts& c) {
     for (int64_t k = 0; k < n; ++k) {
-        const float g = c.grad_scale * (g32 ? g32[k] : bf16_to_f32(g16[k]));
+        const float g = c.grad_scale * (g32 ? g32[k] : FP16 ? f16_to_f32(g16[k]) : bf16_to_f32(g16[k]));
         const float mk = fmaf(c.beta1, m[k], c.omb1 * g);
         const float vk = fmaf(c.beta2, v[k], (c.omb2 * g) * g);
         const float denom = fmaf(sqrtf(vk), c.inv_sqrt_bc2, c.eps);
@@ -54,12 +98,13 @@ void adam_scalar(float* p, float* m, float* v, const float* g32, const uint16_t*
         p[k] = pk;
         m[k] = mk;
         v[k] = vk;
-        if (out) out[k] = f32_to_bf16(pk);
+        if (out) out[k] = FP16 ? f32_to_f16(pk) : f32_to_bf16(pk);
     }
 }
 
-__attribute__((target("avx2,fma"))) void adam_avx2(float* p, float* m, float* v, const float* g32, const uint16_t* g16,
-                                                  uint16_t* out, int64_t n, const Consts& c) {
+template <bool FP16>
+__attribute__((target("avx2,fma,f16c"))) void adam_avx2(float* p, float* m, float* v, const float* g32, const uint16_t* g16,
+                                                       uint16_t* out, int64_t n, const Consts& c) {
     const __m256 b1 = _mm256_set1_ps(c.beta1), o1 = _mm256_set1_ps(c.omb1), b2 = _mm256_set1_ps(c.beta2),
                  o2 = _mm256_set1_ps(c.omb2), ss = _mm256_set1_ps(c.step_size), ib = _mm256_set1_ps(c.inv_sqrt_bc2),
                  eps = _mm256_set1_ps(c.eps), nlw = _mm256_set1_ps(-c.lr_wd), gs = _mm256_set1_ps(c.grad_scale);
@@ -67,6 +112,7 @@ __attribute__((target("avx2,fma"))) void adam_avx2(float* p, float* m, float* v,
     for (; k + 8 <= n; k += 8) {
         __m256 g;
         if (g32) g = _mm256_loadu_ps(g32 + k);
+        else if (FP16) g = _mm256_cvtph_ps(_mm_loadu_si128((const __m128i*)(g16 + k)));
         else g = _mm256_castsi256_ps(_mm256_slli_epi32(_mm256_cvtepu16_epi32(_mm_loadu_si128((const __m128i*)(g16 + k))), 16));
         g = _mm256_mul_ps(gs, g);
         const __m256 pk0 = _mm256_loadu_ps(p + k);
@@ -79,7 +125,9 @@ __attribute__((target("avx2,fma"))) void adam_avx2(float* p, float* m, float* v,
         _mm256_storeu_ps(p + k, pk);
         _mm256_storeu_ps(m + k, mk);
         _mm256_storeu_ps(v + k, vk);
-        if (out) {
+        if (out && FP16) {
+            _mm_storeu_si128((__m128i*)(out + k), _mm256_cvtps_ph(pk, _MM_FROUND_TO_NEAREST_INT | _MM_FROUND_NO_EXC));
+        } else if (out) {
             const __m256i u = _mm256_castps_si256(pk);
             const __m256i lsb = _mm256_and_si256(_mm256_srli_epi32(u, 16), _mm256_set1_epi32(1));
             __m256i r = _mm256_srli_epi32(_mm256_add_epi32(_mm256_add_epi32(u, _mm256_set1_epi32(0x7FFF)), lsb), 16);
@@ -90,9 +138,10 @@ __attribute__((target("avx2,fma"))) void adam_avx2(float* p, float* m, float* v,
             _mm_storeu_si128((__m128i*)(out + k), _mm256_castsi256_si128(packed));
         }
     }
-    if (k < n) adam_scalar(p + k, m + k, v + k, g32 ? g32 + k : nullptr, g16 ? g16 + k : nullptr, out ? out + k : nullptr, n - k, c);
+    if (k < n) adam_scalar<FP16>(p + k, m + k, v + k, g32 ? g32 + k : nullptr, g16 ? g16 + k : nullptr, out ? out + k : nullptr, n - k, c);
 }
 
+template <bool FP16>
 __attribute__((target("avx512f,avx512bw,avx512vl"))) void adam_avx512(float* p, float* m, float* v, const float* g32,
                                                                      const uint16_t* g16, uint16_t* out, int64_t n,
                                                                      const Consts& c) {
@@ -102,13 +151,14 @@ __attribute__((target("avx512f,avx512bw,avx512vl"))) void adam_avx512(float* p, 
     // leading elements up to the first 64-byte boundary of p, so that the streaming stores are aligned
     int64_t head = (int64_t)(((64 - ((uintptr_t)p & 63)) & 63) / 4);
     if (head > n) head = n;
-    if (head) adam_scalar(p, m, v, g32, g16, out, head, c);
+    if (head) adam_scalar<FP16>(p, m, v, g32, g16, out, head, c);
     const bool stream = (((uintptr_t)(m + head) | (uintptr_t)(v + head)) & 63) == 0;
     const bool stream_out = out && (((uintptr_t)(out + head)) & 31) == 0;
     int64_t k = head;
     for (; k + 16 <= n; k += 16) {
         __m512 g;
         if (g32) g = _mm512_loadu_ps(g32 + k);
+        else if (FP16) g = _mm512_cvtph_ps(_mm256_loadu_si256((const __m256i*)(g16 + k)));
         else g = _mm512_castsi512_ps(_mm512_slli_epi32(_mm512_cvtepu16_epi32(_mm256_loadu_si256((const __m256i*)(g16 + k))), 16));
         g = _mm512_mul_ps(gs, g);
         const __m512 pk0 = _mm512_load_ps(p + k);
@@ -126,7 +176,11 @@ __attribute__((target("avx512f,avx512bw,avx512vl"))) void adam_avx512(float* p, 
             _mm512_storeu_ps(m + k, mk);
             _mm512_storeu_ps(v + k, vk);
         }
-        if (out) {
+        if (out && FP16) {
+            const __m256i packed = _mm512_cvtps_ph(pk, _MM_FROUND_TO_NEAREST_INT | _MM_FROUND_NO_EXC);
+            if (stream_out) _mm256_stream_si256((__m256i*)(out + k), packed);
+            else _mm256_storeu_si256((__m256i*)(out + k), packed);
+        } else if (out) {
             const __m512i u = _mm512_castps_si512(pk);
             const __m512i lsb = _mm512_and_si512(_mm512_srli_epi32(u, 16), _mm512_set1_epi32(1));
             __m512i r = _mm512_srli_epi32(_mm512_add_epi32(_mm512_add_epi32(u, _mm512_set1_epi32(0x7FFF)), lsb), 16);
@@ -138,17 +192,17 @@ __attribute__((target("avx512f,avx512bw,avx512vl"))) void adam_avx512(float* p, 
         }
     }
     _mm_sfence();
-    if (k < n) adam_scalar(p + k, m + k, v + k, g32 ? g32 + k : nullptr, g16 ? g16 + k : nullptr, out ? out + k : nullptr, n - k, c);
+    if (k < n) adam_scalar<FP16>(p + k, m + k, v + k, g32 ? g32 + k : nullptr, g16 ? g16 + k : nullptr, out ? out + k : nullptr, n - k, c);
 }
 
 typedef void (*AdamFn)(float*, float*, float*, const float*, const uint16_t*, uint16_t*, int64_t, const Consts&);
 
 // Best instruction set the CPU offers; the environment variable ELIXIR_HOST_ISA (scalar | avx2 | avx512) can only
 // lower the choice (used by tests to exercise every variant on one machine).
-AdamFn pick_kernel(const char** name) {
+AdamFn pick_kernel(const char** name, bool fp16 = false) {
     __builtin_cpu_init();
     int level = 0;
-    if (__builtin_cpu_supports("avx2") && __builtin_cpu_supports("fma")) level = 1;
+    if (__builtin_cpu_supports("avx2") && __builtin_cpu_supports("fma") && __builtin_cpu_supports("f16c")) level = 1;
     if (level == 1 && __builtin_cpu_supports("avx512f") && __builtin_cpu_supports("avx512bw") && __builtin_cpu_supports("avx512vl")) level = 2;
     if (const char* want = getenv("ELIXIR_HOST_ISA")) {
         const int cap = !strcmp(want, "scalar") ? 0 : !strcmp(want, "avx2") ? 1 : 2;
@@ -156,14 +210,14 @@ AdamFn pick_kernel(const char** name) {
     }
     if (level == 2) {
         *name = "avx512";
-        return adam_avx512;
+        return fp16 ? adam_avx512<true> : adam_avx512<false>;
     }
     if (level == 1) {
         *name = "avx2";
-        return adam_avx2;
+        return fp16 ? adam_avx2<true> : adam_avx2<false>;
     }
     *name = "scalar";
-    return adam_scalar;
+    return fp16 ? adam_scalar<true> : adam_scalar<false>;
 }
 
 int available_cores() {
@@ -235,11 +289,13 @@ int run_threads(const char* what, int T, W&& work) {
 
 }  // namespace
 
-extern "C" int elixir_host_adam_step(float* h_master, float* h_exp_avg, float* h_exp_avg_sq, const float* h_grad_fp32,
-                                     const uint16_t* h_grad_bf16, uint16_t* h_param_bf16, int64_t n,
-                                     const elixir_adam_hparams* hp, float grad_scale, int n_threads) {
+extern "C" int elixir_host_adam_step_lp(float* h_master, float* h_exp_avg, float* h_exp_avg_sq, const float* h_grad_fp32,
+                                        const uint16_t* h_grad_bf16, uint16_t* h_param_bf16, int lowp_format, int64_t n,
+                                        const elixir_adam_hparams* hp, float grad_scale, int n_threads) {
     static const char* what = "elixir_host_adam_step";
     if (const int rc = check_hparams_host(what, n, hp)) return rc;
+    if (lowp_format != ELIXIR_LOWP_BF16 && lowp_format != ELIXIR_LOWP_FP16)
+        return fail(ELIXIR_EINVAL, "%s: lowp_format=%d is neither ELIXIR_LOWP_BF16 nor ELIXIR_LOWP_FP16", what, lowp_format);
     if (n == 0) return ELIXIR_OK;
     if ((h_grad_fp32 != nullptr) == (h_grad_bf16 != nullptr))
         return fail(ELIXIR_EINVAL, "%s: exactly one of h_grad_fp32 / h_grad_bf16 must be given", what);
@@ -249,7 +305,7 @@ extern "C" int elixir_host_adam_step(float* h_master, float* h_exp_avg, float* h
     if ((a4 & 3) || (a2 & 1)) return fail(ELIXIR_EALIGN, "%s: a pointer is not aligned for its element type", what);
     const Consts c = make_consts(hp, grad_scale);
     const char* isa;
-    const AdamFn fn = pick_kernel(&isa);
+    const AdamFn fn = pick_kernel(&isa, lowp_format == ELIXIR_LOWP_FP16);
     int T = n_threads > 0 ? n_threads : available_cores();
     const int64_t min_slice = 1 << 16;  // below this a thread costs more than it saves
     if ((int64_t)T > (n + min_slice - 1) / min_slice) T = (int)((n + min_slice - 1) / min_slice);
@@ -270,11 +326,20 @@ extern "C" int elixir_host_adam_step(float* h_master, float* h_exp_avg, float* h
 
 // The same update on a tiled optimizer chunk ([master tile | m tile | v tile] of ELIXIR_STATE_TILE elements each): a
 // chunk that the plan moves between host and device is then updated in place by either side.  Threads take whole tiles.
-extern "C" int elixir_host_adam_step_tiled(float* h_state, const float* h_grad_fp32, const uint16_t* h_grad_bf16,
-                                           uint16_t* h_param_bf16, int64_t n, const elixir_adam_hparams* hp, float grad_scale,
-                                           int n_threads) {
+extern "C" int elixir_host_adam_step(float* h_master, float* h_exp_avg, float* h_exp_avg_sq, const float* h_grad_fp32,
+                                     const uint16_t* h_grad_bf16, uint16_t* h_param_bf16, int64_t n,
+                                     const elixir_adam_hparams* hp, float grad_scale, int n_threads) {
+    return elixir_host_adam_step_lp(h_master, h_exp_avg, h_exp_avg_sq, h_grad_fp32, h_grad_bf16, h_param_bf16, ELIXIR_LOWP_BF16, n, hp,
+                                    grad_scale, n_threads);
+}
+
+extern "C" int elixir_host_adam_step_tiled_lp(float* h_state, const float* h_grad_fp32, const uint16_t* h_grad_bf16,
+                                              uint16_t* h_param_bf16, int lowp_format, int64_t n, const elixir_adam_hparams* hp,
+                                              float grad_scale, int n_threads) {
     static const char* what = "elixir_host_adam_step_tiled";
     if (const int rc = check_hparams_host(what, n, hp)) return rc;
+    if (lowp_format != ELIXIR_LOWP_BF16 && lowp_format != ELIXIR_LOWP_FP16)
+        return fail(ELIXIR_EINVAL, "%s: lowp_format=%d is neither ELIXIR_LOWP_BF16 nor ELIXIR_LOWP_FP16", what, lowp_format);
     if (n == 0) return ELIXIR_OK;
     if ((h_grad_fp32 != nullptr) == (h_grad_bf16 != nullptr))
         return fail(ELIXIR_EINVAL, "%s: exactly one of h_grad_fp32 / h_grad_bf16 must be given", what);
@@ -283,7 +348,7 @@ extern "C" int elixir_host_adam_step_tiled(float* h_state, const float* h_grad_f
         return fail(ELIXIR_EALIGN, "%s: a pointer is not aligned for its element type", what);
     const Consts c = make_consts(hp, grad_scale);
     const char* isa;
-    const AdamFn fn = pick_kernel(&isa);
+    const AdamFn fn = pick_kernel(&isa, lowp_format == ELIXIR_LOWP_FP16);
     constexpr int64_t kTile = ELIXIR_STATE_TILE;
     const int64_t tiles = (n + kTile - 1) / kTile;
     int T = n_threads > 0 ? n_threads : available_cores();
@@ -298,4 +363,10 @@ extern "C" int elixir_host_adam_step_tiled(float* h_state, const float* h_grad_f
                h_param_bf16 ? h_param_bf16 + e : nullptr, cnt, c);
         }
     });
+}
+
+extern "C" int elixir_host_adam_step_tiled(float* h_state, const float* h_grad_fp32, const uint16_t* h_grad_bf16,
+                                           uint16_t* h_param_bf16, int64_t n, const elixir_adam_hparams* hp, float grad_scale,
+                                           int n_threads) {
+    return elixir_host_adam_step_tiled_lp(h_state, h_grad_fp32, h_grad_bf16, h_param_bf16, ELIXIR_LOWP_BF16, n, hp, grad_scale, n_threads);
 }

@@ -9,13 +9,15 @@
 //   wait     : compute stream waits for `ready`
 //   evict    : d2h stream waits for an event recorded on the compute stream,
 //              copies back, records `evicted`
-// The two copy directions run on different streams so that they can use different
-// DMA engines (elixir_offload_bind_streams sees to it) and uploads, downloads and
-// kernels proceed concurrently.
+// The two copy directions and the updates run on three streams so that uploads, downloads and
+// kernels proceed concurrently; elixir_offload_copy_streams provides copy streams for which that is
+// measured to hold.
+#include <stdlib.h>
+
 #include <algorithm>
 #include <chrono>
+#include <mutex>
 #include <new>
-#include <thread>
 
 #include "common.hpp"
 
@@ -137,62 +139,188 @@ extern "C" int elixir_chunk_evict(elixir_ctx* ctx, int slot, void* h_block, size
     return ELIXIR_OK;
 }
 
-// The HIP runtime gives a stream a DMA engine at the stream's first copy (the first engine that is idle at
-// that moment) and keeps it.  Two streams whose first copies were issued while nothing else was copying
-// therefore share one engine, and uploads and downloads take turns (measured: 28.7 GB/s each way instead of
-// 48.6).  Issuing the download stream's first copy while an upload is in flight puts it on another engine.
-extern "C" int elixir_offload_bind_streams(elixir_ctx* ctx, elixir_stream_t h2d_stream, elixir_stream_t d2h_stream,
-                                           int* overlapped_out) {
-    if (!ctx) return fail(ELIXIR_EINVAL, "elixir_offload_bind_streams: ctx is NULL");
-    if (overlapped_out) *overlapped_out = 0;
-    if (ctx->n_slots == 0) return fail(ELIXIR_ESTATE, "elixir_offload_bind_streams: no staging slots registered");
-    if (h2d_stream == d2h_stream) return fail(ELIXIR_EINVAL, "elixir_offload_bind_streams: the two streams are the same");
-    for (int i = 0; i < ctx->n_slots; ++i)
-        if (ctx->slots[i].held) return fail(ELIXIR_ESTATE, "elixir_offload_bind_streams: slot %d is held", i);
-    for (int i = 0; i < ctx->n_slots; ++i)  // slot 0 is about to be overwritten: let pending evictions finish
-        if (ctx->slots[i].evict_pending) ELIXIR_HIP_TRY(hipEventSynchronize(ctx->slots[i].evicted));
-    hipStream_t up = (hipStream_t)h2d_stream, down = (hipStream_t)d2h_stream;
-    // upload into the first half of slot 0, download from its second half
-    size_t half = ctx->slot_bytes / 2;
-    if (half > ((size_t)128 << 20)) half = (size_t)128 << 20;
-    if (half < 4096) return fail(ELIXIR_EINVAL, "elixir_offload_bind_streams: slots of %zu bytes are too small", ctx->slot_bytes);
-    char* d = static_cast<char*>(ctx->slots[0].d_ptr);
-    char* h = nullptr;
-    ELIXIR_HIP_TRY(hipHostMalloc((void**)&h, 2 * half, hipHostMallocDefault));
-    auto bail = [&](hipError_t e, const char* what) {
-        (void)hipDeviceSynchronize();
-        (void)hipHostFree(h);
-        return fail(ELIXIR_EHIP, "elixir_offload_bind_streams: %s: %s", what, hipGetErrorString(e));
-    };
-    hipError_t e;
-    // The upload must really be running when the download is issued, not merely queued (the very first copy of a
-    // process takes a while to start): wait a quarter of its expected duration, at most half a millisecond.
-    const auto head_start = std::chrono::microseconds(std::min<long long>(500, (long long)(half / 200000)));
-    auto seconds = [&](bool with_down) -> double {
-        const auto t0 = std::chrono::steady_clock::now();
-        (void)hipMemcpyAsync(d, h, half, hipMemcpyHostToDevice, up);
-        if (with_down) (void)hipMemcpyAsync(h + half, d + half, half, hipMemcpyDeviceToHost, down);
-        (void)hipStreamSynchronize(up);
-        (void)hipStreamSynchronize(down);
-        return std::chrono::duration<double>(std::chrono::steady_clock::now() - t0).count();
-    };
-    int overlapped = 0;
-    for (int attempt = 0; attempt < 3 && !overlapped; ++attempt) {
-        // 1. the latch: the download stream's copy is issued while the upload is running
-        if ((e = hipMemcpyAsync(d, h, half, hipMemcpyHostToDevice, up)) != hipSuccess) return bail(e, "upload");
-        std::this_thread::sleep_for(head_start);
-        if ((e = hipMemcpyAsync(h + half, d + half, half, hipMemcpyDeviceToHost, down)) != hipSuccess) return bail(e, "download");
-        if ((e = hipStreamSynchronize(up)) != hipSuccess) return bail(e, "sync");
-        if ((e = hipStreamSynchronize(down)) != hipSuccess) return bail(e, "sync");
-        // 2. the check: both directions together must take clearly less than the two one after the other
-        double t_up = 1e30, t_both = 1e30;  // best of three each: one late wake-up of this thread must not decide
-        for (int r = 0; r < 3; ++r) t_up = std::min(t_up, seconds(false));
-        for (int r = 0; r < 3; ++r) t_both = std::min(t_both, seconds(true));
-        if ((e = hipGetLastError()) != hipSuccess) return bail(e, "timed copies");
-        overlapped = t_both < 1.6 * t_up ? 1 : 0;
+// Copy streams that really run beside the compute stream.
+//
+// The HIP runtime feeds all streams of a process through a few hardware queues (GPU_MAX_HW_QUEUES, 4 by default): a
+// new stream joins the queue with the fewest streams on it.  Two streams on one hardware queue are still ordered
+// correctly, but a wait that one of them has queued (hipStreamWaitEvent, the marker behind a copy) holds back whatever
+// the other one queues behind it.  Measured on MI355X with the offload pipeline of this file: upload and download
+// streams on one queue take turns (28 GB/s each way instead of 46-48), and a compute stream that shares a queue with
+// a copy stream has its kernels wait for 30 ms block copies.  Which streams share a queue depends on how many streams
+// the process has created before (seen: 1 or 2 streams created earlier break the pipeline, 0, 3, 5, 9 or 14 do not), so
+// it cannot be arranged by construction; it can be measured: a marker on stream B that completes only when a long copy
+// on stream A has finished shares A's queue.  elixir_offload_copy_streams creates candidate streams until it has two
+// that share a queue neither with the caller's compute stream nor with each other.
+//
+// Separate queues are necessary, not sufficient.  The DMA engines behind the copies are shared by the whole process,
+// and after a large device allocation has been freed (hipFree of 4 GiB or more: seen every time) an upload and a
+// download issued together take turns whatever streams carry them, until later copy traffic undoes it (one 1 GiB
+// upload on a third stream did, as did twenty 1 GiB downloads; one or four downloads did not).  No stream choice
+// repairs that, so the call only reports it: *full_duplex_out says whether an upload and a download overlapped when
+// the call looked.  A process that wants the full-duplex rate allocates its long-lived buffers once and frees nothing
+// large while it streams (the paper's own rule for long-lived buffers, Sec. 3 "Pre-runtime Profiler").
+
+namespace {
+
+struct QueueProbe {
+    char* d_buf = nullptr;
+    char* h_buf = nullptr;
+    size_t bytes = (size_t)64 << 20;  // ~1.1 ms on the link: far above the ~20 us an unhindered marker takes (buffers hold two such pieces)
+    hipEvent_t ea = nullptr, eb = nullptr;
+    bool verbose = getenv("ELIXIR_TRACE_STREAMS") != nullptr;  // prints what was measured for every candidate
+    ~QueueProbe() {
+        if (ea) (void)hipEventDestroy(ea);
+        if (eb) (void)hipEventDestroy(eb);
+        if (d_buf) (void)hipFree(d_buf);
+        if (h_buf) (void)hipHostFree(h_buf);
     }
-    if (overlapped_out) *overlapped_out = overlapped;
-    ELIXIR_HIP_TRY(hipHostFree(h));
+    hipError_t init() {
+        hipError_t e = hipMalloc((void**)&d_buf, 2 * bytes);
+        if (e == hipSuccess) e = hipHostMalloc((void**)&h_buf, 2 * bytes, hipHostMallocDefault);
+        if (e == hipSuccess) e = hipEventCreateWithFlags(&ea, hipEventDisableTiming);
+        if (e == hipSuccess) e = hipEventCreateWithFlags(&eb, hipEventDisableTiming);
+        return e;
+    }
+    // *shared = a marker on b waits for the work pending on a.  Best of three: a late wake-up of this thread can only
+    // make an independent pair look dependent, never the other way round.
+    hipError_t shares_queue(hipStream_t a, hipStream_t b, bool* shared) {
+        double best = 1e30;
+        for (int r = 0; r < 3 && best > 0.25; ++r) {
+            hipError_t e = hipMemcpyAsync(d_buf, h_buf, bytes, hipMemcpyHostToDevice, a);
+            if (e == hipSuccess) e = hipEventRecord(ea, a);
+            const auto t0 = std::chrono::steady_clock::now();
+            if (e == hipSuccess) e = hipEventRecord(eb, b);
+            if (e == hipSuccess) e = hipEventSynchronize(eb);
+            const auto t1 = std::chrono::steady_clock::now();
+            if (e == hipSuccess) e = hipEventSynchronize(ea);
+            const auto t2 = std::chrono::steady_clock::now();
+            if (e != hipSuccess) {
+                (void)hipDeviceSynchronize();
+                return e;
+            }
+            const double marker = std::chrono::duration<double>(t1 - t0).count(), copy = std::chrono::duration<double>(t2 - t0).count();
+            best = std::min(best, marker / copy);
+        }
+        *shared = best > 0.5;
+        if (verbose) fprintf(stderr, "elixir_offload_copy_streams: marker on %p behind a copy on %p: %.0f%% of the copy's time -> %s\n", (void*)b,
+                             (void*)a, 100.0 * best, *shared ? "same hardware queue" : "independent");
+        return hipSuccess;
+    }
+    // *overlap = an upload on `up` and a download on `down` issued together take clearly less than the two one after the
+    // other.  The runtime picks a DMA engine for a copy from those that are idle when the copy is issued, so the
+    // first download is issued while an upload is known to be running (a small upload and a marker in front of a long
+    // one: once the marker has completed the engine is working on the long one).  Best of three each.
+    hipError_t copies_overlap(hipStream_t up, hipStream_t down, bool* overlap) {
+        hipError_t e = hipMemcpyAsync(d_buf, h_buf, 4096, hipMemcpyHostToDevice, up);
+        if (e == hipSuccess) e = hipEventRecord(ea, up);
+        if (e == hipSuccess) e = hipMemcpyAsync(d_buf, h_buf, bytes, hipMemcpyHostToDevice, up);
+        if (e == hipSuccess) e = hipEventSynchronize(ea);
+        if (e == hipSuccess) e = hipMemcpyAsync(h_buf + bytes, d_buf + bytes, bytes, hipMemcpyDeviceToHost, down);
+        if (e == hipSuccess) e = hipStreamSynchronize(up);
+        if (e == hipSuccess) e = hipStreamSynchronize(down);
+        double t_up = 1e30, t_both = 1e30;
+        for (int r = 0; r < 6 && e == hipSuccess; ++r) {
+            const bool both = r >= 3;
+            const auto t0 = std::chrono::steady_clock::now();
+            e = hipMemcpyAsync(d_buf, h_buf, bytes, hipMemcpyHostToDevice, up);
+            if (both && e == hipSuccess) e = hipMemcpyAsync(h_buf + bytes, d_buf + bytes, bytes, hipMemcpyDeviceToHost, down);
+            if (e == hipSuccess) e = hipStreamSynchronize(up);
+            if (e == hipSuccess) e = hipStreamSynchronize(down);
+            const double t = std::chrono::duration<double>(std::chrono::steady_clock::now() - t0).count();
+            if (both) t_both = std::min(t_both, t);
+            else t_up = std::min(t_up, t);
+        }
+        if (e != hipSuccess) {
+            (void)hipDeviceSynchronize();
+            return e;
+        }
+        *overlap = t_both < 1.6 * t_up;
+        if (verbose) fprintf(stderr, "elixir_offload_copy_streams: upload on %p %.3f ms, with a download on %p %.3f ms -> %s\n", (void*)up,
+                             1e3 * t_up, (void*)down, 1e3 * t_both, *overlap ? "they overlap" : "they take turns");
+        return hipSuccess;
+    }
+};
+
+}  // namespace
+
+namespace {
+// The pair is kept per device for the life of the process and each stream keeps its direction: a stream that is
+// destroyed hands its hardware queue, and with it the DMA engine it used, to the next stream created, and an
+// engine picked for downloads was then seen to serve uploads at half the link rate.
+constexpr int kMaxDevices = 64;
+std::mutex g_pair_mutex;
+hipStream_t g_pair[kMaxDevices][2] = {};
+}  // namespace
+
+extern "C" int elixir_offload_copy_streams(elixir_ctx* ctx, elixir_stream_t compute_stream, elixir_stream_t* h2d_out,
+                                           elixir_stream_t* d2h_out, int* full_duplex_out) {
+    static const char* what = "elixir_offload_copy_streams";
+    if (!ctx || !h2d_out || !d2h_out) return fail(ELIXIR_EINVAL, "%s: NULL argument", what);
+    *h2d_out = *d2h_out = nullptr;
+    if (full_duplex_out) *full_duplex_out = 0;
+    if (ctx->device < 0 || ctx->device >= kMaxDevices) return fail(ELIXIR_ECAP, "%s: device %d", what, ctx->device);
+    std::lock_guard<std::mutex> lock(g_pair_mutex);
+    QueueProbe probe;
+    hipError_t e = probe.init();
+    if (e != hipSuccess) return fail(ELIXIR_EHIP, "%s: set-up of the probe: %s", what, hipGetErrorString(e));
+    hipStream_t cs = (hipStream_t)compute_stream;
+    hipStream_t* pair = g_pair[ctx->device];
+    // does the pair this process already has still run beside this compute stream?
+    if (pair[0] && pair[1]) {
+        bool up_shared = true, down_shared = true, each_other = true, overlap = false;
+        e = probe.shares_queue(cs, pair[0], &up_shared);
+        if (e == hipSuccess) e = probe.shares_queue(cs, pair[1], &down_shared);
+        if (e == hipSuccess) e = probe.shares_queue(pair[0], pair[1], &each_other);
+        if (e == hipSuccess && !up_shared && !down_shared && !each_other) e = probe.copies_overlap(pair[0], pair[1], &overlap);
+        if (e != hipSuccess) return fail(ELIXIR_EHIP, "%s: probing the existing streams: %s", what, hipGetErrorString(e));
+        if (!up_shared && !down_shared && !each_other) {
+            *h2d_out = pair[0];
+            *d2h_out = pair[1];
+            if (full_duplex_out) *full_duplex_out = overlap ? 1 : 0;
+            return ELIXIR_OK;
+        }
+        // Not beside this compute stream: a new pair is looked for.  The old one is left alone (a pipeline may still use it).
+        pair[0] = pair[1] = nullptr;
+    }
+    // Candidates stay alive until the end: each one raises the stream count of its hardware queue, which is what sends
+    // the next candidate to another queue.
+    constexpr int kCandidates = 12;
+    hipStream_t cand[kCandidates] = {};
+    hipStream_t kept[2] = {nullptr, nullptr};
+    int n_cand = 0, n_kept = 0;
+    int rc = ELIXIR_OK;
+    for (; n_cand < kCandidates && n_kept < 2; ++n_cand) {
+        if ((e = hipStreamCreateWithFlags(&cand[n_cand], hipStreamNonBlocking)) != hipSuccess) {
+            rc = fail(ELIXIR_EHIP, "%s: hipStreamCreateWithFlags: %s", what, hipGetErrorString(e));
+            break;
+        }
+        hipStream_t s = cand[n_cand];
+        bool shared = false;
+        if ((e = probe.shares_queue(cs, s, &shared)) == hipSuccess && !shared && n_kept == 1) e = probe.shares_queue(kept[0], s, &shared);
+        if (e != hipSuccess) {
+            rc = fail(ELIXIR_EHIP, "%s: probing a stream: %s", what, hipGetErrorString(e));
+            ++n_cand;
+            break;
+        }
+        if (!shared) kept[n_kept++] = s;
+    }
+    for (int i = 0; i < n_cand; ++i)
+        if (cand[i] && cand[i] != kept[0] && cand[i] != kept[1]) (void)hipStreamDestroy(cand[i]);
+    if (rc == ELIXIR_OK && n_kept < 2)
+        rc = fail(ELIXIR_ESTATE, "%s: of %d new streams fewer than two have a hardware queue to themselves beside the compute stream", what, n_cand);
+    bool overlap = false;
+    if (rc == ELIXIR_OK && (e = probe.copies_overlap(kept[0], kept[1], &overlap)) != hipSuccess)
+        rc = fail(ELIXIR_EHIP, "%s: probing the copies: %s", what, hipGetErrorString(e));
+    if (rc != ELIXIR_OK) {
+        for (hipStream_t k : kept)
+            if (k) (void)hipStreamDestroy(k);
+        return rc;
+    }
+    pair[0] = kept[0];
+    pair[1] = kept[1];
+    *h2d_out = kept[0];
+    *d2h_out = kept[1];
+    if (full_duplex_out) *full_duplex_out = overlap ? 1 : 0;
     return ELIXIR_OK;
 }
 

@@ -106,3 +106,23 @@ def test_benefit_errors():
         assert e.value.code == ex.ELIXIR_EINVAL
     with pytest.raises(ex.ElixirError):
         ex.elixir_offload_plan(1, 1, -1, 1, 1e9, 1e9, 1e9, 1e9, 1e9)
+
+
+def test_product_plan_on_the_paper_rows_follows_the_larger_benefit():
+    """The decision rule after Eq. 2 on the paper's own App. B.1 numbers, through the product: on both servers at n = 1
+    I > J (a cached block is worth more than an uploaded chunk), so spare memory goes to rCache blocks first and chunks
+    only get what is left; where J > I it is the other way round."""
+    C, n_chunks = 64 << 20, 40
+    for srv, n, c2g, g2c, vg, vc in paper_tables():
+        I, J = ex.elixir_offload_benefit(n, C, float(g2c), float(c2g), float(vg), float(vc))
+        if n == 1:
+            assert I > J, (srv, n)
+        # memory for the mandatory block plus five more blocks' worth: at n = 1 that is 5 blocks (10 C bytes) and no chunk,
+        # since a chunk costs 14 C / n bytes
+        allowed = 2.0 * C * 6
+        blocks, chunks = ex.elixir_offload_plan(n, C, n_chunks, 1, allowed, float(g2c), float(c2g), float(vg), float(vc))
+        assert (blocks, chunks) == tuple(orc.offload_plan(n, C, n_chunks, 1, int(allowed), g2c, c2g, vg, vc))
+        if I > J:
+            assert blocks == 6 and chunks == 0
+        else:
+            assert chunks == int(10 * C // (14 * C // n)) and blocks == 1 + (10 * C - chunks * (14 * C // n)) // (2 * C)

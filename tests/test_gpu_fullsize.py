@@ -385,9 +385,8 @@ def test_gpt2_20b_offload_mix_full_size_chunks():
         slots = [torch.full((3, C), float("nan"), dtype=torch.float32, device=DEV) for _ in range(2)]
         ex.elixir_offload_register_slots(ctx, slots, nbytes)
         out = {c: torch.zeros(C, dtype=torch.int16, device=DEV) for c in chunks}
-        compute, h2d, d2h = torch.cuda.Stream(), torch.cuda.Stream(), torch.cuda.Stream()
-        ex.elixir_offload_bind_streams(ctx, h2d, d2h)
-        slots[0].fill_(float("nan"))
+        compute = torch.cuda.Stream()
+        h2d, d2h = ex.elixir_offload_copy_streams(ctx, compute)
         torch.cuda.synchronize()
         pending, inflight = list(host_ids), []
         for c in chunks:

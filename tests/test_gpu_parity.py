@@ -1155,9 +1155,8 @@ def test_offload_is_bitwise_identical_to_resident(ctx, n_slots):
         slots = [torch.full((3, C), float("nan"), dtype=torch.float32, device=DEV) for _ in range(n_slots)]  # poisoned
         ex.elixir_offload_register_slots(ctx, slots, nbytes)
         out = torch.zeros(n_chunks, C, dtype=torch.int16, device=DEV)
-        compute, h2d, d2h = torch.cuda.Stream(), torch.cuda.Stream(), torch.cuda.Stream()
-        ex.elixir_offload_bind_streams(ctx, h2d, d2h)              # overwrites slot 0: poison it again
-        slots[0].fill_(float("nan"))
+        compute = torch.cuda.Stream()
+        h2d, d2h = ex.elixir_offload_copy_streams(ctx, compute)
         sync()
         pending = list(host_ids)
         inflight = []                                            # (chunk, slot) prefetched, not yet updated
@@ -1402,57 +1401,71 @@ def test_cpu_update_of_a_host_resident_chunk_through_the_copy_entry_points():
             ex.elixir_host_free(b)
 
 
-def test_offload_bind_streams_makes_copies_overlap(ctx):
+def test_offload_copy_streams_run_beside_the_compute_stream_and_each_other(ctx):
+    """The copy streams the context hands out: uploads and downloads overlap, and kernels on the compute stream are not
+    held back by block copies -- whatever streams the process has created before (this test runs after many others,
+    and creates a few more first)."""
+    import time
     nbytes = 256 << 20
+    extra = [torch.cuda.Stream() for _ in range(3)]                 # shift the process's stream count
+    for q in extra:
+        with torch.cuda.stream(q):
+            torch.zeros(8, device=DEV).add_(1.0)
+    sync()
+    compute = torch.cuda.Stream()
     slots = [torch.zeros(nbytes // 4, dtype=torch.float32, device=DEV) for _ in range(2)]
-    h2d, d2h = torch.cuda.Stream(), torch.cuda.Stream()
-    with pytest.raises(ex.ElixirError) as e:
-        ex.elixir_offload_bind_streams(ctx, h2d, d2h)                 # no slots yet
-    assert e.value.code == ex.ELIXIR_ESTATE
     ex.elixir_offload_register_slots(ctx, slots, nbytes)
+    blk = [ex.elixir_host_alloc(nbytes) for _ in range(2)]
     try:
-        with pytest.raises(ex.ElixirError) as e:
-            ex.elixir_offload_bind_streams(ctx, h2d, h2d)
-        assert e.value.code == ex.ELIXIR_EINVAL
-        # the flag is a snapshot of what the runtime did with the two streams at that moment (it has been seen False in
-        # processes whose copies overlapped all the same a moment later), so a False is answered with fresh streams, and
-        # what is required is the measured overlap below
-        flag = ex.elixir_offload_bind_streams(ctx, h2d, d2h)
-        for _ in range(2):
-            if flag:
-                break
-            h2d, d2h = torch.cuda.Stream(), torch.cuda.Stream()
-            flag = ex.elixir_offload_bind_streams(ctx, h2d, d2h)
-        assert flag in (True, False)
-        print("bind_streams reported", flag)
-        # 4 uploads + 4 downloads together take clearly less than one after the other
-        blk = [ex.elixir_host_alloc(nbytes) for _ in range(2)]
-        try:
-            import time
+        h2d, d2h, duplex = ex.elixir_offload_copy_streams(ctx, compute, with_flag=True)
+        assert h2d and d2h and h2d != d2h and compute.cuda_stream not in (h2d, d2h)
+        assert ex.elixir_offload_copy_streams(ctx, compute) == (h2d, d2h)      # the pair belongs to the library: asked again, the same two
+        print("copy streams: full duplex measured:", duplex)
 
-            def run(both):
-                sync()
-                t0 = time.perf_counter()
-                for _ in range(4):
+        def copies(up, down):
+            sync()
+            t0 = time.perf_counter()
+            for _ in range(4):
+                if up:
                     s = ex.elixir_chunk_prefetch(ctx, blk[0], nbytes, h2d)
                     ex.elixir_chunk_evict(ctx, s, None, 0, h2d, h2d)
-                    if both:
-                        s = ex.elixir_chunk_prefetch(ctx, blk[1], 4096, d2h)
-                        ex.elixir_chunk_evict(ctx, s, blk[1], nbytes, d2h, d2h)
-                sync()
-                return time.perf_counter() - t0
-
-            run(True)
-            t_up = min(run(False) for _ in range(2))
-            t_both = min(run(True) for _ in range(3))
-            assert t_both < 1.5 * t_up, (t_up, t_both, flag)
-        finally:
+                if down:
+                    s = ex.elixir_chunk_prefetch(ctx, blk[1], 4096, d2h)
+                    ex.elixir_chunk_evict(ctx, s, blk[1], nbytes, d2h, d2h)
             sync()
-            for b in blk:
-                ex.elixir_host_free(b)
+            return time.perf_counter() - t0
+
+        copies(True, True)
+        t_up = min(copies(True, False) for _ in range(2))
+        t_both = min(copies(True, True) for _ in range(3))
+        # both directions at once take clearly less than one after the other -- where the call measured that they can: after a
+        # large hipFree earlier in the process (other tests do that) the runtime makes uploads and downloads take turns for
+        # a while whatever streams carry them, and the flag says so
+        if duplex:
+            assert t_both < 1.6 * t_up, (t_up, t_both)
+        else:
+            assert t_both < 2.3 * t_up, (t_up, t_both)              # taking turns is the worst case: never slower than one after the other
+        # kernels beside the copies: a short kernel on the compute stream finishes while 1 GiB of copies is still under way
+        x = torch.zeros(1 << 20, device=DEV)
+        done = torch.cuda.Event()
+        sync()
+        t0 = time.perf_counter()
+        for _ in range(4):
+            s = ex.elixir_chunk_prefetch(ctx, blk[0], nbytes, h2d)
+            ex.elixir_chunk_evict(ctx, s, blk[1], nbytes, h2d, d2h)
+        with torch.cuda.stream(compute):
+            x.add_(1.0)
+            done.record(compute)
+        done.synchronize()
+        t_kernel = time.perf_counter() - t0
+        sync()
+        t_all = time.perf_counter() - t0
+        assert t_kernel < 0.25 * t_all, (t_kernel, t_all)
     finally:
         sync()
         ex.elixir_offload_register_slots(ctx, [], 0)
+        for b in blk:
+            ex.elixir_host_free(b)
 
 
 # --------------------------------------------------------------------------- determinism, graph capture

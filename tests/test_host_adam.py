@@ -59,6 +59,74 @@ def test_host_adam_matches_oracle(grad_kind, n, shift):
     run_case(n, shift, grad_kind, threads=1, with_out=False)
 
 
+def run_case_fp16(n, shift, threads, steps=2, tiled=False):
+    """The paper's own format: fp16 gradients under a loss scale S (grad_scale = 1/S), fp16 parameters out."""
+    S = 1024.0
+    p, m, v = state(n + 40, 90 + n % 5)
+    gf = gen.fill_f32(gen.stream_key(91, gen.TAG_GRAD, 1), 0, n + 40, 1e-3 * S)
+    g = orc.f32_to_f16(gf)
+    g[::97] = 0
+    s = slice(shift, shift + n)
+    a = [p[s].copy(), m[s].copy(), v[s].copy()]
+    r = [p[s].copy(), m[s].copy(), v[s].copy()]
+    out, ro = np.full(n, 7, np.uint16), np.full(n, 7, np.uint16)
+    T, e = 4096, np.arange(n)
+    tiles = np.zeros(3 * T * max(1, -(-n // T)), np.float32)
+    if tiled:
+        for k, x in enumerate(a):
+            tiles[3 * T * (e // T) + k * T + e % T] = x
+    for t in range(1, steps + 1):
+        if tiled:
+            ex.elixir_host_adam_step_tiled_lp(tiles, None, g[s], out, ex.ELIXIR_LOWP_FP16, n, hp_struct(t), 1.0 / S, threads)
+        else:
+            ex.elixir_host_adam_step_lp(a[0], a[1], a[2], None, g[s], out, ex.ELIXIR_LOWP_FP16, n, hp_struct(t), 1.0 / S, threads)
+        if n:
+            orc.chunk_adam_step(r[0], r[1], r[2], np.ascontiguousarray(g[s]), ro, step=t, grad_scale=1.0 / S, fmt=orc.FP16, **HP)
+    if tiled:
+        a = [tiles[3 * T * (e // T) + k * T + e % T] for k in range(3)]
+    check_adam_close(a[0], a[1], a[2], r[0], r[1], r[2], lr=HP["lr"], gmax=5e-3, steps=steps, what=f"fp16 n={n} shift={shift}")
+    check_bf16_copy(out, a[0], ro, r[0], lr=HP["lr"], steps=steps, fmt=1)
+
+
+def fp16_conversions_on_all_patterns():
+    """Widening of every fp16 pattern and narrowing of every fp16 value, every midpoint between neighbours and values
+    around the overflow threshold, through the update itself: with lr = 0 and zero state the update leaves m = (1 - beta1) g
+    (widening) and writes fp16(p) for any master value p (narrowing)."""
+    bits = np.arange(1 << 16, dtype=np.uint16)
+    finite = (bits & 0x7C00) != 0x7C00
+    n = bits.size
+    m, v, p = np.zeros(n, np.float32), np.zeros(n, np.float32), np.zeros(n, np.float32)
+    hp = ex.make_hparams(0.0, 0.5, 0.5, 1e-8, 0.0, 1)
+    ex.elixir_host_adam_step_lp(p, m, v, None, bits, None, ex.ELIXIR_LOWP_FP16, n, hp, 1.0, 1)
+    want = orc.f16_to_f32(bits)
+    nz = finite & (want != 0)                                                                # 0.5 * g is exact; 0 + (-0) is +0
+    assert np.array_equal((m[nz] * 2).view(np.uint32), want[nz].view(np.uint32)) and not m[finite & (want == 0)].any()
+    vals = want[finite].astype(np.float64)
+    with np.errstate(over="ignore"):
+        nxt = np.nextafter(want[finite].astype(np.float16), np.float16(np.inf)).astype(np.float64)
+    mid = ((vals + nxt) / 2)[np.isfinite(nxt)]
+    probe = np.concatenate([vals, mid, np.nextafter(mid.astype(np.float32), np.float32(np.inf)), np.nextafter(mid.astype(np.float32), np.float32(-np.inf)),
+                            [65504.0, 65519.9, 65520.0, 65536.0, 1e30, -65520.0, 2.0 ** -25, 2.0 ** -25 * 1.0001, 2.0 ** -24 * 1.5]])
+    with np.errstate(over="ignore"):
+        probe = probe.astype(np.float32)
+    probe[probe == 0] = 0.0                      # a master weight of -0 comes out of p + (-(lr wd) p - u) as +0: not a conversion matter
+    k = probe.size
+    out = np.zeros(k, np.uint16)
+    z = np.zeros(k, np.uint16)
+    ex.elixir_host_adam_step_lp(probe.copy(), np.zeros(k, np.float32), np.zeros(k, np.float32), None, z, out, ex.ELIXIR_LOWP_FP16, k, hp, 1.0, 1)
+    assert np.array_equal(out, orc.f32_to_f16(probe))
+
+
+@pytest.mark.parametrize("n,shift,tiled", [(1, 0, False), (17, 1, False), (70_001, 3, False), (262_144, 0, False), (5 * 4096 + 777, 0, True)])
+def test_host_adam_fp16_matches_oracle(n, shift, tiled):
+    run_case_fp16(n, shift, threads=0, tiled=tiled)
+    run_case_fp16(n, shift, threads=1, tiled=tiled)
+
+
+def test_host_adam_fp16_conversions_on_all_patterns():
+    fp16_conversions_on_all_patterns()
+
+
 def test_host_adam_many_threads_and_steps():
     run_case(700_001, 7, "bf16", threads=5, steps=10)
 
@@ -106,6 +174,10 @@ def test_every_isa_variant_in_a_fresh_process(isa):
             "for kind in ('bf16', 'fp32'):\n"
             "    for n, shift in ((17, 1), (70001, 3), (262144, 0)):\n"
             "        t.run_case(n, shift, kind, threads=3)\n"
+            "for n, shift in ((17, 1), (70001, 3), (262144, 0)):\n"
+            "    t.run_case_fp16(n, shift, threads=3)\n"
+            "t.run_case_fp16(5 * 4096 + 777, 0, threads=2, tiled=True)\n"
+            "t.fp16_conversions_on_all_patterns()\n"
             "print('ok')\n") % (ROOT, isa)
     env = dict(os.environ, ELIXIR_HOST_ISA=isa)
     r = subprocess.run([sys.executable, "-c", code], env=env, capture_output=True, text=True, timeout=300)
