@@ -979,6 +979,14 @@ def run_tensor_lists(args, torch, ex, gen):
             segs = by_chunk[c] if per_tensor else [(c, 0, valid[c])]
             fn(chunks[c], C, esz, [data[c][o:o + n] for _, o, n in segs], [n for _, _, n in segs], [o for _, o, _ in segs], sh)
 
+    set_views = {4: [groups["t32"][c][o:o + n] for c, o, n in pieces], 2: s16}     # built once: the timed call should not wait for Python
+    p_c, p_o = [c for c, _, _ in pieces], [o for _, o, _ in pieces]
+
+    def pack_set(esz, unpack=False):
+        chunks = groups["chunk"] if esz == 4 else groups["c16"]
+        fn = ex.elixir_chunks_unpack if unpack else ex.elixir_chunks_pack
+        fn(chunks, C, esz, set_views[esz], p_n, p_c, p_o, sh)
+
     res = {}
     for name, fn, nbytes in (
             ("reduce_overwrite_tensor_list", lambda: reduce_list(False), 6 * n_valid),
@@ -987,6 +995,10 @@ def run_tensor_lists(args, torch, ex, gen):
             ("reduce_accumulate_whole_chunks", lambda: reduce_chunks(True), 10 * n_valid),
             ("pack_fp32_tensor_list", lambda: pack(4, True), 8 * n_valid + 4 * (nch * C - n_valid)),
             ("pack_fp32_whole_chunks", lambda: pack(4, False), 8 * n_valid + 4 * (nch * C - n_valid)),
+            ("pack_fp32_whole_set_one_call", lambda: pack_set(4), 8 * n_valid + 4 * (nch * C - n_valid)),
+            ("unpack_fp32_whole_set_one_call", lambda: pack_set(4, True), 8 * n_valid),
+            ("pack_bf16_whole_set_one_call", lambda: pack_set(2), 4 * n_valid + 2 * (nch * C - n_valid)),
+            ("unpack_bf16_whole_set_one_call", lambda: pack_set(2, True), 4 * n_valid),
             ("unpack_fp32_tensor_list", lambda: pack(4, True, True), 8 * n_valid),
             ("unpack_fp32_whole_chunks", lambda: pack(4, False, True), 8 * n_valid),
             ("pack_bf16_tensor_list", lambda: pack(2, True), 4 * n_valid + 2 * (nch * C - n_valid)),

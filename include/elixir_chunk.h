@@ -124,6 +124,19 @@ int elixir_chunk_unpack(const void* d_chunk, int64_t chunk_elems, int elem_size,
                         const int64_t* numel, const int64_t* offset, int T, elixir_stream_t stream);
 
 /*
+ * The same for a whole parameter set in one call (one launch per chunk, like the per-chunk calls: launches that
+ * sweep several chunks measured slower), taking the layout plan as elixir_layout_plan returns it: tensor i occupies the linear element range
+ * [chunk_id[i] * chunk_elems + offset[i], + numel[i]) of the chunk sequence d_chunks[0], d_chunks[1], ... (a HOST array
+ * of n_chunks device pointers), so a tensor that is longer than the rest of its chunk continues at the start of the
+ * next one and need not be passed piecewise.  pack zero-fills every element of every chunk that no tensor covers.
+ * Same bits as the per-chunk calls.  Tensors must not overlap and must lie inside the n_chunks chunks (ELIXIR_EINVAL).
+ */
+int elixir_chunks_pack(void* const* d_chunks, int n_chunks, int64_t chunk_elems, int elem_size, const void* const* tensors,
+                       const int64_t* numel, const int64_t* chunk_id, const int64_t* offset, int T, elixir_stream_t stream);
+int elixir_chunks_unpack(const void* const* d_chunks, int n_chunks, int64_t chunk_elems, int elem_size, void* const* tensors,
+                         const int64_t* numel, const int64_t* chunk_id, const int64_t* offset, int T, elixir_stream_t stream);
+
+/*
  * Gradient reduction into the fp32 gradient chunk.  In the paper gradients are
  * reduced across ranks and the reduced chunk feeds the optimizer update (Sec. 2
  * "ZeRO", Fig. 3 right); with one GPU the reduction that remains is the sum
@@ -191,8 +204,10 @@ int elixir_chunk_grad_norm_lp(elixir_ctx* ctx, const uint16_t* const* grad_chunk
  * step has gone through it (typically with the last micro-batch), elixir_chunk_grad_norm_finish(n_chunks) turns the
  * slots of chunks 0 .. n_chunks-1 into the norm and the clip coefficient exactly as elixir_chunk_grad_norm does --
  * without reading the gradients again (4 bytes per element saved).  Deterministic like the unfused path (its
- * summation tree differs, so the two norms may differ in the last bit).  The calls of one step must be
- * stream-ordered with each other (they share the context's workspace).
+ * summation tree differs, so the two norms may differ in the last bit).  The calls of one step share the context's
+ * workspace and must use ONE stream: a reduction or the finish call that arrives on another stream than the
+ * reductions since the last finish returns ELIXIR_ESTATE (use one context per stream).  Between steps, and for
+ * elixir_chunk_grad_norm / _lp, ordering calls on different streams is the caller's business.
  */
 int elixir_grad_reduce_chunk_sumsq(elixir_ctx* ctx, int chunk_index, float* d_grad_chunk, const uint16_t* d_grad_lowp,
                                    int lowp_format, int64_t chunk_elems, int64_t valid_len, float scale, int accumulate,

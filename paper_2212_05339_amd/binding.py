@@ -31,7 +31,7 @@ EXPORTS = (
     "elixir_grad_reduce_chunk_sumsq", "elixir_chunk_grad_norm_finish", "elixir_grad_reduce_multi_lp", "elixir_chunk_grad_norm_lp", "elixir_grad_reduce_sources_lp", "elixir_grad_reduce_sources_chunk_sumsq",
     "elixir_state_tiled_len", "elixir_state_tile", "elixir_state_untile", "elixir_chunk_adam_step_tiled_lp",
     "elixir_chunk_adam_step_tiled_multi_lp", "elixir_host_adam_step_tiled", "elixir_chunk_grad_norm_noalloc", "elixir_arena_plan",
-    "elixir_host_adam_step_lp", "elixir_host_adam_step_tiled_lp", "elixir_adam_step_state_init", "elixir_adam_step_state_advance", "elixir_chunk_adam_step_tiled_dev", "elixir_chunk_adam_step_tiled_multi_dev",
+    "elixir_chunks_pack", "elixir_chunks_unpack", "elixir_host_adam_step_lp", "elixir_host_adam_step_tiled_lp", "elixir_adam_step_state_init", "elixir_adam_step_state_advance", "elixir_chunk_adam_step_tiled_dev", "elixir_chunk_adam_step_tiled_multi_dev",
 )
 
 
@@ -89,6 +89,8 @@ def lib() -> ctypes.CDLL:
             "elixir_chunk_evict": [vp, ci, vp, sz, vp, vp],
         }
         sigs["elixir_chunk_grad_norm_noalloc"] = [ctypes.POINTER(vp), pi64, ci, f32, vp, vp, vp]
+        sigs["elixir_chunks_pack"] = [ctypes.POINTER(vp), ci, i64, ci, ctypes.POINTER(vp), pi64, pi64, pi64, ci, vp]
+        sigs["elixir_chunks_unpack"] = [ctypes.POINTER(vp), ci, i64, ci, ctypes.POINTER(vp), pi64, pi64, pi64, ci, vp]
         sigs["elixir_arena_plan"] = [ci, ctypes.POINTER(elixir_arena_array), ci, pi64, i64, pi64]
         sigs["elixir_adam_step_state_init"] = [vp, ctypes.POINTER(elixir_adam_hparams), vp]
         sigs["elixir_adam_step_state_advance"] = [vp, vp, vp]
@@ -240,6 +242,17 @@ def elixir_chunk_unpack(chunk, chunk_elems: int, elem_size: int, tensors, numel,
     T = len(tensors)
     _check(lib().elixir_chunk_unpack(_addr(chunk), chunk_elems, elem_size, _ptr_array(tensors), _i64_array(numel),
                                      _i64_array(offset), T, _stream(stream)))
+
+
+def elixir_chunks_pack(chunks, chunk_elems: int, elem_size: int, tensors, numel, chunk_id, offset, stream=None) -> None:
+    """Every tensor of a set into its place in the chunk sequence (chunk_id, offset as elixir_layout_plan returns them)."""
+    _check(lib().elixir_chunks_pack(_ptr_array(chunks), len(chunks), chunk_elems, elem_size, _ptr_array(tensors), _i64_array(numel),
+                                    _i64_array(chunk_id), _i64_array(offset), len(tensors), _stream(stream)))
+
+
+def elixir_chunks_unpack(chunks, chunk_elems: int, elem_size: int, tensors, numel, chunk_id, offset, stream=None) -> None:
+    _check(lib().elixir_chunks_unpack(_ptr_array(chunks), len(chunks), chunk_elems, elem_size, _ptr_array(tensors), _i64_array(numel),
+                                      _i64_array(chunk_id), _i64_array(offset), len(tensors), _stream(stream)))
 
 
 # --------------------------------------------------------------------------- reduce / norm / step

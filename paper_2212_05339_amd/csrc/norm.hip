@@ -10,7 +10,8 @@
 // Stage 2: a single workgroup adds the slots (each thread a fixed strided
 //   subset in index order, then the same tree) and writes sqrt(sum) and the
 //   clip coefficient.
-// No atomics: the tree is a function of (chunk lengths) only, never of timing.
+// No atomics: the tree is a function of the chunk lengths and of each chunk pointer's offset from a 16-byte boundary
+// (the elements in front of the first boundary are peeled), never of timing or of the launch.
 // Traffic: 4 bytes per element.  When the gradients are being written anyway -- the last micro-batch of the
 // reduction -- elixir_grad_reduce_chunk_sumsq produces the same per-chunk slots from the values in registers and the
 // 4-byte re-read disappears (stage 1b below).  Double-precision arithmetic (2 ops/element)
@@ -268,9 +269,10 @@ __global__ __launch_bounds__(256) void fold_stage_kernel(const double* __restric
     if (lane == 0) slots[j] = acc;
 }
 
+// Returns the first launch error (hipSuccess if all three launches were accepted).
 template <bool ACC, bool FP16>
-void launch_fused(float* dst, const SrcTable& srcs, int n_src, int64_t n, int64_t valid, float scale, double* stage, double* slots,
-                  hipStream_t s) {
+hipError_t launch_fused(float* dst, const SrcTable& srcs, int n_src, int64_t n, int64_t valid, float scale, double* stage, double* slots,
+                        hipStream_t s) {
     const int64_t n4 = n / 4;
     const int64_t blocks = (n4 + kFusedBlock - 1) / kFusedBlock;  // blocks * 64 threads < 2^32: the caller checked chunk_elems
     if (blocks > 0) {
@@ -281,13 +283,16 @@ void launch_fused(float* dst, const SrcTable& srcs, int n_src, int64_t n, int64_
             case 3: hipLaunchKernelGGL((reduce_sumsq_kernel<ACC, FP16, 3>), grid, block, 0, s, dst, srcs, n4, valid, scale, stage); break;
             default: hipLaunchKernelGGL((reduce_sumsq_kernel<ACC, FP16, 4>), grid, block, 0, s, dst, srcs, n4, valid, scale, stage); break;
         }
+        if (const hipError_t e = hipGetLastError()) return e;
     }
     int64_t count = blocks;
     if (n4 * 4 < n) {
         hipLaunchKernelGGL((reduce_sumsq_tail_kernel<ACC, FP16>), dim3(1), dim3(1), 0, s, dst, srcs, n_src, n4 * 4, n, valid, scale, stage + blocks);
+        if (const hipError_t e = hipGetLastError()) return e;
         ++count;
     }
     hipLaunchKernelGGL(fold_stage_kernel, dim3(kNormBlocksPerChunk / 4), dim3(256), 0, s, stage, count, slots);
+    return hipGetLastError();
 }
 
 }  // namespace
@@ -405,8 +410,11 @@ extern "C" int elixir_grad_reduce_sources_chunk_sumsq(elixir_ctx* ctx, int chunk
                                                       const uint16_t* const* d_grad_lowp, int n_sources, int lowp_format,
                                                       int64_t chunk_elems, int64_t valid_len, float scale, int accumulate,
                                                       elixir_stream_t stream) {
-    static const char* what = "elixir_grad_reduce_chunk_sumsq";
+    static const char* what = "elixir_grad_reduce_sources_chunk_sumsq";
     if (!ctx) return fail(ELIXIR_EINVAL, "%s: ctx is NULL", what);
+    if (ctx->fused_open && ctx->fused_stream != stream)
+        return fail(ELIXIR_ESTATE, "%s: the calls of one step share the context's workspace and must use one stream (chunk %d arrives on "
+                                   "another stream than the calls before it)", what, chunk_index);
     if (chunk_index < 0 || chunk_index >= ctx->max_chunks)
         return fail(ELIXIR_ECAP, "%s: chunk_index=%d, context sized for %d chunks", what, chunk_index, ctx->max_chunks);
     if (chunk_elems < 0 || valid_len < 0 || valid_len > chunk_elems)
@@ -420,6 +428,8 @@ extern "C" int elixir_grad_reduce_sources_chunk_sumsq(elixir_ctx* ctx, int chunk
         return fail(ELIXIR_ECAP, "%s: a chunk of %lld elements does not fit one launch", what, (long long)chunk_elems);
     hipStream_t s = (hipStream_t)stream;
     double* slots = ctx->d_partials + (int64_t)chunk_index * kNormBlocksPerChunk;
+    ctx->fused_open = true;
+    ctx->fused_stream = stream;
     if (chunk_elems == 0) {  // nothing to reduce: the chunk contributes zero
         hipLaunchKernelGGL(fold_stage_kernel, dim3(kNormBlocksPerChunk / 4), dim3(256), 0, s, ctx->d_stage, (int64_t)0, slots);
         ELIXIR_LAUNCH_CHECK("fold_stage_kernel");
@@ -441,14 +451,15 @@ extern "C" int elixir_grad_reduce_sources_chunk_sumsq(elixir_ctx* ctx, int chunk
     const int cnt = n_sources - last;
     SrcTable t;
     for (int k = 0; k < kMaxSources; ++k) t.p[k] = k < cnt ? d_grad_lowp[last + k] : nullptr;
+    hipError_t e;
     if (accumulate || last > 0) {
-        if (f16) launch_fused<true, true>(d_grad_chunk, t, cnt, chunk_elems, valid_len, scale, ctx->d_stage, slots, s);
-        else launch_fused<true, false>(d_grad_chunk, t, cnt, chunk_elems, valid_len, scale, ctx->d_stage, slots, s);
+        e = f16 ? launch_fused<true, true>(d_grad_chunk, t, cnt, chunk_elems, valid_len, scale, ctx->d_stage, slots, s)
+                : launch_fused<true, false>(d_grad_chunk, t, cnt, chunk_elems, valid_len, scale, ctx->d_stage, slots, s);
     } else {
-        if (f16) launch_fused<false, true>(d_grad_chunk, t, cnt, chunk_elems, valid_len, scale, ctx->d_stage, slots, s);
-        else launch_fused<false, false>(d_grad_chunk, t, cnt, chunk_elems, valid_len, scale, ctx->d_stage, slots, s);
+        e = f16 ? launch_fused<false, true>(d_grad_chunk, t, cnt, chunk_elems, valid_len, scale, ctx->d_stage, slots, s)
+                : launch_fused<false, false>(d_grad_chunk, t, cnt, chunk_elems, valid_len, scale, ctx->d_stage, slots, s);
     }
-    ELIXIR_LAUNCH_CHECK("reduce_sumsq_kernel");
+    if (e != hipSuccess) return fail(ELIXIR_EHIP, "%s: launch of the fused reduction: %s", what, hipGetErrorString(e));
     return ELIXIR_OK;
 }
 
@@ -467,6 +478,9 @@ extern "C" int elixir_chunk_grad_norm_finish(elixir_ctx* ctx, int n_chunks, floa
     if (n_chunks < 0) return fail(ELIXIR_EINVAL, "%s: n_chunks is negative", what);
     if (n_chunks > ctx->max_chunks) return fail(ELIXIR_ECAP, "%s: %d chunks, context sized for %d", what, n_chunks, ctx->max_chunks);
     if (!aligned(d_norm_out, 4) || !aligned(d_clip_coef_out, 4)) return fail(ELIXIR_EALIGN, "%s: output pointer not 4-byte aligned", what);
+    if (ctx->fused_open && ctx->fused_stream != stream)
+        return fail(ELIXIR_ESTATE, "%s: called on another stream than the reductions whose sums it is to fold", what);
+    ctx->fused_open = false;
     hipLaunchKernelGGL(finish_kernel, dim3(1), dim3(1024), 0, (hipStream_t)stream, ctx->d_partials,
                        (int64_t)n_chunks * kNormBlocksPerChunk, max_norm, 1.0, d_norm_out, d_clip_coef_out);
     ELIXIR_LAUNCH_CHECK("finish_kernel");

@@ -131,6 +131,51 @@ def test_pack_misaligned_tensor_pointers_and_subset_unpack():
     assert np.array_equal(host(out, np.uint16), h_back[5001:5001 + 12_345])
 
 
+@pytest.mark.parametrize("dtype", [np.float32, np.uint16])
+@pytest.mark.parametrize("policy", [0, 1, 2])
+def test_whole_set_pack_unpack_match_the_oracle_chunk_by_chunk(dtype, policy):
+    """elixir_chunks_pack / _unpack take the layout plan as it stands (a tensor that outgrows its chunk continues in the
+    next one); the oracle packs chunk by chunk with the tensor cut into pieces by hand.  Several chunks, more slices than
+    one launch's table holds, ragged and oversize tensors, zero-length tensors, untouched bytes preset to a pattern."""
+    rng = np.random.default_rng(100 + policy)
+    C = 50_000
+    numels = [int(x) for x in rng.integers(0, 3000, size=150)] + [120_001, 7, 50_000, 1, 99_999] + [int(x) for x in rng.integers(1, 900, size=40)]
+    cid, off, valid = orc.layout_plan(numels, C, policy, 1)
+    nch = len(valid)
+    tensors = _random_tensors(rng, numels, dtype)
+    want = np.empty((nch, C), dtype)
+    want.view(np.uint8)[:] = 0xAB
+    per_chunk = [([], []) for _ in range(nch)]
+    for i, n in enumerate(numels):                        # cut by hand: element k of tensor i lies at linear cid*C + off + k
+        c, o, done = cid[i], off[i], 0
+        while done < n:
+            take = min(n - done, C - o)
+            per_chunk[c][0].append(np.ascontiguousarray(tensors[i][done:done + take]))
+            per_chunk[c][1].append(o)
+            done, c, o = done + take, c + 1, 0
+    for c in range(nch):
+        orc.chunk_pack(want[c], per_chunk[c][0], per_chunk[c][1])
+    es = np.dtype(dtype).itemsize
+    d_tensors = [dev(t) for t in tensors]
+    d_chunks = [dev(np.full(C, 0x5A5A, np.uint16) if es == 2 else np.full(C, 1.5, np.float32)) for _ in range(nch)]
+    ex.elixir_chunks_pack(d_chunks, C, es, d_tensors, numels, cid, off)
+    sync()
+    for c in range(nch):
+        assert np.array_equal(host(d_chunks[c], dtype).view(np.uint8), want[c].view(np.uint8)), f"chunk {c}"
+    d_outs = [torch.full_like(t, 3) for t in d_tensors]
+    ex.elixir_chunks_unpack(d_chunks, C, es, d_outs, numels, cid, off)
+    sync()
+    for t, o in zip(tensors, d_outs):
+        assert np.array_equal(host(o, dtype).view(np.uint8), t.view(np.uint8))
+    # errors: a tensor that leaves the chunks, overlapping tensors
+    with pytest.raises(ex.ElixirError) as e:
+        ex.elixir_chunks_pack(d_chunks, C, es, d_tensors[:1], [C * nch + 1], [0], [0])
+    assert e.value.code == ex.ELIXIR_EINVAL
+    with pytest.raises(ex.ElixirError) as e:
+        ex.elixir_chunks_pack(d_chunks, C, es, d_tensors[-2:], numels[-2:], [0, 0], [0, 0])
+    assert e.value.code == ex.ELIXIR_EINVAL
+
+
 def test_pack_empty_and_padding_only():
     C = 1000
     d_chunk = torch.full((C,), 3.0, dtype=torch.float32, device=DEV)
