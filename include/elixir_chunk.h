@@ -427,8 +427,9 @@ typedef struct {
 int elixir_grad_reduce_into_chunk_lp(float* d_grad_chunk, int64_t offset, const uint16_t* d_grad_lowp, int lowp_format,
                                      int64_t n, float scale, int accumulate, elixir_stream_t stream);
 /*
- * The reduction for many tensors in as few launches as possible (one per 64 tensors): gradients arrive tensor by
- * tensor and most tensors are small, so one launch each leaves the GPU idle in between.  d_dst[i] points at the
+ * The reduction for many tensors in few launches: gradients arrive tensor by tensor and most tensors are small, so
+ * one launch each leaves the GPU idle in between.  The tensors are cut into equal pieces plus tails, and pieces of
+ * similar length share a launch as the rows of a 2-D grid (up to 160 rows; no host allocation; any number of tensors).  d_dst[i] points at the
  * tensor's place inside its fp32 gradient chunk (chunk base + offset, computed by the caller), d_grad_lowp[i] at its
  * n[i] low-precision gradients; all three tables are HOST arrays.  Destinations must not overlap.  Results are
  * bit-identical to n_tensors calls of elixir_grad_reduce_into_chunk_lp.
