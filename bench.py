@@ -251,12 +251,13 @@ def side_rows(ex, gen, torch, cfg, C, nch, valid, state, grads, out, stream, ste
             ex.elixir_grad_reduce_into_chunk(d, 0, g, n, 0.25, False, sh)
 
     t_each = timed(per_tensor, 3)
-    t_multi = timed(lambda: ex.elixir_grad_reduce_multi_lp(p_dst, p_src, p_n, ex.ELIXIR_LOWP_BF16, 0.25, False, sh), 3)
+    T_dst, T_src, T_n = ex.elixir_ptr_table(p_dst), ex.elixir_ptr_table(p_src), ex.elixir_i64_table(p_n)   # built once, as a trainer would
+    t_multi = timed(lambda: ex.elixir_grad_reduce_multi_lp(T_dst, T_src, T_n, ex.ELIXIR_LOWP_BF16, 0.25, False, sh), 5)
     rows["grad_reduce_per_tensor"] = {"what": f"bf16 -> fp32, overwrite, the {len(pieces)} tensor pieces of the set: one call per tensor against "
                                               "one elixir_grad_reduce_multi_lp call", "bytes": 6 * sum(p_n),
                                       "one_call_per_tensor_ms": t_each * 1e3, "one_call_per_tensor_GB/s": 6 * sum(p_n) / t_each / 1e9,
                                       "ms": t_multi * 1e3, "GB/s": 6 * sum(p_n) / t_multi / 1e9}
-    t_macc = timed(lambda: ex.elixir_grad_reduce_multi_lp(p_dst, p_src, p_n, ex.ELIXIR_LOWP_BF16, 0.25, True, sh), 3)
+    t_macc = timed(lambda: ex.elixir_grad_reduce_multi_lp(T_dst, T_src, T_n, ex.ELIXIR_LOWP_BF16, 0.25, True, sh), 5)
     rows["grad_reduce_per_tensor"].update({"accumulate_ms": t_macc * 1e3, "accumulate_bytes": 10 * sum(p_n),
                                            "accumulate_GB/s": 10 * sum(p_n) / t_macc / 1e9})
     del rg, _keep_rg, pieces, p_dst, p_src
@@ -340,12 +341,15 @@ def side_rows(ex, gen, torch, cfg, C, nch, valid, state, grads, out, stream, ste
                         for c in range(k * nch // n_host, (k + 1) * nch // n_host):
                             ex.elixir_chunk_adam_step(state[c][0], state[c][1], state[c][2], None, grads[0][c], out[c], C, hp, None, sh)
 
-            t_h2d = min(wall(only_h2d) for _ in range(2))
-            t_d2h = min(wall(only_d2h) for _ in range(2))
-            t_both = min(wall(both_ways) for _ in range(2))
+            # the pipeline first, the bare link afterwards: a process that starts while uploads and downloads take turns (the
+            # flag above says so; it follows large frees, also those of the process that ran before) measures the link too
+            # low until some copy traffic has gone by, and the pipeline's own warm-up run is that traffic
             t_res = min(wall(resident_step) for _ in range(2))
             t_off = min(wall(lambda: offload_step(False)) for _ in range(2))
             t_mix = min(wall(lambda: offload_step(True)) for _ in range(2))
+            t_h2d = min(wall(only_h2d) for _ in range(2))
+            t_d2h = min(wall(only_d2h) for _ in range(2))
+            t_both = min(wall(both_ways) for _ in range(2))
             moved = n_host * nbytes
             t_dma = max(t_h2d, t_d2h)
             rows["offload"] = {
@@ -994,28 +998,39 @@ def run_tensor_lists(args, torch, ex, gen):
     def t(fn):
         return _event_time(torch, stream, fn, reps, 2)[1]
 
+    # host tables built once, as a trainer whose tensor list does not change would: the timed calls should not wait for Python
+    T_d32, T_s16, T_n = ex.elixir_ptr_table(d32), ex.elixir_ptr_table(s16), ex.elixir_i64_table(p_n)
+
     def reduce_list(acc):
-        ex.elixir_grad_reduce_multi_lp(d32, s16, p_n, ex.ELIXIR_LOWP_BF16, 0.25, acc, sh)
+        ex.elixir_grad_reduce_multi_lp(T_d32, T_s16, T_n, ex.ELIXIR_LOWP_BF16, 0.25, acc, sh)
 
     def reduce_chunks(acc):
         for c in range(nch):
             ex.elixir_grad_reduce_into_chunk(groups["chunk"][c], 0, groups["t16"][c], valid[c], 0.25, acc, sh)
 
+    seg_tables = {}
+    for esz, data in ((4, groups["t32"]), (2, groups["t16"])):
+        for per_tensor in (True, False):
+            seg_tables[esz, per_tensor] = []
+            for c in range(nch):
+                segs = by_chunk[c] if per_tensor else [(c, 0, valid[c])]
+                seg_tables[esz, per_tensor].append((ex.elixir_ptr_table([data[c][o:o + n] for _, o, n in segs]),
+                                                    ex.elixir_i64_table([n for _, _, n in segs]), ex.elixir_i64_table([o for _, o, _ in segs])))
+
     def pack(esz, per_tensor, unpack=False):
         chunks = groups["chunk"] if esz == 4 else groups["c16"]
-        data = groups["t32"] if esz == 4 else groups["t16"]
         fn = ex.elixir_chunk_unpack if unpack else ex.elixir_chunk_pack
+        tabs = seg_tables[esz, per_tensor]
         for c in range(nch):
-            segs = by_chunk[c] if per_tensor else [(c, 0, valid[c])]
-            fn(chunks[c], C, esz, [data[c][o:o + n] for _, o, n in segs], [n for _, _, n in segs], [o for _, o, _ in segs], sh)
+            fn(chunks[c], C, esz, tabs[c][0], tabs[c][1], tabs[c][2], sh)
 
-    set_views = {4: [groups["t32"][c][o:o + n] for c, o, n in pieces], 2: s16}     # built once: the timed call should not wait for Python
-    p_c, p_o = [c for c, _, _ in pieces], [o for _, o, _ in pieces]
+    set_views = {4: ex.elixir_ptr_table([groups["t32"][c][o:o + n] for c, o, n in pieces]), 2: T_s16}
+    set_chunks = {4: ex.elixir_ptr_table(groups["chunk"]), 2: ex.elixir_ptr_table(groups["c16"])}
+    T_c, T_o = ex.elixir_i64_table([c for c, _, _ in pieces]), ex.elixir_i64_table([o for _, o, _ in pieces])
 
     def pack_set(esz, unpack=False):
-        chunks = groups["chunk"] if esz == 4 else groups["c16"]
         fn = ex.elixir_chunks_unpack if unpack else ex.elixir_chunks_pack
-        fn(chunks, C, esz, set_views[esz], p_n, p_c, p_o, sh)
+        fn(set_chunks[esz], C, esz, set_views[esz], T_n, T_c, T_o, sh)
 
     res = {}
     for name, fn, nbytes in (

@@ -170,11 +170,27 @@ def _stream(stream) -> Optional[int]:
 
 
 def _i64_array(xs: Sequence[int]):
+    if isinstance(xs, ctypes.Array):     # a table built ahead with elixir_i64_table
+        return xs
     return (ctypes.c_int64 * len(xs))(*[int(x) for x in xs])
 
 
 def _ptr_array(xs):
+    if isinstance(xs, ctypes.Array):     # a table built ahead with elixir_ptr_table
+        return xs
     return (ctypes.c_void_p * len(xs))(*[_addr(x) for x in xs])
+
+
+def elixir_ptr_table(xs):
+    """The host table of addresses a list-taking call builds from `xs` on every call, built once.  A tensor list that does
+    not change from step to step (the gradients of a model, the chunks of a set) can be handed to those calls in this
+    form; the caller keeps the tensors alive."""
+    return _ptr_array(list(xs))
+
+
+def elixir_i64_table(xs):
+    """The host table of lengths / offsets / chunk indices a list-taking call takes, built once."""
+    return _i64_array(list(xs))
 
 
 # --------------------------------------------------------------------------- context

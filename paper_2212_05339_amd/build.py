@@ -14,7 +14,8 @@ HOST_SOURCES = ["host_adam.cpp", "benefit.cpp", "rcache_sim.cpp", "arena.cpp"]  
 #   separately rounded multiply/add of the gradient reduction stay separate.
 # -packed-fp32-ops off: keeps the compiler from forming packed fp32 instructions.
 HIPCC_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-ffp-contract=off",
-               "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wall", "-Wno-unused-command-line-argument"]
+               "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-mllvm", "-amdgpu-kernarg-preload-count=16",
+               "-Wall", "-Wno-unused-command-line-argument"]
 
 
 def build_library(verbose: bool = False) -> str:

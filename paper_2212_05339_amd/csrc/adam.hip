@@ -61,7 +61,7 @@ struct LaunchVec {
             const int64_t pairs = pairs_all < blocks * kAdamBlock ? pairs_all : blocks * kAdamBlock;
             hipLaunchKernelGGL((adam_vec_kernel<GRAD, OUT>), dim3((unsigned)blocks), dim3(kAdamBlock), kAdamLdsBytes, r.s,
                                r.p + at, r.m + at, r.v + at, (const void*)((const char*)r.g + at * grad_elem_size(GRAD)),
-                               OUT != kNone ? r.out + at : nullptr, pairs, c, r.d_scale, r.d_skip);
+                               OUT != kNone ? r.out + at : nullptr, pairs, r.d_scale, r.d_skip, c);
             at += pairs * kAdamVec;
             left -= pairs * kAdamVec;
         }
@@ -208,7 +208,7 @@ struct LaunchTiled {
                                OUT != kNone ? r.out : nullptr, pairs, d_c, r.d_scale, r.d_skip);
         else
             hipLaunchKernelGGL((adam_tiled_kernel<GRAD, OUT>), dim3((unsigned)blocks), dim3(kAdamBlock), kAdamLdsBytes, r.s, state, r.g,
-                               OUT != kNone ? r.out : nullptr, pairs, c, r.d_scale, r.d_skip);
+                               OUT != kNone ? r.out : nullptr, pairs, r.d_scale, r.d_skip, c);
     }
 };
 

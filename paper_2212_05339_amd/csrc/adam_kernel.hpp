@@ -135,9 +135,13 @@ __device__ __forceinline__ void adam_pair(float* master, float* exp_avg, float* 
 }
 
 // A wave of these kernels lives for one pair per lane, so every round trip it makes before its first vector load
-// costs bandwidth.  Left to itself the compiler fetches the length, tests it, and only then fetches the pointers
-// (and later the constants): dependent rounds of scalar loads.  fetch_together() makes the values it is given live at
-// one point, so their loads are issued back to back and waited for once.
+// costs bandwidth.  The single-chunk kernels take what the loads' addresses need (pointers, length) as their first
+// arguments, within the 14 dwords that the library's build has the hardware place in scalar registers when a wave
+// starts (kernel-argument preloading); the step constants follow and are fetched while the vector loads are in flight.
+// The batched kernels index a table by blockIdx.y, which cannot be preloaded: left to itself the compiler fetches the
+// length, tests it, and only then fetches the pointers (and later the constants), dependent rounds of scalar loads.
+// fetch_together() makes the values it is given live at one point, so their loads are issued back to back and waited
+// for once.
 template <typename T>
 __device__ __forceinline__ void keep_scalar(T v) {
     asm volatile("" ::"s"(v));
@@ -158,11 +162,8 @@ template <int GRAD, int OUT>
 __global__ __launch_bounds__(kAdamBlock) void adam_vec_kernel(float* __restrict__ master, float* __restrict__ exp_avg,
                                                              float* __restrict__ exp_avg_sq,
                                                              const void* grad, uint16_t* out,  // may be the same array
-                                                             int64_t n2, AdamConsts c,
-                                                             const float* __restrict__ d_grad_scale,
-                                                             const int32_t* __restrict__ d_skip) {
-    fetch_together(master, exp_avg, exp_avg_sq, grad, out, n2, d_grad_scale, d_skip);
-    fetch_together(c);
+                                                             int64_t n2, const float* __restrict__ d_grad_scale,
+                                                             const int32_t* __restrict__ d_skip, AdamConsts c) {
     const int64_t i = (int64_t)blockIdx.x * kAdamBlock + threadIdx.x;
     adam_pair<GRAD, OUT>(master, exp_avg, exp_avg_sq, grad, out, i, n2, c, d_grad_scale, d_skip);
 }
@@ -219,11 +220,9 @@ __global__ __launch_bounds__(kAdamBlock) void adam_multi_kernel(AdamMultiTable t
 // with base = state + 2 T (e / T).
 template <int GRAD, int OUT>
 __global__ __launch_bounds__(kAdamBlock) void adam_tiled_kernel(float* __restrict__ state, const void* grad,
-                                                               uint16_t* out, int64_t n2, AdamConsts c,
+                                                               uint16_t* out, int64_t n2,
                                                                const float* __restrict__ d_grad_scale,
-                                                               const int32_t* __restrict__ d_skip) {
-    fetch_together(state, grad, out, n2, d_grad_scale, d_skip);
-    fetch_together(c);
+                                                               const int32_t* __restrict__ d_skip, AdamConsts c) {
     const int64_t first = (int64_t)blockIdx.x * kAdamBlock;   // first pair of this workgroup
     float* base = state + 2 * kStateTile * (first / (kStateTile / kAdamVec));
     adam_pair<GRAD, OUT>(base, base + kStateTile, base + 2 * kStateTile, grad, out, first + threadIdx.x, n2, c, d_grad_scale, d_skip);
@@ -241,7 +240,6 @@ __global__ __launch_bounds__(kAdamBlock) void adam_tiled_dev_kernel(float* __res
                                                                    const AdamConsts* __restrict__ d_c,
                                                                    const float* __restrict__ d_grad_scale,
                                                                    const int32_t* __restrict__ d_skip) {
-    fetch_together(state, grad, out, n2, d_c, d_grad_scale, d_skip);
     const AdamConsts c = *d_c;
     const int64_t first = (int64_t)blockIdx.x * kAdamBlock;
     float* base = state + 2 * kStateTile * (first / (kStateTile / kAdamVec));

@@ -220,12 +220,15 @@ __global__ __launch_bounds__(kSumsqBlock) void sumsq_lowp_kernel(LowpChunkTable 
 constexpr int kFusedBlock = 64;
 
 template <bool ACC, bool FP16, int NSRC>
-__global__ __launch_bounds__(kFusedBlock) void reduce_sumsq_kernel(float* __restrict__ dst, SrcTable srcs, int64_t n4, int64_t valid,
-                                                                  float scale, double* __restrict__ stage) {
+__global__ __launch_bounds__(kFusedBlock) void reduce_sumsq_kernel(float* __restrict__ dst, const uint16_t* __restrict__ src0, int64_t n4,
+                                                                  float scale, const uint16_t* __restrict__ src1,
+                                                                  const uint16_t* __restrict__ src2, const uint16_t* __restrict__ src3,
+                                                                  int64_t valid, double* __restrict__ stage) {
+    // argument order: what the loads need comes first, within the dwords preloaded into scalar registers (see reduce_vec_kernel)
     const int64_t i = (int64_t)blockIdx.x * kFusedBlock + threadIdx.x;
     double x = 0.0;
     if (i < n4) {
-        const f32x4 r = reduce_group<ACC, FP16, NSRC>(dst, srcs, i, scale);
+        const f32x4 r = reduce_group<ACC, FP16, NSRC>(dst, SrcTable{{src0, src1, src2, src3}}, i, scale);
         const int64_t k = i * 4;
         if (k + 0 < valid) x = fma((double)r.x, (double)r.x, x);
         if (k + 1 < valid) x = fma((double)r.y, (double)r.y, x);
@@ -278,10 +281,10 @@ hipError_t launch_fused(float* dst, const SrcTable& srcs, int n_src, int64_t n, 
     if (blocks > 0) {
         const dim3 grid((unsigned)blocks), block(kFusedBlock);
         switch (n_src) {
-            case 1: hipLaunchKernelGGL((reduce_sumsq_kernel<ACC, FP16, 1>), grid, block, 0, s, dst, srcs, n4, valid, scale, stage); break;
-            case 2: hipLaunchKernelGGL((reduce_sumsq_kernel<ACC, FP16, 2>), grid, block, 0, s, dst, srcs, n4, valid, scale, stage); break;
-            case 3: hipLaunchKernelGGL((reduce_sumsq_kernel<ACC, FP16, 3>), grid, block, 0, s, dst, srcs, n4, valid, scale, stage); break;
-            default: hipLaunchKernelGGL((reduce_sumsq_kernel<ACC, FP16, 4>), grid, block, 0, s, dst, srcs, n4, valid, scale, stage); break;
+            case 1: hipLaunchKernelGGL((reduce_sumsq_kernel<ACC, FP16, 1>), grid, block, 0, s, dst, srcs.p[0], n4, scale, srcs.p[1], srcs.p[2], srcs.p[3], valid, stage); break;
+            case 2: hipLaunchKernelGGL((reduce_sumsq_kernel<ACC, FP16, 2>), grid, block, 0, s, dst, srcs.p[0], n4, scale, srcs.p[1], srcs.p[2], srcs.p[3], valid, stage); break;
+            case 3: hipLaunchKernelGGL((reduce_sumsq_kernel<ACC, FP16, 3>), grid, block, 0, s, dst, srcs.p[0], n4, scale, srcs.p[1], srcs.p[2], srcs.p[3], valid, stage); break;
+            default: hipLaunchKernelGGL((reduce_sumsq_kernel<ACC, FP16, 4>), grid, block, 0, s, dst, srcs.p[0], n4, scale, srcs.p[1], srcs.p[2], srcs.p[3], valid, stage); break;
         }
         if (const hipError_t e = hipGetLastError()) return e;
     }

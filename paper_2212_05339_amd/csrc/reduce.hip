@@ -13,6 +13,7 @@ using namespace elixir;
 
 namespace {
 
+static_assert(kMaxSources == 4, "reduce_vec_kernel names its sources one by one");
 constexpr int kVecBlock = 64;   // one 4-element group per thread, one single-wavefront workgroup per 256 elements, no
                                 // loop: workgroups are dispatched in index order, so the streams advance as sequential
                                 // fronts, with 128-bit accesses at full residency.  Measured on 64Mi elements, 64 / 128 /
@@ -23,11 +24,16 @@ constexpr int kVecBlock = 64;   // one 4-element group per thread, one single-wa
 constexpr int64_t kMaxBlocksPerLaunch = ((1ll << 32) - 1) / 256;
 constexpr int64_t kMaxRowTiles = 1ll << 22;
 
-// n4 complete groups of 4 elements, one per thread; NSRC gradient arrays in one pass.
+// n4 complete groups of 4 elements, one per thread; NSRC gradient arrays in one pass.  Plain pointer arguments, what
+// every pass needs first: the build has the first 14 dwords of a kernel's arguments placed in scalar registers when a
+// wave starts (kernel-argument preloading, which does not reach into a table passed by value), so these short-lived
+// waves issue their vector loads without waiting for a scalar load.
 template <bool ACC, bool FP16, int NSRC>
-__global__ __launch_bounds__(kVecBlock) void reduce_vec_kernel(float* __restrict__ dst, SrcTable srcs, int64_t n4, float scale) {
+__global__ __launch_bounds__(kVecBlock) void reduce_vec_kernel(float* __restrict__ dst, const uint16_t* __restrict__ src0, int64_t n4,
+                                                              float scale, const uint16_t* __restrict__ src1,
+                                                              const uint16_t* __restrict__ src2, const uint16_t* __restrict__ src3) {
     const int64_t i = (int64_t)blockIdx.x * kVecBlock + threadIdx.x;
-    if (i < n4) (void)reduce_group<ACC, FP16, NSRC>(dst, srcs, i, scale);
+    if (i < n4) (void)reduce_group<ACC, FP16, NSRC>(dst, SrcTable{{src0, src1, src2, src3}}, i, scale);
 }
 
 // elements [first, n), any alignment
@@ -81,7 +87,8 @@ void launch_vec(float* dst, const SrcTable& srcs, int64_t n4, float scale, hipSt
         const int64_t cnt = n4 - at < blocks * kVecBlock ? n4 - at : blocks * kVecBlock;
         SrcTable t;
         for (int k = 0; k < kMaxSources; ++k) t.p[k] = k < NSRC ? srcs.p[k] + at * 4 : nullptr;
-        hipLaunchKernelGGL((reduce_vec_kernel<ACC, FP16, NSRC>), dim3((unsigned)blocks), dim3(kVecBlock), 0, s, dst + at * 4, t, cnt, scale);
+        hipLaunchKernelGGL((reduce_vec_kernel<ACC, FP16, NSRC>), dim3((unsigned)blocks), dim3(kVecBlock), 0, s, dst + at * 4, t.p[0], cnt, scale,
+                           t.p[1], t.p[2], t.p[3]);
         at += cnt;
     }
 }
