@@ -17,6 +17,7 @@
 #include <algorithm>
 
 #include "common.hpp"
+#include "row_plan.hpp"
 
 using namespace elixir;
 
@@ -74,6 +75,33 @@ __global__ __launch_bounds__(kCopyBlock) void segment_copy_kernel(SegTable tab) 
         done = 0;
     }
     if (done < len) move_units<uint16_t>(dst + done, src ? src + done : nullptr, (len - done) >> 1);
+}
+
+// A whole set of slices as the rows of a 2-D grid (see row_plan.hpp): row r moves n16[r] units of 16 bytes from src[r]
+// (nullptr: zero bits) to dst[r], both 16-byte aligned, one unit per lane, workgroup x of the row its x-th KiB.  No
+// search for the owner of a tile, and a few launches for a set instead of one per chunk.
+constexpr int kCopyRowsMax = 160;   // 160 x 24 bytes of table stay below the 4 KB of kernel arguments
+constexpr int64_t kMaxRowTiles = 1ll << 22;
+struct CopyRowTable {
+    char* dst[kCopyRowsMax];
+    const char* src[kCopyRowsMax];
+    int64_t n16[kCopyRowsMax];
+};
+static_assert(sizeof(CopyRowTable) + 16 <= 4096, "the table must fit the kernel arguments");
+
+__global__ __launch_bounds__(kCopyBlock) void copy_rows_kernel(CopyRowTable tab) {
+    const int r = blockIdx.y;
+    char* dst = tab.dst[r];
+    const char* src = tab.src[r];
+    const int64_t n16 = tab.n16[r];
+    asm volatile("" ::"s"(dst), "s"(src), "s"(n16));  // the three table entries in one round of scalar loads
+    if ((int64_t)blockIdx.x * kCopyBlock >= n16) return;  // past the end of a shorter row (uniform per workgroup)
+    const int64_t i = (int64_t)blockIdx.x * kCopyBlock + threadIdx.x;
+    if (i < n16) {
+        u32x4 v = u32x4(0);
+        if (src) v = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(src) + i);
+        __builtin_nontemporal_store(v, reinterpret_cast<u32x4*>(dst) + i);
+    }
 }
 
 struct Seg {
@@ -139,6 +167,64 @@ int launch_segments(const SegTableHost& segs, hipStream_t s, const char* what, s
     return ELIXIR_OK;
 }
 
+// All segments of the table in few launches: those whose two addresses are 16-byte aligned go through the row plan
+// (whole 16-byte units), the others and the last bytes of a segment through the tile kernel above.
+struct CopyRows {
+    const SegTableHost& segs;
+    hipStream_t s;
+    const char* what;
+    CopyRowTable tab;
+    int in_table = 0;
+
+    void add(int k, int64_t first_tile, int64_t n_tiles) {
+        const Seg& g = segs.p[k];
+        int64_t n16 = g.bytes / 16 - first_tile * kCopyBlock;
+        if (n16 > n_tiles * kCopyBlock) n16 = n_tiles * kCopyBlock;
+        tab.dst[in_table] = g.dst + first_tile * kTileBytes;
+        tab.src[in_table] = g.src ? g.src + first_tile * kTileBytes : nullptr;
+        tab.n16[in_table] = n16;
+        ++in_table;
+    }
+    int flush(int64_t row_tiles) {
+        for (int j = in_table; j < kCopyRowsMax; ++j) {
+            tab.dst[j] = nullptr;
+            tab.src[j] = nullptr;
+            tab.n16[j] = 0;
+        }
+        hipLaunchKernelGGL(copy_rows_kernel, dim3((unsigned)row_tiles, (unsigned)in_table), dim3(kCopyBlock), 0, s, tab);
+        in_table = 0;
+        ELIXIR_LAUNCH_CHECK(what);
+        return ELIXIR_OK;
+    }
+};
+
+int launch_rows(const SegTableHost& segs, hipStream_t s, const char* what) {
+    if (segs.n > (size_t)INT32_MAX) return fail(ELIXIR_ECAP, "%s: too many slices", what);
+    auto vec = [&](int k) {
+        const Seg& g = segs.p[k];
+        return g.bytes >= 16 && aligned(g.dst, 16) && aligned(g.src, 16);  // a null source (zero fill) counts as aligned
+    };
+    // what the rows do not take: unaligned segments whole, and the last bytes (fewer than 16) of the others
+    SegTableHost rest;
+    size_t n_rest = 0;
+    for (size_t k = 0; k < segs.n; ++k) n_rest += !vec((int)k) || segs.p[k].bytes % 16;
+    if (!rest.reserve(n_rest)) return fail(ELIXIR_EINVAL, "%s: out of host memory", what);
+    for (size_t k = 0; k < segs.n; ++k) {
+        const Seg& g = segs.p[k];
+        if (g.bytes == 0) continue;
+        if (!vec((int)k)) rest.push(g);
+        else if (g.bytes % 16) {
+            const int64_t done = g.bytes / 16 * 16;
+            rest.push({g.src ? g.src + done : nullptr, g.dst + done, g.bytes - done});
+        }
+    }
+    if (rest.n)
+        if (const int rc = launch_segments(rest, s, what)) return rc;
+    CopyRows rows{segs, s, what};
+    auto tiles = [&](int k) -> int64_t { return vec(k) ? (segs.p[k].bytes / 16 + kCopyBlock - 1) / kCopyBlock : 0; };
+    return plan_rows((int)segs.n, tiles, 1, kCopyRowsMax, kMaxRowTiles, rows);
+}
+
 // Validates the slices and returns their indices ordered by offset (empty slices dropped).
 int check_slices(const char* what, const void* chunk, int64_t chunk_elems, int elem_size, const void* const* tensors,
                  const int64_t* numel, const int64_t* offset, int T, OrderTable* order) {
@@ -188,7 +274,7 @@ int elixir_chunk_pack_impl(void* d_chunk, int64_t chunk_elems, int elem_size, co
         pos = offset[i] + numel[i];
     }
     if (pos < chunk_elems) segs.push({nullptr, base + pos * es, (chunk_elems - pos) * es});
-    return launch_segments(segs, (hipStream_t)stream, what);
+    return launch_rows(segs, (hipStream_t)stream, what);
 }
 }  // namespace
 
@@ -214,7 +300,7 @@ int elixir_chunk_unpack_impl(const void* d_chunk, int64_t chunk_elems, int elem_
         const int i = order.p[k];
         segs.push({base + offset[i] * es, static_cast<char*>(tensors[i]), numel[i] * es});
     }
-    return launch_segments(segs, (hipStream_t)stream, what);
+    return launch_rows(segs, (hipStream_t)stream, what);
 }
 }  // namespace
 
@@ -228,7 +314,7 @@ extern "C" int elixir_chunk_unpack(const void* d_chunk, int64_t chunk_elems, int
 // ---- a whole parameter set at once ------------------------------------------------------------------------------
 //
 // The per-chunk calls above cost one launch per chunk; at set-up a trainer packs every chunk, and the launch boundaries
-// then show (26 launches for the 1.5B set against 7 here).  These take the layout plan as it stands: tensor i occupies
+// then show (26 launches for the 1.5B set against a handful here).  These take the layout plan as it stands: tensor i occupies
 // the linear element range [chunk_id[i] * C + offset[i], + numel[i]) of the chunk sequence, so a tensor longer than the
 // rest of its chunk simply continues at the start of the next one.
 
@@ -267,23 +353,13 @@ int chunks_copy(const char* what, void* const* d_chunks, int n_chunks, int64_t c
             return fail(ELIXIR_EINVAL, "%s: tensors %d and %d overlap", what, order.p[k - 1], order.p[k]);
     SegTableHost segs;
     if (!segs.reserve(2 * n_pieces + 2 * (size_t)n_chunks + 2)) return fail(ELIXIR_EINVAL, "%s: out of host memory", what);
-    // One launch per chunk (per 96 slices of a chunk): measured on the 1.5B set, launches that each sweep one chunk move
-    // 77% of the HBM peak, launches that sweep 96 slices across several chunks 75% (bf16: 75% against 70%) -- the
-    // owner of a tile is found by a search over the launch's table, which is shorter per chunk, and on this part a
-    // copy gains nothing from launches longer than a chunk.  The slices arrive in linear order, so a chunk's slices are
-    // complete when the first slice of a later chunk arrives.
-    int64_t cur_chunk = -1;
-    size_t begin = 0;
-    int rc = ELIXIR_OK;
+    // All slices are collected first (cut at chunk boundaries), then launched as rows: measured on the 1.5B set, one
+    // tile-kernel launch per chunk moves 77% of the HBM peak (26 launches with 5-7 us between them, and a search over
+    // the launch's table in every workgroup), tile-kernel launches of 96 slices across chunks 75%.
     // a run of the linear range, cut at chunk boundaries: src == nullptr fills with zero bits (pack only)
     auto emit = [&](int64_t lin, int64_t count, const char* src) {
-        while (count > 0 && rc == ELIXIR_OK) {
+        while (count > 0) {
             const int64_t c = lin / C, o = lin % C, take = count < C - o ? count : C - o;
-            if (c != cur_chunk) {
-                if (segs.n > begin) rc = launch_segments(segs, stream, what, begin, segs.n);
-                begin = segs.n;
-                cur_chunk = c;
-            }
             char* chunk = static_cast<char*>(d_chunks[c]) + o * es;
             if (PACK) segs.push({src, chunk, take * es});
             else segs.push({chunk, const_cast<char*>(src), take * es});
@@ -300,8 +376,7 @@ int chunks_copy(const char* what, void* const* d_chunks, int n_chunks, int64_t c
         pos = start(i) + numel[i];
     }
     if (PACK && pos < total) emit(pos, total - pos, nullptr);
-    if (rc == ELIXIR_OK && segs.n > begin) rc = launch_segments(segs, stream, what, begin, segs.n);
-    return rc;
+    return launch_rows(segs, stream, what);
 }
 
 }  // namespace

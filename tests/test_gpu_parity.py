@@ -133,13 +133,18 @@ def test_pack_misaligned_tensor_pointers_and_subset_unpack():
 
 @pytest.mark.parametrize("dtype", [np.float32, np.uint16])
 @pytest.mark.parametrize("policy", [0, 1, 2])
-def test_whole_set_pack_unpack_match_the_oracle_chunk_by_chunk(dtype, policy):
+@pytest.mark.parametrize("grain", [1, 64])
+def test_whole_set_pack_unpack_match_the_oracle_chunk_by_chunk(dtype, policy, grain):
     """elixir_chunks_pack / _unpack take the layout plan as it stands (a tensor that outgrows its chunk continues in the
     next one); the oracle packs chunk by chunk with the tensor cut into pieces by hand.  Several chunks, more slices than
-    one launch's table holds, ragged and oversize tensors, zero-length tensors, untouched bytes preset to a pattern."""
+    one launch's table holds, ragged and oversize tensors, zero-length tensors, untouched bytes preset to a pattern.
+    grain 1: lengths of any kind (most slices are not 16-byte aligned on both sides); grain 64: multiples of 64 elements as
+    in a transformer (every slice aligned: the launches with one row per slice take them all)."""
     rng = np.random.default_rng(100 + policy)
-    C = 50_000
+    C = 50_000 if grain == 1 else 65_536 * 3
     numels = [int(x) for x in rng.integers(0, 3000, size=150)] + [120_001, 7, 50_000, 1, 99_999] + [int(x) for x in rng.integers(1, 900, size=40)]
+    if grain > 1:
+        numels = [n // 8 * grain for n in numels] + [C, 2 * C + 64, 1 << 20]
     cid, off, valid = orc.layout_plan(numels, C, policy, 1)
     nch = len(valid)
     tensors = _random_tensors(rng, numels, dtype)
@@ -244,6 +249,47 @@ def test_grad_reduce_multi_is_bit_identical_to_single_calls_and_the_oracle(fmt):
     assert np.array_equal(got.view(np.uint32), host(d_single).view(np.uint32))
     assert np.array_equal(got.view(np.uint32), want.view(np.uint32))
     assert np.all(got[:4] == 1.5) and np.all(got[-5:] == 1.5)        # nothing outside the slices was touched
+
+
+def test_grad_reduce_multi_small_tensor_table_limits():
+    """The compact table of the small-tensor launch at its limits: more small tensors than one table holds (400), the
+    longest tensor it takes (65,535 groups of 4) next to the shortest it does not, and tensors whose destinations lie
+    more than 64 GiB and whose gradients lie more than 32 GiB from the lowest one (slices at both ends of one 70 GiB
+    allocation, of which only the slices are touched), which must take the ordinary table: bit-identical to the oracle."""
+    GiB = 1 << 30
+    big = torch.empty(70 * GiB, dtype=torch.int8, device=DEV)
+    rng = np.random.default_rng(11)
+    lens = [int(x) for x in rng.integers(1, 2000, size=440)] + [262140, 262144, 1600, 4800, 6400] + [1600, 3, 4804]
+    far = len(lens) - 3                                                # the last three lie at the far end
+    dst_at, src_at, d_dst, d_src, gs = [], [], [], [], []
+    d_near, d_far, s_near, s_far = 0, 66 * GiB, 1 * GiB, 34 * GiB + GiB // 2
+    for i, n in enumerate(lens):
+        if i < far:
+            da, sa = d_near, s_near
+            d_near += (4 * n + 15) // 16 * 16 + (16 if i % 5 == 0 else 0)
+            s_near += (2 * n + 7) // 8 * 8 + (8 if i % 7 == 0 else 0)
+        else:
+            da, sa = d_far, s_far
+            d_far += (4 * n + 15) // 16 * 16
+            s_far += (2 * n + 7) // 8 * 8
+        dst_at.append(da)
+        src_at.append(sa)
+        g = gen.fill_bf16(gen.stream_key(91, gen.TAG_GRAD, 0, i), 0, n, 0.02, zero_pct=2)
+        gs.append(g)
+        d_dst.append(big[da:da + 4 * n].view(torch.float32))
+        d_src.append(big[sa:sa + 2 * n].view(torch.int16))
+        d_dst[-1].fill_(1.5)
+        d_src[-1].copy_(dev(g.view(np.int16)))
+    assert d_near < GiB and s_near < 34 * GiB
+    for acc in (False, True):
+        ex.elixir_grad_reduce_multi_lp(d_dst, d_src, lens, ex.ELIXIR_LOWP_BF16, 0.3, acc)
+    sync()
+    for i, n in enumerate(lens):
+        want = np.full(n, 1.5, np.float32)
+        for acc in (False, True):
+            orc.grad_reduce_into_chunk(want, 0, gs[i], 0.3, acc)
+        assert np.array_equal(host(d_dst[i]).view(np.uint32), want.view(np.uint32)), (i, n)
+    del d_dst, d_src, big
 
 
 def test_grad_reduce_multi_errors_and_empty():
