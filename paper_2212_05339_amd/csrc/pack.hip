@@ -77,30 +77,24 @@ __global__ __launch_bounds__(kCopyBlock) void segment_copy_kernel(SegTable tab) 
     if (done < len) move_units<uint16_t>(dst + done, src ? src + done : nullptr, (len - done) >> 1);
 }
 
-// A whole set of slices as the rows of a 2-D grid (see row_plan.hpp): row r moves n16[r] units of 16 bytes from src[r]
-// (nullptr: zero bits) to dst[r], both 16-byte aligned, one unit per lane, workgroup x of the row its x-th KiB.  No
-// search for the owner of a tile, and a few launches for a set instead of one per chunk.
-constexpr int kCopyRowsMax = 160;   // 160 x 24 bytes of table stay below the 4 KB of kernel arguments
+// Slices as the rows of a 2-D grid (see row_plan.hpp): row r moves count[r] units of 16 bytes from its source (none:
+// zero bits) to its destination, both 16-byte aligned, one unit per lane, workgroup x of the row its x-th KiB.  No
+// search for the owner of a tile, up to 336 rows per launch.
 constexpr int64_t kMaxRowTiles = 1ll << 22;
-struct CopyRowTable {
-    char* dst[kCopyRowsMax];
-    const char* src[kCopyRowsMax];
-    int64_t n16[kCopyRowsMax];
-};
-static_assert(sizeof(CopyRowTable) + 16 <= 4096, "the table must fit the kernel arguments");
 
-__global__ __launch_bounds__(kCopyBlock) void copy_rows_kernel(CopyRowTable tab) {
+__global__ __launch_bounds__(kCopyBlock) void copy_rows_kernel(CompactRows tab) {
     const int r = blockIdx.y;
-    char* dst = tab.dst[r];
-    const char* src = tab.src[r];
-    const int64_t n16 = tab.n16[r];
-    asm volatile("" ::"s"(dst), "s"(src), "s"(n16));  // the three table entries in one round of scalar loads
-    if ((int64_t)blockIdx.x * kCopyBlock >= n16) return;  // past the end of a shorter row (uniform per workgroup)
-    const int64_t i = (int64_t)blockIdx.x * kCopyBlock + threadIdx.x;
-    if (i < n16) {
+    const uint32_t d_off = tab.dst_off[r], s_off = tab.src_off[r], n16 = tab.count[r];
+    char* dst_base = tab.dst_base;
+    const char* src_base = tab.src_base;
+    asm volatile("" ::"s"(d_off), "s"(s_off), "s"(n16), "s"(dst_base), "s"(src_base));  // one round of scalar loads
+    const uint32_t phase = d_off % kCopyBlock;  // dst_base is KiB-aligned: the row starts this many units past a KiB boundary
+    if (blockIdx.x * kCopyBlock >= n16 + phase) return;  // past the end of a shorter row (uniform per workgroup)
+    const int32_t i = (int32_t)(blockIdx.x * kCopyBlock + threadIdx.x) - (int32_t)phase;  // the first workgroup's first lanes idle
+    if (i >= 0 && (uint32_t)i < n16) {
         u32x4 v = u32x4(0);
-        if (src) v = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(src) + i);
-        __builtin_nontemporal_store(v, reinterpret_cast<u32x4*>(dst) + i);
+        if (s_off != kNoSource) v = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(src_base) + s_off + i);
+        __builtin_nontemporal_store(v, reinterpret_cast<u32x4*>(dst_base) + d_off + i);
     }
 }
 
@@ -169,33 +163,28 @@ int launch_segments(const SegTableHost& segs, hipStream_t s, const char* what, s
 
 // All segments of the table in few launches: those whose two addresses are 16-byte aligned go through the row plan
 // (whole 16-byte units), the others and the last bytes of a segment through the tile kernel above.
-struct CopyRows {
-    const SegTableHost& segs;
+struct CopyLaunch {
     hipStream_t s;
     const char* what;
-    CopyRowTable tab;
-    int in_table = 0;
-
-    void add(int k, int64_t first_tile, int64_t n_tiles) {
-        const Seg& g = segs.p[k];
-        int64_t n16 = g.bytes / 16 - first_tile * kCopyBlock;
-        if (n16 > n_tiles * kCopyBlock) n16 = n_tiles * kCopyBlock;
-        tab.dst[in_table] = g.dst + first_tile * kTileBytes;
-        tab.src[in_table] = g.src ? g.src + first_tile * kTileBytes : nullptr;
-        tab.n16[in_table] = n16;
-        ++in_table;
-    }
-    int flush(int64_t row_tiles) {
-        for (int j = in_table; j < kCopyRowsMax; ++j) {
-            tab.dst[j] = nullptr;
-            tab.src[j] = nullptr;
-            tab.n16[j] = 0;
-        }
-        hipLaunchKernelGGL(copy_rows_kernel, dim3((unsigned)row_tiles, (unsigned)in_table), dim3(kCopyBlock), 0, s, tab);
-        in_table = 0;
+    int operator()(const CompactRows& tab, int rows, int64_t longest) const {
+        hipLaunchKernelGGL(copy_rows_kernel, dim3((unsigned)longest, (unsigned)rows), dim3(kCopyBlock), 0, s, tab);
         ELIXIR_LAUNCH_CHECK(what);
         return ELIXIR_OK;
     }
+};
+
+struct CopyRows {
+    const SegTableHost& segs;
+    CompactRowBuilder<16, 16, kCopyBlock, CopyLaunch> table;
+    int rc = ELIXIR_OK;
+
+    void add(int k, int64_t first_tile, int64_t n_tiles) {
+        const Seg& g = segs.p[k];
+        int64_t u0, u1;  // the 16-byte units of the segment that these workgroups move
+        row_piece<16, kCopyBlock>(g.dst, g.bytes / 16, first_tile, n_tiles, &u0, &u1);
+        if (rc == ELIXIR_OK) rc = table.add(g.dst + u0 * 16, g.src ? g.src + u0 * 16 : nullptr, u1 - u0);
+    }
+    int flush(int64_t) { return rc != ELIXIR_OK ? rc : table.flush(); }
 };
 
 int launch_rows(const SegTableHost& segs, hipStream_t s, const char* what) {
@@ -220,9 +209,9 @@ int launch_rows(const SegTableHost& segs, hipStream_t s, const char* what) {
     }
     if (rest.n)
         if (const int rc = launch_segments(rest, s, what)) return rc;
-    CopyRows rows{segs, s, what};
-    auto tiles = [&](int k) -> int64_t { return vec(k) ? (segs.p[k].bytes / 16 + kCopyBlock - 1) / kCopyBlock : 0; };
-    return plan_rows((int)segs.n, tiles, 1, kCopyRowsMax, kMaxRowTiles, rows);
+    CopyRows rows{segs, CompactRowBuilder<16, 16, kCopyBlock, CopyLaunch>(CopyLaunch{s, what})};
+    auto tiles = [&](int k) -> int64_t { return vec(k) ? row_tiles<16, kCopyBlock>(segs.p[k].dst, segs.p[k].bytes / 16) : 0; };
+    return plan_rows((int)segs.n, tiles, 1, kCompactRows, kMaxRowTiles, rows);
 }
 
 // Validates the slices and returns their indices ordered by offset (empty slices dropped).

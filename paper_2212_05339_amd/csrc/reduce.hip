@@ -50,61 +50,30 @@ __global__ __launch_bounds__(256) void reduce_scalar_kernel(float* dst, const ui
 // (row_plan.hpp cuts the tensors into equal pieces plus a tail each and groups rows of similar length), workgroups
 // are dispatched x-first, so piece after piece is swept front to back exactly as by reduce_vec_kernel; workgroups
 // past the end of a shorter row exit at once.  The table is a kernel argument and blockIdx.y indexes it directly: a
-// wave's kernel-argument loads all go out together.  (Numbering the tiles of all tensors consecutively and searching
+// wave's kernel-argument loads all go out together.  Launch boundaries cost as well (four launches of 160 equal rows
+// move 82.4% of the HBM peak where one launch of the same bytes moves 83.9%), hence the compact table.  (Numbering the tiles of all tensors consecutively and searching
 // the table for the owner of a tile costs each of these short-lived waves ~200 scalar instructions or a chain of
 // dependent loads; measured, it was no faster than one launch per tensor.)
-constexpr int kReduceMultiMax = 160;  // rows per launch: 160 x 24 bytes of table stay below the 4 KB of kernel arguments
 constexpr int kMultiBlock = 64;       // single-wavefront workgroups, as in reduce_vec_kernel
-struct ReduceMultiTable {
-    float* dst[kReduceMultiMax];           // 16-byte aligned
-    const uint16_t* src[kReduceMultiMax];  // 8-byte aligned
-    int64_t n4[kReduceMultiMax];           // complete groups of 4 elements
-};
-static_assert(sizeof(ReduceMultiTable) + 16 <= 4096, "the table must fit the kernel arguments");
 
+// Rows in the compact form of row_plan.hpp (two bases per launch, 32-bit offsets in groups of 4 elements): 336 rows per
+// launch, so the 611 pieces and 383 small tensors of the 1.5B set take four launches.
 template <bool ACC, bool FP16>
-__global__ __launch_bounds__(kMultiBlock) void reduce_multi_kernel(ReduceMultiTable tab, float scale) {
-    const int seg = blockIdx.y;
+__global__ __launch_bounds__(kMultiBlock) void reduce_rows_kernel(CompactRows tab, float scale) {
+    const int r = blockIdx.y;
     // A wave lives for one group per lane, so what it waits for before its first memory instruction counts: the row's
-    // three table entries and the scale are fetched together, ahead of the test (left to itself the compiler fetches
-    // the length, tests, fetches the source, loads, fetches the destination: three round trips instead of one).
-    float* dst = tab.dst[seg];
-    const uint16_t* src = tab.src[seg];
-    const int64_t n4 = tab.n4[seg];
-    asm volatile("" ::"s"(dst), "s"(src), "s"(n4), "s"(scale));
-    if ((int64_t)blockIdx.x * kMultiBlock >= n4) return;  // a row past the end of a shorter piece (uniform per workgroup)
-    const int64_t i = (int64_t)blockIdx.x * kMultiBlock + threadIdx.x;
-    if (i < n4) (void)reduce_group<ACC, FP16, 1>(dst, SrcTable{{src}}, i, scale);
-}
-
-// Small tensors (biases, norm weights: two thirds of a transformer's tensors, a few KB each) in a launch of their own
-// with a compact table: 10 bytes per row instead of 24 (32-bit offsets from the lowest destination and the lowest
-// source in units of one group, a 16-bit length), so 400 rows travel in the kernel arguments and the 383 small
-// tensors of the 1.5B set take one launch of 5 us instead of three.  A tensor qualifies with fewer than 2^16 groups
-// and offsets that fit (within 64 GiB of the lowest destination, 32 GiB of the lowest source); the others take the
-// table above.
-constexpr int kReduceSmallMax = 400;
-constexpr int64_t kSmallGroups = 1 << 16;
-struct ReduceSmallTable {
-    float* dst_base;
-    const uint16_t* src_base;
-    uint32_t dst_off[kReduceSmallMax];  // groups of 4 floats from dst_base
-    uint32_t src_off[kReduceSmallMax];  // groups of 4 gradients from src_base
-    uint16_t n4[kReduceSmallMax];
-};
-static_assert(sizeof(ReduceSmallTable) + 16 <= 4096, "the table must fit the kernel arguments");
-
-template <bool ACC, bool FP16>
-__global__ __launch_bounds__(kMultiBlock) void reduce_small_kernel(ReduceSmallTable tab, float scale) {
-    const int seg = blockIdx.y;
-    const uint32_t d_off = tab.dst_off[seg], s_off = tab.src_off[seg];
-    const int64_t n4 = tab.n4[seg];
-    float* dst_base = tab.dst_base;
-    const uint16_t* src_base = tab.src_base;
-    asm volatile("" ::"s"(d_off), "s"(s_off), "s"(n4), "s"(dst_base), "s"(src_base), "s"(scale));  // one round of scalar loads
-    if ((int64_t)blockIdx.x * kMultiBlock >= n4) return;
-    const int64_t i = (int64_t)blockIdx.x * kMultiBlock + threadIdx.x;
-    if (i < n4) (void)reduce_group<ACC, FP16, 1>(dst_base + (int64_t)d_off * 4, SrcTable{{src_base + (int64_t)s_off * 4}}, i, scale);
+    // three table entries, the bases and the scale are fetched together, ahead of the test (left to itself the
+    // compiler fetches the length, tests, fetches the source, loads, fetches the destination: three round trips
+    // instead of one).
+    const uint32_t d_off = tab.dst_off[r], s_off = tab.src_off[r], n4 = tab.count[r];
+    float* dst_base = reinterpret_cast<float*>(tab.dst_base);
+    const uint16_t* src_base = reinterpret_cast<const uint16_t*>(tab.src_base);
+    asm volatile("" ::"s"(d_off), "s"(s_off), "s"(n4), "s"(dst_base), "s"(src_base), "s"(scale));
+    const uint32_t phase = d_off % kMultiBlock;  // dst_base is KiB-aligned: the row starts this many groups past a KiB boundary
+    if (blockIdx.x * kMultiBlock >= n4 + phase) return;  // a row past the end of a shorter piece (uniform per workgroup)
+    const int32_t i = (int32_t)(blockIdx.x * kMultiBlock + threadIdx.x) - (int32_t)phase;  // the first workgroup's first lanes idle
+    if (i >= 0 && (uint32_t)i < n4)
+        (void)reduce_group<ACC, FP16, 1>(dst_base + (int64_t)d_off * 4, SrcTable{{src_base + (int64_t)s_off * 4}}, i, scale);
 }
 
 // The vector part of a pass over NSRC sources: n4 groups of 4 elements starting at dst / srcs.
@@ -238,73 +207,36 @@ namespace {
 
 // Rows of the batched reduction: a tile is what one workgroup handles (kMultiBlock groups of 4 elements).
 template <bool ACC, bool FP16>
+struct ReduceLaunch {
+    float scale;
+    hipStream_t s;
+    int operator()(const CompactRows& tab, int rows, int64_t longest) const {
+        hipLaunchKernelGGL((reduce_rows_kernel<ACC, FP16>), dim3((unsigned)longest, (unsigned)rows), dim3(kMultiBlock), 0, s, tab, scale);
+        ELIXIR_LAUNCH_CHECK("reduce_rows_kernel");
+        return ELIXIR_OK;
+    }
+};
+
+template <bool ACC, bool FP16>
 struct ReduceRows {
     float* const* d_dst;
     const uint16_t* const* d_src;
     const int64_t* n;
-    float scale;
-    hipStream_t s;
-    ReduceMultiTable tab;
-    int in_table = 0;
+    CompactRowBuilder<16, 8, kMultiBlock, ReduceLaunch<ACC, FP16>> table;
+    int rc = ELIXIR_OK;
 
     void add(int k, int64_t first_tile, int64_t n_tiles) {
-        const int64_t e0 = first_tile * kMultiBlock * 4;             // first element of the piece
-        int64_t n4 = n[k] / 4 - first_tile * kMultiBlock;            // groups from there to the end of the tensor
-        if (n4 > n_tiles * kMultiBlock) n4 = n_tiles * kMultiBlock;
-        tab.dst[in_table] = d_dst[k] + e0;
-        tab.src[in_table] = d_src[k] + e0;
-        tab.n4[in_table] = n4;
-        ++in_table;
+        int64_t g0, g1;  // the groups of tensor k that these workgroups handle
+        row_piece<16, kMultiBlock>(d_dst[k], n[k] / 4, first_tile, n_tiles, &g0, &g1);
+        if (rc == ELIXIR_OK)
+            rc = table.add(reinterpret_cast<char*>(d_dst[k] + g0 * 4), reinterpret_cast<const char*>(d_src[k] + g0 * 4), g1 - g0);
     }
-    int flush(int64_t row_tiles) {
-        for (int j = in_table; j < kReduceMultiMax; ++j) {
-            tab.dst[j] = nullptr;
-            tab.src[j] = nullptr;
-            tab.n4[j] = 0;
-        }
-        hipLaunchKernelGGL((reduce_multi_kernel<ACC, FP16>), dim3((unsigned)row_tiles, (unsigned)in_table), dim3(kMultiBlock), 0, s, tab, scale);
-        in_table = 0;
-        ELIXIR_LAUNCH_CHECK("reduce_multi_kernel");
-        return ELIXIR_OK;
-    }
-};
-
-// Rows of the small-tensor launch (see reduce_small_kernel).
-template <bool ACC, bool FP16>
-struct ReduceSmallRows {
-    float* const* d_dst;
-    const uint16_t* const* d_src;
-    const int64_t* n;
-    float scale;
-    hipStream_t s;
-    ReduceSmallTable tab;
-    int in_table = 0;
-
-    void add(int k, int64_t first_tile, int64_t n_tiles) {
-        const int64_t g0 = first_tile * kMultiBlock;  // first group of the piece
-        int64_t n4 = n[k] / 4 - g0;
-        if (n4 > n_tiles * kMultiBlock) n4 = n_tiles * kMultiBlock;
-        tab.dst_off[in_table] = (uint32_t)((d_dst[k] - tab.dst_base) / 4 + g0);
-        tab.src_off[in_table] = (uint32_t)((d_src[k] - tab.src_base) / 4 + g0);
-        tab.n4[in_table] = (uint16_t)n4;
-        ++in_table;
-    }
-    int flush(int64_t row_tiles) {
-        for (int j = in_table; j < kReduceSmallMax; ++j) {
-            tab.dst_off[j] = 0;
-            tab.src_off[j] = 0;
-            tab.n4[j] = 0;
-        }
-        hipLaunchKernelGGL((reduce_small_kernel<ACC, FP16>), dim3((unsigned)row_tiles, (unsigned)in_table), dim3(kMultiBlock), 0, s, tab, scale);
-        in_table = 0;
-        ELIXIR_LAUNCH_CHECK("reduce_small_kernel");
-        return ELIXIR_OK;
-    }
+    int flush(int64_t) { return rc != ELIXIR_OK ? rc : table.flush(); }
 };
 
 template <bool ACC, bool FP16>
 int reduce_multi(int T, float* const* d_dst, const uint16_t* const* d_src, const int64_t* n, float scale, hipStream_t s) {
-    // tensors that qualify for the vector kernel go through the row plans; a slice at an odd offset or a handful of
+    // tensors that qualify for the vector kernel go through the row plan; a slice at an odd offset or a handful of
     // elements takes the single path, and so do the at most 3 elements after a tensor's last complete group
     auto vec = [&](int k) { return n[k] >= 4 && aligned(d_dst[k], 16) && aligned(d_src[k], 8); };
     for (int k = 0; k < T; ++k) {
@@ -317,31 +249,9 @@ int reduce_multi(int T, float* const* d_dst, const uint16_t* const* d_src, const
             ELIXIR_LAUNCH_CHECK("reduce_scalar_kernel");
         }
     }
-    // the small tensors: offsets are taken from the lowest destination and the lowest source among them
-    ReduceSmallRows<ACC, FP16> small_rows{d_dst, d_src, n, scale, s};
-    small_rows.tab.dst_base = nullptr;
-    small_rows.tab.src_base = nullptr;
-    int n_small = 0;
-    for (int k = 0; k < T; ++k) {
-        if (!vec(k) || n[k] / 4 >= kSmallGroups) continue;
-        if (!n_small || d_dst[k] < small_rows.tab.dst_base) small_rows.tab.dst_base = d_dst[k];
-        if (!n_small || d_src[k] < small_rows.tab.src_base) small_rows.tab.src_base = d_src[k];
-        ++n_small;
-    }
-    auto small = [&](int k) {
-        if (n_small < 2 || !vec(k) || n[k] / 4 >= kSmallGroups) return false;  // a single one gains nothing over the plain table
-        const int64_t d_groups = (d_dst[k] - small_rows.tab.dst_base) / 4 + n[k] / 4;  // offset of the tensor's end, in groups
-        const int64_t s_groups = (d_src[k] - small_rows.tab.src_base) / 4 + n[k] / 4;
-        return d_groups <= (int64_t)UINT32_MAX && s_groups <= (int64_t)UINT32_MAX;
-    };
-    auto tiles_of = [&](int k) -> int64_t { return (n[k] / 4 + kMultiBlock - 1) / kMultiBlock; };
-    if (n_small >= 2) {
-        auto tiles = [&](int k) -> int64_t { return small(k) ? tiles_of(k) : 0; };
-        if (const int rc = plan_rows(T, tiles, 1, kReduceSmallMax, kMaxRowTiles, small_rows)) return rc;
-    }
-    ReduceRows<ACC, FP16> rows{d_dst, d_src, n, scale, s};
-    auto tiles = [&](int k) -> int64_t { return vec(k) && !small(k) ? tiles_of(k) : 0; };
-    return plan_rows(T, tiles, 1, kReduceMultiMax, kMaxRowTiles, rows);
+    ReduceRows<ACC, FP16> rows{d_dst, d_src, n, CompactRowBuilder<16, 8, kMultiBlock, ReduceLaunch<ACC, FP16>>(ReduceLaunch<ACC, FP16>{scale, s})};
+    auto tiles = [&](int k) -> int64_t { return vec(k) ? row_tiles<16, kMultiBlock>(d_dst[k], n[k] / 4) : 0; };
+    return plan_rows(T, tiles, 1, kCompactRows, kMaxRowTiles, rows);
 }
 
 int elixir_grad_reduce_multi_lp_impl(int n_tensors, float* const* d_dst, const uint16_t* const* d_grad_lowp,

@@ -166,4 +166,124 @@ int plan_rows(int n_items, TilesFn tiles, int64_t granule, int max_rows, int64_t
     return 0;
 }
 
+// ---- the table of rows as it travels in the kernel arguments ----------------------------------------------------------
+//
+// Every launch boundary costs (the chip drains and refills), so a launch should carry as many rows as the 4 KB of kernel
+// arguments allow.  Rows are therefore stored compactly: two base addresses per launch (the lowest destination and the
+// lowest source among its rows) and per row two 32-bit offsets from them, in units of UNIT bytes, and a 32-bit count:
+// 12 bytes instead of 24, 336 rows instead of 160.  A row whose offset would not fit (addresses more than 2^32 units
+// apart within one launch) makes the builder launch what it has and start a new table, so any set of rows is accepted.
+// A row may have no source (a fill): its source offset is kNoSource.
+//
+// Where a row starts matters as well: a wavefront moves TILE consecutive units, and when that KiB of the destination
+// straddles a KiB boundary every boundary line is written by two wavefronts (measured on the gradient reduction, rows of
+// 2.56M elements: 82.9% of the HBM peak with aligned rows, 79.3% with every row 512 bytes past a boundary).  So the
+// destination base is a multiple of TILE units, the kernels take  phase = dst_off mod TILE  of a row as the number of
+// lanes that its first workgroup leaves idle, and every later workgroup of the row is aligned: workgroup x handles
+// units [x TILE - phase, (x + 1) TILE - phase) of the row.  row_phase / row_tiles / row_piece below are the host side
+// of that rule.
+constexpr int kCompactRows = 336;
+constexpr uint32_t kNoSource = 0xFFFFFFFFu;
+struct CompactRows {
+    char* dst_base;
+    const char* src_base;
+    uint32_t dst_off[kCompactRows];   // units of DST_UNIT bytes from dst_base
+    uint32_t src_off[kCompactRows];   // units of SRC_UNIT bytes from src_base, or kNoSource
+    uint32_t count[kCompactRows];     // what the kernel counts (groups of 4 elements, 16-byte units)
+};
+static_assert(sizeof(CompactRows) + 16 <= 4096, "the table (and a scalar beside it) must fit the kernel arguments");
+
+// Collects rows and hands complete tables to launch(table, rows, longest row in tiles).  DST_UNIT / SRC_UNIT: bytes per
+// offset unit (the addresses are multiples of them); TILE: count units per workgroup.
+template <int DST_UNIT, int SRC_UNIT, int TILE, class Launch>
+struct CompactRowBuilder {
+    Launch launch;
+    char* dst[kCompactRows];
+    const char* src[kCompactRows];
+    CompactRows tab;
+    int rows = 0;
+    int64_t longest = 0;   // tiles
+    uintptr_t d_lo = 0, d_hi = 0, s_lo = 0, s_hi = 0;
+    bool any_src = false;
+
+    explicit CompactRowBuilder(Launch l) : launch(l) {}
+
+    static constexpr uint64_t kSpan = 0xFFFFFFFEull;  // largest offset, in units (kNoSource stays free)
+
+    static constexpr uintptr_t kBaseGrain = (uintptr_t)DST_UNIT * TILE;  // the destination base is a multiple of this
+
+    int add(char* d, const char* s, int64_t count) {
+        const uintptr_t da = reinterpret_cast<uintptr_t>(d), sa = reinterpret_cast<uintptr_t>(s);
+        if (rows) {
+            const uintptr_t nd_lo = (da < d_lo ? da : d_lo) / kBaseGrain * kBaseGrain, nd_hi = da > d_hi ? da : d_hi;
+            uintptr_t ns_lo = s_lo, ns_hi = s_hi;
+            if (s && any_src) {
+                ns_lo = sa < s_lo ? sa : s_lo;
+                ns_hi = sa > s_hi ? sa : s_hi;
+            } else if (s) {
+                ns_lo = ns_hi = sa;
+            }
+            const bool fits = (nd_hi - nd_lo) / DST_UNIT <= kSpan && (!(s || any_src) || (ns_hi - ns_lo) / SRC_UNIT <= kSpan);
+            if (!fits || rows == kCompactRows)
+                if (const int rc = flush()) return rc;
+        }
+        if (!rows) {
+            d_lo = d_hi = da;
+            any_src = false;
+        }
+        if (da < d_lo) d_lo = da;
+        if (da > d_hi) d_hi = da;
+        if (s) {
+            if (!any_src) s_lo = s_hi = sa;
+            if (sa < s_lo) s_lo = sa;
+            if (sa > s_hi) s_hi = sa;
+            any_src = true;
+        }
+        dst[rows] = d;
+        src[rows] = s;
+        tab.count[rows] = (uint32_t)count;
+        const int64_t t = (count + (int64_t)(da / DST_UNIT % TILE) + TILE - 1) / TILE;  // the first workgroup starts `phase` lanes in
+        if (t > longest) longest = t;
+        ++rows;
+        return 0;
+    }
+    int flush() {
+        if (!rows) return 0;
+        const uintptr_t d_base = d_lo / kBaseGrain * kBaseGrain;
+        tab.dst_base = reinterpret_cast<char*>(d_base);
+        tab.src_base = any_src ? reinterpret_cast<const char*>(s_lo) : nullptr;
+        for (int r = 0; r < rows; ++r) {
+            tab.dst_off[r] = (uint32_t)((reinterpret_cast<uintptr_t>(dst[r]) - d_base) / DST_UNIT);
+            tab.src_off[r] = src[r] ? (uint32_t)((reinterpret_cast<uintptr_t>(src[r]) - s_lo) / SRC_UNIT) : kNoSource;
+        }
+        for (int r = rows; r < kCompactRows; ++r) {
+            tab.dst_off[r] = 0;
+            tab.src_off[r] = kNoSource;
+            tab.count[r] = 0;
+        }
+        const int rc = launch(tab, rows, longest);
+        rows = 0;
+        longest = 0;
+        return rc;
+    }
+};
+
+// Host side of the alignment rule for an item of n units whose destination starts at address d.
+template <int DST_UNIT, int TILE>
+inline int64_t row_phase(const void* d) {
+    return (int64_t)(reinterpret_cast<uintptr_t>(d) / DST_UNIT % TILE);
+}
+template <int DST_UNIT, int TILE>
+inline int64_t row_tiles(const void* d, int64_t n) {  // workgroups the item takes
+    return (n + row_phase<DST_UNIT, TILE>(d) + TILE - 1) / TILE;
+}
+// The units [*begin, *end) of the item that its workgroups [first_tile, first_tile + n_tiles) handle.
+template <int DST_UNIT, int TILE>
+inline void row_piece(const void* d, int64_t n, int64_t first_tile, int64_t n_tiles, int64_t* begin, int64_t* end) {
+    const int64_t phase = row_phase<DST_UNIT, TILE>(d);
+    *begin = first_tile ? first_tile * TILE - phase : 0;
+    *end = (first_tile + n_tiles) * TILE - phase;
+    if (*end > n) *end = n;
+}
+
 }  // namespace elixir

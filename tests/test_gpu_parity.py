@@ -251,11 +251,12 @@ def test_grad_reduce_multi_is_bit_identical_to_single_calls_and_the_oracle(fmt):
     assert np.all(got[:4] == 1.5) and np.all(got[-5:] == 1.5)        # nothing outside the slices was touched
 
 
-def test_grad_reduce_multi_small_tensor_table_limits():
-    """The compact table of the small-tensor launch at its limits: more small tensors than one table holds (400), the
-    longest tensor it takes (65,535 groups of 4) next to the shortest it does not, and tensors whose destinations lie
-    more than 64 GiB and whose gradients lie more than 32 GiB from the lowest one (slices at both ends of one 70 GiB
-    allocation, of which only the slices are touched), which must take the ordinary table: bit-identical to the oracle."""
+def test_grad_reduce_multi_table_limits():
+    """The compact row table of the batched reduction at its limits: more tensors than one table holds (336 rows),
+    lengths around 2^16 groups, destinations that start anywhere relative to a KiB boundary (the first workgroup of a
+    row then starts some lanes in), and tensors whose destinations lie more than 64 GiB and whose gradients lie more
+    than 32 GiB from the others (slices at both ends of one 70 GiB allocation, of which only the slices are touched),
+    for which the library must start a new launch with bases of its own: bit-identical to the oracle."""
     GiB = 1 << 30
     big = torch.empty(70 * GiB, dtype=torch.int8, device=DEV)
     rng = np.random.default_rng(11)

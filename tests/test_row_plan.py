@@ -100,3 +100,72 @@ def test_transformer_shaped_lists_get_their_common_piece(harness):
     blocks = [(n // 2 + 127) // 128 for n in valid]
     n_launches, idle = check(blocks, plan(harness, blocks, 16, 64), 16, 64, 1 << 22)
     assert n_launches == 1 and idle < 0.06
+
+
+# ---- the compact table of rows (two bases per launch, 32-bit offsets)
+
+def tables(exe, rows):
+    text = "".join(f"{d} {s} {c}\n" for d, s, c in rows)
+    out = subprocess.run([exe, "table"], input=text, capture_output=True, text=True, check=True).stdout
+    got = []
+    for line in out.splitlines():
+        kind, *vals = line.split()
+        assert kind != "P", "an unused entry of the table was not cleared"
+        if kind == "T":
+            got.append(([int(v) for v in vals], []))
+        else:
+            got[-1][1].append(tuple(int(v) for v in vals))
+    return got
+
+
+def check_tables(rows, got, max_rows=336):
+    """Every row once, in the order given; offsets lead back to the addresses; launches within the table size."""
+    NO_SOURCE = 0xFFFFFFFF
+    k = 0
+    for (n_rows, longest, dst_base, src_base), entries in got:
+        assert 1 <= n_rows == len(entries) <= max_rows
+        assert dst_base % 1024 == 0                            # so that dst_off mod 64 is the row's distance from a KiB boundary
+        assert longest == max((c + d_off % 64 + 63) // 64 for d_off, _, c in entries)   # the first workgroup starts that many lanes in
+        for d_off, s_off, count in entries:
+            d, s, c = rows[k]
+            assert dst_base + 16 * d_off == d and count == c
+            if s == 0:
+                assert s_off == NO_SOURCE
+            else:
+                assert s_off < NO_SOURCE and src_base + 8 * s_off == s
+            k += 1
+    assert k == len(rows)
+
+
+def test_compact_table_keeps_every_row_and_its_addresses(harness):
+    rng = np.random.default_rng(3)
+    base_d, base_s = 0x7F0000000000, 0x7E0000000000
+    rows = [(base_d + 16 * int(rng.integers(0, 1 << 28)), base_s + 8 * int(rng.integers(0, 1 << 28)), int(rng.integers(1, 1 << 20))) for _ in range(1000)]
+    rows[5] = (rows[5][0], 0, 77)                      # rows without a source (fills) among the others
+    rows[6] = (rows[6][0], 0, 1)
+    got = tables(harness, rows)
+    check_tables(rows, got)
+    assert [t[0][0] for t in got] == [336, 336, 328]   # full tables, then the rest
+    only_fills = [(base_d + 16 * i, 0, 64) for i in range(10)]
+    got = tables(harness, only_fills)
+    check_tables(only_fills, got)
+    assert got[0][0][3] == 0                            # no source base when no row has a source
+
+
+def test_compact_table_starts_a_new_launch_when_an_offset_would_not_fit(harness):
+    GiB = 1 << 30
+    d0, s0 = 0x7F0000000000, 0x7E0000000000
+    # destinations 16-byte units: 2^32 units = 64 GiB; sources 8-byte units: 2^32 units = 32 GiB
+    rows = [(d0, s0, 100), (d0 + 63 * GiB, s0 + 31 * GiB, 100),          # still one launch
+            (d0 + 65 * GiB, s0, 100),                                     # destination too far from the lowest one
+            (d0 + 65 * GiB + 16, s0 + 33 * GiB, 100),                     # source too far
+            (d0 - 70 * GiB, s0 + 33 * GiB, 100),                          # below the base: the span counts, not the order
+            (d0 - 70 * GiB + 16, 0, 100), (d0 - 70 * GiB + 32, s0 - 40 * GiB, 5)]   # a fill does not move the source span; the next source does
+    got = tables(harness, rows)
+    check_tables(rows, got)
+    assert [t[0][0] for t in got] == [2, 1, 1, 2, 1]
+    # exactly at the limit: the largest offset is 2^32 - 2 units (2^32 - 1 marks a row without a source)
+    edge = [(d0, s0, 1), (d0 + 16 * 0xFFFFFFFE, s0 + 8 * 0xFFFFFFFE, 1), (d0 + 16 * 0xFFFFFFFF, s0, 1)]
+    got = tables(harness, edge)
+    check_tables(edge, got)
+    assert [t[0][0] for t in got] == [2, 1]
