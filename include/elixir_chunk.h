@@ -124,8 +124,9 @@ int elixir_chunk_unpack(const void* d_chunk, int64_t chunk_elems, int elem_size,
                         const int64_t* numel, const int64_t* offset, int T, elixir_stream_t stream);
 
 /*
- * The same for a whole parameter set in one call (one launch per chunk, like the per-chunk calls: launches that
- * sweep several chunks measured slower), taking the layout plan as elixir_layout_plan returns it: tensor i occupies the linear element range
+ * The same for a whole parameter set in one call (a handful of launches instead of one per chunk: slices whose two
+ * addresses are 16-byte aligned travel as the rows of a 2-D grid, up to 336 per launch), taking the layout plan as
+ * elixir_layout_plan returns it: tensor i occupies the linear element range
  * [chunk_id[i] * chunk_elems + offset[i], + numel[i]) of the chunk sequence d_chunks[0], d_chunks[1], ... (a HOST array
  * of n_chunks device pointers), so a tensor that is longer than the rest of its chunk continues at the start of the
  * next one and need not be passed piecewise.  pack zero-fills every element of every chunk that no tensor covers.
@@ -429,7 +430,8 @@ int elixir_grad_reduce_into_chunk_lp(float* d_grad_chunk, int64_t offset, const 
 /*
  * The reduction for many tensors in few launches: gradients arrive tensor by tensor and most tensors are small, so
  * one launch each leaves the GPU idle in between.  The tensors are cut into equal pieces plus tails, and pieces of
- * similar length share a launch as the rows of a 2-D grid (up to 160 rows; no host allocation; any number of tensors).  d_dst[i] points at the
+ * similar length share a launch as the rows of a 2-D grid (up to 336 rows; no host allocation; any number of tensors
+ * at any addresses).  d_dst[i] points at the
  * tensor's place inside its fp32 gradient chunk (chunk base + offset, computed by the caller), d_grad_lowp[i] at its
  * n[i] low-precision gradients; all three tables are HOST arrays.  Destinations must not overlap.  Results are
  * bit-identical to n_tensors calls of elixir_grad_reduce_into_chunk_lp.
