@@ -108,6 +108,39 @@ def test_pack_unpack_bit_exact(dtype, case):
         assert np.array_equal(host(o, dtype).view(np.uint8), t.view(np.uint8))
 
 
+@pytest.mark.parametrize("dtype", [np.float32, np.uint16])
+def test_pack_few_aligned_slices_take_the_row_kernel(dtype):
+    """Up to four segments of a chunk go out as grid rows: slices that start 16-byte aligned but in the middle of a KiB
+    (the first workgroup of a row then leaves its leading lanes idle), lengths that leave fewer than 16 bytes over (those
+    go through the tile kernel), a gap and the padding zero-filled."""
+    rng = np.random.default_rng(21)
+    es = np.dtype(dtype).itemsize
+    per16 = 16 // es
+    C = 300_000
+    numels = [100_000 + 3, 150_000 + per16 + 1]
+    off = [per16 * 5, 100_000 + per16 * 9]                   # both 16-byte aligned, 80 and 144 bytes past a KiB boundary at best
+    tensors = _random_tensors(rng, numels, dtype)
+    want = np.empty(C, dtype)
+    want.view(np.uint8)[:] = 0xAB
+    orc.chunk_pack(want, tensors, off)
+    d_tensors = [dev(t) for t in tensors]
+    d_chunk = dev(np.full(C, 0x5A5A, np.uint16) if es == 2 else np.full(C, 1.5, np.float32))
+    ex.elixir_chunk_pack(d_chunk, C, es, d_tensors, numels, off)      # segments: gap, slice, gap, slice, padding = 5 -> tile kernel
+    sync()
+    assert np.array_equal(host(d_chunk, dtype).view(np.uint8), want.view(np.uint8))
+    d_chunk2 = dev(np.full(C, 0x5A5A, np.uint16) if es == 2 else np.full(C, 1.5, np.float32))
+    ex.elixir_chunk_pack(d_chunk2, C, es, d_tensors[:1], numels[:1], off[:1])   # gap, slice, padding = 3 -> rows
+    sync()
+    want1 = np.empty(C, dtype)
+    orc.chunk_pack(want1, tensors[:1], off[:1])
+    assert np.array_equal(host(d_chunk2, dtype).view(np.uint8), want1.view(np.uint8))
+    d_outs = [torch.zeros_like(t) for t in d_tensors]
+    ex.elixir_chunk_unpack(d_chunk, C, es, d_outs, numels, off)                  # 2 segments -> rows
+    sync()
+    for t, o in zip(tensors, d_outs):
+        assert np.array_equal(host(o, dtype).view(np.uint8), t.view(np.uint8))
+
+
 def test_pack_misaligned_tensor_pointers_and_subset_unpack():
     rng = np.random.default_rng(9)
     C = 50_000
