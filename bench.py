@@ -145,7 +145,8 @@ def parse():
                     help="optimizer chunk as one buffer of interleaved [master|m|v] tiles (default) or as three arrays")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-rows", action="store_true", help="skip the per-row side measurements")
-    ap.add_argument("--configs", default="1,3,4,5", help="gpt2_1p5b: which of the other benchmark configurations get their short runs (rows.config_*)")
+    ap.add_argument("--configs", default="1,3,4,5,f", help="gpt2_1p5b: which of the other benchmark configurations get their short runs (rows.config_*); "
+                                                            "f: the CPU update of host-resident chunks with the split the benefit model chooses (rows.f1_f2_hybrid_20b)")
     ap.add_argument("--no-configs", action="store_true", help="gpt2_1p5b: skip the short runs of the other benchmark configurations "
                                                                "(tiny, sweep, 6B accumulate + clip, 20B offload mix) that fill rows.config_*")
     return ap.parse_args()
@@ -1142,8 +1143,12 @@ def other_configs(args, torch, ex, gen):
                                                  "took_s": round(time.perf_counter() - t0, 1),
                                                  "ran_in": "a child process (this one had freed large allocations: uploads and downloads took turns)"}
                                                 if lines else {"error": f"child process: rc {r.returncode}: {r.stderr[-500:]}"})
-        gc.collect()
-        torch.cuda.empty_cache()
+    if "f" in want:
+        # the paper's own treatment of host-resident chunks (updated by the host cores) and the split its benefit model
+        # chooses from what the run measures; it streams as well, so it too comes before anything large is freed
+        collect("f1_f2_hybrid_20b", run_hybrid, steps=2, free_after=False)
+    gc.collect()
+    torch.cuda.empty_cache()
     if "1" in want:
         collect("config_1_tiny", lambda a, *rest: run_headline(a, *rest, dev), workload="tiny", no_rows=True, multi=True)
     if "3" in want:
