@@ -819,7 +819,7 @@ def run_hybrid(args, torch, ex, gen):
     gkey = gen.stream_key(gen.BASE_SEED, gen.TAG_GRAD, 1, 0, cfg.cfg_id)
     try:
         ex.elixir_offload_register_slots(ctx, slots, nbytes)
-        h2d, d2h = ex.elixir_offload_copy_streams(ctx, compute)
+        h2d, d2h, duplex = ex.elixir_offload_copy_streams(ctx, compute, with_flag=True)
         for c in range(N):
             gen.fill_bf16_device(grads[c].data_ptr(), C, gkey, c * C, cfg.grad_std)
         for c in range(N):
@@ -951,6 +951,10 @@ def run_hybrid(args, torch, ex, gen):
             "sweep": results, "cpu_update_alone": vc, "benefit_model": benefit,
             "plan": plan, "plan_ms": plan_t * 1e3, "fixed60_ms": fixed_cpu["ms_per_step"], "fixed60_streamed_ms": streamed["ms_per_step"],
             "best_sweep_ms": best["ms_per_step"],
+            "link": {"uploads_and_downloads_overlap_at_start": duplex, "GB/s_each_way_all_streamed": link / 1e9,
+                     "state": ("full duplex" if link > 40e9 else
+                               "uploads and downloads took turns in this process (a state of the box that follows large frees, also a previous "
+                               "process's: the streamed rows and B in the benefit model are then half of what a fresh process measures)")},
             "roofline": {"bound": "host memory / host link", "achieved": None, "peak": None, "frac": None, "traffic": None}})
     finally:
         torch.cuda.synchronize()
