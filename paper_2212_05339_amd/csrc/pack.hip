@@ -3,14 +3,18 @@
 // A chunk is the concatenation of a group of flattened parameters (paper Sec. 3
 // "Chunk", Fig. 3 left).  The host turns the request into a list of byte
 // segments (source, destination, length; for pack also the gaps, which are
-// zero-filled), cuts the segments into tiles of kTileBytes and launches one
-// workgroup per tile.  The segment table travels as a kernel argument, so no
-// device memory is allocated or copied for it.  Each tile is moved with the
-// widest access both addresses allow (16, 4 or 2 bytes per lane).  A tile is
-// what one single-wavefront workgroup moves with one 128-bit access per lane
-// (1 KiB); workgroups are dispatched in index order, so source and destination
-// are swept as two sequential fronts (measured: 6.8 TB/s; 6.6 TB/s with
-// 256-thread workgroups and 4 KiB tiles; ~5.4 TB/s for hipMemcpy D2D).
+// zero-filled).  Two kernels move them, both with the table as a kernel
+// argument, so no device memory is allocated or copied for it:
+//   * the tile kernel cuts the segments into tiles of kTileBytes, one
+//     single-wavefront workgroup per tile, which finds its segment by a search
+//     over the table and moves the tile with the widest access both addresses
+//     allow (16, 4 or 2 bytes per lane): any alignment, 96 segments a launch;
+//   * the row kernel takes segments whose two addresses are 16-byte aligned as
+//     the rows of a 2-D grid (row_plan.hpp): no search, 336 rows a launch, rows
+//     started on KiB boundaries of the destination.
+// Workgroups are dispatched in index order, so source and destination are swept
+// as sequential fronts (one slice: 6.8 TB/s; 6.6 TB/s with 256-thread workgroups
+// and 4 KiB tiles; ~5.4 TB/s for hipMemcpy D2D).
 // Traffic: read + write of every byte (write only for gaps).
 #include <stdlib.h>
 
