@@ -145,6 +145,9 @@ def parse():
                     help="optimizer chunk as one buffer of interleaved [master|m|v] tiles (default) or as three arrays")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-rows", action="store_true", help="skip the per-row side measurements")
+    ap.add_argument("--evict-path", choices=["auto", "dma", "kernel"], default="auto",
+                    help="offload workloads: how a staging slot comes back to its host block: the DMA engine, the library's store kernel, or "
+                         "(auto) the kernel only where uploads and downloads by DMA take turns")
     ap.add_argument("--configs", default="1,3,4,5,f", help="gpt2_1p5b: which of the other benchmark configurations get their short runs (rows.config_*); "
                                                             "f: the CPU update of host-resident chunks with the split the benefit model chooses (rows.f1_f2_hybrid_20b)")
     ap.add_argument("--no-configs", action="store_true", help="gpt2_1p5b: skip the short runs of the other benchmark configurations "
@@ -291,6 +294,8 @@ def side_rows(ex, gen, torch, cfg, C, nch, valid, state, grads, out, stream, ste
         slots = [torch.zeros(3, C, dtype=torch.float32, device=dev) for _ in range(n_slots)]
         ex.elixir_offload_register_slots(ctx, slots, nbytes)
         h2d, d2h, duplex = ex.elixir_offload_copy_streams(ctx, stream, with_flag=True)   # two streams with hardware queues of their own beside `stream`
+        if not duplex:          # uploads and downloads by DMA take turns in this process: the slots come back by the store kernel
+            ex.elixir_offload_set_evict_path(ctx, ex.ELIXIR_EVICT_KERNEL)
         hp = ex.make_hparams(cfg.lr, cfg.beta1, cfg.beta2, cfg.eps, cfg.weight_decay, 1)
         try:
             for b in blocks:                                   # touch the host blocks once (first-touch, zero state)
@@ -356,7 +361,7 @@ def side_rows(ex, gen, torch, cfg, C, nch, valid, state, grads, out, stream, ste
             rows["offload"] = {
                 "what": f"{n_host} host-resident chunks of {C} elements ([master|m|v], {nbytes} bytes each) through {n_slots} "
                         f"staging slots, prefetch / AdamW / evict on three streams, with the {nch} resident chunks updated meanwhile",
-                "uploads_and_downloads_overlap_at_start": duplex, "h2d_alone_GB/s": moved / t_h2d / 1e9, "d2h_alone_GB/s": moved / t_d2h / 1e9,
+                "uploads_and_downloads_overlap_at_start": duplex, "evict_path": "DMA" if duplex else "store kernel", "h2d_alone_GB/s": moved / t_h2d / 1e9, "d2h_alone_GB/s": moved / t_d2h / 1e9,
                 "pipeline_ms": t_off * 1e3, "pipeline_GB/s_each_way": moved / t_off / 1e9,
                 "bidirectional_GB/s_each_way": (n_host // 2) * nbytes / t_both / 1e9,
                 "pipeline_frac_of_one_way_link": t_dma / t_off,
@@ -589,10 +594,6 @@ def run_clip(args, torch, ex, gen):
         ex.elixir_ctx_destroy(ctx)
 
 
-class HalfDuplex(Exception):
-    pass
-
-
 def run_offload(args, torch, ex, gen):
     """Offload mix on the 20B set: dense layout, 128Mi-element chunks; 60% of the chunks keep [master|m|v] in pinned
     host memory and are prefetched, updated on the GPU and evicted on side streams; 40% are updated in HBM meanwhile.
@@ -654,10 +655,10 @@ def run_offload(args, torch, ex, gen):
     try:
         ex.elixir_offload_register_slots(ctx, slots, nbytes)
         h2d, d2h, duplex = ex.elixir_offload_copy_streams(ctx, compute, with_flag=True)
-        if not duplex and getattr(args, "child_if_half_duplex", False):
-            # this process has freed large device allocations, after which the runtime makes uploads and downloads take turns
-            # (see elixir_offload_copy_streams): the configuration is measured in a process of its own instead
-            raise HalfDuplex()
+        # where uploads and downloads by DMA take turns (a state that follows large frees, see elixir_offload_copy_streams) the
+        # slots come back by the library's store kernel instead, which needs no DMA engine
+        by_kernel = args.evict_path == "kernel" or (args.evict_path == "auto" and not duplex)
+        ex.elixir_offload_set_evict_path(ctx, ex.ELIXIR_EVICT_KERNEL if by_kernel else ex.ELIXIR_EVICT_DMA)
 
         def wall_of(fn):
             torch.cuda.synchronize()
@@ -771,6 +772,8 @@ def run_offload(args, torch, ex, gen):
                        "params": sum(valid), "pinned_GB": moved / 1e9, "pinned_alloc_s": t_alloc,
                        "copy_streams": "elixir_offload_copy_streams (hardware queues of their own beside the compute stream)",
                        "uploads_and_downloads_overlap_at_start": duplex,
+                       "evict_path": ("store kernel (elixir_offload_set_evict_path)" + ("" if duplex else ": uploads and downloads by DMA took turns "
+                                      "when the run began")) if by_kernel else "DMA",
                        "host_order": args.host_order,
                        "pinned_blocks_the_box_allowed": pinned_limit},
             "offload_GB/s_each_way": moved / wall / 1e9, "link": link,
@@ -820,6 +823,8 @@ def run_hybrid(args, torch, ex, gen):
     try:
         ex.elixir_offload_register_slots(ctx, slots, nbytes)
         h2d, d2h, duplex = ex.elixir_offload_copy_streams(ctx, compute, with_flag=True)
+        by_kernel = args.evict_path == "kernel" or (args.evict_path == "auto" and not duplex)   # see run_offload
+        ex.elixir_offload_set_evict_path(ctx, ex.ELIXIR_EVICT_KERNEL if by_kernel else ex.ELIXIR_EVICT_DMA)
         for c in range(N):
             gen.fill_bf16_device(grads[c].data_ptr(), C, gkey, c * C, cfg.grad_std)
         for c in range(N):
@@ -951,10 +956,12 @@ def run_hybrid(args, torch, ex, gen):
             "sweep": results, "cpu_update_alone": vc, "benefit_model": benefit,
             "plan": plan, "plan_ms": plan_t * 1e3, "fixed60_ms": fixed_cpu["ms_per_step"], "fixed60_streamed_ms": streamed["ms_per_step"],
             "best_sweep_ms": best["ms_per_step"],
-            "link": {"uploads_and_downloads_overlap_at_start": duplex, "GB/s_each_way_all_streamed": link / 1e9,
-                     "state": ("full duplex" if link > 40e9 else
-                               "uploads and downloads took turns in this process (a state of the box that follows large frees, also a previous "
-                               "process's: the streamed rows and B in the benefit model are then half of what a fresh process measures)")},
+            "link": {"uploads_and_downloads_overlap_at_start": duplex, "evict_path": "store kernel" if by_kernel else "DMA",
+                     "GB/s_each_way_all_streamed": link / 1e9,
+                     "state": ("full duplex" if duplex else
+                               "uploads and downloads by DMA took turns when the run began (a state of the box that follows large frees, also a "
+                               "previous process's)" + (": the slots came back by the store kernel instead" if by_kernel else
+                                                        ": the streamed rows and B in the benefit model are half of what a fresh process measures"))},
             "roofline": {"bound": "host memory / host link", "achieved": None, "peak": None, "frac": None, "traffic": None}})
     finally:
         torch.cuda.synchronize()
@@ -1134,19 +1141,9 @@ def other_configs(args, torch, ex, gen):
     want = set(args.configs.split(","))
     if "5" in want:
         # first, and with nothing large freed since the process began (torch keeps the benchmark line's buffers cached): after a
-        # large hipFree the runtime makes uploads and downloads take turns for a while.  Should that state be there all the
-        # same, the configuration runs in a process of its own.
-        collect("config_5_20b_offload_mix", run_offload, steps=2, warmup=1, child_if_half_duplex=True, free_after=False)
-        if "HalfDuplex" in rows["config_5_20b_offload_mix"].get("error", ""):
-            import subprocess
-            t0 = time.perf_counter()
-            r = subprocess.run([sys.executable, os.path.abspath(__file__), "--workload", "gpt2_20b_offload", "--steps", "2", "--warmup", "1"],
-                               capture_output=True, text=True, timeout=300)
-            lines = [json.loads(ln) for ln in r.stdout.splitlines() if ln.startswith("{")]
-            rows["config_5_20b_offload_mix"] = ({"lines": [{k: v for k, v in ln.items() if k not in drop} for ln in lines],
-                                                 "took_s": round(time.perf_counter() - t0, 1),
-                                                 "ran_in": "a child process (this one had freed large allocations: uploads and downloads took turns)"}
-                                                if lines else {"error": f"child process: rc {r.returncode}: {r.stderr[-500:]}"})
+        # large hipFree the runtime makes uploads and downloads by DMA take turns for a while.  Should that state be there all
+        # the same, the slots come back by the store kernel (--evict-path auto).
+        collect("config_5_20b_offload_mix", run_offload, steps=2, warmup=1, free_after=False)
     if "f" in want:
         # the paper's own treatment of host-resident chunks (updated by the host cores) and the split its benefit model
         # chooses from what the run measures; it streams as well, so it too comes before anything large is freed

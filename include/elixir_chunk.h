@@ -404,6 +404,19 @@ int elixir_chunk_evict(elixir_ctx* ctx, int slot, void* h_block, size_t bytes, e
                        elixir_stream_t d2h_stream);
 
 /*
+ * How elixir_chunk_evict brings a slot back to its host block (no passage of the paper: a remedy for a state of the
+ * HIP runtime).  ELIXIR_EVICT_DMA (the default): hipMemcpyAsync, the DMA engine.  ELIXIR_EVICT_KERNEL: a small kernel
+ * on d2h_stream stores the slot into the pinned block over the link.  In a process whose uploads and downloads by DMA
+ * take turns (elixir_offload_copy_streams reports that state in *full_duplex_out; it follows the freeing of large
+ * allocations) the kernel path lets the download run beside the upload again.  The host block must then be pinned
+ * memory that the device can address (elixir_host_alloc's is); for any other block, and for a slot or block that is
+ * not 16-byte aligned, the call copies by DMA as before.  Takes effect from the next elixir_chunk_evict on; same bytes
+ * either way.  ELIXIR_EINVAL for an unknown path.
+ */
+enum { ELIXIR_EVICT_DMA = 0, ELIXIR_EVICT_KERNEL = 1 };
+int elixir_offload_set_evict_path(elixir_ctx* ctx, int path);
+
+/*
  * The paper's own low-precision format, FP16 (Sec. 2 "Mixed Precision Training"), with dynamic loss scaling
  * (Micikevicius et al., "Mixed Precision Training", which the paper cites for its set-up; the paper gives no
  * rule of its own).  The *_lp entry points take the format as an argument and are otherwise the functions

@@ -23,6 +23,7 @@ EXPORTS = (
     "elixir_chunk_unpack", "elixir_grad_reduce_into_chunk", "elixir_chunk_grad_norm", "elixir_chunk_adam_step",
     "elixir_chunk_adam_step_multi",
     "elixir_host_alloc", "elixir_host_free", "elixir_offload_register_slots", "elixir_offload_copy_streams",
+    "elixir_offload_set_evict_path",
     "elixir_chunk_prefetch",
     "elixir_chunk_wait_ready", "elixir_chunk_evict", "elixir_host_adam_step", "elixir_host_adam_isa", "elixir_copy_h2d_async",
     "elixir_copy_d2h_async", "elixir_stream_synchronize", "elixir_offload_benefit", "elixir_offload_plan",
@@ -84,6 +85,7 @@ def lib() -> ctypes.CDLL:
             "elixir_host_free": [vp],
             "elixir_offload_register_slots": [vp, ctypes.POINTER(vp), ci, sz],
             "elixir_offload_copy_streams": [vp, vp, ctypes.POINTER(vp), ctypes.POINTER(vp), ctypes.POINTER(ci)],
+            "elixir_offload_set_evict_path": [vp, ci],
             "elixir_chunk_prefetch": [vp, vp, sz, ctypes.POINTER(ci), vp],
             "elixir_chunk_wait_ready": [vp, ci, vp],
             "elixir_chunk_evict": [vp, ci, vp, sz, vp, vp],
@@ -343,6 +345,14 @@ def elixir_offload_copy_streams(ctx: Ctx, compute_stream=None, with_flag: bool =
     up, down, flag = ctypes.c_void_p(), ctypes.c_void_p(), ctypes.c_int(0)
     _check(lib().elixir_offload_copy_streams(ctx.handle, _stream(compute_stream), ctypes.byref(up), ctypes.byref(down), ctypes.byref(flag)))
     return (up.value, down.value, bool(flag.value)) if with_flag else (up.value, down.value)
+
+
+ELIXIR_EVICT_DMA, ELIXIR_EVICT_KERNEL = 0, 1
+
+
+def elixir_offload_set_evict_path(ctx: Ctx, path: int) -> None:
+    """ELIXIR_EVICT_DMA (default) or ELIXIR_EVICT_KERNEL: how elixir_chunk_evict brings a slot back to its host block."""
+    _check(lib().elixir_offload_set_evict_path(ctx.handle, path))
 
 
 def elixir_chunk_prefetch(ctx: Ctx, h_block: int, nbytes: int, h2d_stream) -> int:

@@ -57,6 +57,7 @@ struct elixir_ctx {
     int n_slots = 0;
     size_t slot_bytes = 0;
     int next_slot = 0;
+    int evict_path = 0;            // ELIXIR_EVICT_DMA or ELIXIR_EVICT_KERNEL (offload.cpp)
     // the fused reduction + sum-of-squares calls of one step share d_stage and d_partials: they must arrive on one stream
     bool fused_open = false;       // a sumsq call has been made since the last finish
     void* fused_stream = nullptr;  // the stream of that call

@@ -1255,8 +1255,12 @@ def test_config_accumulate_clip_step_scaled_down(ctx):
 
 # --------------------------------------------------------------------------- offload pipeline
 
+@pytest.mark.parametrize("evict_path", ["dma", "kernel"])
 @pytest.mark.parametrize("n_slots", [1, 2, 3])
-def test_offload_is_bitwise_identical_to_resident(ctx, n_slots):
+def test_offload_is_bitwise_identical_to_resident(ctx, n_slots, evict_path):
+    """evict_path: the slot comes back by the DMA engine or by the kernel that stores into the pinned block (a block
+    length that is no multiple of 16 bytes, so that the kernel's last-bytes path runs too)."""
+    ex.elixir_offload_set_evict_path(ctx, ex.ELIXIR_EVICT_KERNEL if evict_path == "kernel" else ex.ELIXIR_EVICT_DMA)
     C, n_chunks = 300_000 + 3, 7
     host_ids = [0, 2, 3, 5, 6]                                   # the rest are resident
     key = gen.stream_key(gen.BASE_SEED, gen.TAG_PARAM, cfg=5)
@@ -1321,9 +1325,41 @@ def test_offload_is_bitwise_identical_to_resident(ctx, n_slots):
         assert e.value.code == ex.ELIXIR_ESTATE
     finally:
         sync()
+        ex.elixir_offload_set_evict_path(ctx, ex.ELIXIR_EVICT_DMA)
         ex.elixir_offload_register_slots(ctx, [], 0)
         for b in blocks.values():
             ex.elixir_host_free(b)
+
+
+def test_evict_by_kernel_falls_back_to_dma_where_the_kernel_cannot_go(ctx):
+    """With the kernel path chosen, a host block that the device cannot address (pageable memory) and one that is not
+    16-byte aligned must still arrive, by DMA; an unknown path is refused."""
+    n = 100_000
+    nbytes = 4 * n
+    slots = [torch.zeros(n + 4, dtype=torch.float32, device=DEV)]
+    ex.elixir_offload_register_slots(ctx, slots, 4 * (n + 4))
+    pinned = ex.elixir_host_alloc(nbytes + 64)
+    pageable = np.zeros(n, np.float32)
+    src = gen.fill_f32(gen.stream_key(5, gen.TAG_PARAM), 0, n, 0.02)
+    stream = torch.cuda.Stream()
+    try:
+        with pytest.raises(ex.ElixirError) as e:
+            ex.elixir_offload_set_evict_path(ctx, 7)
+        assert e.value.code == ex.ELIXIR_EINVAL
+        ex.elixir_offload_set_evict_path(ctx, ex.ELIXIR_EVICT_KERNEL)
+        for target, addr in (("pageable", pageable.ctypes.data), ("pinned, 4 bytes off", pinned + 4), ("pinned", pinned)):
+            ctypes.memmove(pinned + 32, src.ctypes.data, nbytes)
+            s = ex.elixir_chunk_prefetch(ctx, pinned + 32, nbytes, stream.cuda_stream)
+            ex.elixir_chunk_evict(ctx, s, addr, nbytes, stream.cuda_stream, stream.cuda_stream)
+            sync()
+            got = np.empty(n, np.float32)
+            ctypes.memmove(got.ctypes.data, addr, nbytes)
+            assert np.array_equal(got.view(np.uint32), src.view(np.uint32)), target
+    finally:
+        sync()
+        ex.elixir_offload_set_evict_path(ctx, ex.ELIXIR_EVICT_DMA)
+        ex.elixir_offload_register_slots(ctx, [], 0)
+        ex.elixir_host_free(pinned)
 
 
 def test_offload_with_fewer_host_chunks_than_slots_over_several_steps(ctx):
