@@ -384,7 +384,8 @@ int elixir_arena_plan(int n_chunks, const elixir_arena_array* arrays, int n_arra
  *       later copy traffic undoes it.  No choice of streams repairs that; *full_duplex_out (may be NULL) reports
  *       whether an upload and a download issued together overlapped when the call looked (1) or took turns (0).
  *       A process that wants the full-duplex rate allocates its long-lived buffers once and frees nothing large
- *       while it streams.  The two streams keep their directions: pass the first wherever this header takes
+ *       while it streams; one that reads 0 here can let the slots come back by a kernel instead
+ *       (elixir_offload_set_evict_path below).  The two streams keep their directions: pass the first wherever this header takes
  *       h2d_stream and the second wherever it takes d2h_stream.  Allocates and frees 128 MiB of device and of pinned
  *       memory and waits for its probe copies (about 30 ms).  ELIXIR_TRACE_STREAMS=1 in the environment prints
  *       what was measured.  Streams of the caller's own making work with the pipeline as well, correctly but with no

@@ -208,7 +208,9 @@ extern "C" int elixir_chunk_evict(elixir_ctx* ctx, int slot, void* h_block, size
 // upload on a third stream did, as did twenty 1 GiB downloads; one or four downloads did not).  No stream choice
 // repairs that, so the call only reports it: *full_duplex_out says whether an upload and a download overlapped when
 // the call looked.  A process that wants the full-duplex rate allocates its long-lived buffers once and frees nothing
-// large while it streams (the paper's own rule for long-lived buffers, Sec. 3 "Pre-runtime Profiler").
+// large while it streams (the paper's own rule for long-lived buffers, Sec. 3 "Pre-runtime Profiler"); one that finds
+// itself in that state lets the slots come back by the store kernel above (elixir_offload_set_evict_path), which leaves
+// the DMA engines to the uploads.
 
 namespace {
 
