@@ -356,6 +356,9 @@ def side_rows(ex, gen, torch, cfg, C, nch, valid, state, grads, out, stream, ste
             t_h2d = min(wall(only_h2d) for _ in range(2))
             t_d2h = min(wall(only_d2h) for _ in range(2))
             t_both = min(wall(both_ways) for _ in range(2))
+            # the same pipeline with the slots coming back the other way (store kernel / DMA engine)
+            ex.elixir_offload_set_evict_path(ctx, ex.ELIXIR_EVICT_KERNEL if duplex else ex.ELIXIR_EVICT_DMA)
+            t_off_other = min(wall(lambda: offload_step(False)) for _ in range(2))
             moved = n_host * nbytes
             t_dma = max(t_h2d, t_d2h)
             rows["offload"] = {
@@ -363,6 +366,7 @@ def side_rows(ex, gen, torch, cfg, C, nch, valid, state, grads, out, stream, ste
                         f"staging slots, prefetch / AdamW / evict on three streams, with the {nch} resident chunks updated meanwhile",
                 "uploads_and_downloads_overlap_at_start": duplex, "evict_path": "DMA" if duplex else "store kernel", "h2d_alone_GB/s": moved / t_h2d / 1e9, "d2h_alone_GB/s": moved / t_d2h / 1e9,
                 "pipeline_ms": t_off * 1e3, "pipeline_GB/s_each_way": moved / t_off / 1e9,
+                ("pipeline_GB/s_each_way_evict_by_store_kernel" if duplex else "pipeline_GB/s_each_way_evict_by_DMA"): moved / t_off_other / 1e9,
                 "bidirectional_GB/s_each_way": (n_host // 2) * nbytes / t_both / 1e9,
                 "pipeline_frac_of_one_way_link": t_dma / t_off,
                 "pipeline_frac_of_bidirectional_link": (moved / t_off) / ((n_host // 2) * nbytes / t_both),
