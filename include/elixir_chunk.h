@@ -378,10 +378,10 @@ int elixir_arena_plan(int n_chunks, const elixir_arena_array* arrays, int n_arra
  *       the process has created, so the call measures it: it creates streams until two of them are seen to run beside
  *       compute_stream and beside each other (a marker on one stream must complete while a 64 MiB copy is still
  *       pending on the other), keeps those and destroys the rest; ELIXIR_ESTATE if there are no two among 12
- *       candidates.  Separate queues are necessary for uploads and downloads to overlap, not sufficient: the DMA
- *       engines are shared by the whole process, and after a large device allocation has been freed (hipFree of 4 GiB
- *       or more) an upload and a download issued together were seen to take turns whatever streams carry them, until
- *       later copy traffic undoes it.  No choice of streams repairs that; *full_duplex_out (may be NULL) reports
+ *       candidates.  Separate queues are necessary for uploads and downloads to overlap, not sufficient: after device
+ *       memory has been freed (by this process or by one that ran before it on the GPU) downloads by DMA were seen to
+ *       run at half rate for about 30 ms per GiB freed, uploads unaffected, whatever streams carry them.  No choice of
+ *       streams changes that; *full_duplex_out (may be NULL) reports
  *       whether an upload and a download issued together overlapped when the call looked (1) or took turns (0).
  *       A process that wants the full-duplex rate allocates its long-lived buffers once and frees nothing large
  *       while it streams; one that reads 0 here can let the slots come back by a kernel instead
@@ -407,9 +407,9 @@ int elixir_chunk_evict(elixir_ctx* ctx, int slot, void* h_block, size_t bytes, e
 /*
  * How elixir_chunk_evict brings a slot back to its host block (no passage of the paper: a remedy for a state of the
  * HIP runtime).  ELIXIR_EVICT_DMA (the default): hipMemcpyAsync, the DMA engine.  ELIXIR_EVICT_KERNEL: a small kernel
- * on d2h_stream stores the slot into the pinned block over the link.  In a process whose uploads and downloads by DMA
- * take turns (elixir_offload_copy_streams reports that state in *full_duplex_out; it follows the freeing of large
- * allocations) the kernel path lets the download run beside the upload again.  The host block must then be pinned
+ * on d2h_stream stores the slot into the pinned block over the link.  While downloads by DMA run at half rate
+ * (elixir_offload_copy_streams reports that in *full_duplex_out; it follows the freeing of device memory and passes
+ * with time) the kernel path lets the download run beside the upload at once.  The host block must then be pinned
  * memory that the device can address (elixir_host_alloc's is); for any other block, and for a slot or block that is
  * not 16-byte aligned, the call copies by DMA as before.  Takes effect from the next elixir_chunk_evict on; same bytes
  * either way.  ELIXIR_EINVAL for an unknown path.

@@ -202,15 +202,16 @@ extern "C" int elixir_chunk_evict(elixir_ctx* ctx, int slot, void* h_block, size
 // on stream A has finished shares A's queue.  elixir_offload_copy_streams creates candidate streams until it has two
 // that share a queue neither with the caller's compute stream nor with each other.
 //
-// Separate queues are necessary, not sufficient.  The DMA engines behind the copies are shared by the whole process,
-// and after a large device allocation has been freed (hipFree of 4 GiB or more: seen every time) an upload and a
-// download issued together take turns whatever streams carry them, until later copy traffic undoes it (one 1 GiB
-// upload on a third stream did, as did twenty 1 GiB downloads; one or four downloads did not).  No stream choice
-// repairs that, so the call only reports it: *full_duplex_out says whether an upload and a download overlapped when
-// the call looked.  A process that wants the full-duplex rate allocates its long-lived buffers once and frees nothing
-// large while it streams (the paper's own rule for long-lived buffers, Sec. 3 "Pre-runtime Profiler"); one that finds
-// itself in that state lets the slots come back by the store kernel above (elixir_offload_set_evict_path), which leaves
-// the DMA engines to the uploads.
+// Separate queues are necessary, not sufficient.  After device memory has been freed, downloads by DMA run at half rate
+// for a while (a download alone 30 GB/s instead of 57, an upload and a download together 29 GB/s each way instead of
+// 48.6; uploads alone are not affected): about 30 ms per GiB freed, whatever is copied meanwhile (measured: 16 GiB
+// under 0.5 s, 64 GiB 2 s), also after the exit of an earlier process on the same GPU.  hipFree itself returns at
+// once, so this looks like work the driver does on the freed memory with the engine that serves downloads.  No stream
+// choice changes it, so the call only reports it: *full_duplex_out says whether an upload and a download overlapped
+// when the call looked.  A process that wants the full-duplex rate allocates its long-lived buffers once and frees
+// nothing large while it streams (the paper's own rule for long-lived buffers, Sec. 3 "Pre-runtime Profiler"); one
+// that cannot wait lets the slots come back by the store kernel above (elixir_offload_set_evict_path), which needs no
+// DMA engine.
 
 namespace {
 

@@ -1599,9 +1599,9 @@ def test_offload_copy_streams_run_beside_the_compute_stream_and_each_other(ctx):
         copies(True, True)
         t_up = min(copies(True, False) for _ in range(2))
         t_both = min(copies(True, True) for _ in range(3))
-        # both directions at once take clearly less than one after the other -- where the call measured that they can: after a
-        # large hipFree earlier in the process (other tests do that) the runtime makes uploads and downloads take turns for
-        # a while whatever streams carry them, and the flag says so
+        # both directions at once take clearly less than one after the other -- where the call measured that they can: for
+        # a while after device memory has been freed (other tests do that) downloads run at half rate whatever streams
+        # carry them, and the flag says so
         if duplex:
             assert t_both < 1.6 * t_up, (t_up, t_both)
         else:
