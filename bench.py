@@ -10,6 +10,15 @@ on the device BEFORE the timed region; one step = the fused AdamW update of ever
 master + two moments read and written, bf16 gradient read, bf16 parameter copy written).
 Prints ONE JSON line: params/s over the valid parameters, the roofline of the dominant kernel
 (measured with HIP events on the launch stream), and the CPU oracle timed on a bounded sample.
+
+After the timed region the same line collects, under `rows`:
+  side_rows()             pack, gradient reduction (whole set and tensor list), norms, fp16 update, a small offload pipeline
+  naive_allocation_row()  the benchmark step with every array an allocation of its own
+  other_configs()         short runs of the other benchmark configurations: run_offload (20B mix, first: it needs a link
+                          nobody has disturbed), run_hybrid (CPU update + benefit model), the tiny set through
+                          run_headline, run_sweep (chunk sizes), run_clip (6B accumulate + norm + clip)
+Each run_* is also `--workload <name>` on its own, as is run_tensor_lists; a row that fails records its error and
+leaves the line alone.
 """
 import argparse
 import json
