@@ -419,6 +419,86 @@ def test_gpt2_20b_offload_mix_full_size_chunks():
         ex.elixir_ctx_destroy(ctx)
 
 
+def test_gpt2_1p5b_tensor_list_reduce_and_whole_set_pack_full_size():
+    """The batched reduction and the whole-set pack / unpack on the real tensor list of the 1.5B set, as
+    `bench.py --workload tensor_lists` and `rows.grad_reduce_per_tensor` launch them: 580 tensors = 581 pieces in 26
+    chunks of 64Mi elements, every tensor's gradient a slice of a chunk-shaped bf16 array.  Two micro-batches (overwrite,
+    then accumulate); the oracle reduces sampled pieces from the seed (large ones at their head, middle and tail) and
+    packs two whole chunks; everything no tensor covers must keep its preset pattern (reduction) or read zero (pack)."""
+    cfg = gen.CONFIGS["gpt2_1p5b"]
+    C = cfg.chunk_elems
+    numels = cfg.numels()
+    cid, off, valid = ex.elixir_layout_plan(numels, C, ex.ELIXIR_LAYOUT_NEXT_FIT, 1)
+    nch = len(valid)
+    rng = np.random.default_rng(8)
+    pieces = []                                                       # (chunk, offset, length): a tensor that spans chunks in pieces
+    for i, n in enumerate(numels):
+        c, o, left = cid[i], off[i], n
+        while left > 0:
+            take = min(left, C - o)
+            pieces.append((c, o, take))
+            left, c, o = left - take, c + 1, 0
+    assert len(pieces) == 581
+    chunks = [torch.full((C,), 1.5, dtype=torch.float32, device=DEV) for _ in range(nch)]
+    g16 = [torch.empty(C, dtype=torch.int16, device=DEV) for _ in range(nch)]
+    keys = [gen.stream_key(gen.BASE_SEED, gen.TAG_GRAD, 1, mb, cfg.cfg_id) for mb in range(2)]
+    d32 = ex.elixir_ptr_table([chunks[c][o:o + n] for c, o, n in pieces])
+    s16 = ex.elixir_ptr_table([g16[c][o:o + n] for c, o, n in pieces])
+    lens = ex.elixir_i64_table([n for _, _, n in pieces])
+    for mb, key in enumerate(keys):
+        for c in range(nch):
+            gen.fill_bf16_device(g16[c].data_ptr(), valid[c], key, c * C, cfg.grad_std, cfg.grad_zero_pct)
+        ex.elixir_grad_reduce_multi_lp(d32, s16, lens, ex.ELIXIR_LOWP_BF16, 0.25, mb > 0)
+        torch.cuda.synchronize()
+
+    def windows(n):                                                   # what the oracle looks at of a piece of n elements
+        if n <= 300_000:
+            return [(0, n)]
+        mid = int(rng.integers(100_000, n - 200_000)) // 4 * 4 + 1   # an odd start inside the piece
+        return [(0, 100_000), (mid, 100_003), (n - 100_000, 100_000)]
+
+    order = sorted(range(len(pieces)), key=lambda k: pieces[k][2])
+    sampled = set(order[:6] + order[-4:] + [0, 1, 2, len(pieces) - 1] + [int(x) for x in rng.integers(0, len(pieces), size=24)])
+    sampled |= {k for k, (c, o, n) in enumerate(pieces) if o == 0 or o + n == C}        # pieces of tensors that span chunks
+    checked = 0
+    for k in sorted(sampled):
+        c, o, n = pieces[k]
+        got = chunks[c][o:o + n].cpu().numpy()
+        for a, m in windows(n):
+            want = np.full(m, 1.5, np.float32)
+            for mb, key in enumerate(keys):
+                orc.grad_reduce_into_chunk(want, 0, gen.fill_bf16(key, c * C + o + a, m, cfg.grad_std, cfg.grad_zero_pct), 0.25, mb > 0)
+            assert np.array_equal(got[a:a + m].view(np.uint32), want.view(np.uint32)), f"piece {k} (chunk {c}, offset {o}, {n} elements) at {a}"
+            checked += m
+    for c in range(nch):                                              # nothing outside the tensors was written
+        tail = chunks[c][valid[c]:]
+        assert tail.numel() == 0 or bool((tail == 1.5).all()), f"padding of chunk {c}"
+    print(f"reduction: {len(sampled)} pieces, {checked} elements checked against the oracle")
+
+    # ---- whole-set pack / unpack of fp32 data
+    pkey = gen.stream_key(gen.BASE_SEED, gen.TAG_PARAM, cfg=cfg.cfg_id)
+    data = [torch.zeros(C, dtype=torch.float32, device=DEV) for _ in range(nch)]        # tensor data, chunk-shaped like the gradients
+    for c in range(nch):
+        gen.fill_f32_device(data[c].data_ptr(), valid[c], pkey, c * C, cfg.param_std)
+    views = ex.elixir_ptr_table([data[c][o:o + n] for c, o, n in pieces])
+    p_c, p_o = ex.elixir_i64_table([c for c, _, _ in pieces]), ex.elixir_i64_table([o for _, o, _ in pieces])
+    ex.elixir_chunks_pack(chunks, C, 4, views, lens, p_c, p_o)         # over the reduced values and the 1.5 pattern
+    torch.cuda.synchronize()
+    for c in (0, nch - 1):                                            # the oracle packs two whole chunks
+        mine = [(o, n) for cc, o, n in pieces if cc == c]
+        tensors = [gen.fill_f32(pkey, c * C + o, n, cfg.param_std) for o, n in mine]
+        want = np.full(C, 7.0, np.float32)
+        orc.chunk_pack(want, tensors, [o for o, _ in mine])
+        assert np.array_equal(chunks[c].cpu().numpy().view(np.uint32), want.view(np.uint32)), f"packed chunk {c}"
+    for c in range(nch):
+        assert torch.equal(chunks[c][:valid[c]], data[c][:valid[c]]) and not bool(chunks[c][valid[c]:].any()), f"packed chunk {c}"
+    back = [torch.full((C,), 3.0, dtype=torch.float32, device=DEV) for _ in range(nch)]
+    ex.elixir_chunks_unpack(chunks, C, 4, ex.elixir_ptr_table([back[c][o:o + n] for c, o, n in pieces]), lens, p_c, p_o)
+    torch.cuda.synchronize()
+    for c in range(nch):
+        assert torch.equal(back[c][:valid[c]], data[c][:valid[c]]) and bool((back[c][valid[c]:] == 3.0).all()), f"unpacked chunk {c}"
+
+
 def test_one_chunk_past_four_gib_per_array():
     """A single chunk of 1.25 Gi + 3 elements: every fp32 array is longer than 4 GiB, so any 32-bit byte or element
     arithmetic in a kernel or in the host code would show.  Reduce (plain and fused with the sum of squares), norm,
