@@ -141,7 +141,7 @@ def parse():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="gpt2_1p5b",
-                    help="gpt2_1p5b (default, the benchmark line), tiny, sweep (chunk sizes 8Mi..256Mi), gpt2_6b_clip, gpt2_20b_offload, gpt2_20b_hybrid (CPU update + streaming), tensor_lists (pack / unpack / reduction over the 580 tensors of the 1.5B set)")
+                    help="gpt2_1p5b (default, the benchmark line), tiny, sweep (chunk sizes 8Mi..256Mi), gpt2_6b_clip, gpt2_20b_offload, gpt2_20b_hybrid (CPU update + streaming), tensor_lists (pack / unpack / reduction over the 580 tensors of the 1.5B set), link_after_free (the host link in the seconds after device memory has been freed)")
     ap.add_argument("--host-threads", type=int, default=0, help="gpt2_20b_hybrid: threads of the CPU update (default: all cores)")
     ap.add_argument("--host-chunks", type=int, default=0, help="gpt2_20b_offload: allocate only about this many host-resident chunks")
     ap.add_argument("--multi", action="store_true",
@@ -1099,6 +1099,60 @@ def run_tensor_lists(args, torch, ex, gen):
                        "kernel": "reduce_multi_kernel<false, false> (bf16 -> fp32, overwrite, 6 bytes per element)"}})
 
 
+def run_link_after_free(args, torch, ex, gen):
+    """What a large hipFree does to the host link: bare pinned copies of 256 MiB (upload alone, download alone, both at
+    once, on two streams of their own) every half second after 16, 64 and 128 GiB of device memory have been freed.
+    One JSON line; the time series is what profiles/host_link_after_a_large_free.txt summarises."""
+    dev = torch.device("cuda:0")
+    n = 256 << 20
+    h_up, h_dn = ex.elixir_host_alloc(n), ex.elixir_host_alloc(n)
+    d_up = torch.zeros(n, dtype=torch.uint8, device=dev)
+    d_dn = torch.zeros(n, dtype=torch.uint8, device=dev)
+    s_up, s_dn = torch.cuda.Stream(), torch.cuda.Stream()
+
+    def rate(up, dn):
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        if up:
+            ex.elixir_copy_h2d_async(d_up, h_up, n, s_up.cuda_stream)
+        if dn:
+            ex.elixir_copy_d2h_async(h_dn, d_dn, n, s_dn.cuda_stream)
+        torch.cuda.synchronize()
+        return n / (time.perf_counter() - t0) / 1e9
+
+    try:
+        for _ in range(3):
+            rate(True, True)
+        fresh = {"up_alone": rate(True, False), "down_alone": rate(False, True), "both_each_way": rate(True, True)}
+        series = []
+        for gib in (16, 64, 128):
+            x = torch.zeros(gib << 30, dtype=torch.uint8, device=dev)
+            torch.cuda.synchronize()
+            del x
+            t0 = time.perf_counter()
+            torch.cuda.empty_cache()
+            t_free = time.perf_counter() - t0
+            rows, settled = [], None
+            for k in range(40):
+                t = time.perf_counter() - t0
+                d, u, b = rate(False, True), rate(True, False), rate(True, True)
+                rows.append({"t_s": round(t, 2), "down_alone": round(d, 1), "up_alone": round(u, 1), "both_each_way": round(b, 1)})
+                if b > 0.9 * fresh["both_each_way"] and d > 0.9 * fresh["down_alone"]:
+                    settled = settled if settled is not None else t
+                    if k >= 3:
+                        break
+                time.sleep(0.5)
+            series.append({"freed_GiB": gib, "hipFree_s": round(t_free, 4), "first_sample_at_full_rate_s": None if settled is None else round(settled, 2),
+                           "samples": rows})
+        emit({"metric": "host link after a large free", "value": fresh["both_each_way"], "unit": "GB/s each way, fresh", "steps": 1, "warmup": 0,
+              "ms_per_step": None, "dtype": "u8", "config": {"workload": "host link after a large free", "copy_bytes": n}, "fresh": fresh, "after_free": series,
+              "roofline": {"bound": "host link", "achieved": fresh["both_each_way"], "peak": None, "unit": "GB/s", "frac": None, "traffic": None}})
+    finally:
+        torch.cuda.synchronize()
+        ex.elixir_host_free(h_up)
+        ex.elixir_host_free(h_dn)
+
+
 def naive_allocation_row(args, torch, ex, gen, cfg, valid, lens, dev, stream):
     """The same step with every array an ordinary allocation of its own (what a caller gets who does not plan where its
     buffers lie): per chunk one tiled optimizer chunk, two gradient sets, one parameter copy, each from torch's allocator."""
@@ -1185,7 +1239,7 @@ def other_configs(args, torch, ex, gen):
     return rows
 
 
-OTHER_WORKLOADS = {"tensor_lists": run_tensor_lists, "sweep": run_sweep, "gpt2_6b_clip": run_clip, "gpt2_20b_offload": run_offload, "gpt2_20b_hybrid": run_hybrid}
+OTHER_WORKLOADS = {"link_after_free": run_link_after_free, "tensor_lists": run_tensor_lists, "sweep": run_sweep, "gpt2_6b_clip": run_clip, "gpt2_20b_offload": run_offload, "gpt2_20b_hybrid": run_hybrid}
 
 
 def main():
